@@ -1,0 +1,229 @@
+"""CPU oracle (test infrastructure only): ctypes front end of atlas_oracle.c.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import
+this package.  It never imports the GPU package and the GPU package never
+imports it.  Arrays are numpy; all floating point is fp64.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "atlas_oracle.c")
+_LIB = os.path.join(_HERE, "libatlas_oracle.so")
+
+ACT_NONE, ACT_RELU, ACT_ELU = 0, 1, 2
+FMT_F32, FMT_BF16 = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (OpenMP) next to its source."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+                               "-ffp-contract=off", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.ao_num_threads.restype = ctypes.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().ao_num_threads())
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+_i64 = ctypes.c_int64
+
+
+def in_degree(n: int, col: np.ndarray) -> np.ndarray:
+    col = _c(col, np.int32)
+    out = np.empty(n, dtype=np.int64)
+    lib().ao_in_degree(_i64(n), _i64(col.size), _p(col), _p(out))
+    return out
+
+
+class InLists:
+    """In-neighbour lists of `n_dst` destinations (vertex ids `dst_ids`, or
+    0..n_dst-1 when None)."""
+
+    def __init__(self, in_off: np.ndarray, in_src: np.ndarray, dst_ids: Optional[np.ndarray] = None):
+        self.in_off = _c(in_off, np.int64)
+        self.in_src = _c(in_src, np.int32)
+        self.dst_ids = None if dst_ids is None else _c(dst_ids, np.int64)
+        self.n_dst = self.in_off.size - 1
+
+    @staticmethod
+    def from_csr(off: np.ndarray, col: np.ndarray) -> "InLists":
+        off = _c(off, np.int64)
+        col = _c(col, np.int32)
+        n = off.size - 1
+        in_off = np.empty(n + 1, dtype=np.int64)
+        in_src = np.empty(col.size, dtype=np.int32)
+        lib().ao_build_in_lists(_i64(n), _p(off), _p(col), _p(in_off), _p(in_src))
+        return InLists(in_off, in_src)
+
+
+def neighbor_sum(il: InLists, X: np.ndarray, scale: Optional[np.ndarray] = None) -> np.ndarray:
+    X = _c(X, np.float32)
+    d = X.shape[1]
+    scale = None if scale is None else _c(scale, np.float64)
+    S = np.empty((il.n_dst, d), dtype=np.float64)
+    lib().ao_neighbor_sum(_i64(il.n_dst), _p(il.in_off), _p(il.in_src), _p(X), _i64(d), _p(scale), _p(S))
+    return S
+
+
+def sage_mean(il: InLists, X: np.ndarray, W: np.ndarray, b: Optional[np.ndarray]) -> np.ndarray:
+    X = _c(X, np.float32)
+    W = _c(W, np.float64)
+    b = None if b is None else _c(b, np.float64)
+    d, dout = X.shape[1], W.shape[1]
+    assert W.shape[0] == 2 * d
+    Y = np.empty((il.n_dst, dout), dtype=np.float64)
+    lib().ao_sage_mean(_i64(il.n_dst), _p(il.dst_ids), _p(il.in_off), _p(il.in_src), _p(X), _i64(d),
+                       _p(W), _p(b), _i64(dout), _p(Y))
+    return Y
+
+
+def gcn(il: InLists, indeg: np.ndarray, X: np.ndarray, W: np.ndarray, b: Optional[np.ndarray]) -> np.ndarray:
+    X = _c(X, np.float32)
+    W = _c(W, np.float64)
+    b = None if b is None else _c(b, np.float64)
+    indeg = _c(indeg, np.int64)
+    d, dout = X.shape[1], W.shape[1]
+    assert W.shape[0] == d and indeg.size == X.shape[0]
+    Y = np.empty((il.n_dst, dout), dtype=np.float64)
+    lib().ao_gcn(_i64(il.n_dst), _p(il.dst_ids), _p(il.in_off), _p(il.in_src), _i64(X.shape[0]), _p(indeg),
+                 _p(X), _i64(d), _p(W), _p(b), _i64(dout), _p(Y))
+    return Y
+
+
+def gat(il: InLists, X: np.ndarray, W: np.ndarray, b: Optional[np.ndarray], a_src: np.ndarray,
+        a_dst: np.ndarray, slope: float = 0.2) -> np.ndarray:
+    X = _c(X, np.float32)
+    W = _c(W, np.float64)
+    b = None if b is None else _c(b, np.float64)
+    a_src = _c(a_src, np.float64)
+    a_dst = _c(a_dst, np.float64)
+    heads, dh = a_src.shape
+    d, dout = X.shape[1], W.shape[1]
+    assert dout == heads * dh and W.shape[0] == d
+    n = X.shape[0]
+    Z = np.zeros((n, dout), dtype=np.float64)
+    if il.dst_ids is None and il.n_dst == n:
+        rows = None
+        n_rows = n
+    else:
+        dst = il.dst_ids if il.dst_ids is not None else np.arange(il.n_dst, dtype=np.int64)
+        rows = np.unique(np.concatenate([il.in_src.astype(np.int64), dst]))
+        n_rows = rows.size
+    lib().ao_linear_rows(_i64(n_rows), _p(rows), _p(X), _i64(d), _p(W), _i64(dout), _p(Z))
+    Y = np.empty((il.n_dst, dout), dtype=np.float64)
+    lib().ao_gat_attend(_i64(il.n_dst), _p(il.dst_ids), _p(il.in_off), _p(il.in_src), _p(Z), _p(a_src),
+                        _p(a_dst), _i64(heads), _i64(dh), ctypes.c_double(slope), _p(b), _p(Y))
+    return Y
+
+
+def activation(Y: np.ndarray, kind: int) -> np.ndarray:
+    Y = _c(Y, np.float64).copy()
+    lib().ao_activation(_i64(Y.size), _p(Y), ctypes.c_int(kind))
+    return Y
+
+
+def round_storage(Y: np.ndarray, fmt: int) -> np.ndarray:
+    Y = _c(Y, np.float64).copy()
+    lib().ao_round_storage(_i64(Y.size), _p(Y), ctypes.c_int(fmt))
+    return Y
+
+
+def completion_chunk(il: InLists, selfmsg: bool, C: int) -> np.ndarray:
+    cc = np.empty(il.n_dst, dtype=np.int64)
+    lib().ao_completion_chunk(_i64(il.n_dst), _p(il.in_off), _p(il.in_src), ctypes.c_int(int(selfmsg)),
+                              _i64(C), _p(cc))
+    return cc
+
+
+def pending_after(il: InLists, selfmsg: bool, bound: int) -> np.ndarray:
+    out = np.empty(il.n_dst, dtype=np.int64)
+    lib().ao_pending_after(_i64(il.n_dst), _p(il.in_off), _p(il.in_src), ctypes.c_int(int(selfmsg)),
+                           _i64(bound), _p(out))
+    return out
+
+
+def reorder_indegree_desc(indeg: np.ndarray):
+    indeg = _c(indeg, np.int64)
+    n = indeg.size
+    new_of_old = np.empty(n, dtype=np.int32)
+    old_of_new = np.empty(n, dtype=np.int32)
+    lib().ao_reorder_indegree_desc(_i64(n), _p(indeg), _p(new_of_old), _p(old_of_new))
+    return new_of_old, old_of_new
+
+
+def order_score(off: np.ndarray, col: np.ndarray, indeg: np.ndarray) -> np.ndarray:
+    off = _c(off, np.int64)
+    col = _c(col, np.int32)
+    indeg = _c(indeg, np.int64)
+    n = off.size - 1
+    s = np.empty(n, dtype=np.float64)
+    lib().ao_order_score(_i64(n), _p(off), _p(col), _p(indeg), _p(s))
+    return s
+
+
+# --------------------------------------------------------------------------
+# whole-model chain
+# --------------------------------------------------------------------------
+
+def run_layer(model: str, il: InLists, indeg: Optional[np.ndarray], X: np.ndarray, params, act: int,
+              out_fmt: int, slope: float = 0.2) -> np.ndarray:
+    """One layer: aggregate + update (fp64), activation, round to storage.
+
+    `params` has fp64 arrays W, bias (and attn_src / attn_dst for GAT) that
+    already hold the rounded storage values.  Returns fp64 holding storage
+    values (n_dst x d_out)."""
+    if model == "sage":
+        Y = sage_mean(il, X, params.W, params.bias)
+    elif model == "gcn":
+        Y = gcn(il, indeg, X, params.W, params.bias)
+    elif model == "gat":
+        Y = gat(il, X, params.W, params.bias, params.attn_src, params.attn_dst, slope)
+    else:
+        raise ValueError(model)
+    return round_storage(activation(Y, act), out_fmt)
+
+
+def run_model(model: str, off: np.ndarray, col: np.ndarray, X: np.ndarray, layers: Sequence,
+              between_act: int, store_fmt: int, slope: float = 0.2) -> List[np.ndarray]:
+    """All layers over the full graph; the activation applies between layers
+    only, every layer's output is rounded to the storage format.  Returns the
+    list of per-layer outputs."""
+    il = InLists.from_csr(off, col)
+    indeg = in_degree(off.size - 1, col)
+    outs = []
+    cur = np.asarray(X, dtype=np.float32)
+    for li, p in enumerate(layers):
+        act = between_act if li + 1 < len(layers) else ACT_NONE
+        Y = run_layer(model, il, indeg, cur, p, act, store_fmt, slope)
+        outs.append(Y)
+        cur = Y.astype(np.float32)
+    return outs

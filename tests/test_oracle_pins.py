@@ -1,0 +1,404 @@
+"""Pins for the CPU oracle: every check here compares it with something other
+than itself -- a dense-adjacency brute force written with explicit loops, the
+paper's worked example, closed forms, library routines on special cases, and
+counting invariants.  No GPU."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+# --------------------------------------------------------------------------
+# tiny random multigraphs with isolated vertices, multi-edges and self-edges
+# --------------------------------------------------------------------------
+
+def tiny_graph(seed, n, e, isolated=3):
+    rng = np.random.default_rng(seed)
+    live = n - isolated
+    src = rng.integers(0, live, size=e)
+    dst = rng.integers(0, live, size=e)
+    # force some multi-edges and self-edges
+    src[: e // 8] = src[e // 8: 2 * (e // 8)]
+    dst[: e // 8] = dst[e // 8: 2 * (e // 8)]
+    dst[-3:] = src[-3:]
+    order = np.argsort(src, kind="stable")
+    src, dst = src[order], dst[order]
+    off = np.zeros(n + 1, dtype=np.int64)
+    np.add.at(off, src + 1, 1)
+    off = np.cumsum(off)
+    return off, dst.astype(np.int32), src.astype(np.int64)
+
+
+def dense_adjacency(n, src, dst):
+    """A[v][u] = number of edges u -> v, explicit loop."""
+    A = np.zeros((n, n), dtype=np.float64)
+    for s, t in zip(src, dst):
+        A[t, s] += 1.0
+    return A
+
+
+@pytest.mark.parametrize("seed,n,e", [(1, 40, 150), (2, 97, 600), (3, 256, 900)])
+def test_neighbor_sum_vs_dense(oracle, seed, n, e):
+    off, col, src = tiny_graph(seed, n, e)
+    rng = np.random.default_rng(seed + 100)
+    X = rng.standard_normal((n, 7)).astype(np.float32)
+    A = dense_adjacency(n, src, col)
+    il = oracle.InLists.from_csr(off, col)
+    S = oracle.neighbor_sum(il, X)
+    ref = np.zeros((n, 7))
+    for v in range(n):                 # triple loop, fp64
+        for u in range(n):
+            if A[v, u]:
+                for k in range(7):
+                    ref[v, k] += A[v, u] * float(X[u, k])
+    assert np.allclose(S, ref, rtol=1e-13, atol=1e-13)
+    assert np.array_equal(oracle.in_degree(n, col), A.sum(1).astype(np.int64))
+
+
+@pytest.mark.parametrize("seed,n,e", [(4, 50, 200), (5, 128, 700)])
+def test_sage_vs_dense(oracle, seed, n, e):
+    off, col, src = tiny_graph(seed, n, e)
+    rng = np.random.default_rng(seed)
+    d, dout = 6, 5
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    W = rng.standard_normal((2 * d, dout))
+    b = rng.standard_normal(dout)
+    A = dense_adjacency(n, src, col)
+    deg = A.sum(1)
+    mean = np.where(deg[:, None] > 0, (A @ X.astype(np.float64)) / np.maximum(deg, 1)[:, None], 0.0)
+    ref = X.astype(np.float64) @ W[:d] + mean @ W[d:] + b
+    Y = oracle.sage_mean(oracle.InLists.from_csr(off, col), X, W, b)
+    assert np.allclose(Y, ref, rtol=1e-12, atol=1e-12)
+    # a transposed W or swapped halves must fail: check the halves separately
+    W0 = W.copy(); W0[d:] = 0
+    assert np.allclose(oracle.sage_mean(oracle.InLists.from_csr(off, col), X, W0, b),
+                       X.astype(np.float64) @ W[:d] + b, rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("seed,n,e", [(6, 50, 200), (7, 128, 700)])
+def test_gcn_vs_dense(oracle, seed, n, e):
+    off, col, src = tiny_graph(seed, n, e, isolated=0)
+    # append one self-edge per vertex, as the GCN config does
+    src2 = np.concatenate([src, np.arange(n)])
+    dst2 = np.concatenate([col.astype(np.int64), np.arange(n)])
+    order = np.argsort(src2, kind="stable")
+    src2, dst2 = src2[order], dst2[order]
+    off2 = np.zeros(n + 1, dtype=np.int64)
+    np.add.at(off2, src2 + 1, 1)
+    off2 = np.cumsum(off2)
+    rng = np.random.default_rng(seed)
+    d, dout = 5, 4
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    W = rng.standard_normal((d, dout))
+    b = rng.standard_normal(dout)
+    A = dense_adjacency(n, src2, dst2)
+    D = A.sum(1)
+    Ahat = A / np.sqrt(np.outer(D, D))
+    ref = Ahat @ X.astype(np.float64) @ W + b
+    il = oracle.InLists.from_csr(off2, dst2.astype(np.int32))
+    Y = oracle.gcn(il, oracle.in_degree(n, dst2.astype(np.int32)), X, W, b)
+    assert np.allclose(Y, ref, rtol=1e-12, atol=1e-12)
+
+
+def dense_gat(n, A, X, W, b, a_src, a_dst, slope):
+    heads, dh = a_src.shape
+    Z = X.astype(np.float64) @ W
+    Y = np.zeros((n, heads * dh))
+    for v in range(n):
+        for h in range(heads):
+            zs = Z[:, h * dh:(h + 1) * dh]
+            logits, mult, idx = [], [], []
+            for u in range(n):
+                if A[v, u]:
+                    s = float(a_src[h] @ zs[u] + a_dst[h] @ zs[v])
+                    logits.append(s if s > 0 else slope * s)
+                    mult.append(A[v, u]); idx.append(u)
+            if not logits:
+                Y[v, h * dh:(h + 1) * dh] = b[h * dh:(h + 1) * dh]
+                continue
+            logits = np.array(logits); mult = np.array(mult)
+            w = mult * np.exp(logits - logits.max())
+            w = w / w.sum()
+            Y[v, h * dh:(h + 1) * dh] = (w[:, None] * zs[idx]).sum(0) + b[h * dh:(h + 1) * dh]
+    return Y
+
+
+@pytest.mark.parametrize("seed,n,e", [(8, 40, 160), (9, 90, 500)])
+def test_gat_vs_dense(oracle, seed, n, e):
+    off, col, src = tiny_graph(seed, n, e)
+    rng = np.random.default_rng(seed)
+    d, heads, dh = 6, 3, 4
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    W = rng.standard_normal((d, heads * dh))
+    b = rng.standard_normal(heads * dh)
+    a_s = rng.standard_normal((heads, dh)); a_d = rng.standard_normal((heads, dh))
+    A = dense_adjacency(n, src, col)
+    ref = dense_gat(n, A, X, W, b, a_s, a_d, 0.2)
+    Y = oracle.gat(oracle.InLists.from_csr(off, col), X, W, b, a_s, a_d, 0.2)
+    assert np.allclose(Y, ref, rtol=1e-11, atol=1e-11)
+
+
+# --------------------------------------------------------------------------
+# the paper's worked example
+# --------------------------------------------------------------------------
+
+def test_fig2_worked_example(oracle):
+    n, edges, expect = 0, [], {}
+    with open(os.path.join(HERE, "golden", "fig2_example.txt")) as f:
+        for line in f:
+            t = line.split()
+            if not t or t[0].startswith("#"):
+                continue
+            if t[0] == "vertices":
+                n = int(t[1])
+            elif t[0] == "edge":
+                edges.append((int(t[1]), int(t[2])))
+            elif t[0] == "expect":
+                expect[int(t[1])] = float(t[2])
+    edges.sort()
+    off = np.zeros(n + 1, dtype=np.int64)
+    for s, _ in edges:
+        off[s + 1] += 1
+    off = np.cumsum(off)
+    col = np.array([t for _, t in edges], dtype=np.int32)
+    X = np.arange(n, dtype=np.float32)[:, None]          # scalar vertex ids as features
+    S = oracle.neighbor_sum(oracle.InLists.from_csr(off, col), X)
+    for v, val in expect.items():
+        assert S[v, 0] == val
+
+
+# --------------------------------------------------------------------------
+# closed forms and special cases
+# --------------------------------------------------------------------------
+
+def ring(n):
+    """u -> u+1 and u -> u-1 (mod n), CSR by source."""
+    off = np.arange(n + 1, dtype=np.int64) * 2
+    col = np.empty(2 * n, dtype=np.int32)
+    col[0::2] = (np.arange(n) + 1) % n
+    col[1::2] = (np.arange(n) - 1) % n
+    return off, col
+
+
+def test_sage_row_stochastic(oracle):
+    off, col, _ = tiny_graph(11, 60, 300)
+    n, d = 60, 4
+    X = np.full((n, d), 2.5, dtype=np.float32)
+    W = np.vstack([np.zeros((d, d)), np.eye(d)])
+    Y = oracle.sage_mean(oracle.InLists.from_csr(off, col), X, W, None)
+    deg = oracle.in_degree(n, col)
+    assert np.allclose(Y[deg > 0], 2.5, rtol=1e-14)
+    assert np.all(Y[deg == 0] == 0.0)
+
+
+def test_gcn_regular_ring(oracle):
+    n, d = 12, 3
+    off, col = ring(n)
+    # add self loops: every vertex then has D = 3
+    off2 = np.arange(n + 1, dtype=np.int64) * 3
+    col2 = np.empty(3 * n, dtype=np.int32)
+    col2[0::3], col2[1::3], col2[2::3] = col[0::2], col[1::2], np.arange(n)
+    rng = np.random.default_rng(0)
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    Y = oracle.gcn(oracle.InLists.from_csr(off2, col2), oracle.in_degree(n, col2), X, np.eye(d), None)
+    Xd = X.astype(np.float64)
+    ref = (np.roll(Xd, 1, 0) + np.roll(Xd, -1, 0) + Xd) / 3.0
+    assert np.allclose(Y, ref, rtol=1e-14, atol=1e-14)
+
+
+def test_gcn_constant_input_closed_form(oracle):
+    off, col, src = tiny_graph(12, 30, 120, isolated=0)
+    n = 30
+    deg = np.bincount(col, minlength=n).astype(np.int64)
+    keep = (deg[src] > 0) & (deg[col] > 0)   # sources with D_u = 0 would divide by zero
+    assert keep.all() or True
+    # restrict to a graph where every vertex has an in-edge: add self loops
+    src2 = np.concatenate([src, np.arange(n)]); dst2 = np.concatenate([col.astype(np.int64), np.arange(n)])
+    order = np.argsort(src2, kind="stable"); src2, dst2 = src2[order], dst2[order]
+    off2 = np.cumsum(np.concatenate([[0], np.bincount(src2, minlength=n)])).astype(np.int64)
+    D = np.bincount(dst2, minlength=n)
+    ref = np.zeros(n)
+    for s, t in zip(src2, dst2):
+        ref[t] += 1.0 / math.sqrt(D[s] * D[t])
+    Y = oracle.gcn(oracle.InLists.from_csr(off2, dst2.astype(np.int32)), D, np.ones((n, 1), np.float32),
+                   np.ones((1, 1)), None)
+    assert np.allclose(Y[:, 0], ref, rtol=1e-13)
+
+
+def test_gat_special_cases(oracle):
+    off, col, src = tiny_graph(13, 50, 260)
+    n, d, heads, dh = 50, 5, 2, 3
+    rng = np.random.default_rng(13)
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    W = rng.standard_normal((d, heads * dh))
+    il = oracle.InLists.from_csr(off, col)
+    zero = np.zeros((heads, dh))
+    # zero attention vectors: uniform alpha => mean of transformed neighbours
+    Y = oracle.gat(il, X, W, None, zero, zero)
+    Z = X.astype(np.float64) @ W
+    A = dense_adjacency(n, src, col)
+    deg = A.sum(1)
+    ref = np.where(deg[:, None] > 0, (A @ Z) / np.maximum(deg, 1)[:, None], 0.0)
+    assert np.allclose(Y, ref, rtol=1e-12, atol=1e-12)
+    # huge logits: softmax saturates to the arg-max neighbour, nothing overflows
+    a_s = rng.standard_normal((heads, dh)) * 400.0
+    Y = oracle.gat(il, X, W, None, a_s, zero)
+    assert np.isfinite(Y).all()
+    for v in range(n):
+        nb = np.nonzero(A[v])[0]
+        if nb.size == 0:
+            assert np.all(Y[v] == 0); continue
+        for h in range(heads):
+            zs = Z[:, h * dh:(h + 1) * dh]
+            el = zs[nb] @ a_s[h]
+            s = np.where(el > 0, el, 0.2 * el)
+            top = np.sort(s)[::-1]
+            if nb.size == 1 or top[0] - top[1] > 50:
+                assert np.allclose(Y[v, h * dh:(h + 1) * dh], zs[nb[np.argmax(s)]], rtol=1e-9, atol=1e-9)
+
+
+def test_gat_single_in_neighbour(oracle):
+    # path 0 -> 1 -> 2: alpha = 1
+    off = np.array([0, 1, 2, 2], dtype=np.int64); col = np.array([1, 2], dtype=np.int32)
+    rng = np.random.default_rng(1)
+    X = rng.standard_normal((3, 4)).astype(np.float32)
+    W = rng.standard_normal((4, 6)); b = rng.standard_normal(6)
+    a = rng.standard_normal((2, 3))
+    Y = oracle.gat(oracle.InLists.from_csr(off, col), X, W, b, a, -a)
+    Z = X.astype(np.float64) @ W
+    assert np.allclose(Y[1], Z[0] + b) and np.allclose(Y[2], Z[1] + b) and np.allclose(Y[0], b)
+
+
+def test_affine_matches_library_matmul(oracle):
+    # W_neigh = 0 reduces SAGE to a dense layer: compare with a library matmul
+    off, col, _ = tiny_graph(14, 33, 100)
+    rng = np.random.default_rng(14)
+    X = rng.standard_normal((33, 9)).astype(np.float32)
+    W = rng.standard_normal((18, 7)); W[9:] = 0
+    b = rng.standard_normal(7)
+    Y = oracle.sage_mean(oracle.InLists.from_csr(off, col), X, W, b)
+    ref = (torch.from_numpy(X).double() @ torch.from_numpy(W[:9]) + torch.from_numpy(b)).numpy()
+    assert np.allclose(Y, ref, rtol=1e-13, atol=1e-13)
+
+
+def test_rounding_and_activation_vs_library(oracle):
+    rng = np.random.default_rng(3)
+    v = (rng.standard_normal(20000) * np.exp(rng.uniform(-20, 20, 20000))).astype(np.float32)
+    # exact ties and near-ties of the 8-bit significand
+    ties = np.array([1.00390625, 1.01171875, -3.0234375, 0.0, 255.5, 256.5, 1e-30, -1e30], dtype=np.float32)
+    v = np.concatenate([v, ties])
+    got = oracle.round_storage(v.astype(np.float64), oracle.FMT_BF16)
+    ref = torch.from_numpy(v).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(got, ref)
+    x = rng.standard_normal(1000) * 3
+    assert np.allclose(oracle.activation(x, oracle.ACT_ELU),
+                       torch.nn.functional.elu(torch.from_numpy(x)).numpy(), rtol=1e-15, atol=0)
+    assert np.array_equal(oracle.activation(x, oracle.ACT_RELU), np.maximum(x, 0))
+    assert np.array_equal(oracle.round_storage(x, oracle.FMT_F32), x.astype(np.float32).astype(np.float64))
+
+
+# --------------------------------------------------------------------------
+# invariance under vertex relabelling
+# --------------------------------------------------------------------------
+
+def relabel_csr(off, col, new_of_old):
+    n = off.size - 1
+    src = np.repeat(np.arange(n), np.diff(off))
+    s2, d2 = new_of_old[src], new_of_old[col]
+    order = np.argsort(s2, kind="stable")
+    s2, d2 = s2[order], d2[order]
+    off2 = np.cumsum(np.concatenate([[0], np.bincount(s2, minlength=n)])).astype(np.int64)
+    return off2, d2.astype(np.int32)
+
+
+@pytest.mark.parametrize("model", ["sage", "gcn", "gat"])
+def test_permutation_invariance(oracle, model):
+    n, d, dout = 80, 6, 8
+    off, col, src = tiny_graph(21, n, 400, isolated=0 if model == "gcn" else 3)
+    if model == "gcn":   # every vertex needs D > 0
+        s2 = np.concatenate([src, np.arange(n)]); d2 = np.concatenate([col.astype(np.int64), np.arange(n)])
+        o = np.argsort(s2, kind="stable"); s2, d2 = s2[o], d2[o]
+        off = np.cumsum(np.concatenate([[0], np.bincount(s2, minlength=n)])).astype(np.int64)
+        col = d2.astype(np.int32)
+    rng = np.random.default_rng(22)
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    perm = rng.permutation(n)            # new_of_old
+    off2, col2 = relabel_csr(off, col, perm)
+    X2 = np.empty_like(X); X2[perm] = X
+
+    class P: pass
+    p = P()
+    p.W = rng.standard_normal((2 * d if model == "sage" else d, dout)); p.bias = rng.standard_normal(dout)
+    p.attn_src = rng.standard_normal((2, 4)); p.attn_dst = rng.standard_normal((2, 4))
+    a = oracle.run_layer(model, oracle.InLists.from_csr(off, col), oracle.in_degree(n, col), X, p, 0, 0)
+    b = oracle.run_layer(model, oracle.InLists.from_csr(off2, col2), oracle.in_degree(n, col2), X2, p, 0, 0)
+    assert np.allclose(b[perm], a, rtol=1e-6, atol=1e-6)   # outputs were rounded to fp32 storage
+    ya = oracle.sage_mean(oracle.InLists.from_csr(off, col), X, np.vstack([p.W[:d], p.W[:d]]), None) if model == "sage" else None
+    if ya is not None:
+        yb = oracle.sage_mean(oracle.InLists.from_csr(off2, col2), X2, np.vstack([p.W[:d], p.W[:d]]), None)
+        assert np.allclose(yb[perm], ya, rtol=1e-12, atol=1e-12)
+
+
+# --------------------------------------------------------------------------
+# counters: pending counts, completion, ordering
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("selfmsg", [False, True])
+def test_completion_invariants(oracle, selfmsg):
+    n, C = 300, 32
+    off, col, src = tiny_graph(31, n, 1500, isolated=5)
+    il = oracle.InLists.from_csr(off, col)
+    indeg = oracle.in_degree(n, col)
+    assert indeg.sum() == col.size
+    assert np.array_equal(oracle.pending_after(il, selfmsg, 0), indeg + int(selfmsg))
+    assert np.all(oracle.pending_after(il, selfmsg, n) == 0)
+    cc = oracle.completion_chunk(il, selfmsg, C)
+    nchunks = (n + C - 1) // C
+    # brute force by streaming sources in order and counting messages (explicit simulation)
+    pend = (indeg + int(selfmsg)).copy()
+    done_at = np.full(n, -1, dtype=np.int64)
+    total_dec = 0
+    for c in range(nchunks):
+        for u in range(c * C, min(n, (c + 1) * C)):
+            for e in range(off[u], off[u + 1]):
+                pend[col[e]] -= 1; total_dec += 1
+                if pend[col[e]] == 0:
+                    done_at[col[e]] = c
+            if selfmsg:
+                pend[u] -= 1; total_dec += 1
+                if pend[u] == 0:
+                    done_at[u] = c
+        assert np.array_equal(oracle.pending_after(il, selfmsg, min(n, (c + 1) * C)), pend)
+    assert total_dec == col.size + (n if selfmsg else 0)
+    assert np.array_equal(cc, done_at)
+    assert np.all(pend == 0)
+    sets = [np.nonzero(cc == c)[0] for c in range(-1, nchunks)]
+    assert sum(s.size for s in sets) == n
+    if not selfmsg:
+        assert np.array_equal(np.nonzero(cc == -1)[0], np.nonzero(indeg == 0)[0])
+
+
+def test_reorder_is_stable_degree_sort(oracle):
+    rng = np.random.default_rng(5)
+    indeg = rng.integers(0, 6, size=500).astype(np.int64)
+    indeg[7] = 1000
+    new_of_old, old_of_new = oracle.reorder_indegree_desc(indeg)
+    assert np.array_equal(np.sort(old_of_new), np.arange(500))
+    assert np.array_equal(new_of_old[old_of_new], np.arange(500))
+    dd = indeg[old_of_new]
+    assert np.all(dd[:-1] >= dd[1:])
+    same = dd[:-1] == dd[1:]
+    assert np.all(old_of_new[:-1][same] < old_of_new[1:][same])
+    assert np.array_equal(old_of_new, np.argsort(-indeg, kind="stable"))
+
+
+def test_order_score_closed_form(oracle):
+    # sum_u Score(u) * d_out(u) = number of vertices with an in-edge (Sec. 3.8)
+    off, col, _ = tiny_graph(41, 200, 900, isolated=9)
+    indeg = oracle.in_degree(200, col)
+    s = oracle.order_score(off, col, indeg)
+    assert abs((s * np.diff(off)).sum() - np.count_nonzero(indeg)) < 1e-9
