@@ -1,0 +1,191 @@
+/*
+ * atlas.h -- C ABI of the broadcast-based GNN layer step for MI355X (gfx950).
+ *
+ * One layer of layer-wise full-graph inference is run as a stream of source
+ * chunks (paper Sec. 3.1 "Broadcast Execution Model", Sec. 3.3 chunk iterator,
+ * Sec. 3.4 orchestrator, Sec. 3.6 graduation):
+ *
+ *   atlas_layer_init       per-vertex pending-message counts, zeroed
+ *                          accumulators, empty ready list        (Sec. 3.4)
+ *   atlas_broadcast_chunk  push the embeddings of sources [b, e) along their
+ *                          out-edges into per-destination accumulators; every
+ *                          message decrements the destination's pending count;
+ *                          destinations reaching zero are appended to the ready
+ *                          list                                   (Sec. 3.1, 3.4)
+ *   atlas_flush_ready      dense update of the ready ("graduated") rows and
+ *                          write of their next-layer embeddings   (Sec. 3.6)
+ *   atlas_layer_finish     exactly-once check, statistics, release (Sec. 3.1:
+ *                          every embedding is consumed exactly once per layer)
+ *
+ * All work runs in HIP kernels on the current device.  Nothing here allocates
+ * or touches torch objects; every pointer is a plain address whose residency
+ * (device / pinned host / pageable host) is stated per argument.  No function
+ * throws or aborts; every function returns ATLAS_OK (0) or a negative
+ * atlas_status code and has no partial effect when it rejects its arguments.
+ * A layer object must be used from one host thread at a time, and all calls on
+ * one layer must be given the same HIP stream (or streams the caller orders).
+ */
+#ifndef ATLAS_H
+#define ATLAS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct atlas_layer atlas_layer_t; /* opaque, library-owned */
+
+enum atlas_status {
+    ATLAS_OK = 0,
+    ATLAS_E_NULL = -1,       /* a required pointer is NULL                                  */
+    ATLAS_E_BAD_DIMS = -2,   /* unsupported width / heads / enum value                      */
+    ATLAS_E_RANGE = -3,      /* chunk bounds outside [0, N] or longer than max_chunk_sources */
+    ATLAS_E_ORDER = -4,      /* chunks must be contiguous and ascending, starting at 0      */
+    ATLAS_E_INCOMPLETE = -5, /* finish before every vertex was completed and flushed        */
+    ATLAS_E_OVERFLOW = -6,   /* N >= 2^31 (vertex ids and counts are int32)                 */
+    ATLAS_E_HIP = -7,        /* a HIP call failed; see atlas_last_hip_error()               */
+    ATLAS_E_NOMEM = -8,      /* device or host allocation failed                            */
+    ATLAS_E_STATE = -9       /* call not valid in the layer's current state                 */
+};
+
+enum atlas_residency { ATLAS_RESIDENT_DEVICE = 0, ATLAS_RESIDENT_PINNED_HOST = 1 };
+enum atlas_model { ATLAS_MODEL_SAGE_MEAN = 0, ATLAS_MODEL_GCN_SYM = 1, ATLAS_MODEL_GAT = 2 };
+enum atlas_dtype { ATLAS_DTYPE_F32 = 0, ATLAS_DTYPE_BF16 = 1 };
+enum atlas_activation { ATLAS_ACT_NONE = 0, ATLAS_ACT_RELU = 1, ATLAS_ACT_ELU = 2 };
+enum atlas_flags { ATLAS_FLAG_TIMING = 1 }; /* record per-stage GPU time with HIP events */
+
+/* The graph: CSR by SOURCE vertex (paper Sec. 3.2: out-edges, read sequentially
+ * by offsets).  Vertex ids are the (re-ordered) ids the chunks are streamed in.
+ * Multi-edges and self-edges are ordinary edges.  Caller-owned; must stay valid
+ * and unchanged until atlas_layer_finish returns. */
+typedef struct {
+    int64_t num_vertices;       /* N, 0 <= N < 2^31                                        */
+    int64_t num_edges;          /* E = row_offsets[N]                                      */
+    const int64_t *row_offsets; /* N+1 ascending edge offsets; DEVICE: device memory,
+                                   PINNED_HOST: pinned host memory                         */
+    const int32_t *col_indices; /* E destination ids; same residency as row_offsets        */
+    const int32_t *in_degree;   /* N in-degrees (multiplicity counted) in DEVICE memory,
+                                   or NULL: the library counts them at init                */
+    int32_t residency;          /* atlas_residency of row_offsets / col_indices            */
+} atlas_graph_t;
+
+/* Layer shape.  d_in must be a multiple of 64 (one wavefront holds a row),
+ * at most 512; d_out a multiple of 16, at most 256; GAT: d_out % heads == 0,
+ * d_out a multiple of 64 and (d_out / heads) a power of two <= 64. */
+typedef struct {
+    int32_t model;             /* atlas_model                                              */
+    int32_t d_in, d_out;       /* input / output embedding width                           */
+    int32_t heads;             /* GAT heads (1 otherwise)                                  */
+    int32_t in_dtype;          /* atlas_dtype of the chunk embeddings                      */
+    int32_t out_dtype;         /* atlas_dtype of the rows atlas_flush_ready writes         */
+    int32_t activation;        /* atlas_activation applied after bias                      */
+    float neg_slope;           /* GAT LeakyReLU slope                                      */
+    int64_t max_chunk_sources; /* upper bound on src_end - src_begin of any chunk          */
+    int32_t flags;             /* atlas_flags                                              */
+} atlas_dims_t;
+
+/* Layer parameters, DEVICE memory, row-major, caller-owned; they are repacked
+ * at init and need not outlive atlas_layer_init.
+ *   SAGE_MEAN: W is [2*d_in][d_out]; rows 0..d_in-1 multiply the vertex's own
+ *              embedding, rows d_in.. multiply the neighbour mean
+ *              (self-concatenation, Sec. 4.3);  y = [h_v || mean] W + bias.
+ *   GCN_SYM:   W is [d_in][d_out];  y = (sum_u h_u / sqrt(D_u D_v)) W + bias,
+ *              D = in-degree of the graph as given (self-edges already added).
+ *   GAT:       W is [d_in][d_out], head k owns columns k*dh..(k+1)*dh-1,
+ *              attn_src / attn_dst are [heads][dh].
+ * bias is [d_out] or NULL. */
+typedef struct {
+    const void *W, *bias, *attn_src, *attn_dst;
+    int32_t dtype; /* atlas_dtype of all four arrays */
+} atlas_weights_t;
+
+typedef struct {
+    int64_t edges_processed;    /* messages pushed along edges                              */
+    int64_t sources_processed;  /* sources broadcast (must equal N at finish)               */
+    int64_t vertices_completed; /* ready-list length                                        */
+    int64_t vertices_flushed;   /* rows written by atlas_flush_ready                        */
+    int64_t num_chunks, num_flushes;
+    int64_t bytes_copied_h2d;   /* PINNED_HOST residency: bytes staged into HBM             */
+    float ms_aggregate;         /* ATLAS_FLAG_TIMING: sum over chunks of broadcast kernels  */
+    float ms_update;            /* ATLAS_FLAG_TIMING: sum over flushes of update kernels    */
+    float ms_copy;              /* ATLAS_FLAG_TIMING: sum of staging copies                 */
+} atlas_layer_stats_t;
+
+/* Create the state of one layer (Sec. 3.4: pending-message tracker and
+ * per-vertex arrays; Sec. 3.8: a vertex is complete after d_in(v) messages).
+ * pending0[v] = d_in(v) (+1 for SAGE_MEAN: the vertex's own embedding is a
+ * message to itself that arrives with its own chunk).  Vertices with
+ * pending0 == 0 are placed on the ready list here.  Accumulators are zeroed.
+ * Enqueues on `hip_stream` (a hipStream_t, NULL = default stream) and returns
+ * without waiting.  *out receives the layer.  Errors: E_NULL, E_BAD_DIMS,
+ * E_OVERFLOW, E_NOMEM, E_HIP. */
+int atlas_layer_init(const atlas_graph_t *graph, const atlas_dims_t *dims,
+                     const atlas_weights_t *weights, void *hip_stream, atlas_layer_t **out);
+
+/* GAT only: attention terms el[u] = a_src . (W^T h_u), er[u] = a_dst . (W^T h_u)
+ * of rows [src_begin, src_end).  Every row must have been through this call
+ * before the first atlas_broadcast_chunk (a destination's term is needed when
+ * its first message arrives).  Same chunk rules and `emb` meaning as
+ * atlas_broadcast_chunk.  E_STATE for other models. */
+int atlas_attention_prepass(atlas_layer_t *layer, int64_t src_begin, int64_t src_end,
+                            const void *emb, void *hip_stream);
+
+/* Broadcast sources [src_begin, src_end) (Sec. 3.1, 3.3, 3.4).  `emb` points at
+ * the (src_end - src_begin) x d_in row-major embeddings OF THE CHUNK ONLY, in
+ * dims.in_dtype; device memory for DEVICE graphs, pinned host memory for
+ * PINNED_HOST graphs (the library stages it and the chunk's CSR slice into HBM
+ * on its own copy stream, overlapped with the previous chunk's kernels).
+ * For every out-edge (u, v): acc[v] += g(u) h_u and pending[v] -= 1; v joins
+ * the ready list when its count reaches zero.  Chunks must arrive in ascending
+ * contiguous order starting at 0 ("strictly ordered", Sec. 3.4).  Only
+ * enqueues; `emb` must stay valid until the stream has passed this point.
+ * Errors: E_NULL, E_RANGE, E_ORDER, E_STATE, E_HIP. */
+int atlas_broadcast_chunk(atlas_layer_t *layer, int64_t src_begin, int64_t src_end,
+                          const void *emb, void *hip_stream);
+
+/* Update every vertex that became ready since the previous flush (Sec. 3.6):
+ * gather its finished aggregate, normalise, multiply by W, add bias, apply the
+ * activation and write row v of `out` (DEVICE memory, N x d_out row-major,
+ * dims.out_dtype).  Only rows of flushed vertices are written.  If n_flushed is
+ * not NULL the call waits for the stream and stores the number of rows written;
+ * with NULL it only enqueues.  Errors: E_NULL, E_STATE, E_HIP. */
+int atlas_flush_ready(atlas_layer_t *layer, void *out, int64_t *n_flushed, void *hip_stream);
+
+/* Wait for the layer's work, verify that all N sources were broadcast and that
+ * every vertex was completed and flushed exactly once, fill *stats (may be
+ * NULL) and free the layer -- also when it returns E_INCOMPLETE. */
+int atlas_layer_finish(atlas_layer_t *layer, atlas_layer_stats_t *stats);
+
+/* In-degree of every vertex (histogram of col_indices), int32[N] in DEVICE
+ * memory.  Works for both residencies (a PINNED_HOST edge array is read over
+ * the host link).  Enqueues on hip_stream. */
+int atlas_in_degree(const atlas_graph_t *graph, int32_t *in_degree, void *hip_stream);
+
+/* In-degree-descending vertex order, ties by smaller old id first:
+ * old_of_new[i] is the vertex placed at position i, new_of_old its inverse.
+ * graph->in_degree must be set.  Both outputs are int32[N] DEVICE memory.
+ * Synchronous. */
+int atlas_reorder_indegree_desc(const atlas_graph_t *graph, int32_t *new_of_old,
+                                int32_t *old_of_new);
+
+/* Synchronise and copy one internal array to host memory, for tests. */
+enum atlas_debug_what {
+    ATLAS_DBG_INDEG = 0,       /* int32[N]                                  */
+    ATLAS_DBG_PENDING = 1,     /* int32[N]                                  */
+    ATLAS_DBG_READY = 2,       /* int32[ready count], completion order      */
+    ATLAS_DBG_READY_COUNT = 3, /* int64[2]: {ready tail, flushed head}      */
+    ATLAS_DBG_ACC = 4          /* float[N][acc width]                       */
+};
+int atlas_debug_copy(atlas_layer_t *layer, int what, void *host_dst, int64_t bytes);
+
+/* Free the device buffers the library keeps for reuse between layers. */
+int atlas_release_cache(void);
+
+const char *atlas_strerror(int status);
+const char *atlas_last_hip_error(void); /* text of the last failed HIP call on this thread */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ATLAS_H */

@@ -1,0 +1,192 @@
+"""Python binding of libatlas.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (include/atlas.h).
+Tensors are used for their device / pinned-host addresses; streams are raw
+hipStream_t handles (torch.cuda.Stream().cuda_stream).  There is no fallback:
+if the HIP library has not been built the import of any entry point raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libatlas.so")
+
+OK = 0
+E_NULL, E_BAD_DIMS, E_RANGE, E_ORDER, E_INCOMPLETE, E_OVERFLOW, E_HIP, E_NOMEM, E_STATE = range(-1, -10, -1)
+RESIDENT_DEVICE, RESIDENT_PINNED_HOST = 0, 1
+MODEL_SAGE_MEAN, MODEL_GCN_SYM, MODEL_GAT = 0, 1, 2
+DTYPE_F32, DTYPE_BF16 = 0, 1
+ACT_NONE, ACT_RELU, ACT_ELU = 0, 1, 2
+FLAG_TIMING = 1
+DBG_INDEG, DBG_PENDING, DBG_READY, DBG_READY_COUNT, DBG_ACC = range(5)
+
+EXPORTS = [
+    "atlas_layer_init", "atlas_attention_prepass", "atlas_broadcast_chunk", "atlas_flush_ready",
+    "atlas_layer_finish", "atlas_in_degree", "atlas_reorder_indegree_desc", "atlas_debug_copy",
+    "atlas_release_cache", "atlas_strerror", "atlas_last_hip_error",
+]
+
+
+class atlas_graph_t(ctypes.Structure):
+    _fields_ = [("num_vertices", ctypes.c_int64), ("num_edges", ctypes.c_int64),
+                ("row_offsets", ctypes.c_void_p), ("col_indices", ctypes.c_void_p),
+                ("in_degree", ctypes.c_void_p), ("residency", ctypes.c_int32)]
+
+
+class atlas_dims_t(ctypes.Structure):
+    _fields_ = [("model", ctypes.c_int32), ("d_in", ctypes.c_int32), ("d_out", ctypes.c_int32),
+                ("heads", ctypes.c_int32), ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
+                ("activation", ctypes.c_int32), ("neg_slope", ctypes.c_float),
+                ("max_chunk_sources", ctypes.c_int64), ("flags", ctypes.c_int32)]
+
+
+class atlas_weights_t(ctypes.Structure):
+    _fields_ = [("W", ctypes.c_void_p), ("bias", ctypes.c_void_p), ("attn_src", ctypes.c_void_p),
+                ("attn_dst", ctypes.c_void_p), ("dtype", ctypes.c_int32)]
+
+
+class atlas_layer_stats_t(ctypes.Structure):
+    _fields_ = [("edges_processed", ctypes.c_int64), ("sources_processed", ctypes.c_int64),
+                ("vertices_completed", ctypes.c_int64), ("vertices_flushed", ctypes.c_int64),
+                ("num_chunks", ctypes.c_int64), ("num_flushes", ctypes.c_int64),
+                ("bytes_copied_h2d", ctypes.c_int64), ("ms_aggregate", ctypes.c_float),
+                ("ms_update", ctypes.c_float), ("ms_copy", ctypes.c_float)]
+
+
+class AtlasError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        detail = ""
+        if status in (E_HIP, E_NOMEM):
+            detail = " [" + lib().atlas_last_hip_error().decode() + "]"
+        super().__init__("%s: %s (%d)%s" % (where, lib().atlas_strerror(status).decode(), status, detail))
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libatlas.so; raises if it has not been built (no CPU fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libatlas.so is missing: run `python -m paper_2605_09402_amd.build` "
+                              "(hipcc, gfx950) first; there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+        L.atlas_layer_init.argtypes = [ctypes.POINTER(atlas_graph_t), ctypes.POINTER(atlas_dims_t),
+                                       ctypes.POINTER(atlas_weights_t), vp, ctypes.POINTER(vp)]
+        L.atlas_attention_prepass.argtypes = [vp, i64, i64, vp, vp]
+        L.atlas_broadcast_chunk.argtypes = [vp, i64, i64, vp, vp]
+        L.atlas_flush_ready.argtypes = [vp, vp, ctypes.POINTER(i64), vp]
+        L.atlas_layer_finish.argtypes = [vp, ctypes.POINTER(atlas_layer_stats_t)]
+        L.atlas_in_degree.argtypes = [ctypes.POINTER(atlas_graph_t), vp, vp]
+        L.atlas_reorder_indegree_desc.argtypes = [ctypes.POINTER(atlas_graph_t), vp, vp]
+        L.atlas_debug_copy.argtypes = [vp, i32, vp, i64]
+        L.atlas_release_cache.argtypes = []
+        for name in EXPORTS:
+            getattr(L, name).restype = ctypes.c_int      # raises AttributeError on a missing export
+        L.atlas_strerror.argtypes = [i32]
+        L.atlas_strerror.restype = ctypes.c_char_p
+        L.atlas_last_hip_error.argtypes = []
+        L.atlas_last_hip_error.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _ptr(t) -> Optional[int]:
+    """Address of a tensor's storage (or an int / None passed through)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _check(status: int, where: str):
+    if status != OK:
+        raise AtlasError(status, where)
+
+
+def make_graph(num_vertices: int, num_edges: int, row_offsets, col_indices, in_degree=None,
+               residency: int = RESIDENT_DEVICE) -> atlas_graph_t:
+    """Fill an atlas_graph_t from tensors (int64 offsets, int32 columns / degrees).
+    The caller keeps the tensors alive."""
+    return atlas_graph_t(num_vertices, num_edges, _ptr(row_offsets), _ptr(col_indices), _ptr(in_degree),
+                         residency)
+
+
+def make_dims(model: int, d_in: int, d_out: int, in_dtype: int, out_dtype: int, activation: int,
+              max_chunk_sources: int, heads: int = 1, neg_slope: float = 0.2, flags: int = 0) -> atlas_dims_t:
+    return atlas_dims_t(model, d_in, d_out, heads, in_dtype, out_dtype, activation, neg_slope,
+                        max_chunk_sources, flags)
+
+
+def make_weights(W, bias, dtype: int, attn_src=None, attn_dst=None) -> atlas_weights_t:
+    return atlas_weights_t(_ptr(W), _ptr(bias), _ptr(attn_src), _ptr(attn_dst), dtype)
+
+
+def atlas_layer_init(graph: atlas_graph_t, dims: atlas_dims_t, weights: atlas_weights_t, stream=None) -> int:
+    h = ctypes.c_void_p()
+    _check(lib().atlas_layer_init(ctypes.byref(graph), ctypes.byref(dims), ctypes.byref(weights),
+                                  _stream(stream), ctypes.byref(h)), "atlas_layer_init")
+    return h.value
+
+
+def atlas_attention_prepass(layer: int, src_begin: int, src_end: int, emb, stream=None) -> None:
+    _check(lib().atlas_attention_prepass(layer, src_begin, src_end, _ptr(emb), _stream(stream)),
+           "atlas_attention_prepass")
+
+
+def atlas_broadcast_chunk(layer: int, src_begin: int, src_end: int, emb, stream=None) -> None:
+    _check(lib().atlas_broadcast_chunk(layer, src_begin, src_end, _ptr(emb), _stream(stream)),
+           "atlas_broadcast_chunk")
+
+
+def atlas_flush_ready(layer: int, out, stream=None, count: bool = False) -> Optional[int]:
+    """count=True waits for the stream and returns the number of rows written."""
+    n = ctypes.c_int64(0)
+    _check(lib().atlas_flush_ready(layer, _ptr(out), ctypes.byref(n) if count else None, _stream(stream)),
+           "atlas_flush_ready")
+    return n.value if count else None
+
+
+def atlas_layer_finish(layer: int) -> dict:
+    st = atlas_layer_stats_t()
+    status = lib().atlas_layer_finish(layer, ctypes.byref(st))
+    stats = {name: getattr(st, name) for name, _ in atlas_layer_stats_t._fields_}
+    if status != OK:
+        err = AtlasError(status, "atlas_layer_finish")
+        err.stats = stats
+        raise err
+    return stats
+
+
+def atlas_in_degree(graph: atlas_graph_t, in_degree, stream=None) -> None:
+    _check(lib().atlas_in_degree(ctypes.byref(graph), _ptr(in_degree), _stream(stream)), "atlas_in_degree")
+
+
+def atlas_reorder_indegree_desc(graph: atlas_graph_t, new_of_old, old_of_new) -> None:
+    _check(lib().atlas_reorder_indegree_desc(ctypes.byref(graph), _ptr(new_of_old), _ptr(old_of_new)),
+           "atlas_reorder_indegree_desc")
+
+
+def atlas_debug_copy(layer: int, what: int, host_array) -> None:
+    """host_array: a numpy array (contiguous) that receives the bytes."""
+    _check(lib().atlas_debug_copy(layer, what, host_array.ctypes.data, host_array.nbytes), "atlas_debug_copy")
+
+
+def atlas_release_cache() -> None:
+    _check(lib().atlas_release_cache(), "atlas_release_cache")

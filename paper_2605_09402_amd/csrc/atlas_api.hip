@@ -1,0 +1,502 @@
+// Host side of the C ABI declared in include/atlas.h: argument checks, the
+// per-layer state machine (strictly ordered chunks, paper Sec. 3.4), buffer
+// ownership, the pinned-host chunk loader on a second stream (the reader that
+// runs ahead of the orchestrator, Sec. 3.3) and the exactly-once check at the
+// end of a layer (Sec. 3.1).
+#include "../../include/atlas.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <mutex>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "atlas_kernels.h"
+
+using namespace atlas;
+
+namespace {
+
+thread_local std::string g_hip_error;
+
+int hip_fail(hipError_t e, const char *what) {
+    g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+    return e == hipErrorOutOfMemory ? ATLAS_E_NOMEM : ATLAS_E_HIP;
+}
+
+#define HIP_TRY(expr)                                     \
+    do {                                                  \
+        hipError_t e_ = (expr);                           \
+        if (e_ != hipSuccess) return hip_fail(e_, #expr); \
+    } while (0)
+
+// ---- device buffer cache: layers of one model reuse each other's buffers ----
+struct CachedBuf { void *p; size_t bytes; };
+std::mutex g_cache_mu;
+std::vector<CachedBuf> g_cache;
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+hipError_t cache_alloc(void **out, size_t bytes) {
+    bytes = round_up(bytes > 0 ? bytes : 1, 256);
+    {
+        std::lock_guard<std::mutex> lk(g_cache_mu);
+        int best = -1;
+        for (int i = 0; i < static_cast<int>(g_cache.size()); ++i)
+            if (g_cache[i].bytes >= bytes && g_cache[i].bytes <= bytes + bytes / 4 &&
+                (best < 0 || g_cache[i].bytes < g_cache[best].bytes))
+                best = i;
+        if (best >= 0) {
+            *out = g_cache[best].p;
+            g_cache.erase(g_cache.begin() + best);
+            return hipSuccess;
+        }
+    }
+    return hipMalloc(out, bytes);
+}
+
+struct Buf {
+    void *p = nullptr;
+    size_t bytes = 0;
+    hipError_t alloc(size_t n) {
+        bytes = round_up(n > 0 ? n : 1, 256);
+        return cache_alloc(&p, bytes);
+    }
+    void release() {
+        if (!p) return;
+        std::lock_guard<std::mutex> lk(g_cache_mu);
+        g_cache.push_back({p, bytes});
+        p = nullptr;
+    }
+};
+
+size_t dtype_size(int dt) { return dt == ATLAS_DTYPE_BF16 ? 2 : 4; }
+
+struct TimedSpan { hipEvent_t a, b; };
+
+}  // namespace
+
+struct atlas_layer {
+    atlas_graph_t g{};
+    atlas_dims_t dims{};
+    int64_t n = 0, e = 0;
+    int K = 0;
+    int compute_bf16 = 0;
+    int selfmsg = 0;
+    int acc_width = 0;
+
+    Buf indeg_own, pending, ready, counters, counters64, acc, self_rows, packed_w, bias, dev_off;
+    const int32_t *indeg = nullptr;
+    const int64_t *off_dev = nullptr;  // device-visible row offsets
+
+    int64_t next_src = 0;
+    int64_t num_chunks = 0, num_flushes = 0;
+    int64_t bytes_h2d = 0;
+
+    // pinned-host loader
+    hipStream_t copy_stream = nullptr;
+    hipEvent_t slot_loaded[2] = {nullptr, nullptr};
+    hipEvent_t slot_free[2] = {nullptr, nullptr};
+    bool slot_used[2] = {false, false};
+    Buf stage_col[2], stage_emb[2];
+
+    std::vector<TimedSpan> t_agg, t_upd, t_copy;
+    hipStream_t last_stream = nullptr;
+
+    int32_t *ctr() { return static_cast<int32_t *>(counters.p); }
+
+    void destroy() {
+        for (Buf *b : {&indeg_own, &pending, &ready, &counters, &counters64, &acc, &self_rows, &packed_w, &bias,
+                       &dev_off, &stage_col[0], &stage_col[1], &stage_emb[0], &stage_emb[1]})
+            b->release();
+        for (auto *v : {&t_agg, &t_upd, &t_copy})
+            for (auto &sp : *v) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
+        for (int i = 0; i < 2; ++i) {
+            if (slot_loaded[i]) (void)hipEventDestroy(slot_loaded[i]);
+            if (slot_free[i]) (void)hipEventDestroy(slot_free[i]);
+        }
+        if (copy_stream) (void)hipStreamDestroy(copy_stream);
+    }
+};
+
+namespace {
+
+int check_dims(const atlas_dims_t &d, const atlas_weights_t &w) {
+    if (d.model != ATLAS_MODEL_SAGE_MEAN && d.model != ATLAS_MODEL_GCN_SYM) return ATLAS_E_BAD_DIMS;
+    if (d.d_in <= 0 || d.d_in % 64 != 0 || d.d_in > 512) return ATLAS_E_BAD_DIMS;
+    if (d.d_out <= 0 || d.d_out % 16 != 0 || d.d_out > 256) return ATLAS_E_BAD_DIMS;
+    for (int dt : {d.in_dtype, d.out_dtype, w.dtype})
+        if (dt != ATLAS_DTYPE_F32 && dt != ATLAS_DTYPE_BF16) return ATLAS_E_BAD_DIMS;
+    if (d.activation < ATLAS_ACT_NONE || d.activation > ATLAS_ACT_ELU) return ATLAS_E_BAD_DIMS;
+    if (d.max_chunk_sources <= 0) return ATLAS_E_BAD_DIMS;
+    const int K = d.model == ATLAS_MODEL_SAGE_MEAN ? 2 * d.d_in : d.d_in;
+    const bool bf16c = d.in_dtype == ATLAS_DTYPE_BF16;
+    const size_t lds = 256 + static_cast<size_t>(64) * (K + (bf16c ? 8 : 1)) * (bf16c ? 2 : 4);
+    if (lds > 160 * 1024) return ATLAS_E_BAD_DIMS;
+    return ATLAS_OK;
+}
+
+int start_span(atlas_layer *L, std::vector<TimedSpan> &v, hipStream_t s) {
+    if (!(L->dims.flags & ATLAS_FLAG_TIMING)) return ATLAS_OK;
+    TimedSpan sp{};
+    HIP_TRY(hipEventCreate(&sp.a));
+    HIP_TRY(hipEventCreate(&sp.b));
+    v.push_back(sp);
+    HIP_TRY(hipEventRecord(sp.a, s));
+    return ATLAS_OK;
+}
+int end_span(atlas_layer *L, std::vector<TimedSpan> &v, hipStream_t s) {
+    if (!(L->dims.flags & ATLAS_FLAG_TIMING)) return ATLAS_OK;
+    HIP_TRY(hipEventRecord(v.back().b, s));
+    return ATLAS_OK;
+}
+float sum_spans(std::vector<TimedSpan> &v) {
+    float total = 0.f;
+    for (auto &sp : v) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, sp.a, sp.b) == hipSuccess) total += ms;
+    }
+    return total;
+}
+
+int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
+    const atlas_dims_t &d = L->dims;
+    const int64_t n = L->n;
+    const size_t n1 = static_cast<size_t>(n > 0 ? n : 1);
+    HIP_TRY(L->counters.alloc(CTR_COUNT * sizeof(int32_t)));
+    HIP_TRY(L->counters64.alloc(CTR64_COUNT * sizeof(unsigned long long)));
+    HIP_TRY(L->pending.alloc(n1 * sizeof(int32_t)));
+    HIP_TRY(L->ready.alloc(n1 * sizeof(int32_t)));
+    HIP_TRY(L->acc.alloc(n1 * L->acc_width * sizeof(float)));
+    if (d.model == ATLAS_MODEL_SAGE_MEAN) HIP_TRY(L->self_rows.alloc(n1 * d.d_in * dtype_size(d.in_dtype)));
+    HIP_TRY(L->packed_w.alloc(packed_weight_bytes(L->K, d.d_out, L->compute_bf16)));
+    HIP_TRY(launch_fill_zero(L->counters.p, L->counters.bytes, s));
+    HIP_TRY(launch_fill_zero(L->counters64.p, L->counters64.bytes, s));
+    HIP_TRY(launch_fill_zero(L->acc.p, static_cast<size_t>(n) * L->acc_width * sizeof(float), s));
+
+    if (L->g.residency == ATLAS_RESIDENT_PINNED_HOST) {
+        // row offsets are small next to the edge array: keep a device copy for the kernels
+        HIP_TRY(L->dev_off.alloc((n1 + 1) * sizeof(int64_t)));
+        HIP_TRY(hipMemcpyAsync(L->dev_off.p, L->g.row_offsets, (static_cast<size_t>(n) + 1) * sizeof(int64_t),
+                               hipMemcpyHostToDevice, s));
+        L->off_dev = static_cast<const int64_t *>(L->dev_off.p);
+        L->bytes_h2d += (n + 1) * static_cast<int64_t>(sizeof(int64_t));
+        HIP_TRY(hipStreamCreateWithFlags(&L->copy_stream, hipStreamNonBlocking));
+        for (int i = 0; i < 2; ++i) {
+            HIP_TRY(hipEventCreateWithFlags(&L->slot_loaded[i], hipEventDisableTiming));
+            HIP_TRY(hipEventCreateWithFlags(&L->slot_free[i], hipEventDisableTiming));
+        }
+        // size the edge staging slots for the largest aligned chunk
+        int64_t max_edges = 0;
+        const int64_t C = d.max_chunk_sources;
+        for (int64_t b = 0; b < n; b += C) {
+            const int64_t e = std::min(n, b + C);
+            max_edges = std::max(max_edges, L->g.row_offsets[e] - L->g.row_offsets[b]);
+        }
+        for (int i = 0; i < 2; ++i) {
+            HIP_TRY(L->stage_col[i].alloc(static_cast<size_t>(std::max<int64_t>(max_edges, 1)) * sizeof(int32_t)));
+            if (d.model != ATLAS_MODEL_SAGE_MEAN)
+                HIP_TRY(L->stage_emb[i].alloc(static_cast<size_t>(std::min(C, std::max<int64_t>(n, 1))) * d.d_in *
+                                              dtype_size(d.in_dtype)));
+        }
+    } else {
+        L->off_dev = L->g.row_offsets;
+    }
+
+    if (L->g.in_degree) {
+        L->indeg = L->g.in_degree;
+    } else {
+        HIP_TRY(L->indeg_own.alloc(n1 * sizeof(int32_t)));
+        HIP_TRY(launch_in_degree(L->g.col_indices, L->e, static_cast<int32_t *>(L->indeg_own.p), n, s));
+        L->indeg = static_cast<const int32_t *>(L->indeg_own.p);
+    }
+    HIP_TRY(launch_init_pending(L->indeg, L->selfmsg, n, static_cast<int32_t *>(L->pending.p),
+                                static_cast<int32_t *>(L->ready.p), L->ctr(), s));
+    HIP_TRY(launch_pack_weights(w->W, w->dtype == ATLAS_DTYPE_BF16, L->K, d.d_out, L->compute_bf16,
+                                L->packed_w.p, s));
+    if (w->bias) {
+        HIP_TRY(L->bias.alloc(d.d_out * sizeof(float)));
+        HIP_TRY(launch_to_f32(w->bias, w->dtype == ATLAS_DTYPE_BF16, d.d_out, static_cast<float *>(L->bias.p), s));
+    }
+    return ATLAS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int atlas_layer_init(const atlas_graph_t *graph, const atlas_dims_t *dims, const atlas_weights_t *weights,
+                     void *hip_stream, atlas_layer_t **out) {
+    if (!graph || !dims || !weights || !out) return ATLAS_E_NULL;
+    if (graph->num_vertices < 0 || graph->num_edges < 0) return ATLAS_E_RANGE;
+    if (graph->num_vertices >= (int64_t(1) << 31)) return ATLAS_E_OVERFLOW;
+    if (!graph->row_offsets || (graph->num_edges > 0 && !graph->col_indices) || !weights->W) return ATLAS_E_NULL;
+    if (graph->residency != ATLAS_RESIDENT_DEVICE && graph->residency != ATLAS_RESIDENT_PINNED_HOST)
+        return ATLAS_E_BAD_DIMS;
+    int rc = check_dims(*dims, *weights);
+    if (rc != ATLAS_OK) return rc;
+
+    atlas_layer *L = new (std::nothrow) atlas_layer();
+    if (!L) return ATLAS_E_NOMEM;
+    L->g = *graph;
+    L->dims = *dims;
+    L->n = graph->num_vertices;
+    L->e = graph->num_edges;
+    L->selfmsg = dims->model == ATLAS_MODEL_SAGE_MEAN ? 1 : 0;
+    L->K = dims->model == ATLAS_MODEL_SAGE_MEAN ? 2 * dims->d_in : dims->d_in;
+    L->compute_bf16 = dims->in_dtype == ATLAS_DTYPE_BF16;
+    L->acc_width = dims->d_in;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    L->last_stream = s;
+    rc = init_impl(L, weights, s);
+    if (rc != ATLAS_OK) {
+        (void)hipStreamSynchronize(s);
+        L->destroy();
+        delete L;
+        return rc;
+    }
+    *out = L;
+    return ATLAS_OK;
+}
+
+int atlas_attention_prepass(atlas_layer_t *layer, int64_t, int64_t, const void *, void *) {
+    if (!layer) return ATLAS_E_NULL;
+    return ATLAS_E_STATE;
+}
+
+int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, const void *emb,
+                          void *hip_stream) {
+    if (!L || !emb) return ATLAS_E_NULL;
+    if (src_begin < 0 || src_end > L->n || src_begin >= src_end ||
+        src_end - src_begin > L->dims.max_chunk_sources)
+        return ATLAS_E_RANGE;
+    if (src_begin != L->next_src) return ATLAS_E_ORDER;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    L->last_stream = s;
+    const atlas_dims_t &d = L->dims;
+    const size_t row_bytes = static_cast<size_t>(d.d_in) * dtype_size(d.in_dtype);
+    const size_t emb_bytes = static_cast<size_t>(src_end - src_begin) * row_bytes;
+
+    AggregateArgs a{};
+    a.off = L->off_dev;
+    a.src_begin = src_begin;
+    a.src_end = src_end;
+    a.d = d.d_in;
+    a.in_bf16 = d.in_dtype == ATLAS_DTYPE_BF16;
+    a.model = d.model;
+    a.acc = static_cast<float *>(L->acc.p);
+    a.pending = static_cast<int32_t *>(L->pending.p);
+    a.indeg = L->indeg;
+    a.ready = static_cast<int32_t *>(L->ready.p);
+    a.counters = L->ctr();
+    a.counters64 = static_cast<unsigned long long *>(L->counters64.p);
+
+    char *self_dst = d.model == ATLAS_MODEL_SAGE_MEAN
+                         ? static_cast<char *>(L->self_rows.p) + static_cast<size_t>(src_begin) * row_bytes
+                         : nullptr;
+    int slot = -1;
+    if (L->g.residency == ATLAS_RESIDENT_PINNED_HOST) {
+        // Stage the chunk into HBM on the copy stream; the compute stream only
+        // waits for this chunk's event, so the copy of chunk k+1 (enqueued by
+        // the next call) overlaps the kernels of chunk k.
+        slot = static_cast<int>(L->num_chunks & 1);
+        const int64_t e0 = L->g.row_offsets[src_begin], e1 = L->g.row_offsets[src_end];
+        const size_t col_bytes = static_cast<size_t>(e1 - e0) * sizeof(int32_t);
+        if (col_bytes > L->stage_col[slot].bytes) {
+            // a chunk larger than any aligned one: wait for the slot, then grow it
+            if (L->slot_used[slot]) HIP_TRY(hipEventSynchronize(L->slot_free[slot]));
+            Buf bigger;
+            HIP_TRY(bigger.alloc(col_bytes));
+            L->stage_col[slot].release();
+            L->stage_col[slot] = bigger;
+        }
+        if (L->slot_used[slot]) HIP_TRY(hipStreamWaitEvent(L->copy_stream, L->slot_free[slot], 0));
+        int rc = start_span(L, L->t_copy, L->copy_stream);
+        if (rc != ATLAS_OK) return rc;
+        void *emb_dst = self_dst ? static_cast<void *>(self_dst) : L->stage_emb[slot].p;
+        HIP_TRY(hipMemcpyAsync(emb_dst, emb, emb_bytes, hipMemcpyHostToDevice, L->copy_stream));
+        if (col_bytes)
+            HIP_TRY(hipMemcpyAsync(L->stage_col[slot].p, L->g.col_indices + e0, col_bytes, hipMemcpyHostToDevice,
+                                   L->copy_stream));
+        rc = end_span(L, L->t_copy, L->copy_stream);
+        if (rc != ATLAS_OK) return rc;
+        HIP_TRY(hipEventRecord(L->slot_loaded[slot], L->copy_stream));
+        HIP_TRY(hipStreamWaitEvent(s, L->slot_loaded[slot], 0));
+        L->bytes_h2d += static_cast<int64_t>(emb_bytes + col_bytes);
+        a.col = static_cast<const int32_t *>(L->stage_col[slot].p);
+        a.col_base = e0;
+        a.emb = emb_dst;
+    } else {
+        a.col = L->g.col_indices;
+        a.col_base = 0;
+        a.emb = emb;
+    }
+
+    int rc = start_span(L, L->t_agg, s);
+    if (rc != ATLAS_OK) return rc;
+    if (self_dst && L->g.residency == ATLAS_RESIDENT_DEVICE)
+        HIP_TRY(hipMemcpyAsync(self_dst, emb, emb_bytes, hipMemcpyDeviceToDevice, s));
+    HIP_TRY(launch_aggregate(a, s));
+    if (L->selfmsg)
+        HIP_TRY(launch_self_message(src_begin, src_end, a.pending, a.ready, a.counters, s));
+    rc = end_span(L, L->t_agg, s);
+    if (rc != ATLAS_OK) return rc;
+    if (slot >= 0) {
+        HIP_TRY(hipEventRecord(L->slot_free[slot], s));
+        L->slot_used[slot] = true;
+    }
+    L->next_src = src_end;
+    L->num_chunks += 1;
+    return ATLAS_OK;
+}
+
+int atlas_flush_ready(atlas_layer_t *L, void *out, int64_t *n_flushed, void *hip_stream) {
+    if (!L || !out) return ATLAS_E_NULL;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    L->last_stream = s;
+    const atlas_dims_t &d = L->dims;
+    int32_t before[2] = {0, 0};
+    if (n_flushed) {
+        HIP_TRY(hipMemcpyAsync(before, L->ctr(), sizeof(before), hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+    }
+    UpdateArgs u{};
+    u.model = d.model;
+    u.d_in = d.d_in;
+    u.d_out = d.d_out;
+    u.K = L->K;
+    u.in_bf16 = d.in_dtype == ATLAS_DTYPE_BF16;
+    u.out_bf16 = d.out_dtype == ATLAS_DTYPE_BF16;
+    u.compute_bf16 = L->compute_bf16;
+    u.activation = d.activation;
+    u.acc = static_cast<const float *>(L->acc.p);
+    u.self_rows = L->self_rows.p;
+    u.indeg = L->indeg;
+    u.ready = static_cast<const int32_t *>(L->ready.p);
+    u.counters = L->ctr();
+    u.packed_w = L->packed_w.p;
+    u.bias = static_cast<const float *>(L->bias.p);
+    u.out = out;
+    u.n = L->n;
+    int rc = start_span(L, L->t_upd, s);
+    if (rc != ATLAS_OK) return rc;
+    HIP_TRY(launch_update(u, s));
+    HIP_TRY(launch_advance_head(L->ctr(), s));
+    rc = end_span(L, L->t_upd, s);
+    if (rc != ATLAS_OK) return rc;
+    L->num_flushes += 1;
+    if (n_flushed) *n_flushed = static_cast<int64_t>(before[CTR_READY_TAIL]) - before[CTR_READY_HEAD];
+    return ATLAS_OK;
+}
+
+int atlas_layer_finish(atlas_layer_t *L, atlas_layer_stats_t *stats) {
+    if (!L) return ATLAS_E_NULL;
+    int rc = ATLAS_OK;
+    int32_t c[CTR_COUNT] = {0};
+    unsigned long long c64[CTR64_COUNT] = {0};
+    hipError_t e = hipStreamSynchronize(L->last_stream);
+    if (e == hipSuccess && L->copy_stream) e = hipStreamSynchronize(L->copy_stream);
+    if (e == hipSuccess) e = hipMemcpy(c, L->counters.p, sizeof(c), hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(c64, L->counters64.p, sizeof(c64), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) rc = hip_fail(e, "atlas_layer_finish");
+    if (stats) {
+        *stats = atlas_layer_stats_t{};
+        stats->edges_processed = static_cast<int64_t>(c64[CTR64_EDGES]);
+        stats->sources_processed = L->next_src;
+        stats->vertices_completed = c[CTR_READY_TAIL];
+        stats->vertices_flushed = c[CTR_READY_HEAD];
+        stats->num_chunks = L->num_chunks;
+        stats->num_flushes = L->num_flushes;
+        stats->bytes_copied_h2d = L->bytes_h2d;
+        if (rc == ATLAS_OK) {
+            stats->ms_aggregate = sum_spans(L->t_agg);
+            stats->ms_update = sum_spans(L->t_upd);
+            stats->ms_copy = sum_spans(L->t_copy);
+        }
+    }
+    if (rc == ATLAS_OK &&
+        (L->next_src != L->n || c[CTR_READY_TAIL] != L->n || c[CTR_READY_HEAD] != L->n ||
+         static_cast<int64_t>(c64[CTR64_EDGES]) != L->e))
+        rc = ATLAS_E_INCOMPLETE;
+    L->destroy();
+    delete L;
+    return rc;
+}
+
+int atlas_in_degree(const atlas_graph_t *graph, int32_t *in_degree, void *hip_stream) {
+    if (!graph || !in_degree) return ATLAS_E_NULL;
+    if (graph->num_edges > 0 && !graph->col_indices) return ATLAS_E_NULL;
+    if (graph->num_vertices < 0 || graph->num_edges < 0) return ATLAS_E_RANGE;
+    if (graph->num_vertices >= (int64_t(1) << 31)) return ATLAS_E_OVERFLOW;
+    HIP_TRY(launch_in_degree(graph->col_indices, graph->num_edges, in_degree, graph->num_vertices,
+                             static_cast<hipStream_t>(hip_stream)));
+    return ATLAS_OK;
+}
+
+int atlas_reorder_indegree_desc(const atlas_graph_t *graph, int32_t *new_of_old, int32_t *old_of_new) {
+    if (!graph || !new_of_old || !old_of_new || !graph->in_degree) return ATLAS_E_NULL;
+    if (graph->num_vertices < 0) return ATLAS_E_RANGE;
+    if (graph->num_vertices >= (int64_t(1) << 31)) return ATLAS_E_OVERFLOW;
+    HIP_TRY(reorder_indegree_desc(graph->in_degree, graph->num_vertices, new_of_old, old_of_new));
+    return ATLAS_OK;
+}
+
+int atlas_debug_copy(atlas_layer_t *L, int what, void *host_dst, int64_t bytes) {
+    if (!L || !host_dst) return ATLAS_E_NULL;
+    if (bytes < 0) return ATLAS_E_RANGE;
+    HIP_TRY(hipStreamSynchronize(L->last_stream));
+    const void *src = nullptr;
+    int64_t avail = 0;
+    int32_t c[2] = {0, 0};
+    HIP_TRY(hipMemcpy(c, L->counters.p, sizeof(c), hipMemcpyDeviceToHost));
+    int64_t pair[2] = {c[CTR_READY_TAIL], c[CTR_READY_HEAD]};
+    switch (what) {
+        case ATLAS_DBG_INDEG: src = L->indeg; avail = L->n * 4; break;
+        case ATLAS_DBG_PENDING: src = L->pending.p; avail = L->n * 4; break;
+        case ATLAS_DBG_READY: src = L->ready.p; avail = static_cast<int64_t>(c[CTR_READY_TAIL]) * 4; break;
+        case ATLAS_DBG_ACC: src = L->acc.p; avail = L->n * L->acc_width * 4; break;
+        case ATLAS_DBG_READY_COUNT:
+            if (bytes < static_cast<int64_t>(sizeof(pair))) return ATLAS_E_RANGE;
+            static_cast<int64_t *>(host_dst)[0] = pair[0];
+            static_cast<int64_t *>(host_dst)[1] = pair[1];
+            return ATLAS_OK;
+        default: return ATLAS_E_BAD_DIMS;
+    }
+    if (bytes > avail) return ATLAS_E_RANGE;
+    if (bytes > 0) HIP_TRY(hipMemcpy(host_dst, src, static_cast<size_t>(bytes), hipMemcpyDeviceToHost));
+    return ATLAS_OK;
+}
+
+int atlas_release_cache(void) {
+    std::lock_guard<std::mutex> lk(g_cache_mu);
+    hipError_t first = hipSuccess;
+    for (auto &b : g_cache) {
+        hipError_t e = hipFree(b.p);
+        if (e != hipSuccess && first == hipSuccess) first = e;
+    }
+    g_cache.clear();
+    if (first != hipSuccess) return hip_fail(first, "hipFree");
+    return ATLAS_OK;
+}
+
+const char *atlas_strerror(int status) {
+    switch (status) {
+        case ATLAS_OK: return "ok";
+        case ATLAS_E_NULL: return "required pointer is NULL";
+        case ATLAS_E_BAD_DIMS: return "unsupported dimensions or enum value";
+        case ATLAS_E_RANGE: return "chunk bounds or size out of range";
+        case ATLAS_E_ORDER: return "chunks must be contiguous and ascending from 0";
+        case ATLAS_E_INCOMPLETE: return "layer finished before every vertex was completed and flushed";
+        case ATLAS_E_OVERFLOW: return "vertex count does not fit int32";
+        case ATLAS_E_HIP: return "HIP call failed";
+        case ATLAS_E_NOMEM: return "out of memory";
+        case ATLAS_E_STATE: return "call not valid in this state";
+        default: return "unknown status";
+    }
+}
+
+const char *atlas_last_hip_error(void) { return g_hip_error.c_str(); }
+
+}  // extern "C"

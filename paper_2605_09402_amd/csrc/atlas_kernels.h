@@ -1,0 +1,81 @@
+// Internal launch interface between the host state machine (atlas_api.hip)
+// and the gfx950 kernels.  Not part of the public ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace atlas {
+
+// Device-side counters of one layer (int32 each, one 256-byte block).
+enum Counter {
+    CTR_READY_TAIL = 0,  // ready-list length (vertices completed so far)
+    CTR_READY_HEAD = 1,  // ready-list prefix already flushed
+    CTR_NUM_FLUSHES = 2,
+    CTR_COUNT = 64
+};
+
+// 64-bit counters (separate block): edges pushed so far.
+enum Counter64 { CTR64_EDGES = 0, CTR64_COUNT = 8 };
+
+struct AggregateArgs {
+    const int64_t *off;    // row offsets addressed by global source id
+    const int32_t *col;    // col[e - col_base] is the destination of edge e
+    int64_t col_base;
+    const void *emb;       // chunk rows; row u lives at (u - src_begin) * d
+    int64_t src_begin, src_end;
+    int d;                 // row width (elements)
+    int in_bf16;           // 1: rows are bf16, 0: fp32
+    int model;             // atlas_model
+    float *acc;            // [N][d] fp32
+    int32_t *pending;      // [N]
+    const int32_t *indeg;  // [N]
+    int32_t *ready;        // [N]
+    int32_t *counters;
+    unsigned long long *counters64;
+};
+
+// S2+S3+S4: edge-balanced scatter-aggregate with fused pending decrement and
+// wave-level ready compaction.
+hipError_t launch_aggregate(const AggregateArgs &a, hipStream_t s);
+
+// SAGE self message of sources [b, e): pending[u] -= 1 with ready compaction.
+hipError_t launch_self_message(int64_t b, int64_t e, int32_t *pending, int32_t *ready,
+                               int32_t *counters, hipStream_t s);
+
+// S0 pieces.
+hipError_t launch_in_degree(const int32_t *col, int64_t num_edges, int32_t *indeg, int64_t n,
+                            hipStream_t s);
+hipError_t launch_init_pending(const int32_t *indeg, int32_t selfmsg, int64_t n, int32_t *pending,
+                               int32_t *ready, int32_t *counters, hipStream_t s);
+hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
+
+// Weight repack into MFMA B-fragment order (see k_update.hip).
+size_t packed_weight_bytes(int K, int d_out, int compute_bf16);
+hipError_t launch_pack_weights(const void *W, int w_bf16, int K, int d_out, int compute_bf16,
+                               void *packed, hipStream_t s);
+hipError_t launch_to_f32(const void *src, int src_bf16, int64_t count, float *dst, hipStream_t s);
+
+struct UpdateArgs {
+    int model;
+    int d_in, d_out, K;       // K = 2*d_in (SAGE) or d_in (GCN)
+    int in_bf16, out_bf16, compute_bf16;
+    int activation;
+    const float *acc;         // [N][d_in]
+    const void *self_rows;    // SAGE: [N][d_in] in in_dtype
+    const int32_t *indeg;
+    const int32_t *ready;
+    int32_t *counters;
+    const void *packed_w;
+    const float *bias;        // fp32 [d_out] or nullptr
+    void *out;                // [N][d_out]
+    int64_t n;
+};
+// S5: gather ready rows, normalise, MFMA GEMM, bias, activation, scatter rows.
+hipError_t launch_update(const UpdateArgs &a, hipStream_t s);
+hipError_t launch_advance_head(int32_t *counters, hipStream_t s);
+
+// Degree ordering.
+hipError_t reorder_indegree_desc(const int32_t *indeg, int64_t n, int32_t *new_of_old,
+                                 int32_t *old_of_new);
+
+}  // namespace atlas

@@ -1,0 +1,215 @@
+// Broadcast step of one source chunk: push every source row along its
+// out-edges into the per-destination fp32 accumulators, decrement the
+// destination's pending-message count once per message, and append the
+// destinations whose count reaches zero to the ready list.
+// (Paper Sec. 3.1 broadcast model; Sec. 3.4 message construction and the
+// pending-message tracker; Sec. 3.6 completion when the count reaches zero.)
+//
+// Work is split by EDGES, not by sources: a wavefront owns 64 consecutive
+// edges of the chunk's CSR slice, so a source with a million out-edges and a
+// run of sources with one edge each cost the same.  The wave finds the source
+// of its first edge with a 64-ary search over the row offsets, resolves the
+// source of every edge in registers, then walks its edges: the 64 lanes hold
+// one source row (d/64 elements per lane, lane-contiguous so that every
+// atomic instruction covers whole cache lines of the destination row).
+#include "atlas_kernels.h"
+
+#include <hip/hip_runtime.h>
+
+namespace atlas {
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kTileEdges = 64;
+constexpr int kBlock = 256;
+
+__device__ __forceinline__ float load_as_f32(const float *p) { return *p; }
+__device__ __forceinline__ float load_as_f32(const uint16_t *p) {
+    return __uint_as_float(static_cast<uint32_t>(*p) << 16);
+}
+
+// Largest u in [lo, hi) with off[u] <= e.  Requires off[lo] <= e < off[hi].
+// All 64 lanes take part; the result is wave-uniform.
+__device__ __forceinline__ int64_t wave_find_source(const int64_t *__restrict__ off, int64_t lo,
+                                                    int64_t hi, int64_t e, int lane) {
+    while (hi - lo > 1) {
+        const int64_t step = (hi - lo + 63) >> 6;
+        const int64_t p = lo + static_cast<int64_t>(lane) * step;
+        bool ok = false;
+        if (p < hi) ok = off[p] <= e;
+        const int c = __popcll(__ballot(ok));  // offsets ascend: a prefix of lanes says yes
+        lo += static_cast<int64_t>(c - 1) * step;
+        const int64_t nh = lo + step;
+        hi = nh < hi ? nh : hi;
+    }
+    return lo;
+}
+
+// Append the lanes flagged `is_ready` to the ready list with one counter
+// update per wave.
+__device__ __forceinline__ void wave_append_ready(bool is_ready, int32_t v, int32_t *ready,
+                                                  int32_t *counters, int lane) {
+    const uint64_t m = __ballot(is_ready);
+    if (m == 0) return;
+    const int leader = __ffsll(static_cast<unsigned long long>(m)) - 1;
+    int base = 0;
+    if (lane == leader) base = atomicAdd(&counters[CTR_READY_TAIL], __popcll(m));
+    base = __shfl(base, leader);
+    if (is_ready) ready[base + __popcll(m & ((1ull << lane) - 1ull))] = v;
+}
+
+template <typename T, int VPL, int MODEL>
+__global__ __launch_bounds__(kBlock) void k_aggregate(AggregateArgs a) {
+    constexpr int D = VPL * kWave;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t wave = static_cast<int64_t>(blockIdx.x) * (kBlock / kWave) + (threadIdx.x >> 6);
+    const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (kBlock / kWave);
+    const int64_t ebeg = a.off[a.src_begin];
+    const int64_t eend = a.off[a.src_end];
+    const int64_t ntiles = (eend - ebeg + kTileEdges - 1) / kTileEdges;
+    const T *__restrict__ emb = static_cast<const T *>(a.emb);
+
+    if (wave == 0 && lane == 0)
+        atomicAdd(&a.counters64[CTR64_EDGES], static_cast<unsigned long long>(eend - ebeg));
+
+    for (int64_t t = wave; t < ntiles; t += nwaves) {
+        const int64_t e0 = ebeg + t * kTileEdges;
+        const int64_t left = eend - e0;
+        const int cnt = left < kTileEdges ? static_cast<int>(left) : kTileEdges;
+        const int64_t u0 = wave_find_source(a.off, a.src_begin, a.src_end, e0, lane);
+
+        int32_t v = 0;
+        if (lane < cnt) v = a.col[e0 + lane - a.col_base];
+
+        // Source of every edge of the tile, as an offset from u0.  Lane k
+        // fetches the end offset of source ubase+k; an edge's source is the
+        // number of row ends at or before it, found by a binary search over
+        // the 64 lane-held ends.  A tile spanning more than 64 sources (long
+        // runs of sources without out-edges) re-anchors with another search.
+        int my_src = 0;
+        bool found = lane >= cnt;
+        int64_t ubase = u0;
+        while (true) {
+            const int64_t u = ubase + lane;
+            int relend = kTileEdges;
+            if (u < a.src_end) {
+                const int64_t r = a.off[u + 1] - e0;
+                relend = r < kTileEdges ? static_cast<int>(r) : kTileEdges;
+            }
+            int lo = 0, hi = kWave;
+#pragma unroll
+            for (int it = 0; it < 7; ++it) {
+                const int mid = (lo + hi) >> 1;
+                const int r = __shfl(relend, mid & (kWave - 1));
+                const bool open = lo < hi;
+                const bool le = r <= lane;
+                if (open && le) lo = mid + 1;
+                if (open && !le) hi = mid;
+            }
+            if (!found && lo < kWave) {
+                my_src = static_cast<int>(ubase - u0) + lo;
+                found = true;
+            }
+            const uint64_t todo = __ballot(!found);
+            if (todo == 0) break;
+            const int first = __ffsll(static_cast<unsigned long long>(todo)) - 1;
+            ubase = wave_find_source(a.off, ubase, a.src_end, e0 + first, lane);
+        }
+
+        float x[VPL];
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) x[i] = 0.f;
+        int uprev = -1;
+        for (int j = 0; j < cnt; ++j) {
+            const int so = __builtin_amdgcn_readlane(my_src, j);
+            const int32_t vj = __builtin_amdgcn_readlane(v, j);
+            if (so != uprev) {
+                uprev = so;
+                const int64_t u = u0 + so;
+                const T *row = emb + (u - a.src_begin) * D + lane;
+                float g = 1.f;
+                if (MODEL == 1) {  // GCN: source side of the symmetric normalisation
+                    const int32_t du = a.indeg[u];
+                    g = 1.0f / sqrtf(static_cast<float>(du > 0 ? du : 1));
+                }
+#pragma unroll
+                for (int i = 0; i < VPL; ++i) x[i] = load_as_f32(row + i * kWave) * g;
+            }
+            float *dst = a.acc + static_cast<int64_t>(vj) * D + lane;
+#pragma unroll
+            for (int i = 0; i < VPL; ++i) unsafeAtomicAdd(dst + i * kWave, x[i]);
+        }
+
+        // One pending-count decrement per message; the message that takes the
+        // count to zero completes the destination.
+        bool is_ready = false;
+        if (lane < cnt) is_ready = atomicSub(&a.pending[v], 1) == 1;
+        wave_append_ready(is_ready, v, a.ready, a.counters, lane);
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_self_message(int64_t b, int64_t e, int32_t *pending,
+                                                         int32_t *ready, int32_t *counters) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    const int64_t span = e - b;
+    const int64_t rounded = (span + kBlock - 1) / kBlock * kBlock;  // keep whole waves in the loop
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; i < rounded; i += stride) {
+        bool is_ready = false;
+        int32_t u = 0;
+        if (i < span) {
+            u = static_cast<int32_t>(b + i);
+            is_ready = atomicSub(&pending[u], 1) == 1;
+        }
+        wave_append_ready(is_ready, u, ready, counters, lane);
+    }
+}
+
+template <typename T, int MODEL>
+hipError_t launch_vpl(const AggregateArgs &a, int grid, hipStream_t s) {
+    switch (a.d / kWave) {
+        case 1: hipLaunchKernelGGL((k_aggregate<T, 1, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 2: hipLaunchKernelGGL((k_aggregate<T, 2, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 3: hipLaunchKernelGGL((k_aggregate<T, 3, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 4: hipLaunchKernelGGL((k_aggregate<T, 4, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 5: hipLaunchKernelGGL((k_aggregate<T, 5, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 6: hipLaunchKernelGGL((k_aggregate<T, 6, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 7: hipLaunchKernelGGL((k_aggregate<T, 7, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 8: hipLaunchKernelGGL((k_aggregate<T, 8, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+int persistent_grid(int blocks_per_cu) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 1024;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        return 1024;
+    return cus * blocks_per_cu;
+}
+
+}  // namespace
+
+hipError_t launch_aggregate(const AggregateArgs &a, hipStream_t s) {
+    if (a.d % kWave != 0) return hipErrorInvalidValue;
+    const int grid = persistent_grid(8);
+    // model 1 (GCN) scales the source row; every other model pushes it as is
+    if (a.in_bf16) {
+        return a.model == 1 ? launch_vpl<uint16_t, 1>(a, grid, s) : launch_vpl<uint16_t, 0>(a, grid, s);
+    }
+    return a.model == 1 ? launch_vpl<float, 1>(a, grid, s) : launch_vpl<float, 0>(a, grid, s);
+}
+
+hipError_t launch_self_message(int64_t b, int64_t e, int32_t *pending, int32_t *ready,
+                               int32_t *counters, hipStream_t s) {
+    if (e <= b) return hipSuccess;
+    int64_t blocks = (e - b + kBlock - 1) / kBlock;
+    const int cap = persistent_grid(8);
+    if (blocks > cap) blocks = cap;
+    hipLaunchKernelGGL(k_self_message, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, s, b, e,
+                       pending, ready, counters);
+    return hipGetLastError();
+}
+
+}  // namespace atlas

@@ -1,0 +1,266 @@
+// Dense update of ready ("graduated") vertices: gather the finished aggregate
+// of every vertex on the ready list, normalise it, multiply by the layer's
+// weight matrix on the matrix cores, add bias, apply the activation and write
+// the row of the next-layer embedding matrix.  (Paper Sec. 3.6: the linear
+// transformation and non-linearity applied to completed vertices; Sec. 3.4 for
+// the mean normalisation; Sec. 4.3 for the self-concatenation of SAGE.)
+//
+// A workgroup (4 waves) takes a tile of 64 ready rows.  The rows are gathered
+// with whole-row coalesced loads, normalised (1/deg for the SAGE mean,
+// deg^-1/2 for GCN), converted to the MFMA input type and staged in LDS as the
+// A operand [64][K].  W is repacked once per layer into the per-lane
+// B-fragment order of the 32x32 MFMA, so a wave fetches a fragment with one
+// contiguous 1 KiB (bf16) / 256 B (fp32) load that stays L2 resident.
+// The 64 x d_out output tile is cut into 32x32 blocks dealt round-robin to the
+// four waves.  Workgroups loop over tiles (the ready count lives on the device,
+// the host never reads it).
+#include "atlas_kernels.h"
+
+#include <hip/hip_runtime.h>
+
+namespace atlas {
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kTileRows = 64;
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x40u);  // NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return static_cast<uint16_t>(u >> 16);
+}
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) {
+    return __uint_as_float(static_cast<uint32_t>(h) << 16);
+}
+
+template <bool BF16C> struct Elem { using type = float; };
+template <> struct Elem<true> { using type = uint16_t; };
+
+template <bool BF16C> __device__ __forceinline__ typename Elem<BF16C>::type to_elem(float f);
+template <> __device__ __forceinline__ float to_elem<false>(float f) { return f; }
+template <> __device__ __forceinline__ uint16_t to_elem<true>(float f) { return f32_to_bf16_rne(f); }
+
+__host__ __device__ constexpr int lds_pad(bool bf16c) { return bf16c ? 8 : 1; }
+
+// Packed-W element index.  bf16: fragment (nb, kk) is 64 lanes x 8 values,
+// value t of lane l is W[kk*16 + (l/32)*8 + t][nb*32 + l%32].
+// fp32: fragment (nb, kk) is 64 lanes x 1 value, W[kk*2 + l/32][nb*32 + l%32].
+template <bool BF16C>
+__global__ __launch_bounds__(kBlock) void k_pack_weights(const void *W, int w_bf16, int K, int d_out,
+                                                         typename Elem<BF16C>::type *packed) {
+    constexpr int kStepK = BF16C ? 16 : 2;
+    constexpr int kPerLane = BF16C ? 8 : 1;
+    const int NB = (d_out + 31) / 32;
+    const int KS = K / kStepK;
+    const int64_t total = static_cast<int64_t>(NB) * KS * 64 * kPerLane;
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (i >= total) return;
+    const int t = static_cast<int>(i % kPerLane);
+    const int l = static_cast<int>((i / kPerLane) % 64);
+    const int64_t frag = i / (kPerLane * 64);
+    const int kk = static_cast<int>(frag % KS);
+    const int nb = static_cast<int>(frag / KS);
+    const int k = kk * kStepK + (l / 32) * kPerLane + t;
+    const int j = nb * 32 + (l % 32);
+    float w = 0.f;
+    if (j < d_out) {
+        const int64_t src = static_cast<int64_t>(k) * d_out + j;
+        w = w_bf16 ? bf16_to_f32(static_cast<const uint16_t *>(W)[src]) : static_cast<const float *>(W)[src];
+    }
+    packed[i] = to_elem<BF16C>(w);
+}
+
+__device__ __forceinline__ float apply_activation(float y, int act) {
+    if (act == 1) return y > 0.f ? y : 0.f;
+    if (act == 2) return y > 0.f ? y : expm1f(y);
+    return y;
+}
+
+template <bool BF16C, int PPW>
+__global__ __launch_bounds__(kBlock) void k_update(UpdateArgs a) {
+    using elem_t = typename Elem<BF16C>::type;
+    extern __shared__ __align__(16) unsigned char smem[];
+    int32_t *ids = reinterpret_cast<int32_t *>(smem);                 // [64]
+    elem_t *A = reinterpret_cast<elem_t *>(smem + kTileRows * sizeof(int32_t));
+    const int K = a.K;
+    const int stride = K + lds_pad(BF16C);
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+    const int NB = (a.d_out + 31) / 32;
+    constexpr int kStepK = BF16C ? 16 : 2;
+    const int KS = K / kStepK;
+
+    const int head = a.counters[CTR_READY_HEAD];
+    const int tail = a.counters[CTR_READY_TAIL];
+    const int ntiles = (tail - head + kTileRows - 1) / kTileRows;
+
+    for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        __syncthreads();  // previous tile's LDS readers are done
+        // ---- gather: wave w stages rows w*16 .. w*16+15 ----
+        for (int rr = 0; rr < kTileRows / 4; ++rr) {
+            const int r = w * (kTileRows / 4) + rr;
+            const int idx = head + tile * kTileRows + r;
+            const int32_t id = idx < tail ? a.ready[idx] : -1;
+            if (lane == 0) ids[r] = id;
+            elem_t *arow = A + r * stride;
+            if (id < 0) {
+                for (int c = lane; c < K; c += 64) arow[c] = to_elem<BF16C>(0.f);
+                continue;
+            }
+            const float *accrow = a.acc + static_cast<int64_t>(id) * a.d_in;
+            const int32_t deg = a.indeg[id];
+            if (a.model == 0) {  // SAGE: [own row || mean of neighbours]
+                if (a.in_bf16) {
+                    const uint16_t *srow = static_cast<const uint16_t *>(a.self_rows) + static_cast<int64_t>(id) * a.d_in;
+                    for (int c = lane; c < a.d_in; c += 64) arow[c] = to_elem<BF16C>(bf16_to_f32(srow[c]));
+                } else {
+                    const float *srow = static_cast<const float *>(a.self_rows) + static_cast<int64_t>(id) * a.d_in;
+                    for (int c = lane; c < a.d_in; c += 64) arow[c] = to_elem<BF16C>(srow[c]);
+                }
+                const float fdeg = static_cast<float>(deg > 0 ? deg : 1);
+                for (int c = lane; c < a.d_in; c += 64) arow[a.d_in + c] = to_elem<BF16C>(accrow[c] / fdeg);
+            } else {  // GCN: destination side of the symmetric normalisation
+                const float g = 1.0f / sqrtf(static_cast<float>(deg > 0 ? deg : 1));
+                for (int c = lane; c < a.d_in; c += 64) arow[c] = to_elem<BF16C>(accrow[c] * g);
+            }
+        }
+        __syncthreads();
+
+        // ---- MFMA: pairs (mb, nb) p = w + 4*i ----
+        f32x16_t c[PPW];
+#pragma unroll
+        for (int i = 0; i < PPW; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) c[i][r] = 0.f;
+
+        for (int kk = 0; kk < KS; ++kk) {
+#pragma unroll
+            for (int i = 0; i < PPW; ++i) {
+                const int p = w + 4 * i;
+                if (p >= 2 * NB) continue;
+                const int nb = p % NB, mb = p / NB;
+                if constexpr (BF16C) {
+                    const uint16_t *ap = A + (mb * 32 + (lane & 31)) * stride + kk * 16 + (lane >> 5) * 8;
+                    const bf16x8_t av = *reinterpret_cast<const bf16x8_t *>(ap);
+                    const bf16x8_t bv = *reinterpret_cast<const bf16x8_t *>(
+                        static_cast<const uint16_t *>(a.packed_w) + ((static_cast<int64_t>(nb) * KS + kk) * 64 + lane) * 8);
+                    c[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, c[i], 0, 0, 0);
+                } else {
+                    const float av = A[(mb * 32 + (lane & 31)) * stride + kk * 2 + (lane >> 5)];
+                    const float bv = static_cast<const float *>(a.packed_w)[(static_cast<int64_t>(nb) * KS + kk) * 64 + lane];
+                    c[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, c[i], 0, 0, 0);
+                }
+            }
+        }
+
+        // ---- epilogue: bias, activation, store row of the next layer ----
+#pragma unroll
+        for (int i = 0; i < PPW; ++i) {
+            const int p = w + 4 * i;
+            if (p >= 2 * NB) continue;
+            const int nb = p % NB, mb = p / NB;
+            const int j = nb * 32 + (lane & 31);
+            if (j >= a.d_out) continue;
+            const float bj = a.bias ? a.bias[j] : 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = mb * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int32_t id = ids[row];
+                if (id < 0) continue;
+                const float y = apply_activation(c[i][r] + bj, a.activation);
+                const int64_t o = static_cast<int64_t>(id) * a.d_out + j;
+                if (a.out_bf16) static_cast<uint16_t *>(a.out)[o] = f32_to_bf16_rne(y);
+                else static_cast<float *>(a.out)[o] = y;
+            }
+        }
+    }
+}
+
+__global__ void k_advance_head(int32_t *counters) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        counters[CTR_READY_HEAD] = counters[CTR_READY_TAIL];
+        counters[CTR_NUM_FLUSHES] += 1;
+    }
+}
+
+size_t update_lds_bytes(int K, bool bf16c) {
+    return kTileRows * sizeof(int32_t) +
+           static_cast<size_t>(kTileRows) * (K + lds_pad(bf16c)) * (bf16c ? 2 : 4);
+}
+
+template <bool BF16C, int PPW>
+hipError_t launch_update_t(const UpdateArgs &a, int grid, hipStream_t s) {
+    const size_t lds = update_lds_bytes(a.K, BF16C);
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_update<BF16C, PPW>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL((k_update<BF16C, PPW>), dim3(grid), dim3(kBlock), lds, s, a);
+    return hipGetLastError();
+}
+
+template <bool BF16C>
+hipError_t launch_update_c(const UpdateArgs &a, int grid, hipStream_t s) {
+    const int NB = (a.d_out + 31) / 32;
+    const int ppw = (2 * NB + 3) / 4;
+    switch (ppw) {
+        case 1: return launch_update_t<BF16C, 1>(a, grid, s);
+        case 2: return launch_update_t<BF16C, 2>(a, grid, s);
+        case 3: return launch_update_t<BF16C, 3>(a, grid, s);
+        case 4: return launch_update_t<BF16C, 4>(a, grid, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+size_t packed_weight_bytes(int K, int d_out, int compute_bf16) {
+    const int NB = (d_out + 31) / 32;
+    return static_cast<size_t>(NB) * 32 * K * (compute_bf16 ? 2 : 4);
+}
+
+hipError_t launch_pack_weights(const void *W, int w_bf16, int K, int d_out, int compute_bf16,
+                               void *packed, hipStream_t s) {
+    const int NB = (d_out + 31) / 32;
+    const int64_t total = static_cast<int64_t>(NB) * 32 * K;
+    const unsigned blocks = static_cast<unsigned>((total + kBlock - 1) / kBlock);
+    if (compute_bf16)
+        hipLaunchKernelGGL(k_pack_weights<true>, dim3(blocks), dim3(kBlock), 0, s, W, w_bf16, K, d_out,
+                           static_cast<uint16_t *>(packed));
+    else
+        hipLaunchKernelGGL(k_pack_weights<false>, dim3(blocks), dim3(kBlock), 0, s, W, w_bf16, K, d_out,
+                           static_cast<float *>(packed));
+    return hipGetLastError();
+}
+
+hipError_t launch_update(const UpdateArgs &a, hipStream_t s) {
+    if (update_lds_bytes(a.K, a.compute_bf16 != 0) > 160 * 1024) return hipErrorInvalidValue;
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess)
+        (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (cus <= 0) cus = 256;
+    const size_t lds = update_lds_bytes(a.K, a.compute_bf16 != 0);
+    int per_cu = static_cast<int>((160 * 1024) / lds);
+    if (per_cu < 1) per_cu = 1;
+    if (per_cu > 8) per_cu = 8;
+    int64_t grid = static_cast<int64_t>(cus) * per_cu;
+    const int64_t max_tiles = (a.n + kTileRows - 1) / kTileRows;
+    if (grid > max_tiles) grid = max_tiles;
+    if (grid < 1) grid = 1;
+    return a.compute_bf16 ? launch_update_c<true>(a, static_cast<int>(grid), s)
+                          : launch_update_c<false>(a, static_cast<int>(grid), s);
+}
+
+hipError_t launch_advance_head(int32_t *counters, hipStream_t s) {
+    hipLaunchKernelGGL(k_advance_head, dim3(1), dim3(64), 0, s, counters);
+    return hipGetLastError();
+}
+
+}  // namespace atlas
