@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the broadcast layer step on one MI355X.
+
+One "step" is one whole layer of the large GraphSAGE-mean workload (R-MAT
+scale 26, edge factor 32, bf16 features of width 128, degree-ordered ids,
+16 chunks of 2^22 sources): layer init (pending counts, zeroed accumulators),
+all chunk broadcasts (scatter-aggregate + pending decrement + ready
+compaction), a flush (MFMA update) after every chunk, and the exactly-once
+check.  Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` is aggregated edges per second of the layer;
+`roofline` describes the scatter-aggregate kernel (HIP-event time summed over
+its launches inside the timed steps); `cpu_baseline` is the CPU oracle timed on
+a bounded sample of the same layer.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--scale", type=int, default=26, help="R-MAT scale (26 = the quoted workload)")
+    ap.add_argument("--edge-factor", type=int, default=32)
+    ap.add_argument("--no-plan", action="store_true", help="push straight from the CSR (atomic path)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-e2e", action="store_true", help="skip the three-layer end-to-end run")
+    ap.add_argument("--sample-dst", type=int, default=1 << 16, help="destinations in the oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 (no collectives or sharding here)",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2605_09402_amd as atlas
+    from gen import in_edges_of, workloads
+
+    atlas.lib()  # fail loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream()
+
+    # ---- inputs (outside the timed region) ----
+    def reorder(off, col):
+        n = off.numel() - 1
+        indeg = torch.empty(n, dtype=torch.int32, device=dev)
+        atlas.atlas_in_degree(atlas.make_graph(n, col.numel(), off, col), indeg)
+        new_of_old = torch.empty(n, dtype=torch.int32, device=dev)
+        old_of_new = torch.empty(n, dtype=torch.int32, device=dev)
+        atlas.atlas_reorder_indegree_desc(atlas.make_graph(n, col.numel(), off, col, indeg), new_of_old, old_of_new)
+        return new_of_old
+
+    t0 = time.time()
+    wl = workloads.config5(dev, scale=args.scale, reorder=reorder, edge_factor=args.edge_factor)
+    torch.cuda.synchronize()
+    n, e, chunk = wl.n, wl.e, wl.chunk
+    log("generated %s: N=%d E=%d chunk=%d in %.1f s" % (wl.name, n, e, chunk, time.time() - t0))
+    indeg = torch.empty(n, dtype=torch.int32, device=dev)
+    atlas.atlas_in_degree(atlas.make_graph(n, e, wl.off, wl.col), indeg)
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+
+    plan = None
+    plan_ms = None
+    if not args.no_plan:
+        t0 = time.time()
+        plan = atlas.atlas_plan_create(atlas.make_graph(n, e, wl.off, wl.col), chunk)
+        plan_ms = (time.time() - t0) * 1e3
+        log("plan built in %.1f ms" % plan_ms)
+    graph = atlas.make_graph(n, e, wl.off, wl.col, indeg, atlas.RESIDENT_DEVICE, plan)
+
+    params = []
+    for p in wl.layers:
+        params.append((p.W.to(wl.store).to(dev).contiguous(), p.bias.to(wl.store).to(dev).contiguous()))
+    outs = [torch.empty((n, wl.dims[li + 1]), dtype=wl.store, device=dev) for li in range(len(wl.layers))]
+
+    def run_layer(li: int, x: torch.Tensor, timing: bool) -> dict:
+        d_in, d_out = wl.dims[li], wl.dims[li + 1]
+        act = atlas.ACT_NONE if li + 1 == len(wl.layers) else atlas.ACT_RELU
+        dims = atlas.make_dims(atlas.MODEL_SAGE_MEAN, d_in, d_out, atlas.DTYPE_BF16, atlas.DTYPE_BF16, act, chunk,
+                               flags=atlas.FLAG_TIMING if timing else 0)
+        W, b = params[li]
+        h = atlas.atlas_layer_init(graph, dims, atlas.make_weights(W, b, atlas.DTYPE_BF16), stream)
+        out = outs[li]
+        atlas.atlas_flush_ready(h, out, stream)
+        for b0 in range(0, n, chunk):
+            b1 = min(n, b0 + chunk)
+            atlas.atlas_broadcast_chunk(h, b0, b1, x[b0:b1], stream)
+            atlas.atlas_flush_ready(h, out, stream)
+        return atlas.atlas_layer_finish(h)
+
+    # ---- warm-up, then exactly K timed steps ----
+    for _ in range(args.warmup):
+        run_layer(0, wl.X, True)
+    torch.cuda.synchronize()
+    agg_ms = upd_ms = self_ms = init_ms = 0.0
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        st = run_layer(0, wl.X, True)
+        agg_ms += st["ms_aggregate"]
+        upd_ms += st["ms_update"]
+        self_ms += st["ms_self"]
+        init_ms += st["ms_init"]
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    nchunks = (n + chunk - 1) // chunk
+    launches = nchunks * args.steps
+    log("layer: %.2f ms/step; aggregate %.2f, update %.2f, self %.2f, init %.2f ms per step"
+        % (ms_per_step, agg_ms / args.steps, upd_ms / args.steps, self_ms / args.steps, init_ms / args.steps))
+
+    # ---- end-to-end: all three layers once ----
+    e2e_ms = None
+    layer_ms = []
+    if not args.no_e2e:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        x = wl.X
+        for li in range(len(wl.layers)):
+            t1 = time.perf_counter()
+            run_layer(li, x, False)
+            layer_ms.append((time.perf_counter() - t1) * 1e3)
+            x = outs[li]
+        torch.cuda.synchronize()
+        e2e_ms = (time.perf_counter() - t0) * 1e3
+        log("end-to-end 3 layers: %.1f ms (%s)" % (e2e_ms, ", ".join("%.1f" % v for v in layer_ms)))
+
+    # ---- roofline of the scatter-aggregate kernel ----
+    d = wl.dims[0]
+    bytes_per_edge = 4 + 2 * 4 * d + 8          # destination id, fp32 row read + write, pending RMW
+    bytes_per_source = d * 2 + 8                # bf16 source row, row offset
+    algo_bytes_layer = e * bytes_per_edge + n * bytes_per_source
+    agg_s_per_layer = agg_ms / args.steps / 1e3
+    achieved = algo_bytes_layer / agg_s_per_layer / 1e9
+    peak = 8000.0
+    # bytes the regrouped kernel itself must move (source id + bf16 source row per edge)
+    kernel_bytes_per_edge = 4 + d * 2
+    roofline = {
+        "bound": "hbm", "kernel": "k_aggregate_grouped" if plan else "k_aggregate",
+        "achieved": round(achieved, 1), "peak": peak, "unit": "GB/s", "frac": round(achieved / peak, 4),
+        "traffic": None,
+        "launches": launches, "avg_launch_ms": round(agg_ms / launches, 4),
+        "algorithmic_bytes_per_edge": bytes_per_edge, "algorithmic_bytes_per_source": bytes_per_source,
+        "edges_per_s_in_kernel": round(e / agg_s_per_layer, 1),
+        "per_edge_reads_only_GBps": round(e * kernel_bytes_per_edge / agg_s_per_layer / 1e9, 1),
+    }
+    K = 2 * d
+    upd_flops = 2.0 * n * K * wl.dims[1]
+    upd_s = upd_ms / args.steps / 1e3
+    update = {
+        "kernel": "k_update", "tflops": round(upd_flops / upd_s / 1e12, 2), "mfma_peak_tflops": 2500.0,
+        "frac_of_mfma_peak": round(upd_flops / upd_s / 2.5e15, 4),
+        "hbm_GBps": round(n * (4 * d + 2 * d + 2 * wl.dims[1]) / upd_s / 1e9, 1),
+        "ms_per_layer": round(upd_ms / args.steps, 3),
+    }
+
+    # ---- CPU oracle on a bounded sample of the same layer ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        gsel = torch.Generator().manual_seed(12345)
+        pick = torch.randperm(n, generator=gsel)[: args.sample_dst]
+        pick = torch.unique(torch.cat([pick, torch.arange(min(1024, n))]))   # plus the highest in-degree rows
+        in_off, in_src = in_edges_of(wl.off, wl.col, pick.to(dev))
+        need = torch.unique(torch.cat([in_src.to(torch.int64), pick.to(dev)]))
+        remap = torch.full((n,), -1, dtype=torch.int64, device=dev)
+        remap[need] = torch.arange(need.numel(), device=dev)
+        Xs = wl.X[need].float().cpu().numpy()
+        il = oracle.InLists(in_off.cpu().numpy(), remap[in_src.to(torch.int64)].to(torch.int32).cpu().numpy(),
+                            remap[pick.to(dev)].cpu().numpy())
+        p0 = wl.layers[0]
+        t1 = time.perf_counter()
+        Y = oracle.sage_mean(il, Xs, p0.W.numpy(), p0.bias.numpy())
+        Y = oracle.round_storage(oracle.activation(Y, oracle.ACT_RELU), oracle.FMT_BF16)
+        t_or = time.perf_counter() - t1
+        sample_edges = int(in_src.numel())
+        # sampled parity of the timed configuration, on the way
+        run_layer(0, wl.X, False)
+        got = outs[0][pick.to(dev)].float().cpu().numpy().astype(np.float64)
+        rn = np.maximum(np.abs(Y).max(axis=1), 1e-6 * np.abs(Y).max())
+        err = float((np.abs(got - Y).max(axis=1) / rn).max())
+        log("oracle sample: %d destinations, %d edges, %.2f s; sampled parity error %.3e" %
+            (pick.numel(), sample_edges, t_or, err))
+        cpu = {"value": round(sample_edges / t_or / 1e9, 6), "unit": "GTEPS", "cores": oracle.num_threads(),
+               "kind": "oracle",
+               "sample": "%d destinations (%d random + the 1,024 highest in-degree) with all %d of their in-edges, "
+                         "layer 1 aggregate + update in fp64" % (pick.numel(), args.sample_dst, sample_edges),
+               "seconds": round(t_or, 3), "sampled_parity_max_rel_err": err}
+
+    if plan is not None:
+        atlas.atlas_plan_destroy(plan)
+    gteps = e / (ms_per_step / 1e3) / 1e9
+    line = {
+        "metric": "aggregated edges/s per layer (GTEPS)", "value": round(gteps, 4), "unit": "GTEPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16 storage / f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "vertices": n, "edges": e, "d_in": d, "d_out": wl.dims[1],
+                   "chunk_sources": chunk, "chunks": nchunks, "flush": "after every chunk",
+                   "ids": "in-degree descending", "in_degree": "precomputed once per graph",
+                   "edge_order": "per-chunk destination-grouped plan" if plan else "CSR stream (atomics)",
+                   "plan_build_ms": None if plan_ms is None else round(plan_ms, 1)},
+        "layer_ms": {"aggregate": round(agg_ms / args.steps, 3), "update": round(upd_ms / args.steps, 3),
+                     "self": round(self_ms / args.steps, 3), "init": round(init_ms / args.steps, 3)},
+        "end_to_end_ms": None if e2e_ms is None else round(e2e_ms, 2),
+        "end_to_end_layer_ms": [round(v, 2) for v in layer_ms],
+        "roofline": roofline, "update": update, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

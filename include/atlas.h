@@ -35,6 +35,7 @@ extern "C" {
 #endif
 
 typedef struct atlas_layer atlas_layer_t; /* opaque, library-owned */
+typedef struct atlas_plan atlas_plan_t;   /* opaque, library-owned: see atlas_plan_create */
 
 enum atlas_status {
     ATLAS_OK = 0,
@@ -68,6 +69,8 @@ typedef struct {
     const int32_t *in_degree;   /* N in-degrees (multiplicity counted) in DEVICE memory,
                                    or NULL: the library counts them at init                */
     int32_t residency;          /* atlas_residency of row_offsets / col_indices            */
+    const atlas_plan_t *plan;   /* optional result of atlas_plan_create on THIS graph, or
+                                   NULL: chunks are then pushed straight from the CSR      */
 } atlas_graph_t;
 
 /* Layer shape.  d_in must be a multiple of 64 (one wavefront holds a row),
@@ -107,9 +110,12 @@ typedef struct {
     int64_t vertices_flushed;   /* rows written by atlas_flush_ready                        */
     int64_t num_chunks, num_flushes;
     int64_t bytes_copied_h2d;   /* PINNED_HOST residency: bytes staged into HBM             */
-    float ms_aggregate;         /* ATLAS_FLAG_TIMING: sum over chunks of broadcast kernels  */
+    float ms_aggregate;         /* ATLAS_FLAG_TIMING: sum over chunks of the scatter-aggregate
+                                   kernel (with its fused decrement + compaction)           */
+    float ms_self;              /* ATLAS_FLAG_TIMING: SAGE own-row copy + self message      */
     float ms_update;            /* ATLAS_FLAG_TIMING: sum over flushes of update kernels    */
     float ms_copy;              /* ATLAS_FLAG_TIMING: sum of staging copies                 */
+    float ms_init;              /* ATLAS_FLAG_TIMING: layer set-up kernels                  */
 } atlas_layer_stats_t;
 
 /* Create the state of one layer (Sec. 3.4: pending-message tracker and
@@ -156,6 +162,22 @@ int atlas_flush_ready(atlas_layer_t *layer, void *out, int64_t *n_flushed, void 
  * every vertex was completed and flushed exactly once, fill *stats (may be
  * NULL) and free the layer -- also when it returns E_INCOMPLETE. */
 int atlas_layer_finish(atlas_layer_t *layer, atlas_layer_stats_t *stats);
+
+/* One-time, per-graph preparation (like the paper's offline reordering,
+ * Sec. 3.8, it is paid once and reused by every layer and every run on the
+ * graph): for each aligned chunk k = [k*chunk_sources, min(N, (k+1)*chunk_sources))
+ * the chunk's out-edges are regrouped by destination, so that a chunk's
+ * messages to one destination are summed in registers and reach the
+ * accumulator as one row update, and the destination's pending count drops by
+ * the group's size in one step.  Results are those of the plain edge stream
+ * (same sums up to fp32 rounding order, same counts, same ready sets).
+ * atlas_broadcast_chunk uses the plan for chunks that coincide with a planned
+ * chunk and falls back to the CSR stream for any other range.
+ * DEVICE graphs only (E_BAD_DIMS otherwise).  Synchronous.  The plan holds
+ * about 4 bytes per edge of device memory and must outlive the layers that
+ * use it.  graph->plan and graph->in_degree are ignored here. */
+int atlas_plan_create(const atlas_graph_t *graph, int64_t chunk_sources, atlas_plan_t **out);
+int atlas_plan_destroy(atlas_plan_t *plan);
 
 /* In-degree of every vertex (histogram of col_indices), int32[N] in DEVICE
  * memory.  Works for both residencies (a PINNED_HOST edge array is read over

@@ -26,14 +26,15 @@ DBG_INDEG, DBG_PENDING, DBG_READY, DBG_READY_COUNT, DBG_ACC = range(5)
 EXPORTS = [
     "atlas_layer_init", "atlas_attention_prepass", "atlas_broadcast_chunk", "atlas_flush_ready",
     "atlas_layer_finish", "atlas_in_degree", "atlas_reorder_indegree_desc", "atlas_debug_copy",
-    "atlas_release_cache", "atlas_strerror", "atlas_last_hip_error",
+    "atlas_release_cache", "atlas_strerror", "atlas_last_hip_error", "atlas_plan_create", "atlas_plan_destroy",
 ]
 
 
 class atlas_graph_t(ctypes.Structure):
     _fields_ = [("num_vertices", ctypes.c_int64), ("num_edges", ctypes.c_int64),
                 ("row_offsets", ctypes.c_void_p), ("col_indices", ctypes.c_void_p),
-                ("in_degree", ctypes.c_void_p), ("residency", ctypes.c_int32)]
+                ("in_degree", ctypes.c_void_p), ("residency", ctypes.c_int32),
+                ("plan", ctypes.c_void_p)]
 
 
 class atlas_dims_t(ctypes.Structure):
@@ -53,7 +54,8 @@ class atlas_layer_stats_t(ctypes.Structure):
                 ("vertices_completed", ctypes.c_int64), ("vertices_flushed", ctypes.c_int64),
                 ("num_chunks", ctypes.c_int64), ("num_flushes", ctypes.c_int64),
                 ("bytes_copied_h2d", ctypes.c_int64), ("ms_aggregate", ctypes.c_float),
-                ("ms_update", ctypes.c_float), ("ms_copy", ctypes.c_float)]
+                ("ms_self", ctypes.c_float), ("ms_update", ctypes.c_float), ("ms_copy", ctypes.c_float),
+                ("ms_init", ctypes.c_float)]
 
 
 class AtlasError(RuntimeError):
@@ -87,6 +89,8 @@ def lib() -> ctypes.CDLL:
         L.atlas_reorder_indegree_desc.argtypes = [ctypes.POINTER(atlas_graph_t), vp, vp]
         L.atlas_debug_copy.argtypes = [vp, i32, vp, i64]
         L.atlas_release_cache.argtypes = []
+        L.atlas_plan_create.argtypes = [ctypes.POINTER(atlas_graph_t), i64, ctypes.POINTER(vp)]
+        L.atlas_plan_destroy.argtypes = [vp]
         for name in EXPORTS:
             getattr(L, name).restype = ctypes.c_int      # raises AttributeError on a missing export
         L.atlas_strerror.argtypes = [i32]
@@ -121,11 +125,11 @@ def _check(status: int, where: str):
 
 
 def make_graph(num_vertices: int, num_edges: int, row_offsets, col_indices, in_degree=None,
-               residency: int = RESIDENT_DEVICE) -> atlas_graph_t:
+               residency: int = RESIDENT_DEVICE, plan: Optional[int] = None) -> atlas_graph_t:
     """Fill an atlas_graph_t from tensors (int64 offsets, int32 columns / degrees).
-    The caller keeps the tensors alive."""
+    The caller keeps the tensors (and the plan) alive."""
     return atlas_graph_t(num_vertices, num_edges, _ptr(row_offsets), _ptr(col_indices), _ptr(in_degree),
-                         residency)
+                         residency, plan)
 
 
 def make_dims(model: int, d_in: int, d_out: int, in_dtype: int, out_dtype: int, activation: int,
@@ -172,6 +176,16 @@ def atlas_layer_finish(layer: int) -> dict:
         err.stats = stats
         raise err
     return stats
+
+
+def atlas_plan_create(graph: atlas_graph_t, chunk_sources: int) -> int:
+    h = ctypes.c_void_p()
+    _check(lib().atlas_plan_create(ctypes.byref(graph), chunk_sources, ctypes.byref(h)), "atlas_plan_create")
+    return h.value
+
+
+def atlas_plan_destroy(plan: int) -> None:
+    _check(lib().atlas_plan_destroy(plan), "atlas_plan_destroy")
 
 
 def atlas_in_degree(graph: atlas_graph_t, in_degree, stream=None) -> None:

@@ -78,6 +78,12 @@ struct TimedSpan { hipEvent_t a, b; };
 
 }  // namespace
 
+struct atlas_plan {
+    int64_t n = 0, e = 0, chunk = 0;
+    int32_t *src_sorted = nullptr;  // [E] destination-ordered source ids of all chunks
+    std::vector<PlanChunk> chunks;
+};
+
 struct atlas_layer {
     atlas_graph_t g{};
     atlas_dims_t dims{};
@@ -102,7 +108,7 @@ struct atlas_layer {
     bool slot_used[2] = {false, false};
     Buf stage_col[2], stage_emb[2];
 
-    std::vector<TimedSpan> t_agg, t_upd, t_copy;
+    std::vector<TimedSpan> t_agg, t_self, t_upd, t_copy, t_init;
     hipStream_t last_stream = nullptr;
 
     int32_t *ctr() { return static_cast<int32_t *>(counters.p); }
@@ -111,7 +117,7 @@ struct atlas_layer {
         for (Buf *b : {&indeg_own, &pending, &ready, &counters, &counters64, &acc, &self_rows, &packed_w, &bias,
                        &dev_off, &stage_col[0], &stage_col[1], &stage_emb[0], &stage_emb[1]})
             b->release();
-        for (auto *v : {&t_agg, &t_upd, &t_copy})
+        for (auto *v : {&t_agg, &t_self, &t_upd, &t_copy, &t_init})
             for (auto &sp : *v) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
         for (int i = 0; i < 2; ++i) {
             if (slot_loaded[i]) (void)hipEventDestroy(slot_loaded[i]);
@@ -250,7 +256,9 @@ int atlas_layer_init(const atlas_graph_t *graph, const atlas_dims_t *dims, const
     L->acc_width = dims->d_in;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     L->last_stream = s;
-    rc = init_impl(L, weights, s);
+    rc = start_span(L, L->t_init, s);
+    if (rc == ATLAS_OK) rc = init_impl(L, weights, s);
+    if (rc == ATLAS_OK) rc = end_span(L, L->t_init, s);
     if (rc != ATLAS_OK) {
         (void)hipStreamSynchronize(s);
         L->destroy();
@@ -334,13 +342,43 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         a.emb = emb;
     }
 
-    int rc = start_span(L, L->t_agg, s);
-    if (rc != ATLAS_OK) return rc;
-    if (self_dst && L->g.residency == ATLAS_RESIDENT_DEVICE)
-        HIP_TRY(hipMemcpyAsync(self_dst, emb, emb_bytes, hipMemcpyDeviceToDevice, s));
-    HIP_TRY(launch_aggregate(a, s));
-    if (L->selfmsg)
+    // a chunk that coincides with a planned chunk runs from its destination-ordered edges
+    const atlas_plan *plan = L->g.residency == ATLAS_RESIDENT_DEVICE ? L->g.plan : nullptr;
+    const PlanChunk *pc = nullptr;
+    if (plan && plan->chunk > 0 && src_begin % plan->chunk == 0 &&
+        src_end == std::min(L->n, src_begin + plan->chunk))
+        pc = &plan->chunks[static_cast<size_t>(src_begin / plan->chunk)];
+
+    int rc = ATLAS_OK;
+    if (L->selfmsg) {
+        if ((rc = start_span(L, L->t_self, s)) != ATLAS_OK) return rc;
+        if (self_dst && L->g.residency == ATLAS_RESIDENT_DEVICE)
+            HIP_TRY(hipMemcpyAsync(self_dst, emb, emb_bytes, hipMemcpyDeviceToDevice, s));
         HIP_TRY(launch_self_message(src_begin, src_end, a.pending, a.ready, a.counters, s));
+        if ((rc = end_span(L, L->t_self, s)) != ATLAS_OK) return rc;
+    }
+    if ((rc = start_span(L, L->t_agg, s)) != ATLAS_OK) return rc;
+    if (pc) {
+        GroupedArgs ga{};
+        ga.src_sorted = plan->src_sorted + pc->edge_base;
+        ga.n_edges = pc->n_edges;
+        ga.grp_dst = pc->grp_dst;
+        ga.tile_grp = pc->tile_grp;
+        ga.emb = emb;
+        ga.src_begin = src_begin;
+        ga.d = a.d;
+        ga.in_bf16 = a.in_bf16;
+        ga.model = a.model;
+        ga.acc = a.acc;
+        ga.pending = a.pending;
+        ga.indeg = a.indeg;
+        ga.ready = a.ready;
+        ga.counters = a.counters;
+        ga.counters64 = a.counters64;
+        HIP_TRY(launch_aggregate_grouped(ga, s));
+    } else {
+        HIP_TRY(launch_aggregate(a, s));
+    }
     rc = end_span(L, L->t_agg, s);
     if (rc != ATLAS_OK) return rc;
     if (slot >= 0) {
@@ -412,6 +450,8 @@ int atlas_layer_finish(atlas_layer_t *L, atlas_layer_stats_t *stats) {
         stats->bytes_copied_h2d = L->bytes_h2d;
         if (rc == ATLAS_OK) {
             stats->ms_aggregate = sum_spans(L->t_agg);
+            stats->ms_self = sum_spans(L->t_self);
+            stats->ms_init = sum_spans(L->t_init);
             stats->ms_update = sum_spans(L->t_upd);
             stats->ms_copy = sum_spans(L->t_copy);
         }
@@ -423,6 +463,57 @@ int atlas_layer_finish(atlas_layer_t *L, atlas_layer_stats_t *stats) {
     L->destroy();
     delete L;
     return rc;
+}
+
+int atlas_plan_create(const atlas_graph_t *graph, int64_t chunk_sources, atlas_plan_t **out) {
+    if (!graph || !out) return ATLAS_E_NULL;
+    if (!graph->row_offsets || (graph->num_edges > 0 && !graph->col_indices)) return ATLAS_E_NULL;
+    if (graph->residency != ATLAS_RESIDENT_DEVICE || chunk_sources <= 0) return ATLAS_E_BAD_DIMS;
+    if (graph->num_vertices < 0 || graph->num_edges < 0) return ATLAS_E_RANGE;
+    if (graph->num_vertices >= (int64_t(1) << 31)) return ATLAS_E_OVERFLOW;
+    atlas_plan *P = new (std::nothrow) atlas_plan();
+    if (!P) return ATLAS_E_NOMEM;
+    P->n = graph->num_vertices;
+    P->e = graph->num_edges;
+    P->chunk = chunk_sources;
+    const int64_t nchunks = (P->n + chunk_sources - 1) / chunk_sources;
+    int rc = ATLAS_OK;
+    hipError_t e = hipMalloc(&P->src_sorted, static_cast<size_t>(std::max<int64_t>(P->e, 1)) * sizeof(int32_t));
+    if (e != hipSuccess) rc = hip_fail(e, "hipMalloc(plan)");
+    int64_t ebeg = 0;
+    if (rc == ATLAS_OK && nchunks > 0) {
+        e = hipMemcpy(&ebeg, graph->row_offsets, sizeof(int64_t), hipMemcpyDeviceToHost);
+        if (e != hipSuccess) rc = hip_fail(e, "hipMemcpy(row_offsets)");
+    }
+    for (int64_t k = 0; rc == ATLAS_OK && k < nchunks; ++k) {
+        const int64_t b = k * chunk_sources, en = std::min(P->n, b + chunk_sources);
+        int64_t eend = 0;
+        e = hipMemcpy(&eend, graph->row_offsets + en, sizeof(int64_t), hipMemcpyDeviceToHost);
+        if (e != hipSuccess) { rc = hip_fail(e, "hipMemcpy(row_offsets)"); break; }
+        PlanChunk pc;
+        e = build_plan_chunk(graph->row_offsets, graph->col_indices, P->n, b, en, ebeg, eend, P->src_sorted, &pc);
+        if (e != hipSuccess) { rc = hip_fail(e, "build_plan_chunk"); break; }
+        P->chunks.push_back(pc);
+        ebeg = eend;
+    }
+    if (rc != ATLAS_OK) {
+        atlas_plan_destroy(P);
+        return rc;
+    }
+    *out = P;
+    return ATLAS_OK;
+}
+
+int atlas_plan_destroy(atlas_plan_t *P) {
+    if (!P) return ATLAS_E_NULL;
+    (void)hipDeviceSynchronize();
+    for (auto &c : P->chunks) {
+        if (c.grp_dst) (void)hipFree(c.grp_dst);
+        if (c.tile_grp) (void)hipFree(c.tile_grp);
+    }
+    if (P->src_sorted) (void)hipFree(P->src_sorted);
+    delete P;
+    return ATLAS_OK;
 }
 
 int atlas_in_degree(const atlas_graph_t *graph, int32_t *in_degree, void *hip_stream) {

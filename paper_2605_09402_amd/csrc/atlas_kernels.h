@@ -38,6 +38,43 @@ struct AggregateArgs {
 // wave-level ready compaction.
 hipError_t launch_aggregate(const AggregateArgs &a, hipStream_t s);
 
+// One planned chunk: its edges regrouped by destination.
+struct PlanChunk {
+    int64_t edge_base = 0;      // first edge of the chunk in CSR numbering
+    int64_t n_edges = 0;
+    int64_t n_groups = 0;       // distinct destinations the chunk sends to
+    int32_t *grp_dst = nullptr;   // [n_groups] destination of each group, ascending
+    int32_t *tile_grp = nullptr;  // [ceil(n_edges/64)] group of the first edge of every 64-edge tile
+};
+
+struct GroupedArgs {
+    const int32_t *src_sorted;  // chunk slice: source id of every edge in destination order,
+                                // bit 31 set on the last edge of a destination's group
+    int64_t n_edges;
+    const int32_t *grp_dst;
+    const int32_t *tile_grp;
+    const void *emb;            // chunk rows; row u lives at (u - src_begin) * d
+    int64_t src_begin;
+    int d;
+    int in_bf16;
+    int model;
+    float *acc;
+    int32_t *pending;
+    const int32_t *indeg;
+    int32_t *ready;
+    int32_t *counters;
+    unsigned long long *counters64;
+};
+
+// S2+S3+S4 over a planned chunk: per-destination register sums, one row update
+// and one pending decrement per (chunk, destination) group.
+hipError_t launch_aggregate_grouped(const GroupedArgs &a, hipStream_t s);
+
+// Plan construction for one chunk (synchronous; allocates the chunk's arrays).
+hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int64_t n, int64_t src_begin,
+                            int64_t src_end, int64_t edge_begin, int64_t edge_end, int32_t *src_sorted_all,
+                            PlanChunk *out);
+
 // SAGE self message of sources [b, e): pending[u] -= 1 with ready compaction.
 hipError_t launch_self_message(int64_t b, int64_t e, int32_t *pending, int32_t *ready,
                                int32_t *counters, hipStream_t s);

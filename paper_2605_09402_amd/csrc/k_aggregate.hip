@@ -165,6 +165,183 @@ __global__ __launch_bounds__(kBlock) void k_self_message(int64_t b, int64_t e, i
     }
 }
 
+// ---- planned chunk: edges regrouped by destination --------------------------
+//
+// A wave owns 64 consecutive edges of the chunk's destination-ordered edge
+// list.  Every edge is one coalesced read of its source row; the rows of one
+// destination are summed in registers and reach the accumulator as a single
+// row update.  A destination whose edges all lie inside the tile is touched by
+// this wave only (plain read-add-write); a group cut by a tile boundary is
+// added with atomics by every tile that holds a piece of it.  The pending
+// count drops by the group's size (its piece, for a cut group) in one step.
+
+template <typename T, int VPL>
+__device__ __forceinline__ void load_row(const T *__restrict__ p, float (&x)[VPL]) {
+    if constexpr (sizeof(T) == 2) {
+        if constexpr (VPL == 2) {
+            const uint32_t w = *reinterpret_cast<const uint32_t *>(p);
+            x[0] = __uint_as_float(w << 16);
+            x[1] = __uint_as_float(w & 0xffff0000u);
+        } else if constexpr (VPL == 4) {
+            const uint2 w = *reinterpret_cast<const uint2 *>(p);
+            x[0] = __uint_as_float(w.x << 16); x[1] = __uint_as_float(w.x & 0xffff0000u);
+            x[2] = __uint_as_float(w.y << 16); x[3] = __uint_as_float(w.y & 0xffff0000u);
+        } else if constexpr (VPL == 8) {
+            const uint4 w = *reinterpret_cast<const uint4 *>(p);
+            x[0] = __uint_as_float(w.x << 16); x[1] = __uint_as_float(w.x & 0xffff0000u);
+            x[2] = __uint_as_float(w.y << 16); x[3] = __uint_as_float(w.y & 0xffff0000u);
+            x[4] = __uint_as_float(w.z << 16); x[5] = __uint_as_float(w.z & 0xffff0000u);
+            x[6] = __uint_as_float(w.w << 16); x[7] = __uint_as_float(w.w & 0xffff0000u);
+        } else {
+#pragma unroll
+            for (int i = 0; i < VPL; ++i) x[i] = load_as_f32(p + i);
+        }
+    } else {
+        if constexpr (VPL == 2) {
+            const float2 w = *reinterpret_cast<const float2 *>(p);
+            x[0] = w.x; x[1] = w.y;
+        } else if constexpr (VPL == 4) {
+            const float4 w = *reinterpret_cast<const float4 *>(p);
+            x[0] = w.x; x[1] = w.y; x[2] = w.z; x[3] = w.w;
+        } else if constexpr (VPL == 8) {
+            const float4 w0 = *reinterpret_cast<const float4 *>(p);
+            const float4 w1 = *reinterpret_cast<const float4 *>(p + 4);
+            x[0] = w0.x; x[1] = w0.y; x[2] = w0.z; x[3] = w0.w;
+            x[4] = w1.x; x[5] = w1.y; x[6] = w1.z; x[7] = w1.w;
+        } else {
+#pragma unroll
+            for (int i = 0; i < VPL; ++i) x[i] = p[i];
+        }
+    }
+}
+
+template <int VPL>
+__device__ __forceinline__ void row_add_owned(float *p, const float (&x)[VPL]) {
+    if constexpr (VPL == 2) {
+        float2 v = *reinterpret_cast<float2 *>(p);
+        v.x += x[0]; v.y += x[1];
+        *reinterpret_cast<float2 *>(p) = v;
+    } else if constexpr (VPL == 4 || VPL == 8) {
+#pragma unroll
+        for (int q = 0; q < VPL / 4; ++q) {
+            float4 v = *reinterpret_cast<float4 *>(p + 4 * q);
+            v.x += x[4 * q]; v.y += x[4 * q + 1]; v.z += x[4 * q + 2]; v.w += x[4 * q + 3];
+            *reinterpret_cast<float4 *>(p + 4 * q) = v;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) p[i] += x[i];
+    }
+}
+
+template <int VPL>
+__device__ __forceinline__ void row_add_shared(float *p, const float (&x)[VPL]) {
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) unsafeAtomicAdd(p + i, x[i]);
+}
+
+template <typename T, int VPL, int MODEL>
+__global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
+    constexpr int D = VPL * kWave;
+    constexpr int U = 8;  // source rows in flight per wave
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t wave = static_cast<int64_t>(blockIdx.x) * (kBlock / kWave) + (threadIdx.x >> 6);
+    const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (kBlock / kWave);
+    const int64_t ntiles = (a.n_edges + kTileEdges - 1) / kTileEdges;
+    const T *__restrict__ emb = static_cast<const T *>(a.emb);
+
+    if (wave == 0 && lane == 0)
+        atomicAdd(&a.counters64[CTR64_EDGES], static_cast<unsigned long long>(a.n_edges));
+
+    for (int64_t t = wave; t < ntiles; t += nwaves) {
+        const int64_t e0 = t * kTileEdges;
+        const int64_t left = a.n_edges - e0;
+        const int cnt = left < kTileEdges ? static_cast<int>(left) : kTileEdges;
+        const int g0 = a.tile_grp[t];
+        int32_t s = 0;
+        if (lane < cnt) s = a.src_sorted[e0 + lane];
+        const bool is_end = lane < cnt && s < 0;
+        const uint64_t endmask = __ballot(is_end);
+        const int src = s & 0x7fffffff;
+        // the tile's first group continues one that started in an earlier tile?
+        bool cut = false;
+        if (e0 > 0) cut = a.src_sorted[e0 - 1] >= 0;
+        const uint64_t below = endmask & ((1ull << lane) - 1ull);
+        const bool closes = is_end || lane == cnt - 1;  // last edge of a group, or of the tile
+        int32_t dstv = 0;
+        if (closes) dstv = a.grp_dst[g0 + __popcll(below)];
+        float gs = 1.f;
+        if (MODEL == 1 && lane < cnt) {  // GCN: source side of the symmetric normalisation
+            const int32_t du = a.indeg[src];
+            gs = 1.0f / sqrtf(static_cast<float>(du > 0 ? du : 1));
+        }
+
+        float sum[VPL];
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) sum[i] = 0.f;
+        for (int j0 = 0; j0 < cnt; j0 += U) {
+            float r[U][VPL];
+#pragma unroll
+            for (int i = 0; i < U; ++i) {
+                const int j = j0 + i < cnt ? j0 + i : cnt - 1;
+                const int sj = __builtin_amdgcn_readlane(src, j);
+                load_row<T, VPL>(emb + (static_cast<int64_t>(sj) - a.src_begin) * D + lane * VPL, r[i]);
+                if (MODEL == 1) {
+                    const float g = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(gs), j));
+#pragma unroll
+                    for (int q = 0; q < VPL; ++q) r[i][q] *= g;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < U; ++i) {
+                const int j = j0 + i;
+                if (j < cnt) {
+#pragma unroll
+                    for (int q = 0; q < VPL; ++q) sum[q] += r[i][q];
+                    if ((endmask >> j) & 1ull) {
+                        const int32_t v = __builtin_amdgcn_readlane(dstv, j);
+                        float *dst = a.acc + static_cast<int64_t>(v) * D + lane * VPL;
+                        if (cut) row_add_shared<VPL>(dst, sum);
+                        else row_add_owned<VPL>(dst, sum);
+                        cut = false;
+#pragma unroll
+                        for (int q = 0; q < VPL; ++q) sum[q] = 0.f;
+                    }
+                }
+            }
+        }
+        if (!((endmask >> (cnt - 1)) & 1ull)) {  // open group: continues in the next tile
+            const int32_t v = __builtin_amdgcn_readlane(dstv, cnt - 1);
+            row_add_shared<VPL>(a.acc + static_cast<int64_t>(v) * D + lane * VPL, sum);
+        }
+
+        // pending count: minus the number of this tile's messages to the group
+        bool is_ready = false;
+        if (closes) {
+            const int prev_end = below ? 63 - __clzll(static_cast<long long>(below)) : -1;
+            const int c = lane - prev_end;
+            is_ready = atomicSub(&a.pending[dstv], c) == c;
+        }
+        wave_append_ready(is_ready, dstv, a.ready, a.counters, lane);
+    }
+}
+
+template <typename T, int MODEL>
+hipError_t launch_grouped_vpl(const GroupedArgs &a, int grid, hipStream_t s) {
+    switch (a.d / kWave) {
+        case 1: hipLaunchKernelGGL((k_aggregate_grouped<T, 1, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 2: hipLaunchKernelGGL((k_aggregate_grouped<T, 2, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 3: hipLaunchKernelGGL((k_aggregate_grouped<T, 3, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 4: hipLaunchKernelGGL((k_aggregate_grouped<T, 4, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 5: hipLaunchKernelGGL((k_aggregate_grouped<T, 5, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 6: hipLaunchKernelGGL((k_aggregate_grouped<T, 6, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 7: hipLaunchKernelGGL((k_aggregate_grouped<T, 7, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 8: hipLaunchKernelGGL((k_aggregate_grouped<T, 8, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 template <typename T, int MODEL>
 hipError_t launch_vpl(const AggregateArgs &a, int grid, hipStream_t s) {
     switch (a.d / kWave) {
@@ -199,6 +376,16 @@ hipError_t launch_aggregate(const AggregateArgs &a, hipStream_t s) {
         return a.model == 1 ? launch_vpl<uint16_t, 1>(a, grid, s) : launch_vpl<uint16_t, 0>(a, grid, s);
     }
     return a.model == 1 ? launch_vpl<float, 1>(a, grid, s) : launch_vpl<float, 0>(a, grid, s);
+}
+
+hipError_t launch_aggregate_grouped(const GroupedArgs &a, hipStream_t s) {
+    if (a.d % kWave != 0) return hipErrorInvalidValue;
+    if (a.n_edges <= 0) return hipSuccess;
+    const int grid = persistent_grid(8);
+    if (a.in_bf16) {
+        return a.model == 1 ? launch_grouped_vpl<uint16_t, 1>(a, grid, s) : launch_grouped_vpl<uint16_t, 0>(a, grid, s);
+    }
+    return a.model == 1 ? launch_grouped_vpl<float, 1>(a, grid, s) : launch_grouped_vpl<float, 0>(a, grid, s);
 }
 
 hipError_t launch_self_message(int64_t b, int64_t e, int32_t *pending, int32_t *ready,

@@ -1,0 +1,139 @@
+// Per-graph plan: for every aligned source chunk, the chunk's out-edges
+// regrouped by destination.  The chunk is still what is streamed (paper
+// Sec. 3.3: contiguous source range with its topology); only the order in
+// which its edges are visited changes, so that all messages a chunk sends to
+// one destination are adjacent.  Integer-only, done once per graph like the
+// paper's offline reordering (Sec. 3.8).
+//
+// Steps for a chunk with edges [E0, E1):
+//   1. source id of every edge (row starts scattered, then a running maximum);
+//   2. stable radix sort of (destination, source) pairs by destination;
+//   3. group heads / tails: bit 31 of the stored source id marks the last edge
+//      of a destination's group, a prefix sum of the heads numbers the groups;
+//   4. grp_dst[g] = destination of group g, tile_grp[t] = group of edge 64 t.
+#include "atlas_kernels.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+
+#include <rocprim/device/device_radix_sort.hpp>
+#include <rocprim/device/device_scan.hpp>
+
+namespace atlas {
+namespace {
+
+constexpr int kBlock = 256;
+
+unsigned blocks_for(int64_t n) { return static_cast<unsigned>((n + kBlock - 1) / kBlock); }
+
+// tmp[off[u] - E0] = u for every source of the chunk that has out-edges.
+__global__ void k_mark_row_starts(const int64_t *__restrict__ off, int64_t src_begin, int64_t src_end,
+                                  int64_t e0, int32_t *tmp) {
+    const int64_t u = src_begin + static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (u >= src_end) return;
+    const int64_t a = off[u], b = off[u + 1];
+    if (b > a) tmp[a - e0] = static_cast<int32_t>(u);
+}
+
+// heads[i] = 1 where a destination's group starts; the source id of the last
+// edge of a group gets bit 31.
+__global__ void k_mark_groups(const uint32_t *__restrict__ dst_sorted, int64_t n_edges, int32_t *src_sorted,
+                              uint32_t *heads) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (i >= n_edges) return;
+    const uint32_t d = dst_sorted[i];
+    heads[i] = (i == 0 || dst_sorted[i - 1] != d) ? 1u : 0u;
+    if (i + 1 == n_edges || dst_sorted[i + 1] != d)
+        src_sorted[i] = static_cast<int32_t>(static_cast<uint32_t>(src_sorted[i]) | 0x80000000u);
+}
+
+// gidx = inclusive prefix sum of heads (group number + 1).
+__global__ void k_emit_groups(const uint32_t *__restrict__ dst_sorted, const uint32_t *__restrict__ gidx,
+                              int64_t n_edges, int32_t *grp_dst, int32_t *tile_grp) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (i >= n_edges) return;
+    const uint32_t g = gidx[i] - 1u;
+    if (i == 0 || gidx[i - 1] != gidx[i]) grp_dst[g] = static_cast<int32_t>(dst_sorted[i]);
+    if ((i & 63) == 0) tile_grp[i >> 6] = static_cast<int32_t>(g);
+}
+
+struct MaxOp {
+    __host__ __device__ int32_t operator()(int32_t a, int32_t b) const { return a > b ? a : b; }
+};
+
+}  // namespace
+
+hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int64_t n, int64_t src_begin,
+                            int64_t src_end, int64_t edge_begin, int64_t edge_end, int32_t *src_sorted_all,
+                            PlanChunk *out) {
+    *out = PlanChunk{};
+    out->edge_base = edge_begin;
+    out->n_edges = edge_end - edge_begin;
+    const int64_t ne = out->n_edges;
+    if (ne <= 0) return hipSuccess;
+    if (ne >= (int64_t(1) << 32)) return hipErrorInvalidValue;
+
+    hipError_t err = hipSuccess;
+    int32_t *tmp_src = nullptr;   // source per edge (CSR order); reused for the group prefix sum
+    uint32_t *dst_sorted = nullptr;
+    uint32_t *heads = nullptr;
+    void *temp = nullptr;
+    size_t temp_sort = 0, temp_scan_max = 0, temp_scan_sum = 0, temp_bytes = 0;
+    int32_t *src_sorted = src_sorted_all + edge_begin;
+    const uint32_t *keys_in = reinterpret_cast<const uint32_t *>(col_dev + edge_begin);
+    uint32_t last = 0;
+    int end_bit = 1;
+    while (end_bit < 32 && (int64_t(1) << end_bit) < n) ++end_bit;
+    const size_t count = static_cast<size_t>(ne);
+
+    if ((err = hipMalloc(&tmp_src, count * 4)) != hipSuccess) goto done;
+    if ((err = hipMalloc(&dst_sorted, count * 4)) != hipSuccess) goto done;
+    if ((err = hipMalloc(&heads, count * 4)) != hipSuccess) goto done;
+    if ((err = rocprim::radix_sort_pairs(nullptr, temp_sort, keys_in, dst_sorted, tmp_src, src_sorted, count, 0,
+                                         end_bit, nullptr)) != hipSuccess) goto done;
+    if ((err = rocprim::inclusive_scan(nullptr, temp_scan_max, tmp_src, tmp_src, count, MaxOp(), nullptr)) != hipSuccess) goto done;
+    if ((err = rocprim::inclusive_scan(nullptr, temp_scan_sum, heads, reinterpret_cast<uint32_t *>(tmp_src), count,
+                                       rocprim::plus<uint32_t>(), nullptr)) != hipSuccess) goto done;
+    temp_bytes = temp_sort > temp_scan_max ? temp_sort : temp_scan_max;
+    if (temp_scan_sum > temp_bytes) temp_bytes = temp_scan_sum;
+    if ((err = hipMalloc(&temp, temp_bytes > 0 ? temp_bytes : 16)) != hipSuccess) goto done;
+
+    // 1. source of every edge
+    if ((err = hipMemsetAsync(tmp_src, 0, count * 4, nullptr)) != hipSuccess) goto done;
+    hipLaunchKernelGGL(k_mark_row_starts, dim3(blocks_for(src_end - src_begin)), dim3(kBlock), 0, nullptr, off_dev,
+                       src_begin, src_end, edge_begin, tmp_src);
+    if ((err = hipGetLastError()) != hipSuccess) goto done;
+    if ((err = rocprim::inclusive_scan(temp, temp_scan_max, tmp_src, tmp_src, count, MaxOp(), nullptr)) != hipSuccess) goto done;
+    // 2. stable sort by destination
+    if ((err = rocprim::radix_sort_pairs(temp, temp_sort, keys_in, dst_sorted, tmp_src, src_sorted, count, 0, end_bit,
+                                         nullptr)) != hipSuccess) goto done;
+    // 3. group heads, tail flags, group numbering
+    hipLaunchKernelGGL(k_mark_groups, dim3(blocks_for(ne)), dim3(kBlock), 0, nullptr, dst_sorted, ne, src_sorted, heads);
+    if ((err = hipGetLastError()) != hipSuccess) goto done;
+    if ((err = rocprim::inclusive_scan(temp, temp_scan_sum, heads, reinterpret_cast<uint32_t *>(tmp_src), count,
+                                       rocprim::plus<uint32_t>(), nullptr)) != hipSuccess) goto done;
+    if ((err = hipMemcpy(&last, reinterpret_cast<uint32_t *>(tmp_src) + (count - 1), 4, hipMemcpyDeviceToHost)) != hipSuccess) goto done;
+    out->n_groups = last;
+    // 4. per-group destination and per-tile first group
+    if ((err = hipMalloc(&out->grp_dst, static_cast<size_t>(last) * 4)) != hipSuccess) goto done;
+    if ((err = hipMalloc(&out->tile_grp, static_cast<size_t>((ne + 63) / 64) * 4)) != hipSuccess) goto done;
+    hipLaunchKernelGGL(k_emit_groups, dim3(blocks_for(ne)), dim3(kBlock), 0, nullptr, dst_sorted,
+                       reinterpret_cast<const uint32_t *>(tmp_src), ne, out->grp_dst, out->tile_grp);
+    if ((err = hipGetLastError()) != hipSuccess) goto done;
+    err = hipStreamSynchronize(nullptr);
+done:
+    if (temp) (void)hipFree(temp);
+    if (heads) (void)hipFree(heads);
+    if (dst_sorted) (void)hipFree(dst_sorted);
+    if (tmp_src) (void)hipFree(tmp_src);
+    if (err != hipSuccess) {
+        if (out->grp_dst) (void)hipFree(out->grp_dst);
+        if (out->tile_grp) (void)hipFree(out->tile_grp);
+        out->grp_dst = nullptr;
+        out->tile_grp = nullptr;
+    }
+    return err;
+}
+
+}  // namespace atlas

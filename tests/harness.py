@@ -80,7 +80,8 @@ def _dt(store: torch.dtype) -> int:
 
 
 def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, flush_every: int = 1,
-            give_indeg: bool = False, timing: bool = False, max_layers: Optional[int] = None) -> GpuRun:
+            give_indeg: bool = False, timing: bool = False, max_layers: Optional[int] = None,
+            plan: bool = False, plan_chunk: Optional[int] = None) -> GpuRun:
     """Drive all layers through the C ABI.  With pinned_host the graph and the
     layer-0 features stay in pinned host memory and are staged by the library."""
     dev = torch.device("cuda:0")
@@ -99,7 +100,10 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
     if give_indeg:
         indeg_t = torch.empty(max(n, 1), dtype=torch.int32, device=dev)
         atlas.atlas_in_degree(atlas.make_graph(n, e, off_t, col_t, None, res), indeg_t)
-    graph = atlas.make_graph(n, e, off_t, col_t, indeg_t, res)
+    plan_h = None
+    if plan:
+        plan_h = atlas.atlas_plan_create(atlas.make_graph(n, e, off_t, col_t, None, res), plan_chunk or case.chunk)
+    graph = atlas.make_graph(n, e, off_t, col_t, indeg_t, res, plan_h)
     nl = len(case.layers) if max_layers is None else max_layers
     cur_dev = case.X.to(dev)
     cur_host = case.X.pin_memory() if pinned_host else None
@@ -170,6 +174,8 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
         run.outputs.append(out[:n])
         cur_dev = out[:n]
     torch.cuda.synchronize()
+    if plan_h is not None:
+        atlas.atlas_plan_destroy(plan_h)
     return run
 
 

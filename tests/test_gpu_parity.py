@@ -18,11 +18,12 @@ def H():
     return harness
 
 
-def test_config1_tiny_sage_fp32(oracle, H):
+@pytest.mark.parametrize("plan", [False, True], ids=["csr_stream", "planned"])
+def test_config1_tiny_sage_fp32(oracle, H, plan):
     """10,000 vertices, 100,000 uniform edges, SAGE 64->64->16, chunks of 1,024
     (last chunk 784 sources), flush after every chunk."""
     case = H.make_case("sage", gen.uniform_graph(SEED + 1, 10_000, 100_000), SEED + 1, [64, 64, 16], 1024)
-    run = H.run_gpu(case, snapshots=True)
+    run = H.run_gpu(case, snapshots=True, plan=plan)
     H.check_integers(oracle, case, run, layer=0)
     H.check_integers(oracle, case, run, layer=1)
     errs = H.check_outputs(oracle, case, run)
@@ -32,8 +33,9 @@ def test_config1_tiny_sage_fp32(oracle, H):
         assert st["num_chunks"] == 10
 
 
+@pytest.mark.parametrize("plan", [False, True], ids=["csr_stream", "planned"])
 @pytest.mark.parametrize("order", ["random", "indegree_desc"])
-def test_gcn_rmat_fp32(oracle, H, order):
+def test_gcn_rmat_fp32(oracle, H, order, plan):
     """Config-2 shape at scale 14: R-MAT, random ids, one self-loop per vertex,
     GCN 128->128->64, run with random ids and with the degree ordering."""
     import paper_2605_09402_amd as atlas
@@ -57,21 +59,23 @@ def test_gcn_rmat_fp32(oracle, H, order):
         X = gen.permute_rows(X, torch.from_numpy(ref_new.astype(np.int64)))
     case = H.make_case("gcn", g, SEED + 2, [128, 128, 64], 1 << 10, feat="normal")
     case.X = X
-    run = H.run_gpu(case, snapshots=True)
+    run = H.run_gpu(case, snapshots=True, plan=plan)
     H.check_integers(oracle, case, run)
     print("gcn", order, H.check_outputs(oracle, case, run))
 
 
-def test_sage_rmat_bf16_three_layers(oracle, H):
+@pytest.mark.parametrize("plan", [False, True], ids=["csr_stream", "planned"])
+def test_sage_rmat_bf16_three_layers(oracle, H, plan):
     """Config-3 shape at scale 13: bf16 storage, fp32 accumulation, d = 256."""
     g = gen.rmat_graph(SEED + 3, 13, 25)
     case = H.make_case("sage", g, SEED + 3, [256, 256, 256, 128], 1 << 9, store=torch.bfloat16)
-    run = H.run_gpu(case, snapshots=True)
+    run = H.run_gpu(case, snapshots=True, plan=plan)
     H.check_integers(oracle, case, run)
     print("sage bf16", H.check_outputs(oracle, case, run))
 
 
-def test_sage_degree_ordered_bf16_d128(oracle, H):
+@pytest.mark.parametrize("plan", [False, True], ids=["csr_stream", "planned"])
+def test_sage_degree_ordered_bf16_d128(oracle, H, plan):
     """Config-5 shape at scale 14: degree-ordered ids, d = 128, 128->128->128->64,
     in-degree handed to the layer, flush every 4 chunks."""
     g = gen.rmat_graph(SEED + 5, 14, 32)
@@ -79,7 +83,7 @@ def test_sage_degree_ordered_bf16_d128(oracle, H):
     new_of_old, _ = oracle.reorder_indegree_desc(oracle.in_degree(g.n, col.numpy()))
     g = g.with_relabel(torch.from_numpy(new_of_old.astype(np.int64)))
     case = H.make_case("sage", g, SEED + 5, [128, 128, 128, 64], 1 << 10, store=torch.bfloat16)
-    run = H.run_gpu(case, give_indeg=True, flush_every=4)
+    run = H.run_gpu(case, give_indeg=True, flush_every=4, plan=plan)
     print("sage s14 degree ordered", H.check_outputs(oracle, case, run))
     for st in run.stats:
         assert st["edges_processed"] == case.e and st["vertices_flushed"] == case.n
