@@ -98,7 +98,7 @@ def main() -> int:
         d_in, d_out = wl.dims[li], wl.dims[li + 1]
         act = atlas.ACT_NONE if li + 1 == len(wl.layers) else atlas.ACT_RELU
         dims = atlas.make_dims(atlas.MODEL_SAGE_MEAN, d_in, d_out, atlas.DTYPE_BF16, atlas.DTYPE_BF16, act, chunk,
-                               flags=atlas.FLAG_TIMING if timing else 0)
+                               flags=(atlas.FLAG_TIMING if timing else 0) | atlas.FLAG_EMB_RESIDENT)
         W, b = params[li]
         h = atlas.atlas_layer_init(graph, dims, atlas.make_weights(W, b, atlas.DTYPE_BF16), stream)
         out = outs[li]

@@ -54,7 +54,15 @@ enum atlas_residency { ATLAS_RESIDENT_DEVICE = 0, ATLAS_RESIDENT_PINNED_HOST = 1
 enum atlas_model { ATLAS_MODEL_SAGE_MEAN = 0, ATLAS_MODEL_GCN_SYM = 1, ATLAS_MODEL_GAT = 2 };
 enum atlas_dtype { ATLAS_DTYPE_F32 = 0, ATLAS_DTYPE_BF16 = 1 };
 enum atlas_activation { ATLAS_ACT_NONE = 0, ATLAS_ACT_RELU = 1, ATLAS_ACT_ELU = 2 };
-enum atlas_flags { ATLAS_FLAG_TIMING = 1 }; /* record per-stage GPU time with HIP events */
+enum atlas_flags {
+    ATLAS_FLAG_TIMING = 1,       /* record per-stage GPU time with HIP events                  */
+    ATLAS_FLAG_EMB_RESIDENT = 2  /* DEVICE graphs, SAGE_MEAN: the caller promises that every
+                                    `emb` given to atlas_broadcast_chunk is the row range
+                                    [src_begin, src_end) of ONE contiguous N x d_in matrix that
+                                    stays valid until atlas_layer_finish; the library then reads
+                                    a vertex's own row from that matrix instead of keeping a
+                                    copy (E_STATE if two chunks disagree about the matrix base) */
+};
 
 /* The graph: CSR by SOURCE vertex (paper Sec. 3.2: out-edges, read sequentially
  * by offsets).  Vertex ids are the (re-ordered) ids the chunks are streamed in.

@@ -21,6 +21,7 @@ MODEL_SAGE_MEAN, MODEL_GCN_SYM, MODEL_GAT = 0, 1, 2
 DTYPE_F32, DTYPE_BF16 = 0, 1
 ACT_NONE, ACT_RELU, ACT_ELU = 0, 1, 2
 FLAG_TIMING = 1
+FLAG_EMB_RESIDENT = 2
 DBG_INDEG, DBG_PENDING, DBG_READY, DBG_READY_COUNT, DBG_ACC = range(5)
 
 EXPORTS = [

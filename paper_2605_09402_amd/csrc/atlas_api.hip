@@ -97,6 +97,9 @@ struct atlas_layer {
     const int32_t *indeg = nullptr;
     const int64_t *off_dev = nullptr;  // device-visible row offsets
 
+    bool emb_resident = false;         // own rows are read from the caller's matrix
+    const char *x_base = nullptr;      // base of that matrix (set by the first chunk)
+
     int64_t next_src = 0;
     int64_t num_chunks = 0, num_flushes = 0;
     int64_t bytes_h2d = 0;
@@ -176,7 +179,10 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
     HIP_TRY(L->pending.alloc(n1 * sizeof(int32_t)));
     HIP_TRY(L->ready.alloc(n1 * sizeof(int32_t)));
     HIP_TRY(L->acc.alloc(n1 * L->acc_width * sizeof(float)));
-    if (d.model == ATLAS_MODEL_SAGE_MEAN) HIP_TRY(L->self_rows.alloc(n1 * d.d_in * dtype_size(d.in_dtype)));
+    L->emb_resident = d.model == ATLAS_MODEL_SAGE_MEAN && (d.flags & ATLAS_FLAG_EMB_RESIDENT) &&
+                      L->g.residency == ATLAS_RESIDENT_DEVICE;
+    if (d.model == ATLAS_MODEL_SAGE_MEAN && !L->emb_resident)
+        HIP_TRY(L->self_rows.alloc(n1 * d.d_in * dtype_size(d.in_dtype)));
     HIP_TRY(L->packed_w.alloc(packed_weight_bytes(L->K, d.d_out, L->compute_bf16)));
     HIP_TRY(launch_fill_zero(L->counters.p, L->counters.bytes, s));
     HIP_TRY(launch_fill_zero(L->counters64.p, L->counters64.bytes, s));
@@ -301,7 +307,12 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
     a.counters = L->ctr();
     a.counters64 = static_cast<unsigned long long *>(L->counters64.p);
 
-    char *self_dst = d.model == ATLAS_MODEL_SAGE_MEAN
+    if (L->emb_resident) {
+        const char *base = static_cast<const char *>(emb) - static_cast<size_t>(src_begin) * row_bytes;
+        if (L->x_base && base != L->x_base) return ATLAS_E_STATE;
+        L->x_base = base;
+    }
+    char *self_dst = d.model == ATLAS_MODEL_SAGE_MEAN && !L->emb_resident
                          ? static_cast<char *>(L->self_rows.p) + static_cast<size_t>(src_begin) * row_bytes
                          : nullptr;
     int slot = -1;
@@ -410,7 +421,7 @@ int atlas_flush_ready(atlas_layer_t *L, void *out, int64_t *n_flushed, void *hip
     u.compute_bf16 = L->compute_bf16;
     u.activation = d.activation;
     u.acc = static_cast<const float *>(L->acc.p);
-    u.self_rows = L->self_rows.p;
+    u.self_rows = L->emb_resident ? static_cast<const void *>(L->x_base) : L->self_rows.p;
     u.indeg = L->indeg;
     u.ready = static_cast<const int32_t *>(L->ready.p);
     u.counters = L->ctr();
@@ -420,7 +431,9 @@ int atlas_flush_ready(atlas_layer_t *L, void *out, int64_t *n_flushed, void *hip
     u.n = L->n;
     int rc = start_span(L, L->t_upd, s);
     if (rc != ATLAS_OK) return rc;
-    HIP_TRY(launch_update(u, s));
+    // SAGE rows become ready only after their own chunk: before the first
+    // broadcast there is nothing to update (and no matrix to read own rows from)
+    if (!(L->emb_resident && !L->x_base)) HIP_TRY(launch_update(u, s));
     HIP_TRY(launch_advance_head(L->ctr(), s));
     rc = end_span(L, L->t_upd, s);
     if (rc != ATLAS_OK) return rc;

@@ -148,6 +148,10 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggregateArgs a) {
     }
 }
 
+// The self message of SAGE: every source of the chunk sends its own row to
+// itself, one pending-count decrement.  No other kernel runs on the layer's
+// stream at the same time and each thread owns one vertex, so the decrement
+// is a plain read-modify-write.
 __global__ __launch_bounds__(kBlock) void k_self_message(int64_t b, int64_t e, int32_t *pending,
                                                          int32_t *ready, int32_t *counters) {
     const int lane = threadIdx.x & (kWave - 1);
@@ -159,7 +163,9 @@ __global__ __launch_bounds__(kBlock) void k_self_message(int64_t b, int64_t e, i
         int32_t u = 0;
         if (i < span) {
             u = static_cast<int32_t>(b + i);
-            is_ready = atomicSub(&pending[u], 1) == 1;
+            const int32_t left_after = pending[u] - 1;
+            pending[u] = left_after;
+            is_ready = left_after == 0;
         }
         wave_append_ready(is_ready, u, ready, counters, lane);
     }
@@ -266,6 +272,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
         // the tile's first group continues one that started in an earlier tile?
         bool cut = false;
         if (e0 > 0) cut = a.src_sorted[e0 - 1] >= 0;
+        const bool cut0 = cut;
         const uint64_t below = endmask & ((1ull << lane) - 1ull);
         const bool closes = is_end || lane == cnt - 1;  // last edge of a group, or of the tile
         int32_t dstv = 0;
@@ -315,12 +322,22 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
             row_add_shared<VPL>(a.acc + static_cast<int64_t>(v) * D + lane * VPL, sum);
         }
 
-        // pending count: minus the number of this tile's messages to the group
+        // pending count: minus the number of this tile's messages to the group.
+        // A group that lies wholly inside the tile is the only writer of its
+        // destination's count during this kernel, so a plain read-modify-write
+        // is enough; pieces of a cut group use the atomic.
         bool is_ready = false;
         if (closes) {
             const int prev_end = below ? 63 - __clzll(static_cast<long long>(below)) : -1;
             const int c = lane - prev_end;
-            is_ready = atomicSub(&a.pending[dstv], c) == c;
+            const bool shared = (below == 0 && cut0) || !is_end;
+            if (shared) {
+                is_ready = atomicSub(&a.pending[dstv], c) == c;
+            } else {
+                const int32_t left_after = a.pending[dstv] - c;
+                a.pending[dstv] = left_after;
+                is_ready = left_after == 0;
+            }
         }
         wave_append_ready(is_ready, dstv, a.ready, a.counters, lane);
     }

@@ -80,6 +80,91 @@ __device__ __forceinline__ float apply_activation(float y, int act) {
     return y;
 }
 
+// Stage 128 columns of 16 rows per pass.  Every load of a pass is issued
+// unconditionally (rows past the end of the ready list and lanes past the row
+// width read a valid dummy location and are dropped later) and kept raw in
+// registers, so the 16 loads are in flight together before the first is used.
+template <bool BF16C> struct OwnRaw { using type = float2; };
+template <> struct OwnRaw<true> { using type = uint32_t; };
+
+template <bool BF16C>
+__device__ __forceinline__ typename OwnRaw<BF16C>::type load_own(const void *rows, int64_t o);
+template <> __device__ __forceinline__ uint32_t load_own<true>(const void *rows, int64_t o) {
+    return *reinterpret_cast<const uint32_t *>(static_cast<const uint16_t *>(rows) + o);
+}
+template <> __device__ __forceinline__ float2 load_own<false>(const void *rows, int64_t o) {
+    return *reinterpret_cast<const float2 *>(static_cast<const float *>(rows) + o);
+}
+__device__ __forceinline__ float2 own_to_f32(uint32_t u) {
+    return make_float2(__uint_as_float(u << 16), __uint_as_float(u & 0xffff0000u));
+}
+__device__ __forceinline__ float2 own_to_f32(float2 v) { return v; }
+
+template <bool BF16C>
+__device__ __forceinline__ void gather_rows(const UpdateArgs &a, typename Elem<BF16C>::type *A, int stride,
+                                            int w, int lane, int32_t idv, float scalev) {
+    constexpr int kRows = kTileRows / 4;  // rows per wave
+    const int d = a.d_in;
+    const int segs = (d + 127) >> 7;
+    const int nitems = kRows * segs;
+    const int col_in_seg = lane * 2;
+    const int acc_base = a.model == 0 ? d : 0;  // SAGE: own row first, then the neighbour mean
+    for (int it0 = 0; it0 < nitems; it0 += 16) {
+        float2 v[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int item = it0 + i < nitems ? it0 + i : nitems - 1;
+            const int rr = item / segs;
+            const int col = (item - rr * segs) * 128 + col_in_seg;
+            const int32_t id = __builtin_amdgcn_readlane(idv, rr);
+            const int64_t o = static_cast<int64_t>(id >= 0 ? id : 0) * d + (col < d ? col : 0);
+            v[i] = *reinterpret_cast<const float2 *>(a.acc + o);
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int item = it0 + i;
+            if (item >= nitems) break;
+            const int rr = item / segs;
+            const int col = (item - rr * segs) * 128 + col_in_seg;
+            const int32_t id = __builtin_amdgcn_readlane(idv, rr);
+            const float g = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(scalev), rr));
+            if (col < d) {
+                typename Elem<BF16C>::type *dst = A + (w * kRows + rr) * stride + acc_base + col;
+                const float x = id >= 0 ? v[i].x : 0.f, y = id >= 0 ? v[i].y : 0.f;
+                dst[0] = to_elem<BF16C>(a.model == 0 ? x / g : x * g);
+                dst[1] = to_elem<BF16C>(a.model == 0 ? y / g : y * g);
+            }
+        }
+    }
+    if (a.model != 0) return;
+    for (int it0 = 0; it0 < nitems; it0 += 16) {  // SAGE: the vertex's own row
+        typename OwnRaw<BF16C>::type v[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int item = it0 + i < nitems ? it0 + i : nitems - 1;
+            const int rr = item / segs;
+            const int col = (item - rr * segs) * 128 + col_in_seg;
+            const int32_t id = __builtin_amdgcn_readlane(idv, rr);
+            const int64_t o = static_cast<int64_t>(id >= 0 ? id : 0) * d + (col < d ? col : 0);
+            v[i] = load_own<BF16C>(a.self_rows, o);
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int item = it0 + i;
+            if (item >= nitems) break;
+            const int rr = item / segs;
+            const int col = (item - rr * segs) * 128 + col_in_seg;
+            const int32_t id = __builtin_amdgcn_readlane(idv, rr);
+            if (col < d) {
+                typename Elem<BF16C>::type *dst = A + (w * kRows + rr) * stride + col;
+                const float2 f = own_to_f32(v[i]);
+                dst[0] = to_elem<BF16C>(id >= 0 ? f.x : 0.f);
+                dst[1] = to_elem<BF16C>(id >= 0 ? f.y : 0.f);
+            }
+        }
+    }
+}
+
 template <bool BF16C, int PPW>
 __global__ __launch_bounds__(kBlock) void k_update(UpdateArgs a) {
     using elem_t = typename Elem<BF16C>::type;
@@ -93,6 +178,7 @@ __global__ __launch_bounds__(kBlock) void k_update(UpdateArgs a) {
     const int NB = (a.d_out + 31) / 32;
     constexpr int kStepK = BF16C ? 16 : 2;
     const int KS = K / kStepK;
+    constexpr int kRows = kTileRows / 4;
 
     const int head = a.counters[CTR_READY_HEAD];
     const int tail = a.counters[CTR_READY_TAIL];
@@ -100,34 +186,21 @@ __global__ __launch_bounds__(kBlock) void k_update(UpdateArgs a) {
 
     for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         __syncthreads();  // previous tile's LDS readers are done
-        // ---- gather: wave w stages rows w*16 .. w*16+15 ----
-        for (int rr = 0; rr < kTileRows / 4; ++rr) {
-            const int r = w * (kTileRows / 4) + rr;
-            const int idx = head + tile * kTileRows + r;
-            const int32_t id = idx < tail ? a.ready[idx] : -1;
-            if (lane == 0) ids[r] = id;
-            elem_t *arow = A + r * stride;
-            if (id < 0) {
-                for (int c = lane; c < K; c += 64) arow[c] = to_elem<BF16C>(0.f);
-                continue;
+        // ---- gather: wave w stages rows w*16 .. w*16+15; lane r holds row r's id ----
+        int32_t idv = -1;
+        float scalev = 1.f;
+        if (lane < kRows) {
+            const int idx = head + tile * kTileRows + w * kRows + lane;
+            if (idx < tail) {
+                idv = a.ready[idx];
+                const int32_t deg = a.indeg[idv];
+                const float fd = static_cast<float>(deg > 0 ? deg : 1);
+                // SAGE divides the sum by the in-degree; GCN multiplies by deg^-1/2
+                scalev = a.model == 0 ? fd : 1.0f / sqrtf(fd);
             }
-            const float *accrow = a.acc + static_cast<int64_t>(id) * a.d_in;
-            const int32_t deg = a.indeg[id];
-            if (a.model == 0) {  // SAGE: [own row || mean of neighbours]
-                if (a.in_bf16) {
-                    const uint16_t *srow = static_cast<const uint16_t *>(a.self_rows) + static_cast<int64_t>(id) * a.d_in;
-                    for (int c = lane; c < a.d_in; c += 64) arow[c] = to_elem<BF16C>(bf16_to_f32(srow[c]));
-                } else {
-                    const float *srow = static_cast<const float *>(a.self_rows) + static_cast<int64_t>(id) * a.d_in;
-                    for (int c = lane; c < a.d_in; c += 64) arow[c] = to_elem<BF16C>(srow[c]);
-                }
-                const float fdeg = static_cast<float>(deg > 0 ? deg : 1);
-                for (int c = lane; c < a.d_in; c += 64) arow[a.d_in + c] = to_elem<BF16C>(accrow[c] / fdeg);
-            } else {  // GCN: destination side of the symmetric normalisation
-                const float g = 1.0f / sqrtf(static_cast<float>(deg > 0 ? deg : 1));
-                for (int c = lane; c < a.d_in; c += 64) arow[c] = to_elem<BF16C>(accrow[c] * g);
-            }
+            ids[w * kRows + lane] = idv;
         }
+        gather_rows<BF16C>(a, A, stride, w, lane, idv, scalev);
         __syncthreads();
 
         // ---- MFMA: pairs (mb, nb) p = w + 4*i ----
@@ -138,20 +211,35 @@ __global__ __launch_bounds__(kBlock) void k_update(UpdateArgs a) {
             for (int r = 0; r < 16; ++r) c[i][r] = 0.f;
 
         for (int kk = 0; kk < KS; ++kk) {
+            int last_nb = -1;
+            if constexpr (BF16C) {
+                bf16x8_t bv = {};
 #pragma unroll
-            for (int i = 0; i < PPW; ++i) {
-                const int p = w + 4 * i;
-                if (p >= 2 * NB) continue;
-                const int nb = p % NB, mb = p / NB;
-                if constexpr (BF16C) {
+                for (int i = 0; i < PPW; ++i) {
+                    const int p = w + 4 * i;
+                    if (p >= 2 * NB) continue;
+                    const int nb = p % NB, mb = p / NB;
                     const uint16_t *ap = A + (mb * 32 + (lane & 31)) * stride + kk * 16 + (lane >> 5) * 8;
                     const bf16x8_t av = *reinterpret_cast<const bf16x8_t *>(ap);
-                    const bf16x8_t bv = *reinterpret_cast<const bf16x8_t *>(
-                        static_cast<const uint16_t *>(a.packed_w) + ((static_cast<int64_t>(nb) * KS + kk) * 64 + lane) * 8);
+                    if (nb != last_nb) {
+                        bv = *reinterpret_cast<const bf16x8_t *>(
+                            static_cast<const uint16_t *>(a.packed_w) + ((static_cast<int64_t>(nb) * KS + kk) * 64 + lane) * 8);
+                        last_nb = nb;
+                    }
                     c[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, c[i], 0, 0, 0);
-                } else {
+                }
+            } else {
+                float bv = 0.f;
+#pragma unroll
+                for (int i = 0; i < PPW; ++i) {
+                    const int p = w + 4 * i;
+                    if (p >= 2 * NB) continue;
+                    const int nb = p % NB, mb = p / NB;
                     const float av = A[(mb * 32 + (lane & 31)) * stride + kk * 2 + (lane >> 5)];
-                    const float bv = static_cast<const float *>(a.packed_w)[(static_cast<int64_t>(nb) * KS + kk) * 64 + lane];
+                    if (nb != last_nb) {
+                        bv = static_cast<const float *>(a.packed_w)[(static_cast<int64_t>(nb) * KS + kk) * 64 + lane];
+                        last_nb = nb;
+                    }
                     c[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, c[i], 0, 0, 0);
                 }
             }
@@ -178,6 +266,206 @@ __global__ __launch_bounds__(kBlock) void k_update(UpdateArgs a) {
             }
         }
     }
+}
+
+// ---- pipelined variant: W resident in LDS, double-buffered A tile -----------
+//
+// Used when d_in <= 128 and W plus two A tiles fit in LDS.  One workgroup of
+// 8 waves per CU loops over 64-row tiles.  While the matrix cores work on tile
+// t (A and W both read from LDS), the global loads of tile t+1's rows are
+// already in flight into registers and the ready ids of tile t+2 are being
+// fetched, so the gather latency is hidden behind the contraction instead of
+// being exposed once per tile.
+constexpr int kPipeBlock = 512;
+constexpr int kPipeRows = kTileRows / (kPipeBlock / 64);  // rows staged per wave = 8
+
+template <bool BF16C>
+struct RowRegs {
+    float2 acc[kPipeRows];
+    typename OwnRaw<BF16C>::type own[kPipeRows];
+};
+
+// Issue the loads of the wave's 8 rows.  Straight-line code: rows past the end
+// of the ready list read row 0 and are dropped when the tile is stored.
+template <bool BF16C>
+__device__ __forceinline__ void pipe_issue_rows(const UpdateArgs &a, int32_t idv, int lane, RowRegs<BF16C> &r,
+                                                int32_t &degv) {
+    const int d = a.d_in;
+    const int col = lane * 2 < d ? lane * 2 : 0;
+    degv = a.indeg[idv >= 0 ? idv : 0];
+#pragma unroll
+    for (int i = 0; i < kPipeRows; ++i) {
+        const int32_t id = __builtin_amdgcn_readlane(idv, i);
+        const int64_t o = static_cast<int64_t>(id >= 0 ? id : 0) * d + col;
+        r.acc[i] = *reinterpret_cast<const float2 *>(a.acc + o);
+        if (a.model == 0) r.own[i] = load_own<BF16C>(a.self_rows, o);
+    }
+}
+
+template <bool BF16C>
+__device__ __forceinline__ void pipe_store_rows(const UpdateArgs &a, typename Elem<BF16C>::type *A, int stride,
+                                                int w, int lane, const RowRegs<BF16C> &r, int32_t idv,
+                                                int32_t degv) {
+    const int d = a.d_in;
+    const int col = lane * 2;
+    const float fd = static_cast<float>(degv > 0 ? degv : 1);
+    // SAGE divides the sum by the in-degree; GCN multiplies by deg^-1/2
+    const float scalev = a.model == 0 ? fd : 1.0f / sqrtf(fd);
+    if (col >= d) return;
+#pragma unroll
+    for (int i = 0; i < kPipeRows; ++i) {
+        const float g = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(scalev), i));
+        const bool live = __builtin_amdgcn_readlane(idv, i) >= 0;
+        typename Elem<BF16C>::type *row = A + (w * kPipeRows + i) * stride;
+        const float ax = live ? r.acc[i].x : 0.f, ay = live ? r.acc[i].y : 0.f;
+        if (a.model == 0) {
+            const float2 f = own_to_f32(r.own[i]);
+            row[col] = to_elem<BF16C>(live ? f.x : 0.f);
+            row[col + 1] = to_elem<BF16C>(live ? f.y : 0.f);
+            row[d + col] = to_elem<BF16C>(ax / g);
+            row[d + col + 1] = to_elem<BF16C>(ay / g);
+        } else {
+            row[col] = to_elem<BF16C>(ax * g);
+            row[col + 1] = to_elem<BF16C>(ay * g);
+        }
+    }
+}
+
+template <bool BF16C, int PPW>
+__global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
+    using elem_t = typename Elem<BF16C>::type;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int K = a.K;
+    const int stride = K + lds_pad(BF16C);
+    const int NB = (a.d_out + 31) / 32;
+    constexpr int kStepK = BF16C ? 16 : 2;
+    const int KS = K / kStepK;
+    const size_t w_elems = static_cast<size_t>(NB) * 32 * K;
+    const size_t a_elems = static_cast<size_t>(kTileRows) * stride;
+    int32_t *ids = reinterpret_cast<int32_t *>(smem);  // [2][64]
+    elem_t *Wl = reinterpret_cast<elem_t *>(smem + 2 * kTileRows * sizeof(int32_t));
+    elem_t *A0 = Wl + ((w_elems + 7) & ~static_cast<size_t>(7));
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+
+    const int head = a.counters[CTR_READY_HEAD];
+    const int tail = a.counters[CTR_READY_TAIL];
+    const int ntiles = (tail - head + kTileRows - 1) / kTileRows;
+    if (static_cast<int>(blockIdx.x) >= ntiles) return;
+
+    {  // W -> LDS, 16 bytes per thread per step
+        const uint4 *src = static_cast<const uint4 *>(a.packed_w);
+        uint4 *dst = reinterpret_cast<uint4 *>(Wl);
+        const size_t vecs = w_elems * sizeof(elem_t) / 16;
+        for (size_t i = threadIdx.x; i < vecs; i += kPipeBlock) dst[i] = src[i];
+    }
+
+    auto load_ids = [&](int tile) -> int32_t {
+        int32_t id = -1;
+        if (tile < ntiles && lane < kPipeRows) {
+            const int idx = head + tile * kTileRows + w * kPipeRows + lane;
+            if (idx < tail) id = a.ready[idx];
+        }
+        return id;
+    };
+
+    float bj[PPW];
+#pragma unroll
+    for (int i = 0; i < PPW; ++i) {
+        const int j = ((w + 8 * i) % NB) * 32 + (lane & 31);
+        bj[i] = (a.bias && j < a.d_out) ? a.bias[j] : 0.f;
+    }
+
+    int tile = blockIdx.x;
+    int32_t idv = load_ids(tile);
+    int32_t idv_next = load_ids(tile + gridDim.x);
+    RowRegs<BF16C> regs;
+    int32_t degv;
+    pipe_issue_rows<BF16C>(a, idv, lane, regs, degv);
+
+    for (int it = 0; tile < ntiles; tile += gridDim.x, ++it) {
+        const int buf = it & 1;
+        elem_t *A = A0 + buf * a_elems;
+        int32_t *tids = ids + buf * kTileRows;
+        pipe_store_rows<BF16C>(a, A, stride, w, lane, regs, idv, degv);
+        if (lane < kPipeRows) tids[w * kPipeRows + lane] = idv;
+        __syncthreads();
+        // rows of the next tile and ids of the one after it go in flight now
+        idv = idv_next;
+        idv_next = load_ids(tile + 2 * gridDim.x);
+        pipe_issue_rows<BF16C>(a, idv, lane, regs, degv);
+
+        f32x16_t c[PPW];
+#pragma unroll
+        for (int i = 0; i < PPW; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) c[i][r] = 0.f;
+        for (int kk = 0; kk < KS; ++kk) {
+#pragma unroll
+            for (int i = 0; i < PPW; ++i) {
+                const int p = w + 8 * i;
+                if (p >= 2 * NB) continue;
+                const int nb = p % NB, mb = p / NB;
+                if constexpr (BF16C) {
+                    const bf16x8_t av = *reinterpret_cast<const bf16x8_t *>(
+                        A + (mb * 32 + (lane & 31)) * stride + kk * 16 + (lane >> 5) * 8);
+                    const bf16x8_t bv = *reinterpret_cast<const bf16x8_t *>(
+                        Wl + ((static_cast<size_t>(nb) * KS + kk) * 64 + lane) * 8);
+                    c[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, c[i], 0, 0, 0);
+                } else {
+                    const float av = A[(mb * 32 + (lane & 31)) * stride + kk * 2 + (lane >> 5)];
+                    const float bv = Wl[(static_cast<size_t>(nb) * KS + kk) * 64 + lane];
+                    c[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, c[i], 0, 0, 0);
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < PPW; ++i) {
+            const int p = w + 8 * i;
+            if (p >= 2 * NB) continue;
+            const int nb = p % NB, mb = p / NB;
+            const int j = nb * 32 + (lane & 31);
+            if (j >= a.d_out) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = mb * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int32_t id = tids[row];
+                if (id < 0) continue;
+                const float y = apply_activation(c[i][r] + bj[i], a.activation);
+                const int64_t o = static_cast<int64_t>(id) * a.d_out + j;
+                if (a.out_bf16) static_cast<uint16_t *>(a.out)[o] = f32_to_bf16_rne(y);
+                else static_cast<float *>(a.out)[o] = y;
+            }
+        }
+    }
+}
+
+size_t pipelined_lds_bytes(int K, int d_out, bool bf16c) {
+    const int NB = (d_out + 31) / 32;
+    const size_t es = bf16c ? 2 : 4;
+    const size_t w_elems = (static_cast<size_t>(NB) * 32 * K + 7) & ~static_cast<size_t>(7);
+    return 2 * kTileRows * sizeof(int32_t) + w_elems * es +
+           2 * static_cast<size_t>(kTileRows) * (K + lds_pad(bf16c)) * es;
+}
+
+template <bool BF16C, int PPW>
+hipError_t launch_pipelined_t(const UpdateArgs &a, int grid, hipStream_t s) {
+    const size_t lds = pipelined_lds_bytes(a.K, a.d_out, BF16C);
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_update_pipelined<BF16C, PPW>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL((k_update_pipelined<BF16C, PPW>), dim3(grid), dim3(kPipeBlock), lds, s, a);
+    return hipGetLastError();
+}
+
+template <bool BF16C>
+hipError_t launch_pipelined_c(const UpdateArgs &a, int grid, hipStream_t s) {
+    const int NB = (a.d_out + 31) / 32;
+    return 2 * NB <= 8 ? launch_pipelined_t<BF16C, 1>(a, grid, s) : launch_pipelined_t<BF16C, 2>(a, grid, s);
 }
 
 __global__ void k_advance_head(int32_t *counters) {
@@ -246,6 +534,14 @@ hipError_t launch_update(const UpdateArgs &a, hipStream_t s) {
     if (hipGetDevice(&dev) == hipSuccess)
         (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (cus <= 0) cus = 256;
+    if (a.d_in <= 128 && pipelined_lds_bytes(a.K, a.d_out, a.compute_bf16 != 0) <= 160 * 1024) {
+        int64_t grid = cus;
+        const int64_t max_tiles = (a.n + kTileRows - 1) / kTileRows;
+        if (grid > max_tiles) grid = max_tiles;
+        if (grid < 1) grid = 1;
+        return a.compute_bf16 ? launch_pipelined_c<true>(a, static_cast<int>(grid), s)
+                              : launch_pipelined_c<false>(a, static_cast<int>(grid), s);
+    }
     const size_t lds = update_lds_bytes(a.K, a.compute_bf16 != 0);
     int per_cu = static_cast<int>((160 * 1024) / lds);
     if (per_cu < 1) per_cu = 1;

@@ -81,7 +81,7 @@ def _dt(store: torch.dtype) -> int:
 
 def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, flush_every: int = 1,
             give_indeg: bool = False, timing: bool = False, max_layers: Optional[int] = None,
-            plan: bool = False, plan_chunk: Optional[int] = None) -> GpuRun:
+            plan: bool = False, plan_chunk: Optional[int] = None, emb_resident: bool = False) -> GpuRun:
     """Drive all layers through the C ABI.  With pinned_host the graph and the
     layer-0 features stay in pinned host memory and are staged by the library."""
     dev = torch.device("cuda:0")
@@ -118,7 +118,8 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
         a_s = None if p.attn_src is None else p.attn_src.to(case.store).to(dev).contiguous()
         a_d = None if p.attn_dst is None else p.attn_dst.to(case.store).to(dev).contiguous()
         dims = atlas.make_dims(MODEL_ID[case.model], d_in, d_out, sdt, sdt, act, case.chunk, heads=case.heads,
-                               neg_slope=case.slope, flags=atlas.FLAG_TIMING if timing else 0)
+                               neg_slope=case.slope, flags=(atlas.FLAG_TIMING if timing else 0) |
+                               (atlas.FLAG_EMB_RESIDENT if emb_resident else 0))
         weights = atlas.make_weights(W, b, sdt, a_s, a_d)
         h = atlas.atlas_layer_init(graph, dims, weights, stream)
         out = torch.full((max(n, 1), d_out), float("nan"), dtype=case.store, device=dev)
