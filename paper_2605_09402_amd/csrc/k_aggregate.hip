@@ -45,17 +45,45 @@ __device__ __forceinline__ int64_t wave_find_source(const int64_t *__restrict__ 
     return lo;
 }
 
-// Append the lanes flagged `is_ready` to the ready list with one counter
-// update per wave.
-__device__ __forceinline__ void wave_append_ready(bool is_ready, int32_t v, int32_t *ready,
-                                                  int32_t *counters, int lane) {
+// Ready-list appends are staged per wave in LDS: every wave appends the
+// vertices it completes to its own buffer and moves them to the global list
+// 256 at a time.  The list's tail counter is one address for the whole GPU and
+// same-address atomics retire at roughly one per 10 ns, so it must see one
+// atomic per few hundred completed vertices, not one per tile.  `count` is
+// wave-uniform and stays below kStageFlush between calls.
+constexpr int kStageFlush = 256;
+constexpr int kStageCap = kStageFlush + kWave;
+
+__device__ __forceinline__ void stage_ready(bool is_ready, int32_t v, int32_t *stage, int &count,
+                                            int32_t *ready, int32_t *counters, int lane) {
     const uint64_t m = __ballot(is_ready);
     if (m == 0) return;
-    const int leader = __ffsll(static_cast<unsigned long long>(m)) - 1;
+    if (is_ready) stage[count + __popcll(m & ((1ull << lane) - 1ull))] = v;
+    count += __popcll(m);
+    __builtin_amdgcn_wave_barrier();
+    if (count >= kStageFlush) {
+        int base = 0;
+        if (lane == 0) base = atomicAdd(&counters[CTR_READY_TAIL], kStageFlush);
+        base = __builtin_amdgcn_readfirstlane(base);
+#pragma unroll
+        for (int k = 0; k < kStageFlush / kWave; ++k) ready[base + k * kWave + lane] = stage[k * kWave + lane];
+        const int rem = count - kStageFlush;
+        int32_t t = 0;
+        if (lane < rem) t = stage[kStageFlush + lane];
+        __builtin_amdgcn_wave_barrier();
+        if (lane < rem) stage[lane] = t;
+        __builtin_amdgcn_wave_barrier();
+        count = rem;
+    }
+}
+
+__device__ __forceinline__ void drain_ready(const int32_t *stage, int count, int32_t *ready,
+                                            int32_t *counters, int lane) {
+    if (count <= 0) return;
     int base = 0;
-    if (lane == leader) base = atomicAdd(&counters[CTR_READY_TAIL], __popcll(m));
-    base = __shfl(base, leader);
-    if (is_ready) ready[base + __popcll(m & ((1ull << lane) - 1ull))] = v;
+    if (lane == 0) base = atomicAdd(&counters[CTR_READY_TAIL], count);
+    base = __builtin_amdgcn_readfirstlane(base);
+    for (int k = lane; k < count; k += kWave) ready[base + k] = stage[k];
 }
 
 template <typename T, int VPL, int MODEL>
@@ -68,6 +96,9 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggregateArgs a) {
     const int64_t eend = a.off[a.src_end];
     const int64_t ntiles = (eend - ebeg + kTileEdges - 1) / kTileEdges;
     const T *__restrict__ emb = static_cast<const T *>(a.emb);
+    __shared__ int32_t stage_all[(kBlock / kWave) * kStageCap];
+    int32_t *stage = stage_all + (threadIdx.x >> 6) * kStageCap;
+    int staged = 0;
 
     if (wave == 0 && lane == 0)
         atomicAdd(&a.counters64[CTR64_EDGES], static_cast<unsigned long long>(eend - ebeg));
@@ -144,8 +175,9 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggregateArgs a) {
         // count to zero completes the destination.
         bool is_ready = false;
         if (lane < cnt) is_ready = atomicSub(&a.pending[v], 1) == 1;
-        wave_append_ready(is_ready, v, a.ready, a.counters, lane);
+        stage_ready(is_ready, v, stage, staged, a.ready, a.counters, lane);
     }
+    drain_ready(stage, staged, a.ready, a.counters, lane);
 }
 
 // The self message of SAGE: every source of the chunk sends its own row to
@@ -158,6 +190,9 @@ __global__ __launch_bounds__(kBlock) void k_self_message(int64_t b, int64_t e, i
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
     const int64_t span = e - b;
     const int64_t rounded = (span + kBlock - 1) / kBlock * kBlock;  // keep whole waves in the loop
+    __shared__ int32_t stage_all[(kBlock / kWave) * kStageCap];
+    int32_t *stage = stage_all + (threadIdx.x >> 6) * kStageCap;
+    int staged = 0;
     for (int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; i < rounded; i += stride) {
         bool is_ready = false;
         int32_t u = 0;
@@ -167,8 +202,9 @@ __global__ __launch_bounds__(kBlock) void k_self_message(int64_t b, int64_t e, i
             pending[u] = left_after;
             is_ready = left_after == 0;
         }
-        wave_append_ready(is_ready, u, ready, counters, lane);
+        stage_ready(is_ready, u, stage, staged, ready, counters, lane);
     }
+    drain_ready(stage, staged, ready, counters, lane);
 }
 
 // ---- planned chunk: edges regrouped by destination --------------------------
@@ -255,6 +291,9 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
     const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (kBlock / kWave);
     const int64_t ntiles = (a.n_edges + kTileEdges - 1) / kTileEdges;
     const T *__restrict__ emb = static_cast<const T *>(a.emb);
+    __shared__ int32_t stage_all[(kBlock / kWave) * kStageCap];
+    int32_t *stage = stage_all + (threadIdx.x >> 6) * kStageCap;
+    int staged = 0;
 
     if (wave == 0 && lane == 0)
         atomicAdd(&a.counters64[CTR64_EDGES], static_cast<unsigned long long>(a.n_edges));
@@ -339,8 +378,9 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
                 is_ready = left_after == 0;
             }
         }
-        wave_append_ready(is_ready, dstv, a.ready, a.counters, lane);
+        stage_ready(is_ready, dstv, stage, staged, a.ready, a.counters, lane);
     }
+    drain_ready(stage, staged, a.ready, a.counters, lane);
 }
 
 template <typename T, int MODEL>

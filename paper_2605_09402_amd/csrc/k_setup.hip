@@ -43,6 +43,8 @@ __global__ __launch_bounds__(kBlock) void k_init_pending(const int32_t *__restri
             pending[i] = p;
             is_ready = p == 0;  // nothing will ever arrive: complete at layer start
         }
+        // seeding happens once per layer and is rare (GAT vertices without
+        // in-edges): one tail update per wave is enough here
         const uint64_t m = __ballot(is_ready);
         if (m) {
             const int leader = __ffsll(static_cast<unsigned long long>(m)) - 1;
