@@ -214,3 +214,12 @@ def check_outputs(oracle, case: Case, run: GpuRun):
         errs.append(err)
         assert err <= tol, "layer %d: row-normalised relative error %.3e > %.1e" % (li, err, tol)
     return errs
+
+
+def case_from_edges(model: str, n: int, src, dst, seed: int, dims: List[int], chunk: int, feat: str = "uniform",
+                    store: torch.dtype = torch.float32, act: str = "relu", heads: int = 1) -> Case:
+    """A case over an explicit edge list (hand-made degenerate graphs)."""
+    src = torch.as_tensor(src, dtype=torch.int64)
+    dst = torch.as_tensor(dst, dtype=torch.int64)
+    g = gen.EdgeSource(n, 1, lambda k: (src, dst))
+    return make_case(model, g, seed, dims, chunk, feat, store, act, heads)

@@ -1,0 +1,188 @@
+"""GPU edge cases: degenerate graphs, width sweep, residency and API errors.
+All through the C ABI, all against the CPU oracle."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import gen
+
+pytestmark = pytest.mark.gpu
+SEED = 0x5EED0100
+
+
+@pytest.fixture(scope="module")
+def H():
+    import harness
+    return harness
+
+
+@pytest.fixture(scope="module")
+def atlas():
+    import paper_2605_09402_amd as a
+    a.lib()
+    return a
+
+
+def both_paths(H, oracle, case, ints=True, **kw):
+    for plan in (False, True):
+        run = H.run_gpu(case, snapshots=ints, plan=plan, **kw)
+        if ints:
+            for li in range(len(case.layers)):
+                H.check_integers(oracle, case, run, layer=li)
+        H.check_outputs(oracle, case, run)
+        for st in run.stats:
+            assert st["edges_processed"] == case.e and st["vertices_flushed"] == case.n
+
+
+@pytest.mark.parametrize("model", ["sage", "gcn"])
+def test_no_edges(oracle, H, model):
+    """N vertices, E = 0: SAGE completes by self messages, GCN at layer start."""
+    case = H.case_from_edges(model, 300, [], [], SEED, [64, 32], 128)
+    both_paths(H, oracle, case)
+
+
+def test_hot_source_and_hot_destination(oracle, H):
+    """One source with 70,000 out-edges and one destination with 70,000
+    in-edges (groups spanning >1,000 tiles; multi-edges), plus a sparse rest."""
+    n = 50_000
+    rng = np.random.default_rng(3)
+    hub_out = rng.integers(0, n, 70_000)
+    hub_in = rng.integers(0, n, 70_000)
+    rest_s = rng.integers(0, n, 30_000)
+    rest_d = rng.integers(0, n, 30_000)
+    src = np.concatenate([np.full(70_000, 17), hub_in, rest_s, np.full(500, 4242)])
+    dst = np.concatenate([hub_out, np.full(70_000, 31_000), rest_d, np.full(500, 99)])   # 500 copies of 4242 -> 99
+    case = H.case_from_edges("sage", n, src, dst, SEED + 1, [128, 64], 4096)
+    both_paths(H, oracle, case)
+
+
+def test_long_runs_of_sources_without_edges(oracle, H):
+    """Every 150th source has one out-edge: a 64-edge tile spans ~9,600 sources."""
+    n = 40_000
+    src = np.arange(0, n, 150)
+    dst = (src * 7 + 3) % n
+    case = H.case_from_edges("gcn", n, np.concatenate([src, np.arange(n)]), np.concatenate([dst, np.arange(n)]),
+                             SEED + 2, [64, 16], 16_384)
+    both_paths(H, oracle, case)
+
+
+@pytest.mark.parametrize("store", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("d_in,d_out", [(64, 16), (192, 48), (256, 160), (512, 256), (128, 96)])
+def test_width_sweep(oracle, H, d_in, d_out, store):
+    if store == torch.float32 and d_in == 512:
+        d_in = 256   # fp32 SAGE tile of K = 1024 does not fit LDS; K = 512 is the fp32 limit
+    g = gen.rmat_graph(SEED + d_in + d_out, 11, 8)
+    for model in ("sage", "gcn"):
+        case = H.make_case(model, g, SEED + d_in, [d_in, d_out], 600, store=store,
+                           feat="normal" if store == torch.float32 else "uniform")
+        if model == "gcn":   # GCN needs D > 0 everywhere: add the self loops
+            case = H.make_case(model, gen.rmat_graph(SEED + d_in + d_out, 11, 8, self_loops=True), SEED + d_in,
+                               [d_in, d_out], 600, store=store)
+        both_paths(H, oracle, case, ints=False)
+
+
+def test_unaligned_chunks_fall_back_to_csr_stream(oracle, H):
+    """Plan built for 1,000-source chunks, layer streamed in 768-source chunks."""
+    case = H.make_case("sage", gen.rmat_graph(SEED + 9, 12, 16), SEED + 9, [128, 64], 768)
+    run = H.run_gpu(case, snapshots=True, plan=True, plan_chunk=1000)
+    H.check_integers(oracle, case, run)
+    H.check_outputs(oracle, case, run)
+
+
+@pytest.mark.parametrize("model,store", [("sage", torch.bfloat16), ("gcn", torch.float32)])
+def test_pinned_host_residency(oracle, H, model, store):
+    """Graph and layer-0 features in pinned host memory, staged chunk by chunk
+    on the library's copy stream (two slots)."""
+    g = gen.rmat_graph(SEED + 11, 12, 16, self_loops=(model == "gcn"))
+    case = H.make_case(model, g, SEED + 11, [128, 128, 64], 500, store=store)
+    run = H.run_gpu(case, snapshots=True, pinned_host=True)
+    H.check_integers(oracle, case, run)
+    H.check_outputs(oracle, case, run)
+    row = 128 * (2 if store == torch.bfloat16 else 4)
+    assert run.stats[0]["bytes_copied_h2d"] == case.n * row + case.e * 4 + (case.n + 1) * 8
+    run2 = H.run_gpu(case, pinned_host=True, flush_every=3)     # no host sync between chunks
+    H.check_outputs(oracle, case, run2)
+
+
+def test_api_errors(atlas, H):
+    dev = torch.device("cuda:0")
+    case = H.make_case("sage", gen.uniform_graph(SEED + 20, 1000, 5000), SEED + 20, [64, 16], 256)
+    off, col = case.off.to(dev), case.col.to(dev)
+    X = case.X.to(dev)
+    W = case.layers[0].W.float().to(dev).contiguous()
+    b = case.layers[0].bias.float().to(dev).contiguous()
+    g = atlas.make_graph(case.n, case.e, off, col)
+    wts = atlas.make_weights(W, b, atlas.DTYPE_F32)
+    L = atlas.lib()
+
+    def dims(**kw):
+        a = dict(model=atlas.MODEL_SAGE_MEAN, d_in=64, d_out=16, in_dtype=0, out_dtype=0, activation=0,
+                 max_chunk_sources=256)
+        a.update(kw)
+        return atlas.make_dims(**a)
+
+    def status(fn, *args):
+        with pytest.raises(atlas.AtlasError) as ei:
+            fn(*args)
+        return ei.value.status
+
+    assert status(atlas.atlas_layer_init, g, dims(d_in=100), wts) == atlas.E_BAD_DIMS
+    assert status(atlas.atlas_layer_init, g, dims(d_out=20), wts) == atlas.E_BAD_DIMS
+    assert status(atlas.atlas_layer_init, g, dims(model=7), wts) == atlas.E_BAD_DIMS
+    assert status(atlas.atlas_layer_init, g, dims(max_chunk_sources=0), wts) == atlas.E_BAD_DIMS
+    assert status(atlas.atlas_layer_init, atlas.make_graph(1 << 31, 0, off, col), dims(), wts) == atlas.E_OVERFLOW
+    assert status(atlas.atlas_layer_init, atlas.make_graph(case.n, case.e, None, col), dims(), wts) == atlas.E_NULL
+    assert L.atlas_layer_init(None, None, None, None, None) == atlas.E_NULL
+    assert L.atlas_broadcast_chunk(None, 0, 1, None, None) == atlas.E_NULL
+    assert L.atlas_layer_finish(None, None) == atlas.E_NULL
+
+    h = atlas.atlas_layer_init(g, dims(), wts)
+    out = torch.zeros((case.n, 16), device=dev)
+    assert status(atlas.atlas_broadcast_chunk, h, 256, 512, X[256:512]) == atlas.E_ORDER     # must start at 0
+    assert status(atlas.atlas_broadcast_chunk, h, 0, 300, X[0:300]) == atlas.E_RANGE         # longer than max
+    assert status(atlas.atlas_broadcast_chunk, h, 0, 0, X[0:1]) == atlas.E_RANGE
+    assert status(atlas.atlas_broadcast_chunk, h, -1, 5, X[0:6]) == atlas.E_RANGE
+    assert status(atlas.atlas_attention_prepass, h, 0, 256, X[0:256]) == atlas.E_STATE       # not a GAT layer
+    atlas.atlas_broadcast_chunk(h, 0, 256, X[0:256])
+    assert status(atlas.atlas_broadcast_chunk, h, 0, 256, X[0:256]) == atlas.E_ORDER         # repeated chunk
+    assert status(atlas.atlas_broadcast_chunk, h, 300, 400, X[300:400]) == atlas.E_ORDER     # gap
+    assert status(atlas.atlas_broadcast_chunk, h, 256, 1001, X[256:]) == atlas.E_RANGE       # past N
+    atlas.atlas_flush_ready(h, out)
+    with pytest.raises(atlas.AtlasError) as ei:      # finish with sources still unbroadcast
+        atlas.atlas_layer_finish(h)
+    assert ei.value.status == atlas.E_INCOMPLETE and ei.value.stats["sources_processed"] == 256
+
+    # all chunks broadcast but the last flush forgotten
+    h = atlas.atlas_layer_init(g, dims(), wts)
+    for b0 in range(0, case.n, 256):
+        atlas.atlas_broadcast_chunk(h, b0, min(case.n, b0 + 256), X[b0:b0 + 256])
+    with pytest.raises(atlas.AtlasError) as ei:
+        atlas.atlas_layer_finish(h)
+    assert ei.value.status == atlas.E_INCOMPLETE
+    assert ei.value.stats["vertices_completed"] == case.n and ei.value.stats["vertices_flushed"] == 0
+
+    # resident-embedding promise broken: second chunk comes from another matrix
+    h = atlas.atlas_layer_init(g, dims(flags=atlas.FLAG_EMB_RESIDENT), wts)
+    atlas.atlas_broadcast_chunk(h, 0, 256, X[0:256])
+    other = X.clone()
+    assert status(atlas.atlas_broadcast_chunk, h, 256, 512, other[256:512]) == atlas.E_STATE
+    with pytest.raises(atlas.AtlasError):
+        atlas.atlas_layer_finish(h)
+    assert status(atlas.atlas_plan_create, atlas.make_graph(case.n, case.e, off, col), 0) == atlas.E_BAD_DIMS
+    atlas.atlas_release_cache()
+
+
+def test_zero_vertices(atlas):
+    dev = torch.device("cuda:0")
+    off = torch.zeros(1, dtype=torch.int64, device=dev)
+    col = torch.zeros(1, dtype=torch.int32, device=dev)
+    W = torch.zeros((128, 16), device=dev)
+    h = atlas.atlas_layer_init(atlas.make_graph(0, 0, off, col),
+                               atlas.make_dims(atlas.MODEL_SAGE_MEAN, 64, 16, 0, 0, 0, 64),
+                               atlas.make_weights(W, None, atlas.DTYPE_F32))
+    out = torch.zeros((1, 16), device=dev)
+    assert atlas.atlas_flush_ready(h, out, count=True) == 0
+    st = atlas.atlas_layer_finish(h)
+    assert st["vertices_flushed"] == 0 and st["edges_processed"] == 0
