@@ -82,8 +82,9 @@ typedef struct {
 } atlas_graph_t;
 
 /* Layer shape.  d_in must be a multiple of 64 (one wavefront holds a row),
- * at most 512; d_out a multiple of 16, at most 256; GAT: d_out % heads == 0,
- * d_out a multiple of 64 and (d_out / heads) a power of two <= 64. */
+ * at most 512 (fp32 SAGE_MEAN: at most 256); d_out a multiple of 16, at most
+ * 256.  GAT: fp32 embeddings on a DEVICE graph, 1 <= heads <= 8, d_out a
+ * multiple of 64 and of heads, and (d_out / heads) a multiple of (d_out / 64). */
 typedef struct {
     int32_t model;             /* atlas_model                                              */
     int32_t d_in, d_out;       /* input / output embedding width                           */

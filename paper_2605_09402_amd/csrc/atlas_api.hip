@@ -94,6 +94,8 @@ struct atlas_layer {
     int acc_width = 0;
 
     Buf indeg_own, pending, ready, counters, counters64, acc, self_rows, packed_w, bias, dev_off;
+    Buf gat_el, gat_er, gat_mcur, gat_mnext, gat_l, gat_wa, gat_z;   // GAT state
+    int64_t prepass_next = 0;
     const int32_t *indeg = nullptr;
     const int64_t *off_dev = nullptr;  // device-visible row offsets
 
@@ -118,7 +120,8 @@ struct atlas_layer {
 
     void destroy() {
         for (Buf *b : {&indeg_own, &pending, &ready, &counters, &counters64, &acc, &self_rows, &packed_w, &bias,
-                       &dev_off, &stage_col[0], &stage_col[1], &stage_emb[0], &stage_emb[1]})
+                       &dev_off, &stage_col[0], &stage_col[1], &stage_emb[0], &stage_emb[1], &gat_el, &gat_er,
+                       &gat_mcur, &gat_mnext, &gat_l, &gat_wa, &gat_z})
             b->release();
         for (auto *v : {&t_agg, &t_self, &t_upd, &t_copy, &t_init})
             for (auto &sp : *v) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
@@ -132,8 +135,17 @@ struct atlas_layer {
 
 namespace {
 
-int check_dims(const atlas_dims_t &d, const atlas_weights_t &w) {
-    if (d.model != ATLAS_MODEL_SAGE_MEAN && d.model != ATLAS_MODEL_GCN_SYM) return ATLAS_E_BAD_DIMS;
+int check_dims(const atlas_dims_t &d, const atlas_weights_t &w, int residency) {
+    if (d.model != ATLAS_MODEL_SAGE_MEAN && d.model != ATLAS_MODEL_GCN_SYM && d.model != ATLAS_MODEL_GAT)
+        return ATLAS_E_BAD_DIMS;
+    if (d.model == ATLAS_MODEL_GAT) {
+        // fp32 embeddings in HBM; a wave holds a transformed row and each lane's
+        // elements must fall into one head
+        if (residency != ATLAS_RESIDENT_DEVICE || d.in_dtype != ATLAS_DTYPE_F32) return ATLAS_E_BAD_DIMS;
+        if (d.heads < 1 || d.heads > 8 || d.d_out % 64 != 0 || d.d_out % d.heads != 0) return ATLAS_E_BAD_DIMS;
+        if ((d.d_out / d.heads) % (d.d_out / 64) != 0) return ATLAS_E_BAD_DIMS;
+        if (!w.attn_src || !w.attn_dst) return ATLAS_E_NULL;
+    }
     if (d.d_in <= 0 || d.d_in % 64 != 0 || d.d_in > 512) return ATLAS_E_BAD_DIMS;
     if (d.d_out <= 0 || d.d_out % 16 != 0 || d.d_out > 256) return ATLAS_E_BAD_DIMS;
     for (int dt : {d.in_dtype, d.out_dtype, w.dtype})
@@ -224,6 +236,22 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
         HIP_TRY(launch_in_degree(L->g.col_indices, L->e, static_cast<int32_t *>(L->indeg_own.p), n, s));
         L->indeg = static_cast<const int32_t *>(L->indeg_own.p);
     }
+    if (d.model == ATLAS_MODEL_GAT) {
+        const size_t nh = n1 * d.heads;
+        HIP_TRY(L->gat_el.alloc(nh * sizeof(float)));
+        HIP_TRY(L->gat_er.alloc(nh * sizeof(float)));
+        HIP_TRY(L->gat_mcur.alloc(nh * sizeof(int32_t)));
+        HIP_TRY(L->gat_mnext.alloc(nh * sizeof(int32_t)));
+        HIP_TRY(L->gat_l.alloc(nh * sizeof(float)));
+        HIP_TRY(L->gat_wa.alloc(static_cast<size_t>(d.d_in) * 2 * d.heads * sizeof(float)));
+        HIP_TRY(L->gat_z.alloc(static_cast<size_t>(std::min<int64_t>(d.max_chunk_sources, std::max<int64_t>(n, 1))) *
+                               d.d_out * sizeof(float)));
+        HIP_TRY(launch_fill_i32(static_cast<int32_t *>(L->gat_mcur.p), gat_encoded_neg_inf(), n * d.heads, s));
+        HIP_TRY(launch_fill_i32(static_cast<int32_t *>(L->gat_mnext.p), gat_encoded_neg_inf(), n * d.heads, s));
+        HIP_TRY(launch_fill_zero(L->gat_l.p, static_cast<size_t>(n) * d.heads * sizeof(float), s));
+        HIP_TRY(launch_gat_fold_attention(w->W, w->attn_src, w->attn_dst, w->dtype == ATLAS_DTYPE_BF16, d.d_in,
+                                          d.heads, d.d_out / d.heads, static_cast<float *>(L->gat_wa.p), s));
+    }
     HIP_TRY(launch_init_pending(L->indeg, L->selfmsg, n, static_cast<int32_t *>(L->pending.p),
                                 static_cast<int32_t *>(L->ready.p), L->ctr(), s));
     HIP_TRY(launch_pack_weights(w->W, w->dtype == ATLAS_DTYPE_BF16, L->K, d.d_out, L->compute_bf16,
@@ -247,7 +275,7 @@ int atlas_layer_init(const atlas_graph_t *graph, const atlas_dims_t *dims, const
     if (!graph->row_offsets || (graph->num_edges > 0 && !graph->col_indices) || !weights->W) return ATLAS_E_NULL;
     if (graph->residency != ATLAS_RESIDENT_DEVICE && graph->residency != ATLAS_RESIDENT_PINNED_HOST)
         return ATLAS_E_BAD_DIMS;
-    int rc = check_dims(*dims, *weights);
+    int rc = check_dims(*dims, *weights, graph->residency);
     if (rc != ATLAS_OK) return rc;
 
     atlas_layer *L = new (std::nothrow) atlas_layer();
@@ -259,7 +287,7 @@ int atlas_layer_init(const atlas_graph_t *graph, const atlas_dims_t *dims, const
     L->selfmsg = dims->model == ATLAS_MODEL_SAGE_MEAN ? 1 : 0;
     L->K = dims->model == ATLAS_MODEL_SAGE_MEAN ? 2 * dims->d_in : dims->d_in;
     L->compute_bf16 = dims->in_dtype == ATLAS_DTYPE_BF16;
-    L->acc_width = dims->d_in;
+    L->acc_width = dims->model == ATLAS_MODEL_GAT ? dims->d_out : dims->d_in;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     L->last_stream = s;
     rc = start_span(L, L->t_init, s);
@@ -275,9 +303,35 @@ int atlas_layer_init(const atlas_graph_t *graph, const atlas_dims_t *dims, const
     return ATLAS_OK;
 }
 
-int atlas_attention_prepass(atlas_layer_t *layer, int64_t, int64_t, const void *, void *) {
-    if (!layer) return ATLAS_E_NULL;
-    return ATLAS_E_STATE;
+namespace {
+GatState gat_state(atlas_layer *L) {
+    GatState g;
+    g.el = static_cast<const float *>(L->gat_el.p);
+    g.er = static_cast<const float *>(L->gat_er.p);
+    g.m_cur = static_cast<int32_t *>(L->gat_mcur.p);
+    g.m_next = static_cast<int32_t *>(L->gat_mnext.p);
+    g.l = static_cast<float *>(L->gat_l.p);
+    g.heads = L->dims.heads;
+    g.dh = L->dims.d_out / L->dims.heads;
+    g.slope = L->dims.neg_slope;
+    return g;
+}
+}  // namespace
+
+int atlas_attention_prepass(atlas_layer_t *L, int64_t src_begin, int64_t src_end, const void *emb,
+                            void *hip_stream) {
+    if (!L || !emb) return ATLAS_E_NULL;
+    if (L->dims.model != ATLAS_MODEL_GAT || L->next_src != 0) return ATLAS_E_STATE;
+    if (src_begin < 0 || src_end > L->n || src_begin >= src_end ||
+        src_end - src_begin > L->dims.max_chunk_sources)
+        return ATLAS_E_RANGE;
+    if (src_begin != L->prepass_next) return ATLAS_E_ORDER;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    L->last_stream = s;
+    HIP_TRY(launch_gat_prepass(emb, 0, src_begin, src_end, L->dims.d_in, static_cast<const float *>(L->gat_wa.p),
+                               L->dims.heads, static_cast<float *>(L->gat_el.p), static_cast<float *>(L->gat_er.p), s));
+    L->prepass_next = src_end;
+    return ATLAS_OK;
 }
 
 int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, const void *emb,
@@ -287,6 +341,8 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         src_end - src_begin > L->dims.max_chunk_sources)
         return ATLAS_E_RANGE;
     if (src_begin != L->next_src) return ATLAS_E_ORDER;
+    // GAT: a destination's attention term must exist before its first message
+    if (L->dims.model == ATLAS_MODEL_GAT && L->prepass_next != L->n) return ATLAS_E_STATE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     L->last_stream = s;
     const atlas_dims_t &d = L->dims;
@@ -368,6 +424,30 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         HIP_TRY(launch_self_message(src_begin, src_end, a.pending, a.ready, a.counters, s));
         if ((rc = end_span(L, L->t_self, s)) != ATLAS_OK) return rc;
     }
+    if (d.model == ATLAS_MODEL_GAT) {
+        // transform the chunk (z = x W on the matrix cores), raise the running
+        // maxima with the chunk's logits, move the touched destinations to them
+        if ((rc = start_span(L, L->t_self, s)) != ATLAS_OK) return rc;
+        UpdateArgs u{};
+        u.model = 2;
+        u.d_in = d.d_in;
+        u.d_out = d.d_out;
+        u.K = L->K;
+        u.acc = static_cast<const float *>(emb);
+        u.counters = L->ctr();
+        u.packed_w = L->packed_w.p;
+        u.out = L->gat_z.p;
+        u.n = src_end - src_begin;
+        u.identity_rows = src_end - src_begin;
+        HIP_TRY(launch_update(u, s));
+        a.gat = gat_state(L);
+        a.emb = L->gat_z.p;
+        a.d = d.d_out;
+        a.in_bf16 = 0;
+        HIP_TRY(launch_gat_chunk_max(a, s));
+        HIP_TRY(launch_gat_rescale(a.gat, a.acc, d.d_out, L->n, s));
+        if ((rc = end_span(L, L->t_self, s)) != ATLAS_OK) return rc;
+    }
     if ((rc = start_span(L, L->t_agg, s)) != ATLAS_OK) return rc;
     if (pc) {
         GroupedArgs ga{};
@@ -375,7 +455,8 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         ga.n_edges = pc->n_edges;
         ga.grp_dst = pc->grp_dst;
         ga.tile_grp = pc->tile_grp;
-        ga.emb = emb;
+        ga.emb = a.emb;
+        ga.gat = a.gat;
         ga.src_begin = src_begin;
         ga.d = a.d;
         ga.in_bf16 = a.in_bf16;
@@ -431,6 +512,22 @@ int atlas_flush_ready(atlas_layer_t *L, void *out, int64_t *n_flushed, void *hip
     u.n = L->n;
     int rc = start_span(L, L->t_upd, s);
     if (rc != ATLAS_OK) return rc;
+    if (d.model == ATLAS_MODEL_GAT) {
+        GatFinalizeArgs f{};
+        f.acc = u.acc;
+        f.l = static_cast<const float *>(L->gat_l.p);
+        f.ready = u.ready;
+        f.counters = u.counters;
+        f.bias = u.bias;
+        f.out = out;
+        f.d_out = d.d_out;
+        f.heads = d.heads;
+        f.dh = d.d_out / d.heads;
+        f.activation = d.activation;
+        f.out_bf16 = u.out_bf16;
+        f.n = L->n;
+        HIP_TRY(launch_gat_finalize(f, s));
+    } else
     // SAGE rows become ready only after their own chunk: before the first
     // broadcast there is nothing to update (and no matrix to read own rows from)
     if (!(L->emb_resident && !L->x_base)) HIP_TRY(launch_update(u, s));

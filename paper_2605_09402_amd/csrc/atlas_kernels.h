@@ -17,6 +17,20 @@ enum Counter {
 // 64-bit counters (separate block): edges pushed so far.
 enum Counter64 { CTR64_EDGES = 0, CTR64_COUNT = 8 };
 
+// Attention state of a GAT layer (all [N][heads], fp32 unless noted).
+// The running maximum is stored as an order-preserving int32 image of the
+// float so that an integer atomicMax implements a float maximum.
+struct GatState {
+    const float *el = nullptr;   // a_src . z_u
+    const float *er = nullptr;   // a_dst . z_v
+    int32_t *m_cur = nullptr;    // reference maximum the accumulated state is relative to
+    int32_t *m_next = nullptr;   // running maximum including the chunk being broadcast
+    float *l = nullptr;          // running softmax denominator (relative to m_cur)
+    int heads = 1;
+    int dh = 0;                  // columns per head
+    float slope = 0.2f;
+};
+
 struct AggregateArgs {
     const int64_t *off;    // row offsets addressed by global source id
     const int32_t *col;    // col[e - col_base] is the destination of edge e
@@ -32,6 +46,7 @@ struct AggregateArgs {
     int32_t *ready;        // [N]
     int32_t *counters;
     unsigned long long *counters64;
+    GatState gat;          // model == GAT only
 };
 
 // S2+S3+S4: edge-balanced scatter-aggregate with fused pending decrement and
@@ -64,6 +79,7 @@ struct GroupedArgs {
     int32_t *ready;
     int32_t *counters;
     unsigned long long *counters64;
+    GatState gat;               // model == GAT only
 };
 
 // S2+S3+S4 over a planned chunk: per-destination register sums, one row update
@@ -74,6 +90,31 @@ hipError_t launch_aggregate_grouped(const GroupedArgs &a, hipStream_t s);
 hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int64_t n, int64_t src_begin,
                             int64_t src_end, int64_t edge_begin, int64_t edge_end, int32_t *src_sorted_all,
                             PlanChunk *out);
+
+// GAT, per chunk: raise m_next[v][h] to the largest logit any edge of the chunk
+// sends to v (CSR order), then bring every destination whose maximum moved to
+// the new reference (rescale l and acc, m_cur = m_next).
+hipError_t launch_gat_chunk_max(const AggregateArgs &a, hipStream_t s);
+hipError_t launch_gat_rescale(const GatState &g, float *acc, int d_out, int64_t n, hipStream_t s);
+// GAT set-up and prepass.
+hipError_t launch_fill_i32(int32_t *p, int32_t value, int64_t count, hipStream_t s);
+int32_t gat_encoded_neg_inf();
+hipError_t launch_gat_fold_attention(const void *W, const void *a_src, const void *a_dst, int w_bf16, int d_in,
+                                     int heads, int dh, float *wa, hipStream_t s);   // wa: [d_in][2*heads]
+hipError_t launch_gat_prepass(const void *emb, int in_bf16, int64_t src_begin, int64_t src_end, int d_in,
+                              const float *wa, int heads, float *el, float *er, hipStream_t s);
+// GAT flush: y = acc / l (+ bias, activation) for the ready rows.
+struct GatFinalizeArgs {
+    const float *acc;
+    const float *l;
+    const int32_t *ready;
+    int32_t *counters;
+    const float *bias;
+    void *out;
+    int d_out, heads, dh, activation, out_bf16;
+    int64_t n;
+};
+hipError_t launch_gat_finalize(const GatFinalizeArgs &a, hipStream_t s);
 
 // SAGE self message of sources [b, e): pending[u] -= 1 with ready compaction.
 hipError_t launch_self_message(int64_t b, int64_t e, int32_t *pending, int32_t *ready,
@@ -106,6 +147,8 @@ struct UpdateArgs {
     const float *bias;        // fp32 [d_out] or nullptr
     void *out;                // [N][d_out]
     int64_t n;
+    int64_t identity_rows;    // > 0: no ready list; rows 0..identity_rows-1 of `acc` (a dense
+                              // row block, model 2 = plain X W) map to the same rows of `out`
 };
 // S5: gather ready rows, normalise, MFMA GEMM, bias, activation, scatter rows.
 hipError_t launch_update(const UpdateArgs &a, hipStream_t s);

@@ -86,6 +86,57 @@ __device__ __forceinline__ void drain_ready(const int32_t *stage, int count, int
     for (int k = lane; k < count; k += kWave) ready[base + k] = stage[k];
 }
 
+// Sources and destinations of the 64 edges [e0, e0 + cnt) of a CSR tile:
+// returns the source u0 of the first edge; lane j gets the destination of edge
+// j in `v` and its source as an offset from u0 in `my_src`.  Lane k fetches
+// the end offset of source ubase+k; an edge's source is the number of row ends
+// at or before it, found by a binary search over the 64 lane-held ends.  A
+// tile spanning more than 64 sources (long runs of sources without out-edges)
+// re-anchors with another search.
+__device__ __forceinline__ int64_t resolve_tile(const AggregateArgs &a, int64_t e0, int cnt, int lane,
+                                                int32_t &v, int &my_src) {
+    const int64_t u0 = wave_find_source(a.off, a.src_begin, a.src_end, e0, lane);
+    v = 0;
+    if (lane < cnt) v = a.col[e0 + lane - a.col_base];
+    my_src = 0;
+    bool found = lane >= cnt;
+    int64_t ubase = u0;
+    while (true) {
+        const int64_t u = ubase + lane;
+        int relend = kTileEdges;
+        if (u < a.src_end) {
+            const int64_t r = a.off[u + 1] - e0;
+            relend = r < kTileEdges ? static_cast<int>(r) : kTileEdges;
+        }
+        int lo = 0, hi = kWave;
+#pragma unroll
+        for (int it = 0; it < 7; ++it) {
+            const int mid = (lo + hi) >> 1;
+            const int r = __shfl(relend, mid & (kWave - 1));
+            const bool open = lo < hi;
+            const bool le = r <= lane;
+            if (open && le) lo = mid + 1;
+            if (open && !le) hi = mid;
+        }
+        if (!found && lo < kWave) {
+            my_src = static_cast<int>(ubase - u0) + lo;
+            found = true;
+        }
+        const uint64_t todo = __ballot(!found);
+        if (todo == 0) break;
+        const int first = __ffsll(static_cast<unsigned long long>(todo)) - 1;
+        ubase = wave_find_source(a.off, ubase, a.src_end, e0 + first, lane);
+    }
+    return u0;
+}
+
+__device__ __forceinline__ int32_t encode_max(float f) {
+    const int32_t b = __float_as_int(f);
+    return b >= 0 ? b : b ^ 0x7fffffff;
+}
+__device__ __forceinline__ float decode_max(int32_t e) { return __int_as_float(e >= 0 ? e : e ^ 0x7fffffff); }
+__device__ __forceinline__ float leaky(float s, float slope) { return s > 0.f ? s : slope * s; }
+
 template <typename T, int VPL, int MODEL>
 __global__ __launch_bounds__(kBlock) void k_aggregate(AggregateArgs a) {
     constexpr int D = VPL * kWave;
@@ -107,49 +158,14 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggregateArgs a) {
         const int64_t e0 = ebeg + t * kTileEdges;
         const int64_t left = eend - e0;
         const int cnt = left < kTileEdges ? static_cast<int>(left) : kTileEdges;
-        const int64_t u0 = wave_find_source(a.off, a.src_begin, a.src_end, e0, lane);
-
-        int32_t v = 0;
-        if (lane < cnt) v = a.col[e0 + lane - a.col_base];
-
-        // Source of every edge of the tile, as an offset from u0.  Lane k
-        // fetches the end offset of source ubase+k; an edge's source is the
-        // number of row ends at or before it, found by a binary search over
-        // the 64 lane-held ends.  A tile spanning more than 64 sources (long
-        // runs of sources without out-edges) re-anchors with another search.
-        int my_src = 0;
-        bool found = lane >= cnt;
-        int64_t ubase = u0;
-        while (true) {
-            const int64_t u = ubase + lane;
-            int relend = kTileEdges;
-            if (u < a.src_end) {
-                const int64_t r = a.off[u + 1] - e0;
-                relend = r < kTileEdges ? static_cast<int>(r) : kTileEdges;
-            }
-            int lo = 0, hi = kWave;
-#pragma unroll
-            for (int it = 0; it < 7; ++it) {
-                const int mid = (lo + hi) >> 1;
-                const int r = __shfl(relend, mid & (kWave - 1));
-                const bool open = lo < hi;
-                const bool le = r <= lane;
-                if (open && le) lo = mid + 1;
-                if (open && !le) hi = mid;
-            }
-            if (!found && lo < kWave) {
-                my_src = static_cast<int>(ubase - u0) + lo;
-                found = true;
-            }
-            const uint64_t todo = __ballot(!found);
-            if (todo == 0) break;
-            const int first = __ffsll(static_cast<unsigned long long>(todo)) - 1;
-            ubase = wave_find_source(a.off, ubase, a.src_end, e0 + first, lane);
-        }
+        int32_t v;
+        int my_src;
+        const int64_t u0 = resolve_tile(a, e0, cnt, lane, v, my_src);
 
         float x[VPL];
+        float elu[VPL];  // GAT: source attention term of the head each element belongs to
 #pragma unroll
-        for (int i = 0; i < VPL; ++i) x[i] = 0.f;
+        for (int i = 0; i < VPL; ++i) x[i] = elu[i] = 0.f;
         int uprev = -1;
         for (int j = 0; j < cnt; ++j) {
             const int so = __builtin_amdgcn_readlane(my_src, j);
@@ -165,10 +181,27 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggregateArgs a) {
                 }
 #pragma unroll
                 for (int i = 0; i < VPL; ++i) x[i] = load_as_f32(row + i * kWave) * g;
+                if (MODEL == 2) {
+#pragma unroll
+                    for (int i = 0; i < VPL; ++i) elu[i] = a.gat.el[u * a.gat.heads + (lane + i * kWave) / a.gat.dh];
+                }
             }
             float *dst = a.acc + static_cast<int64_t>(vj) * D + lane;
+            if (MODEL == 2) {
+                // weight exp(s - m_cur) <= 1: m_cur already covers every logit of this chunk
 #pragma unroll
-            for (int i = 0; i < VPL; ++i) unsafeAtomicAdd(dst + i * kWave, x[i]);
+                for (int i = 0; i < VPL; ++i) {
+                    const int c = lane + i * kWave;
+                    const int64_t vh = static_cast<int64_t>(vj) * a.gat.heads + c / a.gat.dh;
+                    const float sc = leaky(elu[i] + a.gat.er[vh], a.gat.slope);
+                    const float wgt = expf(sc - decode_max(a.gat.m_cur[vh]));
+                    unsafeAtomicAdd(dst + i * kWave, x[i] * wgt);
+                    if (c % a.gat.dh == 0) unsafeAtomicAdd(a.gat.l + vh, wgt);
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < VPL; ++i) unsafeAtomicAdd(dst + i * kWave, x[i]);
+            }
         }
 
         // One pending-count decrement per message; the message that takes the
@@ -178,6 +211,32 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggregateArgs a) {
         stage_ready(is_ready, v, stage, staged, a.ready, a.counters, lane);
     }
     drain_ready(stage, staged, a.ready, a.counters, lane);
+}
+
+// GAT, first sweep of a chunk: every edge raises m_next[v][h] to its logit.
+__global__ __launch_bounds__(kBlock) void k_gat_chunk_max(AggregateArgs a) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t wave = static_cast<int64_t>(blockIdx.x) * (kBlock / kWave) + (threadIdx.x >> 6);
+    const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (kBlock / kWave);
+    const int64_t ebeg = a.off[a.src_begin];
+    const int64_t eend = a.off[a.src_end];
+    const int64_t ntiles = (eend - ebeg + kTileEdges - 1) / kTileEdges;
+    const int H = a.gat.heads;
+    for (int64_t t = wave; t < ntiles; t += nwaves) {
+        const int64_t e0 = ebeg + t * kTileEdges;
+        const int64_t left = eend - e0;
+        const int cnt = left < kTileEdges ? static_cast<int>(left) : kTileEdges;
+        int32_t v;
+        int my_src;
+        const int64_t u0 = resolve_tile(a, e0, cnt, lane, v, my_src);
+        if (lane < cnt) {
+            const int64_t u = u0 + my_src;
+            for (int h = 0; h < H; ++h) {
+                const float sc = leaky(a.gat.el[u * H + h] + a.gat.er[static_cast<int64_t>(v) * H + h], a.gat.slope);
+                atomicMax(&a.gat.m_next[static_cast<int64_t>(v) * H + h], encode_max(sc));
+            }
+        }
+    }
 }
 
 // The self message of SAGE: every source of the chunk sends its own row to
@@ -322,11 +381,17 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
             gs = 1.0f / sqrtf(static_cast<float>(du > 0 ? du : 1));
         }
 
+        // GAT: every lane's elements belong to one head (dh is a multiple of VPL)
+        const int hl = MODEL == 2 ? (lane * VPL) / a.gat.dh : 0;
+        const bool head_first = MODEL == 2 && (lane * VPL) % a.gat.dh == 0;
+        float lsum = 0.f;
+
         float sum[VPL];
 #pragma unroll
         for (int i = 0; i < VPL; ++i) sum[i] = 0.f;
         for (int j0 = 0; j0 < cnt; j0 += U) {
             float r[U][VPL];
+            float wgt[U];
 #pragma unroll
             for (int i = 0; i < U; ++i) {
                 const int j = j0 + i < cnt ? j0 + i : cnt - 1;
@@ -337,19 +402,39 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
 #pragma unroll
                     for (int q = 0; q < VPL; ++q) r[i][q] *= g;
                 }
+                if (MODEL == 2) {
+                    // destination of edge j = the one held by the lane that closes its group
+                    const uint64_t rest = endmask >> j;
+                    const int closer = rest ? j + __ffsll(static_cast<unsigned long long>(rest)) - 1 : cnt - 1;
+                    const int64_t vh = static_cast<int64_t>(__builtin_amdgcn_readlane(dstv, closer)) * a.gat.heads + hl;
+                    const float sc = leaky(a.gat.el[static_cast<int64_t>(sj) * a.gat.heads + hl] + a.gat.er[vh], a.gat.slope);
+                    wgt[i] = expf(sc - decode_max(a.gat.m_cur[vh]));   // <= 1: m_cur covers this chunk
+                }
             }
 #pragma unroll
             for (int i = 0; i < U; ++i) {
                 const int j = j0 + i;
                 if (j < cnt) {
+                    if (MODEL == 2) {
 #pragma unroll
-                    for (int q = 0; q < VPL; ++q) sum[q] += r[i][q];
+                        for (int q = 0; q < VPL; ++q) sum[q] += wgt[i] * r[i][q];
+                        lsum += wgt[i];
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < VPL; ++q) sum[q] += r[i][q];
+                    }
                     if ((endmask >> j) & 1ull) {
                         const int32_t v = __builtin_amdgcn_readlane(dstv, j);
                         float *dst = a.acc + static_cast<int64_t>(v) * D + lane * VPL;
                         if (cut) row_add_shared<VPL>(dst, sum);
                         else row_add_owned<VPL>(dst, sum);
+                        if (MODEL == 2 && head_first) {
+                            float *lp = a.gat.l + static_cast<int64_t>(v) * a.gat.heads + hl;
+                            if (cut) unsafeAtomicAdd(lp, lsum);
+                            else *lp += lsum;
+                        }
                         cut = false;
+                        lsum = 0.f;
 #pragma unroll
                         for (int q = 0; q < VPL; ++q) sum[q] = 0.f;
                     }
@@ -359,6 +444,8 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
         if (!((endmask >> (cnt - 1)) & 1ull)) {  // open group: continues in the next tile
             const int32_t v = __builtin_amdgcn_readlane(dstv, cnt - 1);
             row_add_shared<VPL>(a.acc + static_cast<int64_t>(v) * D + lane * VPL, sum);
+            if (MODEL == 2 && head_first)
+                unsafeAtomicAdd(a.gat.l + static_cast<int64_t>(v) * a.gat.heads + hl, lsum);
         }
 
         // pending count: minus the number of this tile's messages to the group.
@@ -429,16 +516,26 @@ hipError_t launch_aggregate(const AggregateArgs &a, hipStream_t s) {
     if (a.d % kWave != 0) return hipErrorInvalidValue;
     const int grid = persistent_grid(8);
     // model 1 (GCN) scales the source row; every other model pushes it as is
+    if (a.model == 2) return a.in_bf16 ? hipErrorInvalidValue : launch_vpl<float, 2>(a, grid, s);
     if (a.in_bf16) {
         return a.model == 1 ? launch_vpl<uint16_t, 1>(a, grid, s) : launch_vpl<uint16_t, 0>(a, grid, s);
     }
     return a.model == 1 ? launch_vpl<float, 1>(a, grid, s) : launch_vpl<float, 0>(a, grid, s);
 }
 
+hipError_t launch_gat_chunk_max(const AggregateArgs &a, hipStream_t s) {
+    hipLaunchKernelGGL(k_gat_chunk_max, dim3(persistent_grid(8)), dim3(kBlock), 0, s, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_aggregate_grouped(const GroupedArgs &a, hipStream_t s) {
     if (a.d % kWave != 0) return hipErrorInvalidValue;
     if (a.n_edges <= 0) return hipSuccess;
     const int grid = persistent_grid(8);
+    if (a.model == 2) {
+        if (a.in_bf16 || a.gat.dh % (a.d / kWave) != 0) return hipErrorInvalidValue;
+        return launch_grouped_vpl<float, 2>(a, grid, s);
+    }
     if (a.in_bf16) {
         return a.model == 1 ? launch_grouped_vpl<uint16_t, 1>(a, grid, s) : launch_grouped_vpl<uint16_t, 0>(a, grid, s);
     }

@@ -180,8 +180,9 @@ __global__ __launch_bounds__(kBlock) void k_update(UpdateArgs a) {
     const int KS = K / kStepK;
     constexpr int kRows = kTileRows / 4;
 
-    const int head = a.counters[CTR_READY_HEAD];
-    const int tail = a.counters[CTR_READY_TAIL];
+    const bool dense = a.identity_rows > 0;
+    const int head = dense ? 0 : a.counters[CTR_READY_HEAD];
+    const int tail = dense ? static_cast<int>(a.identity_rows) : a.counters[CTR_READY_TAIL];
     const int ntiles = (tail - head + kTileRows - 1) / kTileRows;
 
     for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
@@ -192,11 +193,12 @@ __global__ __launch_bounds__(kBlock) void k_update(UpdateArgs a) {
         if (lane < kRows) {
             const int idx = head + tile * kTileRows + w * kRows + lane;
             if (idx < tail) {
-                idv = a.ready[idx];
-                const int32_t deg = a.indeg[idv];
+                idv = dense ? idx : a.ready[idx];
+                const int32_t deg = a.indeg ? a.indeg[idv] : 1;
                 const float fd = static_cast<float>(deg > 0 ? deg : 1);
-                // SAGE divides the sum by the in-degree; GCN multiplies by deg^-1/2
-                scalev = a.model == 0 ? fd : 1.0f / sqrtf(fd);
+                // SAGE divides the sum by the in-degree; GCN multiplies by deg^-1/2;
+                // a plain linear map (model 2) leaves the row as it is
+                scalev = a.model == 0 ? fd : (a.model == 1 ? 1.0f / sqrtf(fd) : 1.0f);
             }
             ids[w * kRows + lane] = idv;
         }
@@ -292,7 +294,7 @@ __device__ __forceinline__ void pipe_issue_rows(const UpdateArgs &a, int32_t idv
                                                 int32_t &degv) {
     const int d = a.d_in;
     const int col = lane * 2 < d ? lane * 2 : 0;
-    degv = a.indeg[idv >= 0 ? idv : 0];
+    degv = a.indeg ? a.indeg[idv >= 0 ? idv : 0] : 1;
 #pragma unroll
     for (int i = 0; i < kPipeRows; ++i) {
         const int32_t id = __builtin_amdgcn_readlane(idv, i);
@@ -310,7 +312,7 @@ __device__ __forceinline__ void pipe_store_rows(const UpdateArgs &a, typename El
     const int col = lane * 2;
     const float fd = static_cast<float>(degv > 0 ? degv : 1);
     // SAGE divides the sum by the in-degree; GCN multiplies by deg^-1/2
-    const float scalev = a.model == 0 ? fd : 1.0f / sqrtf(fd);
+    const float scalev = a.model == 0 ? fd : (a.model == 1 ? 1.0f / sqrtf(fd) : 1.0f);
     if (col >= d) return;
 #pragma unroll
     for (int i = 0; i < kPipeRows; ++i) {
@@ -348,8 +350,9 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
 
-    const int head = a.counters[CTR_READY_HEAD];
-    const int tail = a.counters[CTR_READY_TAIL];
+    const bool dense = a.identity_rows > 0;
+    const int head = dense ? 0 : a.counters[CTR_READY_HEAD];
+    const int tail = dense ? static_cast<int>(a.identity_rows) : a.counters[CTR_READY_TAIL];
     const int ntiles = (tail - head + kTileRows - 1) / kTileRows;
     if (static_cast<int>(blockIdx.x) >= ntiles) return;
 
@@ -364,7 +367,7 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
         int32_t id = -1;
         if (tile < ntiles && lane < kPipeRows) {
             const int idx = head + tile * kTileRows + w * kPipeRows + lane;
-            if (idx < tail) id = a.ready[idx];
+            if (idx < tail) id = dense ? idx : a.ready[idx];
         }
         return id;
     };

@@ -87,3 +87,31 @@ def test_sage_degree_ordered_bf16_d128(oracle, H, plan):
     print("sage s14 degree ordered", H.check_outputs(oracle, case, run))
     for st in run.stats:
         assert st["edges_processed"] == case.e and st["vertices_flushed"] == case.n
+
+
+@pytest.mark.parametrize("plan", [False, True], ids=["csr_stream", "planned"])
+def test_gat_rmat_fp32(oracle, H, plan):
+    """Config-4 shape at scale 13: GAT 128 -> 4x32 -> 4x32, LeakyReLU 0.2, ELU
+    between layers, running softmax over 16 chunks; about half the vertices
+    have no in-edge and are complete at layer start."""
+    g = gen.rmat_graph(SEED + 4, 13, 16)
+    case = H.make_case("gat", g, SEED + 4, [128, 128, 128], 1 << 9, feat="normal", act="elu", heads=4)
+    run = H.run_gpu(case, snapshots=True, plan=plan)
+    H.check_integers(oracle, case, run, layer=0)
+    H.check_integers(oracle, case, run, layer=1)
+    print("gat", H.check_outputs(oracle, case, run))
+
+
+@pytest.mark.parametrize("plan", [False, True], ids=["csr_stream", "planned"])
+def test_gat_wide_logit_range(oracle, H, plan):
+    """Attention vectors scaled up so that logits span roughly +-80: the
+    running maximum must keep every weight <= 1 and nothing may overflow."""
+    g = gen.rmat_graph(SEED + 14, 11, 16)
+    case = H.make_case("gat", g, SEED + 14, [64, 64], 200, feat="normal", act="elu", heads=2)
+    p = case.layers[0]
+    p.attn_src = (p.attn_src * 12.0).float().double()
+    p.attn_dst = (p.attn_dst * 12.0).float().double()
+    run = H.run_gpu(case, plan=plan)
+    out = run.outputs[0].cpu().numpy()
+    assert np.isfinite(out).all()
+    print("gat wide", H.check_outputs(oracle, case, run))
