@@ -223,3 +223,93 @@ def case_from_edges(model: str, n: int, src, dst, seed: int, dims: List[int], ch
     dst = torch.as_tensor(dst, dtype=torch.int64)
     g = gen.EdgeSource(n, 1, lambda k: (src, dst))
     return make_case(model, g, seed, dims, chunk, feat, store, act, heads)
+
+
+# --------------------------------------------------------------------------
+# full-size workloads: device-resident run + sampled oracle check of layer 1
+# --------------------------------------------------------------------------
+
+def gpu_reorder(off, col):
+    """In-degree-descending permutation from the library (new_of_old, int32, device)."""
+    dev = off.device
+    n = off.numel() - 1
+    indeg = torch.empty(n, dtype=torch.int32, device=dev)
+    atlas.atlas_in_degree(atlas.make_graph(n, col.numel(), off, col), indeg)
+    new_of_old = torch.empty(n, dtype=torch.int32, device=dev)
+    old_of_new = torch.empty(n, dtype=torch.int32, device=dev)
+    atlas.atlas_reorder_indegree_desc(atlas.make_graph(n, col.numel(), off, col, indeg), new_of_old, old_of_new)
+    return new_of_old
+
+
+def run_workload_layer1(wl, plan: bool, emb_resident: bool = False):
+    """Layer 1 of a device-resident workload through the C ABI, flush after
+    every chunk.  Returns (out, stats, indeg, final pending, ready list)."""
+    dev = wl.off.device
+    n, e = wl.n, wl.e
+    indeg = torch.empty(n, dtype=torch.int32, device=dev)
+    atlas.atlas_in_degree(atlas.make_graph(n, e, wl.off, wl.col), indeg)
+    plan_h = atlas.atlas_plan_create(atlas.make_graph(n, e, wl.off, wl.col), wl.chunk) if plan else None
+    graph = atlas.make_graph(n, e, wl.off, wl.col, indeg, atlas.RESIDENT_DEVICE, plan_h)
+    sdt = _dt(wl.store)
+    p = wl.layers[0]
+    W = p.W.to(wl.store).to(dev).contiguous()
+    b = p.bias.to(wl.store).to(dev).contiguous()
+    a_s = None if p.attn_src is None else p.attn_src.to(wl.store).to(dev).contiguous()
+    a_d = None if p.attn_dst is None else p.attn_dst.to(wl.store).to(dev).contiguous()
+    act = {"relu": atlas.ACT_RELU, "elu": atlas.ACT_ELU}[wl.act] if len(wl.layers) > 1 else atlas.ACT_NONE
+    dims = atlas.make_dims(MODEL_ID[wl.model], wl.dims[0], wl.dims[1], sdt, sdt, act, wl.chunk, heads=wl.heads,
+                           flags=atlas.FLAG_EMB_RESIDENT if emb_resident else 0)
+    h = atlas.atlas_layer_init(graph, dims, atlas.make_weights(W, b, sdt, a_s, a_d))
+    out = torch.full((n, wl.dims[1]), float("nan"), dtype=wl.store, device=dev)
+    if wl.model == "gat":
+        for b0 in range(0, n, wl.chunk):
+            atlas.atlas_attention_prepass(h, b0, min(n, b0 + wl.chunk), wl.X[b0:b0 + wl.chunk])
+    atlas.atlas_flush_ready(h, out)
+    for b0 in range(0, n, wl.chunk):
+        b1 = min(n, b0 + wl.chunk)
+        atlas.atlas_broadcast_chunk(h, b0, b1, wl.X[b0:b1])
+        atlas.atlas_flush_ready(h, out)
+    pend = np.empty(n, dtype=np.int32)
+    atlas.atlas_debug_copy(h, atlas.DBG_PENDING, pend)
+    ready = np.empty(n, dtype=np.int32)
+    atlas.atlas_debug_copy(h, atlas.DBG_READY, ready)
+    stats = atlas.atlas_layer_finish(h)
+    if plan_h is not None:
+        atlas.atlas_plan_destroy(plan_h)
+    return out, stats, indeg, pend, ready
+
+
+def sampled_layer1_check(oracle, wl, out, indeg_dev, n_random: int = 1 << 14, n_top: int = 1024, seed: int = 7):
+    """Oracle layer 1 on a sample of destinations (random + highest in-degree)
+    with all their in-edges; also pins the library's in-degree on the sample."""
+    dev = wl.off.device
+    n = wl.n
+    g = torch.Generator().manual_seed(seed)
+    pick = torch.randperm(n, generator=g)[:n_random].to(dev)
+    top = torch.topk(indeg_dev.to(torch.int64), min(n_top, n)).indices
+    pick = torch.unique(torch.cat([pick, top]))
+    in_off, in_src = gen.in_edges_of(wl.off, wl.col, pick)
+    need = torch.unique(torch.cat([in_src.to(torch.int64), pick]))
+    remap = torch.full((n,), -1, dtype=torch.int64, device=dev)
+    remap[need] = torch.arange(need.numel(), device=dev)
+    Xs = wl.X[need].float().cpu().numpy()
+    in_off_h = in_off.cpu().numpy()
+    il = oracle.InLists(in_off_h, remap[in_src.to(torch.int64)].to(torch.int32).cpu().numpy(), remap[pick].cpu().numpy())
+    assert np.array_equal(indeg_dev[pick].cpu().numpy().astype(np.int64), np.diff(in_off_h)), "in-degree of the sample"
+    p = wl.layers[0]
+    act = ORACLE_ACT[wl.act] if len(wl.layers) > 1 else 0
+    fmt = oracle.FMT_BF16 if wl.store == torch.bfloat16 else oracle.FMT_F32
+    Y = oracle.run_layer(wl.model, il, indeg_dev[need].cpu().numpy().astype(np.int64), Xs, p, act, fmt)
+    got = out[pick].float().cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    err = row_rel_err(got, Y)
+    tol = TOL_BF16 if wl.store == torch.bfloat16 else TOL_F32
+    assert err <= tol, "sampled layer-1 error %.3e > %.1e" % (err, tol)
+    return err, int(pick.numel()), int(in_src.numel())
+
+
+def check_layer_counters(wl, stats, pend, ready):
+    assert stats["edges_processed"] == wl.e and stats["vertices_flushed"] == wl.n
+    assert stats["vertices_completed"] == wl.n and stats["sources_processed"] == wl.n
+    assert not pend.any(), "pending counts must all reach zero"
+    assert np.array_equal(np.sort(ready), np.arange(wl.n, dtype=np.int32)), "ready list is a permutation"
