@@ -41,6 +41,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-e2e", action="store_true", help="skip the three-layer end-to-end run")
     ap.add_argument("--sample-dst", type=int, default=1 << 16, help="destinations in the oracle sample")
+    ap.add_argument("--chunk-log2", type=int, default=None, help="chunk size in sources (default N/16)")
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="also run a plain 4 GiB device copy three times (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (no collectives or sharding here)",
@@ -71,7 +74,8 @@ def main() -> int:
         return new_of_old
 
     t0 = time.time()
-    wl = workloads.config5(dev, scale=args.scale, reorder=reorder, edge_factor=args.edge_factor)
+    wl = workloads.config5(dev, scale=args.scale, reorder=reorder, edge_factor=args.edge_factor,
+                           chunk=None if args.chunk_log2 is None else 1 << args.chunk_log2)
     torch.cuda.synchronize()
     n, e, chunk = wl.n, wl.e, wl.chunk
     log("generated %s: N=%d E=%d chunk=%d in %.1f s" % (wl.name, n, e, chunk, time.time() - t0))
@@ -108,6 +112,15 @@ def main() -> int:
             atlas.atlas_broadcast_chunk(h, b0, b1, x[b0:b1], stream)
             atlas.atlas_flush_ready(h, out, stream)
         return atlas.atlas_layer_finish(h)
+
+    if args.traffic_calibration:
+        # a plain copy of known size: 4 GiB read + 4 GiB written per launch
+        ca = torch.empty(1 << 30, dtype=torch.int32, device=dev)
+        cb = torch.empty_like(ca)
+        for _ in range(3):
+            cb.copy_(ca)
+        torch.cuda.synchronize()
+        del ca, cb
 
     # ---- warm-up, then exactly K timed steps ----
     for _ in range(args.warmup):

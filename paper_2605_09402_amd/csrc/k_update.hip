@@ -74,10 +74,53 @@ __global__ __launch_bounds__(kBlock) void k_pack_weights(const void *W, int w_bf
     packed[i] = to_elem<BF16C>(w);
 }
 
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+// two fp32 -> packed bf16x2 (round to nearest even, one hardware instruction)
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    const f32x2_t v = {lo, hi};
+    const bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
+    return *reinterpret_cast<const uint32_t *>(&b);
+}
+
 __device__ __forceinline__ float apply_activation(float y, int act) {
     if (act == 1) return y > 0.f ? y : 0.f;
     if (act == 2) return y > 0.f ? y : expm1f(y);
     return y;
+}
+
+// Epilogue of one 32x32 block computed as D^T (W fragment as the first MFMA
+// operand): lane l then holds, for tile row l%32, the sixteen output columns
+// nbase + 8q + t (q, t < 4) with nbase = 32 nb + 4 (l/32) -- four runs of four
+// consecutive columns, written as 8-byte (bf16) or 16-byte (fp32) stores.
+__device__ __forceinline__ void store_block_row(const UpdateArgs &a, const f32x16_t &c, int64_t out_row,
+                                                int nbase, const float (&bias16)[16]) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int n = nbase + 8 * q;
+        if (n >= a.d_out) continue;
+        float y[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) y[t] = apply_activation(c[4 * q + t] + bias16[4 * q + t], a.activation);
+        const int64_t o = out_row * a.d_out + n;
+        if (a.out_bf16) {
+            const uint2 v = make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
+            *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(a.out) + o) = v;
+        } else {
+            *reinterpret_cast<float4 *>(static_cast<float *>(a.out) + o) = make_float4(y[0], y[1], y[2], y[3]);
+        }
+    }
+}
+
+__device__ __forceinline__ void load_bias16(const UpdateArgs &a, int nbase, float (&bias16)[16]) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int n = nbase + 8 * q + t;
+            bias16[4 * q + t] = (a.bias && n < a.d_out) ? a.bias[n] : 0.f;
+        }
 }
 
 // Stage 128 columns of 16 rows per pass.  Every load of a pass is issued
@@ -228,7 +271,7 @@ __global__ __launch_bounds__(kBlock) void k_update(UpdateArgs a) {
                             static_cast<const uint16_t *>(a.packed_w) + ((static_cast<int64_t>(nb) * KS + kk) * 64 + lane) * 8);
                         last_nb = nb;
                     }
-                    c[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, c[i], 0, 0, 0);
+                    c[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv, av, c[i], 0, 0, 0);   // D^T block
                 }
             } else {
                 float bv = 0.f;
@@ -242,7 +285,7 @@ __global__ __launch_bounds__(kBlock) void k_update(UpdateArgs a) {
                         bv = static_cast<const float *>(a.packed_w)[(static_cast<int64_t>(nb) * KS + kk) * 64 + lane];
                         last_nb = nb;
                     }
-                    c[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, c[i], 0, 0, 0);
+                    c[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av, c[i], 0, 0, 0);
                 }
             }
         }
@@ -253,19 +296,11 @@ __global__ __launch_bounds__(kBlock) void k_update(UpdateArgs a) {
             const int p = w + 4 * i;
             if (p >= 2 * NB) continue;
             const int nb = p % NB, mb = p / NB;
-            const int j = nb * 32 + (lane & 31);
-            if (j >= a.d_out) continue;
-            const float bj = a.bias ? a.bias[j] : 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = mb * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                const int32_t id = ids[row];
-                if (id < 0) continue;
-                const float y = apply_activation(c[i][r] + bj, a.activation);
-                const int64_t o = static_cast<int64_t>(id) * a.d_out + j;
-                if (a.out_bf16) static_cast<uint16_t *>(a.out)[o] = f32_to_bf16_rne(y);
-                else static_cast<float *>(a.out)[o] = y;
-            }
+            const int32_t id = ids[mb * 32 + (lane & 31)];
+            if (id < 0) continue;
+            float bias16[16];
+            load_bias16(a, nb * 32 + 4 * (lane >> 5), bias16);
+            store_block_row(a, c[i], id, nb * 32 + 4 * (lane >> 5), bias16);
         }
     }
 }
@@ -311,24 +346,27 @@ __device__ __forceinline__ void pipe_store_rows(const UpdateArgs &a, typename El
     const int d = a.d_in;
     const int col = lane * 2;
     const float fd = static_cast<float>(degv > 0 ? degv : 1);
-    // SAGE divides the sum by the in-degree; GCN multiplies by deg^-1/2
-    const float scalev = a.model == 0 ? fd : (a.model == 1 ? 1.0f / sqrtf(fd) : 1.0f);
+    // SAGE: mean = sum * (1/deg); GCN: deg^-1/2; plain linear map: 1
+    const float scalev = a.model == 0 ? 1.0f / fd : (a.model == 1 ? 1.0f / sqrtf(fd) : 1.0f);
     if (col >= d) return;
 #pragma unroll
     for (int i = 0; i < kPipeRows; ++i) {
         const float g = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(scalev), i));
         const bool live = __builtin_amdgcn_readlane(idv, i) >= 0;
         typename Elem<BF16C>::type *row = A + (w * kPipeRows + i) * stride;
-        const float ax = live ? r.acc[i].x : 0.f, ay = live ? r.acc[i].y : 0.f;
-        if (a.model == 0) {
-            const float2 f = own_to_f32(r.own[i]);
-            row[col] = to_elem<BF16C>(live ? f.x : 0.f);
-            row[col + 1] = to_elem<BF16C>(live ? f.y : 0.f);
-            row[d + col] = to_elem<BF16C>(ax / g);
-            row[d + col + 1] = to_elem<BF16C>(ay / g);
+        const float ax = live ? r.acc[i].x * g : 0.f, ay = live ? r.acc[i].y * g : 0.f;
+        const int acc_col = a.model == 0 ? d + col : col;
+        if constexpr (BF16C) {
+            // bf16 own rows go to LDS as they were loaded; the aggregate is rounded once
+            if (a.model == 0) *reinterpret_cast<uint32_t *>(row + col) = live ? r.own[i] : 0u;
+            *reinterpret_cast<uint32_t *>(row + acc_col) = pack_bf16x2(ax, ay);
         } else {
-            row[col] = to_elem<BF16C>(ax * g);
-            row[col + 1] = to_elem<BF16C>(ay * g);
+            if (a.model == 0) {
+                row[col] = live ? r.own[i].x : 0.f;
+                row[col + 1] = live ? r.own[i].y : 0.f;
+            }
+            row[acc_col] = ax;
+            row[acc_col + 1] = ay;
         }
     }
 }
@@ -372,30 +410,30 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
         return id;
     };
 
-    float bj[PPW];
+    float bj[PPW][16];
 #pragma unroll
-    for (int i = 0; i < PPW; ++i) {
-        const int j = ((w + 8 * i) % NB) * 32 + (lane & 31);
-        bj[i] = (a.bias && j < a.d_out) ? a.bias[j] : 0.f;
-    }
+    for (int i = 0; i < PPW; ++i) load_bias16(a, ((w + 8 * i) % NB) * 32 + 4 * (lane >> 5), bj[i]);
 
+    // Two tiles of rows are in flight in registers (r0: this workgroup's next
+    // tile, r1: the one after it) and the ready ids of the tile after those are
+    // on their way; every step stores one register set to LDS, refills it with
+    // the tile two steps ahead and runs the contraction of the stored tile.
     int tile = blockIdx.x;
-    int32_t idv = load_ids(tile);
-    int32_t idv_next = load_ids(tile + gridDim.x);
-    RowRegs<BF16C> regs;
-    int32_t degv;
-    pipe_issue_rows<BF16C>(a, idv, lane, regs, degv);
+    const int G = gridDim.x;
+    int32_t id0 = load_ids(tile), id1 = load_ids(tile + G), id_ahead = load_ids(tile + 2 * G);
+    RowRegs<BF16C> r0, r1;
+    int32_t deg0, deg1;
+    pipe_issue_rows<BF16C>(a, id0, lane, r0, deg0);
+    pipe_issue_rows<BF16C>(a, id1, lane, r1, deg1);
 
-    for (int it = 0; tile < ntiles; tile += gridDim.x, ++it) {
-        const int buf = it & 1;
+    auto step = [&](RowRegs<BF16C> &regs, int32_t &idv, int32_t &degv, int buf) {
         elem_t *A = A0 + buf * a_elems;
         int32_t *tids = ids + buf * kTileRows;
         pipe_store_rows<BF16C>(a, A, stride, w, lane, regs, idv, degv);
         if (lane < kPipeRows) tids[w * kPipeRows + lane] = idv;
         __syncthreads();
-        // rows of the next tile and ids of the one after it go in flight now
-        idv = idv_next;
-        idv_next = load_ids(tile + 2 * gridDim.x);
+        idv = id_ahead;
+        id_ahead = load_ids(tile + 3 * G);
         pipe_issue_rows<BF16C>(a, idv, lane, regs, degv);
 
         f32x16_t c[PPW];
@@ -414,11 +452,11 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
                         A + (mb * 32 + (lane & 31)) * stride + kk * 16 + (lane >> 5) * 8);
                     const bf16x8_t bv = *reinterpret_cast<const bf16x8_t *>(
                         Wl + ((static_cast<size_t>(nb) * KS + kk) * 64 + lane) * 8);
-                    c[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, c[i], 0, 0, 0);
+                    c[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv, av, c[i], 0, 0, 0);   // D^T block
                 } else {
                     const float av = A[(mb * 32 + (lane & 31)) * stride + kk * 2 + (lane >> 5)];
                     const float bv = Wl[(static_cast<size_t>(nb) * KS + kk) * 64 + lane];
-                    c[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, c[i], 0, 0, 0);
+                    c[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av, c[i], 0, 0, 0);
                 }
             }
         }
@@ -427,19 +465,18 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
             const int p = w + 8 * i;
             if (p >= 2 * NB) continue;
             const int nb = p % NB, mb = p / NB;
-            const int j = nb * 32 + (lane & 31);
-            if (j >= a.d_out) continue;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = mb * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                const int32_t id = tids[row];
-                if (id < 0) continue;
-                const float y = apply_activation(c[i][r] + bj[i], a.activation);
-                const int64_t o = static_cast<int64_t>(id) * a.d_out + j;
-                if (a.out_bf16) static_cast<uint16_t *>(a.out)[o] = f32_to_bf16_rne(y);
-                else static_cast<float *>(a.out)[o] = y;
-            }
+            const int32_t id = tids[mb * 32 + (lane & 31)];
+            if (id >= 0) store_block_row(a, c[i], id, nb * 32 + 4 * (lane >> 5), bj[i]);
         }
+    };
+
+    while (true) {
+        step(r0, id0, deg0, 0);
+        tile += G;
+        if (tile >= ntiles) break;
+        step(r1, id1, deg1, 1);
+        tile += G;
+        if (tile >= ntiles) break;
     }
 }
 
