@@ -41,6 +41,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-e2e", action="store_true", help="skip the three-layer end-to-end run")
     ap.add_argument("--sample-dst", type=int, default=1 << 16, help="destinations in the oracle sample")
+    ap.add_argument("--residency", choices=["device", "pinned"], default="device",
+                    help="pinned: graph and features stay in pinned host memory and are streamed per chunk "
+                         "(host-link bound; reported for the record, never the headline value)")
     ap.add_argument("--chunk-log2", type=int, default=None, help="chunk size in sources (default N/16)")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run a plain 4 GiB device copy three times (reference for HBM byte counters)")
@@ -86,12 +89,20 @@ def main() -> int:
 
     plan = None
     plan_ms = None
-    if not args.no_plan:
+    if not args.no_plan and args.residency == "device":
         t0 = time.time()
         plan = atlas.atlas_plan_create(atlas.make_graph(n, e, wl.off, wl.col), chunk)
         plan_ms = (time.time() - t0) * 1e3
         log("plan built in %.1f ms" % plan_ms)
     graph = atlas.make_graph(n, e, wl.off, wl.col, indeg, atlas.RESIDENT_DEVICE, plan)
+    x_layer0 = wl.X
+    if args.residency == "pinned":
+        t0 = time.time()
+        off_h = torch.empty(wl.off.shape, dtype=wl.off.dtype, pin_memory=True).copy_(wl.off)
+        col_h = torch.empty(wl.col.shape, dtype=wl.col.dtype, pin_memory=True).copy_(wl.col)
+        x_layer0 = torch.empty(wl.X.shape, dtype=wl.X.dtype, pin_memory=True).copy_(wl.X)
+        graph = atlas.make_graph(n, e, off_h, col_h, indeg, atlas.RESIDENT_PINNED_HOST, None)
+        log("pinned host copies made in %.1f s" % (time.time() - t0))
 
     params = []
     for p in wl.layers:
@@ -124,13 +135,16 @@ def main() -> int:
 
     # ---- warm-up, then exactly K timed steps ----
     for _ in range(args.warmup):
-        run_layer(0, wl.X, True)
+        run_layer(0, x_layer0, True)
     torch.cuda.synchronize()
-    agg_ms = upd_ms = self_ms = init_ms = 0.0
+    agg_ms = upd_ms = self_ms = init_ms = copy_ms = 0.0
+    h2d_bytes = 0
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        st = run_layer(0, wl.X, True)
+        st = run_layer(0, x_layer0, True)
         agg_ms += st["ms_aggregate"]
+        copy_ms += st["ms_copy"]
+        h2d_bytes = st["bytes_copied_h2d"]
         upd_ms += st["ms_update"]
         self_ms += st["ms_self"]
         init_ms += st["ms_init"]
@@ -145,7 +159,7 @@ def main() -> int:
     # ---- end-to-end: all three layers once ----
     e2e_ms = None
     layer_ms = []
-    if not args.no_e2e:
+    if not args.no_e2e and args.residency == "device":
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         x = wl.X
@@ -168,10 +182,21 @@ def main() -> int:
     peak = 8000.0
     # bytes the regrouped kernel itself must move (source id + bf16 source row per edge)
     kernel_bytes_per_edge = 4 + d * 2
+    # HBM bytes per launch from the committed counter summary; null when the
+    # kernels changed after the counters were taken (or for another workload)
+    traffic = None
+    kname = "k_aggregate_grouped" if plan else "k_aggregate"
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_config5_rmat26.json")
+    if os.path.exists(tpath) and args.scale == 26 and args.edge_factor == 32 and args.chunk_log2 is None:
+        from paper_2605_09402_amd.profile_summary import kernel_source_hash
+        doc = json.load(open(tpath))
+        if doc.get("kernel_source_hash") == kernel_source_hash() and kname in doc["kernels"]:
+            traffic = doc["kernels"][kname]["bytes_per_launch"]
     roofline = {
-        "bound": "hbm", "kernel": "k_aggregate_grouped" if plan else "k_aggregate",
+        "bound": "hbm", "kernel": kname,
         "achieved": round(achieved, 1), "peak": peak, "unit": "GB/s", "frac": round(achieved / peak, 4),
-        "traffic": None,
+        "traffic": traffic,
+        "traffic_GBps": None if traffic is None else round(traffic * nchunks / agg_s_per_layer / 1e9, 1),
         "launches": launches, "avg_launch_ms": round(agg_ms / launches, 4),
         "algorithmic_bytes_per_edge": bytes_per_edge, "algorithmic_bytes_per_source": bytes_per_source,
         "edges_per_s_in_kernel": round(e / agg_s_per_layer, 1),
@@ -209,7 +234,7 @@ def main() -> int:
         t_or = time.perf_counter() - t1
         sample_edges = int(in_src.numel())
         # sampled parity of the timed configuration, on the way
-        run_layer(0, wl.X, False)
+        run_layer(0, x_layer0, False)
         got = outs[0][pick.to(dev)].float().cpu().numpy().astype(np.float64)
         rn = np.maximum(np.abs(Y).max(axis=1), 1e-6 * np.abs(Y).max())
         err = float((np.abs(got - Y).max(axis=1) / rn).max())
@@ -232,6 +257,9 @@ def main() -> int:
         "config": {"workload": wl.name, "vertices": n, "edges": e, "d_in": d, "d_out": wl.dims[1],
                    "chunk_sources": chunk, "chunks": nchunks, "flush": "after every chunk",
                    "ids": "in-degree descending", "in_degree": "precomputed once per graph",
+                   "residency": "HBM" if args.residency == "device" else
+                   "pinned host, staged per chunk on a copy stream (%.2f GB, copies %.1f ms per layer)"
+                   % (h2d_bytes / 1e9, copy_ms / args.steps),
                    "edge_order": "per-chunk destination-grouped plan" if plan else "CSR stream (atomics)",
                    "plan_build_ms": None if plan_ms is None else round(plan_ms, 1)},
         "layer_ms": {"aggregate": round(agg_ms / args.steps, 3), "update": round(upd_ms / args.steps, 3),
