@@ -101,7 +101,11 @@ def main() -> int:
         off_h = torch.empty(wl.off.shape, dtype=wl.off.dtype, pin_memory=True).copy_(wl.off)
         col_h = torch.empty(wl.col.shape, dtype=wl.col.dtype, pin_memory=True).copy_(wl.col)
         x_layer0 = torch.empty(wl.X.shape, dtype=wl.X.dtype, pin_memory=True).copy_(wl.X)
-        graph = atlas.make_graph(n, e, off_h, col_h, indeg, atlas.RESIDENT_PINNED_HOST, None)
+        if not args.no_plan:
+            t1 = time.time()
+            plan = atlas.atlas_plan_create(atlas.make_graph(n, e, off_h, col_h, None, atlas.RESIDENT_PINNED_HOST), chunk)
+            plan_ms = (time.time() - t1) * 1e3
+        graph = atlas.make_graph(n, e, off_h, col_h, indeg, atlas.RESIDENT_PINNED_HOST, plan)
         log("pinned host copies made in %.1f s" % (time.time() - t0))
 
     params = []

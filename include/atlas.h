@@ -182,9 +182,12 @@ int atlas_layer_finish(atlas_layer_t *layer, atlas_layer_stats_t *stats);
  * (same sums up to fp32 rounding order, same counts, same ready sets).
  * atlas_broadcast_chunk uses the plan for chunks that coincide with a planned
  * chunk and falls back to the CSR stream for any other range.
- * DEVICE graphs only (E_BAD_DIMS otherwise).  Synchronous.  The plan holds
- * about 4 bytes per edge of device memory and must outlive the layers that
- * use it.  graph->plan and graph->in_degree are ignored here. */
+ * Synchronous.  The plan holds about 4 bytes per edge and lives where the graph
+ * lives: device memory for DEVICE graphs; library-owned pinned host memory for
+ * PINNED_HOST graphs (each chunk's CSR slice is staged into HBM, regrouped
+ * there and brought back; atlas_broadcast_chunk then streams the regrouped
+ * chunk instead of the CSR slice).  It must outlive the layers that use it.
+ * graph->plan and graph->in_degree are ignored here. */
 int atlas_plan_create(const atlas_graph_t *graph, int64_t chunk_sources, atlas_plan_t **out);
 int atlas_plan_destroy(atlas_plan_t *plan);
 

@@ -74,15 +74,39 @@ struct Buf {
 
 size_t dtype_size(int dt) { return dt == ATLAS_DTYPE_BF16 ? 2 : 4; }
 
+// The chunk loader's copy stream is created once per process and shared by
+// all layers: HIP spreads streams over a few hardware queues, and a stream
+// created anew for every layer can land on the queue that carries the caller's
+// kernels, which silently serialises the copies with them.
+hipStream_t g_copy_stream = nullptr;
+hipError_t loader_stream(hipStream_t *out) {
+    std::lock_guard<std::mutex> lk(g_cache_mu);
+    if (!g_copy_stream) {
+        hipError_t e = hipStreamCreateWithFlags(&g_copy_stream, hipStreamNonBlocking);
+        if (e != hipSuccess) return e;
+    }
+    *out = g_copy_stream;
+    return hipSuccess;
+}
+
 struct TimedSpan { hipEvent_t a, b; };
 
 }  // namespace
 
 struct atlas_plan {
     int64_t n = 0, e = 0, chunk = 0;
+    bool host = false;              // arrays live in pinned host memory (plan of a PINNED_HOST graph)
     int32_t *src_sorted = nullptr;  // [E] destination-ordered source ids of all chunks
-    std::vector<PlanChunk> chunks;
+    std::vector<PlanChunk> chunks;  // grp_dst / tile_grp: device, or pinned host when `host`
+    size_t max_stage_bytes = 0;     // host plans: largest staging slot any chunk needs
 };
+
+namespace {
+size_t stage_bytes_of(const PlanChunk &c) {
+    return round_up(static_cast<size_t>(c.n_edges) * 4, 256) + round_up(static_cast<size_t>(c.n_groups) * 4, 256) +
+           round_up(static_cast<size_t>((c.n_edges + 63) / 64) * 4, 256);
+}
+}  // namespace
 
 struct atlas_layer {
     atlas_graph_t g{};
@@ -129,7 +153,6 @@ struct atlas_layer {
             if (slot_loaded[i]) (void)hipEventDestroy(slot_loaded[i]);
             if (slot_free[i]) (void)hipEventDestroy(slot_free[i]);
         }
-        if (copy_stream) (void)hipStreamDestroy(copy_stream);
     }
 };
 
@@ -207,7 +230,7 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
                                hipMemcpyHostToDevice, s));
         L->off_dev = static_cast<const int64_t *>(L->dev_off.p);
         L->bytes_h2d += (n + 1) * static_cast<int64_t>(sizeof(int64_t));
-        HIP_TRY(hipStreamCreateWithFlags(&L->copy_stream, hipStreamNonBlocking));
+        HIP_TRY(loader_stream(&L->copy_stream));
         for (int i = 0; i < 2; ++i) {
             HIP_TRY(hipEventCreateWithFlags(&L->slot_loaded[i], hipEventDisableTiming));
             HIP_TRY(hipEventCreateWithFlags(&L->slot_free[i], hipEventDisableTiming));
@@ -219,8 +242,10 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
             const int64_t e = std::min(n, b + C);
             max_edges = std::max(max_edges, L->g.row_offsets[e] - L->g.row_offsets[b]);
         }
+        size_t slot_bytes = static_cast<size_t>(std::max<int64_t>(max_edges, 1)) * sizeof(int32_t);
+        if (L->g.plan && L->g.plan->host) slot_bytes = std::max(slot_bytes, L->g.plan->max_stage_bytes);
         for (int i = 0; i < 2; ++i) {
-            HIP_TRY(L->stage_col[i].alloc(static_cast<size_t>(std::max<int64_t>(max_edges, 1)) * sizeof(int32_t)));
+            HIP_TRY(L->stage_col[i].alloc(slot_bytes));
             if (d.model != ATLAS_MODEL_SAGE_MEAN)
                 HIP_TRY(L->stage_emb[i].alloc(static_cast<size_t>(std::min(C, std::max<int64_t>(n, 1))) * d.d_in *
                                               dtype_size(d.in_dtype)));
@@ -371,6 +396,15 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
     char *self_dst = d.model == ATLAS_MODEL_SAGE_MEAN && !L->emb_resident
                          ? static_cast<char *>(L->self_rows.p) + static_cast<size_t>(src_begin) * row_bytes
                          : nullptr;
+    // a chunk that coincides with a planned chunk runs from its destination-ordered edges
+    const atlas_plan *plan = L->g.plan;
+    if (plan && plan->host != (L->g.residency == ATLAS_RESIDENT_PINNED_HOST)) plan = nullptr;
+    const PlanChunk *pc = nullptr;
+    if (plan && plan->chunk > 0 && src_begin % plan->chunk == 0 &&
+        src_end == std::min(L->n, src_begin + plan->chunk))
+        pc = &plan->chunks[static_cast<size_t>(src_begin / plan->chunk)];
+    GroupedArgs ga{};
+
     int slot = -1;
     if (L->g.residency == ATLAS_RESIDENT_PINNED_HOST) {
         // Stage the chunk into HBM on the copy stream; the compute stream only
@@ -378,7 +412,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         // the next call) overlaps the kernels of chunk k.
         slot = static_cast<int>(L->num_chunks & 1);
         const int64_t e0 = L->g.row_offsets[src_begin], e1 = L->g.row_offsets[src_end];
-        const size_t col_bytes = static_cast<size_t>(e1 - e0) * sizeof(int32_t);
+        const size_t col_bytes = pc ? stage_bytes_of(*pc) : static_cast<size_t>(e1 - e0) * sizeof(int32_t);
         if (col_bytes > L->stage_col[slot].bytes) {
             // a chunk larger than any aligned one: wait for the slot, then grow it
             if (L->slot_used[slot]) HIP_TRY(hipEventSynchronize(L->slot_free[slot]));
@@ -392,14 +426,32 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         if (rc != ATLAS_OK) return rc;
         void *emb_dst = self_dst ? static_cast<void *>(self_dst) : L->stage_emb[slot].p;
         HIP_TRY(hipMemcpyAsync(emb_dst, emb, emb_bytes, hipMemcpyHostToDevice, L->copy_stream));
-        if (col_bytes)
+        size_t staged_bytes = 0;
+        if (pc) {
+            // planned chunk: its regrouped edges travel instead of the CSR slice (same 4 bytes per edge)
+            char *base = static_cast<char *>(L->stage_col[slot].p);
+            const size_t sb = static_cast<size_t>(pc->n_edges) * 4, gb = static_cast<size_t>(pc->n_groups) * 4,
+                         tb = static_cast<size_t>((pc->n_edges + 63) / 64) * 4;
+            char *g_dev = base + round_up(sb, 256), *t_dev = g_dev + round_up(gb, 256);
+            if (sb) {
+                HIP_TRY(hipMemcpyAsync(base, plan->src_sorted + pc->edge_base, sb, hipMemcpyHostToDevice, L->copy_stream));
+                HIP_TRY(hipMemcpyAsync(g_dev, pc->grp_dst, gb, hipMemcpyHostToDevice, L->copy_stream));
+                HIP_TRY(hipMemcpyAsync(t_dev, pc->tile_grp, tb, hipMemcpyHostToDevice, L->copy_stream));
+            }
+            ga.src_sorted = reinterpret_cast<const int32_t *>(base);
+            ga.grp_dst = reinterpret_cast<const int32_t *>(g_dev);
+            ga.tile_grp = reinterpret_cast<const int32_t *>(t_dev);
+            staged_bytes = sb + gb + tb;
+        } else if (col_bytes) {
             HIP_TRY(hipMemcpyAsync(L->stage_col[slot].p, L->g.col_indices + e0, col_bytes, hipMemcpyHostToDevice,
                                    L->copy_stream));
+            staged_bytes = col_bytes;
+        }
         rc = end_span(L, L->t_copy, L->copy_stream);
         if (rc != ATLAS_OK) return rc;
         HIP_TRY(hipEventRecord(L->slot_loaded[slot], L->copy_stream));
         HIP_TRY(hipStreamWaitEvent(s, L->slot_loaded[slot], 0));
-        L->bytes_h2d += static_cast<int64_t>(emb_bytes + col_bytes);
+        L->bytes_h2d += static_cast<int64_t>(emb_bytes + staged_bytes);
         a.col = static_cast<const int32_t *>(L->stage_col[slot].p);
         a.col_base = e0;
         a.emb = emb_dst;
@@ -408,13 +460,6 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         a.col_base = 0;
         a.emb = emb;
     }
-
-    // a chunk that coincides with a planned chunk runs from its destination-ordered edges
-    const atlas_plan *plan = L->g.residency == ATLAS_RESIDENT_DEVICE ? L->g.plan : nullptr;
-    const PlanChunk *pc = nullptr;
-    if (plan && plan->chunk > 0 && src_begin % plan->chunk == 0 &&
-        src_end == std::min(L->n, src_begin + plan->chunk))
-        pc = &plan->chunks[static_cast<size_t>(src_begin / plan->chunk)];
 
     int rc = ATLAS_OK;
     if (L->selfmsg) {
@@ -450,11 +495,12 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
     }
     if ((rc = start_span(L, L->t_agg, s)) != ATLAS_OK) return rc;
     if (pc) {
-        GroupedArgs ga{};
-        ga.src_sorted = plan->src_sorted + pc->edge_base;
+        if (!plan->host) {
+            ga.src_sorted = plan->src_sorted + pc->edge_base;
+            ga.grp_dst = pc->grp_dst;
+            ga.tile_grp = pc->tile_grp;
+        }
         ga.n_edges = pc->n_edges;
-        ga.grp_dst = pc->grp_dst;
-        ga.tile_grp = pc->tile_grp;
         ga.emb = a.emb;
         ga.gat = a.gat;
         ga.src_begin = src_begin;
@@ -578,7 +624,9 @@ int atlas_layer_finish(atlas_layer_t *L, atlas_layer_stats_t *stats) {
 int atlas_plan_create(const atlas_graph_t *graph, int64_t chunk_sources, atlas_plan_t **out) {
     if (!graph || !out) return ATLAS_E_NULL;
     if (!graph->row_offsets || (graph->num_edges > 0 && !graph->col_indices)) return ATLAS_E_NULL;
-    if (graph->residency != ATLAS_RESIDENT_DEVICE || chunk_sources <= 0) return ATLAS_E_BAD_DIMS;
+    if (chunk_sources <= 0) return ATLAS_E_BAD_DIMS;
+    if (graph->residency != ATLAS_RESIDENT_DEVICE && graph->residency != ATLAS_RESIDENT_PINNED_HOST)
+        return ATLAS_E_BAD_DIMS;
     if (graph->num_vertices < 0 || graph->num_edges < 0) return ATLAS_E_RANGE;
     if (graph->num_vertices >= (int64_t(1) << 31)) return ATLAS_E_OVERFLOW;
     atlas_plan *P = new (std::nothrow) atlas_plan();
@@ -586,24 +634,68 @@ int atlas_plan_create(const atlas_graph_t *graph, int64_t chunk_sources, atlas_p
     P->n = graph->num_vertices;
     P->e = graph->num_edges;
     P->chunk = chunk_sources;
+    P->host = graph->residency == ATLAS_RESIDENT_PINNED_HOST;
     const int64_t nchunks = (P->n + chunk_sources - 1) / chunk_sources;
+    const size_t e_bytes = static_cast<size_t>(std::max<int64_t>(P->e, 1)) * sizeof(int32_t);
     int rc = ATLAS_OK;
-    hipError_t e = hipMalloc(&P->src_sorted, static_cast<size_t>(std::max<int64_t>(P->e, 1)) * sizeof(int32_t));
-    if (e != hipSuccess) rc = hip_fail(e, "hipMalloc(plan)");
+    hipError_t e = P->host ? hipHostMalloc(reinterpret_cast<void **>(&P->src_sorted), e_bytes, hipHostMallocDefault)
+                           : hipMalloc(reinterpret_cast<void **>(&P->src_sorted), e_bytes);
+    if (e != hipSuccess) rc = hip_fail(e, "alloc(plan)");
+
+    auto offset_at = [&](int64_t u, int64_t *v) -> hipError_t {
+        if (P->host) { *v = graph->row_offsets[u]; return hipSuccess; }
+        return hipMemcpy(v, graph->row_offsets + u, sizeof(int64_t), hipMemcpyDeviceToHost);
+    };
     int64_t ebeg = 0;
-    if (rc == ATLAS_OK && nchunks > 0) {
-        e = hipMemcpy(&ebeg, graph->row_offsets, sizeof(int64_t), hipMemcpyDeviceToHost);
-        if (e != hipSuccess) rc = hip_fail(e, "hipMemcpy(row_offsets)");
-    }
+    if (rc == ATLAS_OK && nchunks > 0 && (e = offset_at(0, &ebeg)) != hipSuccess) rc = hip_fail(e, "row_offsets");
     for (int64_t k = 0; rc == ATLAS_OK && k < nchunks; ++k) {
         const int64_t b = k * chunk_sources, en = std::min(P->n, b + chunk_sources);
         int64_t eend = 0;
-        e = hipMemcpy(&eend, graph->row_offsets + en, sizeof(int64_t), hipMemcpyDeviceToHost);
-        if (e != hipSuccess) { rc = hip_fail(e, "hipMemcpy(row_offsets)"); break; }
+        if ((e = offset_at(en, &eend)) != hipSuccess) { rc = hip_fail(e, "row_offsets"); break; }
+        const int64_t ne = eend - ebeg;
         PlanChunk pc;
-        e = build_plan_chunk(graph->row_offsets, graph->col_indices, P->n, b, en, ebeg, eend, P->src_sorted, &pc);
-        if (e != hipSuccess) { rc = hip_fail(e, "build_plan_chunk"); break; }
+        if (!P->host) {
+            e = build_plan_chunk(graph->row_offsets, graph->col_indices, P->n, b, en, ebeg, eend,
+                                 P->src_sorted + ebeg, &pc);
+            if (e != hipSuccess) { rc = hip_fail(e, "build_plan_chunk"); break; }
+        } else {
+            // stage the chunk's CSR slice into HBM, regroup there, bring the result back
+            int64_t *off_tmp = nullptr;
+            int32_t *col_tmp = nullptr, *src_tmp = nullptr;
+            const size_t nsrc = static_cast<size_t>(en - b);
+            const size_t ne1 = static_cast<size_t>(std::max<int64_t>(ne, 1));
+            if ((e = hipMalloc(reinterpret_cast<void **>(&off_tmp), (nsrc + 1) * sizeof(int64_t))) == hipSuccess &&
+                (e = hipMalloc(reinterpret_cast<void **>(&col_tmp), ne1 * 4)) == hipSuccess &&
+                (e = hipMalloc(reinterpret_cast<void **>(&src_tmp), ne1 * 4)) == hipSuccess &&
+                (e = hipMemcpy(off_tmp, graph->row_offsets + b, (nsrc + 1) * sizeof(int64_t), hipMemcpyHostToDevice)) == hipSuccess &&
+                (ne == 0 || (e = hipMemcpy(col_tmp, graph->col_indices + ebeg, static_cast<size_t>(ne) * 4, hipMemcpyHostToDevice)) == hipSuccess)) {
+                e = build_plan_chunk(off_tmp - b, col_tmp - ebeg, P->n, b, en, ebeg, eend, src_tmp, &pc);
+                if (e == hipSuccess && ne > 0)
+                    e = hipMemcpy(P->src_sorted + ebeg, src_tmp, static_cast<size_t>(ne) * 4, hipMemcpyDeviceToHost);
+                if (e == hipSuccess && ne > 0) {
+                    int32_t *g_h = nullptr, *t_h = nullptr;
+                    const size_t gb = static_cast<size_t>(pc.n_groups) * 4, tb = static_cast<size_t>((ne + 63) / 64) * 4;
+                    if ((e = hipHostMalloc(reinterpret_cast<void **>(&g_h), gb, hipHostMallocDefault)) == hipSuccess &&
+                        (e = hipHostMalloc(reinterpret_cast<void **>(&t_h), tb, hipHostMallocDefault)) == hipSuccess &&
+                        (e = hipMemcpy(g_h, pc.grp_dst, gb, hipMemcpyDeviceToHost)) == hipSuccess)
+                        e = hipMemcpy(t_h, pc.tile_grp, tb, hipMemcpyDeviceToHost);
+                    (void)hipFree(pc.grp_dst);
+                    (void)hipFree(pc.tile_grp);
+                    pc.grp_dst = g_h;
+                    pc.tile_grp = t_h;
+                }
+            }
+            if (off_tmp) (void)hipFree(off_tmp);
+            if (col_tmp) (void)hipFree(col_tmp);
+            if (src_tmp) (void)hipFree(src_tmp);
+            if (e != hipSuccess) {
+                P->chunks.push_back(pc);  // so that destroy releases what was allocated
+                rc = hip_fail(e, "build_plan_chunk(host)");
+                break;
+            }
+        }
         P->chunks.push_back(pc);
+        P->max_stage_bytes = std::max(P->max_stage_bytes, stage_bytes_of(pc));
         ebeg = eend;
     }
     if (rc != ATLAS_OK) {
@@ -618,10 +710,10 @@ int atlas_plan_destroy(atlas_plan_t *P) {
     if (!P) return ATLAS_E_NULL;
     (void)hipDeviceSynchronize();
     for (auto &c : P->chunks) {
-        if (c.grp_dst) (void)hipFree(c.grp_dst);
-        if (c.tile_grp) (void)hipFree(c.tile_grp);
+        if (c.grp_dst) (void)(P->host ? hipHostFree(c.grp_dst) : hipFree(c.grp_dst));
+        if (c.tile_grp) (void)(P->host ? hipHostFree(c.tile_grp) : hipFree(c.tile_grp));
     }
-    if (P->src_sorted) (void)hipFree(P->src_sorted);
+    if (P->src_sorted) (void)(P->host ? hipHostFree(P->src_sorted) : hipFree(P->src_sorted));
     delete P;
     return ATLAS_OK;
 }

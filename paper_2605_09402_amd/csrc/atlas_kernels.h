@@ -86,9 +86,12 @@ struct GroupedArgs {
 // and one pending decrement per (chunk, destination) group.
 hipError_t launch_aggregate_grouped(const GroupedArgs &a, hipStream_t s);
 
-// Plan construction for one chunk (synchronous; allocates the chunk's arrays).
+// Plan construction for one chunk (synchronous).  off_dev is addressed by global
+// source id and col_dev by global edge number (only [src_begin, src_end] and
+// [edge_begin, edge_end) are touched); src_sorted receives the chunk's
+// edge_end - edge_begin entries; grp_dst and tile_grp are allocated with hipMalloc.
 hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int64_t n, int64_t src_begin,
-                            int64_t src_end, int64_t edge_begin, int64_t edge_end, int32_t *src_sorted_all,
+                            int64_t src_end, int64_t edge_begin, int64_t edge_end, int32_t *src_sorted,
                             PlanChunk *out);
 
 // GAT, per chunk: raise m_next[v][h] to the largest logit any edge of the chunk

@@ -65,7 +65,7 @@ struct MaxOp {
 }  // namespace
 
 hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int64_t n, int64_t src_begin,
-                            int64_t src_end, int64_t edge_begin, int64_t edge_end, int32_t *src_sorted_all,
+                            int64_t src_end, int64_t edge_begin, int64_t edge_end, int32_t *src_sorted,
                             PlanChunk *out) {
     *out = PlanChunk{};
     out->edge_base = edge_begin;
@@ -80,7 +80,6 @@ hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int6
     uint32_t *heads = nullptr;
     void *temp = nullptr;
     size_t temp_sort = 0, temp_scan_max = 0, temp_scan_sum = 0, temp_bytes = 0;
-    int32_t *src_sorted = src_sorted_all + edge_begin;
     const uint32_t *keys_in = reinterpret_cast<const uint32_t *>(col_dev + edge_begin);
     uint32_t last = 0;
     int end_bit = 1;

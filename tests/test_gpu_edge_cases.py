@@ -104,6 +104,13 @@ def test_pinned_host_residency(oracle, H, model, store):
     assert run.stats[0]["bytes_copied_h2d"] == case.n * row + case.e * 4 + (case.n + 1) * 8
     run2 = H.run_gpu(case, pinned_host=True, flush_every=3)     # no host sync between chunks
     H.check_outputs(oracle, case, run2)
+    # with a plan the regrouped chunks are what is streamed (the plan itself sits in pinned host memory)
+    run3 = H.run_gpu(case, snapshots=True, pinned_host=True, plan=True)
+    H.check_integers(oracle, case, run3)
+    H.check_outputs(oracle, case, run3)
+    assert run3.stats[0]["bytes_copied_h2d"] > case.n * row + case.e * 4
+    run4 = H.run_gpu(case, pinned_host=True, plan=True, flush_every=5)
+    H.check_outputs(oracle, case, run4)
 
 
 def test_api_errors(atlas, H):
