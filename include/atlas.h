@@ -203,6 +203,13 @@ int atlas_in_degree(const atlas_graph_t *graph, int32_t *in_degree, void *hip_st
 int atlas_reorder_indegree_desc(const atlas_graph_t *graph, int32_t *new_of_old,
                                 int32_t *old_of_new);
 
+/* The paper's greedy ordering (Sec. 3.8): vertices by decreasing
+ * Score(u) = (sum_{v in Out(u)} 1/d_in(v)) / d_out(u) (0 without out-edges),
+ * ties by smaller old id first.  Scores are summed in fp64 in CSR order, so the
+ * permutation is reproducible bit for bit.  DEVICE graphs, graph->in_degree
+ * must be set; outputs are int32[N] DEVICE memory.  Synchronous. */
+int atlas_reorder_score_desc(const atlas_graph_t *graph, int32_t *new_of_old, int32_t *old_of_new);
+
 /* Synchronise and copy one internal array to host memory, for tests. */
 enum atlas_debug_what {
     ATLAS_DBG_INDEG = 0,       /* int32[N]                                  */

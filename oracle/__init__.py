@@ -190,6 +190,30 @@ def order_score(off: np.ndarray, col: np.ndarray, indeg: np.ndarray) -> np.ndarr
     return s
 
 
+def reorder_score_desc(off: np.ndarray, col: np.ndarray, indeg: np.ndarray):
+    """The paper's greedy order (Sec. 3.8): vertices by decreasing Score, ties by
+    smaller id first (a stable library sort on the negated score)."""
+    score = order_score(off, col, indeg)
+    old_of_new = np.argsort(-score, kind="stable").astype(np.int32)
+    new_of_old = np.empty_like(old_of_new)
+    new_of_old[old_of_new] = np.arange(old_of_new.size, dtype=np.int32)
+    return new_of_old, old_of_new
+
+
+def message_span(il: "InLists", selfmsg: bool = False) -> np.ndarray:
+    """Span of every vertex (Sec. 4.5): ids between its first and last
+    in-neighbour in streaming order (0 for fewer than two messages)."""
+    span = np.zeros(il.n_dst, dtype=np.int64)
+    for v in range(il.n_dst):
+        a, b = il.in_off[v], il.in_off[v + 1]
+        if b > a:
+            lo, hi = int(il.in_src[a]), int(il.in_src[b - 1])   # lists are ascending
+            if selfmsg:
+                lo, hi = min(lo, v), max(hi, v)
+            span[v] = hi - lo
+    return span
+
+
 # --------------------------------------------------------------------------
 # whole-model chain
 # --------------------------------------------------------------------------

@@ -28,6 +28,7 @@ EXPORTS = [
     "atlas_layer_init", "atlas_attention_prepass", "atlas_broadcast_chunk", "atlas_flush_ready",
     "atlas_layer_finish", "atlas_in_degree", "atlas_reorder_indegree_desc", "atlas_debug_copy",
     "atlas_release_cache", "atlas_strerror", "atlas_last_hip_error", "atlas_plan_create", "atlas_plan_destroy",
+    "atlas_reorder_score_desc",
 ]
 
 
@@ -88,6 +89,7 @@ def lib() -> ctypes.CDLL:
         L.atlas_layer_finish.argtypes = [vp, ctypes.POINTER(atlas_layer_stats_t)]
         L.atlas_in_degree.argtypes = [ctypes.POINTER(atlas_graph_t), vp, vp]
         L.atlas_reorder_indegree_desc.argtypes = [ctypes.POINTER(atlas_graph_t), vp, vp]
+        L.atlas_reorder_score_desc.argtypes = [ctypes.POINTER(atlas_graph_t), vp, vp]
         L.atlas_debug_copy.argtypes = [vp, i32, vp, i64]
         L.atlas_release_cache.argtypes = []
         L.atlas_plan_create.argtypes = [ctypes.POINTER(atlas_graph_t), i64, ctypes.POINTER(vp)]
@@ -196,6 +198,11 @@ def atlas_in_degree(graph: atlas_graph_t, in_degree, stream=None) -> None:
 def atlas_reorder_indegree_desc(graph: atlas_graph_t, new_of_old, old_of_new) -> None:
     _check(lib().atlas_reorder_indegree_desc(ctypes.byref(graph), _ptr(new_of_old), _ptr(old_of_new)),
            "atlas_reorder_indegree_desc")
+
+
+def atlas_reorder_score_desc(graph: atlas_graph_t, new_of_old, old_of_new) -> None:
+    _check(lib().atlas_reorder_score_desc(ctypes.byref(graph), _ptr(new_of_old), _ptr(old_of_new)),
+           "atlas_reorder_score_desc")
 
 
 def atlas_debug_copy(layer: int, what: int, host_array) -> None:

@@ -736,6 +736,17 @@ int atlas_reorder_indegree_desc(const atlas_graph_t *graph, int32_t *new_of_old,
     return ATLAS_OK;
 }
 
+int atlas_reorder_score_desc(const atlas_graph_t *graph, int32_t *new_of_old, int32_t *old_of_new) {
+    if (!graph || !new_of_old || !old_of_new || !graph->in_degree || !graph->row_offsets) return ATLAS_E_NULL;
+    if (graph->num_edges > 0 && !graph->col_indices) return ATLAS_E_NULL;
+    if (graph->residency != ATLAS_RESIDENT_DEVICE) return ATLAS_E_BAD_DIMS;
+    if (graph->num_vertices < 0) return ATLAS_E_RANGE;
+    if (graph->num_vertices >= (int64_t(1) << 31)) return ATLAS_E_OVERFLOW;
+    HIP_TRY(reorder_score_desc(graph->row_offsets, graph->col_indices, graph->in_degree, graph->num_vertices,
+                               new_of_old, old_of_new));
+    return ATLAS_OK;
+}
+
 int atlas_debug_copy(atlas_layer_t *L, int what, void *host_dst, int64_t bytes) {
     if (!L || !host_dst) return ATLAS_E_NULL;
     if (bytes < 0) return ATLAS_E_RANGE;

@@ -160,5 +160,7 @@ hipError_t launch_advance_head(int32_t *counters, hipStream_t s);
 // Degree ordering.
 hipError_t reorder_indegree_desc(const int32_t *indeg, int64_t n, int32_t *new_of_old,
                                  int32_t *old_of_new);
+hipError_t reorder_score_desc(const int64_t *off, const int32_t *col, const int32_t *indeg, int64_t n,
+                              int32_t *new_of_old, int32_t *old_of_new);
 
 }  // namespace atlas

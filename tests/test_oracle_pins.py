@@ -402,3 +402,37 @@ def test_order_score_closed_form(oracle):
     indeg = oracle.in_degree(200, col)
     s = oracle.order_score(off, col, indeg)
     assert abs((s * np.diff(off)).sum() - np.count_nonzero(indeg)) < 1e-9
+
+
+def test_score_order_and_span_on_hand_made_graph(oracle):
+    # 0 -> {1,2,3} (each only reachable from 0: score 1), 4 -> {5,5} with 6 -> 5 as well
+    # (d_in(5) = 3: score(4) = 1/3, score(6) = 1/3), 7 has no out-edges (score 0)
+    edges = [(0, 1), (0, 2), (0, 3), (4, 5), (4, 5), (6, 5)]
+    n = 8
+    off = np.zeros(n + 1, dtype=np.int64)
+    for s, _ in edges:
+        off[s + 1] += 1
+    off = np.cumsum(off)
+    col = np.array([t for _, t in edges], dtype=np.int32)
+    indeg = oracle.in_degree(n, col)
+    score = oracle.order_score(off, col, indeg)
+    assert score[0] == 1.0 and abs(score[4] - 1 / 3) < 1e-15 and score[4] == score[6] and score[7] == 0.0
+    new_of_old, old_of_new = oracle.reorder_score_desc(off, col, indeg)
+    assert list(old_of_new) == [0, 4, 6, 1, 2, 3, 5, 7]          # ties keep ascending id
+    assert np.array_equal(new_of_old[old_of_new], np.arange(n))
+    il = oracle.InLists.from_csr(off, col)
+    span = oracle.message_span(il)
+    assert list(span) == [0, 0, 0, 0, 0, 2, 0, 0]                # vertex 5 hears from 4 .. 6
+    assert list(oracle.message_span(il, selfmsg=True)) == [0, 1, 2, 3, 0, 2, 0, 0]
+
+
+def test_score_order_is_sorted(oracle):
+    off, col, _ = tiny_graph(51, 300, 2000, isolated=7)
+    indeg = oracle.in_degree(300, col)
+    s = oracle.order_score(off, col, indeg)
+    new_of_old, old_of_new = oracle.reorder_score_desc(off, col, indeg)
+    ss = s[old_of_new]
+    assert np.all(ss[:-1] >= ss[1:])
+    same = ss[:-1] == ss[1:]
+    assert np.all(old_of_new[:-1][same] < old_of_new[1:][same])
+    assert np.array_equal(np.sort(old_of_new), np.arange(300))
