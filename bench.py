@@ -35,7 +35,10 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--scale", type=int, default=26, help="R-MAT scale (26 = the quoted workload)")
+    ap.add_argument("--workload", choices=["config2", "config3", "config4", "config5"], default="config5",
+                    help="config5 (default) is the workload the metric is quoted on; the others are the smaller "
+                         "parity workloads, timed for the record")
+    ap.add_argument("--scale", type=int, default=None, help="R-MAT scale (default: the workload's own)")
     ap.add_argument("--edge-factor", type=int, default=32)
     ap.add_argument("--no-plan", action="store_true", help="push straight from the CSR (atomic path)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -44,6 +47,9 @@ def main() -> int:
     ap.add_argument("--residency", choices=["device", "pinned"], default="device",
                     help="pinned: graph and features stay in pinned host memory and are streamed per chunk "
                          "(host-link bound; reported for the record, never the headline value)")
+    ap.add_argument("--order", choices=["indegree", "score", "original"], default="indegree",
+                    help="vertex ids: in-degree descending (the workload's), the paper's greedy Score order, "
+                         "or the generator's raw ids")
     ap.add_argument("--chunk-log2", type=int, default=None, help="chunk size in sources (default N/16)")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run a plain 4 GiB device copy three times (reference for HBM byte counters)")
@@ -73,12 +79,27 @@ def main() -> int:
         atlas.atlas_in_degree(atlas.make_graph(n, col.numel(), off, col), indeg)
         new_of_old = torch.empty(n, dtype=torch.int32, device=dev)
         old_of_new = torch.empty(n, dtype=torch.int32, device=dev)
-        atlas.atlas_reorder_indegree_desc(atlas.make_graph(n, col.numel(), off, col, indeg), new_of_old, old_of_new)
+        g = atlas.make_graph(n, col.numel(), off, col, indeg)
+        if args.order == "score":
+            atlas.atlas_reorder_score_desc(g, new_of_old, old_of_new)
+        else:
+            atlas.atlas_reorder_indegree_desc(g, new_of_old, old_of_new)
         return new_of_old
 
     t0 = time.time()
-    wl = workloads.config5(dev, scale=args.scale, reorder=reorder, edge_factor=args.edge_factor,
-                           chunk=None if args.chunk_log2 is None else 1 << args.chunk_log2)
+    ck = None if args.chunk_log2 is None else 1 << args.chunk_log2
+    ro = None if args.order == "original" else reorder
+    if args.workload == "config5":
+        if args.scale is None:
+            args.scale = 26
+        wl = workloads.config5(dev, scale=args.scale, reorder=ro, edge_factor=args.edge_factor, chunk=ck)
+    elif args.workload == "config2":
+        wl = workloads.config2(dev, scale=args.scale or 20, reorder=ro, chunk=ck)
+    elif args.workload == "config3":
+        wl = workloads.config3(dev, scale=args.scale or 22, chunk=ck)
+    else:
+        wl = workloads.config4(dev, scale=args.scale or 22, chunk=ck)
+    is_headline = args.workload == "config5" and args.scale == 26 and args.edge_factor == 32 and ck is None
     torch.cuda.synchronize()
     n, e, chunk = wl.n, wl.e, wl.chunk
     log("generated %s: N=%d E=%d chunk=%d in %.1f s" % (wl.name, n, e, chunk, time.time() - t0))
@@ -113,14 +134,23 @@ def main() -> int:
         params.append((p.W.to(wl.store).to(dev).contiguous(), p.bias.to(wl.store).to(dev).contiguous()))
     outs = [torch.empty((n, wl.dims[li + 1]), dtype=wl.store, device=dev) for li in range(len(wl.layers))]
 
+    model_id = {"sage": atlas.MODEL_SAGE_MEAN, "gcn": atlas.MODEL_GCN_SYM, "gat": atlas.MODEL_GAT}[wl.model]
+    sdt = atlas.DTYPE_BF16 if wl.store == torch.bfloat16 else atlas.DTYPE_F32
+    between = atlas.ACT_ELU if wl.act == "elu" else atlas.ACT_RELU
+    attn = [(None if p.attn_src is None else p.attn_src.to(wl.store).to(dev).contiguous(),
+             None if p.attn_dst is None else p.attn_dst.to(wl.store).to(dev).contiguous()) for p in wl.layers]
+
     def run_layer(li: int, x: torch.Tensor, timing: bool) -> dict:
         d_in, d_out = wl.dims[li], wl.dims[li + 1]
-        act = atlas.ACT_NONE if li + 1 == len(wl.layers) else atlas.ACT_RELU
-        dims = atlas.make_dims(atlas.MODEL_SAGE_MEAN, d_in, d_out, atlas.DTYPE_BF16, atlas.DTYPE_BF16, act, chunk,
+        act = atlas.ACT_NONE if li + 1 == len(wl.layers) else between
+        dims = atlas.make_dims(model_id, d_in, d_out, sdt, sdt, act, chunk, heads=wl.heads,
                                flags=(atlas.FLAG_TIMING if timing else 0) | atlas.FLAG_EMB_RESIDENT)
         W, b = params[li]
-        h = atlas.atlas_layer_init(graph, dims, atlas.make_weights(W, b, atlas.DTYPE_BF16), stream)
+        h = atlas.atlas_layer_init(graph, dims, atlas.make_weights(W, b, sdt, attn[li][0], attn[li][1]), stream)
         out = outs[li]
+        if wl.model == "gat":
+            for b0 in range(0, n, chunk):
+                atlas.atlas_attention_prepass(h, b0, min(n, b0 + chunk), x[b0:b0 + chunk], stream)
         atlas.atlas_flush_ready(h, out, stream)
         for b0 in range(0, n, chunk):
             b1 = min(n, b0 + chunk)
@@ -174,24 +204,25 @@ def main() -> int:
             x = outs[li]
         torch.cuda.synchronize()
         e2e_ms = (time.perf_counter() - t0) * 1e3
-        log("end-to-end 3 layers: %.1f ms (%s)" % (e2e_ms, ", ".join("%.1f" % v for v in layer_ms)))
+        log("end-to-end all layers: %.1f ms (%s)" % (e2e_ms, ", ".join("%.1f" % v for v in layer_ms)))
 
     # ---- roofline of the scatter-aggregate kernel ----
-    d = wl.dims[0]
+    d = wl.dims[1] if wl.model == "gat" else wl.dims[0]   # width of the accumulated row
+    s_in = 4 if wl.model == "gat" or wl.store == torch.float32 else 2
     bytes_per_edge = 4 + 2 * 4 * d + 8          # destination id, fp32 row read + write, pending RMW
-    bytes_per_source = d * 2 + 8                # bf16 source row, row offset
+    bytes_per_source = d * s_in + 8             # source row, row offset
     algo_bytes_layer = e * bytes_per_edge + n * bytes_per_source
     agg_s_per_layer = agg_ms / args.steps / 1e3
     achieved = algo_bytes_layer / agg_s_per_layer / 1e9
     peak = 8000.0
     # bytes the regrouped kernel itself must move (source id + bf16 source row per edge)
-    kernel_bytes_per_edge = 4 + d * 2
+    kernel_bytes_per_edge = 4 + d * s_in
     # HBM bytes per launch from the committed counter summary; null when the
     # kernels changed after the counters were taken (or for another workload)
     traffic = None
     kname = "k_aggregate_grouped" if plan else "k_aggregate"
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic_config5_rmat26.json")
-    if os.path.exists(tpath) and args.scale == 26 and args.edge_factor == 32 and args.chunk_log2 is None:
+    if os.path.exists(tpath) and is_headline and args.order == "indegree" and args.residency == "device":
         from paper_2605_09402_amd.profile_summary import kernel_source_hash
         doc = json.load(open(tpath))
         if doc.get("kernel_source_hash") == kernel_source_hash() and kname in doc["kernels"]:
@@ -206,13 +237,14 @@ def main() -> int:
         "edges_per_s_in_kernel": round(e / agg_s_per_layer, 1),
         "per_edge_reads_only_GBps": round(e * kernel_bytes_per_edge / agg_s_per_layer / 1e9, 1),
     }
-    K = 2 * d
-    upd_flops = 2.0 * n * K * wl.dims[1]
+    K = 2 * wl.dims[0] if wl.model == "sage" else wl.dims[0]
+    upd_flops = 2.0 * n * K * wl.dims[1]      # SAGE / GCN: the flush GEMM; GAT: the per-chunk transform (in ms_self)
     upd_s = upd_ms / args.steps / 1e3
     update = {
-        "kernel": "k_update", "tflops": round(upd_flops / upd_s / 1e12, 2), "mfma_peak_tflops": 2500.0,
-        "frac_of_mfma_peak": round(upd_flops / upd_s / 2.5e15, 4),
-        "hbm_GBps": round(n * (4 * d + 2 * d + 2 * wl.dims[1]) / upd_s / 1e9, 1),
+        "kernel": "k_update", "tflops": round(upd_flops / upd_s / 1e12, 2),
+        "mfma_peak_tflops": 2500.0 if sdt == atlas.DTYPE_BF16 else 157.3,
+        "frac_of_mfma_peak": round(upd_flops / upd_s / (2.5e15 if sdt == atlas.DTYPE_BF16 else 157.3e12), 4),
+        "hbm_GBps": round(n * (4 * d + (s_in * d if wl.model == "sage" else 0) + s_in * wl.dims[1]) / upd_s / 1e9, 1),
         "ms_per_layer": round(upd_ms / args.steps, 3),
     }
 
@@ -223,7 +255,7 @@ def main() -> int:
         oracle.build()
         gsel = torch.Generator().manual_seed(12345)
         pick = torch.randperm(n, generator=gsel)[: args.sample_dst]
-        pick = torch.unique(torch.cat([pick, torch.arange(min(1024, n))]))   # plus the highest in-degree rows
+        pick = torch.unique(torch.cat([pick, torch.topk(indeg.to(torch.int64), min(1024, n)).indices.cpu()]))
         in_off, in_src = in_edges_of(wl.off, wl.col, pick.to(dev))
         need = torch.unique(torch.cat([in_src.to(torch.int64), pick.to(dev)]))
         remap = torch.full((n,), -1, dtype=torch.int64, device=dev)
@@ -232,9 +264,10 @@ def main() -> int:
         il = oracle.InLists(in_off.cpu().numpy(), remap[in_src.to(torch.int64)].to(torch.int32).cpu().numpy(),
                             remap[pick.to(dev)].cpu().numpy())
         p0 = wl.layers[0]
+        indeg_s = indeg[need].cpu().numpy().astype(np.int64)
         t1 = time.perf_counter()
-        Y = oracle.sage_mean(il, Xs, p0.W.numpy(), p0.bias.numpy())
-        Y = oracle.round_storage(oracle.activation(Y, oracle.ACT_RELU), oracle.FMT_BF16)
+        Y = oracle.run_layer(wl.model, il, indeg_s, Xs, p0, {"relu": oracle.ACT_RELU, "elu": oracle.ACT_ELU}[wl.act],
+                             oracle.FMT_BF16 if wl.store == torch.bfloat16 else oracle.FMT_F32)
         t_or = time.perf_counter() - t1
         sample_edges = int(in_src.numel())
         # sampled parity of the timed configuration, on the way
@@ -256,11 +289,13 @@ def main() -> int:
     line = {
         "metric": "aggregated edges/s per layer (GTEPS)", "value": round(gteps, 4), "unit": "GTEPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16 storage / f32 accumulate",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 storage / f32 accumulate" if sdt == atlas.DTYPE_BF16 else "f32",
         "data": "synthetic",
-        "config": {"workload": wl.name, "vertices": n, "edges": e, "d_in": d, "d_out": wl.dims[1],
+        "config": {"workload": wl.name, "layer_type": wl.model, "vertices": n, "edges": e, "d_in": wl.dims[0], "d_out": wl.dims[1],
                    "chunk_sources": chunk, "chunks": nchunks, "flush": "after every chunk",
-                   "ids": "in-degree descending", "in_degree": "precomputed once per graph",
+                   "ids": {"indegree": "in-degree descending", "score": "greedy Score order (paper Sec. 3.8)",
+                           "original": "generator's raw ids"}[args.order], "in_degree": "precomputed once per graph",
                    "residency": "HBM" if args.residency == "device" else
                    "pinned host, staged per chunk on a copy stream (%.2f GB, copies %.1f ms per layer)"
                    % (h2d_bytes / 1e9, copy_ms / args.steps),
