@@ -489,11 +489,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         a.emb = L->gat_z.p;
         a.d = d.d_out;
         a.in_bf16 = 0;
-        HIP_TRY(launch_gat_chunk_max(a, s));
-        HIP_TRY(launch_gat_rescale(a.gat, a.acc, d.d_out, L->n, s));
-        if ((rc = end_span(L, L->t_self, s)) != ATLAS_OK) return rc;
     }
-    if ((rc = start_span(L, L->t_agg, s)) != ATLAS_OK) return rc;
     if (pc) {
         if (!plan->host) {
             ga.src_sorted = plan->src_sorted + pc->edge_base;
@@ -513,6 +509,15 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         ga.ready = a.ready;
         ga.counters = a.counters;
         ga.counters64 = a.counters64;
+    }
+    if (d.model == ATLAS_MODEL_GAT) {
+        if (pc) HIP_TRY(launch_gat_group_max(ga, s));
+        else HIP_TRY(launch_gat_chunk_max(a, s));
+        HIP_TRY(launch_gat_rescale(a.gat, a.acc, d.d_out, L->n, s));
+        if ((rc = end_span(L, L->t_self, s)) != ATLAS_OK) return rc;
+    }
+    if ((rc = start_span(L, L->t_agg, s)) != ATLAS_OK) return rc;
+    if (pc) {
         HIP_TRY(launch_aggregate_grouped(ga, s));
     } else {
         HIP_TRY(launch_aggregate(a, s));

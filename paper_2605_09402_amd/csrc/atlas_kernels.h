@@ -98,6 +98,7 @@ hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int6
 // sends to v (CSR order), then bring every destination whose maximum moved to
 // the new reference (rescale l and acc, m_cur = m_next).
 hipError_t launch_gat_chunk_max(const AggregateArgs &a, hipStream_t s);
+hipError_t launch_gat_group_max(const GroupedArgs &a, hipStream_t s);   // the same over a planned chunk
 hipError_t launch_gat_rescale(const GatState &g, float *acc, int d_out, int64_t n, hipStream_t s);
 // GAT set-up and prepass.
 hipError_t launch_fill_i32(int32_t *p, int32_t value, int64_t count, hipStream_t s);

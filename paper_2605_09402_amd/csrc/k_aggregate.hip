@@ -470,6 +470,57 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
     drain_ready(stage, staged, a.ready, a.counters, lane);
 }
 
+// GAT, first sweep of a planned chunk: one lane per edge of a 64-edge tile of
+// the destination-ordered list, a segmented max-scan over the lanes of each
+// destination's group, and one update of m_next per (group, head) -- plain for
+// a group that lies inside the tile, atomic for a group cut by a tile boundary.
+__global__ __launch_bounds__(kBlock) void k_gat_group_max(GroupedArgs a) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t wave = static_cast<int64_t>(blockIdx.x) * (kBlock / kWave) + (threadIdx.x >> 6);
+    const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (kBlock / kWave);
+    const int64_t ntiles = (a.n_edges + kTileEdges - 1) / kTileEdges;
+    const int H = a.gat.heads;
+    for (int64_t t = wave; t < ntiles; t += nwaves) {
+        const int64_t e0 = t * kTileEdges;
+        const int64_t left = a.n_edges - e0;
+        const int cnt = left < kTileEdges ? static_cast<int>(left) : kTileEdges;
+        const int g0 = a.tile_grp[t];
+        int32_t s = 0;
+        if (lane < cnt) s = a.src_sorted[e0 + lane];
+        const bool is_end = lane < cnt && s < 0;
+        const uint64_t endmask = __ballot(is_end);
+        const int64_t src = s & 0x7fffffff;
+        bool cut = false;
+        if (e0 > 0) cut = a.src_sorted[e0 - 1] >= 0;
+        const uint64_t below = endmask & ((1ull << lane) - 1ull);
+        const bool closes = is_end || lane == cnt - 1;
+        int32_t dstv = 0;
+        if (closes) dstv = a.grp_dst[g0 + __popcll(below)];
+        // my edge's destination is held by the lane that closes my group
+        const uint64_t rest = endmask >> lane;
+        int closer = rest ? lane + __ffsll(static_cast<unsigned long long>(rest)) - 1 : cnt - 1;
+        if (closer < 0) closer = 0;
+        const int64_t v = __shfl(dstv, closer);
+        const int start = below ? 64 - __clzll(static_cast<long long>(below)) : 0;  // first lane of my group
+        const bool shared = (below == 0 && cut) || !is_end;
+        for (int h = 0; h < H; ++h) {
+            float sc = -INFINITY;
+            if (lane < cnt) sc = leaky(a.gat.el[src * H + h] + a.gat.er[v * H + h], a.gat.slope);
+#pragma unroll
+            for (int o = 1; o < kWave; o <<= 1) {
+                const float up = __shfl_up(sc, o);
+                if (lane - o >= start) sc = fmaxf(sc, up);
+            }
+            if (closes) {
+                int32_t *m = a.gat.m_next + v * H + h;
+                const int32_t enc = encode_max(sc);
+                if (shared) atomicMax(m, enc);
+                else if (enc > *m) *m = enc;
+            }
+        }
+    }
+}
+
 template <typename T, int MODEL>
 hipError_t launch_grouped_vpl(const GroupedArgs &a, int grid, hipStream_t s) {
     switch (a.d / kWave) {
@@ -521,6 +572,12 @@ hipError_t launch_aggregate(const AggregateArgs &a, hipStream_t s) {
         return a.model == 1 ? launch_vpl<uint16_t, 1>(a, grid, s) : launch_vpl<uint16_t, 0>(a, grid, s);
     }
     return a.model == 1 ? launch_vpl<float, 1>(a, grid, s) : launch_vpl<float, 0>(a, grid, s);
+}
+
+hipError_t launch_gat_group_max(const GroupedArgs &a, hipStream_t s) {
+    if (a.n_edges <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_gat_group_max, dim3(persistent_grid(8)), dim3(kBlock), 0, s, a);
+    return hipGetLastError();
 }
 
 hipError_t launch_gat_chunk_max(const AggregateArgs &a, hipStream_t s) {

@@ -51,7 +51,12 @@ __global__ __launch_bounds__(kBlock) void k_gat_fold_attention(const void *W, co
     wa[i] = s;
 }
 
-// One wave per row: el[u][h] and er[u][h] for the rows of the chunk.
+// One wave per row: el[u][h] and er[u][h] for the rows of the chunk.  A lane
+// keeps the folded attention columns of its (up to four) row elements in
+// registers for all the rows it sees.  The 16 partial sums are reduced with a
+// halving butterfly: at each of the first four steps a lane hands half of its
+// values to its partner and keeps the other half, so 15 + 2 shuffles replace
+// 16 x 6.
 template <typename T>
 __global__ __launch_bounds__(kBlock) void k_gat_prepass(const T *__restrict__ emb, int64_t src_begin, int64_t src_end,
                                                         int d_in, const float *__restrict__ wa, int heads, float *el,
@@ -60,12 +65,35 @@ __global__ __launch_bounds__(kBlock) void k_gat_prepass(const T *__restrict__ em
     const int64_t wave = static_cast<int64_t>(blockIdx.x) * (kBlock / 64) + (threadIdx.x >> 6);
     const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (kBlock / 64);
     const int H2 = 2 * heads;
+    constexpr int kRegCols = 4;  // columns lane, lane+64, lane+128, lane+192 live in registers
+    float wreg[kRegCols][16];
+#pragma unroll
+    for (int i = 0; i < kRegCols; ++i)
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int c = lane + 64 * i;
+            wreg[i][k] = (c < d_in && k < H2) ? wa[c * H2 + k] : 0.f;
+        }
+    // value k ends up on the lanes whose low four bits spell k with bit 0 first:
+    // bit0 -> 8, bit1 -> 4, bit2 -> 2, bit3 -> 1
+    const int my_k = ((lane & 1) << 3) | ((lane & 2) << 1) | ((lane & 4) >> 1) | ((lane & 8) >> 3);
     for (int64_t u = src_begin + wave; u < src_end; u += nwaves) {
         const T *row = emb + (u - src_begin) * d_in;
         float part[16];
 #pragma unroll
         for (int k = 0; k < 16; ++k) part[k] = 0.f;
-        for (int c = lane; c < d_in; c += 64) {
+#pragma unroll
+        for (int i = 0; i < kRegCols; ++i) {
+            const int c = lane + 64 * i;
+            float x = 0.f;
+            if (c < d_in) {
+                if constexpr (sizeof(T) == 2) x = __uint_as_float(static_cast<uint32_t>(row[c]) << 16);
+                else x = row[c];
+            }
+#pragma unroll
+            for (int k = 0; k < 16; ++k) part[k] += x * wreg[i][k];
+        }
+        for (int c = lane + 64 * kRegCols; c < d_in; c += 64) {  // wider rows: the rest from memory
             float x;
             if constexpr (sizeof(T) == 2) x = __uint_as_float(static_cast<uint32_t>(row[c]) << 16);
             else x = row[c];
@@ -73,20 +101,46 @@ __global__ __launch_bounds__(kBlock) void k_gat_prepass(const T *__restrict__ em
             for (int k = 0; k < 16; ++k)
                 if (k < H2) part[k] += x * wa[c * H2 + k];
         }
+        // halving steps: 16 -> 8 -> 4 -> 2 -> 1 values per lane
+        float p8[8], p4[4], p2[2], p1;
+        {
+            const bool hi = lane & 1;
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            if (k < H2) {
-                float v = part[k];
-#pragma unroll
-                for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-                part[k] = v;
+            for (int k = 0; k < 8; ++k) {
+                const float give = hi ? part[k] : part[k + 8];
+                const float keep = hi ? part[k + 8] : part[k];
+                p8[k] = keep + __shfl_xor(give, 1);
             }
         }
-        if (lane == 0) {
-            for (int k = 0; k < heads; ++k) {
-                el[u * heads + k] = part[k];
-                er[u * heads + k] = part[heads + k];
+        {
+            const bool hi = lane & 2;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float give = hi ? p8[k] : p8[k + 4];
+                const float keep = hi ? p8[k + 4] : p8[k];
+                p4[k] = keep + __shfl_xor(give, 2);
             }
+        }
+        {
+            const bool hi = lane & 4;
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const float give = hi ? p4[k] : p4[k + 2];
+                const float keep = hi ? p4[k + 2] : p4[k];
+                p2[k] = keep + __shfl_xor(give, 4);
+            }
+        }
+        {
+            const bool hi = lane & 8;
+            const float give = hi ? p2[0] : p2[1];
+            const float keep = hi ? p2[1] : p2[0];
+            p1 = keep + __shfl_xor(give, 8);
+        }
+        p1 += __shfl_xor(p1, 16);
+        p1 += __shfl_xor(p1, 32);
+        if (lane < 16 && my_k < H2) {
+            if (my_k < heads) el[u * heads + my_k] = p1;
+            else er[u * heads + (my_k - heads)] = p1;
         }
     }
 }
