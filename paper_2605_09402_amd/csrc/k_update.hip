@@ -173,9 +173,13 @@ __device__ __forceinline__ void gather_rows(const UpdateArgs &a, typename Elem<B
             const float g = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(scalev), rr));
             if (col < d) {
                 typename Elem<BF16C>::type *dst = A + (w * kRows + rr) * stride + acc_base + col;
-                const float x = id >= 0 ? v[i].x : 0.f, y = id >= 0 ? v[i].y : 0.f;
-                dst[0] = to_elem<BF16C>(a.model == 0 ? x / g : x * g);
-                dst[1] = to_elem<BF16C>(a.model == 0 ? y / g : y * g);
+                const float x = id >= 0 ? v[i].x * g : 0.f, y = id >= 0 ? v[i].y * g : 0.f;
+                if constexpr (BF16C) {
+                    *reinterpret_cast<uint32_t *>(dst) = pack_bf16x2(x, y);
+                } else {
+                    dst[0] = x;
+                    dst[1] = y;
+                }
             }
         }
     }
@@ -200,9 +204,12 @@ __device__ __forceinline__ void gather_rows(const UpdateArgs &a, typename Elem<B
             const int32_t id = __builtin_amdgcn_readlane(idv, rr);
             if (col < d) {
                 typename Elem<BF16C>::type *dst = A + (w * kRows + rr) * stride + col;
-                const float2 f = own_to_f32(v[i]);
-                dst[0] = to_elem<BF16C>(id >= 0 ? f.x : 0.f);
-                dst[1] = to_elem<BF16C>(id >= 0 ? f.y : 0.f);
+                if constexpr (BF16C) {
+                    *reinterpret_cast<uint32_t *>(dst) = id >= 0 ? v[i] : 0u;   // bf16 rows go in as loaded
+                } else {
+                    dst[0] = id >= 0 ? v[i].x : 0.f;
+                    dst[1] = id >= 0 ? v[i].y : 0.f;
+                }
             }
         }
     }
@@ -239,9 +246,8 @@ __global__ __launch_bounds__(kBlock) void k_update(UpdateArgs a) {
                 idv = dense ? idx : a.ready[idx];
                 const int32_t deg = a.indeg ? a.indeg[idv] : 1;
                 const float fd = static_cast<float>(deg > 0 ? deg : 1);
-                // SAGE divides the sum by the in-degree; GCN multiplies by deg^-1/2;
-                // a plain linear map (model 2) leaves the row as it is
-                scalev = a.model == 0 ? fd : (a.model == 1 ? 1.0f / sqrtf(fd) : 1.0f);
+                // SAGE: mean = sum * (1/deg); GCN: deg^-1/2; a plain linear map (model 2): 1
+                scalev = a.model == 0 ? 1.0f / fd : (a.model == 1 ? 1.0f / sqrtf(fd) : 1.0f);
             }
             ids[w * kRows + lane] = idv;
         }
