@@ -193,3 +193,36 @@ def test_zero_vertices(atlas):
     assert atlas.atlas_flush_ready(h, out, count=True) == 0
     st = atlas.atlas_layer_finish(h)
     assert st["vertices_flushed"] == 0 and st["edges_processed"] == 0
+
+
+@pytest.mark.parametrize("model", ["sage", "gcn"])
+@pytest.mark.parametrize("plan", [False, True], ids=["csr_stream", "planned"])
+def test_accumulators_alone(oracle, H, atlas, model, plan):
+    """The scatter-aggregate step on its own: after all chunks (and before any
+    update) the fp32 accumulators equal the oracle's neighbour sums."""
+    dev = torch.device("cuda:0")
+    g = gen.rmat_graph(SEED + 30, 12, 16, self_loops=(model == "gcn"))
+    case = H.make_case(model, g, SEED + 30, [128, 64], 500, feat="normal")
+    off, col, X = case.off.to(dev), case.col.to(dev), case.X.to(dev)
+    n, e = case.n, case.e
+    plan_h = atlas.atlas_plan_create(atlas.make_graph(n, e, off, col), 500) if plan else None
+    graph = atlas.make_graph(n, e, off, col, None, atlas.RESIDENT_DEVICE, plan_h)
+    p = case.layers[0]
+    W, b = p.W.float().to(dev).contiguous(), p.bias.float().to(dev).contiguous()
+    h = atlas.atlas_layer_init(graph, atlas.make_dims(H.MODEL_ID[model], 128, 64, 0, 0, 0, 500),
+                               atlas.make_weights(W, b, atlas.DTYPE_F32))
+    for b0 in range(0, n, 500):
+        atlas.atlas_broadcast_chunk(h, b0, min(n, b0 + 500), X[b0:b0 + 500])
+    acc = np.empty((n, 128), dtype=np.float32)
+    atlas.atlas_debug_copy(h, atlas.DBG_ACC, acc)
+    out = torch.empty((n, 64), device=dev)
+    atlas.atlas_flush_ready(h, out)
+    atlas.atlas_layer_finish(h)
+    if plan_h:
+        atlas.atlas_plan_destroy(plan_h)
+    il = oracle.InLists.from_csr(case.off.numpy(), case.col.numpy())
+    scale = None
+    if model == "gcn":      # the source side of the symmetric normalisation is applied while pushing
+        scale = 1.0 / np.sqrt(oracle.in_degree(n, case.col.numpy()).astype(np.float64))
+    ref = oracle.neighbor_sum(il, case.X.numpy(), scale)
+    assert H.row_rel_err(acc.astype(np.float64), ref) <= 1e-5

@@ -26,6 +26,7 @@ def _go(oracle, H, wl, plan=True, emb_resident=False, n_random=1 << 14):
     print("%s plan=%s: sampled %d destinations / %d in-edges, error %.3e" % (wl.name, plan, nd, ne, err))
     del out
     torch.cuda.empty_cache()
+    H.atlas.atlas_release_cache()
 
 
 def test_config1_full(oracle, H):
