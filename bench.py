@@ -144,7 +144,8 @@ def main() -> int:
         d_in, d_out = wl.dims[li], wl.dims[li + 1]
         act = atlas.ACT_NONE if li + 1 == len(wl.layers) else between
         dims = atlas.make_dims(model_id, d_in, d_out, sdt, sdt, act, chunk, heads=wl.heads,
-                               flags=(atlas.FLAG_TIMING if timing else 0) | atlas.FLAG_EMB_RESIDENT)
+                               flags=(atlas.FLAG_TIMING if timing else 0) | atlas.FLAG_EMB_RESIDENT |
+                               (atlas.FLAG_PLANNED_ONLY if plan is not None else 0))
         W, b = params[li]
         h = atlas.atlas_layer_init(graph, dims, atlas.make_weights(W, b, sdt, attn[li][0], attn[li][1]), stream)
         out = outs[li]

@@ -56,12 +56,20 @@ enum atlas_dtype { ATLAS_DTYPE_F32 = 0, ATLAS_DTYPE_BF16 = 1 };
 enum atlas_activation { ATLAS_ACT_NONE = 0, ATLAS_ACT_RELU = 1, ATLAS_ACT_ELU = 2 };
 enum atlas_flags {
     ATLAS_FLAG_TIMING = 1,       /* record per-stage GPU time with HIP events                  */
-    ATLAS_FLAG_EMB_RESIDENT = 2  /* DEVICE graphs, SAGE_MEAN: the caller promises that every
+    ATLAS_FLAG_EMB_RESIDENT = 2, /* DEVICE graphs, SAGE_MEAN: the caller promises that every
                                     `emb` given to atlas_broadcast_chunk is the row range
                                     [src_begin, src_end) of ONE contiguous N x d_in matrix that
                                     stays valid until atlas_layer_finish; the library then reads
                                     a vertex's own row from that matrix instead of keeping a
                                     copy (E_STATE if two chunks disagree about the matrix base) */
+    ATLAS_FLAG_PLANNED_ONLY = 4  /* SAGE_MEAN / GCN_SYM on a graph with a plan: the caller promises
+                                    that every chunk coincides with a planned chunk
+                                    (atlas_broadcast_chunk returns E_RANGE otherwise).  The layer
+                                    then skips the zero fill of the accumulators: a row is first
+                                    written by its destination's first group, and the accumulator
+                                    of a vertex without in-edges is never read.  Ignored without
+                                    a plan and for GAT.  With it, ATLAS_DBG_ACC rows of vertices
+                                    that have received nothing yet are undefined. */
 };
 
 /* The graph: CSR by SOURCE vertex (paper Sec. 3.2: out-edges, read sequentially

@@ -22,6 +22,7 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 ACT_NONE, ACT_RELU, ACT_ELU = 0, 1, 2
 FLAG_TIMING = 1
 FLAG_EMB_RESIDENT = 2
+FLAG_PLANNED_ONLY = 4
 DBG_INDEG, DBG_PENDING, DBG_READY, DBG_READY_COUNT, DBG_ACC = range(5)
 
 EXPORTS = [

@@ -123,6 +123,7 @@ struct atlas_layer {
     const int32_t *indeg = nullptr;
     const int64_t *off_dev = nullptr;  // device-visible row offsets
 
+    bool planned_only = false;         // every chunk runs from the plan: no accumulator zero fill
     bool emb_resident = false;         // own rows are read from the caller's matrix
     const char *x_base = nullptr;      // base of that matrix (set by the first chunk)
 
@@ -221,7 +222,14 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
     HIP_TRY(L->packed_w.alloc(packed_weight_bytes(L->K, d.d_out, L->compute_bf16)));
     HIP_TRY(launch_fill_zero(L->counters.p, L->counters.bytes, s));
     HIP_TRY(launch_fill_zero(L->counters64.p, L->counters64.bytes, s));
-    HIP_TRY(launch_fill_zero(L->acc.p, static_cast<size_t>(n) * L->acc_width * sizeof(float), s));
+    // With ATLAS_FLAG_PLANNED_ONLY every row is first written (not added to) by
+    // its destination's first group, so the zero fill is skipped.  GAT rescales
+    // its accumulators and keeps the fill.
+    L->planned_only = (d.flags & ATLAS_FLAG_PLANNED_ONLY) && L->g.plan && d.model != ATLAS_MODEL_GAT &&
+                      L->g.plan->host == (L->g.residency == ATLAS_RESIDENT_PINNED_HOST) &&
+                      L->g.plan->n == n && L->g.plan->e == L->e;
+    if (!L->planned_only)
+        HIP_TRY(launch_fill_zero(L->acc.p, static_cast<size_t>(n) * L->acc_width * sizeof(float), s));
 
     if (L->g.residency == ATLAS_RESIDENT_PINNED_HOST) {
         // row offsets are small next to the edge array: keep a device copy for the kernels
@@ -403,6 +411,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
     if (plan && plan->chunk > 0 && src_begin % plan->chunk == 0 &&
         src_end == std::min(L->n, src_begin + plan->chunk))
         pc = &plan->chunks[static_cast<size_t>(src_begin / plan->chunk)];
+    if (L->planned_only && !pc) return ATLAS_E_RANGE;  // the layer promised planned chunks only
     GroupedArgs ga{};
 
     int slot = -1;
@@ -518,6 +527,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
     }
     if ((rc = start_span(L, L->t_agg, s)) != ATLAS_OK) return rc;
     if (pc) {
+        if (L->planned_only) HIP_TRY(launch_zero_cut_first_rows(ga, s));
         HIP_TRY(launch_aggregate_grouped(ga, s));
     } else {
         HIP_TRY(launch_aggregate(a, s));
@@ -651,6 +661,13 @@ int atlas_plan_create(const atlas_graph_t *graph, int64_t chunk_sources, atlas_p
         if (P->host) { *v = graph->row_offsets[u]; return hipSuccess; }
         return hipMemcpy(v, graph->row_offsets + u, sizeof(int64_t), hipMemcpyDeviceToHost);
     };
+    uint8_t *seen = nullptr;  // first-touch map of the whole plan
+    if (rc == ATLAS_OK) {
+        const size_t nb = static_cast<size_t>(std::max<int64_t>(P->n, 1));
+        if ((e = hipMalloc(reinterpret_cast<void **>(&seen), nb)) != hipSuccess ||
+            (e = hipMemset(seen, 0, nb)) != hipSuccess)
+            rc = hip_fail(e, "alloc(plan first-touch map)");
+    }
     int64_t ebeg = 0;
     if (rc == ATLAS_OK && nchunks > 0 && (e = offset_at(0, &ebeg)) != hipSuccess) rc = hip_fail(e, "row_offsets");
     for (int64_t k = 0; rc == ATLAS_OK && k < nchunks; ++k) {
@@ -661,7 +678,7 @@ int atlas_plan_create(const atlas_graph_t *graph, int64_t chunk_sources, atlas_p
         PlanChunk pc;
         if (!P->host) {
             e = build_plan_chunk(graph->row_offsets, graph->col_indices, P->n, b, en, ebeg, eend,
-                                 P->src_sorted + ebeg, &pc);
+                                 P->src_sorted + ebeg, seen, &pc);
             if (e != hipSuccess) { rc = hip_fail(e, "build_plan_chunk"); break; }
         } else {
             // stage the chunk's CSR slice into HBM, regroup there, bring the result back
@@ -674,7 +691,7 @@ int atlas_plan_create(const atlas_graph_t *graph, int64_t chunk_sources, atlas_p
                 (e = hipMalloc(reinterpret_cast<void **>(&src_tmp), ne1 * 4)) == hipSuccess &&
                 (e = hipMemcpy(off_tmp, graph->row_offsets + b, (nsrc + 1) * sizeof(int64_t), hipMemcpyHostToDevice)) == hipSuccess &&
                 (ne == 0 || (e = hipMemcpy(col_tmp, graph->col_indices + ebeg, static_cast<size_t>(ne) * 4, hipMemcpyHostToDevice)) == hipSuccess)) {
-                e = build_plan_chunk(off_tmp - b, col_tmp - ebeg, P->n, b, en, ebeg, eend, src_tmp, &pc);
+                e = build_plan_chunk(off_tmp - b, col_tmp - ebeg, P->n, b, en, ebeg, eend, src_tmp, seen, &pc);
                 if (e == hipSuccess && ne > 0)
                     e = hipMemcpy(P->src_sorted + ebeg, src_tmp, static_cast<size_t>(ne) * 4, hipMemcpyDeviceToHost);
                 if (e == hipSuccess && ne > 0) {
@@ -703,6 +720,7 @@ int atlas_plan_create(const atlas_graph_t *graph, int64_t chunk_sources, atlas_p
         P->max_stage_bytes = std::max(P->max_stage_bytes, stage_bytes_of(pc));
         ebeg = eend;
     }
+    if (seen) (void)hipFree(seen);
     if (rc != ATLAS_OK) {
         atlas_plan_destroy(P);
         return rc;

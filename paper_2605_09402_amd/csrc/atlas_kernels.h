@@ -58,7 +58,8 @@ struct PlanChunk {
     int64_t edge_base = 0;      // first edge of the chunk in CSR numbering
     int64_t n_edges = 0;
     int64_t n_groups = 0;       // distinct destinations the chunk sends to
-    int32_t *grp_dst = nullptr;   // [n_groups] destination of each group, ascending
+    int32_t *grp_dst = nullptr;   // [n_groups] destination of each group, ascending; bit 31 set when no
+                                  // earlier chunk sends to that destination (its first group of the layer)
     int32_t *tile_grp = nullptr;  // [ceil(n_edges/64)] group of the first edge of every 64-edge tile
 };
 
@@ -88,11 +89,12 @@ hipError_t launch_aggregate_grouped(const GroupedArgs &a, hipStream_t s);
 
 // Plan construction for one chunk (synchronous).  off_dev is addressed by global
 // source id and col_dev by global edge number (only [src_begin, src_end] and
-// [edge_begin, edge_end) are touched); src_sorted receives the chunk's
+// [edge_begin, edge_end) are touched); `seen` is the plan-wide N-byte first-touch map
+// (zeroed before the first chunk, chunks built in streaming order); src_sorted receives the chunk's
 // edge_end - edge_begin entries; grp_dst and tile_grp are allocated with hipMalloc.
 hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int64_t n, int64_t src_begin,
                             int64_t src_end, int64_t edge_begin, int64_t edge_end, int32_t *src_sorted,
-                            PlanChunk *out);
+                            uint8_t *seen, PlanChunk *out);
 
 // GAT, per chunk: raise m_next[v][h] to the largest logit any edge of the chunk
 // sends to v (CSR order), then bring every destination whose maximum moved to
@@ -119,6 +121,11 @@ struct GatFinalizeArgs {
     int64_t n;
 };
 hipError_t launch_gat_finalize(const GatFinalizeArgs &a, hipStream_t s);
+
+// Planned-only layers skip the accumulator zero fill: rows are first written by
+// their first group.  A first group cut by a tile boundary is added with
+// atomics from several tiles, so its row is zeroed here before the chunk runs.
+hipError_t launch_zero_cut_first_rows(const GroupedArgs &a, hipStream_t s);
 
 // SAGE self message of sources [b, e): pending[u] -= 1 with ready compaction.
 hipError_t launch_self_message(int64_t b, int64_t e, int32_t *pending, int32_t *ready,

@@ -336,6 +336,20 @@ __device__ __forceinline__ void row_add_owned(float *p, const float (&x)[VPL]) {
 }
 
 template <int VPL>
+__device__ __forceinline__ void row_store(float *p, const float (&x)[VPL]) {
+    if constexpr (VPL == 2) {
+        *reinterpret_cast<float2 *>(p) = make_float2(x[0], x[1]);
+    } else if constexpr (VPL == 4 || VPL == 8) {
+#pragma unroll
+        for (int q = 0; q < VPL / 4; ++q)
+            *reinterpret_cast<float4 *>(p + 4 * q) = make_float4(x[4 * q], x[4 * q + 1], x[4 * q + 2], x[4 * q + 3]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) p[i] = x[i];
+    }
+}
+
+template <int VPL>
 __device__ __forceinline__ void row_add_shared(float *p, const float (&x)[VPL]) {
 #pragma unroll
     for (int i = 0; i < VPL; ++i) unsafeAtomicAdd(p + i, x[i]);
@@ -374,7 +388,13 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
         const uint64_t below = endmask & ((1ull << lane) - 1ull);
         const bool closes = is_end || lane == cnt - 1;  // last edge of a group, or of the tile
         int32_t dstv = 0;
-        if (closes) dstv = a.grp_dst[g0 + __popcll(below)];
+        bool first_touch = false;  // no earlier chunk sent to this destination: its row holds nothing yet
+        if (closes) {
+            const int32_t gd = a.grp_dst[g0 + __popcll(below)];
+            first_touch = gd < 0;
+            dstv = gd & 0x7fffffff;
+        }
+        const uint64_t firstmask = __ballot(first_touch);
         float gs = 1.f;
         if (MODEL == 1 && lane < cnt) {  // GCN: source side of the symmetric normalisation
             const int32_t du = a.indeg[src];
@@ -427,6 +447,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
                         const int32_t v = __builtin_amdgcn_readlane(dstv, j);
                         float *dst = a.acc + static_cast<int64_t>(v) * D + lane * VPL;
                         if (cut) row_add_shared<VPL>(dst, sum);
+                        else if (MODEL != 2 && ((firstmask >> j) & 1ull)) row_store<VPL>(dst, sum);
                         else row_add_owned<VPL>(dst, sum);
                         if (MODEL == 2 && head_first) {
                             float *lp = a.gat.l + static_cast<int64_t>(v) * a.gat.heads + hl;
@@ -495,7 +516,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_group_max(GroupedArgs a) {
         const uint64_t below = endmask & ((1ull << lane) - 1ull);
         const bool closes = is_end || lane == cnt - 1;
         int32_t dstv = 0;
-        if (closes) dstv = a.grp_dst[g0 + __popcll(below)];
+        if (closes) dstv = a.grp_dst[g0 + __popcll(below)] & 0x7fffffff;
         // my edge's destination is held by the lane that closes my group
         const uint64_t rest = endmask >> lane;
         int closer = rest ? lane + __ffsll(static_cast<unsigned long long>(rest)) - 1 : cnt - 1;
@@ -517,6 +538,31 @@ __global__ __launch_bounds__(kBlock) void k_gat_group_max(GroupedArgs a) {
                 if (shared) atomicMax(m, enc);
                 else if (enc > *m) *m = enc;
             }
+        }
+    }
+}
+
+// One lane per tile boundary: if the boundary cuts a group and that group is
+// its destination's first, the wave zeroes the destination's row together
+// (see launch_zero_cut_first_rows).
+__global__ __launch_bounds__(kBlock) void k_zero_cut_first_rows(GroupedArgs a) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t ntiles = (a.n_edges + kTileEdges - 1) / kTileEdges;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    // every lane of a wave runs the same number of rounds (t0 is wave-uniform)
+    for (int64_t t0 = 1 + static_cast<int64_t>(blockIdx.x) * kBlock + (threadIdx.x & ~(kWave - 1)); t0 < ntiles;
+         t0 += stride) {
+        const int64_t t = t0 + lane;
+        int32_t gd = 0;
+        if (t < ntiles && a.src_sorted[t * kTileEdges - 1] >= 0)  // the previous tile ends inside a group
+            gd = a.grp_dst[a.tile_grp[t]];                        // group of the tile's first edge = the cut one
+        uint64_t todo = __ballot(gd < 0);
+        while (todo) {
+            const int j = __ffsll(static_cast<unsigned long long>(todo)) - 1;
+            todo &= todo - 1;
+            const int64_t v = __builtin_amdgcn_readlane(gd, j) & 0x7fffffff;
+            float *row = a.acc + v * a.d;
+            for (int c = lane; c < a.d; c += kWave) row[c] = 0.f;
         }
     }
 }
@@ -572,6 +618,16 @@ hipError_t launch_aggregate(const AggregateArgs &a, hipStream_t s) {
         return a.model == 1 ? launch_vpl<uint16_t, 1>(a, grid, s) : launch_vpl<uint16_t, 0>(a, grid, s);
     }
     return a.model == 1 ? launch_vpl<float, 1>(a, grid, s) : launch_vpl<float, 0>(a, grid, s);
+}
+
+hipError_t launch_zero_cut_first_rows(const GroupedArgs &a, hipStream_t s) {
+    const int64_t ntiles = (a.n_edges + kTileEdges - 1) / kTileEdges;
+    if (ntiles <= 1) return hipSuccess;
+    int64_t blocks = (ntiles + kBlock - 1) / kBlock;
+    const int cap = persistent_grid(8);
+    if (blocks > cap) blocks = cap;
+    hipLaunchKernelGGL(k_zero_cut_first_rows, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, s, a);
+    return hipGetLastError();
 }
 
 hipError_t launch_gat_group_max(const GroupedArgs &a, hipStream_t s) {

@@ -10,7 +10,8 @@
 //   2. stable radix sort of (destination, source) pairs by destination;
 //   3. group heads / tails: bit 31 of the stored source id marks the last edge
 //      of a destination's group, a prefix sum of the heads numbers the groups;
-//   4. grp_dst[g] = destination of group g, tile_grp[t] = group of edge 64 t.
+//   4. grp_dst[g] = destination of group g (bit 31: the destination's first group in
+//      the whole stream), tile_grp[t] = group of edge 64 t.
 #include "atlas_kernels.h"
 
 #include <hip/hip_runtime.h>
@@ -49,12 +50,20 @@ __global__ void k_mark_groups(const uint32_t *__restrict__ dst_sorted, int64_t n
 }
 
 // gidx = inclusive prefix sum of heads (group number + 1).
+// `seen[v]` says whether an earlier chunk of the plan already sends to v; a
+// group that is its destination's first gets bit 31 of grp_dst (chunks are
+// planned in streaming order and a destination has one group per chunk).
 __global__ void k_emit_groups(const uint32_t *__restrict__ dst_sorted, const uint32_t *__restrict__ gidx,
-                              int64_t n_edges, int32_t *grp_dst, int32_t *tile_grp) {
+                              int64_t n_edges, int32_t *grp_dst, int32_t *tile_grp, uint8_t *seen) {
     const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
     if (i >= n_edges) return;
     const uint32_t g = gidx[i] - 1u;
-    if (i == 0 || gidx[i - 1] != gidx[i]) grp_dst[g] = static_cast<int32_t>(dst_sorted[i]);
+    if (i == 0 || gidx[i - 1] != gidx[i]) {
+        const uint32_t v = dst_sorted[i];
+        const bool first = seen[v] == 0;
+        seen[v] = 1;
+        grp_dst[g] = static_cast<int32_t>(first ? (v | 0x80000000u) : v);
+    }
     if ((i & 63) == 0) tile_grp[i >> 6] = static_cast<int32_t>(g);
 }
 
@@ -66,7 +75,7 @@ struct MaxOp {
 
 hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int64_t n, int64_t src_begin,
                             int64_t src_end, int64_t edge_begin, int64_t edge_end, int32_t *src_sorted,
-                            PlanChunk *out) {
+                            uint8_t *seen, PlanChunk *out) {
     *out = PlanChunk{};
     out->edge_base = edge_begin;
     out->n_edges = edge_end - edge_begin;
@@ -118,7 +127,7 @@ hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int6
     if ((err = hipMalloc(&out->grp_dst, static_cast<size_t>(last) * 4)) != hipSuccess) goto done;
     if ((err = hipMalloc(&out->tile_grp, static_cast<size_t>((ne + 63) / 64) * 4)) != hipSuccess) goto done;
     hipLaunchKernelGGL(k_emit_groups, dim3(blocks_for(ne)), dim3(kBlock), 0, nullptr, dst_sorted,
-                       reinterpret_cast<const uint32_t *>(tmp_src), ne, out->grp_dst, out->tile_grp);
+                       reinterpret_cast<const uint32_t *>(tmp_src), ne, out->grp_dst, out->tile_grp, seen);
     if ((err = hipGetLastError()) != hipSuccess) goto done;
     err = hipStreamSynchronize(nullptr);
 done:

@@ -145,7 +145,7 @@ __device__ __forceinline__ float2 own_to_f32(float2 v) { return v; }
 
 template <bool BF16C>
 __device__ __forceinline__ void gather_rows(const UpdateArgs &a, typename Elem<BF16C>::type *A, int stride,
-                                            int w, int lane, int32_t idv, float scalev) {
+                                            int w, int lane, int32_t idv, float scalev, int has_aggv) {
     constexpr int kRows = kTileRows / 4;  // rows per wave
     const int d = a.d_in;
     const int segs = (d + 127) >> 7;
@@ -173,7 +173,8 @@ __device__ __forceinline__ void gather_rows(const UpdateArgs &a, typename Elem<B
             const float g = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(scalev), rr));
             if (col < d) {
                 typename Elem<BF16C>::type *dst = A + (w * kRows + rr) * stride + acc_base + col;
-                const float x = id >= 0 ? v[i].x * g : 0.f, y = id >= 0 ? v[i].y * g : 0.f;
+                const bool has_agg = id >= 0 && __builtin_amdgcn_readlane(has_aggv, rr) != 0;
+                const float x = has_agg ? v[i].x * g : 0.f, y = has_agg ? v[i].y * g : 0.f;
                 if constexpr (BF16C) {
                     *reinterpret_cast<uint32_t *>(dst) = pack_bf16x2(x, y);
                 } else {
@@ -240,18 +241,20 @@ __global__ __launch_bounds__(kBlock) void k_update(UpdateArgs a) {
         // ---- gather: wave w stages rows w*16 .. w*16+15; lane r holds row r's id ----
         int32_t idv = -1;
         float scalev = 1.f;
+        bool idv_has_agg = true;
         if (lane < kRows) {
             const int idx = head + tile * kTileRows + w * kRows + lane;
             if (idx < tail) {
                 idv = dense ? idx : a.ready[idx];
                 const int32_t deg = a.indeg ? a.indeg[idv] : 1;
+                if (deg <= 0) idv_has_agg = false;   // accumulator never written: aggregate is zero
                 const float fd = static_cast<float>(deg > 0 ? deg : 1);
                 // SAGE: mean = sum * (1/deg); GCN: deg^-1/2; a plain linear map (model 2): 1
                 scalev = a.model == 0 ? 1.0f / fd : (a.model == 1 ? 1.0f / sqrtf(fd) : 1.0f);
             }
             ids[w * kRows + lane] = idv;
         }
-        gather_rows<BF16C>(a, A, stride, w, lane, idv, scalev);
+        gather_rows<BF16C>(a, A, stride, w, lane, idv, scalev, idv_has_agg ? 1 : 0);
         __syncthreads();
 
         // ---- MFMA: pairs (mb, nb) p = w + 4*i ----
@@ -360,7 +363,9 @@ __device__ __forceinline__ void pipe_store_rows(const UpdateArgs &a, typename El
         const float g = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(scalev), i));
         const bool live = __builtin_amdgcn_readlane(idv, i) >= 0;
         typename Elem<BF16C>::type *row = A + (w * kPipeRows + i) * stride;
-        const float ax = live ? r.acc[i].x * g : 0.f, ay = live ? r.acc[i].y * g : 0.f;
+        // a vertex without in-edges never had its accumulator written: its aggregate is zero
+        const bool has_agg = live && __builtin_amdgcn_readlane(degv, i) > 0;
+        const float ax = has_agg ? r.acc[i].x * g : 0.f, ay = has_agg ? r.acc[i].y * g : 0.f;
         const int acc_col = a.model == 0 ? d + col : col;
         if constexpr (BF16C) {
             // bf16 own rows go to LDS as they were loaded; the aggregate is rounded once

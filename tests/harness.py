@@ -81,9 +81,12 @@ def _dt(store: torch.dtype) -> int:
 
 def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, flush_every: int = 1,
             give_indeg: bool = False, timing: bool = False, max_layers: Optional[int] = None,
-            plan: bool = False, plan_chunk: Optional[int] = None, emb_resident: bool = False) -> GpuRun:
+            plan: bool = False, plan_chunk: Optional[int] = None, emb_resident: bool = False,
+            planned_only: bool = False) -> GpuRun:
     """Drive all layers through the C ABI.  With pinned_host the graph and the
-    layer-0 features stay in pinned host memory and are staged by the library."""
+    layer-0 features stay in pinned host memory and are staged by the library.
+    planned_only sets ATLAS_FLAG_PLANNED_ONLY (no zero fill of the accumulators;
+    the buffers then still hold whatever the previous layer or test left there)."""
     dev = torch.device("cuda:0")
     n, e = case.n, case.e
     run = GpuRun()
@@ -119,7 +122,8 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
         a_d = None if p.attn_dst is None else p.attn_dst.to(case.store).to(dev).contiguous()
         dims = atlas.make_dims(MODEL_ID[case.model], d_in, d_out, sdt, sdt, act, case.chunk, heads=case.heads,
                                neg_slope=case.slope, flags=(atlas.FLAG_TIMING if timing else 0) |
-                               (atlas.FLAG_EMB_RESIDENT if emb_resident else 0))
+                               (atlas.FLAG_EMB_RESIDENT if emb_resident else 0) |
+                               (atlas.FLAG_PLANNED_ONLY if planned_only else 0))
         weights = atlas.make_weights(W, b, sdt, a_s, a_d)
         h = atlas.atlas_layer_init(graph, dims, weights, stream)
         out = torch.full((max(n, 1), d_out), float("nan"), dtype=case.store, device=dev)
@@ -241,7 +245,7 @@ def gpu_reorder(off, col):
     return new_of_old
 
 
-def run_workload_layer1(wl, plan: bool, emb_resident: bool = False):
+def run_workload_layer1(wl, plan: bool, emb_resident: bool = False, planned_only: bool = False):
     """Layer 1 of a device-resident workload through the C ABI, flush after
     every chunk.  Returns (out, stats, indeg, final pending, ready list)."""
     dev = wl.off.device
@@ -258,7 +262,8 @@ def run_workload_layer1(wl, plan: bool, emb_resident: bool = False):
     a_d = None if p.attn_dst is None else p.attn_dst.to(wl.store).to(dev).contiguous()
     act = {"relu": atlas.ACT_RELU, "elu": atlas.ACT_ELU}[wl.act] if len(wl.layers) > 1 else atlas.ACT_NONE
     dims = atlas.make_dims(MODEL_ID[wl.model], wl.dims[0], wl.dims[1], sdt, sdt, act, wl.chunk, heads=wl.heads,
-                           flags=atlas.FLAG_EMB_RESIDENT if emb_resident else 0)
+                           flags=(atlas.FLAG_EMB_RESIDENT if emb_resident else 0) |
+                           (atlas.FLAG_PLANNED_ONLY if planned_only else 0))
     h = atlas.atlas_layer_init(graph, dims, atlas.make_weights(W, b, sdt, a_s, a_d))
     out = torch.full((n, wl.dims[1]), float("nan"), dtype=wl.store, device=dev)
     if wl.model == "gat":

@@ -59,7 +59,7 @@ def test_gcn_rmat_fp32(oracle, H, order, plan):
         X = gen.permute_rows(X, torch.from_numpy(ref_new.astype(np.int64)))
     case = H.make_case("gcn", g, SEED + 2, [128, 128, 64], 1 << 10, feat="normal")
     case.X = X
-    run = H.run_gpu(case, snapshots=True, plan=plan)
+    run = H.run_gpu(case, snapshots=True, plan=plan, planned_only=plan and order == "random")
     H.check_integers(oracle, case, run)
     print("gcn", order, H.check_outputs(oracle, case, run))
 
@@ -83,7 +83,7 @@ def test_sage_degree_ordered_bf16_d128(oracle, H, plan):
     new_of_old, _ = oracle.reorder_indegree_desc(oracle.in_degree(g.n, col.numpy()))
     g = g.with_relabel(torch.from_numpy(new_of_old.astype(np.int64)))
     case = H.make_case("sage", g, SEED + 5, [128, 128, 128, 64], 1 << 10, store=torch.bfloat16)
-    run = H.run_gpu(case, give_indeg=True, flush_every=4, plan=plan, emb_resident=plan)
+    run = H.run_gpu(case, give_indeg=True, flush_every=4, plan=plan, emb_resident=plan, planned_only=plan)
     print("sage s14 degree ordered", H.check_outputs(oracle, case, run))
     for st in run.stats:
         assert st["edges_processed"] == case.e and st["vertices_flushed"] == case.n
