@@ -17,6 +17,7 @@
 #include "atlas_kernels.h"
 
 #include <hip/hip_runtime.h>
+#include <type_traits>
 
 namespace atlas {
 namespace {
@@ -94,22 +95,32 @@ __device__ __forceinline__ float apply_activation(float y, int act) {
 // operand): lane l then holds, for tile row l%32, the sixteen output columns
 // nbase + 8q + t (q, t < 4) with nbase = 32 nb + 4 (l/32) -- four runs of four
 // consecutive columns, written as 8-byte (bf16) or 16-byte (fp32) stores.
+template <bool ADD_BIAS>
 __device__ __forceinline__ void store_block_row(const UpdateArgs &a, const f32x16_t &c, int64_t out_row,
-                                                int nbase, const float (&bias16)[16]) {
+                                                int nbase, const float *bias16) {
+    float y[16];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int n = nbase + 8 * q;
-        if (n >= a.d_out) continue;
-        float y[4];
+    for (int r = 0; r < 16; ++r) y[r] = ADD_BIAS ? c[r] + bias16[r] : c[r];
+    if (a.activation == 1) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) y[t] = apply_activation(c[4 * q + t] + bias16[4 * q + t], a.activation);
-        const int64_t o = out_row * a.d_out + n;
-        if (a.out_bf16) {
-            const uint2 v = make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
-            *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(a.out) + o) = v;
-        } else {
-            *reinterpret_cast<float4 *>(static_cast<float *>(a.out) + o) = make_float4(y[0], y[1], y[2], y[3]);
-        }
+        for (int r = 0; r < 16; ++r) y[r] = fmaxf(y[r], 0.f);
+    } else if (a.activation == 2) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) y[r] = y[r] > 0.f ? y[r] : expm1f(y[r]);
+    }
+    if (a.out_bf16) {
+        uint16_t *o = static_cast<uint16_t *>(a.out) + out_row * a.d_out + nbase;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (nbase + 8 * q < a.d_out)
+                *reinterpret_cast<uint2 *>(o + 8 * q) =
+                    make_uint2(pack_bf16x2(y[4 * q], y[4 * q + 1]), pack_bf16x2(y[4 * q + 2], y[4 * q + 3]));
+    } else {
+        float *o = static_cast<float *>(a.out) + out_row * a.d_out + nbase;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (nbase + 8 * q < a.d_out)
+                *reinterpret_cast<float4 *>(o + 8 * q) = make_float4(y[4 * q], y[4 * q + 1], y[4 * q + 2], y[4 * q + 3]);
     }
 }
 
@@ -160,7 +171,9 @@ __device__ __forceinline__ void gather_rows(const UpdateArgs &a, typename Elem<B
             const int rr = item / segs;
             const int col = (item - rr * segs) * 128 + col_in_seg;
             const int32_t id = __builtin_amdgcn_readlane(idv, rr);
-            const int64_t o = static_cast<int64_t>(id >= 0 ? id : 0) * d + (col < d ? col : 0);
+            // rows past the list's end and vertices without in-edges read row 0 (value unused)
+            const bool fetch = id >= 0 && __builtin_amdgcn_readlane(has_aggv, rr) != 0;
+            const int64_t o = static_cast<int64_t>(fetch ? id : 0) * d + (col < d ? col : 0);
             v[i] = *reinterpret_cast<const float2 *>(a.acc + o);
         }
 #pragma unroll
@@ -309,7 +322,7 @@ __global__ __launch_bounds__(kBlock) void k_update(UpdateArgs a) {
             if (id < 0) continue;
             float bias16[16];
             load_bias16(a, nb * 32 + 4 * (lane >> 5), bias16);
-            store_block_row(a, c[i], id, nb * 32 + 4 * (lane >> 5), bias16);
+            store_block_row<true>(a, c[i], id, nb * 32 + 4 * (lane >> 5), bias16);
         }
     }
 }
@@ -322,67 +335,157 @@ __global__ __launch_bounds__(kBlock) void k_update(UpdateArgs a) {
 // already in flight into registers and the ready ids of tile t+2 are being
 // fetched, so the gather latency is hidden behind the contraction instead of
 // being exposed once per tile.
+//
+// With two waves per SIMD the kernel is bound by instruction issue long before
+// the matrix cores or HBM are busy, so the staging code is written for few
+// vector instructions per row: half a wave covers a row (16 bytes of the
+// accumulator and 8 or 16 bytes of the own row per lane, two rows per load
+// instruction), per-row values sit in the lanes of a quad and are spread with
+// DPP quad broadcasts, the bias is the initial value of the MFMA accumulator,
+// and the k-loop is fully unrolled so every LDS read has an immediate offset.
 constexpr int kPipeBlock = 512;
 constexpr int kPipeRows = kTileRows / (kPipeBlock / 64);  // rows staged per wave = 8
+constexpr int kPipeIters = kPipeRows / 2;                 // two rows per load instruction
+
+template <bool BF16C> struct OwnRaw4 { using type = float4; };
+template <> struct OwnRaw4<true> { using type = uint2; };
 
 template <bool BF16C>
 struct RowRegs {
-    float2 acc[kPipeRows];
-    typename OwnRaw<BF16C>::type own[kPipeRows];
+    float4 acc[kPipeIters];
+    typename OwnRaw4<BF16C>::type own[kPipeIters];
 };
 
-// Issue the loads of the wave's 8 rows.  Straight-line code: rows past the end
-// of the ready list read row 0 and are dropped when the tile is stored.
-template <bool BF16C>
-__device__ __forceinline__ void pipe_issue_rows(const UpdateArgs &a, int32_t idv, int lane, RowRegs<BF16C> &r,
-                                                int32_t &degv) {
-    const int d = a.d_in;
-    const int col = lane * 2 < d ? lane * 2 : 0;
-    degv = a.indeg ? a.indeg[idv >= 0 ? idv : 0] : 1;
-#pragma unroll
-    for (int i = 0; i < kPipeRows; ++i) {
-        const int32_t id = __builtin_amdgcn_readlane(idv, i);
-        const int64_t o = static_cast<int64_t>(id >= 0 ? id : 0) * d + col;
-        r.acc[i] = *reinterpret_cast<const float2 *>(a.acc + o);
-        if (a.model == 0) r.own[i] = load_own<BF16C>(a.self_rows, o);
+template <int CTRL>
+__device__ __forceinline__ int32_t dpp_quad(int32_t v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+// value held by lane (quad base + i) of every lane's quad; i is a constant after unrolling
+__device__ __forceinline__ int32_t quad_bcast(int32_t v, int i) {
+    switch (i) {
+        case 0: return dpp_quad<0x00>(v);
+        case 1: return dpp_quad<0x55>(v);
+        case 2: return dpp_quad<0xAA>(v);
+        default: return dpp_quad<0xFF>(v);
     }
 }
 
-template <bool BF16C>
-__device__ __forceinline__ void pipe_store_rows(const UpdateArgs &a, typename Elem<BF16C>::type *A, int stride,
-                                                int w, int lane, const RowRegs<BF16C> &r, int32_t idv,
-                                                int32_t degv) {
+// Issue the loads of the wave's 8 rows: lanes 0..31 take row 2i, lanes 32..63
+// row 2i+1 in round i.  `idv` / `degv` hold, in lane l, the values of row
+// 2 (l % 4) + l / 32.  Straight-line code: rows past the end of the ready list
+// read row 0 and are dropped when the tile is stored; so do the accumulator
+// loads of vertices without in-edges (nothing was ever added to their rows,
+// and the one shared address stays in cache).
+template <bool BF16C, bool SAGE>
+__device__ __forceinline__ void pipe_issue_rows(const UpdateArgs &a, int32_t idv, int32_t degv, int lane,
+                                                RowRegs<BF16C> &r) {
     const int d = a.d_in;
-    const int col = lane * 2;
-    const float fd = static_cast<float>(degv > 0 ? degv : 1);
-    // SAGE: mean = sum * (1/deg); GCN: deg^-1/2; plain linear map: 1
-    const float scalev = a.model == 0 ? 1.0f / fd : (a.model == 1 ? 1.0f / sqrtf(fd) : 1.0f);
-    if (col >= d) return;
+    const int c4 = (lane & 31) * 4;
+    const int col = c4 < d ? c4 : 0;
 #pragma unroll
-    for (int i = 0; i < kPipeRows; ++i) {
-        const float g = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(scalev), i));
-        const bool live = __builtin_amdgcn_readlane(idv, i) >= 0;
-        typename Elem<BF16C>::type *row = A + (w * kPipeRows + i) * stride;
-        // a vertex without in-edges never had its accumulator written: its aggregate is zero
-        const bool has_agg = live && __builtin_amdgcn_readlane(degv, i) > 0;
-        const float ax = has_agg ? r.acc[i].x * g : 0.f, ay = has_agg ? r.acc[i].y * g : 0.f;
-        const int acc_col = a.model == 0 ? d + col : col;
-        if constexpr (BF16C) {
-            // bf16 own rows go to LDS as they were loaded; the aggregate is rounded once
-            if (a.model == 0) *reinterpret_cast<uint32_t *>(row + col) = live ? r.own[i] : 0u;
-            *reinterpret_cast<uint32_t *>(row + acc_col) = pack_bf16x2(ax, ay);
-        } else {
-            if (a.model == 0) {
-                row[col] = live ? r.own[i].x : 0.f;
-                row[col + 1] = live ? r.own[i].y : 0.f;
-            }
-            row[acc_col] = ax;
-            row[acc_col + 1] = ay;
+    for (int i = 0; i < kPipeIters; ++i) {
+        const int32_t id = quad_bcast(idv, i);
+        const int32_t dg = quad_bcast(degv, i);
+        const int32_t row = id >= 0 ? id : 0;
+        const int32_t arow = dg > 0 ? row : 0;
+        r.acc[i] = *reinterpret_cast<const float4 *>(a.acc + static_cast<int64_t>(arow) * d + col);
+        if constexpr (SAGE) {
+            const int64_t o = static_cast<int64_t>(row) * d + col;
+            if constexpr (BF16C) r.own[i] = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(a.self_rows) + o);
+            else r.own[i] = *reinterpret_cast<const float4 *>(static_cast<const float *>(a.self_rows) + o);
         }
     }
 }
 
-template <bool BF16C, int PPW>
+// Normalise and convert the rows loaded by pipe_issue_rows and store them into
+// the A tile.  Rows past the end of the ready list are stored as they came:
+// a row of A only feeds the same row of the product, which is never written.
+template <bool BF16C, bool SAGE>
+__device__ __forceinline__ void pipe_store_rows(const UpdateArgs &a, typename Elem<BF16C>::type *A, int stride,
+                                                int w, int lane, const RowRegs<BF16C> &r, int32_t degv) {
+    const int d = a.d_in;
+    const int c4 = (lane & 31) * 4;
+    const float fd = static_cast<float>(degv > 0 ? degv : 1);
+    // SAGE: mean = sum * (1/deg); GCN: deg^-1/2; plain linear map: 1
+    const float scalev = a.model == 0 ? 1.0f / fd : (a.model == 1 ? 1.0f / sqrtf(fd) : 1.0f);
+    if (c4 >= d) return;
+    typename Elem<BF16C>::type *row0 = A + (w * kPipeRows + (lane >> 5)) * stride + c4 + (SAGE ? d : 0);
+#pragma unroll
+    for (int i = 0; i < kPipeIters; ++i) {
+        const float g = __uint_as_float(static_cast<uint32_t>(quad_bcast(static_cast<int32_t>(__float_as_uint(scalev)), i)));
+        // a vertex without in-edges never had its accumulator written: its aggregate is zero
+        const bool has_agg = quad_bcast(degv, i) > 0;
+        typename Elem<BF16C>::type *row = row0 + 2 * i * stride;
+        const float4 v = r.acc[i];
+        if constexpr (BF16C) {
+            const uint32_t lo = pack_bf16x2(v.x * g, v.y * g), hi = pack_bf16x2(v.z * g, v.w * g);
+            *reinterpret_cast<uint2 *>(row) = make_uint2(has_agg ? lo : 0u, has_agg ? hi : 0u);
+            // bf16 own rows go to LDS as they were loaded; the aggregate is rounded once
+            if constexpr (SAGE) *reinterpret_cast<uint2 *>(row - d) = r.own[i];
+        } else {
+            row[0] = has_agg ? v.x * g : 0.f;
+            row[1] = has_agg ? v.y * g : 0.f;
+            row[2] = has_agg ? v.z * g : 0.f;
+            row[3] = has_agg ? v.w * g : 0.f;
+            if constexpr (SAGE) {
+                row[0 - d] = r.own[i].x;
+                row[1 - d] = r.own[i].y;
+                row[2 - d] = r.own[i].z;
+                row[3 - d] = r.own[i].w;
+            }
+        }
+    }
+}
+
+// acc (+)= A[32 rows of mb] x W[32 columns of nb] over KS k-steps, as D^T.
+// KS > 0: compile-time trip count, fully unrolled (immediate LDS offsets);
+// KS == 0: run-time trip count `ks`, a multiple of 4, in groups of four whose
+// LDS reads are issued one group ahead of the matrix instructions.
+template <bool BF16C, int KS>
+__device__ __forceinline__ void contract_block(const typename Elem<BF16C>::type *arow,
+                                               const typename Elem<BF16C>::type *wfrag, int ks, f32x16_t &c) {
+    if constexpr (BF16C && KS > 0) {
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) {
+            const bf16x8_t av = *reinterpret_cast<const bf16x8_t *>(arow + kk * 16);
+            const bf16x8_t bv = *reinterpret_cast<const bf16x8_t *>(wfrag + kk * 64 * 8);
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv, av, c, 0, 0, 0);
+        }
+    } else {
+        constexpr int kUnroll = 4;
+        using frag_t = typename std::conditional<BF16C, bf16x8_t, float>::type;
+        auto load = [&](int kk, frag_t &af, frag_t &bf) {
+            if constexpr (BF16C) {
+                af = *reinterpret_cast<const bf16x8_t *>(arow + kk * 16);
+                bf = *reinterpret_cast<const bf16x8_t *>(wfrag + static_cast<size_t>(kk) * 64 * 8);
+            } else {
+                af = arow[kk * 2];
+                bf = wfrag[static_cast<size_t>(kk) * 64];
+            }
+        };
+        frag_t av[kUnroll], bv[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) load(u, av[u], bv[u]);
+        for (int kk = 0; kk < ks; kk += kUnroll) {
+            frag_t an[kUnroll], bn[kUnroll];
+            const int nxt = kk + kUnroll < ks ? kk + kUnroll : kk;  // the last group re-reads itself
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) load(nxt + u, an[u], bn[u]);
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                if constexpr (BF16C) c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv[u], av[u], c, 0, 0, 0);
+                else c = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[u], av[u], c, 0, 0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                av[u] = an[u];
+                bv[u] = bn[u];
+            }
+        }
+    }
+}
+
+template <bool BF16C, int PPW, bool SAGE>
 __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
     using elem_t = typename Elem<BF16C>::type;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -398,6 +501,7 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
     elem_t *A0 = Wl + ((w_elems + 7) & ~static_cast<size_t>(7));
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
+    const int my_row = 2 * (lane & 3) + (lane >> 5);   // the row of the wave's eight whose id this lane holds
 
     const bool dense = a.identity_rows > 0;
     const int head = dense ? 0 : a.counters[CTR_READY_HEAD];
@@ -414,61 +518,76 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
 
     auto load_ids = [&](int tile) -> int32_t {
         int32_t id = -1;
-        if (tile < ntiles && lane < kPipeRows) {
-            const int idx = head + tile * kTileRows + w * kPipeRows + lane;
+        if (tile < ntiles) {
+            const int idx = head + tile * kTileRows + w * kPipeRows + my_row;
             if (idx < tail) id = dense ? idx : a.ready[idx];
         }
         return id;
     };
+    auto load_deg = [&](int32_t id) -> int32_t { return (a.indeg && id >= 0) ? a.indeg[id] : 1; };
 
-    float bj[PPW][16];
+    // per (mb, nb) block of this wave: LDS addresses and the bias as the initial accumulator
+    f32x16_t bj[PPW];
+    int a_off[PPW];
+    const elem_t *wfrag[PPW];
 #pragma unroll
-    for (int i = 0; i < PPW; ++i) load_bias16(a, ((w + 8 * i) % NB) * 32 + 4 * (lane >> 5), bj[i]);
+    for (int i = 0; i < PPW; ++i) {
+        const int p = w + 8 * i;
+        const int nb = p % NB, mb = (p / NB) & 1;   // waves past the last block compute and discard
+        float b16[16];
+        load_bias16(a, nb * 32 + 4 * (lane >> 5), b16);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) bj[i][r] = b16[r];
+        if constexpr (BF16C) {
+            a_off[i] = (mb * 32 + (lane & 31)) * stride + (lane >> 5) * 8;
+            wfrag[i] = Wl + (static_cast<size_t>(nb) * KS * 64 + lane) * 8;
+        } else {
+            a_off[i] = (mb * 32 + (lane & 31)) * stride + (lane >> 5);
+            wfrag[i] = Wl + static_cast<size_t>(nb) * KS * 64 + lane;
+        }
+    }
 
     // Two tiles of rows are in flight in registers (r0: this workgroup's next
-    // tile, r1: the one after it) and the ready ids of the tile after those are
-    // on their way; every step stores one register set to LDS, refills it with
-    // the tile two steps ahead and runs the contraction of the stored tile.
+    // tile, r1: the one after it); the in-degrees of the tile after those and
+    // the ready ids of the one after that are on their way.  Every step stores
+    // one register set to LDS, refills it with the tile two steps ahead and
+    // runs the contraction of the stored tile.
     int tile = blockIdx.x;
     const int G = gridDim.x;
-    int32_t id0 = load_ids(tile), id1 = load_ids(tile + G), id_ahead = load_ids(tile + 2 * G);
+    int32_t id0 = load_ids(tile), id1 = load_ids(tile + G), id_a = load_ids(tile + 2 * G);
+    int32_t id_b = load_ids(tile + 3 * G);
+    int32_t deg0 = load_deg(id0), deg1 = load_deg(id1), deg_a = load_deg(id_a);
     RowRegs<BF16C> r0, r1;
-    int32_t deg0, deg1;
-    pipe_issue_rows<BF16C>(a, id0, lane, r0, deg0);
-    pipe_issue_rows<BF16C>(a, id1, lane, r1, deg1);
+    pipe_issue_rows<BF16C, SAGE>(a, id0, deg0, lane, r0);
+    pipe_issue_rows<BF16C, SAGE>(a, id1, deg1, lane, r1);
 
     auto step = [&](RowRegs<BF16C> &regs, int32_t &idv, int32_t &degv, int buf) {
         elem_t *A = A0 + buf * a_elems;
         int32_t *tids = ids + buf * kTileRows;
-        pipe_store_rows<BF16C>(a, A, stride, w, lane, regs, idv, degv);
-        if (lane < kPipeRows) tids[w * kPipeRows + lane] = idv;
+        pipe_store_rows<BF16C, SAGE>(a, A, stride, w, lane, regs, degv);
+        if ((lane & 31) < 4) tids[w * kPipeRows + my_row] = idv;
         __syncthreads();
-        idv = id_ahead;
-        id_ahead = load_ids(tile + 3 * G);
-        pipe_issue_rows<BF16C>(a, idv, lane, regs, degv);
+        idv = id_a;
+        degv = deg_a;
+        id_a = id_b;
+        deg_a = load_deg(id_a);
+        id_b = load_ids(tile + 4 * G);
+        pipe_issue_rows<BF16C, SAGE>(a, idv, degv, lane, regs);
 
         f32x16_t c[PPW];
 #pragma unroll
-        for (int i = 0; i < PPW; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) c[i][r] = 0.f;
-        for (int kk = 0; kk < KS; ++kk) {
-#pragma unroll
-            for (int i = 0; i < PPW; ++i) {
-                const int p = w + 8 * i;
-                if (p >= 2 * NB) continue;
-                const int nb = p % NB, mb = p / NB;
-                if constexpr (BF16C) {
-                    const bf16x8_t av = *reinterpret_cast<const bf16x8_t *>(
-                        A + (mb * 32 + (lane & 31)) * stride + kk * 16 + (lane >> 5) * 8);
-                    const bf16x8_t bv = *reinterpret_cast<const bf16x8_t *>(
-                        Wl + ((static_cast<size_t>(nb) * KS + kk) * 64 + lane) * 8);
-                    c[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv, av, c[i], 0, 0, 0);   // D^T block
-                } else {
-                    const float av = A[(mb * 32 + (lane & 31)) * stride + kk * 2 + (lane >> 5)];
-                    const float bv = Wl[(static_cast<size_t>(nb) * KS + kk) * 64 + lane];
-                    c[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av, c[i], 0, 0, 0);
+        for (int i = 0; i < PPW; ++i) {
+            c[i] = bj[i];
+            const elem_t *arow = A + a_off[i];
+            if constexpr (BF16C) {
+                switch (KS) {
+                    case 4: contract_block<true, 4>(arow, wfrag[i], KS, c[i]); break;
+                    case 8: contract_block<true, 8>(arow, wfrag[i], KS, c[i]); break;
+                    case 16: contract_block<true, 16>(arow, wfrag[i], KS, c[i]); break;
+                    default: contract_block<true, 0>(arow, wfrag[i], KS, c[i]); break;
                 }
+            } else {
+                contract_block<false, 0>(arow, wfrag[i], KS, c[i]);
             }
         }
 #pragma unroll
@@ -477,7 +596,7 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
             if (p >= 2 * NB) continue;
             const int nb = p % NB, mb = p / NB;
             const int32_t id = tids[mb * 32 + (lane & 31)];
-            if (id >= 0) store_block_row(a, c[i], id, nb * 32 + 4 * (lane >> 5), bj[i]);
+            if (id >= 0) store_block_row<false>(a, c[i], id, nb * 32 + 4 * (lane >> 5), nullptr);
         }
     };
 
@@ -499,24 +618,26 @@ size_t pipelined_lds_bytes(int K, int d_out, bool bf16c) {
            2 * static_cast<size_t>(kTileRows) * (K + lds_pad(bf16c)) * es;
 }
 
-template <bool BF16C, int PPW>
+template <bool BF16C, int PPW, bool SAGE>
 hipError_t launch_pipelined_t(const UpdateArgs &a, int grid, hipStream_t s) {
     const size_t lds = pipelined_lds_bytes(a.K, a.d_out, BF16C);
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_update_pipelined<BF16C, PPW>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_update_pipelined<BF16C, PPW, SAGE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL((k_update_pipelined<BF16C, PPW>), dim3(grid), dim3(kPipeBlock), lds, s, a);
+    hipLaunchKernelGGL((k_update_pipelined<BF16C, PPW, SAGE>), dim3(grid), dim3(kPipeBlock), lds, s, a);
     return hipGetLastError();
 }
 
 template <bool BF16C>
 hipError_t launch_pipelined_c(const UpdateArgs &a, int grid, hipStream_t s) {
     const int NB = (a.d_out + 31) / 32;
-    return 2 * NB <= 8 ? launch_pipelined_t<BF16C, 1>(a, grid, s) : launch_pipelined_t<BF16C, 2>(a, grid, s);
+    if (a.model == 0)
+        return 2 * NB <= 8 ? launch_pipelined_t<BF16C, 1, true>(a, grid, s) : launch_pipelined_t<BF16C, 2, true>(a, grid, s);
+    return 2 * NB <= 8 ? launch_pipelined_t<BF16C, 1, false>(a, grid, s) : launch_pipelined_t<BF16C, 2, false>(a, grid, s);
 }
 
 __global__ void k_advance_head(int32_t *counters) {
