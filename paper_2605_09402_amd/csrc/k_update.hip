@@ -559,6 +559,7 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
     int32_t deg0 = load_deg(id0), deg1 = load_deg(id1), deg_a = load_deg(id_a);
     RowRegs<BF16C> r0, r1;
     pipe_issue_rows<BF16C, SAGE>(a, id0, deg0, lane, r0);
+    __builtin_amdgcn_sched_barrier(0);   // keep the two sets' loads in this order, as in the loop
     pipe_issue_rows<BF16C, SAGE>(a, id1, deg1, lane, r1);
 
     auto step = [&](RowRegs<BF16C> &regs, int32_t &idv, int32_t &degv, int buf) {
@@ -600,13 +601,14 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
         }
     };
 
-    while (true) {
+    // Both steps run in every round (the second on an empty tile when the
+    // workgroup's tile count is odd: ids of -1, nothing stored).  With an exit
+    // between them the compiler has to assume that a round may start right
+    // after the first step's loads were issued, and then waits for them all.
+    for (; tile < ntiles; tile += G) {
         step(r0, id0, deg0, 0);
         tile += G;
-        if (tile >= ntiles) break;
         step(r1, id1, deg1, 1);
-        tile += G;
-        if (tile >= ntiles) break;
     }
 }
 
