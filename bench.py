@@ -239,13 +239,17 @@ def main() -> int:
         "per_edge_reads_only_GBps": round(e * kernel_bytes_per_edge / agg_s_per_layer / 1e9, 1),
     }
     K = 2 * wl.dims[0] if wl.model == "sage" else wl.dims[0]
+    n_with_in = int((indeg > 0).sum().item())
     upd_flops = 2.0 * n * K * wl.dims[1]      # SAGE / GCN: the flush GEMM; GAT: the per-chunk transform (in ms_self)
     upd_s = upd_ms / args.steps / 1e3
     update = {
         "kernel": "k_update", "tflops": round(upd_flops / upd_s / 1e12, 2),
         "mfma_peak_tflops": 2500.0 if sdt == atlas.DTYPE_BF16 else 157.3,
         "frac_of_mfma_peak": round(upd_flops / upd_s / (2.5e15 if sdt == atlas.DTYPE_BF16 else 157.3e12), 4),
-        "hbm_GBps": round(n * (4 * d + (s_in * d if wl.model == "sage" else 0) + s_in * wl.dims[1]) / upd_s / 1e9, 1),
+        # accumulator rows are read only for vertices that received something
+        "hbm_GBps": round((n_with_in * 4 * d + n * ((s_in * d if wl.model == "sage" else 0) + s_in * wl.dims[1]))
+                          / upd_s / 1e9, 1),
+        "rows_with_in_edges": n_with_in,
         "ms_per_layer": round(upd_ms / args.steps, 3),
     }
 
