@@ -134,104 +134,101 @@ __device__ __forceinline__ void load_bias16(const UpdateArgs &a, int nbase, floa
         }
 }
 
-// Stage 128 columns of 16 rows per pass.  Every load of a pass is issued
-// unconditionally (rows past the end of the ready list and lanes past the row
-// width read a valid dummy location and are dropped later) and kept raw in
-// registers, so the 16 loads are in flight together before the first is used.
-template <bool BF16C> struct OwnRaw { using type = float2; };
-template <> struct OwnRaw<true> { using type = uint32_t; };
+// Stage the wave's eight rows of the tile (generic kernel).  A row is covered
+// by 256-column segments of 4 columns per lane; every load is issued
+// unconditionally (rows past the end of the ready list, lanes past the row
+// width and vertices without in-edges read a valid dummy location whose value
+// is dropped) and kept raw in registers, so all loads of the wave are in flight
+// together before the first is used.  d_in <= 512: at most 16 items.
+template <bool BF16C> struct OwnRaw4 { using type = float4; };
+template <> struct OwnRaw4<true> { using type = uint2; };
 
-template <bool BF16C>
-__device__ __forceinline__ typename OwnRaw<BF16C>::type load_own(const void *rows, int64_t o);
-template <> __device__ __forceinline__ uint32_t load_own<true>(const void *rows, int64_t o) {
-    return *reinterpret_cast<const uint32_t *>(static_cast<const uint16_t *>(rows) + o);
-}
-template <> __device__ __forceinline__ float2 load_own<false>(const void *rows, int64_t o) {
-    return *reinterpret_cast<const float2 *>(static_cast<const float *>(rows) + o);
-}
-__device__ __forceinline__ float2 own_to_f32(uint32_t u) {
-    return make_float2(__uint_as_float(u << 16), __uint_as_float(u & 0xffff0000u));
-}
-__device__ __forceinline__ float2 own_to_f32(float2 v) { return v; }
-
-template <bool BF16C>
+template <bool BF16C, int SEGS>
 __device__ __forceinline__ void gather_rows(const UpdateArgs &a, typename Elem<BF16C>::type *A, int stride,
                                             int w, int lane, int32_t idv, float scalev, int has_aggv) {
-    constexpr int kRows = kTileRows / 4;  // rows per wave
+    constexpr int kRows = kTileRows / 8;  // rows per wave
+    constexpr bool two = SEGS == 2;       // one or two 256-column segments per row
+    constexpr int nitems = SEGS * kRows;
+    constexpr int kBatch = 8;             // loads in flight per pass
     const int d = a.d_in;
-    const int segs = (d + 127) >> 7;
-    const int nitems = kRows * segs;
-    const int col_in_seg = lane * 2;
+    const int c4 = lane * 4;
     const int acc_base = a.model == 0 ? d : 0;  // SAGE: own row first, then the neighbour mean
-    for (int it0 = 0; it0 < nitems; it0 += 16) {
-        float2 v[16];
+    auto row_of = [&](int item) { return two ? item >> 1 : item; };
+    auto col_of = [&](int item) { return (two ? (item & 1) * 256 : 0) + c4; };
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int item = it0 + i < nitems ? it0 + i : nitems - 1;
-            const int rr = item / segs;
-            const int col = (item - rr * segs) * 128 + col_in_seg;
+    for (int base = 0; base < nitems; base += kBatch) {
+        float4 v[kBatch];
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+            const int rr = row_of(base + i), col = col_of(base + i);
             const int32_t id = __builtin_amdgcn_readlane(idv, rr);
-            // rows past the list's end and vertices without in-edges read row 0 (value unused)
             const bool fetch = id >= 0 && __builtin_amdgcn_readlane(has_aggv, rr) != 0;
             const int64_t o = static_cast<int64_t>(fetch ? id : 0) * d + (col < d ? col : 0);
-            v[i] = *reinterpret_cast<const float2 *>(a.acc + o);
+            v[i] = *reinterpret_cast<const float4 *>(a.acc + o);
         }
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int item = it0 + i;
-            if (item >= nitems) break;
-            const int rr = item / segs;
-            const int col = (item - rr * segs) * 128 + col_in_seg;
-            const int32_t id = __builtin_amdgcn_readlane(idv, rr);
+        for (int i = 0; i < kBatch; ++i) {
+            const int rr = row_of(base + i), col = col_of(base + i);
+            if (col >= d) continue;
             const float g = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(scalev), rr));
-            if (col < d) {
-                typename Elem<BF16C>::type *dst = A + (w * kRows + rr) * stride + acc_base + col;
-                const bool has_agg = id >= 0 && __builtin_amdgcn_readlane(has_aggv, rr) != 0;
-                const float x = has_agg ? v[i].x * g : 0.f, y = has_agg ? v[i].y * g : 0.f;
-                if constexpr (BF16C) {
-                    *reinterpret_cast<uint32_t *>(dst) = pack_bf16x2(x, y);
-                } else {
-                    dst[0] = x;
-                    dst[1] = y;
-                }
+            // a vertex without in-edges never had its accumulator written: its aggregate is zero
+            const bool has_agg = __builtin_amdgcn_readlane(has_aggv, rr) != 0;
+            typename Elem<BF16C>::type *dst = A + (w * kRows + rr) * stride + acc_base + col;
+            if constexpr (BF16C) {
+                const uint32_t lo = pack_bf16x2(v[i].x * g, v[i].y * g), hi = pack_bf16x2(v[i].z * g, v[i].w * g);
+                *reinterpret_cast<uint2 *>(dst) = make_uint2(has_agg ? lo : 0u, has_agg ? hi : 0u);
+            } else {
+                dst[0] = has_agg ? v[i].x * g : 0.f;
+                dst[1] = has_agg ? v[i].y * g : 0.f;
+                dst[2] = has_agg ? v[i].z * g : 0.f;
+                dst[3] = has_agg ? v[i].w * g : 0.f;
             }
         }
     }
     if (a.model != 0) return;
-    for (int it0 = 0; it0 < nitems; it0 += 16) {  // SAGE: the vertex's own row
-        typename OwnRaw<BF16C>::type v[16];
+    // SAGE: the vertex's own row (rows past the list's end are stored as loaded and never used)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int item = it0 + i < nitems ? it0 + i : nitems - 1;
-            const int rr = item / segs;
-            const int col = (item - rr * segs) * 128 + col_in_seg;
+    for (int base = 0; base < nitems; base += kBatch) {
+        typename OwnRaw4<BF16C>::type v[kBatch];
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+            const int rr = row_of(base + i), col = col_of(base + i);
             const int32_t id = __builtin_amdgcn_readlane(idv, rr);
             const int64_t o = static_cast<int64_t>(id >= 0 ? id : 0) * d + (col < d ? col : 0);
-            v[i] = load_own<BF16C>(a.self_rows, o);
+            if constexpr (BF16C) v[i] = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(a.self_rows) + o);
+            else v[i] = *reinterpret_cast<const float4 *>(static_cast<const float *>(a.self_rows) + o);
         }
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int item = it0 + i;
-            if (item >= nitems) break;
-            const int rr = item / segs;
-            const int col = (item - rr * segs) * 128 + col_in_seg;
-            const int32_t id = __builtin_amdgcn_readlane(idv, rr);
-            if (col < d) {
-                typename Elem<BF16C>::type *dst = A + (w * kRows + rr) * stride + col;
-                if constexpr (BF16C) {
-                    *reinterpret_cast<uint32_t *>(dst) = id >= 0 ? v[i] : 0u;   // bf16 rows go in as loaded
-                } else {
-                    dst[0] = id >= 0 ? v[i].x : 0.f;
-                    dst[1] = id >= 0 ? v[i].y : 0.f;
-                }
+        for (int i = 0; i < kBatch; ++i) {
+            const int rr = row_of(base + i), col = col_of(base + i);
+            if (col >= d) continue;
+            typename Elem<BF16C>::type *dst = A + (w * kRows + rr) * stride + col;
+            if constexpr (BF16C) {
+                *reinterpret_cast<uint2 *>(dst) = v[i];   // bf16 rows go in as loaded
+            } else {
+                dst[0] = v[i].x;
+                dst[1] = v[i].y;
+                dst[2] = v[i].z;
+                dst[3] = v[i].w;
             }
         }
     }
 }
 
-template <bool BF16C, int PPW>
-__global__ __launch_bounds__(kBlock) void k_update(UpdateArgs a) {
+// ---- generic variant: W streamed from L2, one A tile in LDS ------------------
+//
+// A workgroup of 8 waves takes a tile of 64 ready rows; two or more workgroups
+// share a CU, so one's gather overlaps another's contraction.  BOTH_MB (more
+// than four column blocks): wave w computes column block w for both 32-row
+// halves, so a W fragment fetched from L2 feeds two matrix instructions;
+// otherwise wave w computes column block w % 4 of half w / 4.  The W fragments
+// of the next four k-steps are fetched while the current four are multiplied.
+constexpr int kGenBlock = 512;
+
+template <bool BF16C, bool BOTH_MB>
+__global__ __launch_bounds__(kGenBlock, 4) void k_update(UpdateArgs a) {
     using elem_t = typename Elem<BF16C>::type;
+    using frag_t = typename std::conditional<BF16C, bf16x8_t, float>::type;
     extern __shared__ __align__(16) unsigned char smem[];
     int32_t *ids = reinterpret_cast<int32_t *>(smem);                 // [64]
     elem_t *A = reinterpret_cast<elem_t *>(smem + kTileRows * sizeof(int32_t));
@@ -240,89 +237,89 @@ __global__ __launch_bounds__(kBlock) void k_update(UpdateArgs a) {
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
     const int NB = (a.d_out + 31) / 32;
-    constexpr int kStepK = BF16C ? 16 : 2;
+    constexpr int kStepK = BF16C ? 16 : 2;   // k per matrix instruction
+    constexpr int kFrag = BF16C ? 8 : 1;     // W / A elements per lane and instruction
+    constexpr int kUnroll = 4;
+    constexpr int kMB = BOTH_MB ? 2 : 1;
+    constexpr int kRows = kTileRows / 8;
     const int KS = K / kStepK;
-    constexpr int kRows = kTileRows / 4;
+    const int G = KS / kUnroll;              // K is a multiple of 64: KS is a multiple of 4
 
     const bool dense = a.identity_rows > 0;
     const int head = dense ? 0 : a.counters[CTR_READY_HEAD];
     const int tail = dense ? static_cast<int>(a.identity_rows) : a.counters[CTR_READY_TAIL];
     const int ntiles = (tail - head + kTileRows - 1) / kTileRows;
 
+    const int nb = BOTH_MB ? w : (w & 3);
+    const int mb0 = BOTH_MB ? 0 : (w >> 2);
+    const bool works = nb < NB;                               // waves past the last block compute and discard
+    const int nbc = works ? nb : NB - 1;
+    const elem_t *wp = static_cast<const elem_t *>(a.packed_w) + (static_cast<size_t>(nbc) * KS * 64 + lane) * kFrag;
+    const int a_off = (mb0 * 32 + (lane & 31)) * stride + (lane >> 5) * kFrag;
+    auto load_w = [&](int g, frag_t (&f)[kUnroll]) {
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u)
+            f[u] = *reinterpret_cast<const frag_t *>(wp + static_cast<size_t>(g * kUnroll + u) * 64 * kFrag);
+    };
+
     for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         __syncthreads();  // previous tile's LDS readers are done
-        // ---- gather: wave w stages rows w*16 .. w*16+15; lane r holds row r's id ----
+        // ---- gather: wave w stages rows w*8 .. w*8+7; lane r < 8 holds row r's id ----
         int32_t idv = -1;
         float scalev = 1.f;
-        bool idv_has_agg = true;
+        int has_aggv = 1;
         if (lane < kRows) {
             const int idx = head + tile * kTileRows + w * kRows + lane;
             if (idx < tail) {
                 idv = dense ? idx : a.ready[idx];
                 const int32_t deg = a.indeg ? a.indeg[idv] : 1;
-                if (deg <= 0) idv_has_agg = false;   // accumulator never written: aggregate is zero
+                if (deg <= 0) has_aggv = 0;
                 const float fd = static_cast<float>(deg > 0 ? deg : 1);
                 // SAGE: mean = sum * (1/deg); GCN: deg^-1/2; a plain linear map (model 2): 1
                 scalev = a.model == 0 ? 1.0f / fd : (a.model == 1 ? 1.0f / sqrtf(fd) : 1.0f);
             }
             ids[w * kRows + lane] = idv;
         }
-        gather_rows<BF16C>(a, A, stride, w, lane, idv, scalev, idv_has_agg ? 1 : 0);
+        frag_t wcur[kUnroll];
+        load_w(0, wcur);   // on its way while the rows are gathered
+        if (a.d_in > 256) gather_rows<BF16C, 2>(a, A, stride, w, lane, idv, scalev, has_aggv);
+        else gather_rows<BF16C, 1>(a, A, stride, w, lane, idv, scalev, has_aggv);
         __syncthreads();
 
-        // ---- MFMA: pairs (mb, nb) p = w + 4*i ----
-        f32x16_t c[PPW];
+        // ---- contraction, as D^T blocks; the bias is the initial accumulator ----
+        f32x16_t c[kMB];
+        {
+            float b16[16];   // re-read per tile (cache hit) rather than held in registers
+            load_bias16(a, nbc * 32 + 4 * (lane >> 5), b16);
 #pragma unroll
-        for (int i = 0; i < PPW; ++i)
+            for (int m = 0; m < kMB; ++m)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) c[i][r] = 0.f;
-
-        for (int kk = 0; kk < KS; ++kk) {
-            int last_nb = -1;
-            if constexpr (BF16C) {
-                bf16x8_t bv = {};
+                for (int r = 0; r < 16; ++r) c[m][r] = b16[r];
+        }
+        for (int g = 0; g < G; ++g) {
+            frag_t wnxt[kUnroll];
+            load_w(g + 1 < G ? g + 1 : g, wnxt);   // the last group re-reads itself
 #pragma unroll
-                for (int i = 0; i < PPW; ++i) {
-                    const int p = w + 4 * i;
-                    if (p >= 2 * NB) continue;
-                    const int nb = p % NB, mb = p / NB;
-                    const uint16_t *ap = A + (mb * 32 + (lane & 31)) * stride + kk * 16 + (lane >> 5) * 8;
-                    const bf16x8_t av = *reinterpret_cast<const bf16x8_t *>(ap);
-                    if (nb != last_nb) {
-                        bv = *reinterpret_cast<const bf16x8_t *>(
-                            static_cast<const uint16_t *>(a.packed_w) + ((static_cast<int64_t>(nb) * KS + kk) * 64 + lane) * 8);
-                        last_nb = nb;
-                    }
-                    c[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv, av, c[i], 0, 0, 0);   // D^T block
-                }
-            } else {
-                float bv = 0.f;
+            for (int u = 0; u < kUnroll; ++u) {
+                const int kk = g * kUnroll + u;
 #pragma unroll
-                for (int i = 0; i < PPW; ++i) {
-                    const int p = w + 4 * i;
-                    if (p >= 2 * NB) continue;
-                    const int nb = p % NB, mb = p / NB;
-                    const float av = A[(mb * 32 + (lane & 31)) * stride + kk * 2 + (lane >> 5)];
-                    if (nb != last_nb) {
-                        bv = static_cast<const float *>(a.packed_w)[(static_cast<int64_t>(nb) * KS + kk) * 64 + lane];
-                        last_nb = nb;
-                    }
-                    c[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av, c[i], 0, 0, 0);
+                for (int m = 0; m < kMB; ++m) {
+                    const frag_t av = *reinterpret_cast<const frag_t *>(A + a_off + m * 32 * stride + kk * kStepK);
+                    if constexpr (BF16C) c[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wcur[u], av, c[m], 0, 0, 0);
+                    else c[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(wcur[u], av, c[m], 0, 0, 0);
                 }
             }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) wcur[u] = wnxt[u];
         }
 
-        // ---- epilogue: bias, activation, store row of the next layer ----
+        // ---- epilogue: activation, store row of the next layer ----
+        if (works) {
 #pragma unroll
-        for (int i = 0; i < PPW; ++i) {
-            const int p = w + 4 * i;
-            if (p >= 2 * NB) continue;
-            const int nb = p % NB, mb = p / NB;
-            const int32_t id = ids[mb * 32 + (lane & 31)];
-            if (id < 0) continue;
-            float bias16[16];
-            load_bias16(a, nb * 32 + 4 * (lane >> 5), bias16);
-            store_block_row<true>(a, c[i], id, nb * 32 + 4 * (lane >> 5), bias16);
+            for (int m = 0; m < kMB; ++m) {
+                const int32_t id = ids[(mb0 + m) * 32 + (lane & 31)];
+                if (id >= 0) store_block_row<false>(a, c[m], id, nb * 32 + 4 * (lane >> 5), nullptr);
+            }
         }
     }
 }
@@ -346,9 +343,6 @@ __global__ __launch_bounds__(kBlock) void k_update(UpdateArgs a) {
 constexpr int kPipeBlock = 512;
 constexpr int kPipeRows = kTileRows / (kPipeBlock / 64);  // rows staged per wave = 8
 constexpr int kPipeIters = kPipeRows / 2;                 // two rows per load instruction
-
-template <bool BF16C> struct OwnRaw4 { using type = float4; };
-template <> struct OwnRaw4<true> { using type = uint2; };
 
 template <bool BF16C>
 struct RowRegs {
@@ -654,31 +648,25 @@ size_t update_lds_bytes(int K, bool bf16c) {
            static_cast<size_t>(kTileRows) * (K + lds_pad(bf16c)) * (bf16c ? 2 : 4);
 }
 
-template <bool BF16C, int PPW>
+template <bool BF16C, bool BOTH_MB>
 hipError_t launch_update_t(const UpdateArgs &a, int grid, hipStream_t s) {
     const size_t lds = update_lds_bytes(a.K, BF16C);
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_update<BF16C, PPW>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_update<BF16C, BOTH_MB>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL((k_update<BF16C, PPW>), dim3(grid), dim3(kBlock), lds, s, a);
+    hipLaunchKernelGGL((k_update<BF16C, BOTH_MB>), dim3(grid), dim3(kGenBlock), lds, s, a);
     return hipGetLastError();
 }
 
 template <bool BF16C>
 hipError_t launch_update_c(const UpdateArgs &a, int grid, hipStream_t s) {
     const int NB = (a.d_out + 31) / 32;
-    const int ppw = (2 * NB + 3) / 4;
-    switch (ppw) {
-        case 1: return launch_update_t<BF16C, 1>(a, grid, s);
-        case 2: return launch_update_t<BF16C, 2>(a, grid, s);
-        case 3: return launch_update_t<BF16C, 3>(a, grid, s);
-        case 4: return launch_update_t<BF16C, 4>(a, grid, s);
-        default: return hipErrorInvalidValue;
-    }
+    if (NB > 8 || a.d_in > 512) return hipErrorInvalidValue;
+    return NB > 4 ? launch_update_t<BF16C, true>(a, grid, s) : launch_update_t<BF16C, false>(a, grid, s);
 }
 
 }  // namespace
@@ -719,7 +707,7 @@ hipError_t launch_update(const UpdateArgs &a, hipStream_t s) {
     const size_t lds = update_lds_bytes(a.K, a.compute_bf16 != 0);
     int per_cu = static_cast<int>((160 * 1024) / lds);
     if (per_cu < 1) per_cu = 1;
-    if (per_cu > 8) per_cu = 8;
+    if (per_cu > 4) per_cu = 4;   // 8 waves per workgroup, 32 per CU
     int64_t grid = static_cast<int64_t>(cus) * per_cu;
     const int64_t max_tiles = (a.n + kTileRows - 1) / kTileRows;
     if (grid > max_tiles) grid = max_tiles;
