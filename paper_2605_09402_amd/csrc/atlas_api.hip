@@ -119,6 +119,7 @@ struct atlas_layer {
 
     Buf indeg_own, pending, ready, counters, counters64, acc, self_rows, packed_w, bias, dev_off;
     Buf gat_el, gat_er, gat_mcur, gat_mnext, gat_l, gat_wa, gat_z;   // GAT state
+    Buf gat_scores;                                                  // GAT, planned chunks: per-edge logits
     int64_t prepass_next = 0;
     const int32_t *indeg = nullptr;
     const int64_t *off_dev = nullptr;  // device-visible row offsets
@@ -146,7 +147,7 @@ struct atlas_layer {
     void destroy() {
         for (Buf *b : {&indeg_own, &pending, &ready, &counters, &counters64, &acc, &self_rows, &packed_w, &bias,
                        &dev_off, &stage_col[0], &stage_col[1], &stage_emb[0], &stage_emb[1], &gat_el, &gat_er,
-                       &gat_mcur, &gat_mnext, &gat_l, &gat_wa, &gat_z})
+                       &gat_mcur, &gat_mnext, &gat_l, &gat_wa, &gat_z, &gat_scores})
             b->release();
         for (auto *v : {&t_agg, &t_self, &t_upd, &t_copy, &t_init})
             for (auto &sp : *v) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
@@ -279,6 +280,11 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
         HIP_TRY(L->gat_wa.alloc(static_cast<size_t>(d.d_in) * 2 * d.heads * sizeof(float)));
         HIP_TRY(L->gat_z.alloc(static_cast<size_t>(std::min<int64_t>(d.max_chunk_sources, std::max<int64_t>(n, 1))) *
                                d.d_out * sizeof(float)));
+        if (L->g.plan) {   // room for the logits of the largest planned chunk
+            int64_t most = 1;
+            for (const PlanChunk &c : L->g.plan->chunks) most = std::max(most, c.n_edges);
+            HIP_TRY(L->gat_scores.alloc(static_cast<size_t>(most) * d.heads * sizeof(float)));
+        }
         HIP_TRY(launch_fill_i32(static_cast<int32_t *>(L->gat_mcur.p), gat_encoded_neg_inf(), n * d.heads, s));
         HIP_TRY(launch_fill_i32(static_cast<int32_t *>(L->gat_mnext.p), gat_encoded_neg_inf(), n * d.heads, s));
         HIP_TRY(launch_fill_zero(L->gat_l.p, static_cast<size_t>(n) * d.heads * sizeof(float), s));
@@ -520,9 +526,21 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         ga.counters64 = a.counters64;
     }
     if (d.model == ATLAS_MODEL_GAT) {
-        if (pc) HIP_TRY(launch_gat_group_max(ga, s));
-        else HIP_TRY(launch_gat_chunk_max(a, s));
-        HIP_TRY(launch_gat_rescale(a.gat, a.acc, d.d_out, L->n, s));
+        if (pc) {
+            // logits of the chunk's edges, kept between the max sweep and the aggregation
+            const size_t need = static_cast<size_t>(std::max<int64_t>(pc->n_edges, 1)) * d.heads * sizeof(float);
+            if (L->gat_scores.bytes < need) {
+                HIP_TRY(hipStreamSynchronize(s));   // the previous chunk may still read the old buffer
+                L->gat_scores.release();
+                HIP_TRY(L->gat_scores.alloc(need));
+            }
+            ga.scores = static_cast<float *>(L->gat_scores.p);
+            HIP_TRY(launch_gat_group_max(ga, s));
+            HIP_TRY(launch_gat_rescale_cut_groups(ga, s));   // other groups: rescaled by the aggregation
+        } else {
+            HIP_TRY(launch_gat_chunk_max(a, s));
+            HIP_TRY(launch_gat_rescale(a.gat, a.acc, d.d_out, L->n, s));
+        }
         if ((rc = end_span(L, L->t_self, s)) != ATLAS_OK) return rc;
     }
     if ((rc = start_span(L, L->t_agg, s)) != ATLAS_OK) return rc;

@@ -81,6 +81,8 @@ struct GroupedArgs {
     int32_t *counters;
     unsigned long long *counters64;
     GatState gat;               // model == GAT only
+    float *scores = nullptr;    // GAT only: [n_edges][heads] attention logits of the chunk's edges, written
+                                // by the max sweep and read by the aggregation
 };
 
 // S2+S3+S4 over a planned chunk: per-destination register sums, one row update
@@ -100,7 +102,12 @@ hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int6
 // sends to v (CSR order), then bring every destination whose maximum moved to
 // the new reference (rescale l and acc, m_cur = m_next).
 hipError_t launch_gat_chunk_max(const AggregateArgs &a, hipStream_t s);
-hipError_t launch_gat_group_max(const GroupedArgs &a, hipStream_t s);   // the same over a planned chunk
+hipError_t launch_gat_group_max(const GroupedArgs &a, hipStream_t s);   // the same over a planned chunk; also
+                                                                        // stores every edge's logits in a.scores
+// Planned GAT chunk, between the max sweep and the aggregation: destinations whose group is cut by a tile
+// boundary are brought to the new maximum here (acc and l times exp(m_cur - m_next), m_cur = m_next), once
+// per group; groups inside a tile are rescaled by the aggregation itself as part of their row update.
+hipError_t launch_gat_rescale_cut_groups(const GroupedArgs &a, hipStream_t s);
 hipError_t launch_gat_rescale(const GatState &g, float *acc, int d_out, int64_t n, hipStream_t s);
 // GAT set-up and prepass.
 hipError_t launch_fill_i32(int32_t *p, int32_t value, int64_t count, hipStream_t s);

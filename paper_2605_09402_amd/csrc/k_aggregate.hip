@@ -21,6 +21,7 @@ namespace {
 
 constexpr int kWave = 64;
 constexpr int kTileEdges = 64;
+constexpr int kMaxHeads = 8;   // attention heads (checked at layer init)
 constexpr int kBlock = 256;
 
 __device__ __forceinline__ float load_as_f32(const float *p) { return *p; }
@@ -349,6 +350,30 @@ __device__ __forceinline__ void row_store(float *p, const float (&x)[VPL]) {
     }
 }
 
+// p = p * f + x for the only writer of the row
+template <int VPL>
+__device__ __forceinline__ void row_scale_add_owned(float *p, float f, const float (&x)[VPL]) {
+    float y[VPL];
+    if constexpr (VPL == 2) {
+        const float2 o = *reinterpret_cast<const float2 *>(p);
+        y[0] = o.x * f + x[0];
+        y[1] = o.y * f + x[1];
+    } else if constexpr (VPL == 4 || VPL == 8) {
+#pragma unroll
+        for (int q = 0; q < VPL / 4; ++q) {
+            const float4 o = *reinterpret_cast<const float4 *>(p + 4 * q);
+            y[4 * q] = o.x * f + x[4 * q];
+            y[4 * q + 1] = o.y * f + x[4 * q + 1];
+            y[4 * q + 2] = o.z * f + x[4 * q + 2];
+            y[4 * q + 3] = o.w * f + x[4 * q + 3];
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) y[i] = p[i] * f + x[i];
+    }
+    row_store<VPL>(p, y);
+}
+
 template <int VPL>
 __device__ __forceinline__ void row_add_shared(float *p, const float (&x)[VPL]) {
 #pragma unroll
@@ -367,6 +392,9 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
     __shared__ int32_t stage_all[(kBlock / kWave) * kStageCap];
     int32_t *stage = stage_all + (threadIdx.x >> 6) * kStageCap;
     int staged = 0;
+    // GAT: the tile's attention weights, [edge][head], written by the edge's lane and read per row
+    __shared__ float wgt_all[MODEL == 2 ? (kBlock / kWave) * kTileEdges * kMaxHeads : 1];
+    float *wl = wgt_all + (MODEL == 2 ? (threadIdx.x >> 6) * kTileEdges * kMaxHeads : 0);
 
     if (wave == 0 && lane == 0)
         atomicAdd(&a.counters64[CTR64_EDGES], static_cast<unsigned long long>(a.n_edges));
@@ -405,6 +433,18 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
         const int hl = MODEL == 2 ? (lane * VPL) / a.gat.dh : 0;
         const bool head_first = MODEL == 2 && (lane * VPL) % a.gat.dh == 0;
         float lsum = 0.f;
+        if (MODEL == 2) {
+            // lane e: weights of edge e for every head, exp(logit - new maximum of its destination) <= 1;
+            // the destination is held by the lane that closes the edge's group
+            const int H = a.gat.heads;
+            const uint64_t rest = endmask >> lane;
+            int closer = rest ? lane + __ffsll(static_cast<unsigned long long>(rest)) - 1 : cnt - 1;
+            const int64_t ve = __shfl(dstv, closer);
+            if (lane < cnt)
+                for (int h = 0; h < H; ++h)
+                    wl[lane * H + h] = expf(a.scores[(e0 + lane) * H + h] - decode_max(a.gat.m_next[ve * H + h]));
+            __builtin_amdgcn_wave_barrier();   // the weights are read across lanes below
+        }
 
         float sum[VPL];
 #pragma unroll
@@ -422,14 +462,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
 #pragma unroll
                     for (int q = 0; q < VPL; ++q) r[i][q] *= g;
                 }
-                if (MODEL == 2) {
-                    // destination of edge j = the one held by the lane that closes its group
-                    const uint64_t rest = endmask >> j;
-                    const int closer = rest ? j + __ffsll(static_cast<unsigned long long>(rest)) - 1 : cnt - 1;
-                    const int64_t vh = static_cast<int64_t>(__builtin_amdgcn_readlane(dstv, closer)) * a.gat.heads + hl;
-                    const float sc = leaky(a.gat.el[static_cast<int64_t>(sj) * a.gat.heads + hl] + a.gat.er[vh], a.gat.slope);
-                    wgt[i] = expf(sc - decode_max(a.gat.m_cur[vh]));   // <= 1: m_cur covers this chunk
-                }
+                if (MODEL == 2) wgt[i] = wl[j * a.gat.heads + hl];
             }
 #pragma unroll
             for (int i = 0; i < U; ++i) {
@@ -446,13 +479,26 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
                     if ((endmask >> j) & 1ull) {
                         const int32_t v = __builtin_amdgcn_readlane(dstv, j);
                         float *dst = a.acc + static_cast<int64_t>(v) * D + lane * VPL;
-                        if (cut) row_add_shared<VPL>(dst, sum);
-                        else if (MODEL != 2 && ((firstmask >> j) & 1ull)) row_store<VPL>(dst, sum);
-                        else row_add_owned<VPL>(dst, sum);
-                        if (MODEL == 2 && head_first) {
-                            float *lp = a.gat.l + static_cast<int64_t>(v) * a.gat.heads + hl;
-                            if (cut) unsafeAtomicAdd(lp, lsum);
-                            else *lp += lsum;
+                        if (MODEL == 2) {
+                            const int64_t vh = static_cast<int64_t>(v) * a.gat.heads + hl;
+                            if (cut) {   // already at the new maximum (k_gat_rescale_cut_groups)
+                                row_add_shared<VPL>(dst, sum);
+                                if (head_first) unsafeAtomicAdd(a.gat.l + vh, lsum);
+                            } else {     // sole writer: move the row to the new maximum while adding
+                                const int32_t mc = a.gat.m_cur[vh], mn = a.gat.m_next[vh];
+                                const float f = mc == mn ? 1.f : expf(decode_max(mc) - decode_max(mn));
+                                row_scale_add_owned<VPL>(dst, f, sum);
+                                if (head_first) {
+                                    a.gat.l[vh] = a.gat.l[vh] * f + lsum;
+                                    a.gat.m_cur[vh] = mn;
+                                }
+                            }
+                        } else if (cut) {
+                            row_add_shared<VPL>(dst, sum);
+                        } else if ((firstmask >> j) & 1ull) {
+                            row_store<VPL>(dst, sum);
+                        } else {
+                            row_add_owned<VPL>(dst, sum);
                         }
                         cut = false;
                         lsum = 0.f;
@@ -526,7 +572,10 @@ __global__ __launch_bounds__(kBlock) void k_gat_group_max(GroupedArgs a) {
         const bool shared = (below == 0 && cut) || !is_end;
         for (int h = 0; h < H; ++h) {
             float sc = -INFINITY;
-            if (lane < cnt) sc = leaky(a.gat.el[src * H + h] + a.gat.er[v * H + h], a.gat.slope);
+            if (lane < cnt) {
+                sc = leaky(a.gat.el[src * H + h] + a.gat.er[v * H + h], a.gat.slope);
+                a.scores[(e0 + lane) * H + h] = sc;   // the aggregation reuses the logit
+            }
 #pragma unroll
             for (int o = 1; o < kWave; o <<= 1) {
                 const float up = __shfl_up(sc, o);
@@ -539,6 +588,52 @@ __global__ __launch_bounds__(kBlock) void k_gat_group_max(GroupedArgs a) {
                 else if (enc > *m) *m = enc;
             }
         }
+    }
+}
+
+// Planned GAT chunk: one lane per tile boundary.  A group cut by tile boundaries
+// is added to by several waves with atomics, so its destination is moved to the
+// new maximum beforehand, by the lane of the FIRST boundary that cuts it (the
+// group starts in the previous tile): acc and l times
+// exp(m_cur - m_next) per head, then m_cur = m_next.  A first touch
+// (m_cur = -inf, state still zero) only moves the reference.
+__global__ __launch_bounds__(kBlock) void k_gat_rescale_cut_groups(GroupedArgs a) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t ntiles = (a.n_edges + kTileEdges - 1) / kTileEdges;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    const int H = a.gat.heads;
+    for (int64_t t0 = 1 + static_cast<int64_t>(blockIdx.x) * kBlock + (threadIdx.x & ~(kWave - 1)); t0 < ntiles;
+         t0 += stride) {
+        const int64_t t = t0 + lane;
+        int64_t v = -1;
+        if (t < ntiles && a.src_sorted[t * kTileEdges - 1] >= 0) {   // the previous tile ends inside a group
+            const int32_t g = a.tile_grp[t];                          // group of the tile's first edge = the cut one
+            // first boundary of the group: it starts inside the previous tile, or exactly on that tile's first edge
+            if (a.tile_grp[t - 1] != g || t == 1 || a.src_sorted[(t - 1) * kTileEdges - 1] < 0)
+                v = a.grp_dst[g] & 0x7fffffff;
+        }
+        bool rows = false;
+        if (v >= 0)
+            for (int h = 0; h < H; ++h) {
+                const int32_t mc = a.gat.m_cur[v * H + h];
+                if (mc != a.gat.m_next[v * H + h] && decode_max(mc) != -INFINITY) rows = true;
+            }
+        uint64_t todo = __ballot(rows);
+        while (todo) {  // the whole wave rescales one destination row at a time
+            const int j = __ffsll(static_cast<unsigned long long>(todo)) - 1;
+            todo &= todo - 1;
+            const int64_t vv = __shfl(v, j);
+            for (int c = lane; c < a.d; c += kWave) {
+                const int h = c / a.gat.dh;
+                a.acc[vv * a.d + c] *= expf(decode_max(a.gat.m_cur[vv * H + h]) - decode_max(a.gat.m_next[vv * H + h]));
+            }
+            if (lane < H)
+                a.gat.l[vv * H + lane] *= expf(decode_max(a.gat.m_cur[vv * H + lane]) - decode_max(a.gat.m_next[vv * H + lane]));
+        }
+        // every lane has finished reading m_cur of the rows above before any lane moves it
+        __builtin_amdgcn_wave_barrier();
+        if (v >= 0)
+            for (int h = 0; h < H; ++h) a.gat.m_cur[v * H + h] = a.gat.m_next[v * H + h];
     }
 }
 
@@ -633,6 +728,16 @@ hipError_t launch_zero_cut_first_rows(const GroupedArgs &a, hipStream_t s) {
 hipError_t launch_gat_group_max(const GroupedArgs &a, hipStream_t s) {
     if (a.n_edges <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_gat_group_max, dim3(persistent_grid(8)), dim3(kBlock), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_gat_rescale_cut_groups(const GroupedArgs &a, hipStream_t s) {
+    const int64_t ntiles = (a.n_edges + kTileEdges - 1) / kTileEdges;
+    if (ntiles <= 1) return hipSuccess;
+    int64_t blocks = (ntiles + kBlock - 1) / kBlock;
+    const int cap = persistent_grid(8);
+    if (blocks > cap) blocks = cap;
+    hipLaunchKernelGGL(k_gat_rescale_cut_groups, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, s, a);
     return hipGetLastError();
 }
 

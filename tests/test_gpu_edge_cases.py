@@ -60,6 +60,27 @@ def test_hot_source_and_hot_destination(oracle, H):
     both_paths(H, oracle, case)
 
 
+@pytest.mark.parametrize("model", ["gat", "sage", "gcn"])
+def test_group_starting_on_a_tile_boundary(oracle, H, model):
+    """Per chunk, destination 5 gets exactly 64 messages (one full 64-edge tile
+    of the destination-ordered list), destination 6 the next 100 (its group
+    starts on the first edge of a tile and is cut by the next boundary) and
+    destination 7 another 28; three chunks, so the running softmax state of the
+    cut destination is rescaled twice.  GCN gets its self loops at the end."""
+    n, chunk = 600, 200
+    src, dst = [], []
+    for c in range(3):
+        base = c * chunk
+        src += list(range(base, base + 64)) + list(range(base + 10, base + 110)) + list(range(base + 150, base + 178))
+        dst += [5] * 64 + [6] * 100 + [7] * 28
+    if model == "gcn":
+        src += list(range(n))
+        dst += list(range(n))
+    kw = dict(feat="normal", act="elu", heads=2) if model == "gat" else {}
+    case = H.case_from_edges(model, n, src, dst, SEED + 31, [64, 64, 64] if model == "gat" else [64, 32], chunk, **kw)
+    both_paths(H, oracle, case)
+
+
 def test_long_runs_of_sources_without_edges(oracle, H):
     """Every 150th source has one out-edge: a 64-edge tile spans ~9,600 sources."""
     n = 40_000
