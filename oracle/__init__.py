@@ -119,6 +119,30 @@ def gcn(il: InLists, indeg: np.ndarray, X: np.ndarray, W: np.ndarray, b: Optiona
     return Y
 
 
+def gin(il: InLists, X: np.ndarray, W: np.ndarray, b: Optional[np.ndarray], eps: float = 0.0) -> np.ndarray:
+    """GIN layer with one linear map: ((1 + eps) x_v + sum of in-neighbours) W + b."""
+    X = _c(X, np.float32)
+    W = _c(W, np.float64)
+    b = None if b is None else _c(b, np.float64)
+    d, dout = X.shape[1], W.shape[1]
+    assert W.shape[0] == d
+    Y = np.empty((il.n_dst, dout), dtype=np.float64)
+    lib().ao_gin(_i64(il.n_dst), _p(il.dst_ids), _p(il.in_off), _p(il.in_src), _p(X), _i64(d),
+                 ctypes.c_double(eps), _p(W), _p(b), _i64(dout), _p(Y))
+    return Y
+
+
+def sgc_hop(il: InLists, indeg: np.ndarray, X: np.ndarray) -> np.ndarray:
+    """One SGC propagation step: the symmetric-normalised neighbour sum, no weights."""
+    X = _c(X, np.float32)
+    indeg = _c(indeg, np.int64)
+    assert indeg.size == X.shape[0]
+    Y = np.empty((il.n_dst, X.shape[1]), dtype=np.float64)
+    lib().ao_sym_propagate(_i64(il.n_dst), _p(il.dst_ids), _p(il.in_off), _p(il.in_src), _p(indeg), _p(X),
+                           _i64(X.shape[1]), _p(Y))
+    return Y
+
+
 def gat(il: InLists, X: np.ndarray, W: np.ndarray, b: Optional[np.ndarray], a_src: np.ndarray,
         a_dst: np.ndarray, slope: float = 0.2) -> np.ndarray:
     X = _c(X, np.float32)
@@ -219,7 +243,7 @@ def message_span(il: "InLists", selfmsg: bool = False) -> np.ndarray:
 # --------------------------------------------------------------------------
 
 def run_layer(model: str, il: InLists, indeg: Optional[np.ndarray], X: np.ndarray, params, act: int,
-              out_fmt: int, slope: float = 0.2) -> np.ndarray:
+              out_fmt: int, slope: float = 0.2, eps: float = 0.0) -> np.ndarray:
     """One layer: aggregate + update (fp64), activation, round to storage.
 
     `params` has fp64 arrays W, bias (and attn_src / attn_dst for GAT) that
@@ -231,13 +255,17 @@ def run_layer(model: str, il: InLists, indeg: Optional[np.ndarray], X: np.ndarra
         Y = gcn(il, indeg, X, params.W, params.bias)
     elif model == "gat":
         Y = gat(il, X, params.W, params.bias, params.attn_src, params.attn_dst, slope)
+    elif model == "gin":
+        Y = gin(il, X, params.W, params.bias, eps)
+    elif model == "sgc":   # propagation-only hops (no weights), then one GCN layer
+        Y = sgc_hop(il, indeg, X) if params.W is None else gcn(il, indeg, X, params.W, params.bias)
     else:
         raise ValueError(model)
     return round_storage(activation(Y, act), out_fmt)
 
 
 def run_model(model: str, off: np.ndarray, col: np.ndarray, X: np.ndarray, layers: Sequence,
-              between_act: int, store_fmt: int, slope: float = 0.2) -> List[np.ndarray]:
+              between_act: int, store_fmt: int, slope: float = 0.2, eps: float = 0.0) -> List[np.ndarray]:
     """All layers over the full graph; the activation applies between layers
     only, every layer's output is rounded to the storage format.  Returns the
     list of per-layer outputs."""
@@ -247,7 +275,9 @@ def run_model(model: str, off: np.ndarray, col: np.ndarray, X: np.ndarray, layer
     cur = np.asarray(X, dtype=np.float32)
     for li, p in enumerate(layers):
         act = between_act if li + 1 < len(layers) else ACT_NONE
-        Y = run_layer(model, il, indeg, cur, p, act, store_fmt, slope)
+        if model == "sgc":
+            act = ACT_NONE   # SGC has no non-linearity between its hops
+        Y = run_layer(model, il, indeg, cur, p, act, store_fmt, slope, eps)
         outs.append(Y)
         cur = Y.astype(np.float32)
     return outs

@@ -21,6 +21,11 @@
  *       Sec. 4.1, gives no formula) with D = in-degree of the graph as given;
  *   GAT: the textbook attention layer (the paper only names it as adoptable,
  *       Sec. 3.9), plain two-pass softmax over the in-neighbour multiset;
+ *   GIN: the sum-aggregation layer of Xu et al. that the paper evaluates as
+ *       "GINConv" (Sec. 4.1, no formula given): y_v = ((1+eps) x_v + sum x_u) W + b,
+ *       with a single linear map standing for the layer's MLP;
+ *   SGC hop: one application of the symmetric-normalised adjacency without a
+ *       weight matrix (Wu et al.; named as adoptable in Sec. 3.9);
  *   completion: a vertex is complete when it has received d_in(v) messages
  *       (Sec. 3.8, k_v(t) = d_in(v)).
  *
@@ -144,6 +149,38 @@ void ao_gcn(int64_t n_dst, const int64_t *dst_ids, const int64_t *in_off, const 
     (void)n;
     ao_affine(n_dst, S, d, W, b, dout, Y);
     free(S);
+}
+
+/* GIN: y_v = ((1 + eps) x_v + sum_{u in N(v)} x_u) * W + b, W is d x dout. */
+void ao_gin(int64_t n_dst, const int64_t *dst_ids, const int64_t *in_off, const int32_t *in_src,
+            const float *X, int64_t d, double eps, const double *W, const double *b, int64_t dout,
+            double *Y) {
+    double *S = (double *)malloc((size_t)(n_dst > 0 ? n_dst : 1) * d * sizeof(double));
+    ao_neighbor_sum(n_dst, in_off, in_src, X, d, NULL, S);
+    for (int64_t i = 0; i < n_dst; ++i) {
+        int64_t v = dst_id(dst_ids, i);
+        for (int64_t k = 0; k < d; ++k) S[i * d + k] += (1.0 + eps) * (double)X[v * d + k];
+    }
+    ao_affine(n_dst, S, d, W, b, dout, Y);
+    free(S);
+}
+
+/* SGC hop: y_v = sum_{u in N(v)} x_u / sqrt(D_u D_v), D = in-degree of the graph as
+ * given (self-edges already added by the caller); no weights, Y is n_dst x d. */
+void ao_sym_propagate(int64_t n_dst, const int64_t *dst_ids, const int64_t *in_off,
+                      const int32_t *in_src, const int64_t *indeg, const float *X, int64_t d,
+                      double *Y) {
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t i = 0; i < n_dst; ++i) {
+        int64_t v = dst_id(dst_ids, i);
+        double *y = Y + i * d;
+        for (int64_t k = 0; k < d; ++k) y[k] = 0.0;
+        for (int64_t p = in_off[i]; p < in_off[i + 1]; ++p) {
+            int64_t u = in_src[p];
+            double g = 1.0 / sqrt((double)indeg[u] * (double)indeg[v]);
+            for (int64_t k = 0; k < d; ++k) y[k] += g * (double)X[u * d + k];
+        }
+    }
 }
 
 /* Z[r][:] = X[r][:] * W for the listed rows r (row_ids == NULL: all n_rows

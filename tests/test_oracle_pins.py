@@ -104,6 +104,82 @@ def test_gcn_vs_dense(oracle, seed, n, e):
     assert np.allclose(Y, ref, rtol=1e-12, atol=1e-12)
 
 
+def with_self_loops(n, src, col):
+    src2 = np.concatenate([src, np.arange(n)])
+    dst2 = np.concatenate([col.astype(np.int64), np.arange(n)])
+    order = np.argsort(src2, kind="stable")
+    src2, dst2 = src2[order], dst2[order]
+    off2 = np.cumsum(np.concatenate([[0], np.bincount(src2, minlength=n)])).astype(np.int64)
+    return off2, src2, dst2
+
+
+@pytest.mark.parametrize("seed,n,e,eps", [(31, 45, 170, 0.0), (32, 110, 640, 0.25), (33, 64, 300, -1.0)])
+def test_gin_vs_dense(oracle, seed, n, e, eps):
+    """GIN with one linear map against ((1+eps) I + A) X W + b on the dense
+    adjacency (multi-edges counted, isolated vertices keep (1+eps) x_v);
+    eps = -1 removes the self term and must give the plain neighbour sum."""
+    off, col, src = tiny_graph(seed, n, e)
+    rng = np.random.default_rng(seed)
+    d, dout = 6, 5
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    W = rng.standard_normal((d, dout))
+    b = rng.standard_normal(dout)
+    A = dense_adjacency(n, src, col)
+    ref = ((1.0 + eps) * np.eye(n) + A) @ X.astype(np.float64) @ W + b
+    il = oracle.InLists.from_csr(off, col)
+    Y = oracle.gin(il, X, W, b, eps)
+    assert np.allclose(Y, ref, rtol=1e-12, atol=1e-12)
+    if eps == -1.0:
+        assert np.allclose(oracle.gin(il, X, np.eye(d), None, eps), oracle.neighbor_sum(il, X), rtol=1e-13, atol=1e-13)
+    # a transposed weight matrix or a dropped self term must not pass
+    assert not np.allclose(Y, (A @ X.astype(np.float64)) @ W + b) or eps == -1.0
+
+
+@pytest.mark.parametrize("seed,n,e", [(34, 50, 220), (35, 120, 800)])
+def test_sgc_hops_vs_dense_power(oracle, seed, n, e):
+    """K propagation hops equal S^K X with S = D^-1/2 A D^-1/2 on the dense
+    adjacency (self loops included, D = row sums); one hop equals the GCN layer
+    with the identity as weight matrix."""
+    off, col, src = tiny_graph(seed, n, e, isolated=0)
+    off2, src2, dst2 = with_self_loops(n, src, col)
+    col2 = dst2.astype(np.int32)
+    rng = np.random.default_rng(seed)
+    d = 5
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    A = dense_adjacency(n, src2, dst2)
+    D = A.sum(1)
+    S = A / np.sqrt(np.outer(D, D))
+    il = oracle.InLists.from_csr(off2, col2)
+    indeg = oracle.in_degree(n, col2)
+    assert np.array_equal(indeg, D.astype(np.int64))
+    Y1 = oracle.sgc_hop(il, indeg, X)
+    assert np.allclose(Y1, S @ X.astype(np.float64), rtol=1e-12, atol=1e-12)
+    assert np.allclose(Y1, oracle.gcn(il, indeg, X, np.eye(d), None), rtol=1e-13, atol=1e-13)
+    # three hops through run_model (fp32 storage between hops), then the classifier
+    class P: pass
+    hops = []
+    for _ in range(2):
+        p = P(); p.W = None; p.bias = None; hops.append(p)
+    last = P(); last.W = rng.standard_normal((d, 3)); last.bias = rng.standard_normal(3); hops.append(last)
+    outs = oracle.run_model("sgc", off2, col2, X, hops, oracle.ACT_RELU, oracle.FMT_F32)
+    ref = S @ (S @ (S @ X.astype(np.float64))) @ last.W + last.bias
+    assert outs[0].shape == (n, d) and outs[2].shape == (n, 3)
+    assert np.allclose(outs[2], ref, rtol=1e-5, atol=1e-5)      # two roundings to fp32 on the way
+    assert not np.allclose(outs[2], np.maximum(ref, 0.0), rtol=1e-5, atol=1e-5)   # no activation in SGC
+
+
+def test_sgc_hop_regular_ring_is_the_local_average(oracle):
+    n, d = 10, 2
+    off, col = ring(n)
+    off2 = np.arange(n + 1, dtype=np.int64) * 3
+    col2 = np.empty(3 * n, dtype=np.int32)
+    col2[0::3], col2[1::3], col2[2::3] = col[0::2], col[1::2], np.arange(n)
+    X = np.random.default_rng(1).standard_normal((n, d)).astype(np.float32)
+    Y = oracle.sgc_hop(oracle.InLists.from_csr(off2, col2), oracle.in_degree(n, col2), X)
+    Xd = X.astype(np.float64)
+    assert np.allclose(Y, (np.roll(Xd, 1, 0) + np.roll(Xd, -1, 0) + Xd) / 3.0, rtol=1e-14, atol=1e-14)
+
+
 def dense_gat(n, A, X, W, b, a_src, a_dst, slope):
     heads, dh = a_src.shape
     Z = X.astype(np.float64) @ W
@@ -315,7 +391,7 @@ def relabel_csr(off, col, new_of_old):
     return off2, d2.astype(np.int32)
 
 
-@pytest.mark.parametrize("model", ["sage", "gcn", "gat"])
+@pytest.mark.parametrize("model", ["sage", "gcn", "gat", "gin"])
 def test_permutation_invariance(oracle, model):
     n, d, dout = 80, 6, 8
     off, col, src = tiny_graph(21, n, 400, isolated=0 if model == "gcn" else 3)
