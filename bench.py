@@ -38,6 +38,8 @@ def main() -> int:
     ap.add_argument("--workload", choices=["config2", "config3", "config4", "config5"], default="config5",
                     help="config5 (default) is the workload the metric is quoted on; the others are the smaller "
                          "parity workloads, timed for the record")
+    ap.add_argument("--layer-type", choices=["sage", "gin"], default="sage",
+                    help="config5 only: run the same graph and widths through GIN layers instead of SAGE-mean")
     ap.add_argument("--scale", type=int, default=None, help="R-MAT scale (default: the workload's own)")
     ap.add_argument("--edge-factor", type=int, default=32)
     ap.add_argument("--no-plan", action="store_true", help="push straight from the CSR (atomic path)")
@@ -92,14 +94,16 @@ def main() -> int:
     if args.workload == "config5":
         if args.scale is None:
             args.scale = 26
-        wl = workloads.config5(dev, scale=args.scale, reorder=ro, edge_factor=args.edge_factor, chunk=ck)
+        wl = workloads.config5(dev, scale=args.scale, reorder=ro, edge_factor=args.edge_factor, chunk=ck,
+                               model=args.layer_type)
     elif args.workload == "config2":
         wl = workloads.config2(dev, scale=args.scale or 20, reorder=ro, chunk=ck)
     elif args.workload == "config3":
         wl = workloads.config3(dev, scale=args.scale or 22, chunk=ck)
     else:
         wl = workloads.config4(dev, scale=args.scale or 22, chunk=ck)
-    is_headline = args.workload == "config5" and args.scale == 26 and args.edge_factor == 32 and ck is None
+    is_headline = (args.workload == "config5" and args.scale == 26 and args.edge_factor == 32 and ck is None
+                   and args.layer_type == "sage")
     torch.cuda.synchronize()
     n, e, chunk = wl.n, wl.e, wl.chunk
     log("generated %s: N=%d E=%d chunk=%d in %.1f s" % (wl.name, n, e, chunk, time.time() - t0))
@@ -134,7 +138,8 @@ def main() -> int:
         params.append((p.W.to(wl.store).to(dev).contiguous(), p.bias.to(wl.store).to(dev).contiguous()))
     outs = [torch.empty((n, wl.dims[li + 1]), dtype=wl.store, device=dev) for li in range(len(wl.layers))]
 
-    model_id = {"sage": atlas.MODEL_SAGE_MEAN, "gcn": atlas.MODEL_GCN_SYM, "gat": atlas.MODEL_GAT}[wl.model]
+    model_id = {"sage": atlas.MODEL_SAGE_MEAN, "gcn": atlas.MODEL_GCN_SYM, "gat": atlas.MODEL_GAT,
+                "gin": atlas.MODEL_GIN}[wl.model]
     sdt = atlas.DTYPE_BF16 if wl.store == torch.bfloat16 else atlas.DTYPE_F32
     between = atlas.ACT_ELU if wl.act == "elu" else atlas.ACT_RELU
     attn = [(None if p.attn_src is None else p.attn_src.to(wl.store).to(dev).contiguous(),
@@ -247,7 +252,7 @@ def main() -> int:
         "mfma_peak_tflops": 2500.0 if sdt == atlas.DTYPE_BF16 else 157.3,
         "frac_of_mfma_peak": round(upd_flops / upd_s / (2.5e15 if sdt == atlas.DTYPE_BF16 else 157.3e12), 4),
         # accumulator rows are read only for vertices that received something
-        "hbm_GBps": round((n_with_in * 4 * d + n * ((s_in * d if wl.model == "sage" else 0) + s_in * wl.dims[1]))
+        "hbm_GBps": round((n_with_in * 4 * d + n * ((s_in * d if wl.model in ("sage", "gin") else 0) + s_in * wl.dims[1]))
                           / upd_s / 1e9, 1),
         "rows_with_in_edges": n_with_in,
         "ms_per_layer": round(upd_ms / args.steps, 3),

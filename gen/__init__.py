@@ -292,8 +292,8 @@ class LayerParams:
     K = d_in otherwise.  GAT: column block k*(d_out/heads).. belongs to head
     k; attn_src / attn_dst are [heads, d_out/heads].
     """
-    W: torch.Tensor
-    bias: torch.Tensor
+    W: Optional[torch.Tensor]        # None: a layer without parameters (SGC propagation hop)
+    bias: Optional[torch.Tensor]
     attn_src: Optional[torch.Tensor] = None
     attn_dst: Optional[torch.Tensor] = None
 
@@ -310,9 +310,11 @@ def layer_params(seed: int, layer: int, model: str, d_in: int, d_out: int, heads
         a = math.sqrt(6.0 / (d_in + d_out))
         W = _uniform_param(seed, base, (2 * d_in, d_out), a)
         return LayerParams(W, bias)
-    if model == "gcn":
+    if model in ("gcn", "gin"):
         a = math.sqrt(6.0 / (d_in + d_out))
         return LayerParams(_uniform_param(seed, base, (d_in, d_out), a), bias)
+    if model == "sgc_hop":   # propagation only: no parameters
+        return LayerParams(None, None)
     if model == "gat":
         dh = d_out // heads
         a = math.sqrt(6.0 / (d_in + dh))

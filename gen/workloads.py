@@ -22,7 +22,7 @@ SEED0 = 0x5EED0000
 @dataclass
 class Workload:
     name: str
-    model: str                 # "sage" | "gcn" | "gat"
+    model: str                 # "sage" | "gcn" | "gat" | "gin"
     off: torch.Tensor          # int64 [n+1]
     col: torch.Tensor          # int32 [E]
     X: torch.Tensor            # [n, d0], storage dtype
@@ -96,9 +96,10 @@ def config4(device="cpu", scale: int = 22, chunk: Optional[int] = None) -> Workl
 
 
 def config5(device="cpu", scale: int = 26, reorder: Optional[Reorder] = None, chunk: Optional[int] = None,
-            edge_factor: int = 32) -> Workload:
-    """Large GraphSAGE-mean on R-MAT, bf16, d = 128, degree-ordered ids."""
+            edge_factor: int = 32, model: str = "sage") -> Workload:
+    """Large GraphSAGE-mean on R-MAT, bf16, d = 128, degree-ordered ids
+    (model="gin": the same graph and widths through GIN layers)."""
     seed = SEED0 + 5
     g = rmat_graph(seed, scale, edge_factor, device=device)
-    return _finish("config5_sage_rmat%d_bf16" % scale, "sage", g, seed, [128, 128, 128, 64],
+    return _finish("config5_%s_rmat%d_bf16" % (model, scale), model, g, seed, [128, 128, 128, 64],
                    chunk or max(64, (1 << scale) // 16), "uniform", torch.bfloat16, "relu", device, reorder=reorder)

@@ -51,7 +51,16 @@ enum atlas_status {
 };
 
 enum atlas_residency { ATLAS_RESIDENT_DEVICE = 0, ATLAS_RESIDENT_PINNED_HOST = 1 };
-enum atlas_model { ATLAS_MODEL_SAGE_MEAN = 0, ATLAS_MODEL_GCN_SYM = 1, ATLAS_MODEL_GAT = 2 };
+/* The layer types the paper evaluates (GraphConv, SAGEConv, GINConv: Sec. 4.1) and the two it names as
+ * adoptable into the same execution model (GAT, SGC: Sec. 3.9). */
+enum atlas_model {
+    ATLAS_MODEL_SAGE_MEAN = 0,
+    ATLAS_MODEL_GCN_SYM = 1,
+    ATLAS_MODEL_GAT = 2,
+    ATLAS_MODEL_GIN = 3,     /* sum aggregation, (1 + gin_eps) x own embedding added, one linear map */
+    ATLAS_MODEL_SGC_HOP = 4  /* one propagation step of SGC: the symmetric-normalised neighbour sum
+                                without weights; K hops = K-1 such layers and one GCN_SYM layer */
+};
 enum atlas_dtype { ATLAS_DTYPE_F32 = 0, ATLAS_DTYPE_BF16 = 1 };
 enum atlas_activation { ATLAS_ACT_NONE = 0, ATLAS_ACT_RELU = 1, ATLAS_ACT_ELU = 2 };
 enum atlas_flags {
@@ -92,7 +101,8 @@ typedef struct {
 /* Layer shape.  d_in must be a multiple of 64 (one wavefront holds a row),
  * at most 512 (fp32 SAGE_MEAN: at most 256); d_out a multiple of 16, at most
  * 256.  GAT: fp32 embeddings on a DEVICE graph, 1 <= heads <= 8, d_out a
- * multiple of 64 and of heads, and (d_out / heads) a multiple of (d_out / 64). */
+ * multiple of 64 and of heads, and (d_out / heads) a multiple of (d_out / 64).
+ * SGC_HOP: d_out == d_in (up to 512), activation NONE. */
 typedef struct {
     int32_t model;             /* atlas_model                                              */
     int32_t d_in, d_out;       /* input / output embedding width                           */
@@ -103,6 +113,7 @@ typedef struct {
     float neg_slope;           /* GAT LeakyReLU slope                                      */
     int64_t max_chunk_sources; /* upper bound on src_end - src_begin of any chunk          */
     int32_t flags;             /* atlas_flags                                              */
+    float gin_eps;             /* GIN: weight 1 + gin_eps of the vertex's own embedding    */
 } atlas_dims_t;
 
 /* Layer parameters, DEVICE memory, row-major, caller-owned; they are repacked
@@ -114,6 +125,9 @@ typedef struct {
  *              D = in-degree of the graph as given (self-edges already added).
  *   GAT:       W is [d_in][d_out], head k owns columns k*dh..(k+1)*dh-1,
  *              attn_src / attn_dst are [heads][dh].
+ *   GIN:       W is [d_in][d_out]; y = ((1 + gin_eps) x_v + sum of in-neighbours) W + b.
+ *   SGC_HOP:   no weights (all four pointers may be NULL);
+ *              y_v = sum_{u in N(v)} x_u / sqrt(D_u D_v), D as for GCN_SYM.
  * bias is [d_out] or NULL. */
 typedef struct {
     const void *W, *bias, *attn_src, *attn_dst;
@@ -137,7 +151,7 @@ typedef struct {
 
 /* Create the state of one layer (Sec. 3.4: pending-message tracker and
  * per-vertex arrays; Sec. 3.8: a vertex is complete after d_in(v) messages).
- * pending0[v] = d_in(v) (+1 for SAGE_MEAN: the vertex's own embedding is a
+ * pending0[v] = d_in(v) (+1 for SAGE_MEAN and GIN: the vertex's own embedding is a
  * message to itself that arrives with its own chunk).  Vertices with
  * pending0 == 0 are placed on the ready list here.  Accumulators are zeroed.
  * Enqueues on `hip_stream` (a hipStream_t, NULL = default stream) and returns

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libatlas.so")
 OK = 0
 E_NULL, E_BAD_DIMS, E_RANGE, E_ORDER, E_INCOMPLETE, E_OVERFLOW, E_HIP, E_NOMEM, E_STATE = range(-1, -10, -1)
 RESIDENT_DEVICE, RESIDENT_PINNED_HOST = 0, 1
-MODEL_SAGE_MEAN, MODEL_GCN_SYM, MODEL_GAT = 0, 1, 2
+MODEL_SAGE_MEAN, MODEL_GCN_SYM, MODEL_GAT, MODEL_GIN, MODEL_SGC_HOP = 0, 1, 2, 3, 4
 DTYPE_F32, DTYPE_BF16 = 0, 1
 ACT_NONE, ACT_RELU, ACT_ELU = 0, 1, 2
 FLAG_TIMING = 1
@@ -44,7 +44,7 @@ class atlas_dims_t(ctypes.Structure):
     _fields_ = [("model", ctypes.c_int32), ("d_in", ctypes.c_int32), ("d_out", ctypes.c_int32),
                 ("heads", ctypes.c_int32), ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
                 ("activation", ctypes.c_int32), ("neg_slope", ctypes.c_float),
-                ("max_chunk_sources", ctypes.c_int64), ("flags", ctypes.c_int32)]
+                ("max_chunk_sources", ctypes.c_int64), ("flags", ctypes.c_int32), ("gin_eps", ctypes.c_float)]
 
 
 class atlas_weights_t(ctypes.Structure):
@@ -137,9 +137,10 @@ def make_graph(num_vertices: int, num_edges: int, row_offsets, col_indices, in_d
 
 
 def make_dims(model: int, d_in: int, d_out: int, in_dtype: int, out_dtype: int, activation: int,
-              max_chunk_sources: int, heads: int = 1, neg_slope: float = 0.2, flags: int = 0) -> atlas_dims_t:
+              max_chunk_sources: int, heads: int = 1, neg_slope: float = 0.2, flags: int = 0,
+              gin_eps: float = 0.0) -> atlas_dims_t:
     return atlas_dims_t(model, d_in, d_out, heads, in_dtype, out_dtype, activation, neg_slope,
-                        max_chunk_sources, flags)
+                        max_chunk_sources, flags, gin_eps)
 
 
 def make_weights(W, bias, dtype: int, attn_src=None, attn_dst=None) -> atlas_weights_t:

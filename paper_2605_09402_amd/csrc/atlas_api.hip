@@ -160,9 +160,22 @@ struct atlas_layer {
 
 namespace {
 
+// layers whose update uses the vertex's own embedding: it travels as a self message
+bool has_self_term(int model) { return model == ATLAS_MODEL_SAGE_MEAN || model == ATLAS_MODEL_GIN; }
+// the aggregation kernels know three kinds of sum: plain, source-scaled by deg^-1/2, attention-weighted
+int aggregate_kind(int model) {
+    if (model == ATLAS_MODEL_GCN_SYM || model == ATLAS_MODEL_SGC_HOP) return 1;
+    return model == ATLAS_MODEL_GAT ? 2 : 0;
+}
+
 int check_dims(const atlas_dims_t &d, const atlas_weights_t &w, int residency) {
-    if (d.model != ATLAS_MODEL_SAGE_MEAN && d.model != ATLAS_MODEL_GCN_SYM && d.model != ATLAS_MODEL_GAT)
-        return ATLAS_E_BAD_DIMS;
+    if (d.model < ATLAS_MODEL_SAGE_MEAN || d.model > ATLAS_MODEL_SGC_HOP) return ATLAS_E_BAD_DIMS;
+    if (d.model == ATLAS_MODEL_SGC_HOP) {
+        // propagation only: no weights, the output row is the scaled accumulator row
+        if (d.d_out != d.d_in || d.activation != ATLAS_ACT_NONE) return ATLAS_E_BAD_DIMS;
+    } else if (!w.W) {
+        return ATLAS_E_NULL;
+    }
     if (d.model == ATLAS_MODEL_GAT) {
         // fp32 embeddings in HBM; a wave holds a transformed row and each lane's
         // elements must fall into one head
@@ -172,7 +185,8 @@ int check_dims(const atlas_dims_t &d, const atlas_weights_t &w, int residency) {
         if (!w.attn_src || !w.attn_dst) return ATLAS_E_NULL;
     }
     if (d.d_in <= 0 || d.d_in % 64 != 0 || d.d_in > 512) return ATLAS_E_BAD_DIMS;
-    if (d.d_out <= 0 || d.d_out % 16 != 0 || d.d_out > 256) return ATLAS_E_BAD_DIMS;
+    if (d.d_out <= 0 || d.d_out % 16 != 0 || (d.d_out > 256 && d.model != ATLAS_MODEL_SGC_HOP))
+        return ATLAS_E_BAD_DIMS;
     for (int dt : {d.in_dtype, d.out_dtype, w.dtype})
         if (dt != ATLAS_DTYPE_F32 && dt != ATLAS_DTYPE_BF16) return ATLAS_E_BAD_DIMS;
     if (d.activation < ATLAS_ACT_NONE || d.activation > ATLAS_ACT_ELU) return ATLAS_E_BAD_DIMS;
@@ -216,9 +230,9 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
     HIP_TRY(L->pending.alloc(n1 * sizeof(int32_t)));
     HIP_TRY(L->ready.alloc(n1 * sizeof(int32_t)));
     HIP_TRY(L->acc.alloc(n1 * L->acc_width * sizeof(float)));
-    L->emb_resident = d.model == ATLAS_MODEL_SAGE_MEAN && (d.flags & ATLAS_FLAG_EMB_RESIDENT) &&
+    L->emb_resident = has_self_term(d.model) && (d.flags & ATLAS_FLAG_EMB_RESIDENT) &&
                       L->g.residency == ATLAS_RESIDENT_DEVICE;
-    if (d.model == ATLAS_MODEL_SAGE_MEAN && !L->emb_resident)
+    if (has_self_term(d.model) && !L->emb_resident)
         HIP_TRY(L->self_rows.alloc(n1 * d.d_in * dtype_size(d.in_dtype)));
     HIP_TRY(L->packed_w.alloc(packed_weight_bytes(L->K, d.d_out, L->compute_bf16)));
     HIP_TRY(launch_fill_zero(L->counters.p, L->counters.bytes, s));
@@ -255,7 +269,7 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
         if (L->g.plan && L->g.plan->host) slot_bytes = std::max(slot_bytes, L->g.plan->max_stage_bytes);
         for (int i = 0; i < 2; ++i) {
             HIP_TRY(L->stage_col[i].alloc(slot_bytes));
-            if (d.model != ATLAS_MODEL_SAGE_MEAN)
+            if (!has_self_term(d.model))
                 HIP_TRY(L->stage_emb[i].alloc(static_cast<size_t>(std::min(C, std::max<int64_t>(n, 1))) * d.d_in *
                                               dtype_size(d.in_dtype)));
         }
@@ -293,9 +307,10 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
     }
     HIP_TRY(launch_init_pending(L->indeg, L->selfmsg, n, static_cast<int32_t *>(L->pending.p),
                                 static_cast<int32_t *>(L->ready.p), L->ctr(), s));
-    HIP_TRY(launch_pack_weights(w->W, w->dtype == ATLAS_DTYPE_BF16, L->K, d.d_out, L->compute_bf16,
-                                L->packed_w.p, s));
-    if (w->bias) {
+    if (d.model != ATLAS_MODEL_SGC_HOP)
+        HIP_TRY(launch_pack_weights(w->W, w->dtype == ATLAS_DTYPE_BF16, L->K, d.d_out, L->compute_bf16,
+                                    L->packed_w.p, s));
+    if (w->bias && d.model != ATLAS_MODEL_SGC_HOP) {
         HIP_TRY(L->bias.alloc(d.d_out * sizeof(float)));
         HIP_TRY(launch_to_f32(w->bias, w->dtype == ATLAS_DTYPE_BF16, d.d_out, static_cast<float *>(L->bias.p), s));
     }
@@ -311,7 +326,7 @@ int atlas_layer_init(const atlas_graph_t *graph, const atlas_dims_t *dims, const
     if (!graph || !dims || !weights || !out) return ATLAS_E_NULL;
     if (graph->num_vertices < 0 || graph->num_edges < 0) return ATLAS_E_RANGE;
     if (graph->num_vertices >= (int64_t(1) << 31)) return ATLAS_E_OVERFLOW;
-    if (!graph->row_offsets || (graph->num_edges > 0 && !graph->col_indices) || !weights->W) return ATLAS_E_NULL;
+    if (!graph->row_offsets || (graph->num_edges > 0 && !graph->col_indices)) return ATLAS_E_NULL;
     if (graph->residency != ATLAS_RESIDENT_DEVICE && graph->residency != ATLAS_RESIDENT_PINNED_HOST)
         return ATLAS_E_BAD_DIMS;
     int rc = check_dims(*dims, *weights, graph->residency);
@@ -323,7 +338,7 @@ int atlas_layer_init(const atlas_graph_t *graph, const atlas_dims_t *dims, const
     L->dims = *dims;
     L->n = graph->num_vertices;
     L->e = graph->num_edges;
-    L->selfmsg = dims->model == ATLAS_MODEL_SAGE_MEAN ? 1 : 0;
+    L->selfmsg = has_self_term(dims->model) ? 1 : 0;
     L->K = dims->model == ATLAS_MODEL_SAGE_MEAN ? 2 * dims->d_in : dims->d_in;
     L->compute_bf16 = dims->in_dtype == ATLAS_DTYPE_BF16;
     L->acc_width = dims->model == ATLAS_MODEL_GAT ? dims->d_out : dims->d_in;
@@ -394,7 +409,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
     a.src_end = src_end;
     a.d = d.d_in;
     a.in_bf16 = d.in_dtype == ATLAS_DTYPE_BF16;
-    a.model = d.model;
+    a.model = aggregate_kind(d.model);
     a.acc = static_cast<float *>(L->acc.p);
     a.pending = static_cast<int32_t *>(L->pending.p);
     a.indeg = L->indeg;
@@ -407,7 +422,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         if (L->x_base && base != L->x_base) return ATLAS_E_STATE;
         L->x_base = base;
     }
-    char *self_dst = d.model == ATLAS_MODEL_SAGE_MEAN && !L->emb_resident
+    char *self_dst = has_self_term(d.model) && !L->emb_resident
                          ? static_cast<char *>(L->self_rows.p) + static_cast<size_t>(src_begin) * row_bytes
                          : nullptr;
     // a chunk that coincides with a planned chunk runs from its destination-ordered edges
@@ -572,7 +587,8 @@ int atlas_flush_ready(atlas_layer_t *L, void *out, int64_t *n_flushed, void *hip
         HIP_TRY(hipStreamSynchronize(s));
     }
     UpdateArgs u{};
-    u.model = d.model;
+    u.model = d.model == ATLAS_MODEL_GIN ? 3 : d.model;
+    u.self_scale = 1.0f + d.gin_eps;
     u.d_in = d.d_in;
     u.d_out = d.d_out;
     u.K = L->K;
@@ -606,8 +622,10 @@ int atlas_flush_ready(atlas_layer_t *L, void *out, int64_t *n_flushed, void *hip
         f.out_bf16 = u.out_bf16;
         f.n = L->n;
         HIP_TRY(launch_gat_finalize(f, s));
+    } else if (d.model == ATLAS_MODEL_SGC_HOP) {
+        HIP_TRY(launch_scale_rows(u, s));
     } else
-    // SAGE rows become ready only after their own chunk: before the first
+    // SAGE / GIN rows become ready only after their own chunk: before the first
     // broadcast there is nothing to update (and no matrix to read own rows from)
     if (!(L->emb_resident && !L->x_base)) HIP_TRY(launch_update(u, s));
     HIP_TRY(launch_advance_head(L->ctr(), s));

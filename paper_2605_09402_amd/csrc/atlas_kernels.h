@@ -152,8 +152,10 @@ hipError_t launch_pack_weights(const void *W, int w_bf16, int K, int d_out, int 
 hipError_t launch_to_f32(const void *src, int src_bf16, int64_t count, float *dst, hipStream_t s);
 
 struct UpdateArgs {
-    int model;
-    int d_in, d_out, K;       // K = 2*d_in (SAGE) or d_in (GCN)
+    int model;                // 0 SAGE (own row || mean), 1 GCN (deg^-1/2 sum), 2 plain rows of `acc`,
+                              // 3 GIN (sum + self_scale * own row)
+    float self_scale;         // GIN: 1 + eps
+    int d_in, d_out, K;       // K = 2*d_in (SAGE) or d_in
     int in_bf16, out_bf16, compute_bf16;
     int activation;
     const float *acc;         // [N][d_in]
@@ -170,6 +172,8 @@ struct UpdateArgs {
 };
 // S5: gather ready rows, normalise, MFMA GEMM, bias, activation, scatter rows.
 hipError_t launch_update(const UpdateArgs &a, hipStream_t s);
+// SGC hop: out[v] = acc[v] * deg(v)^-1/2 for the ready rows (no contraction).
+hipError_t launch_scale_rows(const UpdateArgs &a, hipStream_t s);
 hipError_t launch_advance_head(int32_t *counters, hipStream_t s);
 
 // Degree ordering.

@@ -142,6 +142,11 @@ __device__ __forceinline__ void load_bias16(const UpdateArgs &a, int nbase, floa
 // together before the first is used.  d_in <= 512: at most 16 items.
 template <bool BF16C> struct OwnRaw4 { using type = float4; };
 template <> struct OwnRaw4<true> { using type = uint2; };
+__device__ __forceinline__ float4 own_to_f32(uint2 u) {   // four bf16 -> fp32
+    return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u),
+                       __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xffff0000u));
+}
+__device__ __forceinline__ float4 own_to_f32(float4 v) { return v; }
 
 template <bool BF16C, int SEGS>
 __device__ __forceinline__ void gather_rows(const UpdateArgs &a, typename Elem<BF16C>::type *A, int stride,
@@ -155,6 +160,45 @@ __device__ __forceinline__ void gather_rows(const UpdateArgs &a, typename Elem<B
     const int acc_base = a.model == 0 ? d : 0;  // SAGE: own row first, then the neighbour mean
     auto row_of = [&](int item) { return two ? item >> 1 : item; };
     auto col_of = [&](int item) { return (two ? (item & 1) * 256 : 0) + c4; };
+    if (a.model == 3) {   // GIN: sum + self_scale * own row, rounded once
+#pragma unroll
+        for (int base = 0; base < nitems; base += kBatch) {
+            float4 v[kBatch];
+            typename OwnRaw4<BF16C>::type o[kBatch];
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                const int rr = row_of(base + i), col = col_of(base + i);
+                const int32_t id = __builtin_amdgcn_readlane(idv, rr);
+                const bool fetch = id >= 0 && __builtin_amdgcn_readlane(has_aggv, rr) != 0;
+                const int cc = col < d ? col : 0;
+                v[i] = *reinterpret_cast<const float4 *>(a.acc + static_cast<int64_t>(fetch ? id : 0) * d + cc);
+                const int64_t oo = static_cast<int64_t>(id >= 0 ? id : 0) * d + cc;
+                if constexpr (BF16C) o[i] = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(a.self_rows) + oo);
+                else o[i] = *reinterpret_cast<const float4 *>(static_cast<const float *>(a.self_rows) + oo);
+            }
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                const int rr = row_of(base + i), col = col_of(base + i);
+                if (col >= d) continue;
+                const bool has_agg = __builtin_amdgcn_readlane(has_aggv, rr) != 0;
+                const float4 own = own_to_f32(o[i]);
+                const float x0 = (has_agg ? v[i].x : 0.f) + a.self_scale * own.x;
+                const float x1 = (has_agg ? v[i].y : 0.f) + a.self_scale * own.y;
+                const float x2 = (has_agg ? v[i].z : 0.f) + a.self_scale * own.z;
+                const float x3 = (has_agg ? v[i].w : 0.f) + a.self_scale * own.w;
+                typename Elem<BF16C>::type *dst = A + (w * kRows + rr) * stride + col;
+                if constexpr (BF16C) {
+                    *reinterpret_cast<uint2 *>(dst) = make_uint2(pack_bf16x2(x0, x1), pack_bf16x2(x2, x3));
+                } else {
+                    dst[0] = x0;
+                    dst[1] = x1;
+                    dst[2] = x2;
+                    dst[3] = x3;
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int base = 0; base < nitems; base += kBatch) {
         float4 v[kBatch];
@@ -370,7 +414,7 @@ __device__ __forceinline__ int32_t quad_bcast(int32_t v, int i) {
 // read row 0 and are dropped when the tile is stored; so do the accumulator
 // loads of vertices without in-edges (nothing was ever added to their rows,
 // and the one shared address stays in cache).
-template <bool BF16C, bool SAGE>
+template <bool BF16C, int OWN>
 __device__ __forceinline__ void pipe_issue_rows(const UpdateArgs &a, int32_t idv, int32_t degv, int lane,
                                                 RowRegs<BF16C> &r) {
     const int d = a.d_in;
@@ -383,7 +427,7 @@ __device__ __forceinline__ void pipe_issue_rows(const UpdateArgs &a, int32_t idv
         const int32_t row = id >= 0 ? id : 0;
         const int32_t arow = dg > 0 ? row : 0;
         r.acc[i] = *reinterpret_cast<const float4 *>(a.acc + static_cast<int64_t>(arow) * d + col);
-        if constexpr (SAGE) {
+        if constexpr (OWN != 0) {
             const int64_t o = static_cast<int64_t>(row) * d + col;
             if constexpr (BF16C) r.own[i] = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(a.self_rows) + o);
             else r.own[i] = *reinterpret_cast<const float4 *>(static_cast<const float *>(a.self_rows) + o);
@@ -394,7 +438,7 @@ __device__ __forceinline__ void pipe_issue_rows(const UpdateArgs &a, int32_t idv
 // Normalise and convert the rows loaded by pipe_issue_rows and store them into
 // the A tile.  Rows past the end of the ready list are stored as they came:
 // a row of A only feeds the same row of the product, which is never written.
-template <bool BF16C, bool SAGE>
+template <bool BF16C, int OWN>
 __device__ __forceinline__ void pipe_store_rows(const UpdateArgs &a, typename Elem<BF16C>::type *A, int stride,
                                                 int w, int lane, const RowRegs<BF16C> &r, int32_t degv) {
     const int d = a.d_in;
@@ -403,25 +447,37 @@ __device__ __forceinline__ void pipe_store_rows(const UpdateArgs &a, typename El
     // SAGE: mean = sum * (1/deg); GCN: deg^-1/2; plain linear map: 1
     const float scalev = a.model == 0 ? 1.0f / fd : (a.model == 1 ? 1.0f / sqrtf(fd) : 1.0f);
     if (c4 >= d) return;
-    typename Elem<BF16C>::type *row0 = A + (w * kPipeRows + (lane >> 5)) * stride + c4 + (SAGE ? d : 0);
+    typename Elem<BF16C>::type *row0 = A + (w * kPipeRows + (lane >> 5)) * stride + c4 + (OWN == 1 ? d : 0);
 #pragma unroll
     for (int i = 0; i < kPipeIters; ++i) {
         const float g = __uint_as_float(static_cast<uint32_t>(quad_bcast(static_cast<int32_t>(__float_as_uint(scalev)), i)));
         // a vertex without in-edges never had its accumulator written: its aggregate is zero
         const bool has_agg = quad_bcast(degv, i) > 0;
         typename Elem<BF16C>::type *row = row0 + 2 * i * stride;
-        const float4 v = r.acc[i];
+        float4 v = r.acc[i];
+        v.x *= g;
+        v.y *= g;
+        v.z *= g;
+        v.w *= g;
+        if constexpr (OWN == 2) {   // GIN: sum + self_scale * own row, rounded once
+            const float4 own = own_to_f32(r.own[i]);
+            v.x = (has_agg ? v.x : 0.f) + a.self_scale * own.x;
+            v.y = (has_agg ? v.y : 0.f) + a.self_scale * own.y;
+            v.z = (has_agg ? v.z : 0.f) + a.self_scale * own.z;
+            v.w = (has_agg ? v.w : 0.f) + a.self_scale * own.w;
+        }
+        const bool keep = OWN == 2 || has_agg;
         if constexpr (BF16C) {
-            const uint32_t lo = pack_bf16x2(v.x * g, v.y * g), hi = pack_bf16x2(v.z * g, v.w * g);
-            *reinterpret_cast<uint2 *>(row) = make_uint2(has_agg ? lo : 0u, has_agg ? hi : 0u);
+            const uint32_t lo = pack_bf16x2(v.x, v.y), hi = pack_bf16x2(v.z, v.w);
+            *reinterpret_cast<uint2 *>(row) = make_uint2(keep ? lo : 0u, keep ? hi : 0u);
             // bf16 own rows go to LDS as they were loaded; the aggregate is rounded once
-            if constexpr (SAGE) *reinterpret_cast<uint2 *>(row - d) = r.own[i];
+            if constexpr (OWN == 1) *reinterpret_cast<uint2 *>(row - d) = r.own[i];
         } else {
-            row[0] = has_agg ? v.x * g : 0.f;
-            row[1] = has_agg ? v.y * g : 0.f;
-            row[2] = has_agg ? v.z * g : 0.f;
-            row[3] = has_agg ? v.w * g : 0.f;
-            if constexpr (SAGE) {
+            row[0] = keep ? v.x : 0.f;
+            row[1] = keep ? v.y : 0.f;
+            row[2] = keep ? v.z : 0.f;
+            row[3] = keep ? v.w : 0.f;
+            if constexpr (OWN == 1) {
                 row[0 - d] = r.own[i].x;
                 row[1 - d] = r.own[i].y;
                 row[2 - d] = r.own[i].z;
@@ -479,7 +535,7 @@ __device__ __forceinline__ void contract_block(const typename Elem<BF16C>::type 
     }
 }
 
-template <bool BF16C, int PPW, bool SAGE>
+template <bool BF16C, int PPW, int OWN>
 __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
     using elem_t = typename Elem<BF16C>::type;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -552,14 +608,14 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
     int32_t id_b = load_ids(tile + 3 * G);
     int32_t deg0 = load_deg(id0), deg1 = load_deg(id1), deg_a = load_deg(id_a);
     RowRegs<BF16C> r0, r1;
-    pipe_issue_rows<BF16C, SAGE>(a, id0, deg0, lane, r0);
+    pipe_issue_rows<BF16C, OWN>(a, id0, deg0, lane, r0);
     __builtin_amdgcn_sched_barrier(0);   // keep the two sets' loads in this order, as in the loop
-    pipe_issue_rows<BF16C, SAGE>(a, id1, deg1, lane, r1);
+    pipe_issue_rows<BF16C, OWN>(a, id1, deg1, lane, r1);
 
     auto step = [&](RowRegs<BF16C> &regs, int32_t &idv, int32_t &degv, int buf) {
         elem_t *A = A0 + buf * a_elems;
         int32_t *tids = ids + buf * kTileRows;
-        pipe_store_rows<BF16C, SAGE>(a, A, stride, w, lane, regs, degv);
+        pipe_store_rows<BF16C, OWN>(a, A, stride, w, lane, regs, degv);
         if ((lane & 31) < 4) tids[w * kPipeRows + my_row] = idv;
         __syncthreads();
         idv = id_a;
@@ -567,7 +623,7 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
         id_a = id_b;
         deg_a = load_deg(id_a);
         id_b = load_ids(tile + 4 * G);
-        pipe_issue_rows<BF16C, SAGE>(a, idv, degv, lane, regs);
+        pipe_issue_rows<BF16C, OWN>(a, idv, degv, lane, regs);
 
         f32x16_t c[PPW];
 #pragma unroll
@@ -614,26 +670,57 @@ size_t pipelined_lds_bytes(int K, int d_out, bool bf16c) {
            2 * static_cast<size_t>(kTileRows) * (K + lds_pad(bf16c)) * es;
 }
 
-template <bool BF16C, int PPW, bool SAGE>
+template <bool BF16C, int PPW, int OWN>
 hipError_t launch_pipelined_t(const UpdateArgs &a, int grid, hipStream_t s) {
     const size_t lds = pipelined_lds_bytes(a.K, a.d_out, BF16C);
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_update_pipelined<BF16C, PPW, SAGE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_update_pipelined<BF16C, PPW, OWN>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL((k_update_pipelined<BF16C, PPW, SAGE>), dim3(grid), dim3(kPipeBlock), lds, s, a);
+    hipLaunchKernelGGL((k_update_pipelined<BF16C, PPW, OWN>), dim3(grid), dim3(kPipeBlock), lds, s, a);
     return hipGetLastError();
 }
 
+template <bool BF16C, int OWN>
+hipError_t launch_pipelined_o(const UpdateArgs &a, int grid, hipStream_t s) {
+    const int NB = (a.d_out + 31) / 32;
+    return 2 * NB <= 8 ? launch_pipelined_t<BF16C, 1, OWN>(a, grid, s) : launch_pipelined_t<BF16C, 2, OWN>(a, grid, s);
+}
+
+// own row: concatenated (SAGE), added (GIN) or unused
 template <bool BF16C>
 hipError_t launch_pipelined_c(const UpdateArgs &a, int grid, hipStream_t s) {
-    const int NB = (a.d_out + 31) / 32;
-    if (a.model == 0)
-        return 2 * NB <= 8 ? launch_pipelined_t<BF16C, 1, true>(a, grid, s) : launch_pipelined_t<BF16C, 2, true>(a, grid, s);
-    return 2 * NB <= 8 ? launch_pipelined_t<BF16C, 1, false>(a, grid, s) : launch_pipelined_t<BF16C, 2, false>(a, grid, s);
+    if (a.model == 0) return launch_pipelined_o<BF16C, 1>(a, grid, s);
+    if (a.model == 3) return launch_pipelined_o<BF16C, 2>(a, grid, s);
+    return launch_pipelined_o<BF16C, 0>(a, grid, s);
+}
+
+// SGC hop: the ready rows of the accumulator times deg^-1/2, one wave per row.
+__global__ __launch_bounds__(kBlock) void k_scale_rows(UpdateArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = static_cast<int64_t>(blockIdx.x) * (kBlock / 64) + (threadIdx.x >> 6);
+    const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (kBlock / 64);
+    const int head = a.counters[CTR_READY_HEAD];
+    const int tail = a.counters[CTR_READY_TAIL];
+    const int d = a.d_in;
+    for (int64_t i = head + wave; i < tail; i += nwaves) {
+        const int64_t v = a.ready[i];
+        const int32_t deg = a.indeg[v];
+        const float g = deg > 0 ? 1.0f / sqrtf(static_cast<float>(deg)) : 0.f;
+        for (int c = lane * 4; c < d; c += 256) {
+            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (deg > 0) x = *reinterpret_cast<const float4 *>(a.acc + v * d + c);   // never written otherwise
+            if (a.out_bf16)
+                *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(a.out) + v * d + c) =
+                    make_uint2(pack_bf16x2(x.x * g, x.y * g), pack_bf16x2(x.z * g, x.w * g));
+            else
+                *reinterpret_cast<float4 *>(static_cast<float *>(a.out) + v * d + c) =
+                    make_float4(x.x * g, x.y * g, x.z * g, x.w * g);
+        }
+    }
 }
 
 __global__ void k_advance_head(int32_t *counters) {
@@ -714,6 +801,18 @@ hipError_t launch_update(const UpdateArgs &a, hipStream_t s) {
     if (grid < 1) grid = 1;
     return a.compute_bf16 ? launch_update_c<true>(a, static_cast<int>(grid), s)
                           : launch_update_c<false>(a, static_cast<int>(grid), s);
+}
+
+hipError_t launch_scale_rows(const UpdateArgs &a, hipStream_t s) {
+    if (a.n <= 0) return hipSuccess;
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess)
+        (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (cus <= 0) cus = 256;
+    int64_t blocks = (a.n + (kBlock / 64) - 1) / (kBlock / 64);
+    if (blocks > static_cast<int64_t>(cus) * 8) blocks = static_cast<int64_t>(cus) * 8;
+    hipLaunchKernelGGL(k_scale_rows, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, s, a);
+    return hipGetLastError();
 }
 
 hipError_t launch_advance_head(int32_t *counters, hipStream_t s) {

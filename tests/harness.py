@@ -12,7 +12,8 @@ import torch
 import gen
 import paper_2605_09402_amd as atlas
 
-MODEL_ID = {"sage": atlas.MODEL_SAGE_MEAN, "gcn": atlas.MODEL_GCN_SYM, "gat": atlas.MODEL_GAT}
+MODEL_ID = {"sage": atlas.MODEL_SAGE_MEAN, "gcn": atlas.MODEL_GCN_SYM, "gat": atlas.MODEL_GAT,
+            "gin": atlas.MODEL_GIN, "sgc": atlas.MODEL_GCN_SYM}   # "sgc": hops without weights, then one GCN layer
 ORACLE_ACT = {"none": 0, "relu": 1, "elu": 2}
 TOL_F32 = 1e-4   # maximum row-normalised relative error, fp32 outputs
 TOL_BF16 = 2e-2  # the same where outputs are stored in bf16
@@ -31,6 +32,7 @@ class Case:
     act: str = "relu"
     heads: int = 1
     slope: float = 0.2
+    eps: float = 0.0             # GIN
 
     @property
     def n(self):
@@ -42,12 +44,16 @@ class Case:
 
 
 def make_case(model: str, g: gen.EdgeSource, seed: int, dims: List[int], chunk: int, feat: str = "uniform",
-              store: torch.dtype = torch.float32, act: str = "relu", heads: int = 1) -> Case:
+              store: torch.dtype = torch.float32, act: str = "relu", heads: int = 1, eps: float = 0.0) -> Case:
     off, col = gen.build_csr(g)
     X = gen.features(seed, g.n, dims[0], feat, store)
-    layers = [gen.layer_params(seed, li, model, dims[li], dims[li + 1], heads).rounded(store)
+    def kind(li):
+        if model != "sgc":
+            return model
+        return "gcn" if li + 2 == len(dims) else "sgc_hop"
+    layers = [gen.layer_params(seed, li, kind(li), dims[li], dims[li + 1], heads).rounded(store)
               for li in range(len(dims) - 1)]
-    return Case(model, off, col, X, layers, dims, chunk, store, act, heads)
+    return Case(model, off, col, X, layers, dims, chunk, store, act, heads, eps=eps)
 
 
 def row_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
@@ -63,7 +69,7 @@ def row_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
 def oracle_outputs(oracle, case: Case) -> List[np.ndarray]:
     fmt = oracle.FMT_BF16 if case.store == torch.bfloat16 else oracle.FMT_F32
     return oracle.run_model(case.model, case.off.numpy(), case.col.numpy(), case.X.float().numpy(), case.layers,
-                            ORACLE_ACT[case.act], fmt, case.slope)
+                            ORACLE_ACT[case.act], fmt, case.slope, case.eps)
 
 
 @dataclass
@@ -116,12 +122,17 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
         d_in, d_out = case.dims[li], case.dims[li + 1]
         last = li + 1 == len(case.layers)
         act = atlas.ACT_NONE if last else {"relu": atlas.ACT_RELU, "elu": atlas.ACT_ELU, "none": atlas.ACT_NONE}[case.act]
-        W = p.W.to(case.store).to(dev).contiguous()
-        b = p.bias.to(case.store).to(dev).contiguous()
+        model_id = MODEL_ID[case.model]
+        if case.model == "sgc":
+            act = atlas.ACT_NONE
+            if p.W is None:
+                model_id = atlas.MODEL_SGC_HOP
+        W = None if p.W is None else p.W.to(case.store).to(dev).contiguous()
+        b = None if p.bias is None else p.bias.to(case.store).to(dev).contiguous()
         a_s = None if p.attn_src is None else p.attn_src.to(case.store).to(dev).contiguous()
         a_d = None if p.attn_dst is None else p.attn_dst.to(case.store).to(dev).contiguous()
-        dims = atlas.make_dims(MODEL_ID[case.model], d_in, d_out, sdt, sdt, act, case.chunk, heads=case.heads,
-                               neg_slope=case.slope, flags=(atlas.FLAG_TIMING if timing else 0) |
+        dims = atlas.make_dims(model_id, d_in, d_out, sdt, sdt, act, case.chunk, heads=case.heads,
+                               neg_slope=case.slope, gin_eps=case.eps, flags=(atlas.FLAG_TIMING if timing else 0) |
                                (atlas.FLAG_EMB_RESIDENT if emb_resident else 0) |
                                (atlas.FLAG_PLANNED_ONLY if planned_only else 0))
         weights = atlas.make_weights(W, b, sdt, a_s, a_d)
@@ -190,7 +201,7 @@ keep: list = []  # pinned staging tensors kept alive until the run has synchroni
 def check_integers(oracle, case: Case, run: GpuRun, layer: int = 0):
     """Bit-exact: in-degree, pending after every chunk, ready set per flush."""
     il = oracle.InLists.from_csr(case.off.numpy(), case.col.numpy())
-    selfmsg = case.model == "sage"
+    selfmsg = case.model in ("sage", "gin")
     n, C = case.n, case.chunk
     assert np.array_equal(run.indeg.astype(np.int64), oracle.in_degree(n, case.col.numpy()))
     nchunks = (n + C - 1) // C
@@ -221,12 +232,12 @@ def check_outputs(oracle, case: Case, run: GpuRun):
 
 
 def case_from_edges(model: str, n: int, src, dst, seed: int, dims: List[int], chunk: int, feat: str = "uniform",
-                    store: torch.dtype = torch.float32, act: str = "relu", heads: int = 1) -> Case:
+                    store: torch.dtype = torch.float32, act: str = "relu", heads: int = 1, eps: float = 0.0) -> Case:
     """A case over an explicit edge list (hand-made degenerate graphs)."""
     src = torch.as_tensor(src, dtype=torch.int64)
     dst = torch.as_tensor(dst, dtype=torch.int64)
     g = gen.EdgeSource(n, 1, lambda k: (src, dst))
-    return make_case(model, g, seed, dims, chunk, feat, store, act, heads)
+    return make_case(model, g, seed, dims, chunk, feat, store, act, heads, eps)
 
 
 # --------------------------------------------------------------------------

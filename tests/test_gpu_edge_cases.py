@@ -38,9 +38,9 @@ def both_paths(H, oracle, case, ints=True, **kw):
             assert st["edges_processed"] == case.e and st["vertices_flushed"] == case.n
 
 
-@pytest.mark.parametrize("model", ["sage", "gcn"])
+@pytest.mark.parametrize("model", ["sage", "gcn", "gin"])
 def test_no_edges(oracle, H, model):
-    """N vertices, E = 0: SAGE completes by self messages, GCN at layer start."""
+    """N vertices, E = 0: SAGE and GIN complete by self messages, GCN at layer start."""
     case = H.case_from_edges(model, 300, [], [], SEED, [64, 32], 128)
     both_paths(H, oracle, case)
 
@@ -201,6 +201,16 @@ def test_api_errors(atlas, H):
     with pytest.raises(atlas.AtlasError):
         atlas.atlas_layer_finish(h)
     assert status(atlas.atlas_plan_create, atlas.make_graph(case.n, case.e, off, col), 0) == atlas.E_BAD_DIMS
+
+    # SGC propagation hop: no weights, but the widths must agree and there is no activation
+    none = atlas.make_weights(None, None, atlas.DTYPE_F32)
+    sgc = dict(model=atlas.MODEL_SGC_HOP, d_in=64, d_out=64)
+    assert status(atlas.atlas_layer_init, g, dims(model=atlas.MODEL_SGC_HOP), none) == atlas.E_BAD_DIMS   # 64 -> 16
+    assert status(atlas.atlas_layer_init, g, dims(activation=atlas.ACT_RELU, **sgc), none) == atlas.E_BAD_DIMS
+    assert status(atlas.atlas_layer_init, g, dims(model=atlas.MODEL_GIN), none) == atlas.E_NULL   # GIN needs W
+    h = atlas.atlas_layer_init(g, dims(**sgc), none)
+    with pytest.raises(atlas.AtlasError):
+        atlas.atlas_layer_finish(h)
 
     # planned-only promise broken: the plan was built for 256-source chunks, the caller sends 128
     plan_h = atlas.atlas_plan_create(atlas.make_graph(case.n, case.e, off, col), 256)

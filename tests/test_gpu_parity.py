@@ -144,3 +144,33 @@ def test_greedy_score_ordering(oracle, H):
     il0 = oracle.InLists.from_csr(off.numpy(), col.numpy())
     il1 = oracle.InLists.from_csr(case.off.numpy(), case.col.numpy())
     print("mean span: original %.0f, score order %.0f" % (oracle.message_span(il0).mean(), oracle.message_span(il1).mean()))
+
+
+@pytest.mark.parametrize("store", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("plan", [False, True], ids=["csr_stream", "planned"])
+def test_gin_rmat(oracle, H, plan, store):
+    """GIN (sum aggregation, (1 + eps) x own embedding, one linear map per layer;
+    the paper's GINConv runs, Sec. 4.1) on R-MAT scale 13, 128 -> 128 -> 64,
+    eps = 0.25; the planned variant also skips the accumulator zero fill."""
+    g = gen.rmat_graph(SEED + 7, 13, 16)
+    case = H.make_case("gin", g, SEED + 7, [128, 128, 64], 1 << 9, store=store, eps=0.25,
+                       feat="normal" if store == torch.float32 else "uniform")
+    run = H.run_gpu(case, snapshots=True, plan=plan, planned_only=plan)
+    H.check_integers(oracle, case, run, layer=0)
+    H.check_integers(oracle, case, run, layer=1)
+    print("gin", H.check_outputs(oracle, case, run))
+
+
+@pytest.mark.parametrize("d", [64, 256, 512])
+@pytest.mark.parametrize("plan", [False, True], ids=["csr_stream", "planned"])
+def test_sgc_three_hops(oracle, H, plan, d):
+    """SGC (named as adoptable, Sec. 3.9): two propagation-only hops and the
+    final GCN layer, no activation, on R-MAT scale 12 with self loops."""
+    g = gen.rmat_graph(SEED + 8, 12, 12, random_ids=True, self_loops=True)
+    dims = [d, d, d, 48] if d <= 256 else [d, d, d]
+    case = H.make_case("sgc", g, SEED + 8, dims, 700)
+    if d > 256:   # widths above 256 exist for the hops only: make the last layer a hop as well
+        case.layers[-1] = gen.layer_params(SEED + 8, 2, "sgc_hop", d, d)
+    run = H.run_gpu(case, snapshots=True, plan=plan, planned_only=plan)
+    H.check_integers(oracle, case, run, layer=0)
+    print("sgc", d, H.check_outputs(oracle, case, run))
