@@ -239,6 +239,73 @@ def message_span(il: "InLists", selfmsg: bool = False) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------
+# bounded hot store (Sec. 3.5): which partial states are evicted and reloaded
+# --------------------------------------------------------------------------
+
+EVICT_MIN_PENDING, EVICT_MAX_PENDING = 0, 1
+
+
+def hot_store_trace(off: np.ndarray, col: np.ndarray, chunk: int, slots: int, selfmsg: bool,
+                    policy: int = EVICT_MIN_PENDING):
+    """Replay of the memory manager of Sec. 3.5 for one layer streamed in
+    chunks of `chunk` sources with `slots` hot-store slots, written as plain
+    set bookkeeping (small graphs only).
+
+    A vertex holds a slot from its first message until it has completed (all
+    d_in messages, plus its own with `selfmsg`) and been flushed, which happens
+    at the end of every chunk.  The self message carries no data: it never
+    starts a state, but it needs the state in the hot store once one exists.
+    Before a chunk's messages are applied, every destination of the chunk
+    without a slot needs one; if the free slots do not suffice, the shortfall
+    is evicted from the vertices that are hot, are not addressed by this chunk
+    and are still incomplete -- fewest pending messages first (most, with
+    EVICT_MAX_PENDING), ties by vertex id.  An evicted vertex that is addressed
+    again is reloaded.  Returns (evictions, reloads, peak_hot) with per-chunk
+    lists for the first two; raises ValueError if a chunk does not fit."""
+    off = np.asarray(off, dtype=np.int64)
+    col = np.asarray(col, dtype=np.int64)
+    n = off.size - 1
+    pending = np.bincount(col, minlength=n).astype(np.int64) + (1 if selfmsg else 0)
+    hot, cold = set(), set()
+    evictions, reloads, peak = [], [], 0
+    for b0 in range(0, n, chunk):
+        b1 = min(n, b0 + chunk)
+        dst = col[off[b0]:off[b1]]
+        addressed = set(int(v) for v in np.unique(dst))
+        if selfmsg:
+            addressed |= {v for v in range(b0, b1) if v in hot or v in cold}
+        need = sorted(v for v in addressed if v not in hot)
+        free = slots - len(hot)
+        ev = 0
+        if len(need) > free:
+            ev = len(need) - free
+            cands = [v for v in hot if v not in addressed and pending[v] > 0]
+            if len(cands) < ev:
+                raise ValueError("chunk [%d, %d) does not fit %d slots" % (b0, b1, slots))
+            sign = 1 if policy == EVICT_MIN_PENDING else -1
+            cands.sort(key=lambda v: (sign * int(pending[v]), v))
+            for v in cands[:ev]:
+                hot.remove(v)
+                cold.add(v)
+        rl = 0
+        for v in need:
+            if v in cold:
+                cold.remove(v)
+                rl += 1
+            hot.add(v)
+        peak = max(peak, len(hot))
+        np.subtract.at(pending, dst, 1)
+        if selfmsg:
+            pending[b0:b1] -= 1
+        for v in [v for v in hot if pending[v] == 0]:   # completed: flushed, slot released
+            hot.remove(v)
+        evictions.append(ev)
+        reloads.append(rl)
+    assert not hot and not cold and (pending == 0).all()
+    return evictions, reloads, peak
+
+
+# --------------------------------------------------------------------------
 # whole-model chain
 # --------------------------------------------------------------------------
 

@@ -512,3 +512,75 @@ def test_score_order_is_sorted(oracle):
     same = ss[:-1] == ss[1:]
     assert np.all(old_of_new[:-1][same] < old_of_new[1:][same])
     assert np.array_equal(np.sort(old_of_new), np.arange(300))
+
+
+# --------------------------------------------------------------------------
+# bounded hot store replay (Sec. 3.5)
+# --------------------------------------------------------------------------
+
+def _hot_example():
+    src = [0, 0, 1, 1, 2, 2, 3, 3, 4, 5, 6, 7]
+    dst = [4, 5, 4, 6, 5, 6, 6, 7, 5, 7, 4, 6]
+    off = np.cumsum(np.concatenate([[0], np.bincount(src, minlength=8)])).astype(np.int64)
+    return off, np.array(dst, dtype=np.int32)
+
+
+def test_hot_store_hand_worked_example(oracle):
+    """The fixture was worked out by hand (see its comments)."""
+    off, col = _hot_example()
+    want = {}
+    cur = None
+    for line in open(os.path.join(HERE, "golden", "hot_store_example.txt")):
+        t = line.split()
+        if not t or t[0].startswith("#"):
+            continue
+        if t[0] == "slots":
+            cur = want.setdefault(int(t[1]), {})
+        else:
+            cur[t[0]] = [int(x) for x in t[1:]]
+    for slots, w in want.items():
+        ev, rl, peak = oracle.hot_store_trace(off, col, 2, slots, selfmsg=False)
+        assert ev == w["evictions"] and rl == w["reloads"] and [peak] == w["peak_hot"]
+    with pytest.raises(ValueError):
+        oracle.hot_store_trace(off, col, 2, 2, selfmsg=False)
+    # evicting the vertex with the MOST pending messages instead: in chunk 1 the only candidate is
+    # still v4, so this example cannot tell the policies apart; a second one can
+    ev2, rl2, _ = oracle.hot_store_trace(off, col, 2, 3, selfmsg=False, policy=oracle.EVICT_MAX_PENDING)
+    assert ev2 == [0, 1, 0, 0] and rl2 == [0, 0, 0, 1]
+
+
+def test_hot_store_policy_and_invariants(oracle):
+    """Chain example where the policies differ, and counting invariants on random graphs."""
+    # chunk 0 = {0}: 0 -> 5 (pending 5: 3 -> 2), 0 -> 6 (pending 6: 2 -> 1); chunk 1 = {1}: 1 -> 7.
+    # 2 slots: chunk 1 needs one slot, candidates v5 (2 pending) and v6 (1 pending).
+    src = [0, 0, 1, 2, 2, 3, 3, 4]
+    dst = [5, 6, 7, 5, 6, 5, 7, 7]
+    off = np.cumsum(np.concatenate([[0], np.bincount(src, minlength=8)])).astype(np.int64)
+    col = np.array(dst, dtype=np.int32)
+    ev_min, rl_min, _ = oracle.hot_store_trace(off, col, 1, 2, selfmsg=False, policy=oracle.EVICT_MIN_PENDING)
+    ev_max, rl_max, _ = oracle.hot_store_trace(off, col, 1, 2, selfmsg=False, policy=oracle.EVICT_MAX_PENDING)
+    # min-pending evicts v6 in chunk 1; chunk 2 (2 -> 5, 2 -> 6) reloads v6 and must evict v7 (v5 addressed);
+    # v6 completes there.  chunk 3 (3 -> 5, 3 -> 7): v7 reloaded into the slot v6 left.
+    assert ev_min[:4] == [0, 1, 1, 0] and rl_min[:4] == [0, 0, 1, 1]
+    # max-pending evicts v5 in chunk 1 instead; chunk 2 addresses v5 and v6: reload v5, evict v7.
+    assert ev_max[:4] == [0, 1, 1, 0] and rl_max[:4] == [0, 0, 1, 1]
+    assert sum(rl_min) == sum(ev_min) and sum(rl_max) == sum(ev_max)
+
+    rng = np.random.default_rng(5)
+    for selfmsg in (False, True):
+        off, col, _ = tiny_graph(40 + selfmsg, 120, 900, isolated=4)
+        indeg = np.bincount(col, minlength=120)
+        n_started = int((indeg > 0).sum())
+        ev, rl, peak = oracle.hot_store_trace(off, col, 16, n_started, selfmsg)
+        assert sum(ev) == 0 and sum(rl) == 0 and peak <= n_started        # enough slots: no traffic
+        prev = None
+        for slots in (n_started, 100, 90, 80):
+            try:
+                ev, rl, peak = oracle.hot_store_trace(off, col, 16, slots, selfmsg)
+            except ValueError:
+                break
+            assert peak <= slots
+            assert sum(rl) == sum(ev)          # whatever is evicted is incomplete and comes back exactly once per eviction
+            if prev is not None:
+                assert sum(ev) >= prev          # fewer slots never mean fewer evictions here
+            prev = sum(ev)
