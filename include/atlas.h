@@ -114,7 +114,28 @@ typedef struct {
     int64_t max_chunk_sources; /* upper bound on src_end - src_begin of any chunk          */
     int32_t flags;             /* atlas_flags                                              */
     float gin_eps;             /* GIN: weight 1 + gin_eps of the vertex's own embedding    */
+    int64_t hot_slots;         /* 0 (or >= N): one accumulator row per vertex.  0 < hot_slots < N:
+                                  bounded accumulator store with that many rows, see below  */
+    int32_t evict_policy;      /* atlas_evict_policy of the bounded store                   */
 } atlas_dims_t;
+
+/* Bounded accumulator store (the paper's memory manager, Sec. 3.5, with HBM as the
+ * hot tier and library-owned pinned host memory as the cold tier).  Only vertices
+ * that have received a message and are not yet flushed hold one of the hot_slots
+ * rows.  Before a chunk is pushed every vertex it addresses gets a row; when the
+ * free rows do not suffice, the shortfall is evicted to the cold tier from the
+ * resident vertices the chunk does not address, by evict_policy, ties by vertex
+ * id, and an evicted vertex is reloaded when a later chunk addresses it.  Rows
+ * are released by the atlas_flush_ready that writes the vertex's output, so the
+ * rows needed at once are the chunk's destinations plus the completed vertices
+ * not yet flushed; atlas_broadcast_chunk returns E_NOMEM when they do not fit.
+ * Requires a DEVICE graph with a plan and chunks that coincide with the planned
+ * ones (as with ATLAS_FLAG_PLANNED_ONLY); not available for GAT.  Each chunk
+ * costs one wait for the stream (the host reads the slot counts). */
+enum atlas_evict_policy {
+    ATLAS_EVICT_MIN_PENDING = 0, /* fewest pending messages first (the paper's policy)      */
+    ATLAS_EVICT_MAX_PENDING = 1  /* most pending messages first (for comparison)            */
+};
 
 /* Layer parameters, DEVICE memory, row-major, caller-owned; they are repacked
  * at init and need not outlive atlas_layer_init.
@@ -147,6 +168,9 @@ typedef struct {
     float ms_update;            /* ATLAS_FLAG_TIMING: sum over flushes of update kernels    */
     float ms_copy;              /* ATLAS_FLAG_TIMING: sum of staging copies                 */
     float ms_init;              /* ATLAS_FLAG_TIMING: layer set-up kernels                  */
+    int64_t hot_evictions;      /* bounded store: rows written to the cold tier             */
+    int64_t hot_reloads;        /* bounded store: rows read back from the cold tier         */
+    int64_t hot_peak_slots;     /* bounded store: most rows in use at once                  */
 } atlas_layer_stats_t;
 
 /* Create the state of one layer (Sec. 3.4: pending-message tracker and

@@ -23,6 +23,7 @@ ACT_NONE, ACT_RELU, ACT_ELU = 0, 1, 2
 FLAG_TIMING = 1
 FLAG_EMB_RESIDENT = 2
 FLAG_PLANNED_ONLY = 4
+EVICT_MIN_PENDING, EVICT_MAX_PENDING = 0, 1
 DBG_INDEG, DBG_PENDING, DBG_READY, DBG_READY_COUNT, DBG_ACC = range(5)
 
 EXPORTS = [
@@ -44,7 +45,8 @@ class atlas_dims_t(ctypes.Structure):
     _fields_ = [("model", ctypes.c_int32), ("d_in", ctypes.c_int32), ("d_out", ctypes.c_int32),
                 ("heads", ctypes.c_int32), ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
                 ("activation", ctypes.c_int32), ("neg_slope", ctypes.c_float),
-                ("max_chunk_sources", ctypes.c_int64), ("flags", ctypes.c_int32), ("gin_eps", ctypes.c_float)]
+                ("max_chunk_sources", ctypes.c_int64), ("flags", ctypes.c_int32), ("gin_eps", ctypes.c_float),
+                ("hot_slots", ctypes.c_int64), ("evict_policy", ctypes.c_int32)]
 
 
 class atlas_weights_t(ctypes.Structure):
@@ -58,7 +60,8 @@ class atlas_layer_stats_t(ctypes.Structure):
                 ("num_chunks", ctypes.c_int64), ("num_flushes", ctypes.c_int64),
                 ("bytes_copied_h2d", ctypes.c_int64), ("ms_aggregate", ctypes.c_float),
                 ("ms_self", ctypes.c_float), ("ms_update", ctypes.c_float), ("ms_copy", ctypes.c_float),
-                ("ms_init", ctypes.c_float)]
+                ("ms_init", ctypes.c_float), ("hot_evictions", ctypes.c_int64), ("hot_reloads", ctypes.c_int64),
+                ("hot_peak_slots", ctypes.c_int64)]
 
 
 class AtlasError(RuntimeError):
@@ -138,9 +141,9 @@ def make_graph(num_vertices: int, num_edges: int, row_offsets, col_indices, in_d
 
 def make_dims(model: int, d_in: int, d_out: int, in_dtype: int, out_dtype: int, activation: int,
               max_chunk_sources: int, heads: int = 1, neg_slope: float = 0.2, flags: int = 0,
-              gin_eps: float = 0.0) -> atlas_dims_t:
+              gin_eps: float = 0.0, hot_slots: int = 0, evict_policy: int = 0) -> atlas_dims_t:
     return atlas_dims_t(model, d_in, d_out, heads, in_dtype, out_dtype, activation, neg_slope,
-                        max_chunk_sources, flags, gin_eps)
+                        max_chunk_sources, flags, gin_eps, hot_slots, evict_policy)
 
 
 def make_weights(W, bias, dtype: int, attn_src=None, attn_dst=None) -> atlas_weights_t:

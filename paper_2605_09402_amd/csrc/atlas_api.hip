@@ -74,6 +74,26 @@ struct Buf {
 
 size_t dtype_size(int dt) { return dt == ATLAS_DTYPE_BF16 ? 2 : 4; }
 
+// Cold tier of the bounded accumulator store: one pinned host buffer per
+// process, grown on demand and kept until atlas_release_cache (pinning tens of
+// gigabytes takes seconds; layers with a bounded store run one after another
+// and reuse it).
+void *g_cold = nullptr;
+size_t g_cold_bytes = 0;
+hipError_t cold_buffer(size_t bytes, void **out) {
+    std::lock_guard<std::mutex> lk(g_cache_mu);
+    if (g_cold_bytes < bytes) {
+        if (g_cold) (void)hipHostFree(g_cold);
+        g_cold = nullptr;
+        g_cold_bytes = 0;
+        hipError_t e = hipHostMalloc(&g_cold, bytes, hipHostMallocDefault);
+        if (e != hipSuccess) return e;
+        g_cold_bytes = bytes;
+    }
+    *out = g_cold;
+    return hipSuccess;
+}
+
 // The chunk loader's copy stream is created once per process and shared by
 // all layers: HIP spreads streams over a few hardware queues, and a stream
 // created anew for every layer can land on the queue that carries the caller's
@@ -124,6 +144,12 @@ struct atlas_layer {
     const int32_t *indeg = nullptr;
     const int64_t *off_dev = nullptr;  // device-visible row offsets
 
+    // bounded accumulator store (dims.hot_slots > 0)
+    bool bounded = false;
+    HotStore hs{};
+    Buf hs_slot_of, hs_owner, hs_free, hs_stamp, hs_need, hs_ctr, hs_keys, hs_keys_sorted, hs_sort_temp;
+    int64_t hot_evictions = 0, hot_reloads = 0;
+
     bool planned_only = false;         // every chunk runs from the plan: no accumulator zero fill
     bool emb_resident = false;         // own rows are read from the caller's matrix
     const char *x_base = nullptr;      // base of that matrix (set by the first chunk)
@@ -147,7 +173,8 @@ struct atlas_layer {
     void destroy() {
         for (Buf *b : {&indeg_own, &pending, &ready, &counters, &counters64, &acc, &self_rows, &packed_w, &bias,
                        &dev_off, &stage_col[0], &stage_col[1], &stage_emb[0], &stage_emb[1], &gat_el, &gat_er,
-                       &gat_mcur, &gat_mnext, &gat_l, &gat_wa, &gat_z, &gat_scores})
+                       &gat_mcur, &gat_mnext, &gat_l, &gat_wa, &gat_z, &gat_scores, &hs_slot_of, &hs_owner, &hs_free,
+                       &hs_stamp, &hs_need, &hs_ctr, &hs_keys, &hs_keys_sorted, &hs_sort_temp})
             b->release();
         for (auto *v : {&t_agg, &t_self, &t_upd, &t_copy, &t_init})
             for (auto &sp : *v) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
@@ -191,6 +218,9 @@ int check_dims(const atlas_dims_t &d, const atlas_weights_t &w, int residency) {
         if (dt != ATLAS_DTYPE_F32 && dt != ATLAS_DTYPE_BF16) return ATLAS_E_BAD_DIMS;
     if (d.activation < ATLAS_ACT_NONE || d.activation > ATLAS_ACT_ELU) return ATLAS_E_BAD_DIMS;
     if (d.max_chunk_sources <= 0) return ATLAS_E_BAD_DIMS;
+    if (d.hot_slots < 0 || d.evict_policy < ATLAS_EVICT_MIN_PENDING || d.evict_policy > ATLAS_EVICT_MAX_PENDING)
+        return ATLAS_E_BAD_DIMS;
+    if (d.hot_slots > 0 && (d.model == ATLAS_MODEL_GAT || residency != ATLAS_RESIDENT_DEVICE)) return ATLAS_E_BAD_DIMS;
     const int K = d.model == ATLAS_MODEL_SAGE_MEAN ? 2 * d.d_in : d.d_in;
     const bool bf16c = d.in_dtype == ATLAS_DTYPE_BF16;
     const size_t lds = 256 + static_cast<size_t>(64) * (K + (bf16c ? 8 : 1)) * (bf16c ? 2 : 4);
@@ -229,7 +259,15 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
     HIP_TRY(L->counters64.alloc(CTR64_COUNT * sizeof(unsigned long long)));
     HIP_TRY(L->pending.alloc(n1 * sizeof(int32_t)));
     HIP_TRY(L->ready.alloc(n1 * sizeof(int32_t)));
-    HIP_TRY(L->acc.alloc(n1 * L->acc_width * sizeof(float)));
+    // A bounded store needs the per-chunk destination lists of a plan; it implies the planned-only promise.
+    L->bounded = d.hot_slots > 0 && d.hot_slots < n;
+    if (L->bounded) {
+        const atlas_plan *pl = L->g.plan;
+        if (!pl || pl->host || pl->n != n || pl->e != L->e) return ATLAS_E_STATE;
+        if (d.hot_slots >= (int64_t(1) << 31)) return ATLAS_E_OVERFLOW;
+    }
+    const size_t acc_rows = L->bounded ? static_cast<size_t>(d.hot_slots) : n1;
+    HIP_TRY(L->acc.alloc(acc_rows * L->acc_width * sizeof(float)));
     L->emb_resident = has_self_term(d.model) && (d.flags & ATLAS_FLAG_EMB_RESIDENT) &&
                       L->g.residency == ATLAS_RESIDENT_DEVICE;
     if (has_self_term(d.model) && !L->emb_resident)
@@ -240,11 +278,41 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
     // With ATLAS_FLAG_PLANNED_ONLY every row is first written (not added to) by
     // its destination's first group, so the zero fill is skipped.  GAT rescales
     // its accumulators and keeps the fill.
-    L->planned_only = (d.flags & ATLAS_FLAG_PLANNED_ONLY) && L->g.plan && d.model != ATLAS_MODEL_GAT &&
+    L->planned_only = ((d.flags & ATLAS_FLAG_PLANNED_ONLY) || L->bounded) && L->g.plan && d.model != ATLAS_MODEL_GAT &&
                       L->g.plan->host == (L->g.residency == ATLAS_RESIDENT_PINNED_HOST) &&
                       L->g.plan->n == n && L->g.plan->e == L->e;
     if (!L->planned_only)
         HIP_TRY(launch_fill_zero(L->acc.p, static_cast<size_t>(n) * L->acc_width * sizeof(float), s));
+    if (L->bounded) {
+        const size_t S = static_cast<size_t>(d.hot_slots);
+        HIP_TRY(L->hs_slot_of.alloc(n1 * sizeof(int32_t)));
+        HIP_TRY(L->hs_stamp.alloc(n1 * sizeof(int32_t)));
+        HIP_TRY(L->hs_owner.alloc(S * sizeof(int32_t)));
+        HIP_TRY(L->hs_free.alloc(S * sizeof(int32_t)));
+        HIP_TRY(L->hs_need.alloc(S * sizeof(int32_t)));
+        HIP_TRY(L->hs_ctr.alloc(HS_COUNT * sizeof(int32_t)));
+        HIP_TRY(L->hs_keys.alloc(S * sizeof(uint64_t)));
+        HIP_TRY(L->hs_keys_sorted.alloc(S * sizeof(uint64_t)));
+        HIP_TRY(L->hs_sort_temp.alloc(hot_sort_temp_bytes(d.hot_slots)));
+        void *cold = nullptr;
+        if (hipError_t e = cold_buffer(n1 * L->acc_width * sizeof(float), &cold); e != hipSuccess) {
+            (void)hip_fail(e, "hipHostMalloc(cold store)");
+            return ATLAS_E_NOMEM;
+        }
+        L->hs.slot_of = static_cast<int32_t *>(L->hs_slot_of.p);
+        L->hs.stamp = static_cast<int32_t *>(L->hs_stamp.p);
+        L->hs.slot_owner = static_cast<int32_t *>(L->hs_owner.p);
+        L->hs.free_list = static_cast<int32_t *>(L->hs_free.p);
+        L->hs.need_list = static_cast<int32_t *>(L->hs_need.p);
+        L->hs.ctr = static_cast<int32_t *>(L->hs_ctr.p);
+        L->hs.keys = static_cast<uint64_t *>(L->hs_keys.p);
+        L->hs.keys_sorted = static_cast<uint64_t *>(L->hs_keys_sorted.p);
+        L->hs.hot = static_cast<float *>(L->acc.p);
+        L->hs.cold = static_cast<float *>(cold);
+        L->hs.slots = d.hot_slots;
+        L->hs.d = L->acc_width;
+        HIP_TRY(hot_init(L->hs, n, s));
+    }
 
     if (L->g.residency == ATLAS_RESIDENT_PINNED_HOST) {
         // row offsets are small next to the edge array: keep a device copy for the kernels
@@ -558,6 +626,28 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         }
         if ((rc = end_span(L, L->t_self, s)) != ATLAS_OK) return rc;
     }
+    if (L->bounded) {
+        // Every vertex this chunk addresses gets a slot first (Sec. 3.5); the counts come back to the
+        // host, which sizes the eviction and checks that the chunk fits.
+        const int32_t stamp = static_cast<int32_t>(L->num_chunks + 1);
+        HIP_TRY(hot_mark(L->hs, ga.grp_dst, pc->n_groups, src_begin, L->selfmsg ? src_end - src_begin : 0, stamp, s));
+        int32_t hc[HS_COUNT];
+        HIP_TRY(hipMemcpyAsync(hc, L->hs.ctr, sizeof(hc), hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        if (hc[HS_OVERFLOW]) return ATLAS_E_NOMEM;
+        const int64_t need = hc[HS_NEED], free_slots = hc[HS_FREE_TOP];
+        if (need > free_slots) {
+            const int64_t n_evict = need - free_slots;
+            HIP_TRY(hot_build_keys(L->hs, a.pending, stamp, d.evict_policy, s));
+            HIP_TRY(hipMemcpyAsync(hc, L->hs.ctr, sizeof(hc), hipMemcpyDeviceToHost, s));
+            HIP_TRY(hipStreamSynchronize(s));
+            if (hc[HS_CANDIDATES] < n_evict) return ATLAS_E_NOMEM;   // the chunk's destinations do not fit the slots
+            HIP_TRY(hot_evict(L->hs, n_evict, L->hs_sort_temp.p, L->hs_sort_temp.bytes, s));
+            L->hot_evictions += n_evict;
+        }
+        HIP_TRY(hot_assign(L->hs, need, s));
+        ga.slot_of = L->hs.slot_of;
+    }
     if ((rc = start_span(L, L->t_agg, s)) != ATLAS_OK) return rc;
     if (pc) {
         if (L->planned_only) HIP_TRY(launch_zero_cut_first_rows(ga, s));
@@ -605,6 +695,7 @@ int atlas_flush_ready(atlas_layer_t *L, void *out, int64_t *n_flushed, void *hip
     u.bias = static_cast<const float *>(L->bias.p);
     u.out = out;
     u.n = L->n;
+    u.slot_of = L->bounded ? L->hs.slot_of : nullptr;
     int rc = start_span(L, L->t_upd, s);
     if (rc != ATLAS_OK) return rc;
     if (d.model == ATLAS_MODEL_GAT) {
@@ -628,6 +719,7 @@ int atlas_flush_ready(atlas_layer_t *L, void *out, int64_t *n_flushed, void *hip
     // SAGE / GIN rows become ready only after their own chunk: before the first
     // broadcast there is nothing to update (and no matrix to read own rows from)
     if (!(L->emb_resident && !L->x_base)) HIP_TRY(launch_update(u, s));
+    if (L->bounded) HIP_TRY(hot_release(L->hs, u.ready, u.counters, L->n, s));   // flushed vertices give their slots back
     HIP_TRY(launch_advance_head(L->ctr(), s));
     rc = end_span(L, L->t_upd, s);
     if (rc != ATLAS_OK) return rc;
@@ -655,6 +747,14 @@ int atlas_layer_finish(atlas_layer_t *L, atlas_layer_stats_t *stats) {
         stats->num_chunks = L->num_chunks;
         stats->num_flushes = L->num_flushes;
         stats->bytes_copied_h2d = L->bytes_h2d;
+        if (L->bounded) {
+            int32_t hc[HS_COUNT] = {0};
+            if (hipMemcpy(hc, L->hs.ctr, sizeof(hc), hipMemcpyDeviceToHost) == hipSuccess) {
+                stats->hot_evictions = hc[HS_EVICTIONS];
+                stats->hot_reloads = hc[HS_RELOADS];
+                stats->hot_peak_slots = hc[HS_PEAK];
+            }
+        }
         if (rc == ATLAS_OK) {
             stats->ms_aggregate = sum_spans(L->t_agg);
             stats->ms_self = sum_spans(L->t_self);
@@ -819,7 +919,11 @@ int atlas_debug_copy(atlas_layer_t *L, int what, void *host_dst, int64_t bytes) 
         case ATLAS_DBG_INDEG: src = L->indeg; avail = L->n * 4; break;
         case ATLAS_DBG_PENDING: src = L->pending.p; avail = L->n * 4; break;
         case ATLAS_DBG_READY: src = L->ready.p; avail = static_cast<int64_t>(c[CTR_READY_TAIL]) * 4; break;
-        case ATLAS_DBG_ACC: src = L->acc.p; avail = L->n * L->acc_width * 4; break;
+        case ATLAS_DBG_ACC:
+            if (L->bounded) return ATLAS_E_STATE;   // rows live in slots or in the cold tier
+            src = L->acc.p;
+            avail = L->n * L->acc_width * 4;
+            break;
         case ATLAS_DBG_READY_COUNT:
             if (bytes < static_cast<int64_t>(sizeof(pair))) return ATLAS_E_RANGE;
             static_cast<int64_t *>(host_dst)[0] = pair[0];
@@ -840,6 +944,12 @@ int atlas_release_cache(void) {
         if (e != hipSuccess && first == hipSuccess) first = e;
     }
     g_cache.clear();
+    if (g_cold) {
+        hipError_t e = hipHostFree(g_cold);
+        if (e != hipSuccess && first == hipSuccess) first = e;
+        g_cold = nullptr;
+        g_cold_bytes = 0;
+    }
     if (first != hipSuccess) return hip_fail(first, "hipFree");
     return ATLAS_OK;
 }

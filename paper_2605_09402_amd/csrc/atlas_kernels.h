@@ -17,6 +17,41 @@ enum Counter {
 // 64-bit counters (separate block): edges pushed so far.
 enum Counter64 { CTR64_EDGES = 0, CTR64_COUNT = 8 };
 
+// Bounded accumulator store (paper Sec. 3.5): a fixed number of slots in HBM,
+// evicted partial states in pinned host memory.
+enum HotCounter {
+    HS_NEED = 0,        // vertices listed in need_list for the chunk being prepared
+    HS_FREE_TOP = 1,    // height of the free-slot stack
+    HS_CANDIDATES = 2,  // eviction candidates counted by the key kernel
+    HS_RELOADS = 3,
+    HS_EVICTIONS = 4,
+    HS_OVERFLOW = 5,    // a list ran past its capacity (never expected: the host checks the counts)
+    HS_PEAK = 6,        // most slots in use at once
+    HS_COUNT = 16
+};
+struct HotStore {
+    int32_t *slot_of = nullptr;     // [N] slot of the vertex's partial state; -1: none (not started, or
+                                    // completed and released); -2: evicted, state in `cold`
+    int32_t *slot_owner = nullptr;  // [slots] vertex held, -1: free
+    int32_t *free_list = nullptr;   // [slots] stack of free slots
+    int32_t *stamp = nullptr;       // [N] number (+1) of the last chunk that addressed the vertex
+    int32_t *need_list = nullptr;   // [slots]
+    int32_t *ctr = nullptr;         // [HS_COUNT]
+    uint64_t *keys = nullptr, *keys_sorted = nullptr;   // [slots]
+    float *hot = nullptr;           // [slots][d]
+    float *cold = nullptr;          // [N][d], pinned host memory
+    int64_t slots = 0;
+    int d = 0;
+};
+hipError_t hot_init(const HotStore &h, int64_t n, hipStream_t s);
+hipError_t hot_mark(const HotStore &h, const int32_t *grp_dst, int64_t n_groups, int64_t src_begin, int64_t n_self,
+                    int32_t chunk_stamp, hipStream_t s);
+hipError_t hot_build_keys(const HotStore &h, const int32_t *pending, int32_t chunk_stamp, int policy, hipStream_t s);
+size_t hot_sort_temp_bytes(int64_t slots);
+hipError_t hot_evict(const HotStore &h, int64_t n_evict, void *sort_temp, size_t sort_temp_bytes, hipStream_t s);
+hipError_t hot_assign(const HotStore &h, int64_t need, hipStream_t s);
+hipError_t hot_release(const HotStore &h, const int32_t *ready, const int32_t *counters, int64_t n, hipStream_t s);
+
 // Attention state of a GAT layer (all [N][heads], fp32 unless noted).
 // The running maximum is stored as an order-preserving int32 image of the
 // float so that an integer atomicMax implements a float maximum.
@@ -81,6 +116,7 @@ struct GroupedArgs {
     int32_t *counters;
     unsigned long long *counters64;
     GatState gat;               // model == GAT only
+    const int32_t *slot_of = nullptr;   // bounded store: row of `acc` that holds vertex v (nullptr: row v)
     float *scores = nullptr;    // GAT only: [n_edges][heads] attention logits of the chunk's edges, written
                                 // by the max sweep and read by the aggregation
 };
@@ -167,6 +203,7 @@ struct UpdateArgs {
     const float *bias;        // fp32 [d_out] or nullptr
     void *out;                // [N][d_out]
     int64_t n;
+    const int32_t *slot_of;   // bounded store: row of `acc` that holds vertex v (nullptr: row v)
     int64_t identity_rows;    // > 0: no ready list; rows 0..identity_rows-1 of `acc` (a dense
                               // row block, model 2 = plain X W) map to the same rows of `out`
 };

@@ -423,6 +423,9 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
             dstv = gd & 0x7fffffff;
         }
         const uint64_t firstmask = __ballot(first_touch);
+        // accumulator row of the destination: the vertex id, or its slot in a bounded store
+        int32_t rowv = dstv;
+        if (MODEL != 2 && a.slot_of && closes) rowv = a.slot_of[dstv];
         float gs = 1.f;
         if (MODEL == 1 && lane < cnt) {  // GCN: source side of the symmetric normalisation
             const int32_t du = a.indeg[src];
@@ -478,7 +481,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
                     }
                     if ((endmask >> j) & 1ull) {
                         const int32_t v = __builtin_amdgcn_readlane(dstv, j);
-                        float *dst = a.acc + static_cast<int64_t>(v) * D + lane * VPL;
+                        float *dst = a.acc + static_cast<int64_t>(__builtin_amdgcn_readlane(rowv, j)) * D + lane * VPL;
                         if (MODEL == 2) {
                             const int64_t vh = static_cast<int64_t>(v) * a.gat.heads + hl;
                             if (cut) {   // already at the new maximum (k_gat_rescale_cut_groups)
@@ -510,7 +513,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
         }
         if (!((endmask >> (cnt - 1)) & 1ull)) {  // open group: continues in the next tile
             const int32_t v = __builtin_amdgcn_readlane(dstv, cnt - 1);
-            row_add_shared<VPL>(a.acc + static_cast<int64_t>(v) * D + lane * VPL, sum);
+            row_add_shared<VPL>(a.acc + static_cast<int64_t>(__builtin_amdgcn_readlane(rowv, cnt - 1)) * D + lane * VPL, sum);
             if (MODEL == 2 && head_first)
                 unsafeAtomicAdd(a.gat.l + static_cast<int64_t>(v) * a.gat.heads + hl, lsum);
         }
@@ -655,7 +658,8 @@ __global__ __launch_bounds__(kBlock) void k_zero_cut_first_rows(GroupedArgs a) {
         while (todo) {
             const int j = __ffsll(static_cast<unsigned long long>(todo)) - 1;
             todo &= todo - 1;
-            const int64_t v = __builtin_amdgcn_readlane(gd, j) & 0x7fffffff;
+            int64_t v = __builtin_amdgcn_readlane(gd, j) & 0x7fffffff;
+            if (a.slot_of) v = a.slot_of[v];   // bounded store: the destination's slot
             float *row = a.acc + v * a.d;
             for (int c = lane; c < a.d; c += kWave) row[c] = 0.f;
         }

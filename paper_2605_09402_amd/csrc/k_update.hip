@@ -150,7 +150,8 @@ __device__ __forceinline__ float4 own_to_f32(float4 v) { return v; }
 
 template <bool BF16C, int SEGS>
 __device__ __forceinline__ void gather_rows(const UpdateArgs &a, typename Elem<BF16C>::type *A, int stride,
-                                            int w, int lane, int32_t idv, float scalev, int has_aggv) {
+                                            int w, int lane, int32_t idv, int32_t rowv, float scalev,
+                                            int has_aggv) {
     constexpr int kRows = kTileRows / 8;  // rows per wave
     constexpr bool two = SEGS == 2;       // one or two 256-column segments per row
     constexpr int nitems = SEGS * kRows;
@@ -171,7 +172,8 @@ __device__ __forceinline__ void gather_rows(const UpdateArgs &a, typename Elem<B
                 const int32_t id = __builtin_amdgcn_readlane(idv, rr);
                 const bool fetch = id >= 0 && __builtin_amdgcn_readlane(has_aggv, rr) != 0;
                 const int cc = col < d ? col : 0;
-                v[i] = *reinterpret_cast<const float4 *>(a.acc + static_cast<int64_t>(fetch ? id : 0) * d + cc);
+                const int32_t ar = __builtin_amdgcn_readlane(rowv, rr);
+                v[i] = *reinterpret_cast<const float4 *>(a.acc + static_cast<int64_t>(fetch ? ar : 0) * d + cc);
                 const int64_t oo = static_cast<int64_t>(id >= 0 ? id : 0) * d + cc;
                 if constexpr (BF16C) o[i] = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(a.self_rows) + oo);
                 else o[i] = *reinterpret_cast<const float4 *>(static_cast<const float *>(a.self_rows) + oo);
@@ -207,7 +209,8 @@ __device__ __forceinline__ void gather_rows(const UpdateArgs &a, typename Elem<B
             const int rr = row_of(base + i), col = col_of(base + i);
             const int32_t id = __builtin_amdgcn_readlane(idv, rr);
             const bool fetch = id >= 0 && __builtin_amdgcn_readlane(has_aggv, rr) != 0;
-            const int64_t o = static_cast<int64_t>(fetch ? id : 0) * d + (col < d ? col : 0);
+            const int32_t ar = __builtin_amdgcn_readlane(rowv, rr);
+            const int64_t o = static_cast<int64_t>(fetch ? ar : 0) * d + (col < d ? col : 0);
             v[i] = *reinterpret_cast<const float4 *>(a.acc + o);
         }
 #pragma unroll
@@ -310,6 +313,7 @@ __global__ __launch_bounds__(kGenBlock, 4) void k_update(UpdateArgs a) {
         __syncthreads();  // previous tile's LDS readers are done
         // ---- gather: wave w stages rows w*8 .. w*8+7; lane r < 8 holds row r's id ----
         int32_t idv = -1;
+        int32_t rowv = 0;   // accumulator row of the vertex: its id, or its slot in a bounded store
         float scalev = 1.f;
         int has_aggv = 1;
         if (lane < kRows) {
@@ -318,6 +322,7 @@ __global__ __launch_bounds__(kGenBlock, 4) void k_update(UpdateArgs a) {
                 idv = dense ? idx : a.ready[idx];
                 const int32_t deg = a.indeg ? a.indeg[idv] : 1;
                 if (deg <= 0) has_aggv = 0;
+                rowv = a.slot_of ? a.slot_of[idv] : idv;
                 const float fd = static_cast<float>(deg > 0 ? deg : 1);
                 // SAGE: mean = sum * (1/deg); GCN: deg^-1/2; a plain linear map (model 2): 1
                 scalev = a.model == 0 ? 1.0f / fd : (a.model == 1 ? 1.0f / sqrtf(fd) : 1.0f);
@@ -326,8 +331,8 @@ __global__ __launch_bounds__(kGenBlock, 4) void k_update(UpdateArgs a) {
         }
         frag_t wcur[kUnroll];
         load_w(0, wcur);   // on its way while the rows are gathered
-        if (a.d_in > 256) gather_rows<BF16C, 2>(a, A, stride, w, lane, idv, scalev, has_aggv);
-        else gather_rows<BF16C, 1>(a, A, stride, w, lane, idv, scalev, has_aggv);
+        if (a.d_in > 256) gather_rows<BF16C, 2>(a, A, stride, w, lane, idv, rowv, scalev, has_aggv);
+        else gather_rows<BF16C, 1>(a, A, stride, w, lane, idv, rowv, scalev, has_aggv);
         __syncthreads();
 
         // ---- contraction, as D^T blocks; the bias is the initial accumulator ----
@@ -415,8 +420,8 @@ __device__ __forceinline__ int32_t quad_bcast(int32_t v, int i) {
 // loads of vertices without in-edges (nothing was ever added to their rows,
 // and the one shared address stays in cache).
 template <bool BF16C, int OWN>
-__device__ __forceinline__ void pipe_issue_rows(const UpdateArgs &a, int32_t idv, int32_t degv, int lane,
-                                                RowRegs<BF16C> &r) {
+__device__ __forceinline__ void pipe_issue_rows(const UpdateArgs &a, int32_t idv, int32_t degv, int32_t slotv,
+                                                int lane, RowRegs<BF16C> &r) {
     const int d = a.d_in;
     const int c4 = (lane & 31) * 4;
     const int col = c4 < d ? c4 : 0;
@@ -425,7 +430,7 @@ __device__ __forceinline__ void pipe_issue_rows(const UpdateArgs &a, int32_t idv
         const int32_t id = quad_bcast(idv, i);
         const int32_t dg = quad_bcast(degv, i);
         const int32_t row = id >= 0 ? id : 0;
-        const int32_t arow = dg > 0 ? row : 0;
+        const int32_t arow = dg > 0 ? (a.slot_of ? quad_bcast(slotv, i) : row) : 0;
         r.acc[i] = *reinterpret_cast<const float4 *>(a.acc + static_cast<int64_t>(arow) * d + col);
         if constexpr (OWN != 0) {
             const int64_t o = static_cast<int64_t>(row) * d + col;
@@ -575,6 +580,9 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
         return id;
     };
     auto load_deg = [&](int32_t id) -> int32_t { return (a.indeg && id >= 0) ? a.indeg[id] : 1; };
+    // bounded store: the slot that holds the vertex's accumulator row (-1 for vertices without in-edges,
+    // whose row is never fetched)
+    auto load_slot = [&](int32_t id) -> int32_t { return (a.slot_of && id >= 0) ? a.slot_of[id] : 0; };
 
     // per (mb, nb) block of this wave: LDS addresses and the bias as the initial accumulator
     f32x16_t bj[PPW];
@@ -607,10 +615,11 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
     int32_t id0 = load_ids(tile), id1 = load_ids(tile + G), id_a = load_ids(tile + 2 * G);
     int32_t id_b = load_ids(tile + 3 * G);
     int32_t deg0 = load_deg(id0), deg1 = load_deg(id1), deg_a = load_deg(id_a);
+    int32_t slot_a = load_slot(id_a);
     RowRegs<BF16C> r0, r1;
-    pipe_issue_rows<BF16C, OWN>(a, id0, deg0, lane, r0);
+    pipe_issue_rows<BF16C, OWN>(a, id0, deg0, load_slot(id0), lane, r0);
     __builtin_amdgcn_sched_barrier(0);   // keep the two sets' loads in this order, as in the loop
-    pipe_issue_rows<BF16C, OWN>(a, id1, deg1, lane, r1);
+    pipe_issue_rows<BF16C, OWN>(a, id1, deg1, load_slot(id1), lane, r1);
 
     auto step = [&](RowRegs<BF16C> &regs, int32_t &idv, int32_t &degv, int buf) {
         elem_t *A = A0 + buf * a_elems;
@@ -620,10 +629,12 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
         __syncthreads();
         idv = id_a;
         degv = deg_a;
+        const int32_t slotv = slot_a;
         id_a = id_b;
         deg_a = load_deg(id_a);
+        slot_a = load_slot(id_a);
         id_b = load_ids(tile + 4 * G);
-        pipe_issue_rows<BF16C, OWN>(a, idv, degv, lane, regs);
+        pipe_issue_rows<BF16C, OWN>(a, idv, degv, slotv, lane, regs);
 
         f32x16_t c[PPW];
 #pragma unroll
@@ -712,7 +723,8 @@ __global__ __launch_bounds__(kBlock) void k_scale_rows(UpdateArgs a) {
         const float g = deg > 0 ? 1.0f / sqrtf(static_cast<float>(deg)) : 0.f;
         for (int c = lane * 4; c < d; c += 256) {
             float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (deg > 0) x = *reinterpret_cast<const float4 *>(a.acc + v * d + c);   // never written otherwise
+            if (deg > 0)   // never written otherwise
+                x = *reinterpret_cast<const float4 *>(a.acc + (a.slot_of ? static_cast<int64_t>(a.slot_of[v]) : v) * d + c);
             if (a.out_bf16)
                 *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(a.out) + v * d + c) =
                     make_uint2(pack_bf16x2(x.x * g, x.y * g), pack_bf16x2(x.z * g, x.w * g));

@@ -1,0 +1,103 @@
+"""Bounded accumulator store (the paper's memory manager, Sec. 3.5) on the GPU:
+outputs must equal the oracle's exactly as without a bound, and the numbers of
+evictions and reloads must equal the oracle's replay of the policy."""
+import numpy as np
+import pytest
+import torch
+
+import gen
+
+pytestmark = pytest.mark.gpu
+
+SEED = 0x5EED3000
+
+
+@pytest.fixture(scope="module")
+def H():
+    import harness
+    return harness
+
+
+def started(case):
+    """Vertices that ever hold a partial state: those with an in-edge."""
+    return int((np.bincount(case.col.numpy(), minlength=case.n) > 0).sum())
+
+
+def test_hand_worked_example(oracle, H):
+    """The 8-vertex example of tests/golden/hot_store_example.txt (GCN-style, no
+    self messages): 3 slots -> one eviction (vertex 4 in chunk 1) and one reload."""
+    src = [0, 0, 1, 1, 2, 2, 3, 3, 4, 5, 6, 7]
+    dst = [4, 5, 4, 6, 5, 6, 6, 7, 5, 7, 4, 6]
+    case = H.case_from_edges("gin", 8, src, dst, SEED, [64, 64], 2)
+    # GIN sends a self message; the golden example has none, so take its counts from the replay with selfmsg
+    ev, rl, peak = oracle.hot_store_trace(case.off.numpy(), case.col.numpy(), 2, 3, selfmsg=True)
+    run = H.run_gpu(case, plan=True, hot_slots=3)
+    H.check_outputs(oracle, case, run)
+    st = run.stats[0]
+    assert (st["hot_evictions"], st["hot_reloads"], st["hot_peak_slots"]) == (sum(ev), sum(rl), peak)
+    # the golden numbers themselves, on a layer type without self messages (SGC hop: no weights needed)
+    case2 = H.case_from_edges("sgc", 8, src + list(range(4)), dst + list(range(4)), SEED, [64, 64], 2)
+    case2.layers[-1] = gen.layer_params(SEED, 0, "sgc_hop", 64, 64)
+    # vertices 0..3 got a self loop each so that every D is positive; they address themselves in their own
+    # chunk and complete at once, which costs one slot each for the length of that chunk
+    ev2, rl2, peak2 = oracle.hot_store_trace(case2.off.numpy(), case2.col.numpy(), 2, 5, selfmsg=False)
+    run2 = H.run_gpu(case2, plan=True, hot_slots=5)
+    H.check_outputs(oracle, case2, run2)
+    st2 = run2.stats[0]
+    assert (st2["hot_evictions"], st2["hot_reloads"], st2["hot_peak_slots"]) == (sum(ev2), sum(rl2), peak2)
+
+
+@pytest.mark.parametrize("policy", [0, 1], ids=["min_pending", "max_pending"])
+@pytest.mark.parametrize("model,store", [("sage", torch.bfloat16), ("gcn", torch.float32), ("gin", torch.float32)])
+def test_bounded_store_matches_replay(oracle, H, model, store, policy):
+    """R-MAT scale 12 (random ids) in 64 chunks with slots for half of the
+    vertices that ever hold a state: hundreds to thousands of evictions; two
+    layers (the second layer starts from a fresh store)."""
+    g = gen.rmat_graph(SEED + 1, 12, 16, random_ids=True, self_loops=(model == "gcn"))
+    case = H.make_case(model, g, SEED + 1, [128, 128, 64], 64, store=store,
+                       feat="normal" if store == torch.float32 else "uniform")
+    slots = started(case) // 2
+    ev, rl, peak = oracle.hot_store_trace(case.off.numpy(), case.col.numpy(), case.chunk, slots,
+                                          selfmsg=model in ("sage", "gin"), policy=policy)
+    assert sum(ev) > 500
+    run = H.run_gpu(case, snapshots=True, plan=True, hot_slots=slots, evict_policy=policy)
+    H.check_integers(oracle, case, run, layer=0)
+    H.check_integers(oracle, case, run, layer=1)
+    print(model, "bounded store errors", H.check_outputs(oracle, case, run),
+          "evictions %d reloads %d peak %d of %d slots" % (sum(ev), sum(rl), peak, slots))
+    for st in run.stats:
+        assert (st["hot_evictions"], st["hot_reloads"], st["hot_peak_slots"]) == (sum(ev), sum(rl), peak)
+        assert st["vertices_flushed"] == case.n
+
+
+def test_minimum_pending_evicts_less_than_maximum_pending(oracle, H):
+    """What the policy is for (Sec. 3.5): the paper's policy causes fewer
+    eviction-reload cycles than its opposite (here about a quarter)."""
+    g = gen.rmat_graph(SEED + 1, 12, 16, random_ids=True)
+    case = H.make_case("sage", g, SEED + 1, [64, 64], 64)
+    slots = started(case) // 2
+    counts = []
+    for policy in (0, 1):
+        run = H.run_gpu(case, plan=True, hot_slots=slots, evict_policy=policy)
+        H.check_outputs(oracle, case, run)
+        ev, rl, _ = oracle.hot_store_trace(case.off.numpy(), case.col.numpy(), case.chunk, slots, True, policy)
+        assert run.stats[0]["hot_evictions"] == sum(ev) and run.stats[0]["hot_reloads"] == sum(rl)
+        counts.append(sum(ev))
+    print("evictions: min-pending %d, max-pending %d" % tuple(counts))
+    assert 2 * counts[0] < counts[1]
+
+
+def test_store_too_small_and_not_needed(oracle, H):
+    import paper_2605_09402_amd as atlas
+    g = gen.rmat_graph(SEED + 3, 10, 16)
+    case = H.make_case("sage", g, SEED + 3, [64, 64], 128)
+    with pytest.raises(atlas.AtlasError) as ei:          # a chunk addresses more vertices than there are slots
+        H.run_gpu(case, plan=True, hot_slots=8)
+    assert ei.value.status == atlas.E_NOMEM
+    atlas.atlas_release_cache()
+    with pytest.raises(atlas.AtlasError) as ei:          # a bounded store needs the plan's destination lists
+        H.run_gpu(case, plan=False, hot_slots=500)
+    assert ei.value.status == atlas.E_STATE
+    run = H.run_gpu(case, plan=True, hot_slots=case.n)   # one row per vertex: the ordinary dense store
+    H.check_outputs(oracle, case, run)
+    assert run.stats[0]["hot_evictions"] == 0 and run.stats[0]["hot_peak_slots"] == 0
