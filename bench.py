@@ -40,6 +40,11 @@ def main() -> int:
                          "parity workloads, timed for the record")
     ap.add_argument("--layer-type", choices=["sage", "gin"], default="sage",
                     help="config5 only: run the same graph and widths through GIN layers instead of SAGE-mean")
+    ap.add_argument("--hot-slots-frac", type=float, default=0.0,
+                    help="bounded accumulator store: slots = this fraction of the vertices with an in-edge "
+                         "(0: one accumulator row per vertex); needs chunks small enough to fit")
+    ap.add_argument("--evict-policy", choices=["min", "max"], default="min",
+                    help="bounded store: evict fewest (the paper's policy) or most pending messages first")
     ap.add_argument("--scale", type=int, default=None, help="R-MAT scale (default: the workload's own)")
     ap.add_argument("--edge-factor", type=int, default=32)
     ap.add_argument("--no-plan", action="store_true", help="push straight from the CSR (atomic path)")
@@ -145,12 +150,18 @@ def main() -> int:
     attn = [(None if p.attn_src is None else p.attn_src.to(wl.store).to(dev).contiguous(),
              None if p.attn_dst is None else p.attn_dst.to(wl.store).to(dev).contiguous()) for p in wl.layers]
 
+    hot_slots = 0
+    if args.hot_slots_frac > 0:
+        hot_slots = max(1, int(args.hot_slots_frac * int((indeg > 0).sum().item())))
+        log("bounded store: %d slots (%.0f%% of the vertices with an in-edge)" % (hot_slots, 100 * args.hot_slots_frac))
+
     def run_layer(li: int, x: torch.Tensor, timing: bool) -> dict:
         d_in, d_out = wl.dims[li], wl.dims[li + 1]
         act = atlas.ACT_NONE if li + 1 == len(wl.layers) else between
         dims = atlas.make_dims(model_id, d_in, d_out, sdt, sdt, act, chunk, heads=wl.heads,
                                flags=(atlas.FLAG_TIMING if timing else 0) | atlas.FLAG_EMB_RESIDENT |
-                               (atlas.FLAG_PLANNED_ONLY if plan is not None else 0))
+                               (atlas.FLAG_PLANNED_ONLY if plan is not None else 0),
+                               hot_slots=hot_slots, evict_policy=1 if args.evict_policy == "max" else 0)
         W, b = params[li]
         h = atlas.atlas_layer_init(graph, dims, atlas.make_weights(W, b, sdt, attn[li][0], attn[li][1]), stream)
         out = outs[li]
@@ -311,6 +322,9 @@ def main() -> int:
                    % (h2d_bytes / 1e9, copy_ms / args.steps),
                    "edge_order": "per-chunk destination-grouped plan" if plan else "CSR stream (atomics)",
                    "plan_build_ms": None if plan_ms is None else round(plan_ms, 1)},
+        "hot_store": None if not hot_slots else {
+            "slots": hot_slots, "policy": args.evict_policy + "-pending", "evictions_per_layer": st["hot_evictions"],
+            "reloads_per_layer": st["hot_reloads"], "peak_slots": st["hot_peak_slots"]},
         "layer_ms": {"aggregate": round(agg_ms / args.steps, 3), "update": round(upd_ms / args.steps, 3),
                      "self": round(self_ms / args.steps, 3), "init": round(init_ms / args.steps, 3)},
         "end_to_end_ms": None if e2e_ms is None else round(e2e_ms, 2),
