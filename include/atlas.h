@@ -71,7 +71,7 @@ enum atlas_flags {
                                     stays valid until atlas_layer_finish; the library then reads
                                     a vertex's own row from that matrix instead of keeping a
                                     copy (E_STATE if two chunks disagree about the matrix base) */
-    ATLAS_FLAG_PLANNED_ONLY = 4  /* SAGE_MEAN / GCN_SYM on a graph with a plan: the caller promises
+    ATLAS_FLAG_PLANNED_ONLY = 4, /* SAGE_MEAN / GCN_SYM on a graph with a plan: the caller promises
                                     that every chunk coincides with a planned chunk
                                     (atlas_broadcast_chunk returns E_RANGE otherwise).  The layer
                                     then skips the zero fill of the accumulators: a row is first
@@ -79,6 +79,13 @@ enum atlas_flags {
                                     of a vertex without in-edges is never read.  Ignored without
                                     a plan and for GAT.  With it, ATLAS_DBG_ACC rows of vertices
                                     that have received nothing yet are undefined. */
+    ATLAS_FLAG_TRANSFORM_FIRST = 8 /* SAGE_MEAN / GCN_SYM / GIN on a DEVICE graph: the weight matrix is
+                                    applied to each chunk's rows before they are pushed (the linear map
+                                    commutes with the neighbour sum), so messages and accumulators are
+                                    d_out wide instead of d_in.  Pays when d_out is well below d_in (wide
+                                    input features); d_in may then be up to 1024 (fp32 embeddings: 512)
+                                    and d_out must be a multiple of 64.  Results equal the default order
+                                    up to fp32 rounding.  Ignored for other models and residencies. */
 };
 
 /* The graph: CSR by SOURCE vertex (paper Sec. 3.2: out-edges, read sequentially

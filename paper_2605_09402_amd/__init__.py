@@ -23,6 +23,7 @@ ACT_NONE, ACT_RELU, ACT_ELU = 0, 1, 2
 FLAG_TIMING = 1
 FLAG_EMB_RESIDENT = 2
 FLAG_PLANNED_ONLY = 4
+FLAG_TRANSFORM_FIRST = 8
 EVICT_MIN_PENDING, EVICT_MAX_PENDING = 0, 1
 DBG_INDEG, DBG_PENDING, DBG_READY, DBG_READY_COUNT, DBG_ACC = range(5)
 

@@ -150,6 +150,12 @@ struct atlas_layer {
     Buf hs_slot_of, hs_owner, hs_free, hs_stamp, hs_need, hs_ctr, hs_keys, hs_keys_sorted, hs_sort_temp;
     int64_t hot_evictions = 0, hot_reloads = 0;
 
+    // transform-first layers
+    bool tf = false;
+    Buf tf_z;       // [chunk][d_out] fp32: the chunk's rows times W (SAGE: W_neigh)
+    Buf tf_self;    // [N][d_out] fp32: SAGE x_v W_self, GIN x_v W
+    Buf packed_w2;  // SAGE: W_self in fragment order
+
     bool planned_only = false;         // every chunk runs from the plan: no accumulator zero fill
     bool emb_resident = false;         // own rows are read from the caller's matrix
     const char *x_base = nullptr;      // base of that matrix (set by the first chunk)
@@ -174,7 +180,8 @@ struct atlas_layer {
         for (Buf *b : {&indeg_own, &pending, &ready, &counters, &counters64, &acc, &self_rows, &packed_w, &bias,
                        &dev_off, &stage_col[0], &stage_col[1], &stage_emb[0], &stage_emb[1], &gat_el, &gat_er,
                        &gat_mcur, &gat_mnext, &gat_l, &gat_wa, &gat_z, &gat_scores, &hs_slot_of, &hs_owner, &hs_free,
-                       &hs_stamp, &hs_need, &hs_ctr, &hs_keys, &hs_keys_sorted, &hs_sort_temp})
+                       &hs_stamp, &hs_need, &hs_ctr, &hs_keys, &hs_keys_sorted, &hs_sort_temp, &tf_z, &tf_self,
+                       &packed_w2})
             b->release();
         for (auto *v : {&t_agg, &t_self, &t_upd, &t_copy, &t_init})
             for (auto &sp : *v) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
@@ -186,6 +193,14 @@ struct atlas_layer {
 };
 
 namespace {
+
+// Transform first (ATLAS_FLAG_TRANSFORM_FIRST): the linear map commutes with the
+// sum, so each chunk's rows are multiplied by W before they are pushed and the
+// accumulators are d_out wide.
+bool transform_first(const atlas_dims_t &d, int residency) {
+    return (d.flags & ATLAS_FLAG_TRANSFORM_FIRST) && residency == ATLAS_RESIDENT_DEVICE &&
+           (d.model == ATLAS_MODEL_SAGE_MEAN || d.model == ATLAS_MODEL_GCN_SYM || d.model == ATLAS_MODEL_GIN);
+}
 
 // layers whose update uses the vertex's own embedding: it travels as a self message
 bool has_self_term(int model) { return model == ATLAS_MODEL_SAGE_MEAN || model == ATLAS_MODEL_GIN; }
@@ -211,7 +226,9 @@ int check_dims(const atlas_dims_t &d, const atlas_weights_t &w, int residency) {
         if ((d.d_out / d.heads) % (d.d_out / 64) != 0) return ATLAS_E_BAD_DIMS;
         if (!w.attn_src || !w.attn_dst) return ATLAS_E_NULL;
     }
-    if (d.d_in <= 0 || d.d_in % 64 != 0 || d.d_in > 512) return ATLAS_E_BAD_DIMS;
+    const bool tf = transform_first(d, residency);
+    if (d.d_in <= 0 || d.d_in % 64 != 0 || d.d_in > (tf ? 1024 : 512)) return ATLAS_E_BAD_DIMS;
+    if (tf && d.d_out % 64 != 0) return ATLAS_E_BAD_DIMS;   // a wave holds one d_out-wide product row
     if (d.d_out <= 0 || d.d_out % 16 != 0 || (d.d_out > 256 && d.model != ATLAS_MODEL_SGC_HOP))
         return ATLAS_E_BAD_DIMS;
     for (int dt : {d.in_dtype, d.out_dtype, w.dtype})
@@ -221,7 +238,7 @@ int check_dims(const atlas_dims_t &d, const atlas_weights_t &w, int residency) {
     if (d.hot_slots < 0 || d.evict_policy < ATLAS_EVICT_MIN_PENDING || d.evict_policy > ATLAS_EVICT_MAX_PENDING)
         return ATLAS_E_BAD_DIMS;
     if (d.hot_slots > 0 && (d.model == ATLAS_MODEL_GAT || residency != ATLAS_RESIDENT_DEVICE)) return ATLAS_E_BAD_DIMS;
-    const int K = d.model == ATLAS_MODEL_SAGE_MEAN ? 2 * d.d_in : d.d_in;
+    const int K = d.model == ATLAS_MODEL_SAGE_MEAN && !tf ? 2 * d.d_in : d.d_in;
     const bool bf16c = d.in_dtype == ATLAS_DTYPE_BF16;
     const size_t lds = 256 + static_cast<size_t>(64) * (K + (bf16c ? 8 : 1)) * (bf16c ? 2 : 4);
     if (lds > 160 * 1024) return ATLAS_E_BAD_DIMS;
@@ -268,9 +285,16 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
     }
     const size_t acc_rows = L->bounded ? static_cast<size_t>(d.hot_slots) : n1;
     HIP_TRY(L->acc.alloc(acc_rows * L->acc_width * sizeof(float)));
-    L->emb_resident = has_self_term(d.model) && (d.flags & ATLAS_FLAG_EMB_RESIDENT) &&
+    L->emb_resident = has_self_term(d.model) && (d.flags & ATLAS_FLAG_EMB_RESIDENT) && !L->tf &&
                       L->g.residency == ATLAS_RESIDENT_DEVICE;
-    if (has_self_term(d.model) && !L->emb_resident)
+    if (L->tf) {
+        const size_t rows = static_cast<size_t>(std::min<int64_t>(d.max_chunk_sources, std::max<int64_t>(n, 1)));
+        if (d.model != ATLAS_MODEL_GIN) HIP_TRY(L->tf_z.alloc(rows * d.d_out * sizeof(float)));
+        if (has_self_term(d.model)) HIP_TRY(L->tf_self.alloc(n1 * d.d_out * sizeof(float)));
+        if (d.model == ATLAS_MODEL_SAGE_MEAN)
+            HIP_TRY(L->packed_w2.alloc(packed_weight_bytes(L->K, d.d_out, L->compute_bf16)));
+    }
+    if (has_self_term(d.model) && !L->emb_resident && !L->tf)
         HIP_TRY(L->self_rows.alloc(n1 * d.d_in * dtype_size(d.in_dtype)));
     HIP_TRY(L->packed_w.alloc(packed_weight_bytes(L->K, d.d_out, L->compute_bf16)));
     HIP_TRY(launch_fill_zero(L->counters.p, L->counters.bytes, s));
@@ -375,7 +399,15 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
     }
     HIP_TRY(launch_init_pending(L->indeg, L->selfmsg, n, static_cast<int32_t *>(L->pending.p),
                                 static_cast<int32_t *>(L->ready.p), L->ctr(), s));
-    if (d.model != ATLAS_MODEL_SGC_HOP)
+    if (L->tf && d.model == ATLAS_MODEL_SAGE_MEAN) {
+        // rows 0..d_in-1 of W multiply the own embedding, rows d_in.. the neighbour mean
+        const char *w_neigh = static_cast<const char *>(w->W) +
+                              static_cast<size_t>(d.d_in) * d.d_out * dtype_size(w->dtype);
+        HIP_TRY(launch_pack_weights(w_neigh, w->dtype == ATLAS_DTYPE_BF16, L->K, d.d_out, L->compute_bf16,
+                                    L->packed_w.p, s));
+        HIP_TRY(launch_pack_weights(w->W, w->dtype == ATLAS_DTYPE_BF16, L->K, d.d_out, L->compute_bf16,
+                                    L->packed_w2.p, s));
+    } else if (d.model != ATLAS_MODEL_SGC_HOP)
         HIP_TRY(launch_pack_weights(w->W, w->dtype == ATLAS_DTYPE_BF16, L->K, d.d_out, L->compute_bf16,
                                     L->packed_w.p, s));
     if (w->bias && d.model != ATLAS_MODEL_SGC_HOP) {
@@ -407,9 +439,10 @@ int atlas_layer_init(const atlas_graph_t *graph, const atlas_dims_t *dims, const
     L->n = graph->num_vertices;
     L->e = graph->num_edges;
     L->selfmsg = has_self_term(dims->model) ? 1 : 0;
-    L->K = dims->model == ATLAS_MODEL_SAGE_MEAN ? 2 * dims->d_in : dims->d_in;
+    L->tf = transform_first(*dims, graph->residency);
+    L->K = dims->model == ATLAS_MODEL_SAGE_MEAN && !L->tf ? 2 * dims->d_in : dims->d_in;
     L->compute_bf16 = dims->in_dtype == ATLAS_DTYPE_BF16;
-    L->acc_width = dims->model == ATLAS_MODEL_GAT ? dims->d_out : dims->d_in;
+    L->acc_width = dims->model == ATLAS_MODEL_GAT || L->tf ? dims->d_out : dims->d_in;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     L->last_stream = s;
     rc = start_span(L, L->t_init, s);
@@ -490,7 +523,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         if (L->x_base && base != L->x_base) return ATLAS_E_STATE;
         L->x_base = base;
     }
-    char *self_dst = has_self_term(d.model) && !L->emb_resident
+    char *self_dst = has_self_term(d.model) && !L->emb_resident && !L->tf
                          ? static_cast<char *>(L->self_rows.p) + static_cast<size_t>(src_begin) * row_bytes
                          : nullptr;
     // a chunk that coincides with a planned chunk runs from its destination-ordered edges
@@ -566,6 +599,35 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
             HIP_TRY(hipMemcpyAsync(self_dst, emb, emb_bytes, hipMemcpyDeviceToDevice, s));
         HIP_TRY(launch_self_message(src_begin, src_end, a.pending, a.ready, a.counters, s));
         if ((rc = end_span(L, L->t_self, s)) != ATLAS_OK) return rc;
+    }
+    if (L->tf) {
+        // multiply the chunk's rows by W on the matrix cores; the products are what is pushed
+        if ((rc = start_span(L, L->t_self, s)) != ATLAS_OK) return rc;
+        UpdateArgs u{};
+        u.model = 4;
+        u.d_in = d.d_in;
+        u.d_out = d.d_out;
+        u.K = L->K;
+        u.in_bf16 = d.in_dtype == ATLAS_DTYPE_BF16;
+        u.compute_bf16 = L->compute_bf16;
+        u.self_rows = a.emb;
+        u.counters = L->ctr();
+        u.n = src_end - src_begin;
+        u.identity_rows = src_end - src_begin;
+        float *self_rows_out = L->tf_self.p ? static_cast<float *>(L->tf_self.p) + static_cast<size_t>(src_begin) * d.d_out
+                                            : nullptr;
+        u.packed_w = L->packed_w.p;
+        u.out = d.model == ATLAS_MODEL_GIN ? static_cast<void *>(self_rows_out) : L->tf_z.p;
+        HIP_TRY(launch_update(u, s));
+        if (d.model == ATLAS_MODEL_SAGE_MEAN) {
+            u.packed_w = L->packed_w2.p;
+            u.out = self_rows_out;
+            HIP_TRY(launch_update(u, s));
+        }
+        if ((rc = end_span(L, L->t_self, s)) != ATLAS_OK) return rc;
+        a.emb = d.model == ATLAS_MODEL_GIN ? static_cast<const void *>(self_rows_out) : L->tf_z.p;
+        a.d = d.d_out;
+        a.in_bf16 = 0;
     }
     if (d.model == ATLAS_MODEL_GAT) {
         // transform the chunk (z = x W on the matrix cores), raise the running
@@ -713,6 +775,23 @@ int atlas_flush_ready(atlas_layer_t *L, void *out, int64_t *n_flushed, void *hip
         f.out_bf16 = u.out_bf16;
         f.n = L->n;
         HIP_TRY(launch_gat_finalize(f, s));
+    } else if (L->tf) {
+        SumFinalizeArgs f{};
+        f.acc = u.acc;
+        f.slot_of = u.slot_of;
+        f.self_term = static_cast<const float *>(L->tf_self.p);
+        f.self_scale = d.model == ATLAS_MODEL_GIN ? 1.0f + d.gin_eps : 1.0f;
+        f.norm = d.model == ATLAS_MODEL_SAGE_MEAN ? 0 : (d.model == ATLAS_MODEL_GCN_SYM ? 1 : 2);
+        f.indeg = u.indeg;
+        f.ready = u.ready;
+        f.counters = u.counters;
+        f.bias = u.bias;
+        f.out = out;
+        f.d_out = d.d_out;
+        f.activation = d.activation;
+        f.out_bf16 = u.out_bf16;
+        f.n = L->n;
+        HIP_TRY(launch_sum_finalize(f, s));
     } else if (d.model == ATLAS_MODEL_SGC_HOP) {
         HIP_TRY(launch_scale_rows(u, s));
     } else

@@ -189,7 +189,8 @@ hipError_t launch_to_f32(const void *src, int src_bf16, int64_t count, float *ds
 
 struct UpdateArgs {
     int model;                // 0 SAGE (own row || mean), 1 GCN (deg^-1/2 sum), 2 plain rows of `acc`,
-                              // 3 GIN (sum + self_scale * own row)
+                              // 3 GIN (sum + self_scale * own row), 4 plain rows of `self_rows` (storage
+                              // dtype, d_in up to 1024; with identity_rows)
     float self_scale;         // GIN: 1 + eps
     int d_in, d_out, K;       // K = 2*d_in (SAGE) or d_in
     int in_bf16, out_bf16, compute_bf16;
@@ -209,6 +210,24 @@ struct UpdateArgs {
 };
 // S5: gather ready rows, normalise, MFMA GEMM, bias, activation, scatter rows.
 hipError_t launch_update(const UpdateArgs &a, hipStream_t s);
+// Transform-first layers: the ready rows' outputs from already-transformed sums,
+// y_v = act(scale(deg_v) * acc[v] + self_scale * self_term[v] + b).
+struct SumFinalizeArgs {
+    const float *acc;         // [N or slots][d_out]
+    const int32_t *slot_of;   // bounded store indirection or nullptr
+    const float *self_term;   // [N][d_out] or nullptr
+    float self_scale;
+    int norm;                 // 0: 1/deg (mean), 1: deg^-1/2, 2: none
+    const int32_t *indeg;
+    const int32_t *ready;
+    int32_t *counters;
+    const float *bias;
+    void *out;
+    int d_out, activation, out_bf16;
+    int64_t n;
+};
+hipError_t launch_sum_finalize(const SumFinalizeArgs &a, hipStream_t s);
+
 // SGC hop: out[v] = acc[v] * deg(v)^-1/2 for the ready rows (no contraction).
 hipError_t launch_scale_rows(const UpdateArgs &a, hipStream_t s);
 hipError_t launch_advance_head(int32_t *counters, hipStream_t s);

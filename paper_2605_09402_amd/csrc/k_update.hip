@@ -149,18 +149,21 @@ __device__ __forceinline__ float4 own_to_f32(uint2 u) {   // four bf16 -> fp32
 __device__ __forceinline__ float4 own_to_f32(float4 v) { return v; }
 
 template <bool BF16C, int SEGS>
+__device__ __forceinline__ void gather_own_rows(const UpdateArgs &a, typename Elem<BF16C>::type *A, int stride,
+                                                int w, int lane, int32_t idv);
+
+template <bool BF16C, int SEGS>
 __device__ __forceinline__ void gather_rows(const UpdateArgs &a, typename Elem<BF16C>::type *A, int stride,
                                             int w, int lane, int32_t idv, int32_t rowv, float scalev,
                                             int has_aggv) {
     constexpr int kRows = kTileRows / 8;  // rows per wave
-    constexpr bool two = SEGS == 2;       // one or two 256-column segments per row
-    constexpr int nitems = SEGS * kRows;
+    constexpr int nitems = SEGS * kRows;  // 256-column segments per row x rows
     constexpr int kBatch = 8;             // loads in flight per pass
     const int d = a.d_in;
     const int c4 = lane * 4;
     const int acc_base = a.model == 0 ? d : 0;  // SAGE: own row first, then the neighbour mean
-    auto row_of = [&](int item) { return two ? item >> 1 : item; };
-    auto col_of = [&](int item) { return (two ? (item & 1) * 256 : 0) + c4; };
+    auto row_of = [&](int item) { return item / SEGS; };
+    auto col_of = [&](int item) { return (item % SEGS) * 256 + c4; };
     if (a.model == 3) {   // GIN: sum + self_scale * own row, rounded once
 #pragma unroll
         for (int base = 0; base < nitems; base += kBatch) {
@@ -233,7 +236,22 @@ __device__ __forceinline__ void gather_rows(const UpdateArgs &a, typename Elem<B
         }
     }
     if (a.model != 0) return;
-    // SAGE: the vertex's own row (rows past the list's end are stored as loaded and never used)
+    gather_own_rows<BF16C, SEGS>(a, A, stride, w, lane, idv);
+}
+
+// Rows of `self_rows` (storage dtype) into columns [0, d_in) of the A tile: the
+// SAGE own rows, or the whole operand of a plain row transform (model 4).
+template <bool BF16C, int SEGS>
+__device__ __forceinline__ void gather_own_rows(const UpdateArgs &a, typename Elem<BF16C>::type *A, int stride,
+                                                int w, int lane, int32_t idv) {
+    constexpr int kRows = kTileRows / 8;
+    constexpr int nitems = SEGS * kRows;
+    constexpr int kBatch = 8;
+    const int d = a.d_in;
+    const int c4 = lane * 4;
+    auto row_of = [&](int item) { return item / SEGS; };
+    auto col_of = [&](int item) { return (item % SEGS) * 256 + c4; };
+    // rows past the list's end are stored as loaded and never used
 #pragma unroll
     for (int base = 0; base < nitems; base += kBatch) {
         typename OwnRaw4<BF16C>::type v[kBatch];
@@ -331,8 +349,15 @@ __global__ __launch_bounds__(kGenBlock, 4) void k_update(UpdateArgs a) {
         }
         frag_t wcur[kUnroll];
         load_w(0, wcur);   // on its way while the rows are gathered
-        if (a.d_in > 256) gather_rows<BF16C, 2>(a, A, stride, w, lane, idv, rowv, scalev, has_aggv);
-        else gather_rows<BF16C, 1>(a, A, stride, w, lane, idv, rowv, scalev, has_aggv);
+        if (a.model == 4) {   // plain rows in the storage dtype, up to 1024 wide
+            if (a.d_in > 512) gather_own_rows<BF16C, 4>(a, A, stride, w, lane, idv);
+            else if (a.d_in > 256) gather_own_rows<BF16C, 2>(a, A, stride, w, lane, idv);
+            else gather_own_rows<BF16C, 1>(a, A, stride, w, lane, idv);
+        } else if (a.d_in > 256) {
+            gather_rows<BF16C, 2>(a, A, stride, w, lane, idv, rowv, scalev, has_aggv);
+        } else {
+            gather_rows<BF16C, 1>(a, A, stride, w, lane, idv, rowv, scalev, has_aggv);
+        }
         __syncthreads();
 
         // ---- contraction, as D^T blocks; the bias is the initial accumulator ----
@@ -709,6 +734,46 @@ hipError_t launch_pipelined_c(const UpdateArgs &a, int grid, hipStream_t s) {
     return launch_pipelined_o<BF16C, 0>(a, grid, s);
 }
 
+// Transform-first layers: one wave per ready row, four columns per lane and round.
+__global__ __launch_bounds__(kBlock) void k_sum_finalize(SumFinalizeArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = static_cast<int64_t>(blockIdx.x) * (kBlock / 64) + (threadIdx.x >> 6);
+    const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (kBlock / 64);
+    const int head = a.counters[CTR_READY_HEAD];
+    const int tail = a.counters[CTR_READY_TAIL];
+    const int d = a.d_out;
+    for (int64_t i = head + wave; i < tail; i += nwaves) {
+        const int64_t v = a.ready[i];
+        const int32_t deg = a.indeg[v];
+        const float fd = static_cast<float>(deg > 0 ? deg : 1);
+        const float g = a.norm == 0 ? 1.0f / fd : (a.norm == 1 ? 1.0f / sqrtf(fd) : 1.0f);
+        const int64_t arow = a.slot_of ? static_cast<int64_t>(a.slot_of[v]) : v;
+        for (int c = lane * 4; c < d; c += 256) {
+            float y[4] = {0.f, 0.f, 0.f, 0.f};
+            if (deg > 0) {   // the accumulator of a vertex without in-edges was never written
+                const float4 x = *reinterpret_cast<const float4 *>(a.acc + arow * d + c);
+                y[0] = x.x * g; y[1] = x.y * g; y[2] = x.z * g; y[3] = x.w * g;
+            }
+            if (a.self_term) {
+                const float4 t = *reinterpret_cast<const float4 *>(a.self_term + v * d + c);
+                y[0] += a.self_scale * t.x; y[1] += a.self_scale * t.y;
+                y[2] += a.self_scale * t.z; y[3] += a.self_scale * t.w;
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if (a.bias) y[k] += a.bias[c + k];
+                if (a.activation == 1) y[k] = fmaxf(y[k], 0.f);
+                else if (a.activation == 2) y[k] = y[k] > 0.f ? y[k] : expm1f(y[k]);
+            }
+            if (a.out_bf16)
+                *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(a.out) + v * d + c) =
+                    make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
+            else
+                *reinterpret_cast<float4 *>(static_cast<float *>(a.out) + v * d + c) = make_float4(y[0], y[1], y[2], y[3]);
+        }
+    }
+}
+
 // SGC hop: the ready rows of the accumulator times deg^-1/2, one wave per row.
 __global__ __launch_bounds__(kBlock) void k_scale_rows(UpdateArgs a) {
     const int lane = threadIdx.x & 63;
@@ -764,7 +829,7 @@ hipError_t launch_update_t(const UpdateArgs &a, int grid, hipStream_t s) {
 template <bool BF16C>
 hipError_t launch_update_c(const UpdateArgs &a, int grid, hipStream_t s) {
     const int NB = (a.d_out + 31) / 32;
-    if (NB > 8 || a.d_in > 512) return hipErrorInvalidValue;
+    if (NB > 8 || a.d_in > (a.model == 4 ? 1024 : 512)) return hipErrorInvalidValue;
     return NB > 4 ? launch_update_t<BF16C, true>(a, grid, s) : launch_update_t<BF16C, false>(a, grid, s);
 }
 
@@ -795,7 +860,7 @@ hipError_t launch_update(const UpdateArgs &a, hipStream_t s) {
     if (hipGetDevice(&dev) == hipSuccess)
         (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (cus <= 0) cus = 256;
-    if (a.d_in <= 128 && pipelined_lds_bytes(a.K, a.d_out, a.compute_bf16 != 0) <= 160 * 1024) {
+    if (a.model != 4 && a.d_in <= 128 && pipelined_lds_bytes(a.K, a.d_out, a.compute_bf16 != 0) <= 160 * 1024) {
         int64_t grid = cus;
         const int64_t max_tiles = (a.n + kTileRows - 1) / kTileRows;
         if (grid > max_tiles) grid = max_tiles;
@@ -813,6 +878,18 @@ hipError_t launch_update(const UpdateArgs &a, hipStream_t s) {
     if (grid < 1) grid = 1;
     return a.compute_bf16 ? launch_update_c<true>(a, static_cast<int>(grid), s)
                           : launch_update_c<false>(a, static_cast<int>(grid), s);
+}
+
+hipError_t launch_sum_finalize(const SumFinalizeArgs &a, hipStream_t s) {
+    if (a.n <= 0) return hipSuccess;
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess)
+        (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (cus <= 0) cus = 256;
+    int64_t blocks = (a.n + (kBlock / 64) - 1) / (kBlock / 64);
+    if (blocks > static_cast<int64_t>(cus) * 8) blocks = static_cast<int64_t>(cus) * 8;
+    hipLaunchKernelGGL(k_sum_finalize, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, s, a);
+    return hipGetLastError();
 }
 
 hipError_t launch_scale_rows(const UpdateArgs &a, hipStream_t s) {

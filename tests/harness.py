@@ -88,7 +88,8 @@ def _dt(store: torch.dtype) -> int:
 def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, flush_every: int = 1,
             give_indeg: bool = False, timing: bool = False, max_layers: Optional[int] = None,
             plan: bool = False, plan_chunk: Optional[int] = None, emb_resident: bool = False,
-            planned_only: bool = False, hot_slots: int = 0, evict_policy: int = 0) -> GpuRun:
+            planned_only: bool = False, hot_slots: int = 0, evict_policy: int = 0,
+            transform_first: bool = False) -> GpuRun:
     """Drive all layers through the C ABI.  With pinned_host the graph and the
     layer-0 features stay in pinned host memory and are staged by the library.
     planned_only sets ATLAS_FLAG_PLANNED_ONLY (no zero fill of the accumulators;
@@ -135,7 +136,8 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
                                neg_slope=case.slope, gin_eps=case.eps, hot_slots=hot_slots,
                                evict_policy=evict_policy, flags=(atlas.FLAG_TIMING if timing else 0) |
                                (atlas.FLAG_EMB_RESIDENT if emb_resident else 0) |
-                               (atlas.FLAG_PLANNED_ONLY if planned_only else 0))
+                               (atlas.FLAG_PLANNED_ONLY if planned_only else 0) |
+                               (atlas.FLAG_TRANSFORM_FIRST if transform_first else 0))
         weights = atlas.make_weights(W, b, sdt, a_s, a_d)
         h = atlas.atlas_layer_init(graph, dims, weights, stream)
         out = torch.full((max(n, 1), d_out), float("nan"), dtype=case.store, device=dev)

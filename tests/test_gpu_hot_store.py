@@ -87,6 +87,17 @@ def test_minimum_pending_evicts_less_than_maximum_pending(oracle, H):
     assert 2 * counts[0] < counts[1]
 
 
+def test_bounded_store_with_transform_first(oracle, H):
+    """Both options together: d_out-wide slots."""
+    g = gen.rmat_graph(SEED + 1, 12, 16, random_ids=True)
+    case = H.make_case("sage", g, SEED + 1, [256, 64, 64], 64, store=torch.bfloat16)
+    slots = started(case) // 2
+    ev, rl, peak = oracle.hot_store_trace(case.off.numpy(), case.col.numpy(), case.chunk, slots, True)
+    run = H.run_gpu(case, plan=True, hot_slots=slots, transform_first=True)
+    H.check_outputs(oracle, case, run)
+    assert (run.stats[0]["hot_evictions"], run.stats[0]["hot_reloads"]) == (sum(ev), sum(rl))
+
+
 def test_store_too_small_and_not_needed(oracle, H):
     import paper_2605_09402_amd as atlas
     g = gen.rmat_graph(SEED + 3, 10, 16)

@@ -174,3 +174,23 @@ def test_sgc_three_hops(oracle, H, plan, d):
     run = H.run_gpu(case, snapshots=True, plan=plan, planned_only=plan)
     H.check_integers(oracle, case, run, layer=0)
     print("sgc", d, H.check_outputs(oracle, case, run))
+
+
+@pytest.mark.parametrize("plan", [False, True], ids=["csr_stream", "planned"])
+@pytest.mark.parametrize("model,store,dims", [
+    ("sage", torch.bfloat16, [1024, 128, 64]),     # wide 16-bit input features, the shape of the paper's largest datasets
+    ("sage", torch.float32, [512, 64, 64]),
+    ("gcn", torch.float32, [256, 64, 64]),
+    ("gin", torch.bfloat16, [768, 128, 128]),
+])
+def test_transform_first(oracle, H, model, store, dims, plan):
+    """ATLAS_FLAG_TRANSFORM_FIRST: the chunk's rows are multiplied by W before
+    they are pushed (d_out-wide messages and accumulators); the result must
+    equal the same oracle as the default order.  R-MAT scale 12."""
+    g = gen.rmat_graph(SEED + 9, 12, 16, random_ids=True, self_loops=(model == "gcn"))
+    case = H.make_case(model, g, SEED + 9, dims, 300, store=store, eps=0.5,
+                       feat="normal" if store == torch.float32 else "uniform")
+    run = H.run_gpu(case, snapshots=True, plan=plan, planned_only=plan, transform_first=True)
+    H.check_integers(oracle, case, run, layer=0)
+    H.check_integers(oracle, case, run, layer=1)
+    print("transform first", model, dims, H.check_outputs(oracle, case, run))
