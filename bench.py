@@ -35,11 +35,15 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", choices=["config2", "config3", "config4", "config5"], default="config5",
+    ap.add_argument("--workload", choices=["config2", "config3", "config4", "config5", "wide"], default="config5",
                     help="config5 (default) is the workload the metric is quoted on; the others are the smaller "
                          "parity workloads, timed for the record")
     ap.add_argument("--layer-type", choices=["sage", "gin"], default="sage",
                     help="config5 only: run the same graph and widths through GIN layers instead of SAGE-mean")
+    ap.add_argument("--d-in", type=int, default=512, help="workload wide: input feature width (up to 1024 with "
+                                                          "--transform-first, 512 without)")
+    ap.add_argument("--transform-first", action="store_true",
+                    help="apply W to each chunk before it is pushed (d_out-wide messages and accumulators)")
     ap.add_argument("--hot-slots-frac", type=float, default=0.0,
                     help="bounded accumulator store: slots = this fraction of the vertices with an in-edge "
                          "(0: one accumulator row per vertex); needs chunks small enough to fit")
@@ -103,6 +107,8 @@ def main() -> int:
                                model=args.layer_type)
     elif args.workload == "config2":
         wl = workloads.config2(dev, scale=args.scale or 20, reorder=ro, chunk=ck)
+    elif args.workload == "wide":
+        wl = workloads.wide(dev, scale=args.scale or 22, d_in=args.d_in, reorder=ro, chunk=ck)
     elif args.workload == "config3":
         wl = workloads.config3(dev, scale=args.scale or 22, chunk=ck)
     else:
@@ -160,7 +166,8 @@ def main() -> int:
         act = atlas.ACT_NONE if li + 1 == len(wl.layers) else between
         dims = atlas.make_dims(model_id, d_in, d_out, sdt, sdt, act, chunk, heads=wl.heads,
                                flags=(atlas.FLAG_TIMING if timing else 0) | atlas.FLAG_EMB_RESIDENT |
-                               (atlas.FLAG_PLANNED_ONLY if plan is not None else 0),
+                               (atlas.FLAG_PLANNED_ONLY if plan is not None else 0) |
+                               (atlas.FLAG_TRANSFORM_FIRST if args.transform_first else 0),
                                hot_slots=hot_slots, evict_policy=1 if args.evict_policy == "max" else 0)
         W, b = params[li]
         h = atlas.atlas_layer_init(graph, dims, atlas.make_weights(W, b, sdt, attn[li][0], attn[li][1]), stream)
@@ -322,6 +329,7 @@ def main() -> int:
                    % (h2d_bytes / 1e9, copy_ms / args.steps),
                    "edge_order": "per-chunk destination-grouped plan" if plan else "CSR stream (atomics)",
                    "plan_build_ms": None if plan_ms is None else round(plan_ms, 1)},
+        "transform_first": bool(args.transform_first),
         "hot_store": None if not hot_slots else {
             "slots": hot_slots, "policy": args.evict_policy + "-pending", "evictions_per_layer": st["hot_evictions"],
             "reloads_per_layer": st["hot_reloads"], "peak_slots": st["hot_peak_slots"]},

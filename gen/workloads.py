@@ -103,3 +103,14 @@ def config5(device="cpu", scale: int = 26, reorder: Optional[Reorder] = None, ch
     g = rmat_graph(seed, scale, edge_factor, device=device)
     return _finish("config5_%s_rmat%d_bf16" % (model, scale), model, g, seed, [128, 128, 128, 64],
                    chunk or max(64, (1 << scale) // 16), "uniform", torch.bfloat16, "relu", device, reorder=reorder)
+
+
+def wide(device="cpu", scale: int = 22, d_in: int = 512, reorder: Optional[Reorder] = None,
+         chunk: Optional[int] = None) -> Workload:
+    """Wide 16-bit input features into a narrow hidden layer, the shape of the first
+    layer on the paper's MAG240M / IGB feature sets (768 / 1024 wide, Sec. 4.1):
+    GraphSAGE-mean d_in -> 128 -> 128 on R-MAT, bf16, edge factor 16."""
+    seed = SEED0 + 6
+    g = rmat_graph(seed, scale, 16, device=device)
+    return _finish("wide%d_sage_rmat%d_bf16" % (d_in, scale), "sage", g, seed, [d_in, 128, 128],
+                   chunk or max(64, (1 << scale) // 16), "uniform", torch.bfloat16, "relu", device, reorder=reorder)

@@ -291,8 +291,10 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
         const size_t rows = static_cast<size_t>(std::min<int64_t>(d.max_chunk_sources, std::max<int64_t>(n, 1)));
         if (d.model != ATLAS_MODEL_GIN) HIP_TRY(L->tf_z.alloc(rows * d.d_out * sizeof(float)));
         if (has_self_term(d.model)) HIP_TRY(L->tf_self.alloc(n1 * d.d_out * sizeof(float)));
+        // SAGE: W_neigh and W_self side by side in one fragment-ordered buffer (column blocks of the
+        // first, then of the second), so that one pass over the chunk's rows yields both products
         if (d.model == ATLAS_MODEL_SAGE_MEAN)
-            HIP_TRY(L->packed_w2.alloc(packed_weight_bytes(L->K, d.d_out, L->compute_bf16)));
+            HIP_TRY(L->packed_w2.alloc(2 * packed_weight_bytes(L->K, d.d_out, L->compute_bf16)));
     }
     if (has_self_term(d.model) && !L->emb_resident && !L->tf)
         HIP_TRY(L->self_rows.alloc(n1 * d.d_in * dtype_size(d.in_dtype)));
@@ -403,10 +405,10 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
         // rows 0..d_in-1 of W multiply the own embedding, rows d_in.. the neighbour mean
         const char *w_neigh = static_cast<const char *>(w->W) +
                               static_cast<size_t>(d.d_in) * d.d_out * dtype_size(w->dtype);
+        char *second = static_cast<char *>(L->packed_w2.p) + packed_weight_bytes(L->K, d.d_out, L->compute_bf16);
         HIP_TRY(launch_pack_weights(w_neigh, w->dtype == ATLAS_DTYPE_BF16, L->K, d.d_out, L->compute_bf16,
-                                    L->packed_w.p, s));
-        HIP_TRY(launch_pack_weights(w->W, w->dtype == ATLAS_DTYPE_BF16, L->K, d.d_out, L->compute_bf16,
                                     L->packed_w2.p, s));
+        HIP_TRY(launch_pack_weights(w->W, w->dtype == ATLAS_DTYPE_BF16, L->K, d.d_out, L->compute_bf16, second, s));
     } else if (d.model != ATLAS_MODEL_SGC_HOP)
         HIP_TRY(launch_pack_weights(w->W, w->dtype == ATLAS_DTYPE_BF16, L->K, d.d_out, L->compute_bf16,
                                     L->packed_w.p, s));
@@ -616,12 +618,27 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         u.identity_rows = src_end - src_begin;
         float *self_rows_out = L->tf_self.p ? static_cast<float *>(L->tf_self.p) + static_cast<size_t>(src_begin) * d.d_out
                                             : nullptr;
-        u.packed_w = L->packed_w.p;
-        u.out = d.model == ATLAS_MODEL_GIN ? static_cast<void *>(self_rows_out) : L->tf_z.p;
-        HIP_TRY(launch_update(u, s));
         if (d.model == ATLAS_MODEL_SAGE_MEAN) {
-            u.packed_w = L->packed_w2.p;
-            u.out = self_rows_out;
+            const size_t half = packed_weight_bytes(L->K, d.d_out, L->compute_bf16);
+            if (d.d_out % 32 == 0 && 2 * d.d_out <= 256) {
+                // one pass over the rows: [x W_neigh | x W_self], the halves go to the two buffers
+                u.packed_w = L->packed_w2.p;
+                u.d_out = 2 * d.d_out;
+                u.split = d.d_out;
+                u.out = L->tf_z.p;
+                u.out2 = self_rows_out;
+                HIP_TRY(launch_update(u, s));
+            } else {
+                u.packed_w = L->packed_w2.p;
+                u.out = L->tf_z.p;
+                HIP_TRY(launch_update(u, s));
+                u.packed_w = static_cast<char *>(L->packed_w2.p) + half;
+                u.out = self_rows_out;
+                HIP_TRY(launch_update(u, s));
+            }
+        } else {
+            u.packed_w = L->packed_w.p;
+            u.out = d.model == ATLAS_MODEL_GIN ? static_cast<void *>(self_rows_out) : L->tf_z.p;
             HIP_TRY(launch_update(u, s));
         }
         if ((rc = end_span(L, L->t_self, s)) != ATLAS_OK) return rc;

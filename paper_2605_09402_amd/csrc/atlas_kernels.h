@@ -203,6 +203,9 @@ struct UpdateArgs {
     const void *packed_w;
     const float *bias;        // fp32 [d_out] or nullptr
     void *out;                // [N][d_out]
+    void *out2;               // split > 0: columns split.. of the product go to out2 (column - split) and
+    int split;                // columns below split to out, both with rows of `split` columns (a product
+                              // with two weight matrices side by side); 0: one output of d_out columns
     int64_t n;
     const int32_t *slot_of;   // bounded store: row of `acc` that holds vertex v (nullptr: row v)
     int64_t identity_rows;    // > 0: no ready list; rows 0..identity_rows-1 of `acc` (a dense

@@ -108,18 +108,29 @@ __device__ __forceinline__ void store_block_row(const UpdateArgs &a, const f32x1
 #pragma unroll
         for (int r = 0; r < 16; ++r) y[r] = y[r] > 0.f ? y[r] : expm1f(y[r]);
     }
+    // two weight matrices side by side: the block lies wholly in one of the two outputs
+    void *outp = a.out;
+    int cols = a.d_out;
+    if (a.split > 0) {
+        cols = a.split;
+        if (nbase >= a.split) {
+            outp = a.out2;
+            nbase -= a.split;
+        }
+    }
+    const int limit = a.split > 0 ? a.split : a.d_out;
     if (a.out_bf16) {
-        uint16_t *o = static_cast<uint16_t *>(a.out) + out_row * a.d_out + nbase;
+        uint16_t *o = static_cast<uint16_t *>(outp) + out_row * cols + nbase;
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-            if (nbase + 8 * q < a.d_out)
+            if (nbase + 8 * q < limit)
                 *reinterpret_cast<uint2 *>(o + 8 * q) =
                     make_uint2(pack_bf16x2(y[4 * q], y[4 * q + 1]), pack_bf16x2(y[4 * q + 2], y[4 * q + 3]));
     } else {
-        float *o = static_cast<float *>(a.out) + out_row * a.d_out + nbase;
+        float *o = static_cast<float *>(outp) + out_row * cols + nbase;
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-            if (nbase + 8 * q < a.d_out)
+            if (nbase + 8 * q < limit)
                 *reinterpret_cast<float4 *>(o + 8 * q) = make_float4(y[4 * q], y[4 * q + 1], y[4 * q + 2], y[4 * q + 3]);
     }
 }
