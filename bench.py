@@ -156,6 +156,10 @@ def main() -> int:
     attn = [(None if p.attn_src is None else p.attn_src.to(wl.store).to(dev).contiguous(),
              None if p.attn_dst is None else p.attn_dst.to(wl.store).to(dev).contiguous()) for p in wl.layers]
 
+    bounds = list(range(0, n, chunk)) + [n]
+    per_chunk = (wl.off[bounds[1:]] - wl.off[bounds[:-1]]).tolist()
+    log("edges per chunk (millions): " + " ".join("%.1f" % (x / 1e6) for x in per_chunk[:16]) +
+        (" ..." if len(per_chunk) > 16 else ""))
     hot_slots = 0
     if args.hot_slots_frac > 0:
         hot_slots = max(1, int(args.hot_slots_frac * int((indeg > 0).sum().item())))
