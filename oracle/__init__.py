@@ -18,7 +18,7 @@ _SRC = os.path.join(_HERE, "atlas_oracle.c")
 _LIB = os.path.join(_HERE, "libatlas_oracle.so")
 
 ACT_NONE, ACT_RELU, ACT_ELU = 0, 1, 2
-FMT_F32, FMT_BF16 = 0, 1
+FMT_F32, FMT_BF16, FMT_F16 = 0, 1, 2
 
 
 def build(force: bool = False) -> str:

@@ -30,7 +30,9 @@
  *       (Sec. 3.8, k_v(t) = d_in(v)).
  *
  * Multi-edges count with multiplicity everywhere.  fp64 throughout; inputs are
- * the already-rounded storage values (passed as float).
+ * the already-rounded storage values (passed as float).  Storage formats: fp32,
+ * bf16 and IEEE half precision (the paper's largest feature set is stored in
+ * FP16, Sec. 4.1), each a single round-to-nearest-even of the fp64 result.
  *
  * Pins: see tests/test_oracle_*.py (dense adjacency brute force, the Fig. 2
  * worked example, closed forms, permutation invariance, counter invariants).
@@ -260,6 +262,14 @@ void ao_round_storage(int64_t count, double *Y, int fmt) {
         double y = Y[i];
         if (fmt == 0) { Y[i] = (double)(float)y; continue; }
         if (y == 0.0 || !isfinite(y)) continue;
+        if (fmt == 2) {   /* IEEE binary16: 11-bit significand, normals from 2^-14, subnormals in steps of 2^-24 */
+            int e16;
+            double m16 = frexp(y, &e16);
+            if (fabs(y) >= 65520.0) { Y[i] = y > 0 ? INFINITY : -INFINITY; continue; }   /* halfway to 2^16 rounds up */
+            if (e16 >= -13) Y[i] = ldexp(nearbyint(m16 * 2048.0), e16 - 11);
+            else Y[i] = ldexp(nearbyint(ldexp(y, 24)), -24);
+            continue;
+        }
         int e;
         double m = frexp(y, &e);              /* y = m * 2^e, 0.5 <= |m| < 1 */
         if (e < -120) { Y[i] = 0.0; continue; }

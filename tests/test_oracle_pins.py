@@ -370,6 +370,14 @@ def test_rounding_and_activation_vs_library(oracle):
     got = oracle.round_storage(v.astype(np.float64), oracle.FMT_BF16)
     ref = torch.from_numpy(v).to(torch.bfloat16).to(torch.float64).numpy()
     assert np.array_equal(got, ref)
+    # half precision: normals, subnormals (below 2^-14), ties, and the overflow threshold
+    h = (rng.standard_normal(20000) * np.exp(rng.uniform(-18, 11, 20000))).astype(np.float32)
+    hties = np.array([1.00048828125, 1.00146484375, 2049.0, 2051.0, 65504.0, 65519.9, 65520.0, -7e4, 5.9e-8, 2.9e-8,
+                      3.1e-8, 6.1e-5, 6.09e-5, 0.0], dtype=np.float32)
+    h = np.concatenate([h, hties])
+    got16 = oracle.round_storage(h.astype(np.float64), oracle.FMT_F16)
+    ref16 = torch.from_numpy(h).to(torch.float16).to(torch.float64).numpy()
+    assert np.array_equal(got16, ref16)
     x = rng.standard_normal(1000) * 3
     assert np.allclose(oracle.activation(x, oracle.ACT_ELU),
                        torch.nn.functional.elu(torch.from_numpy(x)).numpy(), rtol=1e-15, atol=0)
