@@ -151,7 +151,7 @@ def main() -> int:
 
     model_id = {"sage": atlas.MODEL_SAGE_MEAN, "gcn": atlas.MODEL_GCN_SYM, "gat": atlas.MODEL_GAT,
                 "gin": atlas.MODEL_GIN}[wl.model]
-    sdt = atlas.DTYPE_BF16 if wl.store == torch.bfloat16 else atlas.DTYPE_F32
+    sdt = {torch.bfloat16: atlas.DTYPE_BF16, torch.float16: atlas.DTYPE_F16}.get(wl.store, atlas.DTYPE_F32)
     between = atlas.ACT_ELU if wl.act == "elu" else atlas.ACT_RELU
     attn = [(None if p.attn_src is None else p.attn_src.to(wl.store).to(dev).contiguous(),
              None if p.attn_dst is None else p.attn_dst.to(wl.store).to(dev).contiguous()) for p in wl.layers]
@@ -299,7 +299,7 @@ def main() -> int:
         indeg_s = indeg[need].cpu().numpy().astype(np.int64)
         t1 = time.perf_counter()
         Y = oracle.run_layer(wl.model, il, indeg_s, Xs, p0, {"relu": oracle.ACT_RELU, "elu": oracle.ACT_ELU}[wl.act],
-                             oracle.FMT_BF16 if wl.store == torch.bfloat16 else oracle.FMT_F32)
+                             {torch.bfloat16: oracle.FMT_BF16, torch.float16: oracle.FMT_F16}.get(wl.store, oracle.FMT_F32))
         t_or = time.perf_counter() - t1
         sample_edges = int(in_src.numel())
         # sampled parity of the timed configuration, on the way

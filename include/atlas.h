@@ -61,7 +61,13 @@ enum atlas_model {
     ATLAS_MODEL_SGC_HOP = 4  /* one propagation step of SGC: the symmetric-normalised neighbour sum
                                 without weights; K hops = K-1 such layers and one GCN_SYM layer */
 };
-enum atlas_dtype { ATLAS_DTYPE_F32 = 0, ATLAS_DTYPE_BF16 = 1 };
+enum atlas_dtype {
+    ATLAS_DTYPE_F32 = 0,
+    ATLAS_DTYPE_BF16 = 1,
+    ATLAS_DTYPE_F16 = 2  /* IEEE half (the paper's largest feature set is stored so, Sec. 4.1); sums are kept in
+                            fp32, the contraction runs on half operands.  Not for GAT; GIN only together with
+                            ATLAS_FLAG_TRANSFORM_FIRST (a hub's plain sum leaves the range of half) */
+};
 enum atlas_activation { ATLAS_ACT_NONE = 0, ATLAS_ACT_RELU = 1, ATLAS_ACT_ELU = 2 };
 enum atlas_flags {
     ATLAS_FLAG_TIMING = 1,       /* record per-stage GPU time with HIP events                  */

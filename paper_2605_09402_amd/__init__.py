@@ -18,7 +18,7 @@ OK = 0
 E_NULL, E_BAD_DIMS, E_RANGE, E_ORDER, E_INCOMPLETE, E_OVERFLOW, E_HIP, E_NOMEM, E_STATE = range(-1, -10, -1)
 RESIDENT_DEVICE, RESIDENT_PINNED_HOST = 0, 1
 MODEL_SAGE_MEAN, MODEL_GCN_SYM, MODEL_GAT, MODEL_GIN, MODEL_SGC_HOP = 0, 1, 2, 3, 4
-DTYPE_F32, DTYPE_BF16 = 0, 1
+DTYPE_F32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
 ACT_NONE, ACT_RELU, ACT_ELU = 0, 1, 2
 FLAG_TIMING = 1
 FLAG_EMB_RESIDENT = 2

@@ -72,7 +72,7 @@ struct Buf {
     }
 };
 
-size_t dtype_size(int dt) { return dt == ATLAS_DTYPE_BF16 ? 2 : 4; }
+size_t dtype_size(int dt) { return dt == ATLAS_DTYPE_F32 ? 4 : 2; }
 
 // Cold tier of the bounded accumulator store: one pinned host buffer per
 // process, grown on demand and kept until atlas_release_cache (pinning tens of
@@ -133,7 +133,7 @@ struct atlas_layer {
     atlas_dims_t dims{};
     int64_t n = 0, e = 0;
     int K = 0;
-    int compute_bf16 = 0;
+    int compute_dt = 0;
     int selfmsg = 0;
     int acc_width = 0;
 
@@ -232,14 +232,17 @@ int check_dims(const atlas_dims_t &d, const atlas_weights_t &w, int residency) {
     if (d.d_out <= 0 || d.d_out % 16 != 0 || (d.d_out > 256 && d.model != ATLAS_MODEL_SGC_HOP))
         return ATLAS_E_BAD_DIMS;
     for (int dt : {d.in_dtype, d.out_dtype, w.dtype})
-        if (dt != ATLAS_DTYPE_F32 && dt != ATLAS_DTYPE_BF16) return ATLAS_E_BAD_DIMS;
+        if (dt != ATLAS_DTYPE_F32 && dt != ATLAS_DTYPE_BF16 && dt != ATLAS_DTYPE_F16) return ATLAS_E_BAD_DIMS;
     if (d.activation < ATLAS_ACT_NONE || d.activation > ATLAS_ACT_ELU) return ATLAS_E_BAD_DIMS;
     if (d.max_chunk_sources <= 0) return ATLAS_E_BAD_DIMS;
     if (d.hot_slots < 0 || d.evict_policy < ATLAS_EVICT_MIN_PENDING || d.evict_policy > ATLAS_EVICT_MAX_PENDING)
         return ATLAS_E_BAD_DIMS;
     if (d.hot_slots > 0 && (d.model == ATLAS_MODEL_GAT || residency != ATLAS_RESIDENT_DEVICE)) return ATLAS_E_BAD_DIMS;
     const int K = d.model == ATLAS_MODEL_SAGE_MEAN && !tf ? 2 * d.d_in : d.d_in;
-    const bool bf16c = d.in_dtype == ATLAS_DTYPE_BF16;
+    // GIN forms (1 + eps) x_v + sum in the compute type before the contraction: a hub's sum leaves the
+    // range of IEEE half, so half-precision GIN runs transform-first only (products summed in fp32)
+    if (d.model == ATLAS_MODEL_GIN && d.in_dtype == ATLAS_DTYPE_F16 && !tf) return ATLAS_E_BAD_DIMS;
+    const bool bf16c = d.in_dtype != ATLAS_DTYPE_F32;
     const size_t lds = 256 + static_cast<size_t>(64) * (K + (bf16c ? 8 : 1)) * (bf16c ? 2 : 4);
     if (lds > 160 * 1024) return ATLAS_E_BAD_DIMS;
     return ATLAS_OK;
@@ -294,11 +297,11 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
         // SAGE: W_neigh and W_self side by side in one fragment-ordered buffer (column blocks of the
         // first, then of the second), so that one pass over the chunk's rows yields both products
         if (d.model == ATLAS_MODEL_SAGE_MEAN)
-            HIP_TRY(L->packed_w2.alloc(2 * packed_weight_bytes(L->K, d.d_out, L->compute_bf16)));
+            HIP_TRY(L->packed_w2.alloc(2 * packed_weight_bytes(L->K, d.d_out, L->compute_dt)));
     }
     if (has_self_term(d.model) && !L->emb_resident && !L->tf)
         HIP_TRY(L->self_rows.alloc(n1 * d.d_in * dtype_size(d.in_dtype)));
-    HIP_TRY(L->packed_w.alloc(packed_weight_bytes(L->K, d.d_out, L->compute_bf16)));
+    HIP_TRY(L->packed_w.alloc(packed_weight_bytes(L->K, d.d_out, L->compute_dt)));
     HIP_TRY(launch_fill_zero(L->counters.p, L->counters.bytes, s));
     HIP_TRY(launch_fill_zero(L->counters64.p, L->counters64.bytes, s));
     // With ATLAS_FLAG_PLANNED_ONLY every row is first written (not added to) by
@@ -396,7 +399,7 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
         HIP_TRY(launch_fill_i32(static_cast<int32_t *>(L->gat_mcur.p), gat_encoded_neg_inf(), n * d.heads, s));
         HIP_TRY(launch_fill_i32(static_cast<int32_t *>(L->gat_mnext.p), gat_encoded_neg_inf(), n * d.heads, s));
         HIP_TRY(launch_fill_zero(L->gat_l.p, static_cast<size_t>(n) * d.heads * sizeof(float), s));
-        HIP_TRY(launch_gat_fold_attention(w->W, w->attn_src, w->attn_dst, w->dtype == ATLAS_DTYPE_BF16, d.d_in,
+        HIP_TRY(launch_gat_fold_attention(w->W, w->attn_src, w->attn_dst, w->dtype, d.d_in,
                                           d.heads, d.d_out / d.heads, static_cast<float *>(L->gat_wa.p), s));
     }
     HIP_TRY(launch_init_pending(L->indeg, L->selfmsg, n, static_cast<int32_t *>(L->pending.p),
@@ -405,16 +408,16 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
         // rows 0..d_in-1 of W multiply the own embedding, rows d_in.. the neighbour mean
         const char *w_neigh = static_cast<const char *>(w->W) +
                               static_cast<size_t>(d.d_in) * d.d_out * dtype_size(w->dtype);
-        char *second = static_cast<char *>(L->packed_w2.p) + packed_weight_bytes(L->K, d.d_out, L->compute_bf16);
-        HIP_TRY(launch_pack_weights(w_neigh, w->dtype == ATLAS_DTYPE_BF16, L->K, d.d_out, L->compute_bf16,
+        char *second = static_cast<char *>(L->packed_w2.p) + packed_weight_bytes(L->K, d.d_out, L->compute_dt);
+        HIP_TRY(launch_pack_weights(w_neigh, w->dtype, L->K, d.d_out, L->compute_dt,
                                     L->packed_w2.p, s));
-        HIP_TRY(launch_pack_weights(w->W, w->dtype == ATLAS_DTYPE_BF16, L->K, d.d_out, L->compute_bf16, second, s));
+        HIP_TRY(launch_pack_weights(w->W, w->dtype, L->K, d.d_out, L->compute_dt, second, s));
     } else if (d.model != ATLAS_MODEL_SGC_HOP)
-        HIP_TRY(launch_pack_weights(w->W, w->dtype == ATLAS_DTYPE_BF16, L->K, d.d_out, L->compute_bf16,
+        HIP_TRY(launch_pack_weights(w->W, w->dtype, L->K, d.d_out, L->compute_dt,
                                     L->packed_w.p, s));
     if (w->bias && d.model != ATLAS_MODEL_SGC_HOP) {
         HIP_TRY(L->bias.alloc(d.d_out * sizeof(float)));
-        HIP_TRY(launch_to_f32(w->bias, w->dtype == ATLAS_DTYPE_BF16, d.d_out, static_cast<float *>(L->bias.p), s));
+        HIP_TRY(launch_to_f32(w->bias, w->dtype, d.d_out, static_cast<float *>(L->bias.p), s));
     }
     return ATLAS_OK;
 }
@@ -443,7 +446,7 @@ int atlas_layer_init(const atlas_graph_t *graph, const atlas_dims_t *dims, const
     L->selfmsg = has_self_term(dims->model) ? 1 : 0;
     L->tf = transform_first(*dims, graph->residency);
     L->K = dims->model == ATLAS_MODEL_SAGE_MEAN && !L->tf ? 2 * dims->d_in : dims->d_in;
-    L->compute_bf16 = dims->in_dtype == ATLAS_DTYPE_BF16;
+    L->compute_dt = dims->in_dtype;
     L->acc_width = dims->model == ATLAS_MODEL_GAT || L->tf ? dims->d_out : dims->d_in;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     L->last_stream = s;
@@ -511,7 +514,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
     a.src_begin = src_begin;
     a.src_end = src_end;
     a.d = d.d_in;
-    a.in_bf16 = d.in_dtype == ATLAS_DTYPE_BF16;
+    a.in_dt = d.in_dtype;
     a.model = aggregate_kind(d.model);
     a.acc = static_cast<float *>(L->acc.p);
     a.pending = static_cast<int32_t *>(L->pending.p);
@@ -610,8 +613,8 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         u.d_in = d.d_in;
         u.d_out = d.d_out;
         u.K = L->K;
-        u.in_bf16 = d.in_dtype == ATLAS_DTYPE_BF16;
-        u.compute_bf16 = L->compute_bf16;
+        u.in_dt = d.in_dtype;
+        u.compute_dt = L->compute_dt;
         u.self_rows = a.emb;
         u.counters = L->ctr();
         u.n = src_end - src_begin;
@@ -619,7 +622,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         float *self_rows_out = L->tf_self.p ? static_cast<float *>(L->tf_self.p) + static_cast<size_t>(src_begin) * d.d_out
                                             : nullptr;
         if (d.model == ATLAS_MODEL_SAGE_MEAN) {
-            const size_t half = packed_weight_bytes(L->K, d.d_out, L->compute_bf16);
+            const size_t half = packed_weight_bytes(L->K, d.d_out, L->compute_dt);
             if (d.d_out % 32 == 0 && 2 * d.d_out <= 256) {
                 // one pass over the rows: [x W_neigh | x W_self], the halves go to the two buffers
                 u.packed_w = L->packed_w2.p;
@@ -644,7 +647,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         if ((rc = end_span(L, L->t_self, s)) != ATLAS_OK) return rc;
         a.emb = d.model == ATLAS_MODEL_GIN ? static_cast<const void *>(self_rows_out) : L->tf_z.p;
         a.d = d.d_out;
-        a.in_bf16 = 0;
+        a.in_dt = 0;
     }
     if (d.model == ATLAS_MODEL_GAT) {
         // transform the chunk (z = x W on the matrix cores), raise the running
@@ -665,7 +668,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         a.gat = gat_state(L);
         a.emb = L->gat_z.p;
         a.d = d.d_out;
-        a.in_bf16 = 0;
+        a.in_dt = 0;
     }
     if (pc) {
         if (!plan->host) {
@@ -678,7 +681,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         ga.gat = a.gat;
         ga.src_begin = src_begin;
         ga.d = a.d;
-        ga.in_bf16 = a.in_bf16;
+        ga.in_dt = a.in_dt;
         ga.model = a.model;
         ga.acc = a.acc;
         ga.pending = a.pending;
@@ -761,9 +764,9 @@ int atlas_flush_ready(atlas_layer_t *L, void *out, int64_t *n_flushed, void *hip
     u.d_in = d.d_in;
     u.d_out = d.d_out;
     u.K = L->K;
-    u.in_bf16 = d.in_dtype == ATLAS_DTYPE_BF16;
-    u.out_bf16 = d.out_dtype == ATLAS_DTYPE_BF16;
-    u.compute_bf16 = L->compute_bf16;
+    u.in_dt = d.in_dtype;
+    u.out_dt = d.out_dtype;
+    u.compute_dt = L->compute_dt;
     u.activation = d.activation;
     u.acc = static_cast<const float *>(L->acc.p);
     u.self_rows = L->emb_resident ? static_cast<const void *>(L->x_base) : L->self_rows.p;
@@ -789,7 +792,7 @@ int atlas_flush_ready(atlas_layer_t *L, void *out, int64_t *n_flushed, void *hip
         f.heads = d.heads;
         f.dh = d.d_out / d.heads;
         f.activation = d.activation;
-        f.out_bf16 = u.out_bf16;
+        f.out_dt = u.out_dt;
         f.n = L->n;
         HIP_TRY(launch_gat_finalize(f, s));
     } else if (L->tf) {
@@ -806,7 +809,7 @@ int atlas_flush_ready(atlas_layer_t *L, void *out, int64_t *n_flushed, void *hip
         f.out = out;
         f.d_out = d.d_out;
         f.activation = d.activation;
-        f.out_bf16 = u.out_bf16;
+        f.out_dt = u.out_dt;
         f.n = L->n;
         HIP_TRY(launch_sum_finalize(f, s));
     } else if (d.model == ATLAS_MODEL_SGC_HOP) {

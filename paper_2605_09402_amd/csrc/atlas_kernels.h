@@ -73,7 +73,7 @@ struct AggregateArgs {
     const void *emb;       // chunk rows; row u lives at (u - src_begin) * d
     int64_t src_begin, src_end;
     int d;                 // row width (elements)
-    int in_bf16;           // 1: rows are bf16, 0: fp32
+    int in_dt;             // storage of the rows: 0 fp32, 1 bf16, 2 IEEE half (the atlas_dtype values)
     int model;             // atlas_model
     float *acc;            // [N][d] fp32
     int32_t *pending;      // [N]
@@ -107,7 +107,7 @@ struct GroupedArgs {
     const void *emb;            // chunk rows; row u lives at (u - src_begin) * d
     int64_t src_begin;
     int d;
-    int in_bf16;
+    int in_dt;
     int model;
     float *acc;
     int32_t *pending;
@@ -148,9 +148,9 @@ hipError_t launch_gat_rescale(const GatState &g, float *acc, int d_out, int64_t 
 // GAT set-up and prepass.
 hipError_t launch_fill_i32(int32_t *p, int32_t value, int64_t count, hipStream_t s);
 int32_t gat_encoded_neg_inf();
-hipError_t launch_gat_fold_attention(const void *W, const void *a_src, const void *a_dst, int w_bf16, int d_in,
+hipError_t launch_gat_fold_attention(const void *W, const void *a_src, const void *a_dst, int w_dt, int d_in,
                                      int heads, int dh, float *wa, hipStream_t s);   // wa: [d_in][2*heads]
-hipError_t launch_gat_prepass(const void *emb, int in_bf16, int64_t src_begin, int64_t src_end, int d_in,
+hipError_t launch_gat_prepass(const void *emb, int in_dt, int64_t src_begin, int64_t src_end, int d_in,
                               const float *wa, int heads, float *el, float *er, hipStream_t s);
 // GAT flush: y = acc / l (+ bias, activation) for the ready rows.
 struct GatFinalizeArgs {
@@ -160,7 +160,7 @@ struct GatFinalizeArgs {
     int32_t *counters;
     const float *bias;
     void *out;
-    int d_out, heads, dh, activation, out_bf16;
+    int d_out, heads, dh, activation, out_dt;
     int64_t n;
 };
 hipError_t launch_gat_finalize(const GatFinalizeArgs &a, hipStream_t s);
@@ -182,10 +182,10 @@ hipError_t launch_init_pending(const int32_t *indeg, int32_t selfmsg, int64_t n,
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
 
 // Weight repack into MFMA B-fragment order (see k_update.hip).
-size_t packed_weight_bytes(int K, int d_out, int compute_bf16);
-hipError_t launch_pack_weights(const void *W, int w_bf16, int K, int d_out, int compute_bf16,
+size_t packed_weight_bytes(int K, int d_out, int compute_dt);
+hipError_t launch_pack_weights(const void *W, int w_dt, int K, int d_out, int compute_dt,
                                void *packed, hipStream_t s);
-hipError_t launch_to_f32(const void *src, int src_bf16, int64_t count, float *dst, hipStream_t s);
+hipError_t launch_to_f32(const void *src, int src_dt, int64_t count, float *dst, hipStream_t s);
 
 struct UpdateArgs {
     int model;                // 0 SAGE (own row || mean), 1 GCN (deg^-1/2 sum), 2 plain rows of `acc`,
@@ -193,7 +193,7 @@ struct UpdateArgs {
                               // dtype, d_in up to 1024; with identity_rows)
     float self_scale;         // GIN: 1 + eps
     int d_in, d_out, K;       // K = 2*d_in (SAGE) or d_in
-    int in_bf16, out_bf16, compute_bf16;
+    int in_dt, out_dt, compute_dt;
     int activation;
     const float *acc;         // [N][d_in]
     const void *self_rows;    // SAGE: [N][d_in] in in_dtype
@@ -226,7 +226,7 @@ struct SumFinalizeArgs {
     int32_t *counters;
     const float *bias;
     void *out;
-    int d_out, activation, out_bf16;
+    int d_out, activation, out_dt;
     int64_t n;
 };
 hipError_t launch_sum_finalize(const SumFinalizeArgs &a, hipStream_t s);

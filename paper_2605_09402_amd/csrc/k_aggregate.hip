@@ -15,6 +15,7 @@
 #include "atlas_kernels.h"
 
 #include <hip/hip_runtime.h>
+#include <type_traits>
 
 namespace atlas {
 namespace {
@@ -25,9 +26,13 @@ constexpr int kMaxHeads = 8;   // attention heads (checked at layer init)
 constexpr int kBlock = 256;
 
 __device__ __forceinline__ float load_as_f32(const float *p) { return *p; }
-__device__ __forceinline__ float load_as_f32(const uint16_t *p) {
+__device__ __forceinline__ float load_as_f32(const uint16_t *p) {   // bf16
     return __uint_as_float(static_cast<uint32_t>(*p) << 16);
 }
+__device__ __forceinline__ float load_as_f32(const _Float16 *p) { return static_cast<float>(*p); }
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 
 // Largest u in [lo, hi) with off[u] <= e.  Requires off[lo] <= e < off[hi].
 // All 64 lanes take part; the result is wave-uniform.
@@ -279,7 +284,23 @@ __global__ __launch_bounds__(kBlock) void k_self_message(int64_t b, int64_t e, i
 
 template <typename T, int VPL>
 __device__ __forceinline__ void load_row(const T *__restrict__ p, float (&x)[VPL]) {
-    if constexpr (sizeof(T) == 2) {
+    if constexpr (std::is_same<T, _Float16>::value) {   // IEEE half rows: one vector load, then conversions
+        if constexpr (VPL == 2) {
+            const f16x2_t w = *reinterpret_cast<const f16x2_t *>(p);
+            x[0] = static_cast<float>(w[0]); x[1] = static_cast<float>(w[1]);
+        } else if constexpr (VPL == 4) {
+            const f16x4_t w = *reinterpret_cast<const f16x4_t *>(p);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) x[i] = static_cast<float>(w[i]);
+        } else if constexpr (VPL == 8) {
+            const f16x8_t w = *reinterpret_cast<const f16x8_t *>(p);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) x[i] = static_cast<float>(w[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < VPL; ++i) x[i] = load_as_f32(p + i);
+        }
+    } else if constexpr (sizeof(T) == 2) {
         if constexpr (VPL == 2) {
             const uint32_t w = *reinterpret_cast<const uint32_t *>(p);
             x[0] = __uint_as_float(w << 16);
@@ -712,10 +733,9 @@ hipError_t launch_aggregate(const AggregateArgs &a, hipStream_t s) {
     if (a.d % kWave != 0) return hipErrorInvalidValue;
     const int grid = persistent_grid(8);
     // model 1 (GCN) scales the source row; every other model pushes it as is
-    if (a.model == 2) return a.in_bf16 ? hipErrorInvalidValue : launch_vpl<float, 2>(a, grid, s);
-    if (a.in_bf16) {
-        return a.model == 1 ? launch_vpl<uint16_t, 1>(a, grid, s) : launch_vpl<uint16_t, 0>(a, grid, s);
-    }
+    if (a.model == 2) return a.in_dt ? hipErrorInvalidValue : launch_vpl<float, 2>(a, grid, s);
+    if (a.in_dt == 2) return a.model == 1 ? launch_vpl<_Float16, 1>(a, grid, s) : launch_vpl<_Float16, 0>(a, grid, s);
+    if (a.in_dt == 1) return a.model == 1 ? launch_vpl<uint16_t, 1>(a, grid, s) : launch_vpl<uint16_t, 0>(a, grid, s);
     return a.model == 1 ? launch_vpl<float, 1>(a, grid, s) : launch_vpl<float, 0>(a, grid, s);
 }
 
@@ -755,12 +775,13 @@ hipError_t launch_aggregate_grouped(const GroupedArgs &a, hipStream_t s) {
     if (a.n_edges <= 0) return hipSuccess;
     const int grid = persistent_grid(8);
     if (a.model == 2) {
-        if (a.in_bf16 || a.gat.dh % (a.d / kWave) != 0) return hipErrorInvalidValue;
+        if (a.in_dt || a.gat.dh % (a.d / kWave) != 0) return hipErrorInvalidValue;
         return launch_grouped_vpl<float, 2>(a, grid, s);
     }
-    if (a.in_bf16) {
+    if (a.in_dt == 2)
+        return a.model == 1 ? launch_grouped_vpl<_Float16, 1>(a, grid, s) : launch_grouped_vpl<_Float16, 0>(a, grid, s);
+    if (a.in_dt == 1)
         return a.model == 1 ? launch_grouped_vpl<uint16_t, 1>(a, grid, s) : launch_grouped_vpl<uint16_t, 0>(a, grid, s);
-    }
     return a.model == 1 ? launch_grouped_vpl<float, 1>(a, grid, s) : launch_grouped_vpl<float, 0>(a, grid, s);
 }
 

@@ -30,15 +30,17 @@ __global__ __launch_bounds__(kBlock) void k_fill_i32(int32_t *p, int32_t value, 
     for (int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; i < count; i += stride) p[i] = value;
 }
 
-__device__ __forceinline__ float param_f32(const void *p, int bf16, int64_t i) {
-    return bf16 ? __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t *>(p)[i]) << 16)
-                : static_cast<const float *>(p)[i];
+// parameter i of an array stored as fp32 (0), bf16 (1) or IEEE half (2)
+__device__ __forceinline__ float param_f32(const void *p, int dt, int64_t i) {
+    if (dt == 2) return static_cast<float>(static_cast<const _Float16 *>(p)[i]);
+    return dt == 1 ? __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t *>(p)[i]) << 16)
+                   : static_cast<const float *>(p)[i];
 }
 
 // wa[c][h] = sum_j W[c][h*dh + j] a_src[h][j],  wa[c][heads + h] likewise with a_dst:
 // a . (W^T x) = (W a) . x, so the attention terms need no transformed row.
 __global__ __launch_bounds__(kBlock) void k_gat_fold_attention(const void *W, const void *a_src, const void *a_dst,
-                                                               int w_bf16, int d_in, int heads, int dh, float *wa) {
+                                                               int w_dt, int d_in, int heads, int dh, float *wa) {
     const int i = blockIdx.x * kBlock + threadIdx.x;
     if (i >= d_in * 2 * heads) return;
     const int c = i / (2 * heads);
@@ -47,7 +49,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_fold_attention(const void *W, co
     const void *av = k < heads ? a_src : a_dst;
     float s = 0.f;
     for (int j = 0; j < dh; ++j)
-        s += param_f32(W, w_bf16, static_cast<int64_t>(c) * heads * dh + h * dh + j) * param_f32(av, w_bf16, h * dh + j);
+        s += param_f32(W, w_dt, static_cast<int64_t>(c) * heads * dh + h * dh + j) * param_f32(av, w_dt, h * dh + j);
     wa[i] = s;
 }
 
@@ -210,7 +212,8 @@ __global__ __launch_bounds__(kBlock) void k_gat_finalize(GatFinalizeArgs a) {
             if (a.bias) y += a.bias[c];
             if (a.activation == 1) y = y > 0.f ? y : 0.f;
             else if (a.activation == 2) y = y > 0.f ? y : expm1f(y);
-            if (a.out_bf16) static_cast<uint16_t *>(a.out)[v * a.d_out + c] = f32_to_bf16_rne(y);
+            if (a.out_dt == 2) static_cast<_Float16 *>(a.out)[v * a.d_out + c] = static_cast<_Float16>(y);
+            else if (a.out_dt == 1) static_cast<uint16_t *>(a.out)[v * a.d_out + c] = f32_to_bf16_rne(y);
             else static_cast<float *>(a.out)[v * a.d_out + c] = y;
         }
     }
@@ -248,20 +251,20 @@ hipError_t launch_fill_i32(int32_t *p, int32_t value, int64_t count, hipStream_t
     return hipGetLastError();
 }
 
-hipError_t launch_gat_fold_attention(const void *W, const void *a_src, const void *a_dst, int w_bf16, int d_in,
+hipError_t launch_gat_fold_attention(const void *W, const void *a_src, const void *a_dst, int w_dt, int d_in,
                                      int heads, int dh, float *wa, hipStream_t s) {
     const int total = d_in * 2 * heads;
     hipLaunchKernelGGL(k_gat_fold_attention, dim3((total + kBlock - 1) / kBlock), dim3(kBlock), 0, s, W, a_src, a_dst,
-                       w_bf16, d_in, heads, dh, wa);
+                       w_dt, d_in, heads, dh, wa);
     return hipGetLastError();
 }
 
-hipError_t launch_gat_prepass(const void *emb, int in_bf16, int64_t src_begin, int64_t src_end, int d_in,
+hipError_t launch_gat_prepass(const void *emb, int in_dt, int64_t src_begin, int64_t src_end, int d_in,
                               const float *wa, int heads, float *el, float *er, hipStream_t s) {
     if (src_end <= src_begin) return hipSuccess;
     if (heads > 8) return hipErrorInvalidValue;
     const int grid = grid_for_waves(src_end - src_begin);
-    if (in_bf16)
+    if (in_dt)
         hipLaunchKernelGGL(k_gat_prepass<uint16_t>, dim3(grid), dim3(kBlock), 0, s,
                            static_cast<const uint16_t *>(emb), src_begin, src_end, d_in, wa, heads, el, er);
     else

@@ -62,10 +62,12 @@ __global__ __launch_bounds__(kBlock) void k_fill_zero(uint4 *p, size_t vecs) {
         p[i] = make_uint4(0, 0, 0, 0);
 }
 
-__global__ __launch_bounds__(kBlock) void k_to_f32(const void *src, int src_bf16, int64_t count, float *dst) {
+__global__ __launch_bounds__(kBlock) void k_to_f32(const void *src, int src_dt, int64_t count, float *dst) {
     const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
     if (i >= count) return;
-    if (src_bf16)
+    if (src_dt == 2)        // IEEE half
+        dst[i] = static_cast<float>(static_cast<const _Float16 *>(src)[i]);
+    else if (src_dt == 1)   // bf16
         dst[i] = __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t *>(src)[i]) << 16);
     else
         dst[i] = static_cast<const float *>(src)[i];
@@ -100,10 +102,10 @@ hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s) {
     return hipGetLastError();
 }
 
-hipError_t launch_to_f32(const void *src, int src_bf16, int64_t count, float *dst, hipStream_t s) {
+hipError_t launch_to_f32(const void *src, int src_dt, int64_t count, float *dst, hipStream_t s) {
     if (count == 0) return hipSuccess;
     const unsigned blocks = static_cast<unsigned>((count + kBlock - 1) / kBlock);
-    hipLaunchKernelGGL(k_to_f32, dim3(blocks), dim3(kBlock), 0, s, src, src_bf16, count, dst);
+    hipLaunchKernelGGL(k_to_f32, dim3(blocks), dim3(kBlock), 0, s, src, src_dt, count, dst);
     return hipGetLastError();
 }
 

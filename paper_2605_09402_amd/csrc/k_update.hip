@@ -26,6 +26,8 @@ constexpr int kBlock = 256;
 constexpr int kTileRows = 64;
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
@@ -38,23 +40,34 @@ __device__ __forceinline__ float bf16_to_f32(uint16_t h) {
     return __uint_as_float(static_cast<uint32_t>(h) << 16);
 }
 
-template <bool BF16C> struct Elem { using type = float; };
-template <> struct Elem<true> { using type = uint16_t; };
+__device__ __forceinline__ uint16_t f32_to_f16_bits(float f) {
+    const _Float16 h = static_cast<_Float16>(f);   // round to nearest even
+    return *reinterpret_cast<const uint16_t *>(&h);
+}
+__device__ __forceinline__ float f16_bits_to_f32(uint16_t b) {
+    return static_cast<float>(*reinterpret_cast<const _Float16 *>(&b));
+}
 
-template <bool BF16C> __device__ __forceinline__ typename Elem<BF16C>::type to_elem(float f);
-template <> __device__ __forceinline__ float to_elem<false>(float f) { return f; }
-template <> __device__ __forceinline__ uint16_t to_elem<true>(float f) { return f32_to_bf16_rne(f); }
+// Compute type CT of the contraction, the atlas_dtype of the layer's embeddings:
+// 0 fp32, 1 bf16, 2 IEEE half.  16-bit operands are held as raw bits.
+template <int CT> struct Elem { using type = uint16_t; };
+template <> struct Elem<0> { using type = float; };
 
-__host__ __device__ constexpr int lds_pad(bool bf16c) { return bf16c ? 8 : 1; }
+template <int CT> __device__ __forceinline__ typename Elem<CT>::type to_elem(float f);
+template <> __device__ __forceinline__ float to_elem<0>(float f) { return f; }
+template <> __device__ __forceinline__ uint16_t to_elem<1>(float f) { return f32_to_bf16_rne(f); }
+template <> __device__ __forceinline__ uint16_t to_elem<2>(float f) { return f32_to_f16_bits(f); }
+
+__host__ __device__ constexpr int lds_pad(bool sixteen_bit) { return sixteen_bit ? 8 : 1; }
 
 // Packed-W element index.  bf16: fragment (nb, kk) is 64 lanes x 8 values,
 // value t of lane l is W[kk*16 + (l/32)*8 + t][nb*32 + l%32].
 // fp32: fragment (nb, kk) is 64 lanes x 1 value, W[kk*2 + l/32][nb*32 + l%32].
-template <bool BF16C>
-__global__ __launch_bounds__(kBlock) void k_pack_weights(const void *W, int w_bf16, int K, int d_out,
-                                                         typename Elem<BF16C>::type *packed) {
-    constexpr int kStepK = BF16C ? 16 : 2;
-    constexpr int kPerLane = BF16C ? 8 : 1;
+template <int CT>
+__global__ __launch_bounds__(kBlock) void k_pack_weights(const void *W, int w_dt, int K, int d_out,
+                                                         typename Elem<CT>::type *packed) {
+    constexpr int kStepK = CT ? 16 : 2;
+    constexpr int kPerLane = CT ? 8 : 1;
     const int NB = (d_out + 31) / 32;
     const int KS = K / kStepK;
     const int64_t total = static_cast<int64_t>(NB) * KS * 64 * kPerLane;
@@ -70,9 +83,10 @@ __global__ __launch_bounds__(kBlock) void k_pack_weights(const void *W, int w_bf
     float w = 0.f;
     if (j < d_out) {
         const int64_t src = static_cast<int64_t>(k) * d_out + j;
-        w = w_bf16 ? bf16_to_f32(static_cast<const uint16_t *>(W)[src]) : static_cast<const float *>(W)[src];
+        if (w_dt == 2) w = f16_bits_to_f32(static_cast<const uint16_t *>(W)[src]);
+        else w = w_dt == 1 ? bf16_to_f32(static_cast<const uint16_t *>(W)[src]) : static_cast<const float *>(W)[src];
     }
-    packed[i] = to_elem<BF16C>(w);
+    packed[i] = to_elem<CT>(w);
 }
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -83,6 +97,33 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     const f32x2_t v = {lo, hi};
     const bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
     return *reinterpret_cast<const uint32_t *>(&b);
+}
+
+// two fp32 -> packed IEEE half pair (round to nearest even)
+__device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
+    const f32x2_t v = {lo, hi};
+    const f16x2_t b = __builtin_convertvector(v, f16x2_t);
+    return *reinterpret_cast<const uint32_t *>(&b);
+}
+// ... in the compute type CT (1 or 2), or by a run-time dtype code
+template <int CT>
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    if constexpr (CT == 2) return pack_f16x2(lo, hi);
+    else return pack_bf16x2(lo, hi);
+}
+__device__ __forceinline__ uint32_t pack2_dt(int dt, float lo, float hi) {
+    return dt == 2 ? pack_f16x2(lo, hi) : pack_bf16x2(lo, hi);
+}
+
+// per-lane operand of one matrix instruction and the instruction itself, by compute type
+template <int CT> struct Frag { using type = float; };
+template <> struct Frag<1> { using type = bf16x8_t; };
+template <> struct Frag<2> { using type = f16x8_t; };
+template <int CT>
+__device__ __forceinline__ f32x16_t mfma_block(typename Frag<CT>::type b, typename Frag<CT>::type a, f32x16_t c) {
+    if constexpr (CT == 1) return __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, c, 0, 0, 0);
+    else if constexpr (CT == 2) return __builtin_amdgcn_mfma_f32_32x32x16_f16(b, a, c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_32x32x2f32(b, a, c, 0, 0, 0);
 }
 
 __device__ __forceinline__ float apply_activation(float y, int act) {
@@ -119,13 +160,13 @@ __device__ __forceinline__ void store_block_row(const UpdateArgs &a, const f32x1
         }
     }
     const int limit = a.split > 0 ? a.split : a.d_out;
-    if (a.out_bf16) {
+    if (a.out_dt) {
         uint16_t *o = static_cast<uint16_t *>(outp) + out_row * cols + nbase;
 #pragma unroll
         for (int q = 0; q < 4; ++q)
             if (nbase + 8 * q < limit)
                 *reinterpret_cast<uint2 *>(o + 8 * q) =
-                    make_uint2(pack_bf16x2(y[4 * q], y[4 * q + 1]), pack_bf16x2(y[4 * q + 2], y[4 * q + 3]));
+                    make_uint2(pack2_dt(a.out_dt, y[4 * q], y[4 * q + 1]), pack2_dt(a.out_dt, y[4 * q + 2], y[4 * q + 3]));
     } else {
         float *o = static_cast<float *>(outp) + out_row * cols + nbase;
 #pragma unroll
@@ -151,20 +192,26 @@ __device__ __forceinline__ void load_bias16(const UpdateArgs &a, int nbase, floa
 // width and vertices without in-edges read a valid dummy location whose value
 // is dropped) and kept raw in registers, so all loads of the wave are in flight
 // together before the first is used.  d_in <= 512: at most 16 items.
-template <bool BF16C> struct OwnRaw4 { using type = float4; };
-template <> struct OwnRaw4<true> { using type = uint2; };
-__device__ __forceinline__ float4 own_to_f32(uint2 u) {   // four bf16 -> fp32
+template <int CT> struct OwnRaw4 { using type = float4; };
+template <> struct OwnRaw4<1> { using type = uint2; };
+template <> struct OwnRaw4<2> { using type = uint2; };
+template <int CT> __device__ __forceinline__ float4 own_to_f32(typename OwnRaw4<CT>::type u);
+template <> __device__ __forceinline__ float4 own_to_f32<2>(uint2 u) {   // four IEEE halves -> fp32
+    return make_float4(f16_bits_to_f32(static_cast<uint16_t>(u.x)), f16_bits_to_f32(static_cast<uint16_t>(u.x >> 16)),
+                       f16_bits_to_f32(static_cast<uint16_t>(u.y)), f16_bits_to_f32(static_cast<uint16_t>(u.y >> 16)));
+}
+template <> __device__ __forceinline__ float4 own_to_f32<1>(uint2 u) {   // four bf16 -> fp32
     return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u),
                        __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xffff0000u));
 }
-__device__ __forceinline__ float4 own_to_f32(float4 v) { return v; }
+template <> __device__ __forceinline__ float4 own_to_f32<0>(float4 v) { return v; }
 
-template <bool BF16C, int SEGS>
-__device__ __forceinline__ void gather_own_rows(const UpdateArgs &a, typename Elem<BF16C>::type *A, int stride,
+template <int CT, int SEGS>
+__device__ __forceinline__ void gather_own_rows(const UpdateArgs &a, typename Elem<CT>::type *A, int stride,
                                                 int w, int lane, int32_t idv);
 
-template <bool BF16C, int SEGS>
-__device__ __forceinline__ void gather_rows(const UpdateArgs &a, typename Elem<BF16C>::type *A, int stride,
+template <int CT, int SEGS>
+__device__ __forceinline__ void gather_rows(const UpdateArgs &a, typename Elem<CT>::type *A, int stride,
                                             int w, int lane, int32_t idv, int32_t rowv, float scalev,
                                             int has_aggv) {
     constexpr int kRows = kTileRows / 8;  // rows per wave
@@ -179,7 +226,7 @@ __device__ __forceinline__ void gather_rows(const UpdateArgs &a, typename Elem<B
 #pragma unroll
         for (int base = 0; base < nitems; base += kBatch) {
             float4 v[kBatch];
-            typename OwnRaw4<BF16C>::type o[kBatch];
+            typename OwnRaw4<CT>::type o[kBatch];
 #pragma unroll
             for (int i = 0; i < kBatch; ++i) {
                 const int rr = row_of(base + i), col = col_of(base + i);
@@ -189,7 +236,7 @@ __device__ __forceinline__ void gather_rows(const UpdateArgs &a, typename Elem<B
                 const int32_t ar = __builtin_amdgcn_readlane(rowv, rr);
                 v[i] = *reinterpret_cast<const float4 *>(a.acc + static_cast<int64_t>(fetch ? ar : 0) * d + cc);
                 const int64_t oo = static_cast<int64_t>(id >= 0 ? id : 0) * d + cc;
-                if constexpr (BF16C) o[i] = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(a.self_rows) + oo);
+                if constexpr (CT) o[i] = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(a.self_rows) + oo);
                 else o[i] = *reinterpret_cast<const float4 *>(static_cast<const float *>(a.self_rows) + oo);
             }
 #pragma unroll
@@ -197,14 +244,14 @@ __device__ __forceinline__ void gather_rows(const UpdateArgs &a, typename Elem<B
                 const int rr = row_of(base + i), col = col_of(base + i);
                 if (col >= d) continue;
                 const bool has_agg = __builtin_amdgcn_readlane(has_aggv, rr) != 0;
-                const float4 own = own_to_f32(o[i]);
+                const float4 own = own_to_f32<CT>(o[i]);
                 const float x0 = (has_agg ? v[i].x : 0.f) + a.self_scale * own.x;
                 const float x1 = (has_agg ? v[i].y : 0.f) + a.self_scale * own.y;
                 const float x2 = (has_agg ? v[i].z : 0.f) + a.self_scale * own.z;
                 const float x3 = (has_agg ? v[i].w : 0.f) + a.self_scale * own.w;
-                typename Elem<BF16C>::type *dst = A + (w * kRows + rr) * stride + col;
-                if constexpr (BF16C) {
-                    *reinterpret_cast<uint2 *>(dst) = make_uint2(pack_bf16x2(x0, x1), pack_bf16x2(x2, x3));
+                typename Elem<CT>::type *dst = A + (w * kRows + rr) * stride + col;
+                if constexpr (CT) {
+                    *reinterpret_cast<uint2 *>(dst) = make_uint2(pack2<CT>(x0, x1), pack2<CT>(x2, x3));
                 } else {
                     dst[0] = x0;
                     dst[1] = x1;
@@ -234,9 +281,9 @@ __device__ __forceinline__ void gather_rows(const UpdateArgs &a, typename Elem<B
             const float g = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(scalev), rr));
             // a vertex without in-edges never had its accumulator written: its aggregate is zero
             const bool has_agg = __builtin_amdgcn_readlane(has_aggv, rr) != 0;
-            typename Elem<BF16C>::type *dst = A + (w * kRows + rr) * stride + acc_base + col;
-            if constexpr (BF16C) {
-                const uint32_t lo = pack_bf16x2(v[i].x * g, v[i].y * g), hi = pack_bf16x2(v[i].z * g, v[i].w * g);
+            typename Elem<CT>::type *dst = A + (w * kRows + rr) * stride + acc_base + col;
+            if constexpr (CT) {
+                const uint32_t lo = pack2<CT>(v[i].x * g, v[i].y * g), hi = pack2<CT>(v[i].z * g, v[i].w * g);
                 *reinterpret_cast<uint2 *>(dst) = make_uint2(has_agg ? lo : 0u, has_agg ? hi : 0u);
             } else {
                 dst[0] = has_agg ? v[i].x * g : 0.f;
@@ -247,13 +294,13 @@ __device__ __forceinline__ void gather_rows(const UpdateArgs &a, typename Elem<B
         }
     }
     if (a.model != 0) return;
-    gather_own_rows<BF16C, SEGS>(a, A, stride, w, lane, idv);
+    gather_own_rows<CT, SEGS>(a, A, stride, w, lane, idv);
 }
 
 // Rows of `self_rows` (storage dtype) into columns [0, d_in) of the A tile: the
 // SAGE own rows, or the whole operand of a plain row transform (model 4).
-template <bool BF16C, int SEGS>
-__device__ __forceinline__ void gather_own_rows(const UpdateArgs &a, typename Elem<BF16C>::type *A, int stride,
+template <int CT, int SEGS>
+__device__ __forceinline__ void gather_own_rows(const UpdateArgs &a, typename Elem<CT>::type *A, int stride,
                                                 int w, int lane, int32_t idv) {
     constexpr int kRows = kTileRows / 8;
     constexpr int nitems = SEGS * kRows;
@@ -265,21 +312,21 @@ __device__ __forceinline__ void gather_own_rows(const UpdateArgs &a, typename El
     // rows past the list's end are stored as loaded and never used
 #pragma unroll
     for (int base = 0; base < nitems; base += kBatch) {
-        typename OwnRaw4<BF16C>::type v[kBatch];
+        typename OwnRaw4<CT>::type v[kBatch];
 #pragma unroll
         for (int i = 0; i < kBatch; ++i) {
             const int rr = row_of(base + i), col = col_of(base + i);
             const int32_t id = __builtin_amdgcn_readlane(idv, rr);
             const int64_t o = static_cast<int64_t>(id >= 0 ? id : 0) * d + (col < d ? col : 0);
-            if constexpr (BF16C) v[i] = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(a.self_rows) + o);
+            if constexpr (CT) v[i] = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(a.self_rows) + o);
             else v[i] = *reinterpret_cast<const float4 *>(static_cast<const float *>(a.self_rows) + o);
         }
 #pragma unroll
         for (int i = 0; i < kBatch; ++i) {
             const int rr = row_of(base + i), col = col_of(base + i);
             if (col >= d) continue;
-            typename Elem<BF16C>::type *dst = A + (w * kRows + rr) * stride + col;
-            if constexpr (BF16C) {
+            typename Elem<CT>::type *dst = A + (w * kRows + rr) * stride + col;
+            if constexpr (CT) {
                 *reinterpret_cast<uint2 *>(dst) = v[i];   // bf16 rows go in as loaded
             } else {
                 dst[0] = v[i].x;
@@ -301,20 +348,20 @@ __device__ __forceinline__ void gather_own_rows(const UpdateArgs &a, typename El
 // of the next four k-steps are fetched while the current four are multiplied.
 constexpr int kGenBlock = 512;
 
-template <bool BF16C, bool BOTH_MB>
+template <int CT, bool BOTH_MB>
 __global__ __launch_bounds__(kGenBlock, 4) void k_update(UpdateArgs a) {
-    using elem_t = typename Elem<BF16C>::type;
-    using frag_t = typename std::conditional<BF16C, bf16x8_t, float>::type;
+    using elem_t = typename Elem<CT>::type;
+    using frag_t = typename Frag<CT>::type;
     extern __shared__ __align__(16) unsigned char smem[];
     int32_t *ids = reinterpret_cast<int32_t *>(smem);                 // [64]
     elem_t *A = reinterpret_cast<elem_t *>(smem + kTileRows * sizeof(int32_t));
     const int K = a.K;
-    const int stride = K + lds_pad(BF16C);
+    const int stride = K + lds_pad(CT);
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
     const int NB = (a.d_out + 31) / 32;
-    constexpr int kStepK = BF16C ? 16 : 2;   // k per matrix instruction
-    constexpr int kFrag = BF16C ? 8 : 1;     // W / A elements per lane and instruction
+    constexpr int kStepK = CT ? 16 : 2;   // k per matrix instruction
+    constexpr int kFrag = CT ? 8 : 1;     // W / A elements per lane and instruction
     constexpr int kUnroll = 4;
     constexpr int kMB = BOTH_MB ? 2 : 1;
     constexpr int kRows = kTileRows / 8;
@@ -361,13 +408,13 @@ __global__ __launch_bounds__(kGenBlock, 4) void k_update(UpdateArgs a) {
         frag_t wcur[kUnroll];
         load_w(0, wcur);   // on its way while the rows are gathered
         if (a.model == 4) {   // plain rows in the storage dtype, up to 1024 wide
-            if (a.d_in > 512) gather_own_rows<BF16C, 4>(a, A, stride, w, lane, idv);
-            else if (a.d_in > 256) gather_own_rows<BF16C, 2>(a, A, stride, w, lane, idv);
-            else gather_own_rows<BF16C, 1>(a, A, stride, w, lane, idv);
+            if (a.d_in > 512) gather_own_rows<CT, 4>(a, A, stride, w, lane, idv);
+            else if (a.d_in > 256) gather_own_rows<CT, 2>(a, A, stride, w, lane, idv);
+            else gather_own_rows<CT, 1>(a, A, stride, w, lane, idv);
         } else if (a.d_in > 256) {
-            gather_rows<BF16C, 2>(a, A, stride, w, lane, idv, rowv, scalev, has_aggv);
+            gather_rows<CT, 2>(a, A, stride, w, lane, idv, rowv, scalev, has_aggv);
         } else {
-            gather_rows<BF16C, 1>(a, A, stride, w, lane, idv, rowv, scalev, has_aggv);
+            gather_rows<CT, 1>(a, A, stride, w, lane, idv, rowv, scalev, has_aggv);
         }
         __syncthreads();
 
@@ -390,8 +437,7 @@ __global__ __launch_bounds__(kGenBlock, 4) void k_update(UpdateArgs a) {
 #pragma unroll
                 for (int m = 0; m < kMB; ++m) {
                     const frag_t av = *reinterpret_cast<const frag_t *>(A + a_off + m * 32 * stride + kk * kStepK);
-                    if constexpr (BF16C) c[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wcur[u], av, c[m], 0, 0, 0);
-                    else c[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(wcur[u], av, c[m], 0, 0, 0);
+                    c[m] = mfma_block<CT>(wcur[u], av, c[m]);
                 }
             }
 #pragma unroll
@@ -429,10 +475,10 @@ constexpr int kPipeBlock = 512;
 constexpr int kPipeRows = kTileRows / (kPipeBlock / 64);  // rows staged per wave = 8
 constexpr int kPipeIters = kPipeRows / 2;                 // two rows per load instruction
 
-template <bool BF16C>
+template <int CT>
 struct RowRegs {
     float4 acc[kPipeIters];
-    typename OwnRaw4<BF16C>::type own[kPipeIters];
+    typename OwnRaw4<CT>::type own[kPipeIters];
 };
 
 template <int CTRL>
@@ -455,9 +501,9 @@ __device__ __forceinline__ int32_t quad_bcast(int32_t v, int i) {
 // read row 0 and are dropped when the tile is stored; so do the accumulator
 // loads of vertices without in-edges (nothing was ever added to their rows,
 // and the one shared address stays in cache).
-template <bool BF16C, int OWN>
+template <int CT, int OWN>
 __device__ __forceinline__ void pipe_issue_rows(const UpdateArgs &a, int32_t idv, int32_t degv, int32_t slotv,
-                                                int lane, RowRegs<BF16C> &r) {
+                                                int lane, RowRegs<CT> &r) {
     const int d = a.d_in;
     const int c4 = (lane & 31) * 4;
     const int col = c4 < d ? c4 : 0;
@@ -470,7 +516,7 @@ __device__ __forceinline__ void pipe_issue_rows(const UpdateArgs &a, int32_t idv
         r.acc[i] = *reinterpret_cast<const float4 *>(a.acc + static_cast<int64_t>(arow) * d + col);
         if constexpr (OWN != 0) {
             const int64_t o = static_cast<int64_t>(row) * d + col;
-            if constexpr (BF16C) r.own[i] = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(a.self_rows) + o);
+            if constexpr (CT) r.own[i] = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(a.self_rows) + o);
             else r.own[i] = *reinterpret_cast<const float4 *>(static_cast<const float *>(a.self_rows) + o);
         }
     }
@@ -479,37 +525,37 @@ __device__ __forceinline__ void pipe_issue_rows(const UpdateArgs &a, int32_t idv
 // Normalise and convert the rows loaded by pipe_issue_rows and store them into
 // the A tile.  Rows past the end of the ready list are stored as they came:
 // a row of A only feeds the same row of the product, which is never written.
-template <bool BF16C, int OWN>
-__device__ __forceinline__ void pipe_store_rows(const UpdateArgs &a, typename Elem<BF16C>::type *A, int stride,
-                                                int w, int lane, const RowRegs<BF16C> &r, int32_t degv) {
+template <int CT, int OWN>
+__device__ __forceinline__ void pipe_store_rows(const UpdateArgs &a, typename Elem<CT>::type *A, int stride,
+                                                int w, int lane, const RowRegs<CT> &r, int32_t degv) {
     const int d = a.d_in;
     const int c4 = (lane & 31) * 4;
     const float fd = static_cast<float>(degv > 0 ? degv : 1);
     // SAGE: mean = sum * (1/deg); GCN: deg^-1/2; plain linear map: 1
     const float scalev = a.model == 0 ? 1.0f / fd : (a.model == 1 ? 1.0f / sqrtf(fd) : 1.0f);
     if (c4 >= d) return;
-    typename Elem<BF16C>::type *row0 = A + (w * kPipeRows + (lane >> 5)) * stride + c4 + (OWN == 1 ? d : 0);
+    typename Elem<CT>::type *row0 = A + (w * kPipeRows + (lane >> 5)) * stride + c4 + (OWN == 1 ? d : 0);
 #pragma unroll
     for (int i = 0; i < kPipeIters; ++i) {
         const float g = __uint_as_float(static_cast<uint32_t>(quad_bcast(static_cast<int32_t>(__float_as_uint(scalev)), i)));
         // a vertex without in-edges never had its accumulator written: its aggregate is zero
         const bool has_agg = quad_bcast(degv, i) > 0;
-        typename Elem<BF16C>::type *row = row0 + 2 * i * stride;
+        typename Elem<CT>::type *row = row0 + 2 * i * stride;
         float4 v = r.acc[i];
         v.x *= g;
         v.y *= g;
         v.z *= g;
         v.w *= g;
         if constexpr (OWN == 2) {   // GIN: sum + self_scale * own row, rounded once
-            const float4 own = own_to_f32(r.own[i]);
+            const float4 own = own_to_f32<CT>(r.own[i]);
             v.x = (has_agg ? v.x : 0.f) + a.self_scale * own.x;
             v.y = (has_agg ? v.y : 0.f) + a.self_scale * own.y;
             v.z = (has_agg ? v.z : 0.f) + a.self_scale * own.z;
             v.w = (has_agg ? v.w : 0.f) + a.self_scale * own.w;
         }
         const bool keep = OWN == 2 || has_agg;
-        if constexpr (BF16C) {
-            const uint32_t lo = pack_bf16x2(v.x, v.y), hi = pack_bf16x2(v.z, v.w);
+        if constexpr (CT) {
+            const uint32_t lo = pack2<CT>(v.x, v.y), hi = pack2<CT>(v.z, v.w);
             *reinterpret_cast<uint2 *>(row) = make_uint2(keep ? lo : 0u, keep ? hi : 0u);
             // bf16 own rows go to LDS as they were loaded; the aggregate is rounded once
             if constexpr (OWN == 1) *reinterpret_cast<uint2 *>(row - d) = r.own[i];
@@ -532,23 +578,24 @@ __device__ __forceinline__ void pipe_store_rows(const UpdateArgs &a, typename El
 // KS > 0: compile-time trip count, fully unrolled (immediate LDS offsets);
 // KS == 0: run-time trip count `ks`, a multiple of 4, in groups of four whose
 // LDS reads are issued one group ahead of the matrix instructions.
-template <bool BF16C, int KS>
-__device__ __forceinline__ void contract_block(const typename Elem<BF16C>::type *arow,
-                                               const typename Elem<BF16C>::type *wfrag, int ks, f32x16_t &c) {
-    if constexpr (BF16C && KS > 0) {
+template <int CT, int KS>
+__device__ __forceinline__ void contract_block(const typename Elem<CT>::type *arow,
+                                               const typename Elem<CT>::type *wfrag, int ks, f32x16_t &c) {
+    if constexpr (CT && KS > 0) {
 #pragma unroll
         for (int kk = 0; kk < KS; ++kk) {
-            const bf16x8_t av = *reinterpret_cast<const bf16x8_t *>(arow + kk * 16);
-            const bf16x8_t bv = *reinterpret_cast<const bf16x8_t *>(wfrag + kk * 64 * 8);
-            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv, av, c, 0, 0, 0);
+            using frag16_t = typename Frag<CT>::type;
+            const frag16_t av = *reinterpret_cast<const frag16_t *>(arow + kk * 16);
+            const frag16_t bv = *reinterpret_cast<const frag16_t *>(wfrag + kk * 64 * 8);
+            c = mfma_block<CT>(bv, av, c);
         }
     } else {
         constexpr int kUnroll = 4;
-        using frag_t = typename std::conditional<BF16C, bf16x8_t, float>::type;
+        using frag_t = typename Frag<CT>::type;
         auto load = [&](int kk, frag_t &af, frag_t &bf) {
-            if constexpr (BF16C) {
-                af = *reinterpret_cast<const bf16x8_t *>(arow + kk * 16);
-                bf = *reinterpret_cast<const bf16x8_t *>(wfrag + static_cast<size_t>(kk) * 64 * 8);
+            if constexpr (CT) {
+                af = *reinterpret_cast<const frag_t *>(arow + kk * 16);
+                bf = *reinterpret_cast<const frag_t *>(wfrag + static_cast<size_t>(kk) * 64 * 8);
             } else {
                 af = arow[kk * 2];
                 bf = wfrag[static_cast<size_t>(kk) * 64];
@@ -564,8 +611,7 @@ __device__ __forceinline__ void contract_block(const typename Elem<BF16C>::type 
             for (int u = 0; u < kUnroll; ++u) load(nxt + u, an[u], bn[u]);
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
-                if constexpr (BF16C) c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv[u], av[u], c, 0, 0, 0);
-                else c = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[u], av[u], c, 0, 0, 0);
+                c = mfma_block<CT>(bv[u], av[u], c);
             }
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
@@ -576,14 +622,14 @@ __device__ __forceinline__ void contract_block(const typename Elem<BF16C>::type 
     }
 }
 
-template <bool BF16C, int PPW, int OWN>
+template <int CT, int PPW, int OWN>
 __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
-    using elem_t = typename Elem<BF16C>::type;
+    using elem_t = typename Elem<CT>::type;
     extern __shared__ __align__(16) unsigned char smem[];
     const int K = a.K;
-    const int stride = K + lds_pad(BF16C);
+    const int stride = K + lds_pad(CT);
     const int NB = (a.d_out + 31) / 32;
-    constexpr int kStepK = BF16C ? 16 : 2;
+    constexpr int kStepK = CT ? 16 : 2;
     const int KS = K / kStepK;
     const size_t w_elems = static_cast<size_t>(NB) * 32 * K;
     const size_t a_elems = static_cast<size_t>(kTileRows) * stride;
@@ -632,7 +678,7 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
         load_bias16(a, nb * 32 + 4 * (lane >> 5), b16);
 #pragma unroll
         for (int r = 0; r < 16; ++r) bj[i][r] = b16[r];
-        if constexpr (BF16C) {
+        if constexpr (CT) {
             a_off[i] = (mb * 32 + (lane & 31)) * stride + (lane >> 5) * 8;
             wfrag[i] = Wl + (static_cast<size_t>(nb) * KS * 64 + lane) * 8;
         } else {
@@ -652,15 +698,15 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
     int32_t id_b = load_ids(tile + 3 * G);
     int32_t deg0 = load_deg(id0), deg1 = load_deg(id1), deg_a = load_deg(id_a);
     int32_t slot_a = load_slot(id_a);
-    RowRegs<BF16C> r0, r1;
-    pipe_issue_rows<BF16C, OWN>(a, id0, deg0, load_slot(id0), lane, r0);
+    RowRegs<CT> r0, r1;
+    pipe_issue_rows<CT, OWN>(a, id0, deg0, load_slot(id0), lane, r0);
     __builtin_amdgcn_sched_barrier(0);   // keep the two sets' loads in this order, as in the loop
-    pipe_issue_rows<BF16C, OWN>(a, id1, deg1, load_slot(id1), lane, r1);
+    pipe_issue_rows<CT, OWN>(a, id1, deg1, load_slot(id1), lane, r1);
 
-    auto step = [&](RowRegs<BF16C> &regs, int32_t &idv, int32_t &degv, int buf) {
+    auto step = [&](RowRegs<CT> &regs, int32_t &idv, int32_t &degv, int buf) {
         elem_t *A = A0 + buf * a_elems;
         int32_t *tids = ids + buf * kTileRows;
-        pipe_store_rows<BF16C, OWN>(a, A, stride, w, lane, regs, degv);
+        pipe_store_rows<CT, OWN>(a, A, stride, w, lane, regs, degv);
         if ((lane & 31) < 4) tids[w * kPipeRows + my_row] = idv;
         __syncthreads();
         idv = id_a;
@@ -670,22 +716,22 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
         deg_a = load_deg(id_a);
         slot_a = load_slot(id_a);
         id_b = load_ids(tile + 4 * G);
-        pipe_issue_rows<BF16C, OWN>(a, idv, degv, slotv, lane, regs);
+        pipe_issue_rows<CT, OWN>(a, idv, degv, slotv, lane, regs);
 
         f32x16_t c[PPW];
 #pragma unroll
         for (int i = 0; i < PPW; ++i) {
             c[i] = bj[i];
             const elem_t *arow = A + a_off[i];
-            if constexpr (BF16C) {
+            if constexpr (CT) {
                 switch (KS) {
-                    case 4: contract_block<true, 4>(arow, wfrag[i], KS, c[i]); break;
-                    case 8: contract_block<true, 8>(arow, wfrag[i], KS, c[i]); break;
-                    case 16: contract_block<true, 16>(arow, wfrag[i], KS, c[i]); break;
-                    default: contract_block<true, 0>(arow, wfrag[i], KS, c[i]); break;
+                    case 4: contract_block<CT, 4>(arow, wfrag[i], KS, c[i]); break;
+                    case 8: contract_block<CT, 8>(arow, wfrag[i], KS, c[i]); break;
+                    case 16: contract_block<CT, 16>(arow, wfrag[i], KS, c[i]); break;
+                    default: contract_block<CT, 0>(arow, wfrag[i], KS, c[i]); break;
                 }
             } else {
-                contract_block<false, 0>(arow, wfrag[i], KS, c[i]);
+                contract_block<0, 0>(arow, wfrag[i], KS, c[i]);
             }
         }
 #pragma unroll
@@ -717,32 +763,32 @@ size_t pipelined_lds_bytes(int K, int d_out, bool bf16c) {
            2 * static_cast<size_t>(kTileRows) * (K + lds_pad(bf16c)) * es;
 }
 
-template <bool BF16C, int PPW, int OWN>
+template <int CT, int PPW, int OWN>
 hipError_t launch_pipelined_t(const UpdateArgs &a, int grid, hipStream_t s) {
-    const size_t lds = pipelined_lds_bytes(a.K, a.d_out, BF16C);
+    const size_t lds = pipelined_lds_bytes(a.K, a.d_out, CT);
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_update_pipelined<BF16C, PPW, OWN>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_update_pipelined<CT, PPW, OWN>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL((k_update_pipelined<BF16C, PPW, OWN>), dim3(grid), dim3(kPipeBlock), lds, s, a);
+    hipLaunchKernelGGL((k_update_pipelined<CT, PPW, OWN>), dim3(grid), dim3(kPipeBlock), lds, s, a);
     return hipGetLastError();
 }
 
-template <bool BF16C, int OWN>
+template <int CT, int OWN>
 hipError_t launch_pipelined_o(const UpdateArgs &a, int grid, hipStream_t s) {
     const int NB = (a.d_out + 31) / 32;
-    return 2 * NB <= 8 ? launch_pipelined_t<BF16C, 1, OWN>(a, grid, s) : launch_pipelined_t<BF16C, 2, OWN>(a, grid, s);
+    return 2 * NB <= 8 ? launch_pipelined_t<CT, 1, OWN>(a, grid, s) : launch_pipelined_t<CT, 2, OWN>(a, grid, s);
 }
 
 // own row: concatenated (SAGE), added (GIN) or unused
-template <bool BF16C>
+template <int CT>
 hipError_t launch_pipelined_c(const UpdateArgs &a, int grid, hipStream_t s) {
-    if (a.model == 0) return launch_pipelined_o<BF16C, 1>(a, grid, s);
-    if (a.model == 3) return launch_pipelined_o<BF16C, 2>(a, grid, s);
-    return launch_pipelined_o<BF16C, 0>(a, grid, s);
+    if (a.model == 0) return launch_pipelined_o<CT, 1>(a, grid, s);
+    if (a.model == 3) return launch_pipelined_o<CT, 2>(a, grid, s);
+    return launch_pipelined_o<CT, 0>(a, grid, s);
 }
 
 // Transform-first layers: one wave per ready row, four columns per lane and round.
@@ -776,9 +822,9 @@ __global__ __launch_bounds__(kBlock) void k_sum_finalize(SumFinalizeArgs a) {
                 if (a.activation == 1) y[k] = fmaxf(y[k], 0.f);
                 else if (a.activation == 2) y[k] = y[k] > 0.f ? y[k] : expm1f(y[k]);
             }
-            if (a.out_bf16)
+            if (a.out_dt)
                 *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(a.out) + v * d + c) =
-                    make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
+                    make_uint2(pack2_dt(a.out_dt, y[0], y[1]), pack2_dt(a.out_dt, y[2], y[3]));
             else
                 *reinterpret_cast<float4 *>(static_cast<float *>(a.out) + v * d + c) = make_float4(y[0], y[1], y[2], y[3]);
         }
@@ -801,9 +847,9 @@ __global__ __launch_bounds__(kBlock) void k_scale_rows(UpdateArgs a) {
             float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
             if (deg > 0)   // never written otherwise
                 x = *reinterpret_cast<const float4 *>(a.acc + (a.slot_of ? static_cast<int64_t>(a.slot_of[v]) : v) * d + c);
-            if (a.out_bf16)
+            if (a.out_dt)
                 *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(a.out) + v * d + c) =
-                    make_uint2(pack_bf16x2(x.x * g, x.y * g), pack_bf16x2(x.z * g, x.w * g));
+                    make_uint2(pack2_dt(a.out_dt, x.x * g, x.y * g), pack2_dt(a.out_dt, x.z * g, x.w * g));
             else
                 *reinterpret_cast<float4 *>(static_cast<float *>(a.out) + v * d + c) =
                     make_float4(x.x * g, x.y * g, x.z * g, x.w * g);
@@ -823,63 +869,67 @@ size_t update_lds_bytes(int K, bool bf16c) {
            static_cast<size_t>(kTileRows) * (K + lds_pad(bf16c)) * (bf16c ? 2 : 4);
 }
 
-template <bool BF16C, bool BOTH_MB>
+template <int CT, bool BOTH_MB>
 hipError_t launch_update_t(const UpdateArgs &a, int grid, hipStream_t s) {
-    const size_t lds = update_lds_bytes(a.K, BF16C);
+    const size_t lds = update_lds_bytes(a.K, CT);
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_update<BF16C, BOTH_MB>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_update<CT, BOTH_MB>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL((k_update<BF16C, BOTH_MB>), dim3(grid), dim3(kGenBlock), lds, s, a);
+    hipLaunchKernelGGL((k_update<CT, BOTH_MB>), dim3(grid), dim3(kGenBlock), lds, s, a);
     return hipGetLastError();
 }
 
-template <bool BF16C>
+template <int CT>
 hipError_t launch_update_c(const UpdateArgs &a, int grid, hipStream_t s) {
     const int NB = (a.d_out + 31) / 32;
     if (NB > 8 || a.d_in > (a.model == 4 ? 1024 : 512)) return hipErrorInvalidValue;
-    return NB > 4 ? launch_update_t<BF16C, true>(a, grid, s) : launch_update_t<BF16C, false>(a, grid, s);
+    return NB > 4 ? launch_update_t<CT, true>(a, grid, s) : launch_update_t<CT, false>(a, grid, s);
 }
 
 }  // namespace
 
-size_t packed_weight_bytes(int K, int d_out, int compute_bf16) {
+size_t packed_weight_bytes(int K, int d_out, int compute_dt) {
     const int NB = (d_out + 31) / 32;
-    return static_cast<size_t>(NB) * 32 * K * (compute_bf16 ? 2 : 4);
+    return static_cast<size_t>(NB) * 32 * K * (compute_dt ? 2 : 4);
 }
 
-hipError_t launch_pack_weights(const void *W, int w_bf16, int K, int d_out, int compute_bf16,
+hipError_t launch_pack_weights(const void *W, int w_dt, int K, int d_out, int compute_dt,
                                void *packed, hipStream_t s) {
     const int NB = (d_out + 31) / 32;
     const int64_t total = static_cast<int64_t>(NB) * 32 * K;
     const unsigned blocks = static_cast<unsigned>((total + kBlock - 1) / kBlock);
-    if (compute_bf16)
-        hipLaunchKernelGGL(k_pack_weights<true>, dim3(blocks), dim3(kBlock), 0, s, W, w_bf16, K, d_out,
+    if (compute_dt == 2)
+        hipLaunchKernelGGL(k_pack_weights<2>, dim3(blocks), dim3(kBlock), 0, s, W, w_dt, K, d_out,
+                           static_cast<uint16_t *>(packed));
+    else if (compute_dt == 1)
+        hipLaunchKernelGGL(k_pack_weights<1>, dim3(blocks), dim3(kBlock), 0, s, W, w_dt, K, d_out,
                            static_cast<uint16_t *>(packed));
     else
-        hipLaunchKernelGGL(k_pack_weights<false>, dim3(blocks), dim3(kBlock), 0, s, W, w_bf16, K, d_out,
+        hipLaunchKernelGGL(k_pack_weights<0>, dim3(blocks), dim3(kBlock), 0, s, W, w_dt, K, d_out,
                            static_cast<float *>(packed));
     return hipGetLastError();
 }
 
 hipError_t launch_update(const UpdateArgs &a, hipStream_t s) {
-    if (update_lds_bytes(a.K, a.compute_bf16 != 0) > 160 * 1024) return hipErrorInvalidValue;
+    if (update_lds_bytes(a.K, a.compute_dt != 0) > 160 * 1024) return hipErrorInvalidValue;
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess)
         (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (cus <= 0) cus = 256;
-    if (a.model != 4 && a.d_in <= 128 && pipelined_lds_bytes(a.K, a.d_out, a.compute_bf16 != 0) <= 160 * 1024) {
+    if (a.model != 4 && a.d_in <= 128 && pipelined_lds_bytes(a.K, a.d_out, a.compute_dt != 0) <= 160 * 1024) {
         int64_t grid = cus;
         const int64_t max_tiles = (a.n + kTileRows - 1) / kTileRows;
         if (grid > max_tiles) grid = max_tiles;
         if (grid < 1) grid = 1;
-        return a.compute_bf16 ? launch_pipelined_c<true>(a, static_cast<int>(grid), s)
-                              : launch_pipelined_c<false>(a, static_cast<int>(grid), s);
+        if (a.compute_dt == 2) return launch_pipelined_c<2>(a, static_cast<int>(grid), s);
+        return a.compute_dt == 1 ? launch_pipelined_c<1>(a, static_cast<int>(grid), s)
+                                 : launch_pipelined_c<0>(a, static_cast<int>(grid), s);
     }
-    const size_t lds = update_lds_bytes(a.K, a.compute_bf16 != 0);
+    const size_t lds = update_lds_bytes(a.K, a.compute_dt != 0);
     int per_cu = static_cast<int>((160 * 1024) / lds);
     if (per_cu < 1) per_cu = 1;
     if (per_cu > 4) per_cu = 4;   // 8 waves per workgroup, 32 per CU
@@ -887,8 +937,9 @@ hipError_t launch_update(const UpdateArgs &a, hipStream_t s) {
     const int64_t max_tiles = (a.n + kTileRows - 1) / kTileRows;
     if (grid > max_tiles) grid = max_tiles;
     if (grid < 1) grid = 1;
-    return a.compute_bf16 ? launch_update_c<true>(a, static_cast<int>(grid), s)
-                          : launch_update_c<false>(a, static_cast<int>(grid), s);
+    if (a.compute_dt == 2) return launch_update_c<2>(a, static_cast<int>(grid), s);
+    return a.compute_dt == 1 ? launch_update_c<1>(a, static_cast<int>(grid), s)
+                             : launch_update_c<0>(a, static_cast<int>(grid), s);
 }
 
 hipError_t launch_sum_finalize(const SumFinalizeArgs &a, hipStream_t s) {

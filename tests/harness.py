@@ -16,7 +16,17 @@ MODEL_ID = {"sage": atlas.MODEL_SAGE_MEAN, "gcn": atlas.MODEL_GCN_SYM, "gat": at
             "gin": atlas.MODEL_GIN, "sgc": atlas.MODEL_GCN_SYM}   # "sgc": hops without weights, then one GCN layer
 ORACLE_ACT = {"none": 0, "relu": 1, "elu": 2}
 TOL_F32 = 1e-4   # maximum row-normalised relative error, fp32 outputs
-TOL_BF16 = 2e-2  # the same where outputs are stored in bf16
+TOL_BF16 = 2e-2  # the same where outputs are stored in bf16 (5 units of its 2^-8 spacing)
+TOL_F16 = 2.5e-3  # IEEE half outputs: the same 5 units of its 2^-11 spacing (one for the stored output, the
+                  # rest for the half-precision operands of the contraction)
+
+
+def tol_of(store: torch.dtype) -> float:
+    return {torch.bfloat16: TOL_BF16, torch.float16: TOL_F16}.get(store, TOL_F32)
+
+
+def fmt_of(oracle, store: torch.dtype) -> int:
+    return {torch.bfloat16: oracle.FMT_BF16, torch.float16: oracle.FMT_F16}.get(store, oracle.FMT_F32)
 
 
 @dataclass
@@ -67,7 +77,7 @@ def row_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
 
 
 def oracle_outputs(oracle, case: Case) -> List[np.ndarray]:
-    fmt = oracle.FMT_BF16 if case.store == torch.bfloat16 else oracle.FMT_F32
+    fmt = fmt_of(oracle, case.store)
     return oracle.run_model(case.model, case.off.numpy(), case.col.numpy(), case.X.float().numpy(), case.layers,
                             ORACLE_ACT[case.act], fmt, case.slope, case.eps)
 
@@ -82,7 +92,7 @@ class GpuRun:
 
 
 def _dt(store: torch.dtype) -> int:
-    return atlas.DTYPE_BF16 if store == torch.bfloat16 else atlas.DTYPE_F32
+    return {torch.bfloat16: atlas.DTYPE_BF16, torch.float16: atlas.DTYPE_F16}.get(store, atlas.DTYPE_F32)
 
 
 def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, flush_every: int = 1,
@@ -223,7 +233,7 @@ def check_integers(oracle, case: Case, run: GpuRun, layer: int = 0):
 
 def check_outputs(oracle, case: Case, run: GpuRun):
     refs = oracle_outputs(oracle, case)
-    tol = TOL_BF16 if case.store == torch.bfloat16 else TOL_F32
+    tol = tol_of(case.store)
     errs = []
     for li, (got, ref) in enumerate(zip(run.outputs, refs)):
         g = got.float().cpu().numpy().astype(np.float64)
@@ -317,12 +327,12 @@ def sampled_layer1_check(oracle, wl, out, indeg_dev, n_random: int = 1 << 14, n_
     assert np.array_equal(indeg_dev[pick].cpu().numpy().astype(np.int64), np.diff(in_off_h)), "in-degree of the sample"
     p = wl.layers[0]
     act = ORACLE_ACT[wl.act] if len(wl.layers) > 1 else 0
-    fmt = oracle.FMT_BF16 if wl.store == torch.bfloat16 else oracle.FMT_F32
+    fmt = fmt_of(oracle, wl.store)
     Y = oracle.run_layer(wl.model, il, indeg_dev[need].cpu().numpy().astype(np.int64), Xs, p, act, fmt)
     got = out[pick].float().cpu().numpy().astype(np.float64)
     assert np.isfinite(got).all()
     err = row_rel_err(got, Y)
-    tol = TOL_BF16 if wl.store == torch.bfloat16 else TOL_F32
+    tol = tol_of(wl.store)
     assert err <= tol, "sampled layer-1 error %.3e > %.1e" % (err, tol)
     return err, int(pick.numel()), int(in_src.numel())
 

@@ -194,3 +194,32 @@ def test_transform_first(oracle, H, model, store, dims, plan):
     H.check_integers(oracle, case, run, layer=0)
     H.check_integers(oracle, case, run, layer=1)
     print("transform first", model, dims, H.check_outputs(oracle, case, run))
+
+
+@pytest.mark.parametrize("plan", [False, True], ids=["csr_stream", "planned"])
+@pytest.mark.parametrize("model,dims,tf", [
+    ("sage", [128, 128, 64], False),      # pipelined update kernel, half-precision MFMA
+    ("sage", [256, 256, 128], False),     # generic update kernel
+    ("gcn", [128, 64, 64], False),
+    ("sgc", [128, 128, 128], False),
+    ("sage", [1024, 128, 64], True),      # the paper's widest FP16 feature set: 1024 columns (Sec. 4.1)
+    ("gin", [256, 64, 64], True),
+])
+def test_half_precision_storage(oracle, H, model, dims, tf, plan):
+    """Embeddings, weights and outputs stored in IEEE half (the format of the
+    paper's largest feature set), fp32 sums, half operands in the contraction;
+    tolerance 2.5e-3 (five units of half's spacing).  R-MAT scale 12."""
+    g = gen.rmat_graph(SEED + 10, 12, 16, random_ids=True, self_loops=(model in ("gcn", "sgc")))
+    case = H.make_case(model, g, SEED + 10, dims, 400, store=torch.float16, eps=0.25)
+    run = H.run_gpu(case, snapshots=True, plan=plan, planned_only=plan, transform_first=tf)
+    H.check_integers(oracle, case, run, layer=0)
+    print("half", model, dims, H.check_outputs(oracle, case, run))
+
+
+def test_half_precision_gin_needs_transform_first(H):
+    import paper_2605_09402_amd as atlas
+    g = gen.rmat_graph(SEED + 10, 10, 8)
+    case = H.make_case("gin", g, SEED + 10, [64, 64], 256, store=torch.float16)
+    with pytest.raises(atlas.AtlasError) as ei:
+        H.run_gpu(case)
+    assert ei.value.status == atlas.E_BAD_DIMS
