@@ -84,6 +84,9 @@ def lib() -> ctypes.CDLL:
         if not os.path.exists(LIB_PATH):
             raise ImportError("libatlas.so is missing: run `python -m paper_2605_09402_amd.build` "
                               "(hipcc, gfx950) first; there is no fallback path")
+        # torch ships its own HIP runtime: load it first so that the library binds to the runtime the
+        # caller's tensors and streams live in (two runtimes in one process do not share devices)
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
         L.atlas_layer_init.argtypes = [ctypes.POINTER(atlas_graph_t), ctypes.POINTER(atlas_dims_t),
