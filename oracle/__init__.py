@@ -239,6 +239,33 @@ def message_span(il: "InLists", selfmsg: bool = False) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------
+# neighbourhood sampling by disabling edges (Sec. 3.9)
+# --------------------------------------------------------------------------
+
+def sample_in_edges(off: np.ndarray, col: np.ndarray, edge_key: np.ndarray, fanout: int):
+    """The preprocessing pass the paper sketches for sampled inference (Sec.
+    3.9): every destination keeps at most `fanout` of its in-edges and the rest
+    are disabled.  Which ones is decided by the caller's random key per edge:
+    the `fanout` smallest keys of each destination, ties by the edge's position
+    in the CSR.  Returns the CSR (by source, original edge order) of the kept
+    edges.  Plain per-destination selection."""
+    off = np.asarray(off, dtype=np.int64)
+    col = np.asarray(col, dtype=np.int64)
+    key = np.asarray(edge_key, dtype=np.uint32)
+    n, e = off.size - 1, col.size
+    assert key.size == e and fanout >= 0
+    keep = np.zeros(e, dtype=bool)
+    order = np.lexsort((np.arange(e), key, col))     # by destination, then key, then position
+    dst_sorted = col[order]
+    start = np.searchsorted(dst_sorted, dst_sorted, side="left")
+    keep[order[np.arange(e) - start < fanout]] = True
+    src = np.repeat(np.arange(n), np.diff(off))
+    new_off = np.zeros(n + 1, dtype=np.int64)
+    np.add.at(new_off, src[keep] + 1, 1)
+    return np.cumsum(new_off), col[keep].astype(np.int32)
+
+
+# --------------------------------------------------------------------------
 # bounded hot store (Sec. 3.5): which partial states are evicted and reloaded
 # --------------------------------------------------------------------------
 

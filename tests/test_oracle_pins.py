@@ -592,3 +592,45 @@ def test_hot_store_policy_and_invariants(oracle):
             if prev is not None:
                 assert sum(ev) >= prev          # fewer slots never mean fewer evictions here
             prev = sum(ev)
+
+
+# --------------------------------------------------------------------------
+# sampling by disabling edges (Sec. 3.9)
+# --------------------------------------------------------------------------
+
+def test_sample_in_edges_vs_per_destination_loop(oracle):
+    """Against a loop that walks every destination's in-edge list and sorts it,
+    plus the properties the pass must have."""
+    for seed, n, e, fanout in ((51, 40, 300, 3), (52, 97, 900, 5), (53, 64, 500, 1), (54, 30, 200, 0)):
+        off, col, src = tiny_graph(seed, n, e)
+        rng = np.random.default_rng(seed)
+        key = rng.integers(0, 16, size=e, dtype=np.uint32)       # few distinct keys: plenty of ties
+        new_off, new_col = oracle.sample_in_edges(off, col, key, fanout)
+        # reference: per destination, (key, position) tuples sorted by Python
+        kept = set()
+        for v in range(n):
+            mine = sorted((int(key[i]), i) for i in range(e) if col[i] == v)
+            kept |= {i for _, i in mine[:fanout]}
+        ref_src = [int(src[i]) for i in sorted(kept)]
+        ref_col = [int(col[i]) for i in sorted(kept)]
+        got_src = np.repeat(np.arange(n), np.diff(new_off))
+        assert list(got_src) == ref_src and list(new_col) == ref_col
+        indeg = np.bincount(col, minlength=n)
+        assert np.array_equal(np.bincount(new_col, minlength=n), np.minimum(indeg, fanout))
+    # a fanout at least as large as the largest in-degree keeps the graph as it is
+    off, col, _ = tiny_graph(55, 50, 400)
+    key = np.random.default_rng(55).integers(0, 2**32, size=400, dtype=np.uint32)
+    o2, c2 = oracle.sample_in_edges(off, col, key, int(np.bincount(col).max()))
+    assert np.array_equal(o2, off) and np.array_equal(c2, col)
+    # with uniform keys every in-edge of a destination is equally likely to be kept
+    n, deg, trials = 1, 8, 4000
+    off1 = np.arange(deg + 1, dtype=np.int64)           # 8 sources, one edge each, all into vertex 0
+    off1 = np.concatenate([off1, np.full(0, deg)])
+    col1 = np.zeros(deg, dtype=np.int32)
+    hits = np.zeros(deg)
+    rng = np.random.default_rng(56)
+    for _ in range(trials):
+        k = rng.integers(0, 2**32, size=deg, dtype=np.uint32)
+        o, c = oracle.sample_in_edges(off1, col1, k, 2)
+        hits += np.diff(o)
+    assert hits.sum() == 2 * trials and np.all(np.abs(hits / trials - 0.25) < 0.03)
