@@ -70,6 +70,7 @@ STREAM_GRAPH = 0
 STREAM_IDPERM = 1
 STREAM_FEATURES = 2
 STREAM_WEIGHTS = 3  # + layer index * 4 + {0: W, 1: bias, 2: attn_src, 3: attn_dst}
+STREAM_SAMPLING = 1000
 
 
 # --------------------------------------------------------------------------
@@ -323,6 +324,15 @@ def layer_params(seed: int, layer: int, model: str, d_in: int, d_out: int, heads
         return LayerParams(W, bias, _uniform_param(seed, base + 2, (heads, dh), aa),
                            _uniform_param(seed, base + 3, (heads, dh), aa))
     raise ValueError(model)
+
+
+def edge_keys(seed: int, num_edges: int, device="cpu", bits: int = 32) -> torch.Tensor:
+    """One random key per edge (uint32 values held in an int32 tensor, edge e's
+    key is a function of (seed, e) only), for neighbourhood sampling.  `bits`
+    < 32 leaves few distinct values, i.e. many ties."""
+    e = torch.arange(num_edges, dtype=torch.int64, device=device)
+    k = _lsr(hash_counter(seed, STREAM_SAMPLING, e), 64 - bits)
+    return (k & 0xFFFFFFFF).to(torch.int32) if bits < 32 else ((k ^ 0x80000000) - 0x80000000).to(torch.int32)
 
 
 # --------------------------------------------------------------------------

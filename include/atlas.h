@@ -269,6 +269,19 @@ int atlas_reorder_indegree_desc(const atlas_graph_t *graph, int32_t *new_of_old,
  * must be set; outputs are int32[N] DEVICE memory.  Synchronous. */
 int atlas_reorder_score_desc(const atlas_graph_t *graph, int32_t *new_of_old, int32_t *old_of_new);
 
+/* Neighbourhood sampling as a preprocessing pass over the topology (Sec. 3.9:
+ * edges that are not required are disabled, the broadcast then runs unchanged
+ * on what is left).  Every destination keeps at most `fanout` of its in-edges:
+ * those with the smallest edge_key (one caller-drawn uint32 per edge, DEVICE
+ * memory, in CSR order), ties by position in the CSR.  out_row_offsets
+ * (int64[N+1]) and out_col_indices (int32, room for num_edges) in DEVICE memory
+ * receive the CSR by source of the kept edges in their original order;
+ * *out_num_edges (host, may be NULL) their number.  DEVICE graphs with fewer
+ * than 2^32 edges.  Synchronous.  Errors: E_NULL, E_BAD_DIMS, E_RANGE,
+ * E_OVERFLOW, E_NOMEM, E_HIP. */
+int atlas_sample_in_edges(const atlas_graph_t *graph, const uint32_t *edge_key, int32_t fanout,
+                          int64_t *out_row_offsets, int32_t *out_col_indices, int64_t *out_num_edges);
+
 /* Synchronise and copy one internal array to host memory, for tests. */
 enum atlas_debug_what {
     ATLAS_DBG_INDEG = 0,       /* int32[N]                                  */

@@ -31,7 +31,7 @@ EXPORTS = [
     "atlas_layer_init", "atlas_attention_prepass", "atlas_broadcast_chunk", "atlas_flush_ready",
     "atlas_layer_finish", "atlas_in_degree", "atlas_reorder_indegree_desc", "atlas_debug_copy",
     "atlas_release_cache", "atlas_strerror", "atlas_last_hip_error", "atlas_plan_create", "atlas_plan_destroy",
-    "atlas_reorder_score_desc",
+    "atlas_reorder_score_desc", "atlas_sample_in_edges",
 ]
 
 
@@ -98,6 +98,7 @@ def lib() -> ctypes.CDLL:
         L.atlas_in_degree.argtypes = [ctypes.POINTER(atlas_graph_t), vp, vp]
         L.atlas_reorder_indegree_desc.argtypes = [ctypes.POINTER(atlas_graph_t), vp, vp]
         L.atlas_reorder_score_desc.argtypes = [ctypes.POINTER(atlas_graph_t), vp, vp]
+        L.atlas_sample_in_edges.argtypes = [ctypes.POINTER(atlas_graph_t), vp, i32, vp, vp, ctypes.POINTER(i64)]
         L.atlas_debug_copy.argtypes = [vp, i32, vp, i64]
         L.atlas_release_cache.argtypes = []
         L.atlas_plan_create.argtypes = [ctypes.POINTER(atlas_graph_t), i64, ctypes.POINTER(vp)]
@@ -212,6 +213,14 @@ def atlas_reorder_indegree_desc(graph: atlas_graph_t, new_of_old, old_of_new) ->
 def atlas_reorder_score_desc(graph: atlas_graph_t, new_of_old, old_of_new) -> None:
     _check(lib().atlas_reorder_score_desc(ctypes.byref(graph), _ptr(new_of_old), _ptr(old_of_new)),
            "atlas_reorder_score_desc")
+
+
+def atlas_sample_in_edges(graph: atlas_graph_t, edge_key, fanout: int, out_row_offsets, out_col_indices) -> int:
+    """Returns the number of kept edges."""
+    kept = ctypes.c_int64(0)
+    _check(lib().atlas_sample_in_edges(ctypes.byref(graph), _ptr(edge_key), fanout, _ptr(out_row_offsets),
+                                       _ptr(out_col_indices), ctypes.byref(kept)), "atlas_sample_in_edges")
+    return kept.value
 
 
 def atlas_debug_copy(layer: int, what: int, host_array) -> None:

@@ -1005,6 +1005,20 @@ int atlas_reorder_score_desc(const atlas_graph_t *graph, int32_t *new_of_old, in
     return ATLAS_OK;
 }
 
+int atlas_sample_in_edges(const atlas_graph_t *graph, const uint32_t *edge_key, int32_t fanout,
+                          int64_t *out_row_offsets, int32_t *out_col_indices, int64_t *out_num_edges) {
+    if (!graph || !out_row_offsets || !graph->row_offsets) return ATLAS_E_NULL;
+    if (graph->num_edges > 0 && (!graph->col_indices || !edge_key || !out_col_indices)) return ATLAS_E_NULL;
+    if (graph->residency != ATLAS_RESIDENT_DEVICE) return ATLAS_E_BAD_DIMS;
+    if (graph->num_vertices < 0 || graph->num_edges < 0 || fanout < 0) return ATLAS_E_RANGE;
+    if (graph->num_vertices >= (int64_t(1) << 31) || graph->num_edges >= (int64_t(1) << 32)) return ATLAS_E_OVERFLOW;
+    HIP_TRY(sample_in_edges(graph->row_offsets, graph->col_indices, graph->num_vertices, graph->num_edges, edge_key,
+                            fanout, out_row_offsets, out_col_indices));
+    if (out_num_edges)
+        HIP_TRY(hipMemcpy(out_num_edges, out_row_offsets + graph->num_vertices, sizeof(int64_t), hipMemcpyDeviceToHost));
+    return ATLAS_OK;
+}
+
 int atlas_debug_copy(atlas_layer_t *L, int what, void *host_dst, int64_t bytes) {
     if (!L || !host_dst) return ATLAS_E_NULL;
     if (bytes < 0) return ATLAS_E_RANGE;

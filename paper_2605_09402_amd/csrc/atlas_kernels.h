@@ -241,4 +241,10 @@ hipError_t reorder_indegree_desc(const int32_t *indeg, int64_t n, int32_t *new_o
 hipError_t reorder_score_desc(const int64_t *off, const int32_t *col, const int32_t *indeg, int64_t n,
                               int32_t *new_of_old, int32_t *old_of_new);
 
+// Sampling by disabling edges: keep, per destination, the `fanout` in-edges with the
+// smallest keys (ties by CSR position); out_off [n+1] / out_col [<= e] receive the CSR
+// of the kept edges.  Synchronous.
+hipError_t sample_in_edges(const int64_t *off, const int32_t *col, int64_t n, int64_t e, const uint32_t *key,
+                           int32_t fanout, int64_t *out_off, int32_t *out_col);
+
 }  // namespace atlas
