@@ -40,6 +40,12 @@ def main() -> int:
                          "parity workloads, timed for the record")
     ap.add_argument("--layer-type", choices=["sage", "gin"], default="sage",
                     help="config5 only: run the same graph and widths through GIN layers instead of SAGE-mean")
+    ap.add_argument("--plan-block-log2", type=int, default=-1,
+                    help="source-blocked plan: log2 of the sources per block (0: plain destination order; default: "
+                         "blocks of 2 MiB of rows for config5, plain order for the other workloads)")
+    ap.add_argument("--plan-hot-min", type=int, default=0,
+                    help="source-blocked plan: destinations with at least this many messages from a chunk are blocked "
+                         "(default: 32 per block of the chunk)")
     ap.add_argument("--d-in", type=int, default=512, help="workload wide: input feature width (up to 1024 with "
                                                           "--transform-first, 512 without)")
     ap.add_argument("--transform-first", action="store_true",
@@ -66,7 +72,7 @@ def main() -> int:
                     help="also run a plain 4 GiB device copy three times (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only; --gpus must be 1 (no collectives or sharding here)",
+        print("bench.py: this library runs on one GPU only; --gpus must be 1 (no collectives or sharding here)",
               file=sys.stderr)
         return 2
 
@@ -127,7 +133,18 @@ def main() -> int:
     plan_ms = None
     if not args.no_plan and args.residency == "device":
         t0 = time.time()
-        plan = atlas.atlas_plan_create(atlas.make_graph(n, e, wl.off, wl.col), chunk)
+        pg = atlas.make_graph(n, e, wl.off, wl.col)
+        if args.plan_block_log2 < 0:   # default: 2 MiB of source rows per block on the large workload
+            row_bytes = wl.dims[0] * (2 if wl.store != torch.float32 else 4)
+            args.plan_block_log2 = max(6, ((2 << 20) // row_bytes).bit_length() - 1) if args.workload == "config5" else 0
+        if args.plan_block_log2 > 0 and args.plan_hot_min <= 0:
+            args.plan_hot_min = 32 * max(1, chunk >> args.plan_block_log2)
+        if args.plan_block_log2 > 0 and chunk <= (1 << args.plan_block_log2):
+            args.plan_block_log2 = 0   # a chunk of one block: nothing to reorder
+        if args.plan_block_log2 > 0:
+            plan = atlas.atlas_plan_create_blocked(pg, chunk, 1 << args.plan_block_log2, args.plan_hot_min)
+        else:
+            plan = atlas.atlas_plan_create(pg, chunk)
         plan_ms = (time.time() - t0) * 1e3
         log("plan built in %.1f ms" % plan_ms)
     graph = atlas.make_graph(n, e, wl.off, wl.col, indeg, atlas.RESIDENT_DEVICE, plan)
@@ -334,6 +351,8 @@ def main() -> int:
                    "edge_order": "per-chunk destination-grouped plan" if plan else "CSR stream (atomics)",
                    "plan_build_ms": None if plan_ms is None else round(plan_ms, 1)},
         "transform_first": bool(args.transform_first),
+        "plan_blocking": None if args.plan_block_log2 <= 0 else {"block_sources": 1 << args.plan_block_log2,
+                                                                  "hot_min_edges": args.plan_hot_min},
         "hot_store": None if not hot_slots else {
             "slots": hot_slots, "policy": args.evict_policy + "-pending", "evictions_per_layer": st["hot_evictions"],
             "reloads_per_layer": st["hot_reloads"], "peak_slots": st["hot_peak_slots"]},

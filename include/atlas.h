@@ -248,6 +248,21 @@ int atlas_layer_finish(atlas_layer_t *layer, atlas_layer_stats_t *stats);
  * chunk instead of the CSR slice).  It must outlive the layers that use it.
  * graph->plan and graph->in_degree are ignored here. */
 int atlas_plan_create(const atlas_graph_t *graph, int64_t chunk_sources, atlas_plan_t **out);
+
+/* atlas_plan_create with a source-blocked edge order for the heavy destinations.
+ * In destination order the group of a high-degree destination walks the rows
+ * of the whole chunk, far more than a cache holds, so nothing is reused between
+ * groups.  Here the edges of every destination that receives at least
+ * hot_min_edges messages from a chunk are ordered by (source block,
+ * destination), a block being block_sources consecutive sources: while the
+ * kernel works through one block its rows stay cache resident.  Choose
+ * block_sources so that a block's rows fit an L2 (4 MiB on this GPU: 16,384
+ * rows of 256 bytes) and hot_min_edges at several times the number of blocks
+ * per chunk (every such destination gets one group per block).  Results are the
+ * same sums in another order.  block_sources = 0: plain atlas_plan_create.
+ * Not for GAT layers (E_BAD_DIMS at atlas_layer_init); N < 2^30 (E_OVERFLOW). */
+int atlas_plan_create_blocked(const atlas_graph_t *graph, int64_t chunk_sources, int64_t block_sources,
+                              int64_t hot_min_edges, atlas_plan_t **out);
 int atlas_plan_destroy(atlas_plan_t *plan);
 
 /* In-degree of every vertex (histogram of col_indices), int32[N] in DEVICE

@@ -31,7 +31,7 @@ EXPORTS = [
     "atlas_layer_init", "atlas_attention_prepass", "atlas_broadcast_chunk", "atlas_flush_ready",
     "atlas_layer_finish", "atlas_in_degree", "atlas_reorder_indegree_desc", "atlas_debug_copy",
     "atlas_release_cache", "atlas_strerror", "atlas_last_hip_error", "atlas_plan_create", "atlas_plan_destroy",
-    "atlas_reorder_score_desc", "atlas_sample_in_edges",
+    "atlas_reorder_score_desc", "atlas_sample_in_edges", "atlas_plan_create_blocked",
 ]
 
 
@@ -102,6 +102,7 @@ def lib() -> ctypes.CDLL:
         L.atlas_debug_copy.argtypes = [vp, i32, vp, i64]
         L.atlas_release_cache.argtypes = []
         L.atlas_plan_create.argtypes = [ctypes.POINTER(atlas_graph_t), i64, ctypes.POINTER(vp)]
+        L.atlas_plan_create_blocked.argtypes = [ctypes.POINTER(atlas_graph_t), i64, i64, i64, ctypes.POINTER(vp)]
         L.atlas_plan_destroy.argtypes = [vp]
         for name in EXPORTS:
             getattr(L, name).restype = ctypes.c_int      # raises AttributeError on a missing export
@@ -194,6 +195,13 @@ def atlas_layer_finish(layer: int) -> dict:
 def atlas_plan_create(graph: atlas_graph_t, chunk_sources: int) -> int:
     h = ctypes.c_void_p()
     _check(lib().atlas_plan_create(ctypes.byref(graph), chunk_sources, ctypes.byref(h)), "atlas_plan_create")
+    return h.value
+
+
+def atlas_plan_create_blocked(graph: atlas_graph_t, chunk_sources: int, block_sources: int, hot_min_edges: int) -> int:
+    h = ctypes.c_void_p()
+    _check(lib().atlas_plan_create_blocked(ctypes.byref(graph), chunk_sources, block_sources, hot_min_edges,
+                                           ctypes.byref(h)), "atlas_plan_create_blocked")
     return h.value
 
 

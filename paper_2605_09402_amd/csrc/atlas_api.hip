@@ -117,6 +117,7 @@ struct atlas_plan {
     int64_t n = 0, e = 0, chunk = 0;
     bool host = false;              // arrays live in pinned host memory (plan of a PINNED_HOST graph)
     int32_t *src_sorted = nullptr;  // [E] destination-ordered source ids of all chunks
+    bool blocked = false;           // some chunk is in source-blocked order (grp_dst bit 30 in use)
     std::vector<PlanChunk> chunks;  // grp_dst / tile_grp: device, or pinned host when `host`
     size_t max_stage_bytes = 0;     // host plans: largest staging slot any chunk needs
 };
@@ -382,6 +383,8 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
         L->indeg = static_cast<const int32_t *>(L->indeg_own.p);
     }
     if (d.model == ATLAS_MODEL_GAT) {
+        // the attention sweeps assume one group per destination and chunk
+        if (L->g.plan && L->g.plan->blocked) return ATLAS_E_BAD_DIMS;
         const size_t nh = n1 * d.heads;
         HIP_TRY(L->gat_el.alloc(nh * sizeof(float)));
         HIP_TRY(L->gat_er.alloc(nh * sizeof(float)));
@@ -677,6 +680,8 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
             ga.tile_grp = pc->tile_grp;
         }
         ga.n_edges = pc->n_edges;
+        ga.n_groups = pc->n_groups;
+        ga.multi_bit = pc->blocked ? 0x40000000 : 0;
         ga.emb = a.emb;
         ga.gat = a.gat;
         ga.src_begin = src_begin;
@@ -712,7 +717,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         // Every vertex this chunk addresses gets a slot first (Sec. 3.5); the counts come back to the
         // host, which sizes the eviction and checks that the chunk fits.
         const int32_t stamp = static_cast<int32_t>(L->num_chunks + 1);
-        HIP_TRY(hot_mark(L->hs, ga.grp_dst, pc->n_groups, src_begin, L->selfmsg ? src_end - src_begin : 0, stamp, s));
+        HIP_TRY(hot_mark(L->hs, ga.grp_dst, 0x7fffffff & ~ga.multi_bit, pc->n_groups, src_begin, L->selfmsg ? src_end - src_begin : 0, stamp, s));
         int32_t hc[HS_COUNT];
         HIP_TRY(hipMemcpyAsync(hc, L->hs.ctr, sizeof(hc), hipMemcpyDeviceToHost, s));
         HIP_TRY(hipStreamSynchronize(s));
@@ -872,7 +877,15 @@ int atlas_layer_finish(atlas_layer_t *L, atlas_layer_stats_t *stats) {
 }
 
 int atlas_plan_create(const atlas_graph_t *graph, int64_t chunk_sources, atlas_plan_t **out) {
+    return atlas_plan_create_blocked(graph, chunk_sources, 0, 0, out);
+}
+
+int atlas_plan_create_blocked(const atlas_graph_t *graph, int64_t chunk_sources, int64_t block_sources,
+                              int64_t hot_min_edges, atlas_plan_t **out) {
     if (!graph || !out) return ATLAS_E_NULL;
+    if (block_sources < 0 || hot_min_edges < 0) return ATLAS_E_BAD_DIMS;
+    // bit 30 of a stored destination id marks destinations with several groups per chunk
+    if (block_sources > 0 && graph->num_vertices >= (int64_t(1) << 30)) return ATLAS_E_OVERFLOW;
     if (!graph->row_offsets || (graph->num_edges > 0 && !graph->col_indices)) return ATLAS_E_NULL;
     if (chunk_sources <= 0) return ATLAS_E_BAD_DIMS;
     if (graph->residency != ATLAS_RESIDENT_DEVICE && graph->residency != ATLAS_RESIDENT_PINNED_HOST)
@@ -913,7 +926,7 @@ int atlas_plan_create(const atlas_graph_t *graph, int64_t chunk_sources, atlas_p
         PlanChunk pc;
         if (!P->host) {
             e = build_plan_chunk(graph->row_offsets, graph->col_indices, P->n, b, en, ebeg, eend,
-                                 P->src_sorted + ebeg, seen, &pc);
+                                 P->src_sorted + ebeg, seen, block_sources, hot_min_edges, &pc);
             if (e != hipSuccess) { rc = hip_fail(e, "build_plan_chunk"); break; }
         } else {
             // stage the chunk's CSR slice into HBM, regroup there, bring the result back
@@ -926,7 +939,8 @@ int atlas_plan_create(const atlas_graph_t *graph, int64_t chunk_sources, atlas_p
                 (e = hipMalloc(reinterpret_cast<void **>(&src_tmp), ne1 * 4)) == hipSuccess &&
                 (e = hipMemcpy(off_tmp, graph->row_offsets + b, (nsrc + 1) * sizeof(int64_t), hipMemcpyHostToDevice)) == hipSuccess &&
                 (ne == 0 || (e = hipMemcpy(col_tmp, graph->col_indices + ebeg, static_cast<size_t>(ne) * 4, hipMemcpyHostToDevice)) == hipSuccess)) {
-                e = build_plan_chunk(off_tmp - b, col_tmp - ebeg, P->n, b, en, ebeg, eend, src_tmp, seen, &pc);
+                e = build_plan_chunk(off_tmp - b, col_tmp - ebeg, P->n, b, en, ebeg, eend, src_tmp, seen, block_sources,
+                                     hot_min_edges, &pc);
                 if (e == hipSuccess && ne > 0)
                     e = hipMemcpy(P->src_sorted + ebeg, src_tmp, static_cast<size_t>(ne) * 4, hipMemcpyDeviceToHost);
                 if (e == hipSuccess && ne > 0) {
@@ -951,6 +965,7 @@ int atlas_plan_create(const atlas_graph_t *graph, int64_t chunk_sources, atlas_p
                 break;
             }
         }
+        P->blocked = P->blocked || pc.blocked;
         P->chunks.push_back(pc);
         P->max_stage_bytes = std::max(P->max_stage_bytes, stage_bytes_of(pc));
         ebeg = eend;

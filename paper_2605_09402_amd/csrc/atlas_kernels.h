@@ -44,8 +44,8 @@ struct HotStore {
     int d = 0;
 };
 hipError_t hot_init(const HotStore &h, int64_t n, hipStream_t s);
-hipError_t hot_mark(const HotStore &h, const int32_t *grp_dst, int64_t n_groups, int64_t src_begin, int64_t n_self,
-                    int32_t chunk_stamp, hipStream_t s);
+hipError_t hot_mark(const HotStore &h, const int32_t *grp_dst, int32_t dst_mask, int64_t n_groups, int64_t src_begin,
+                    int64_t n_self, int32_t chunk_stamp, hipStream_t s);
 hipError_t hot_build_keys(const HotStore &h, const int32_t *pending, int32_t chunk_stamp, int policy, hipStream_t s);
 size_t hot_sort_temp_bytes(int64_t slots);
 hipError_t hot_evict(const HotStore &h, int64_t n_evict, void *sort_temp, size_t sort_temp_bytes, hipStream_t s);
@@ -96,6 +96,7 @@ struct PlanChunk {
     int32_t *grp_dst = nullptr;   // [n_groups] destination of each group, ascending; bit 31 set when no
                                   // earlier chunk sends to that destination (its first group of the layer)
     int32_t *tile_grp = nullptr;  // [ceil(n_edges/64)] group of the first edge of every 64-edge tile
+    bool blocked = false;         // source-blocked order: grp_dst bit 30 marks destinations with several groups
 };
 
 struct GroupedArgs {
@@ -117,6 +118,9 @@ struct GroupedArgs {
     unsigned long long *counters64;
     GatState gat;               // model == GAT only
     const int32_t *slot_of = nullptr;   // bounded store: row of `acc` that holds vertex v (nullptr: row v)
+    int64_t n_groups = 0;
+    int32_t multi_bit = 0;      // source-blocked chunk: 0x40000000, the grp_dst bit of destinations that have
+                                // several groups in this chunk (all of them add with atomics); else 0
     float *scores = nullptr;    // GAT only: [n_edges][heads] attention logits of the chunk's edges, written
                                 // by the max sweep and read by the aggregation
 };
@@ -132,7 +136,7 @@ hipError_t launch_aggregate_grouped(const GroupedArgs &a, hipStream_t s);
 // edge_end - edge_begin entries; grp_dst and tile_grp are allocated with hipMalloc.
 hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int64_t n, int64_t src_begin,
                             int64_t src_end, int64_t edge_begin, int64_t edge_end, int32_t *src_sorted,
-                            uint8_t *seen, PlanChunk *out);
+                            uint8_t *seen, int64_t block_sources, int64_t hot_min_edges, PlanChunk *out);
 
 // GAT, per chunk: raise m_next[v][h] to the largest logit any edge of the chunk
 // sends to v (CSR order), then bring every destination whose maximum moved to

@@ -438,12 +438,15 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
         const bool closes = is_end || lane == cnt - 1;  // last edge of a group, or of the tile
         int32_t dstv = 0;
         bool first_touch = false;  // no earlier chunk sent to this destination: its row holds nothing yet
+        bool multi = false;        // source-blocked chunk: other groups of this launch address the same destination
         if (closes) {
             const int32_t gd = a.grp_dst[g0 + __popcll(below)];
             first_touch = gd < 0;
-            dstv = gd & 0x7fffffff;
+            multi = (gd & a.multi_bit) != 0;
+            dstv = gd & 0x7fffffff & ~a.multi_bit;
         }
         const uint64_t firstmask = __ballot(first_touch);
+        const uint64_t multimask = __ballot(multi);
         // accumulator row of the destination: the vertex id, or its slot in a bounded store
         int32_t rowv = dstv;
         if (MODEL != 2 && a.slot_of && closes) rowv = a.slot_of[dstv];
@@ -517,7 +520,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
                                     a.gat.m_cur[vh] = mn;
                                 }
                             }
-                        } else if (cut) {
+                        } else if (cut || ((multimask >> j) & 1ull)) {
                             row_add_shared<VPL>(dst, sum);
                         } else if ((firstmask >> j) & 1ull) {
                             row_store<VPL>(dst, sum);
@@ -547,7 +550,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
         if (closes) {
             const int prev_end = below ? 63 - __clzll(static_cast<long long>(below)) : -1;
             const int c = lane - prev_end;
-            const bool shared = (below == 0 && cut0) || !is_end;
+            const bool shared = (below == 0 && cut0) || !is_end || multi;
             if (shared) {
                 is_ready = atomicSub(&a.pending[dstv], c) == c;
             } else {
@@ -679,8 +682,26 @@ __global__ __launch_bounds__(kBlock) void k_zero_cut_first_rows(GroupedArgs a) {
         while (todo) {
             const int j = __ffsll(static_cast<unsigned long long>(todo)) - 1;
             todo &= todo - 1;
-            int64_t v = __builtin_amdgcn_readlane(gd, j) & 0x7fffffff;
+            int64_t v = __builtin_amdgcn_readlane(gd, j) & 0x7fffffff & ~a.multi_bit;
             if (a.slot_of) v = a.slot_of[v];   // bounded store: the destination's slot
+            float *row = a.acc + v * a.d;
+            for (int c = lane; c < a.d; c += kWave) row[c] = 0.f;
+        }
+    }
+    if (!a.multi_bit) return;
+    // source-blocked chunk: a destination with several groups is added to with atomics by all of them;
+    // its first group of the layer (one per destination) has the row cleared here
+    for (int64_t g0 = static_cast<int64_t>(blockIdx.x) * kBlock + (threadIdx.x & ~(kWave - 1)); g0 < a.n_groups;
+         g0 += stride) {
+        const int64_t g = g0 + lane;
+        int32_t gd = 0;
+        if (g < a.n_groups) gd = a.grp_dst[g];
+        uint64_t todo = __ballot(gd < 0 && (gd & a.multi_bit) != 0);
+        while (todo) {
+            const int j = __ffsll(static_cast<unsigned long long>(todo)) - 1;
+            todo &= todo - 1;
+            int64_t v = __builtin_amdgcn_readlane(gd, j) & 0x7fffffff & ~a.multi_bit;
+            if (a.slot_of) v = a.slot_of[v];
             float *row = a.acc + v * a.d;
             for (int c = lane; c < a.d; c += kWave) row[c] = 0.f;
         }
@@ -741,8 +762,9 @@ hipError_t launch_aggregate(const AggregateArgs &a, hipStream_t s) {
 
 hipError_t launch_zero_cut_first_rows(const GroupedArgs &a, hipStream_t s) {
     const int64_t ntiles = (a.n_edges + kTileEdges - 1) / kTileEdges;
-    if (ntiles <= 1) return hipSuccess;
-    int64_t blocks = (ntiles + kBlock - 1) / kBlock;
+    if (ntiles <= 1 && !a.multi_bit) return hipSuccess;
+    int64_t blocks = (std::max(ntiles, a.multi_bit ? a.n_groups : int64_t(0)) + kBlock - 1) / kBlock;
+    if (blocks < 1) blocks = 1;
     const int cap = persistent_grid(8);
     if (blocks > cap) blocks = cap;
     hipLaunchKernelGGL(k_zero_cut_first_rows, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, s, a);

@@ -60,7 +60,7 @@ __device__ __forceinline__ void wave_append(bool want, int32_t v, int32_t *list,
 // sources, whose self message needs an existing state to be resident (it never
 // starts one).  Every addressed vertex is stamped with the chunk; those without
 // a slot are listed once.
-__global__ __launch_bounds__(kBlock) void k_hot_mark(HotStore h, const int32_t *__restrict__ grp_dst,
+__global__ __launch_bounds__(kBlock) void k_hot_mark(HotStore h, const int32_t *__restrict__ grp_dst, int32_t dst_mask,
                                                     int64_t n_groups, int64_t src_begin, int64_t n_self,
                                                     int32_t chunk_stamp) {
     const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(kBlock) void k_hot_mark(HotStore h, const int32_t *
     int32_t v = 0;
     if (i < n_groups + n_self) {
         const bool self = i >= n_groups;
-        v = self ? static_cast<int32_t>(src_begin + (i - n_groups)) : (grp_dst[i] & 0x7fffffff);
+        v = self ? static_cast<int32_t>(src_begin + (i - n_groups)) : (grp_dst[i] & dst_mask);
         const int32_t st = h.slot_of[v];
         if (!(self && st == -1)) {
             const int32_t old = atomicExch(&h.stamp[v], chunk_stamp);
@@ -196,12 +196,12 @@ hipError_t hot_init(const HotStore &h, int64_t n, hipStream_t s) {
     return hipGetLastError();
 }
 
-hipError_t hot_mark(const HotStore &h, const int32_t *grp_dst, int64_t n_groups, int64_t src_begin, int64_t n_self,
-                    int32_t chunk_stamp, hipStream_t s) {
+hipError_t hot_mark(const HotStore &h, const int32_t *grp_dst, int32_t dst_mask, int64_t n_groups, int64_t src_begin,
+                    int64_t n_self, int32_t chunk_stamp, hipStream_t s) {
     const int64_t items = n_groups + n_self;
     if (items <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_hot_mark, dim3(static_cast<unsigned>((items + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, h,
-                       grp_dst, n_groups, src_begin, n_self, chunk_stamp);
+                       grp_dst, dst_mask, n_groups, src_begin, n_self, chunk_stamp);
     return hipGetLastError();
 }
 

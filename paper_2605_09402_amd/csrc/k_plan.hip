@@ -12,6 +12,17 @@
 //      of a destination's group, a prefix sum of the heads numbers the groups;
 //   4. grp_dst[g] = destination of group g (bit 31: the destination's first group in
 //      the whole stream), tile_grp[t] = group of edge 64 t.
+//
+// Source-blocked variant (block_sources > 0), between steps 2 and 3.  In
+// destination order a hub's group walks the whole chunk's rows once, far more
+// than an L2 holds, and the next hub walks them again: nothing is reused.  So
+// the edges of destinations that receive at least hot_min_edges messages from
+// the chunk are reordered by (source block, destination), a block being
+// block_sources consecutive sources whose rows fit an L2: while the kernel
+// sweeps one block's edges its rows stay cache resident and are gathered many
+// times.  Such a destination then has one group per source block (bit 30 of
+// grp_dst: several groups of this chunk address the destination, so all of them
+// add with atomics); all other edges keep the destination order and follow.
 #include "atlas_kernels.h"
 
 #include <hip/hip_runtime.h>
@@ -54,7 +65,8 @@ __global__ void k_mark_groups(const uint32_t *__restrict__ dst_sorted, int64_t n
 // group that is its destination's first gets bit 31 of grp_dst (chunks are
 // planned in streaming order and a destination has one group per chunk).
 __global__ void k_emit_groups(const uint32_t *__restrict__ dst_sorted, const uint32_t *__restrict__ gidx,
-                              int64_t n_edges, int32_t *grp_dst, int32_t *tile_grp, uint8_t *seen) {
+                              int64_t n_edges, int32_t *grp_dst, int32_t *tile_grp, uint8_t *seen,
+                              const uint32_t *__restrict__ block_key, uint32_t n_blocks) {
     const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
     if (i >= n_edges) return;
     const uint32_t g = gidx[i] - 1u;
@@ -62,9 +74,42 @@ __global__ void k_emit_groups(const uint32_t *__restrict__ dst_sorted, const uin
         const uint32_t v = dst_sorted[i];
         const bool first = seen[v] == 0;
         seen[v] = 1;
-        grp_dst[g] = static_cast<int32_t>(first ? (v | 0x80000000u) : v);
+        // source-blocked chunks: the destination has a group in every source block
+        const uint32_t multi = (block_key && block_key[i] < n_blocks) ? 0x40000000u : 0u;
+        grp_dst[g] = static_cast<int32_t>((first ? (v | 0x80000000u) : v) | multi);
     }
     if ((i & 63) == 0) tile_grp[i >> 6] = static_cast<int32_t>(g);
+}
+
+// gstart[g] = position of the first edge of group g (gidx = group number + 1 per edge)
+__global__ void k_group_starts(const uint32_t *__restrict__ heads, const uint32_t *__restrict__ gidx, int64_t n_edges,
+                               uint32_t *gstart) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (i >= n_edges) return;
+    if (heads[i]) gstart[gidx[i] - 1u] = static_cast<uint32_t>(i);
+    if (i + 1 == n_edges) gstart[gidx[i]] = static_cast<uint32_t>(n_edges);
+}
+
+// key[i] = source block of edge i if its destination's group has at least hot_min edges, n_blocks otherwise
+__global__ void k_block_keys(const int32_t *__restrict__ src_sorted, const uint32_t *__restrict__ gidx,
+                             const uint32_t *__restrict__ gstart, int64_t n_edges, int64_t src_begin,
+                             int64_t block_sources, uint32_t n_blocks, uint32_t hot_min, uint32_t *key, uint32_t *pos) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (i >= n_edges) return;
+    const uint32_t g = gidx[i] - 1u;
+    const uint32_t len = gstart[g + 1] - gstart[g];
+    const int64_t u = src_sorted[i] & 0x7fffffff;
+    key[i] = len >= hot_min ? static_cast<uint32_t>((u - src_begin) / block_sources) : n_blocks;
+    pos[i] = static_cast<uint32_t>(i);
+}
+
+__global__ void k_apply_order(const uint32_t *__restrict__ pos, const uint32_t *__restrict__ dst_in,
+                              const int32_t *__restrict__ src_in, int64_t n_edges, uint32_t *dst_out, int32_t *src_out) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (i >= n_edges) return;
+    const uint32_t p = pos[i];
+    dst_out[i] = dst_in[p];
+    src_out[i] = src_in[p] & 0x7fffffff;   // group tails are marked again for the new order
 }
 
 struct MaxOp {
@@ -75,7 +120,7 @@ struct MaxOp {
 
 hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int64_t n, int64_t src_begin,
                             int64_t src_end, int64_t edge_begin, int64_t edge_end, int32_t *src_sorted,
-                            uint8_t *seen, PlanChunk *out) {
+                            uint8_t *seen, int64_t block_sources, int64_t hot_min_edges, PlanChunk *out) {
     *out = PlanChunk{};
     out->edge_base = edge_begin;
     out->n_edges = edge_end - edge_begin;
@@ -84,6 +129,14 @@ hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int6
     if (ne >= (int64_t(1) << 32)) return hipErrorInvalidValue;
 
     hipError_t err = hipSuccess;
+    // source-blocked order: only for chunks of more than one block
+    const int64_t n_blocks64 = block_sources > 0 ? (src_end - src_begin + block_sources - 1) / block_sources : 0;
+    const bool blocked = n_blocks64 > 1;
+    const uint32_t n_blocks = static_cast<uint32_t>(n_blocks64);
+    uint32_t *bkey = nullptr, *bkey_sorted = nullptr, *bpos = nullptr, *bpos_sorted = nullptr, *gstart = nullptr;
+    int32_t *src_new = nullptr;
+    size_t temp_bsort = 0;
+    int bkey_bits = 1;
     int32_t *tmp_src = nullptr;   // source per edge (CSR order); reused for the group prefix sum
     uint32_t *dst_sorted = nullptr;
     uint32_t *heads = nullptr;
@@ -105,6 +158,18 @@ hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int6
                                        rocprim::plus<uint32_t>(), nullptr)) != hipSuccess) goto done;
     temp_bytes = temp_sort > temp_scan_max ? temp_sort : temp_scan_max;
     if (temp_scan_sum > temp_bytes) temp_bytes = temp_scan_sum;
+    if (blocked) {
+        while (bkey_bits < 32 && (uint64_t(1) << bkey_bits) <= n_blocks) ++bkey_bits;   // keys 0 .. n_blocks
+        if ((err = hipMalloc(&bkey, count * 4)) != hipSuccess) goto done;
+        if ((err = hipMalloc(&bkey_sorted, count * 4)) != hipSuccess) goto done;
+        if ((err = hipMalloc(&bpos, count * 4)) != hipSuccess) goto done;
+        if ((err = hipMalloc(&bpos_sorted, count * 4)) != hipSuccess) goto done;
+        if ((err = hipMalloc(&gstart, (count + 1) * 4)) != hipSuccess) goto done;
+        if ((err = hipMalloc(&src_new, count * 4)) != hipSuccess) goto done;
+        if ((err = rocprim::radix_sort_pairs(nullptr, temp_bsort, bkey, bkey_sorted, bpos, bpos_sorted, count, 0,
+                                             bkey_bits, nullptr)) != hipSuccess) goto done;
+        if (temp_bsort > temp_bytes) temp_bytes = temp_bsort;
+    }
     if ((err = hipMalloc(&temp, temp_bytes > 0 ? temp_bytes : 16)) != hipSuccess) goto done;
 
     // 1. source of every edge
@@ -116,6 +181,30 @@ hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int6
     // 2. stable sort by destination
     if ((err = rocprim::radix_sort_pairs(temp, temp_sort, keys_in, dst_sorted, tmp_src, src_sorted, count, 0, end_bit,
                                          nullptr)) != hipSuccess) goto done;
+    if (blocked) {
+        // groups of the destination order and their sizes, then the stable sort by source block (edges of
+        // small groups all get the key n_blocks and stay behind, in destination order)
+        hipLaunchKernelGGL(k_mark_groups, dim3(blocks_for(ne)), dim3(kBlock), 0, nullptr, dst_sorted, ne, src_sorted, heads);
+        if ((err = hipGetLastError()) != hipSuccess) goto done;
+        if ((err = rocprim::inclusive_scan(temp, temp_scan_sum, heads, reinterpret_cast<uint32_t *>(tmp_src), count,
+                                           rocprim::plus<uint32_t>(), nullptr)) != hipSuccess) goto done;
+        hipLaunchKernelGGL(k_group_starts, dim3(blocks_for(ne)), dim3(kBlock), 0, nullptr, heads,
+                           reinterpret_cast<const uint32_t *>(tmp_src), ne, gstart);
+        hipLaunchKernelGGL(k_block_keys, dim3(blocks_for(ne)), dim3(kBlock), 0, nullptr, src_sorted,
+                           reinterpret_cast<const uint32_t *>(tmp_src), gstart, ne, src_begin, block_sources, n_blocks,
+                           static_cast<uint32_t>(std::min<int64_t>(std::max<int64_t>(hot_min_edges, 1), 0xffffffffll)),
+                           bkey, bpos);
+        if ((err = hipGetLastError()) != hipSuccess) goto done;
+        if ((err = rocprim::radix_sort_pairs(temp, temp_bsort, bkey, bkey_sorted, bpos, bpos_sorted, count, 0, bkey_bits,
+                                             nullptr)) != hipSuccess) goto done;
+        // heads is free again: it receives the destinations in the new order
+        hipLaunchKernelGGL(k_apply_order, dim3(blocks_for(ne)), dim3(kBlock), 0, nullptr, bpos_sorted, dst_sorted,
+                           src_sorted, ne, heads, src_new);
+        if ((err = hipGetLastError()) != hipSuccess) goto done;
+        if ((err = hipMemcpyAsync(dst_sorted, heads, count * 4, hipMemcpyDeviceToDevice, nullptr)) != hipSuccess) goto done;
+        if ((err = hipMemcpyAsync(src_sorted, src_new, count * 4, hipMemcpyDeviceToDevice, nullptr)) != hipSuccess) goto done;
+        out->blocked = true;
+    }
     // 3. group heads, tail flags, group numbering
     hipLaunchKernelGGL(k_mark_groups, dim3(blocks_for(ne)), dim3(kBlock), 0, nullptr, dst_sorted, ne, src_sorted, heads);
     if ((err = hipGetLastError()) != hipSuccess) goto done;
@@ -127,10 +216,14 @@ hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int6
     if ((err = hipMalloc(&out->grp_dst, static_cast<size_t>(last) * 4)) != hipSuccess) goto done;
     if ((err = hipMalloc(&out->tile_grp, static_cast<size_t>((ne + 63) / 64) * 4)) != hipSuccess) goto done;
     hipLaunchKernelGGL(k_emit_groups, dim3(blocks_for(ne)), dim3(kBlock), 0, nullptr, dst_sorted,
-                       reinterpret_cast<const uint32_t *>(tmp_src), ne, out->grp_dst, out->tile_grp, seen);
+                       reinterpret_cast<const uint32_t *>(tmp_src), ne, out->grp_dst, out->tile_grp, seen,
+                       blocked ? bkey_sorted : nullptr, n_blocks);
     if ((err = hipGetLastError()) != hipSuccess) goto done;
     err = hipStreamSynchronize(nullptr);
 done:
+    for (void *p : {static_cast<void *>(bkey), static_cast<void *>(bkey_sorted), static_cast<void *>(bpos),
+                    static_cast<void *>(bpos_sorted), static_cast<void *>(gstart), static_cast<void *>(src_new)})
+        if (p) (void)hipFree(p);
     if (temp) (void)hipFree(temp);
     if (heads) (void)hipFree(heads);
     if (dst_sorted) (void)hipFree(dst_sorted);

@@ -99,7 +99,7 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
             give_indeg: bool = False, timing: bool = False, max_layers: Optional[int] = None,
             plan: bool = False, plan_chunk: Optional[int] = None, emb_resident: bool = False,
             planned_only: bool = False, hot_slots: int = 0, evict_policy: int = 0,
-            transform_first: bool = False) -> GpuRun:
+            transform_first: bool = False, plan_block: Optional[tuple] = None) -> GpuRun:
     """Drive all layers through the C ABI.  With pinned_host the graph and the
     layer-0 features stay in pinned host memory and are staged by the library.
     planned_only sets ATLAS_FLAG_PLANNED_ONLY (no zero fill of the accumulators;
@@ -122,7 +122,11 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
         atlas.atlas_in_degree(atlas.make_graph(n, e, off_t, col_t, None, res), indeg_t)
     plan_h = None
     if plan:
-        plan_h = atlas.atlas_plan_create(atlas.make_graph(n, e, off_t, col_t, None, res), plan_chunk or case.chunk)
+        pg = atlas.make_graph(n, e, off_t, col_t, None, res)
+        if plan_block:   # (block_sources, hot_min_edges): source-blocked order for the heavy destinations
+            plan_h = atlas.atlas_plan_create_blocked(pg, plan_chunk or case.chunk, plan_block[0], plan_block[1])
+        else:
+            plan_h = atlas.atlas_plan_create(pg, plan_chunk or case.chunk)
     graph = atlas.make_graph(n, e, off_t, col_t, indeg_t, res, plan_h)
     nl = len(case.layers) if max_layers is None else max_layers
     cur_dev = case.X.to(dev)

@@ -223,3 +223,45 @@ def test_half_precision_gin_needs_transform_first(H):
     with pytest.raises(atlas.AtlasError) as ei:
         H.run_gpu(case)
     assert ei.value.status == atlas.E_BAD_DIMS
+
+
+@pytest.mark.parametrize("model,store,lazy", [("sage", torch.bfloat16, True), ("sage", torch.float32, False),
+                                               ("gcn", torch.float32, True), ("gin", torch.float32, True)])
+def test_source_blocked_plan(oracle, H, model, store, lazy):
+    """atlas_plan_create_blocked: destinations that get at least 24 messages from
+    a chunk have that chunk's edges ordered by (block of 128 sources,
+    destination), i.e. up to 16 groups per chunk that all add with atomics;
+    degree-ordered R-MAT scale 13, so the first chunks are full of such hubs."""
+    g = gen.rmat_graph(SEED + 11, 13, 16, self_loops=(model == "gcn"))
+    off, col = gen.build_csr(g)
+    new_of_old, _ = oracle.reorder_indegree_desc(oracle.in_degree(g.n, col.numpy()))
+    g = g.with_relabel(torch.from_numpy(new_of_old.astype(np.int64)))
+    case = H.make_case(model, g, SEED + 11, [128, 128, 64], 2048, store=store,
+                       feat="normal" if store == torch.float32 else "uniform")
+    run = H.run_gpu(case, snapshots=True, plan=True, planned_only=lazy, plan_block=(128, 24))
+    H.check_integers(oracle, case, run, layer=0)
+    H.check_integers(oracle, case, run, layer=1)
+    print("blocked plan", model, H.check_outputs(oracle, case, run))
+    for st in run.stats:
+        assert st["edges_processed"] == case.e and st["vertices_flushed"] == case.n
+
+
+def test_source_blocked_plan_other_paths(oracle, H):
+    """The blocked order through the pinned-host loader, the bounded store and
+    transform-first; GAT refuses such a plan."""
+    import paper_2605_09402_amd as atlas
+    g = gen.rmat_graph(SEED + 12, 12, 16)
+    case = H.make_case("sage", g, SEED + 12, [128, 64], 512, store=torch.bfloat16)
+    H.check_outputs(oracle, case, H.run_gpu(case, plan=True, pinned_host=True, plan_block=(64, 8)))
+    H.check_outputs(oracle, case, H.run_gpu(case, plan=True, transform_first=True, plan_block=(64, 8)))
+    started = int((np.bincount(case.col.numpy(), minlength=case.n) > 0).sum())
+    case2 = H.make_case("sage", gen.rmat_graph(SEED + 12, 12, 16, random_ids=True), SEED + 12, [128, 64], 64)
+    slots = int((np.bincount(case2.col.numpy(), minlength=case2.n) > 0).sum()) // 2
+    ev, rl, peak = oracle.hot_store_trace(case2.off.numpy(), case2.col.numpy(), 64, slots, True)
+    run = H.run_gpu(case2, plan=True, hot_slots=slots, plan_block=(16, 4))
+    H.check_outputs(oracle, case2, run)
+    assert (run.stats[0]["hot_evictions"], run.stats[0]["hot_reloads"]) == (sum(ev), sum(rl)) and started > 0
+    gat = H.make_case("gat", g, SEED + 12, [64, 64], 512, feat="normal", act="elu", heads=2)
+    with pytest.raises(atlas.AtlasError) as ei:
+        H.run_gpu(gat, plan=True, plan_block=(64, 8))
+    assert ei.value.status == atlas.E_BAD_DIMS
