@@ -737,7 +737,12 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
     }
     if ((rc = start_span(L, L->t_agg, s)) != ATLAS_OK) return rc;
     if (pc) {
-        if (L->planned_only) HIP_TRY(launch_zero_cut_first_rows(ga, s));
+        if (L->planned_only) {
+            if (pc->has_zero_rows)   // (device memory also in plans of pinned-host graphs)
+                HIP_TRY(launch_zero_rows(pc->zero_rows, pc->n_zero_rows, ga.acc, ga.slot_of, ga.d, s));
+            else
+                HIP_TRY(launch_zero_cut_first_rows(ga, s));
+        }
         HIP_TRY(launch_aggregate_grouped(ga, s));
     } else {
         HIP_TRY(launch_aggregate(a, s));
@@ -985,6 +990,7 @@ int atlas_plan_destroy(atlas_plan_t *P) {
     for (auto &c : P->chunks) {
         if (c.grp_dst) (void)(P->host ? hipHostFree(c.grp_dst) : hipFree(c.grp_dst));
         if (c.tile_grp) (void)(P->host ? hipHostFree(c.tile_grp) : hipFree(c.tile_grp));
+        if (c.zero_rows) (void)hipFree(c.zero_rows);
     }
     if (P->src_sorted) (void)(P->host ? hipHostFree(P->src_sorted) : hipFree(P->src_sorted));
     delete P;

@@ -97,6 +97,9 @@ struct PlanChunk {
                                   // earlier chunk sends to that destination (its first group of the layer)
     int32_t *tile_grp = nullptr;  // [ceil(n_edges/64)] group of the first edge of every 64-edge tile
     bool blocked = false;         // source-blocked order: grp_dst bit 30 marks destinations with several groups
+    int32_t *zero_rows = nullptr; // device plans: destinations a planned-only layer clears before this chunk (their
+    int64_t n_zero_rows = 0;      // first group is added to with atomics by several waves); may hold duplicates
+    bool has_zero_rows = false;   // false: not precomputed, the launch scans the tile boundaries instead
 };
 
 struct GroupedArgs {
@@ -173,6 +176,9 @@ hipError_t launch_gat_finalize(const GatFinalizeArgs &a, hipStream_t s);
 // their first group.  A first group cut by a tile boundary is added with
 // atomics from several tiles, so its row is zeroed here before the chunk runs.
 hipError_t launch_zero_cut_first_rows(const GroupedArgs &a, hipStream_t s);
+// The same from a list of rows precomputed with the plan.
+hipError_t launch_zero_rows(const int32_t *rows, int64_t n_rows, float *acc, const int32_t *slot_of, int d,
+                            hipStream_t s);
 
 // SAGE self message of sources [b, e): pending[u] -= 1 with ready compaction.
 hipError_t launch_self_message(int64_t b, int64_t e, int32_t *pending, int32_t *ready,

@@ -708,6 +708,20 @@ __global__ __launch_bounds__(kBlock) void k_zero_cut_first_rows(GroupedArgs a) {
     }
 }
 
+// One wave per listed row.
+__global__ __launch_bounds__(kBlock) void k_zero_rows(const int32_t *__restrict__ rows, int64_t n_rows, float *acc,
+                                                     const int32_t *__restrict__ slot_of, int d) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t wave = static_cast<int64_t>(blockIdx.x) * (kBlock / kWave) + (threadIdx.x >> 6);
+    const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (kBlock / kWave);
+    for (int64_t i = wave; i < n_rows; i += nwaves) {
+        int64_t v = rows[i];
+        if (slot_of) v = slot_of[v];
+        float *row = acc + v * d;
+        for (int c = lane; c < d; c += kWave) row[c] = 0.f;
+    }
+}
+
 template <typename T, int MODEL>
 hipError_t launch_grouped_vpl(const GroupedArgs &a, int grid, hipStream_t s) {
     switch (a.d / kWave) {
@@ -774,6 +788,16 @@ hipError_t launch_zero_cut_first_rows(const GroupedArgs &a, hipStream_t s) {
 hipError_t launch_gat_group_max(const GroupedArgs &a, hipStream_t s) {
     if (a.n_edges <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_gat_group_max, dim3(persistent_grid(8)), dim3(kBlock), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_zero_rows(const int32_t *rows, int64_t n_rows, float *acc, const int32_t *slot_of, int d,
+                            hipStream_t s) {
+    if (n_rows <= 0) return hipSuccess;
+    int64_t blocks = (n_rows + (kBlock / kWave) - 1) / (kBlock / kWave);
+    const int cap = persistent_grid(8);
+    if (blocks > cap) blocks = cap;
+    hipLaunchKernelGGL(k_zero_rows, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, s, rows, n_rows, acc, slot_of, d);
     return hipGetLastError();
 }
 

@@ -112,6 +112,28 @@ __global__ void k_apply_order(const uint32_t *__restrict__ pos, const uint32_t *
     src_out[i] = src_in[p] & 0x7fffffff;   // group tails are marked again for the new order
 }
 
+// gstart[g] = position of group g's first edge, from the per-edge group numbers (gidx = group + 1)
+__global__ void k_group_starts_only(const uint32_t *__restrict__ gidx, int64_t n_edges, uint32_t *gstart) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (i >= n_edges) return;
+    if (i == 0 || gidx[i - 1] != gidx[i]) gstart[gidx[i] - 1u] = static_cast<uint32_t>(i);
+}
+
+// The rows a planned-only layer must clear before this chunk runs: destinations whose FIRST group of the
+// layer is added to with atomics by more than one wave -- it is cut by a 64-edge tile boundary, or the
+// destination has one group per source block.  One thread per group; duplicates are harmless.
+__global__ void k_collect_zero_rows(const int32_t *__restrict__ grp_dst, const uint32_t *__restrict__ gstart_of_group,
+                                    int64_t n_groups, int64_t n_edges, int32_t *rows, unsigned int *count) {
+    const int64_t g = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (g >= n_groups) return;
+    const int32_t gd = grp_dst[g];
+    if (gd >= 0) return;                                    // not a first group
+    const int64_t b = gstart_of_group[g];
+    const int64_t e = g + 1 < n_groups ? gstart_of_group[g + 1] : n_edges;   // one past the group's last edge
+    const bool cut = (b >> 6) != ((e - 1) >> 6);
+    if (cut || (gd & 0x40000000)) rows[atomicAdd(count, 1u)] = gd & 0x3fffffff;
+}
+
 struct MaxOp {
     __host__ __device__ int32_t operator()(int32_t a, int32_t b) const { return a > b ? a : b; }
 };
@@ -219,6 +241,31 @@ hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int6
                        reinterpret_cast<const uint32_t *>(tmp_src), ne, out->grp_dst, out->tile_grp, seen,
                        blocked ? bkey_sorted : nullptr, n_blocks);
     if ((err = hipGetLastError()) != hipSuccess) goto done;
+    if (n < (int64_t(1) << 30)) {
+        // rows to clear for planned-only layers (first groups that several waves add to)
+        uint32_t *gs = heads;   // free again: start position of every group
+        unsigned int *cnt = nullptr, n_zero = 0;
+        hipLaunchKernelGGL(k_group_starts_only, dim3(blocks_for(ne)), dim3(kBlock), 0, nullptr,
+                           reinterpret_cast<const uint32_t *>(tmp_src), ne, gs);
+        if ((err = hipMalloc(&cnt, sizeof(unsigned int))) != hipSuccess) goto done;
+        if ((err = hipMemsetAsync(cnt, 0, sizeof(unsigned int), nullptr)) != hipSuccess) { (void)hipFree(cnt); goto done; }
+        // worst case one row per group; the list is trimmed below
+        int32_t *rows = nullptr;
+        if ((err = hipMalloc(&rows, static_cast<size_t>(last) * 4)) != hipSuccess) { (void)hipFree(cnt); goto done; }
+        hipLaunchKernelGGL(k_collect_zero_rows, dim3(blocks_for(last)), dim3(kBlock), 0, nullptr, out->grp_dst, gs,
+                           static_cast<int64_t>(last), ne, rows, cnt);
+        err = hipMemcpy(&n_zero, cnt, sizeof(unsigned int), hipMemcpyDeviceToHost);
+        (void)hipFree(cnt);
+        if (err == hipSuccess && n_zero > 0) {
+            err = hipMalloc(&out->zero_rows, static_cast<size_t>(n_zero) * 4);
+            if (err == hipSuccess)
+                err = hipMemcpy(out->zero_rows, rows, static_cast<size_t>(n_zero) * 4, hipMemcpyDeviceToDevice);
+        }
+        (void)hipFree(rows);
+        if (err != hipSuccess) goto done;
+        out->n_zero_rows = n_zero;
+        out->has_zero_rows = true;
+    }
     err = hipStreamSynchronize(nullptr);
 done:
     for (void *p : {static_cast<void *>(bkey), static_cast<void *>(bkey_sorted), static_cast<void *>(bpos),
@@ -231,8 +278,10 @@ done:
     if (err != hipSuccess) {
         if (out->grp_dst) (void)hipFree(out->grp_dst);
         if (out->tile_grp) (void)hipFree(out->tile_grp);
+        if (out->zero_rows) (void)hipFree(out->zero_rows);
         out->grp_dst = nullptr;
         out->tile_grp = nullptr;
+        out->zero_rows = nullptr;
     }
     return err;
 }
