@@ -60,6 +60,7 @@ __device__ __forceinline__ int64_t wave_find_source(const int64_t *__restrict__ 
 constexpr int kStageFlush = 256;
 constexpr int kStageCap = kStageFlush + kWave;
 
+template <int FLUSH = kStageFlush>
 __device__ __forceinline__ void stage_ready(bool is_ready, int32_t v, int32_t *stage, int &count,
                                             int32_t *ready, int32_t *counters, int lane) {
     const uint64_t m = __ballot(is_ready);
@@ -67,15 +68,15 @@ __device__ __forceinline__ void stage_ready(bool is_ready, int32_t v, int32_t *s
     if (is_ready) stage[count + __popcll(m & ((1ull << lane) - 1ull))] = v;
     count += __popcll(m);
     __builtin_amdgcn_wave_barrier();
-    if (count >= kStageFlush) {
+    if (count >= FLUSH) {
         int base = 0;
-        if (lane == 0) base = atomicAdd(&counters[CTR_READY_TAIL], kStageFlush);
+        if (lane == 0) base = atomicAdd(&counters[CTR_READY_TAIL], FLUSH);
         base = __builtin_amdgcn_readfirstlane(base);
 #pragma unroll
-        for (int k = 0; k < kStageFlush / kWave; ++k) ready[base + k * kWave + lane] = stage[k * kWave + lane];
-        const int rem = count - kStageFlush;
+        for (int k = 0; k < FLUSH / kWave; ++k) ready[base + k * kWave + lane] = stage[k * kWave + lane];
+        const int rem = count - FLUSH;
         int32_t t = 0;
-        if (lane < rem) t = stage[kStageFlush + lane];
+        if (lane < rem) t = stage[FLUSH + lane];
         __builtin_amdgcn_wave_barrier();
         if (lane < rem) stage[lane] = t;
         __builtin_amdgcn_wave_barrier();
@@ -252,22 +253,31 @@ __global__ __launch_bounds__(kBlock) void k_gat_chunk_max(AggregateArgs a) {
 __global__ __launch_bounds__(kBlock) void k_self_message(int64_t b, int64_t e, int32_t *pending,
                                                          int32_t *ready, int32_t *counters) {
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    const int64_t wave = static_cast<int64_t>(blockIdx.x) * (kBlock / kWave) + (threadIdx.x >> 6);
+    const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (kBlock / kWave);
     const int64_t span = e - b;
-    const int64_t rounded = (span + kBlock - 1) / kBlock * kBlock;  // keep whole waves in the loop
-    __shared__ int32_t stage_all[(kBlock / kWave) * kStageCap];
-    int32_t *stage = stage_all + (threadIdx.x >> 6) * kStageCap;
+    // about half the vertices of a power-law graph complete by this message alone: few waves with a large
+    // staging buffer each keep the number of appends to the one ready-tail counter (about 10 ns each,
+    // serialised) down; four independent counts per lane are in flight to cover the latency instead
+    constexpr int kSelfFlush = 2048;
+    constexpr int kPer = 4;
+    __shared__ int32_t stage_all[(kBlock / kWave) * (kSelfFlush + kWave)];
+    int32_t *stage = stage_all + (threadIdx.x >> 6) * (kSelfFlush + kWave);
     int staged = 0;
-    for (int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; i < rounded; i += stride) {
-        bool is_ready = false;
-        int32_t u = 0;
-        if (i < span) {
-            u = static_cast<int32_t>(b + i);
-            const int32_t left_after = pending[u] - 1;
-            pending[u] = left_after;
-            is_ready = left_after == 0;
+    for (int64_t i0 = wave * (kWave * kPer); i0 < span; i0 += nwaves * (kWave * kPer)) {
+        int32_t left[kPer];
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) {
+            const int64_t i = i0 + k * kWave + lane;
+            left[k] = i < span ? pending[b + i] - 1 : -1;
         }
-        stage_ready(is_ready, u, stage, staged, ready, counters, lane);
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) {
+            const int64_t i = i0 + k * kWave + lane;
+            if (i < span) pending[b + i] = left[k];
+            stage_ready<kSelfFlush>(i < span && left[k] == 0, static_cast<int32_t>(b + i), stage, staged, ready,
+                                    counters, lane);
+        }
     }
     drain_ready(stage, staged, ready, counters, lane);
 }
@@ -834,8 +844,8 @@ hipError_t launch_aggregate_grouped(const GroupedArgs &a, hipStream_t s) {
 hipError_t launch_self_message(int64_t b, int64_t e, int32_t *pending, int32_t *ready,
                                int32_t *counters, hipStream_t s) {
     if (e <= b) return hipSuccess;
-    int64_t blocks = (e - b + kBlock - 1) / kBlock;
-    const int cap = persistent_grid(8);
+    int64_t blocks = (e - b + kBlock * 4 - 1) / (kBlock * 4);
+    const int cap = persistent_grid(2);
     if (blocks > cap) blocks = cap;
     hipLaunchKernelGGL(k_self_message, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, s, b, e,
                        pending, ready, counters);
