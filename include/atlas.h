@@ -307,6 +307,16 @@ enum atlas_debug_what {
 };
 int atlas_debug_copy(atlas_layer_t *layer, int what, void *host_dst, int64_t bytes);
 
+/* Launch shape of the planned aggregation (Sec. 3.3, the push of one chunk's
+ * messages): each wave takes runs of `tiles` consecutive 64-edge tiles of the
+ * chunk's destination-ordered edge list and keeps a destination's partial sum
+ * in registers from one tile of a run to the next.  0 (the default) lets the
+ * library choose from the chunk's size (1 for small chunks, up to 16); 1..16
+ * forces that length for every later launch of the process, which is how the
+ * tests reach the long-run path on small graphs.  Results do not depend on it
+ * beyond fp32 summation order.  Errors: E_RANGE. */
+int atlas_set_tiles_per_run(int tiles);
+
 /* Free the device buffers the library keeps for reuse between layers. */
 int atlas_release_cache(void);
 

@@ -31,7 +31,7 @@ EXPORTS = [
     "atlas_layer_init", "atlas_attention_prepass", "atlas_broadcast_chunk", "atlas_flush_ready",
     "atlas_layer_finish", "atlas_in_degree", "atlas_reorder_indegree_desc", "atlas_debug_copy",
     "atlas_release_cache", "atlas_strerror", "atlas_last_hip_error", "atlas_plan_create", "atlas_plan_destroy",
-    "atlas_reorder_score_desc", "atlas_sample_in_edges", "atlas_plan_create_blocked",
+    "atlas_reorder_score_desc", "atlas_sample_in_edges", "atlas_plan_create_blocked", "atlas_set_tiles_per_run",
 ]
 
 
@@ -100,6 +100,7 @@ def lib() -> ctypes.CDLL:
         L.atlas_reorder_score_desc.argtypes = [ctypes.POINTER(atlas_graph_t), vp, vp]
         L.atlas_sample_in_edges.argtypes = [ctypes.POINTER(atlas_graph_t), vp, i32, vp, vp, ctypes.POINTER(i64)]
         L.atlas_debug_copy.argtypes = [vp, i32, vp, i64]
+        L.atlas_set_tiles_per_run.argtypes = [ctypes.c_int]
         L.atlas_release_cache.argtypes = []
         L.atlas_plan_create.argtypes = [ctypes.POINTER(atlas_graph_t), i64, ctypes.POINTER(vp)]
         L.atlas_plan_create_blocked.argtypes = [ctypes.POINTER(atlas_graph_t), i64, i64, i64, ctypes.POINTER(vp)]
@@ -234,6 +235,10 @@ def atlas_sample_in_edges(graph: atlas_graph_t, edge_key, fanout: int, out_row_o
 def atlas_debug_copy(layer: int, what: int, host_array) -> None:
     """host_array: a numpy array (contiguous) that receives the bytes."""
     _check(lib().atlas_debug_copy(layer, what, host_array.ctypes.data, host_array.nbytes), "atlas_debug_copy")
+
+
+def atlas_set_tiles_per_run(tiles: int) -> None:
+    _check(lib().atlas_set_tiles_per_run(int(tiles)), "atlas_set_tiles_per_run")
 
 
 def atlas_release_cache() -> None:

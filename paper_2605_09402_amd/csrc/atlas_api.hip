@@ -1088,6 +1088,12 @@ int atlas_release_cache(void) {
     return ATLAS_OK;
 }
 
+int atlas_set_tiles_per_run(int tiles) {
+    if (tiles < 0 || tiles > atlas::kMaxTilesPerRun) return ATLAS_E_RANGE;
+    atlas::set_tiles_per_run(tiles);
+    return ATLAS_OK;
+}
+
 const char *atlas_strerror(int status) {
     switch (status) {
         case ATLAS_OK: return "ok";

@@ -126,7 +126,12 @@ struct GroupedArgs {
                                 // several groups in this chunk (all of them add with atomics); else 0
     float *scores = nullptr;    // GAT only: [n_edges][heads] attention logits of the chunk's edges, written
                                 // by the max sweep and read by the aggregation
+    int tiles_per_run = 1;      // consecutive 64-edge tiles one wave takes at a time (set by the launcher)
 };
+
+// forced run length of the grouped aggregation, 0 = chosen per launch
+void set_tiles_per_run(int tiles);
+constexpr int kMaxTilesPerRun = 16;
 
 // S2+S3+S4 over a planned chunk: per-destination register sums, one row update
 // and one pending decrement per (chunk, destination) group.

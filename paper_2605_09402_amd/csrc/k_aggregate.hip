@@ -15,6 +15,7 @@
 #include "atlas_kernels.h"
 
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <type_traits>
 
 namespace atlas {
@@ -348,18 +349,23 @@ __device__ __forceinline__ void load_row(const T *__restrict__ p, float (&x)[VPL
     }
 }
 
+// Accumulator rows are touched once per chunk: their loads and stores carry
+// the streaming hint so that they displace as little as possible in L2.
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
 template <int VPL>
 __device__ __forceinline__ void row_add_owned(float *p, const float (&x)[VPL]) {
     if constexpr (VPL == 2) {
-        float2 v = *reinterpret_cast<float2 *>(p);
-        v.x += x[0]; v.y += x[1];
-        *reinterpret_cast<float2 *>(p) = v;
+        f32x2_t v = __builtin_nontemporal_load(reinterpret_cast<f32x2_t *>(p));
+        v[0] += x[0]; v[1] += x[1];
+        __builtin_nontemporal_store(v, reinterpret_cast<f32x2_t *>(p));
     } else if constexpr (VPL == 4 || VPL == 8) {
 #pragma unroll
         for (int q = 0; q < VPL / 4; ++q) {
-            float4 v = *reinterpret_cast<float4 *>(p + 4 * q);
-            v.x += x[4 * q]; v.y += x[4 * q + 1]; v.z += x[4 * q + 2]; v.w += x[4 * q + 3];
-            *reinterpret_cast<float4 *>(p + 4 * q) = v;
+            f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<f32x4_t *>(p + 4 * q));
+            v[0] += x[4 * q]; v[1] += x[4 * q + 1]; v[2] += x[4 * q + 2]; v[3] += x[4 * q + 3];
+            __builtin_nontemporal_store(v, reinterpret_cast<f32x4_t *>(p + 4 * q));
         }
     } else {
 #pragma unroll
@@ -370,11 +376,14 @@ __device__ __forceinline__ void row_add_owned(float *p, const float (&x)[VPL]) {
 template <int VPL>
 __device__ __forceinline__ void row_store(float *p, const float (&x)[VPL]) {
     if constexpr (VPL == 2) {
-        *reinterpret_cast<float2 *>(p) = make_float2(x[0], x[1]);
+        f32x2_t v; v[0] = x[0]; v[1] = x[1];
+        __builtin_nontemporal_store(v, reinterpret_cast<f32x2_t *>(p));
     } else if constexpr (VPL == 4 || VPL == 8) {
 #pragma unroll
-        for (int q = 0; q < VPL / 4; ++q)
-            *reinterpret_cast<float4 *>(p + 4 * q) = make_float4(x[4 * q], x[4 * q + 1], x[4 * q + 2], x[4 * q + 3]);
+        for (int q = 0; q < VPL / 4; ++q) {
+            f32x4_t v; v[0] = x[4 * q]; v[1] = x[4 * q + 1]; v[2] = x[4 * q + 2]; v[3] = x[4 * q + 3];
+            __builtin_nontemporal_store(v, reinterpret_cast<f32x4_t *>(p + 4 * q));
+        }
     } else {
 #pragma unroll
         for (int i = 0; i < VPL; ++i) p[i] = x[i];
@@ -411,14 +420,26 @@ __device__ __forceinline__ void row_add_shared(float *p, const float (&x)[VPL]) 
     for (int i = 0; i < VPL; ++i) unsafeAtomicAdd(p + i, x[i]);
 }
 
+// Second half of a tile's pending-count update: `old` is what the lane's read
+// (or atomic) returned.  The sole writer stores the new count here.
+__device__ __forceinline__ void finish_pending(bool closes, bool shared, int32_t old, int32_t c, int32_t dst,
+                                               const GroupedArgs &a, int32_t *stage, int &staged, int lane) {
+    bool is_ready = false;
+    if (closes) {
+        is_ready = old == c;
+        if (!shared) a.pending[dst] = old - c;
+    }
+    stage_ready(is_ready, dst, stage, staged, a.ready, a.counters, lane);
+}
+
 template <typename T, int VPL, int MODEL>
-__global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VPL <= 2 && MODEL != 2 ? 8 : 1, 8))) void k_aggregate_grouped(GroupedArgs a) {
     constexpr int D = VPL * kWave;
     constexpr int U = 8;  // source rows in flight per wave
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t wave = static_cast<int64_t>(blockIdx.x) * (kBlock / kWave) + (threadIdx.x >> 6);
-    const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (kBlock / kWave);
-    const int64_t ntiles = (a.n_edges + kTileEdges - 1) / kTileEdges;
+    const int wave = blockIdx.x * (kBlock / kWave) + (threadIdx.x >> 6);
+    const int nwaves = gridDim.x * (kBlock / kWave);
+    const int ntiles = static_cast<int>((a.n_edges + kTileEdges - 1) / kTileEdges);  // < 2^31: checked by the launcher
     const T *__restrict__ emb = static_cast<const T *>(a.emb);
     __shared__ int32_t stage_all[(kBlock / kWave) * kStageCap];
     int32_t *stage = stage_all + (threadIdx.x >> 6) * kStageCap;
@@ -430,27 +451,87 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
     if (wave == 0 && lane == 0)
         atomicAdd(&a.counters64[CTR64_EDGES], static_cast<unsigned long long>(a.n_edges));
 
-    for (int64_t t = wave; t < ntiles; t += nwaves) {
-        const int64_t e0 = t * kTileEdges;
+    // A wave takes runs of `run` consecutive tiles.  A group that is open at
+    // the end of a tile stays in the wave's registers when the next tile is
+    // the wave's own, so a long group costs one shared add per run, not per tile.
+    //
+    // The loop is software-pipelined: a tile's edge words, first group index
+    // and group destinations are fetched while the tile before it gathers
+    // rows, and the result of a tile's pending-count reads is consumed during
+    // the next tile, so that the only memory waits on the wave's critical
+    // path are those of the row gathers.
+    const int run = a.tiles_per_run;
+    const int nruns = (ntiles + run - 1) / run;
+    float sum[VPL];
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) sum[i] = 0.f;
+    float lsum = 0.f;
+    // `cut`: other waves may add to the current group's destination row
+    // (the group began before this run); it persists from tile to tile.
+    bool cut = false;
+    bool open_prev = false;
+
+    // the tile in hand (fetched ahead)
+    int rn = wave;
+    int t = rn < nruns ? rn * run : -1;
+    int t_end = t + run < ntiles ? t + run : ntiles;
+    bool run_start = true;
+    int32_t s = 0, g0 = 0, prev_word = -1, gd = 0;
+    if (t >= 0) {
+        const int64_t e0 = static_cast<int64_t>(t) * kTileEdges;
         const int64_t left = a.n_edges - e0;
         const int cnt = left < kTileEdges ? static_cast<int>(left) : kTileEdges;
-        const int g0 = a.tile_grp[t];
-        int32_t s = 0;
         if (lane < cnt) s = a.src_sorted[e0 + lane];
+        g0 = a.tile_grp[t];
+        if (e0 > 0) prev_word = a.src_sorted[e0 - 1];
+        const bool is_end = lane < cnt && s < 0;
+        const uint64_t below = __ballot(is_end) & ((1ull << lane) - 1ull);
+        if (is_end || lane == cnt - 1) gd = a.grp_dst[g0 + __popcll(below)];
+    }
+    // pending-count update of the tile before, not yet consumed
+    bool pd_closes = false, pd_shared = false;
+    int32_t pd_old = 0, pd_c = 0, pd_dst = 0;
+
+    while (t >= 0) {
+        // which tile comes next, and its edge words
+        int rn_n = rn, t_n = t + 1, t_end_n = t_end;
+        bool run_start_n = false;
+        if (t_n == t_end) {
+            rn_n = rn + nwaves;
+            t_n = rn_n < nruns ? rn_n * run : -1;
+            t_end_n = t_n + run < ntiles ? t_n + run : ntiles;
+            run_start_n = true;
+        }
+        int32_t s_n = 0, g0_n = 0, prev_word_n = -1, gd_n = 0;
+        int cnt_n = 0;
+        if (t_n >= 0) {
+            const int64_t e0n = static_cast<int64_t>(t_n) * kTileEdges;
+            const int64_t leftn = a.n_edges - e0n;
+            cnt_n = leftn < kTileEdges ? static_cast<int>(leftn) : kTileEdges;
+            if (lane < cnt_n) s_n = a.src_sorted[e0n + lane];
+            g0_n = a.tile_grp[t_n];
+            prev_word_n = a.src_sorted[e0n - 1];   // e0n > 0: the wave's first tile was fetched above
+        }
+        bool ahead_done = false;
+
+        const int64_t e0 = static_cast<int64_t>(t) * kTileEdges;
+        const int64_t left = a.n_edges - e0;
+        const int cnt = left < kTileEdges ? static_cast<int>(left) : kTileEdges;
         const bool is_end = lane < cnt && s < 0;
         const uint64_t endmask = __ballot(is_end);
         const int src = s & 0x7fffffff;
         // the tile's first group continues one that started in an earlier tile?
-        bool cut = false;
-        if (e0 > 0) cut = a.src_sorted[e0 - 1] >= 0;
-        const bool cut0 = cut;
+        bool cut0 = open_prev;
+        if (run_start) {
+            cut = prev_word >= 0;
+            cut0 = cut;
+        }
         const uint64_t below = endmask & ((1ull << lane) - 1ull);
         const bool closes = is_end || lane == cnt - 1;  // last edge of a group, or of the tile
         int32_t dstv = 0;
         bool first_touch = false;  // no earlier chunk sent to this destination: its row holds nothing yet
         bool multi = false;        // source-blocked chunk: other groups of this launch address the same destination
         if (closes) {
-            const int32_t gd = a.grp_dst[g0 + __popcll(below)];
             first_touch = gd < 0;
             multi = (gd & a.multi_bit) != 0;
             dstv = gd & 0x7fffffff & ~a.multi_bit;
@@ -469,7 +550,6 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
         // GAT: every lane's elements belong to one head (dh is a multiple of VPL)
         const int hl = MODEL == 2 ? (lane * VPL) / a.gat.dh : 0;
         const bool head_first = MODEL == 2 && (lane * VPL) % a.gat.dh == 0;
-        float lsum = 0.f;
         if (MODEL == 2) {
             // lane e: weights of edge e for every head, exp(logit - new maximum of its destination) <= 1;
             // the destination is held by the lane that closes the edge's group
@@ -483,10 +563,18 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
             __builtin_amdgcn_wave_barrier();   // the weights are read across lanes below
         }
 
-        float sum[VPL];
-#pragma unroll
-        for (int i = 0; i < VPL; ++i) sum[i] = 0.f;
         for (int j0 = 0; j0 < cnt; j0 += U) {
+            if (j0 == U) {
+                // the words fetched before the first batch have arrived with it
+                ahead_done = true;
+                if (t_n >= 0) {
+                    const bool is_end_n = lane < cnt_n && s_n < 0;
+                    const uint64_t below_n = __ballot(is_end_n) & ((1ull << lane) - 1ull);
+                    if (is_end_n || lane == cnt_n - 1) gd_n = a.grp_dst[g0_n + __popcll(below_n)];
+                }
+                finish_pending(pd_closes, pd_shared, pd_old, pd_c, pd_dst, a, stage, staged, lane);
+                pd_closes = false;
+            }
             float r[U][VPL];
             float wgt[U];
 #pragma unroll
@@ -545,32 +633,44 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_grouped(GroupedArgs a) {
                 }
             }
         }
-        if (!((endmask >> (cnt - 1)) & 1ull)) {  // open group: continues in the next tile
+        open_prev = !((endmask >> (cnt - 1)) & 1ull);
+        if (open_prev && t + 1 == t_end) {  // open group that continues in another wave's tile
             const int32_t v = __builtin_amdgcn_readlane(dstv, cnt - 1);
             row_add_shared<VPL>(a.acc + static_cast<int64_t>(__builtin_amdgcn_readlane(rowv, cnt - 1)) * D + lane * VPL, sum);
             if (MODEL == 2 && head_first)
                 unsafeAtomicAdd(a.gat.l + static_cast<int64_t>(v) * a.gat.heads + hl, lsum);
+#pragma unroll
+            for (int q = 0; q < VPL; ++q) sum[q] = 0.f;
+            lsum = 0.f;
+        }
+        if (!ahead_done) {   // a tile of one batch (the chunk's last)
+            if (t_n >= 0) {
+                const bool is_end_n = lane < cnt_n && s_n < 0;
+                const uint64_t below_n = __ballot(is_end_n) & ((1ull << lane) - 1ull);
+                if (is_end_n || lane == cnt_n - 1) gd_n = a.grp_dst[g0_n + __popcll(below_n)];
+            }
+            finish_pending(pd_closes, pd_shared, pd_old, pd_c, pd_dst, a, stage, staged, lane);
         }
 
         // pending count: minus the number of this tile's messages to the group.
         // A group that lies wholly inside the tile is the only writer of its
         // destination's count during this kernel, so a plain read-modify-write
-        // is enough; pieces of a cut group use the atomic.
-        bool is_ready = false;
+        // is enough; pieces of a cut group use the atomic.  The value read is
+        // used (and the plain write made) while the next tile gathers.
+        pd_closes = closes;
+        pd_dst = dstv;
         if (closes) {
             const int prev_end = below ? 63 - __clzll(static_cast<long long>(below)) : -1;
-            const int c = lane - prev_end;
-            const bool shared = (below == 0 && cut0) || !is_end || multi;
-            if (shared) {
-                is_ready = atomicSub(&a.pending[dstv], c) == c;
-            } else {
-                const int32_t left_after = a.pending[dstv] - c;
-                a.pending[dstv] = left_after;
-                is_ready = left_after == 0;
-            }
+            pd_c = lane - prev_end;
+            pd_shared = (below == 0 && cut0) || !is_end || multi;
+            if (pd_shared) pd_old = atomicSub(&a.pending[dstv], pd_c);
+            else pd_old = a.pending[dstv];
         }
-        stage_ready(is_ready, dstv, stage, staged, a.ready, a.counters, lane);
+
+        rn = rn_n; t = t_n; t_end = t_end_n; run_start = run_start_n;
+        s = s_n; g0 = g0_n; prev_word = prev_word_n; gd = gd_n;
     }
+    finish_pending(pd_closes, pd_shared, pd_old, pd_c, pd_dst, a, stage, staged, lane);
     drain_ready(stage, staged, a.ready, a.counters, lane);
 }
 
@@ -732,8 +832,19 @@ __global__ __launch_bounds__(kBlock) void k_zero_rows(const int32_t *__restrict_
     }
 }
 
+std::atomic<int> g_tiles_per_run{0};
+
 template <typename T, int MODEL>
-hipError_t launch_grouped_vpl(const GroupedArgs &a, int grid, hipStream_t s) {
+hipError_t launch_grouped_vpl(const GroupedArgs &a_in, int grid, hipStream_t s) {
+    GroupedArgs a = a_in;
+    // runs of several tiles only where every wave still gets many runs
+    const int64_t ntiles = (a.n_edges + kTileEdges - 1) / kTileEdges;
+    const int64_t nwaves = static_cast<int64_t>(grid) * (kBlock / kWave);
+    const int64_t fit = ntiles / (4 * nwaves);
+    a.tiles_per_run = static_cast<int>(fit < 1 ? 1 : fit > kMaxTilesPerRun ? kMaxTilesPerRun : fit);
+    const int forced = g_tiles_per_run.load(std::memory_order_relaxed);
+    if (forced > 0) a.tiles_per_run = forced;
+    if (ntiles > 0x7fffffff) return hipErrorInvalidValue;   // tile indices are 32-bit in the kernel
     switch (a.d / kWave) {
         case 1: hipLaunchKernelGGL((k_aggregate_grouped<T, 1, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
         case 2: hipLaunchKernelGGL((k_aggregate_grouped<T, 2, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
@@ -773,6 +884,8 @@ int persistent_grid(int blocks_per_cu) {
 }
 
 }  // namespace
+
+void set_tiles_per_run(int tiles) { g_tiles_per_run.store(tiles, std::memory_order_relaxed); }
 
 hipError_t launch_aggregate(const AggregateArgs &a, hipStream_t s) {
     if (a.d % kWave != 0) return hipErrorInvalidValue;
