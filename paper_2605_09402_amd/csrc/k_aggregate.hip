@@ -285,13 +285,14 @@ __global__ __launch_bounds__(kBlock) void k_self_message(int64_t b, int64_t e, i
 
 // ---- planned chunk: edges regrouped by destination --------------------------
 //
-// A wave owns 64 consecutive edges of the chunk's destination-ordered edge
-// list.  Every edge is one coalesced read of its source row; the rows of one
-// destination are summed in registers and reach the accumulator as a single
-// row update.  A destination whose edges all lie inside the tile is touched by
-// this wave only (plain read-add-write); a group cut by a tile boundary is
-// added with atomics by every tile that holds a piece of it.  The pending
-// count drops by the group's size (its piece, for a cut group) in one step.
+// A tile is 64 consecutive edges of the chunk's destination-ordered edge list
+// and a wave owns runs of consecutive tiles.  Every edge is one coalesced read
+// of its source row; the rows of one destination are summed in registers and
+// reach the accumulator as a single row update.  A destination whose edges all
+// lie inside one run is touched by this wave only (plain read-add-write); a
+// group cut by a run boundary is added with atomics by every run that holds a
+// piece of it.  The pending count drops tile by tile, by the size of the
+// group's piece in the tile.
 
 template <typename T, int VPL>
 __device__ __forceinline__ void load_row(const T *__restrict__ p, float (&x)[VPL]) {
@@ -433,7 +434,13 @@ __device__ __forceinline__ void finish_pending(bool closes, bool shared, int32_t
 }
 
 template <typename T, int VPL, int MODEL>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VPL <= 2 && MODEL != 2 ? 8 : 1, 8))) void k_aggregate_grouped(GroupedArgs a) {
+// The kernel is latency-bound on the row gathers.  Instantiations whose eight
+// rows in flight take at most 16 registers are held to all 8 waves of a SIMD
+// (scalar registers beyond that budget spill to lanes, nothing to memory), the
+// narrow GAT ones to 6.
+__global__ __launch_bounds__(kBlock)
+__attribute__((amdgpu_waves_per_eu(MODEL == 2 ? (VPL <= 2 ? 6 : 1) : (VPL * sizeof(T) <= 8 ? 8 : 1), 8)))
+void k_aggregate_grouped(GroupedArgs a) {
     constexpr int D = VPL * kWave;
     constexpr int U = 8;  // source rows in flight per wave
     const int lane = threadIdx.x & (kWave - 1);

@@ -273,14 +273,19 @@ def gpu_reorder(off, col):
     return new_of_old
 
 
-def run_workload_layer1(wl, plan: bool, emb_resident: bool = False, planned_only: bool = False):
+def run_workload_layer1(wl, plan: bool, emb_resident: bool = False, planned_only: bool = False, plan_block=None):
     """Layer 1 of a device-resident workload through the C ABI, flush after
-    every chunk.  Returns (out, stats, indeg, final pending, ready list)."""
+    every chunk.  plan_block = (block_sources, hot_min_edges) builds the
+    source-blocked plan.  Returns (out, stats, indeg, final pending, ready list)."""
     dev = wl.off.device
     n, e = wl.n, wl.e
     indeg = torch.empty(n, dtype=torch.int32, device=dev)
     atlas.atlas_in_degree(atlas.make_graph(n, e, wl.off, wl.col), indeg)
-    plan_h = atlas.atlas_plan_create(atlas.make_graph(n, e, wl.off, wl.col), wl.chunk) if plan else None
+    plan_h = None
+    if plan and plan_block:
+        plan_h = atlas.atlas_plan_create_blocked(atlas.make_graph(n, e, wl.off, wl.col), wl.chunk, *plan_block)
+    elif plan:
+        plan_h = atlas.atlas_plan_create(atlas.make_graph(n, e, wl.off, wl.col), wl.chunk)
     graph = atlas.make_graph(n, e, wl.off, wl.col, indeg, atlas.RESIDENT_DEVICE, plan_h)
     sdt = _dt(wl.store)
     p = wl.layers[0]

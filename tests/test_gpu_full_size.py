@@ -19,8 +19,8 @@ def H():
     return harness
 
 
-def _go(oracle, H, wl, plan=True, emb_resident=False, n_random=1 << 14):
-    out, stats, indeg, pend, ready = H.run_workload_layer1(wl, plan, emb_resident)
+def _go(oracle, H, wl, plan=True, emb_resident=False, n_random=1 << 14, planned_only=False, plan_block=None):
+    out, stats, indeg, pend, ready = H.run_workload_layer1(wl, plan, emb_resident, planned_only, plan_block)
     H.check_layer_counters(wl, stats, pend, ready)
     err, nd, ne = H.sampled_layer1_check(oracle, wl, out, indeg, n_random=n_random)
     print("%s plan=%s: sampled %d destinations / %d in-edges, error %.3e" % (wl.name, plan, nd, ne, err))
@@ -54,7 +54,12 @@ def test_config4_gat_scale22(oracle, H):
 
 
 def test_config5_sage_scale26_bf16(oracle, H):
-    """The benchmark's workload and launch configuration."""
+    """The benchmark's workload and launch configuration: resident embeddings,
+    every chunk planned (no zero fill at the layer start), source-blocked plan
+    with 2 MiB of source rows per block and 32 messages per block as the
+    threshold for a blocked destination."""
     wl = workloads.config5("cuda:0", reorder=H.gpu_reorder)
     assert wl.n == 1 << 26 and wl.e == 1 << 31 and wl.chunk == 1 << 22
-    _go(oracle, H, wl, emb_resident=True, n_random=1 << 15)
+    block = (2 << 20) // (wl.dims[0] * 2)
+    _go(oracle, H, wl, emb_resident=True, n_random=1 << 15, planned_only=True,
+        plan_block=(block, 32 * (wl.chunk // block)))
