@@ -48,6 +48,9 @@ def main() -> int:
                          "(default: 32 per block of the chunk)")
     ap.add_argument("--d-in", type=int, default=512, help="workload wide: input feature width (up to 1024 with "
                                                           "--transform-first, 512 without)")
+    ap.add_argument("--store", choices=["bf16", "f16"], default="bf16",
+                    help="config5 / wide: 16-bit storage format of features, weights and outputs (f16 = IEEE half, "
+                         "half-precision MFMA in the update)")
     ap.add_argument("--transform-first", action="store_true",
                     help="apply W to each chunk before it is pushed (d_out-wide messages and accumulators)")
     ap.add_argument("--hot-slots-frac", type=float, default=0.0,
@@ -106,21 +109,22 @@ def main() -> int:
     t0 = time.time()
     ck = None if args.chunk_log2 is None else 1 << args.chunk_log2
     ro = None if args.order == "original" else reorder
+    store = torch.float16 if args.store == "f16" else torch.bfloat16
     if args.workload == "config5":
         if args.scale is None:
             args.scale = 26
         wl = workloads.config5(dev, scale=args.scale, reorder=ro, edge_factor=args.edge_factor, chunk=ck,
-                               model=args.layer_type)
+                               model=args.layer_type, store=store)
     elif args.workload == "config2":
         wl = workloads.config2(dev, scale=args.scale or 20, reorder=ro, chunk=ck)
     elif args.workload == "wide":
-        wl = workloads.wide(dev, scale=args.scale or 22, d_in=args.d_in, reorder=ro, chunk=ck)
+        wl = workloads.wide(dev, scale=args.scale or 22, d_in=args.d_in, reorder=ro, chunk=ck, store=store)
     elif args.workload == "config3":
         wl = workloads.config3(dev, scale=args.scale or 22, chunk=ck)
     else:
         wl = workloads.config4(dev, scale=args.scale or 22, chunk=ck)
     is_headline = (args.workload == "config5" and args.scale == 26 and args.edge_factor == 32 and ck is None
-                   and args.layer_type == "sage")
+                   and args.layer_type == "sage" and args.store == "bf16")
     torch.cuda.synchronize()
     n, e, chunk = wl.n, wl.e, wl.chunk
     log("generated %s: N=%d E=%d chunk=%d in %.1f s" % (wl.name, n, e, chunk, time.time() - t0))
@@ -291,8 +295,8 @@ def main() -> int:
     upd_s = upd_ms / args.steps / 1e3
     update = {
         "kernel": "k_update", "tflops": round(upd_flops / upd_s / 1e12, 2),
-        "mfma_peak_tflops": 2500.0 if sdt == atlas.DTYPE_BF16 else 157.3,
-        "frac_of_mfma_peak": round(upd_flops / upd_s / (2.5e15 if sdt == atlas.DTYPE_BF16 else 157.3e12), 4),
+        "mfma_peak_tflops": 2500.0 if sdt in (atlas.DTYPE_BF16, atlas.DTYPE_F16) else 157.3,
+        "frac_of_mfma_peak": round(upd_flops / upd_s / (2.5e15 if sdt in (atlas.DTYPE_BF16, atlas.DTYPE_F16) else 157.3e12), 4),
         # accumulator rows are read only for vertices that received something
         "hbm_GBps": round((n_with_in * 4 * d + n * ((s_in * d if wl.model in ("sage", "gin") else 0) + s_in * wl.dims[1]))
                           / upd_s / 1e9, 1),
@@ -343,7 +347,7 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "ms_per_step_median": round(sorted(step_ms)[len(step_ms) // 2], 3), "ms_per_step_min": round(min(step_ms), 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 storage / f32 accumulate" if sdt == atlas.DTYPE_BF16 else "f32",
+        "dtype": {atlas.DTYPE_BF16: "bf16 storage / f32 accumulate", atlas.DTYPE_F16: "f16 storage / f32 accumulate"}.get(sdt, "f32"),
         "data": "synthetic",
         "config": {"workload": wl.name, "layer_type": wl.model, "vertices": n, "edges": e, "d_in": wl.dims[0], "d_out": wl.dims[1],
                    "chunk_sources": chunk, "chunks": nchunks, "flush": "after every chunk",

@@ -47,6 +47,10 @@ class Workload:
 Reorder = Callable[[torch.Tensor, torch.Tensor], torch.Tensor]
 
 
+def _short(store: torch.dtype) -> str:
+    return {torch.bfloat16: "bf16", torch.float16: "f16", torch.float32: "fp32"}[store]
+
+
 def _finish(name, model, g: EdgeSource, seed, dims, chunk, feat, store, act, device, heads=1,
             reorder: Optional[Reorder] = None) -> Workload:
     off, col = build_csr(g, device)
@@ -96,21 +100,22 @@ def config4(device="cpu", scale: int = 22, chunk: Optional[int] = None) -> Workl
 
 
 def config5(device="cpu", scale: int = 26, reorder: Optional[Reorder] = None, chunk: Optional[int] = None,
-            edge_factor: int = 32, model: str = "sage") -> Workload:
+            edge_factor: int = 32, model: str = "sage", store: torch.dtype = torch.bfloat16) -> Workload:
     """Large GraphSAGE-mean on R-MAT, bf16, d = 128, degree-ordered ids
-    (model="gin": the same graph and widths through GIN layers)."""
+    (model="gin": the same graph and widths through GIN layers; store=float16:
+    IEEE half storage, the format of the paper's larger feature sets)."""
     seed = SEED0 + 5
     g = rmat_graph(seed, scale, edge_factor, device=device)
-    return _finish("config5_%s_rmat%d_bf16" % (model, scale), model, g, seed, [128, 128, 128, 64],
-                   chunk or max(64, (1 << scale) // 16), "uniform", torch.bfloat16, "relu", device, reorder=reorder)
+    return _finish("config5_%s_rmat%d_%s" % (model, scale, _short(store)), model, g, seed, [128, 128, 128, 64],
+                   chunk or max(64, (1 << scale) // 16), "uniform", store, "relu", device, reorder=reorder)
 
 
 def wide(device="cpu", scale: int = 22, d_in: int = 512, reorder: Optional[Reorder] = None,
-         chunk: Optional[int] = None) -> Workload:
+         chunk: Optional[int] = None, store: torch.dtype = torch.bfloat16) -> Workload:
     """Wide 16-bit input features into a narrow hidden layer, the shape of the first
     layer on the paper's MAG240M / IGB feature sets (768 / 1024 wide, Sec. 4.1):
     GraphSAGE-mean d_in -> 128 -> 128 on R-MAT, bf16, edge factor 16."""
     seed = SEED0 + 6
     g = rmat_graph(seed, scale, 16, device=device)
-    return _finish("wide%d_sage_rmat%d_bf16" % (d_in, scale), "sage", g, seed, [d_in, 128, 128],
-                   chunk or max(64, (1 << scale) // 16), "uniform", torch.bfloat16, "relu", device, reorder=reorder)
+    return _finish("wide%d_sage_rmat%d_%s" % (d_in, scale, _short(store)), "sage", g, seed, [d_in, 128, 128],
+                   chunk or max(64, (1 << scale) // 16), "uniform", store, "relu", device, reorder=reorder)
