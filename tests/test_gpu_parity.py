@@ -302,3 +302,27 @@ def test_runs_of_consecutive_tiles(oracle, H, model, store, tiles):
     with pytest.raises(atlas.AtlasError) as ei:
         atlas.atlas_set_tiles_per_run(17)
     assert ei.value.status == atlas.E_RANGE
+
+
+@pytest.mark.parametrize("model,store,dims", [
+    ("sage", torch.bfloat16, [192, 64, 48]),
+    ("sage", torch.bfloat16, [320, 128, 80]),
+    ("sage", torch.bfloat16, [448, 192, 112]),
+    ("sage", torch.float32, [192, 128, 16]),
+    ("gcn", torch.float32, [320, 64, 48]),
+    ("gcn", torch.float32, [384, 192, 144]),
+    ("gcn", torch.bfloat16, [448, 64, 16]),
+    ("gin", torch.float32, [192, 64, 48]),
+])
+@pytest.mark.parametrize("plan", [False, True])
+def test_odd_widths(oracle, H, model, store, dims, plan):
+    """Input widths that are multiples of 64 but not powers of two (3, 5, 6 and 7
+    elements per lane) and last-layer output widths that are odd multiples of
+    16, through both aggregation kernels and the generic update kernel.  R-MAT
+    scale 11."""
+    g = gen.rmat_graph(SEED + 15, 11, 16, self_loops=(model == "gcn"))
+    case = H.make_case(model, g, SEED + 15, dims, 300, store=store,
+                       feat="normal" if store == torch.float32 else "uniform", eps=0.5 if model == "gin" else 0.0)
+    run = H.run_gpu(case, snapshots=True, plan=plan)
+    H.check_integers(oracle, case, run, layer=0)
+    print("odd widths", model, dims, H.check_outputs(oracle, case, run))
