@@ -90,8 +90,11 @@ enum atlas_flags {
                                     commutes with the neighbour sum), so messages and accumulators are
                                     d_out wide instead of d_in.  Pays when d_out is well below d_in (wide
                                     input features); d_in may then be up to 1024 (fp32 embeddings: 512)
-                                    and d_out must be a multiple of 64.  Results equal the default order
-                                    up to fp32 rounding.  Ignored for other models and residencies. */
+                                    and d_out must be a multiple of 64.  The pushed products are messages
+                                    and travel in the embeddings' storage type (SAGE_MEAN, GCN_SYM; GIN
+                                    pushes fp32), sums stay fp32: results equal the default order up to
+                                    one rounding of each product to that type.  Ignored for other models
+                                    and residencies. */
 };
 
 /* The graph: CSR by SOURCE vertex (paper Sec. 3.2: out-edges, read sequentially

@@ -153,7 +153,7 @@ struct atlas_layer {
 
     // transform-first layers
     bool tf = false;
-    Buf tf_z;       // [chunk][d_out] fp32: the chunk's rows times W (SAGE: W_neigh)
+    Buf tf_z;       // [chunk][d_out] in the storage type: the chunk's rows times W (SAGE: W_neigh)
     Buf tf_self;    // [N][d_out] fp32: SAGE x_v W_self, GIN x_v W
     Buf packed_w2;  // SAGE: W_self in fragment order
 
@@ -624,6 +624,10 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         u.identity_rows = src_end - src_begin;
         float *self_rows_out = L->tf_self.p ? static_cast<float *>(L->tf_self.p) + static_cast<size_t>(src_begin) * d.d_out
                                             : nullptr;
+        // The products that are pushed are messages: they travel in the storage type of the embeddings
+        // (half the bytes per edge for 16-bit storage).  A vertex's own product is read once and stays
+        // fp32; GIN pushes that same buffer.
+        const int push_dt = d.model == ATLAS_MODEL_GIN ? 0 : d.in_dtype;
         if (d.model == ATLAS_MODEL_SAGE_MEAN) {
             const size_t half = packed_weight_bytes(L->K, d.d_out, L->compute_dt);
             if (d.d_out % 32 == 0 && 2 * d.d_out <= 256) {
@@ -632,25 +636,30 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
                 u.d_out = 2 * d.d_out;
                 u.split = d.d_out;
                 u.out = L->tf_z.p;
+                u.out_dt = push_dt;
                 u.out2 = self_rows_out;
+                u.out2_dt = 0;
                 HIP_TRY(launch_update(u, s));
             } else {
                 u.packed_w = L->packed_w2.p;
                 u.out = L->tf_z.p;
+                u.out_dt = push_dt;
                 HIP_TRY(launch_update(u, s));
                 u.packed_w = static_cast<char *>(L->packed_w2.p) + half;
                 u.out = self_rows_out;
+                u.out_dt = 0;
                 HIP_TRY(launch_update(u, s));
             }
         } else {
             u.packed_w = L->packed_w.p;
             u.out = d.model == ATLAS_MODEL_GIN ? static_cast<void *>(self_rows_out) : L->tf_z.p;
+            u.out_dt = push_dt;
             HIP_TRY(launch_update(u, s));
         }
         if ((rc = end_span(L, L->t_self, s)) != ATLAS_OK) return rc;
         a.emb = d.model == ATLAS_MODEL_GIN ? static_cast<const void *>(self_rows_out) : L->tf_z.p;
         a.d = d.d_out;
-        a.in_dt = 0;
+        a.in_dt = push_dt;
     }
     if (d.model == ATLAS_MODEL_GAT) {
         // transform the chunk (z = x W on the matrix cores), raise the running

@@ -221,6 +221,7 @@ struct UpdateArgs {
     void *out2;               // split > 0: columns split.. of the product go to out2 (column - split) and
     int split;                // columns below split to out, both with rows of `split` columns (a product
                               // with two weight matrices side by side); 0: one output of d_out columns
+    int out2_dt;              // element type of out2 (out_dt is that of out)
     int64_t n;
     const int32_t *slot_of;   // bounded store: row of `acc` that holds vertex v (nullptr: row v)
     int64_t identity_rows;    // > 0: no ready list; rows 0..identity_rows-1 of `acc` (a dense

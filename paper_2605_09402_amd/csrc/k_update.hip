@@ -152,21 +152,23 @@ __device__ __forceinline__ void store_block_row(const UpdateArgs &a, const f32x1
     // two weight matrices side by side: the block lies wholly in one of the two outputs
     void *outp = a.out;
     int cols = a.d_out;
+    int odt = a.out_dt;
     if (a.split > 0) {
         cols = a.split;
         if (nbase >= a.split) {
             outp = a.out2;
+            odt = a.out2_dt;
             nbase -= a.split;
         }
     }
     const int limit = a.split > 0 ? a.split : a.d_out;
-    if (a.out_dt) {
+    if (odt) {
         uint16_t *o = static_cast<uint16_t *>(outp) + out_row * cols + nbase;
 #pragma unroll
         for (int q = 0; q < 4; ++q)
             if (nbase + 8 * q < limit)
                 *reinterpret_cast<uint2 *>(o + 8 * q) =
-                    make_uint2(pack2_dt(a.out_dt, y[4 * q], y[4 * q + 1]), pack2_dt(a.out_dt, y[4 * q + 2], y[4 * q + 3]));
+                    make_uint2(pack2_dt(odt, y[4 * q], y[4 * q + 1]), pack2_dt(odt, y[4 * q + 2], y[4 * q + 3]));
     } else {
         float *o = static_cast<float *>(outp) + out_row * cols + nbase;
 #pragma unroll
