@@ -795,40 +795,64 @@ hipError_t launch_pipelined_c(const UpdateArgs &a, int grid, hipStream_t s) {
 
 // Transform-first layers: one wave per ready row, four columns per lane and round.
 __global__ __launch_bounds__(kBlock) void k_sum_finalize(SumFinalizeArgs a) {
-    const int lane = threadIdx.x & 63;
-    const int64_t wave = static_cast<int64_t>(blockIdx.x) * (kBlock / 64) + (threadIdx.x >> 6);
-    const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (kBlock / 64);
+    // One thread per (ready row, run of four columns), four such items in
+    // flight per thread: the vertex ids of all four are read first, then their
+    // degrees and rows, so a thread waits for memory three times per four
+    // items instead of three times per item.
+    constexpr int U = 4;
     const int head = a.counters[CTR_READY_HEAD];
     const int tail = a.counters[CTR_READY_TAIL];
     const int d = a.d_out;
-    for (int64_t i = head + wave; i < tail; i += nwaves) {
-        const int64_t v = a.ready[i];
-        const int32_t deg = a.indeg[v];
-        const float fd = static_cast<float>(deg > 0 ? deg : 1);
-        const float g = a.norm == 0 ? 1.0f / fd : (a.norm == 1 ? 1.0f / sqrtf(fd) : 1.0f);
-        const int64_t arow = a.slot_of ? static_cast<int64_t>(a.slot_of[v]) : v;
-        for (int c = lane * 4; c < d; c += 256) {
-            float y[4] = {0.f, 0.f, 0.f, 0.f};
-            if (deg > 0) {   // the accumulator of a vertex without in-edges was never written
-                const float4 x = *reinterpret_cast<const float4 *>(a.acc + arow * d + c);
-                y[0] = x.x * g; y[1] = x.y * g; y[2] = x.z * g; y[3] = x.w * g;
-            }
-            if (a.self_term) {
-                const float4 t = *reinterpret_cast<const float4 *>(a.self_term + v * d + c);
-                y[0] += a.self_scale * t.x; y[1] += a.self_scale * t.y;
-                y[2] += a.self_scale * t.z; y[3] += a.self_scale * t.w;
-            }
+    const int quads = d / 4;
+    const int64_t total = static_cast<int64_t>(tail - head) * quads;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    for (int64_t it0 = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; it0 < total; it0 += U * stride) {
+        int64_t v[U];
+        int c[U];
+        bool live[U];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                if (a.bias) y[k] += a.bias[c + k];
-                if (a.activation == 1) y[k] = fmaxf(y[k], 0.f);
-                else if (a.activation == 2) y[k] = y[k] > 0.f ? y[k] : expm1f(y[k]);
+        for (int k = 0; k < U; ++k) {
+            int64_t it = it0 + k * stride;
+            live[k] = it < total;
+            if (!live[k]) it = it0;          // a valid item; its result is dropped
+            c[k] = static_cast<int>(it % quads) * 4;
+            v[k] = a.ready[head + it / quads];
+        }
+        int32_t deg[U];
+        int64_t arow[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            deg[k] = a.indeg[v[k]];
+            arow[k] = a.slot_of ? static_cast<int64_t>(a.slot_of[v[k]]) : v[k];
+        }
+        float4 x[U], t[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            x[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+            t[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (deg[k] > 0)   // the accumulator of a vertex without in-edges was never written
+                x[k] = *reinterpret_cast<const float4 *>(a.acc + arow[k] * d + c[k]);
+            if (a.self_term) t[k] = *reinterpret_cast<const float4 *>(a.self_term + v[k] * d + c[k]);
+        }
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            const float fd = static_cast<float>(deg[k] > 0 ? deg[k] : 1);
+            const float g = a.norm == 0 ? 1.0f / fd : (a.norm == 1 ? 1.0f / sqrtf(fd) : 1.0f);
+            float y[4] = {x[k].x * g + a.self_scale * t[k].x, x[k].y * g + a.self_scale * t[k].y,
+                          x[k].z * g + a.self_scale * t[k].z, x[k].w * g + a.self_scale * t[k].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (a.bias) y[e] += a.bias[c[k] + e];
+                if (a.activation == 1) y[e] = fmaxf(y[e], 0.f);
+                else if (a.activation == 2) y[e] = y[e] > 0.f ? y[e] : expm1f(y[e]);
             }
+            if (!live[k]) continue;
             if (a.out_dt)
-                *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(a.out) + v * d + c) =
+                *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(a.out) + v[k] * d + c[k]) =
                     make_uint2(pack2_dt(a.out_dt, y[0], y[1]), pack2_dt(a.out_dt, y[2], y[3]));
             else
-                *reinterpret_cast<float4 *>(static_cast<float *>(a.out) + v * d + c) = make_float4(y[0], y[1], y[2], y[3]);
+                *reinterpret_cast<float4 *>(static_cast<float *>(a.out) + v[k] * d + c[k]) =
+                    make_float4(y[0], y[1], y[2], y[3]);
         }
     }
 }
@@ -950,7 +974,9 @@ hipError_t launch_sum_finalize(const SumFinalizeArgs &a, hipStream_t s) {
     if (hipGetDevice(&dev) == hipSuccess)
         (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (cus <= 0) cus = 256;
-    int64_t blocks = (a.n + (kBlock / 64) - 1) / (kBlock / 64);
+    const int64_t items = a.n * (a.d_out / 4);            // a.n bounds the rows the ready list holds
+    int64_t blocks = (items + 4 * kBlock - 1) / (4 * kBlock);
+    if (blocks < 1) blocks = 1;
     if (blocks > static_cast<int64_t>(cus) * 8) blocks = static_cast<int64_t>(cus) * 8;
     hipLaunchKernelGGL(k_sum_finalize, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, s, a);
     return hipGetLastError();
