@@ -457,6 +457,109 @@ __global__ __launch_bounds__(kGenBlock, 4) void k_update(UpdateArgs a) {
     }
 }
 
+// ---- dense transform: contiguous 16-bit rows times W, K-sliced ---------------
+//
+// The chunk transform of the transform-first order multiplies a dense block
+// of rows (up to 1024 wide) by W.  The generic kernel stages whole rows (one
+// workgroup per CU at that width) and every wave streams its W fragments from
+// L2 once per 64 rows, which is what bounds it.  Here a workgroup of 8 waves
+// owns 128 rows and walks K in slices of 64 columns: the next slice of the
+// rows is in flight from HBM to registers (and the wave's next W fragments
+// from L2) while the matrix cores work on the current one out of a
+// double-buffered LDS tile of 2 x 18 KB, two workgroups per CU.  Wave w
+// computes all 128 rows times column block w, so a W fragment is fetched once
+// per 128 rows.
+constexpr int kDenseRows = 128;
+constexpr int kDenseSlice = 64;
+constexpr int kDenseStride = kDenseSlice + 8;   // elements; 144 B rows keep 16-byte reads aligned and spread banks
+constexpr int kDenseBlock = 512;
+constexpr int kDenseMB = kDenseRows / 32;
+
+template <int CT>
+__global__ __launch_bounds__(kDenseBlock, 2) void k_dense_transform(UpdateArgs a) {
+    static_assert(CT == 1 || CT == 2, "16-bit compute types only");
+    using frag_t = typename Frag<CT>::type;
+    __shared__ __align__(16) uint16_t A[2][kDenseRows * kDenseStride];
+    const int K = a.K;
+    const int KS = K / 16;                     // k-steps of one matrix instruction
+    const int nslices = K / kDenseSlice;
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+    const int NB = (a.d_out + 31) / 32;
+    const bool works = w < NB;
+    const int nb = works ? w : NB - 1;         // waves past the last column block compute and discard
+    const int64_t n = a.identity_rows;
+    const int64_t ntiles = (n + kDenseRows - 1) / kDenseRows;
+    const uint16_t *X = static_cast<const uint16_t *>(a.self_rows);
+    const uint16_t *Wp = static_cast<const uint16_t *>(a.packed_w) + (static_cast<size_t>(nb) * KS * 64 + lane) * 8;
+
+    // staging: thread t moves 16 bytes of row t / 8 (and of row 64 + t / 8), columns (t % 8) * 8 .. + 7 of the slice
+    const int st_row = threadIdx.x >> 3;
+    const int st_col = (threadIdx.x & 7) * 8;
+    const int a_off = (lane & 31) * kDenseStride + (lane >> 5) * 8;
+
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t row0 = tile * kDenseRows;
+        int64_t r0 = row0 + st_row, r1 = row0 + 64 + st_row;
+        if (r0 >= n) r0 = n - 1;               // rows past the end read the last row; their results are dropped
+        if (r1 >= n) r1 = n - 1;
+        const uint16_t *x0 = X + r0 * K + st_col;
+        const uint16_t *x1 = X + r1 * K + st_col;
+        auto load_w = [&](int slice, frag_t (&f)[4]) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                f[u] = *reinterpret_cast<const frag_t *>(Wp + static_cast<size_t>(slice * 4 + u) * 64 * 8);
+        };
+
+        f32x16_t c[kDenseMB];
+#pragma unroll
+        for (int m = 0; m < kDenseMB; ++m)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) c[m][r] = 0.f;
+
+        frag_t wcur[4];
+        load_w(0, wcur);
+        uint4 g0 = *reinterpret_cast<const uint4 *>(x0);
+        uint4 g1 = *reinterpret_cast<const uint4 *>(x1);
+        *reinterpret_cast<uint4 *>(&A[0][st_row * kDenseStride + st_col]) = g0;
+        *reinterpret_cast<uint4 *>(&A[0][(64 + st_row) * kDenseStride + st_col]) = g1;
+        __syncthreads();
+        for (int sl = 0; sl < nslices; ++sl) {
+            const bool more = sl + 1 < nslices;
+            frag_t wnxt[4];
+            if (more) {
+                g0 = *reinterpret_cast<const uint4 *>(x0 + (sl + 1) * kDenseSlice);
+                g1 = *reinterpret_cast<const uint4 *>(x1 + (sl + 1) * kDenseSlice);
+            }
+            load_w(more ? sl + 1 : sl, wnxt);  // the last slice re-reads itself
+            const uint16_t *Ab = A[sl & 1] + a_off;
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int m = 0; m < kDenseMB; ++m) {
+                    const frag_t av = *reinterpret_cast<const frag_t *>(Ab + m * 32 * kDenseStride + u * 16);
+                    c[m] = mfma_block<CT>(wcur[u], av, c[m]);
+                }
+            if (more) {
+                uint16_t *An = A[(sl + 1) & 1];
+                *reinterpret_cast<uint4 *>(&An[st_row * kDenseStride + st_col]) = g0;
+                *reinterpret_cast<uint4 *>(&An[(64 + st_row) * kDenseStride + st_col]) = g1;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) wcur[u] = wnxt[u];
+            __syncthreads();   // the slice just written is complete; the one just read may be overwritten
+        }
+
+        if (works) {
+#pragma unroll
+            for (int m = 0; m < kDenseMB; ++m) {
+                const int64_t row = row0 + m * 32 + (lane & 31);
+                if (row < n) store_block_row<false>(a, c[m], row, nb * 32 + 4 * (lane >> 5), nullptr);
+            }
+        }
+    }
+}
+
 // ---- pipelined variant: W resident in LDS, double-buffered A tile -----------
 //
 // Used when d_in <= 128 and W plus two A tiles fit in LDS.  One workgroup of
@@ -946,6 +1049,18 @@ hipError_t launch_update(const UpdateArgs &a, hipStream_t s) {
     if (hipGetDevice(&dev) == hipSuccess)
         (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (cus <= 0) cus = 256;
+    if (a.model == 4 && a.compute_dt != 0 && a.in_dt == a.compute_dt && a.identity_rows > 0 && a.K == a.d_in &&
+        a.K % kDenseSlice == 0 && a.activation == 0 && !a.bias && a.d_out > 128) {
+        // a dense block of 16-bit rows times a W of more than four column blocks: the K-sliced kernel
+        if (a.d_out > 256 || a.d_in > 1024) return hipErrorInvalidValue;
+        int64_t grid = static_cast<int64_t>(cus) * 2;
+        const int64_t max_tiles = (a.identity_rows + kDenseRows - 1) / kDenseRows;
+        if (grid > max_tiles) grid = max_tiles;
+        const dim3 g(static_cast<unsigned>(grid)), b(kDenseBlock);
+        if (a.compute_dt == 1) hipLaunchKernelGGL((k_dense_transform<1>), g, b, 0, s, a);
+        else hipLaunchKernelGGL((k_dense_transform<2>), g, b, 0, s, a);
+        return hipGetLastError();
+    }
     if (a.model != 4 && a.d_in <= 128 && pipelined_lds_bytes(a.K, a.d_out, a.compute_dt != 0) <= 160 * 1024) {
         int64_t grid = cus;
         const int64_t max_tiles = (a.n + kTileRows - 1) / kTileRows;
