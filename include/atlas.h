@@ -144,7 +144,10 @@ typedef struct {
  * id, and an evicted vertex is reloaded when a later chunk addresses it.  Rows
  * are released by the atlas_flush_ready that writes the vertex's output, so the
  * rows needed at once are the chunk's destinations plus the completed vertices
- * not yet flushed; atlas_broadcast_chunk returns E_NOMEM when they do not fit.
+ * not yet flushed; atlas_broadcast_chunk returns E_NOMEM when they do not fit
+ * (the chunk is then partly marked and the layer can only be finished, which
+ * frees it; a smaller chunk size, more rows or an order that completes vertices
+ * sooner, such as atlas_reorder_score_desc, is the remedy).
  * Requires a DEVICE graph with a plan and chunks that coincide with the planned
  * ones (as with ATLAS_FLAG_PLANNED_ONLY); not available for GAT.  Each chunk
  * costs one wait for the stream (the host reads the slot counts). */
