@@ -62,6 +62,9 @@ def main() -> int:
     ap.add_argument("--edge-factor", type=int, default=32)
     ap.add_argument("--no-plan", action="store_true", help="push straight from the CSR (atomic path)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--side-stream", action="store_true", help="run on a non-default stream")
+    ap.add_argument("--sync-chunks", action="store_true",
+                    help="wait for the device after every chunk (no copy / compute overlap): times the stages alone")
     ap.add_argument("--no-e2e", action="store_true", help="skip the three-layer end-to-end run")
     ap.add_argument("--sample-dst", type=int, default=1 << 16, help="destinations in the oracle sample")
     ap.add_argument("--residency", choices=["device", "pinned"], default="device",
@@ -186,6 +189,8 @@ def main() -> int:
         hot_slots = max(1, int(args.hot_slots_frac * int((indeg > 0).sum().item())))
         log("bounded store: %d slots (%.0f%% of the vertices with an in-edge)" % (hot_slots, 100 * args.hot_slots_frac))
 
+    chunk_wall_ms = []   # --sync-chunks: wall time of every chunk (copy + kernels), all layers run so far
+
     def run_layer(li: int, x: torch.Tensor, timing: bool) -> dict:
         d_in, d_out = wl.dims[li], wl.dims[li + 1]
         act = atlas.ACT_NONE if li + 1 == len(wl.layers) else between
@@ -203,8 +208,12 @@ def main() -> int:
         atlas.atlas_flush_ready(h, out, stream)
         for b0 in range(0, n, chunk):
             b1 = min(n, b0 + chunk)
+            tc = time.perf_counter()
             atlas.atlas_broadcast_chunk(h, b0, b1, x[b0:b1], stream)
             atlas.atlas_flush_ready(h, out, stream)
+            if args.sync_chunks:
+                torch.cuda.synchronize()
+                chunk_wall_ms.append((time.perf_counter() - tc) * 1e3)
         return atlas.atlas_layer_finish(h)
 
     if args.traffic_calibration:
@@ -215,6 +224,14 @@ def main() -> int:
             cb.copy_(ca)
         torch.cuda.synchronize()
         del ca, cb
+
+    if args.side_stream:
+        # The layers run on a stream of their own.  Only from here on: the set-up above calls the
+        # library's synchronous helpers (plan, ordering), which work on the default stream and do not
+        # wait for work queued on other non-blocking streams.
+        torch.cuda.synchronize()
+        stream = torch.cuda.Stream()
+        torch.cuda.set_stream(stream)
 
     # ---- warm-up, then exactly K timed steps ----
     for _ in range(args.warmup):
@@ -241,6 +258,11 @@ def main() -> int:
     launches = nchunks * args.steps
     log("layer: %.2f ms/step; aggregate %.2f, update %.2f, self %.2f, init %.2f ms per step"
         % (ms_per_step, agg_ms / args.steps, upd_ms / args.steps, self_ms / args.steps, init_ms / args.steps))
+    if args.sync_chunks:
+        log("last layer, ms per chunk (copy + kernels, no overlap): " + " ".join("%.1f" % v for v in chunk_wall_ms[-nchunks:]))
+    if copy_ms > 0:
+        log("chunk loader: %.1f GB per layer in %.1f ms on the copy stream = %.1f GB/s"
+            % (h2d_bytes / 1e9, copy_ms / args.steps, h2d_bytes / (copy_ms / args.steps) / 1e6))
 
     # ---- end-to-end: all three layers once ----
     e2e_ms = None

@@ -24,6 +24,11 @@
  * atlas_status code and has no partial effect when it rejects its arguments.
  * A layer object must be used from one host thread at a time, and all calls on
  * one layer must be given the same HIP stream (or streams the caller orders).
+ * The functions documented as "Synchronous" (plans, orderings, sampling) take
+ * no stream: they work on the default stream and return when their result is
+ * complete, but they do not wait for work the caller has queued on other
+ * non-blocking streams, so arrays written there must be complete before the
+ * call (synchronise that stream first).
  */
 #ifndef ATLAS_H
 #define ATLAS_H
