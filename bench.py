@@ -306,6 +306,8 @@ def main() -> int:
         "achieved": round(achieved, 1), "peak": peak, "unit": "GB/s", "frac": round(achieved / peak, 4),
         "traffic": traffic,
         "traffic_GBps": None if traffic is None else round(traffic * nchunks / agg_s_per_layer / 1e9, 1),
+        # measured HBM bytes per second over the peak: what the kernel really draws from memory
+        "traffic_frac_of_peak": None if traffic is None else round(traffic * nchunks / agg_s_per_layer / 1e9 / peak, 4),
         "launches": launches, "avg_launch_ms": round(agg_ms / launches, 4),
         "algorithmic_bytes_per_edge": bytes_per_edge, "algorithmic_bytes_per_source": bytes_per_source,
         "edges_per_s_in_kernel": round(e / agg_s_per_layer, 1),
