@@ -269,3 +269,25 @@ def test_accumulators_alone(oracle, H, atlas, model, plan):
         scale = 1.0 / np.sqrt(oracle.in_degree(n, case.col.numpy()).astype(np.float64))
     ref = oracle.neighbor_sum(il, case.X.numpy(), scale)
     assert H.row_rel_err(acc.astype(np.float64), ref) <= 1e-5
+
+
+def test_non_default_stream(oracle, H):
+    """Every layer call on a non-blocking stream of the caller's (not the default
+    stream): device and pinned-host residency, GAT, the bounded store.  The plan
+    is built (on the default stream, synchronously) from arrays that are complete
+    before the call."""
+    import gen
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        g = gen.rmat_graph(SEED + 31, 12, 16)
+        sage = H.make_case("sage", g, SEED + 31, [128, 128, 64], 300, store=torch.bfloat16)
+        print("side stream sage", H.check_outputs(oracle, sage, H.run_gpu(sage, plan=True, planned_only=True)))
+        print("side stream sage pinned", H.check_outputs(oracle, sage, H.run_gpu(sage, plan=True, pinned_host=True)))
+        print("side stream sage csr", H.check_outputs(oracle, sage, H.run_gpu(sage, pinned_host=True, flush_every=3)))
+        gat = H.make_case("gat", g, SEED + 31, [64, 64, 64], 300, feat="normal", act="elu", heads=2)
+        print("side stream gat", H.check_outputs(oracle, gat, H.run_gpu(gat, plan=True)))
+        rnd = H.make_case("sage", gen.rmat_graph(SEED + 31, 12, 16, random_ids=True), SEED + 31, [128, 64], 64)
+        slots = int((np.bincount(rnd.col.numpy(), minlength=rnd.n) > 0).sum()) // 2
+        print("side stream bounded", H.check_outputs(oracle, rnd, H.run_gpu(rnd, plan=True, hot_slots=slots)))
+    torch.cuda.synchronize()
