@@ -167,10 +167,16 @@ struct atlas_layer {
 
     // pinned-host loader
     hipStream_t copy_stream = nullptr;
-    hipEvent_t slot_loaded[2] = {nullptr, nullptr};
-    hipEvent_t slot_free[2] = {nullptr, nullptr};
-    bool slot_used[2] = {false, false};
-    Buf stage_col[2], stage_emb[2];
+    // Staging ring of the chunk loader.  With four slots the copies of the chunks after a long one
+    // (the first chunk of a degree-ordered graph: 75 ms of kernels at scale 26) keep going while its
+    // kernels run; with two the copy stream sat idle for most of that time.  A slot's edge buffer is
+    // allocated for the first chunk that needs it and grows on demand, so only the slots that ever
+    // see a large chunk are large.
+    static constexpr int kStageSlots = 4;
+    hipEvent_t slot_loaded[kStageSlots] = {};
+    hipEvent_t slot_free[kStageSlots] = {};
+    bool slot_used[kStageSlots] = {};
+    Buf stage_col[kStageSlots], stage_emb[kStageSlots];
 
     std::vector<TimedSpan> t_agg, t_self, t_upd, t_copy, t_init;
     hipStream_t last_stream = nullptr;
@@ -179,14 +185,16 @@ struct atlas_layer {
 
     void destroy() {
         for (Buf *b : {&indeg_own, &pending, &ready, &counters, &counters64, &acc, &self_rows, &packed_w, &bias,
-                       &dev_off, &stage_col[0], &stage_col[1], &stage_emb[0], &stage_emb[1], &gat_el, &gat_er,
+                       &dev_off, &gat_el, &gat_er,
                        &gat_mcur, &gat_mnext, &gat_l, &gat_wa, &gat_z, &gat_scores, &hs_slot_of, &hs_owner, &hs_free,
                        &hs_stamp, &hs_need, &hs_ctr, &hs_keys, &hs_keys_sorted, &hs_sort_temp, &tf_z, &tf_self,
                        &packed_w2})
             b->release();
+        for (Buf &b : stage_col) b.release();
+        for (Buf &b : stage_emb) b.release();
         for (auto *v : {&t_agg, &t_self, &t_upd, &t_copy, &t_init})
             for (auto &sp : *v) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < kStageSlots; ++i) {
             if (slot_loaded[i]) (void)hipEventDestroy(slot_loaded[i]);
             if (slot_free[i]) (void)hipEventDestroy(slot_free[i]);
         }
@@ -348,7 +356,7 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
         // row offsets are small next to the edge array: keep a device copy for the kernels
         HIP_TRY(L->dev_off.alloc((n1 + 1) * sizeof(int64_t)));
         HIP_TRY(loader_stream(&L->copy_stream));
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < atlas_layer::kStageSlots; ++i) {
             HIP_TRY(hipEventCreateWithFlags(&L->slot_loaded[i], hipEventDisableTiming));
             HIP_TRY(hipEventCreateWithFlags(&L->slot_free[i], hipEventDisableTiming));
         }
@@ -363,18 +371,10 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
         HIP_TRY(hipStreamWaitEvent(s, L->slot_loaded[0], 0));
         L->off_dev = static_cast<const int64_t *>(L->dev_off.p);
         L->bytes_h2d += (n + 1) * static_cast<int64_t>(sizeof(int64_t));
-        // size the edge staging slots for the largest aligned chunk
-        int64_t max_edges = 0;
-        const int64_t C = d.max_chunk_sources;
-        for (int64_t b = 0; b < n; b += C) {
-            const int64_t e = std::min(n, b + C);
-            max_edges = std::max(max_edges, L->g.row_offsets[e] - L->g.row_offsets[b]);
-        }
-        size_t slot_bytes = static_cast<size_t>(std::max<int64_t>(max_edges, 1)) * sizeof(int32_t);
-        if (L->g.plan && L->g.plan->host) slot_bytes = std::max(slot_bytes, L->g.plan->max_stage_bytes);
-        for (int i = 0; i < 2; ++i) {
-            HIP_TRY(L->stage_col[i].alloc(slot_bytes));
-            if (!has_self_term(d.model))
+        // edge staging slots are allocated by the first chunk that uses them (atlas_broadcast_chunk)
+        if (!has_self_term(d.model)) {
+            const int64_t C = d.max_chunk_sources;
+            for (int i = 0; i < atlas_layer::kStageSlots; ++i)
                 HIP_TRY(L->stage_emb[i].alloc(static_cast<size_t>(std::min(C, std::max<int64_t>(n, 1))) * d.d_in *
                                               dtype_size(d.in_dtype)));
         }
@@ -556,11 +556,11 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         // Stage the chunk into HBM on the copy stream; the compute stream only
         // waits for this chunk's event, so the copy of chunk k+1 (enqueued by
         // the next call) overlaps the kernels of chunk k.
-        slot = static_cast<int>(L->num_chunks & 1);
+        slot = static_cast<int>(L->num_chunks % atlas_layer::kStageSlots);
         const int64_t e0 = L->g.row_offsets[src_begin], e1 = L->g.row_offsets[src_end];
         const size_t col_bytes = pc ? stage_bytes_of(*pc) : static_cast<size_t>(e1 - e0) * sizeof(int32_t);
-        if (col_bytes > L->stage_col[slot].bytes) {
-            // a chunk larger than any aligned one: wait for the slot, then grow it
+        if (!L->stage_col[slot].p || col_bytes > L->stage_col[slot].bytes) {
+            // first use of the slot, or a chunk larger than those it has held: wait for the slot, then grow it
             if (L->slot_used[slot]) HIP_TRY(hipEventSynchronize(L->slot_free[slot]));
             Buf bigger;
             HIP_TRY(bigger.alloc(col_bytes));
