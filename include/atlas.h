@@ -256,7 +256,9 @@ int atlas_layer_finish(atlas_layer_t *layer, atlas_layer_stats_t *stats);
  * lives: device memory for DEVICE graphs; library-owned pinned host memory for
  * PINNED_HOST graphs (each chunk's CSR slice is staged into HBM, regrouped
  * there and brought back; atlas_broadcast_chunk then streams the regrouped
- * chunk instead of the CSR slice).  It must outlive the layers that use it.
+ * chunk instead of the CSR slice; with chunks of at most 2^23 sources a
+ * pinned-host plan keeps 3 bytes per edge, which is what crosses the host link
+ * in every layer).  It must outlive the layers that use it.
  * graph->plan and graph->in_degree are ignored here. */
 int atlas_plan_create(const atlas_graph_t *graph, int64_t chunk_sources, atlas_plan_t **out);
 

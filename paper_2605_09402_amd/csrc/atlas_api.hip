@@ -117,14 +117,17 @@ struct atlas_plan {
     int64_t n = 0, e = 0, chunk = 0;
     bool host = false;              // arrays live in pinned host memory (plan of a PINNED_HOST graph)
     int32_t *src_sorted = nullptr;  // [E] destination-ordered source ids of all chunks
+    uint8_t *src_packed = nullptr;  // host plans with chunks of at most 2^23 sources: the same words in 3 bytes
+    size_t packed_bytes = 0;        // (PlanChunk::packed_off locates a chunk's words); src_sorted is then unused
     bool blocked = false;           // some chunk is in source-blocked order (grp_dst bit 30 in use)
     std::vector<PlanChunk> chunks;  // grp_dst / tile_grp: device, or pinned host when `host`
     size_t max_stage_bytes = 0;     // host plans: largest staging slot any chunk needs
 };
 
 namespace {
-size_t stage_bytes_of(const PlanChunk &c) {
-    return round_up(static_cast<size_t>(c.n_edges) * 4, 256) + round_up(static_cast<size_t>(c.n_groups) * 4, 256) +
+size_t stage_bytes_of(const PlanChunk &c, bool packed) {
+    const size_t words = packed ? packed24_bytes(c.n_edges) : static_cast<size_t>(c.n_edges) * 4;
+    return round_up(words, 256) + round_up(static_cast<size_t>(c.n_groups) * 4, 256) +
            round_up(static_cast<size_t>((c.n_edges + 63) / 64) * 4, 256);
 }
 }  // namespace
@@ -153,6 +156,7 @@ struct atlas_layer {
 
     // transform-first layers
     bool tf = false;
+    Buf unpacked;   // pinned-host plans with 24-bit edge words: the current chunk's words as the kernels read them
     Buf tf_z;       // [chunk][d_out] in the storage type: the chunk's rows times W (SAGE: W_neigh)
     Buf tf_self;    // [N][d_out] fp32: SAGE x_v W_self, GIN x_v W
     Buf packed_w2;  // SAGE: W_self in fragment order
@@ -187,7 +191,7 @@ struct atlas_layer {
         for (Buf *b : {&indeg_own, &pending, &ready, &counters, &counters64, &acc, &self_rows, &packed_w, &bias,
                        &dev_off, &gat_el, &gat_er,
                        &gat_mcur, &gat_mnext, &gat_l, &gat_wa, &gat_z, &gat_scores, &hs_slot_of, &hs_owner, &hs_free,
-                       &hs_stamp, &hs_need, &hs_ctr, &hs_keys, &hs_keys_sorted, &hs_sort_temp, &tf_z, &tf_self,
+                       &hs_stamp, &hs_need, &hs_ctr, &hs_keys, &hs_keys_sorted, &hs_sort_temp, &tf_z, &tf_self, &unpacked,
                        &packed_w2})
             b->release();
         for (Buf &b : stage_col) b.release();
@@ -558,7 +562,8 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         // the next call) overlaps the kernels of chunk k.
         slot = static_cast<int>(L->num_chunks % atlas_layer::kStageSlots);
         const int64_t e0 = L->g.row_offsets[src_begin], e1 = L->g.row_offsets[src_end];
-        const size_t col_bytes = pc ? stage_bytes_of(*pc) : static_cast<size_t>(e1 - e0) * sizeof(int32_t);
+        const bool packed = pc && plan->src_packed;
+        const size_t col_bytes = pc ? stage_bytes_of(*pc, packed) : static_cast<size_t>(e1 - e0) * sizeof(int32_t);
         if (!L->stage_col[slot].p || col_bytes > L->stage_col[slot].bytes) {
             // first use of the slot, or a chunk larger than those it has held: wait for the slot, then grow it
             if (L->slot_used[slot]) HIP_TRY(hipEventSynchronize(L->slot_free[slot]));
@@ -576,11 +581,13 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         if (pc) {
             // planned chunk: its regrouped edges travel instead of the CSR slice (same 4 bytes per edge)
             char *base = static_cast<char *>(L->stage_col[slot].p);
-            const size_t sb = static_cast<size_t>(pc->n_edges) * 4, gb = static_cast<size_t>(pc->n_groups) * 4,
-                         tb = static_cast<size_t>((pc->n_edges + 63) / 64) * 4;
+            const size_t sb = packed ? packed24_bytes(pc->n_edges) : static_cast<size_t>(pc->n_edges) * 4,
+                         gb = static_cast<size_t>(pc->n_groups) * 4, tb = static_cast<size_t>((pc->n_edges + 63) / 64) * 4;
             char *g_dev = base + round_up(sb, 256), *t_dev = g_dev + round_up(gb, 256);
             if (sb) {
-                HIP_TRY(hipMemcpyAsync(base, plan->src_sorted + pc->edge_base, sb, hipMemcpyHostToDevice, L->copy_stream));
+                const void *words = packed ? static_cast<const void *>(plan->src_packed + pc->packed_off)
+                                           : static_cast<const void *>(plan->src_sorted + pc->edge_base);
+                HIP_TRY(hipMemcpyAsync(base, words, sb, hipMemcpyHostToDevice, L->copy_stream));
                 HIP_TRY(hipMemcpyAsync(g_dev, pc->grp_dst, gb, hipMemcpyHostToDevice, L->copy_stream));
                 HIP_TRY(hipMemcpyAsync(t_dev, pc->tile_grp, tb, hipMemcpyHostToDevice, L->copy_stream));
             }
@@ -597,6 +604,17 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         if (rc != ATLAS_OK) return rc;
         HIP_TRY(hipEventRecord(L->slot_loaded[slot], L->copy_stream));
         HIP_TRY(hipStreamWaitEvent(s, L->slot_loaded[slot], 0));
+        if (packed && pc->n_edges > 0) {
+            // 24-bit words as they came over the link -> the 32-bit words the kernels read
+            const size_t need = static_cast<size_t>((pc->n_edges + 3) / 4) * 16;
+            if (!L->unpacked.p || L->unpacked.bytes < need) {
+                HIP_TRY(hipStreamSynchronize(s));   // the previous chunk's kernels may still read the old buffer
+                L->unpacked.release();
+                HIP_TRY(L->unpacked.alloc(need));
+            }
+            HIP_TRY(launch_unpack24(L->stage_col[slot].p, pc->n_edges, src_begin, static_cast<int32_t *>(L->unpacked.p), s));
+            ga.src_sorted = static_cast<const int32_t *>(L->unpacked.p);
+        }
         L->bytes_h2d += static_cast<int64_t>(emb_bytes + staged_bytes);
         a.col = static_cast<const int32_t *>(L->stage_col[slot].p);
         a.col_base = e0;
@@ -922,9 +940,19 @@ int atlas_plan_create_blocked(const atlas_graph_t *graph, int64_t chunk_sources,
     const int64_t nchunks = (P->n + chunk_sources - 1) / chunk_sources;
     const size_t e_bytes = static_cast<size_t>(std::max<int64_t>(P->e, 1)) * sizeof(int32_t);
     int rc = ATLAS_OK;
-    hipError_t e = P->host ? hipHostMalloc(reinterpret_cast<void **>(&P->src_sorted), e_bytes, hipHostMallocDefault)
-                           : hipMalloc(reinterpret_cast<void **>(&P->src_sorted), e_bytes);
+    // a plan that is copied to the device in every layer keeps its edge words in 3 bytes
+    const bool packed = P->host && chunk_sources <= (int64_t(1) << 23);
+    hipError_t e = hipSuccess;
+    if (packed) {
+        // every chunk's words start on a 256-byte boundary
+        P->packed_bytes = static_cast<size_t>(std::max<int64_t>(P->e, 1)) * 3 + static_cast<size_t>(nchunks + 1) * 268;
+        e = hipHostMalloc(reinterpret_cast<void **>(&P->src_packed), P->packed_bytes, hipHostMallocDefault);
+    } else {
+        e = P->host ? hipHostMalloc(reinterpret_cast<void **>(&P->src_sorted), e_bytes, hipHostMallocDefault)
+                    : hipMalloc(reinterpret_cast<void **>(&P->src_sorted), e_bytes);
+    }
     if (e != hipSuccess) rc = hip_fail(e, "alloc(plan)");
+    size_t packed_off = 0;
 
     auto offset_at = [&](int64_t u, int64_t *v) -> hipError_t {
         if (P->host) { *v = graph->row_offsets[u]; return hipSuccess; }
@@ -956,14 +984,23 @@ int atlas_plan_create_blocked(const atlas_graph_t *graph, int64_t chunk_sources,
             const size_t nsrc = static_cast<size_t>(en - b);
             const size_t ne1 = static_cast<size_t>(std::max<int64_t>(ne, 1));
             if ((e = hipMalloc(reinterpret_cast<void **>(&off_tmp), (nsrc + 1) * sizeof(int64_t))) == hipSuccess &&
-                (e = hipMalloc(reinterpret_cast<void **>(&col_tmp), ne1 * 4)) == hipSuccess &&
+                (e = hipMalloc(reinterpret_cast<void **>(&col_tmp), (ne1 + 3) * 4)) == hipSuccess &&   // also holds the packed words
                 (e = hipMalloc(reinterpret_cast<void **>(&src_tmp), ne1 * 4)) == hipSuccess &&
                 (e = hipMemcpy(off_tmp, graph->row_offsets + b, (nsrc + 1) * sizeof(int64_t), hipMemcpyHostToDevice)) == hipSuccess &&
                 (ne == 0 || (e = hipMemcpy(col_tmp, graph->col_indices + ebeg, static_cast<size_t>(ne) * 4, hipMemcpyHostToDevice)) == hipSuccess)) {
                 e = build_plan_chunk(off_tmp - b, col_tmp - ebeg, P->n, b, en, ebeg, eend, src_tmp, seen, block_sources,
                                      hot_min_edges, &pc);
-                if (e == hipSuccess && ne > 0)
+                if (e == hipSuccess && ne > 0 && packed) {
+                    // the CSR slice is no longer needed: its buffer takes the packed words
+                    const size_t pb = packed24_bytes(ne);
+                    pc.packed_off = static_cast<int64_t>(packed_off);
+                    if (packed_off + pb > P->packed_bytes) e = hipErrorInvalidValue;
+                    if (e == hipSuccess) e = launch_pack24(src_tmp, ne, b, col_tmp, nullptr);
+                    if (e == hipSuccess) e = hipMemcpy(P->src_packed + packed_off, col_tmp, pb, hipMemcpyDeviceToHost);
+                    packed_off += round_up(pb, 256);
+                } else if (e == hipSuccess && ne > 0) {
                     e = hipMemcpy(P->src_sorted + ebeg, src_tmp, static_cast<size_t>(ne) * 4, hipMemcpyDeviceToHost);
+                }
                 if (e == hipSuccess && ne > 0) {
                     int32_t *g_h = nullptr, *t_h = nullptr;
                     const size_t gb = static_cast<size_t>(pc.n_groups) * 4, tb = static_cast<size_t>((ne + 63) / 64) * 4;
@@ -988,7 +1025,7 @@ int atlas_plan_create_blocked(const atlas_graph_t *graph, int64_t chunk_sources,
         }
         P->blocked = P->blocked || pc.blocked;
         P->chunks.push_back(pc);
-        P->max_stage_bytes = std::max(P->max_stage_bytes, stage_bytes_of(pc));
+        P->max_stage_bytes = std::max(P->max_stage_bytes, stage_bytes_of(pc, packed));
         ebeg = eend;
     }
     if (seen) (void)hipFree(seen);
@@ -1009,6 +1046,7 @@ int atlas_plan_destroy(atlas_plan_t *P) {
         if (c.zero_rows) (void)hipFree(c.zero_rows);
     }
     if (P->src_sorted) (void)(P->host ? hipHostFree(P->src_sorted) : hipFree(P->src_sorted));
+    if (P->src_packed) (void)hipHostFree(P->src_packed);
     delete P;
     return ATLAS_OK;
 }

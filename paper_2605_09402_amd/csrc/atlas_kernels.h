@@ -100,7 +100,13 @@ struct PlanChunk {
     int32_t *zero_rows = nullptr; // device plans: destinations a planned-only layer clears before this chunk (their
     int64_t n_zero_rows = 0;      // first group is added to with atomics by several waves); may hold duplicates
     bool has_zero_rows = false;   // false: not precomputed, the launch scans the tile boundaries instead
+    int64_t packed_off = 0;       // plans with 24-bit edge words: byte offset of the chunk's words in the plan's array
 };
+
+// 24-bit edge words of plans that live in pinned host memory (source offset within the chunk, bit 23 = group end)
+size_t packed24_bytes(int64_t n_edges);
+hipError_t launch_pack24(const int32_t *src_sorted, int64_t n_edges, int64_t src_begin, void *packed, hipStream_t s);
+hipError_t launch_unpack24(const void *packed, int64_t n_edges, int64_t src_begin, int32_t *src_sorted, hipStream_t s);
 
 struct GroupedArgs {
     const int32_t *src_sorted;  // chunk slice: source id of every edge in destination order,

@@ -286,4 +286,63 @@ done:
     return err;
 }
 
+// ---- 24-bit edge words for plans that travel over the host link ------------
+//
+// A plan of a pinned-host graph is copied to the device chunk by chunk in every
+// layer, so its edge words are stored in 3 bytes: the source as an offset from
+// the chunk's first source (chunks of at most 2^23 sources) and the group-end
+// flag in bit 23.  Four words make three dwords; a chunk's array is padded to
+// a multiple of four words.
+
+namespace {
+__global__ __launch_bounds__(256) void k_pack24(const int32_t *__restrict__ src_sorted, int64_t n_edges,
+                                                int32_t src_begin, uint32_t *__restrict__ packed) {
+    const int64_t q = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;   // four edges
+    if (q * 4 >= n_edges) return;
+    uint32_t w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int64_t i = q * 4 + j;
+        const int32_t v = i < n_edges ? src_sorted[i] : 0;
+        w[j] = static_cast<uint32_t>((v & 0x7fffffff) - (i < n_edges ? src_begin : 0)) | (v < 0 ? 0x800000u : 0u);
+    }
+    packed[q * 3] = w[0] | (w[1] << 24);
+    packed[q * 3 + 1] = (w[1] >> 8) | (w[2] << 16);
+    packed[q * 3 + 2] = (w[2] >> 16) | (w[3] << 8);
+}
+
+__global__ __launch_bounds__(256) void k_unpack24(const uint32_t *__restrict__ packed, int64_t n_edges,
+                                                  int32_t src_begin, int4 *__restrict__ src_sorted) {
+    const int64_t q = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;   // four edges
+    if (q * 4 >= n_edges) return;
+    const uint32_t d0 = packed[q * 3], d1 = packed[q * 3 + 1], d2 = packed[q * 3 + 2];
+    const uint32_t w[4] = {d0 & 0xffffffu, (d0 >> 24) | ((d1 & 0xffffu) << 8), (d1 >> 16) | ((d2 & 0xffu) << 16), d2 >> 8};
+    int32_t v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        v[j] = static_cast<int32_t>(((w[j] & 0x7fffffu) + static_cast<uint32_t>(src_begin)) | ((w[j] & 0x800000u) << 8));
+    src_sorted[q] = make_int4(v[0], v[1], v[2], v[3]);
+}
+}  // namespace
+
+size_t packed24_bytes(int64_t n_edges) { return static_cast<size_t>((n_edges + 3) / 4) * 12; }
+
+hipError_t launch_pack24(const int32_t *src_sorted, int64_t n_edges, int64_t src_begin, void *packed, hipStream_t s) {
+    if (n_edges <= 0) return hipSuccess;
+    const int64_t quads = (n_edges + 3) / 4;
+    hipLaunchKernelGGL(k_pack24, dim3(static_cast<unsigned>((quads + 255) / 256)), dim3(256), 0, s, src_sorted, n_edges,
+                       static_cast<int32_t>(src_begin), static_cast<uint32_t *>(packed));
+    return hipGetLastError();
+}
+
+// `src_sorted` has room for n_edges rounded up to a multiple of four words.
+hipError_t launch_unpack24(const void *packed, int64_t n_edges, int64_t src_begin, int32_t *src_sorted, hipStream_t s) {
+    if (n_edges <= 0) return hipSuccess;
+    const int64_t quads = (n_edges + 3) / 4;
+    hipLaunchKernelGGL(k_unpack24, dim3(static_cast<unsigned>((quads + 255) / 256)), dim3(256), 0, s,
+                       static_cast<const uint32_t *>(packed), n_edges, static_cast<int32_t>(src_begin),
+                       reinterpret_cast<int4 *>(src_sorted));
+    return hipGetLastError();
+}
+
 }  // namespace atlas
