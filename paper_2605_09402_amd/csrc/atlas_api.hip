@@ -119,6 +119,8 @@ struct atlas_plan {
     int32_t *src_sorted = nullptr;  // [E] destination-ordered source ids of all chunks
     uint8_t *src_packed = nullptr;  // host plans with chunks of at most 2^23 sources: the same words in 3 bytes
     size_t packed_bytes = 0;        // (PlanChunk::packed_off locates a chunk's words); src_sorted is then unused
+    int64_t *dev_off = nullptr;     // host plans: device copy of the graph's row offsets, so that layers need not
+                                    // bring them over the link again
     bool blocked = false;           // some chunk is in source-blocked order (grp_dst bit 30 in use)
     std::vector<PlanChunk> chunks;  // grp_dst / tile_grp: device, or pinned host when `host`
     size_t max_stage_bytes = 0;     // host plans: largest staging slot any chunk needs
@@ -358,7 +360,6 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
 
     if (L->g.residency == ATLAS_RESIDENT_PINNED_HOST) {
         // row offsets are small next to the edge array: keep a device copy for the kernels
-        HIP_TRY(L->dev_off.alloc((n1 + 1) * sizeof(int64_t)));
         HIP_TRY(loader_stream(&L->copy_stream));
         for (int i = 0; i < atlas_layer::kStageSlots; ++i) {
             HIP_TRY(hipEventCreateWithFlags(&L->slot_loaded[i], hipEventDisableTiming));
@@ -369,12 +370,17 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
         // start; the two streams then hold a copy engine each, the copy stream is given one that
         // moves host memory at about half the link rate (31 instead of 57 GB/s measured) and keeps
         // it for the whole layer.
-        HIP_TRY(hipMemcpyAsync(L->dev_off.p, L->g.row_offsets, (static_cast<size_t>(n) + 1) * sizeof(int64_t),
-                               hipMemcpyHostToDevice, L->copy_stream));
-        HIP_TRY(hipEventRecord(L->slot_loaded[0], L->copy_stream));
-        HIP_TRY(hipStreamWaitEvent(s, L->slot_loaded[0], 0));
-        L->off_dev = static_cast<const int64_t *>(L->dev_off.p);
-        L->bytes_h2d += (n + 1) * static_cast<int64_t>(sizeof(int64_t));
+        if (L->g.plan && L->g.plan->host && L->g.plan->dev_off && L->g.plan->n == n) {
+            L->off_dev = L->g.plan->dev_off;   // the plan of this graph already holds them on the device
+        } else {
+            HIP_TRY(L->dev_off.alloc((n1 + 1) * sizeof(int64_t)));
+            HIP_TRY(hipMemcpyAsync(L->dev_off.p, L->g.row_offsets, (static_cast<size_t>(n) + 1) * sizeof(int64_t),
+                                   hipMemcpyHostToDevice, L->copy_stream));
+            HIP_TRY(hipEventRecord(L->slot_loaded[0], L->copy_stream));
+            HIP_TRY(hipStreamWaitEvent(s, L->slot_loaded[0], 0));
+            L->off_dev = static_cast<const int64_t *>(L->dev_off.p);
+            L->bytes_h2d += (n + 1) * static_cast<int64_t>(sizeof(int64_t));
+        }
         // edge staging slots are allocated by the first chunk that uses them (atlas_broadcast_chunk)
         if (!has_self_term(d.model)) {
             const int64_t C = d.max_chunk_sources;
@@ -1029,6 +1035,12 @@ int atlas_plan_create_blocked(const atlas_graph_t *graph, int64_t chunk_sources,
         ebeg = eend;
     }
     if (seen) (void)hipFree(seen);
+    if (rc == ATLAS_OK && P->host) {
+        const size_t ob = (static_cast<size_t>(P->n) + 1) * sizeof(int64_t);
+        if ((e = hipMalloc(reinterpret_cast<void **>(&P->dev_off), ob)) != hipSuccess ||
+            (e = hipMemcpy(P->dev_off, graph->row_offsets, ob, hipMemcpyHostToDevice)) != hipSuccess)
+            rc = hip_fail(e, "plan row offsets");
+    }
     if (rc != ATLAS_OK) {
         atlas_plan_destroy(P);
         return rc;
@@ -1047,6 +1059,7 @@ int atlas_plan_destroy(atlas_plan_t *P) {
     }
     if (P->src_sorted) (void)(P->host ? hipHostFree(P->src_sorted) : hipFree(P->src_sorted));
     if (P->src_packed) (void)hipHostFree(P->src_packed);
+    if (P->dev_off) (void)hipFree(P->dev_off);
     delete P;
     return ATLAS_OK;
 }
