@@ -267,10 +267,12 @@ def main() -> int:
     # ---- end-to-end: all three layers once ----
     e2e_ms = None
     layer_ms = []
-    if not args.no_e2e and args.residency == "device":
+    if not args.no_e2e:
+        # pinned residency: layer 1 streams features and edges from the host, the later layers read the
+        # previous layer's output in HBM and stream the edges only
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        x = wl.X
+        x = x_layer0
         for li in range(len(wl.layers)):
             t1 = time.perf_counter()
             run_layer(li, x, False)

@@ -76,7 +76,7 @@ enum atlas_dtype {
 enum atlas_activation { ATLAS_ACT_NONE = 0, ATLAS_ACT_RELU = 1, ATLAS_ACT_ELU = 2 };
 enum atlas_flags {
     ATLAS_FLAG_TIMING = 1,       /* record per-stage GPU time with HIP events                  */
-    ATLAS_FLAG_EMB_RESIDENT = 2, /* DEVICE graphs, SAGE_MEAN: the caller promises that every
+    ATLAS_FLAG_EMB_RESIDENT = 2, /* embeddings in device memory, SAGE_MEAN / GIN: the caller promises that every
                                     `emb` given to atlas_broadcast_chunk is the row range
                                     [src_begin, src_end) of ONE contiguous N x d_in matrix that
                                     stays valid until atlas_layer_finish; the library then reads
@@ -218,9 +218,11 @@ int atlas_attention_prepass(atlas_layer_t *layer, int64_t src_begin, int64_t src
 
 /* Broadcast sources [src_begin, src_end) (Sec. 3.1, 3.3, 3.4).  `emb` points at
  * the (src_end - src_begin) x d_in row-major embeddings OF THE CHUNK ONLY, in
- * dims.in_dtype; device memory for DEVICE graphs, pinned host memory for
- * PINNED_HOST graphs (the library stages it and the chunk's CSR slice into HBM
- * on its own copy stream, overlapped with the previous chunk's kernels).
+ * dims.in_dtype; device memory for DEVICE graphs; for PINNED_HOST graphs
+ * either pinned host memory (the library stages it and the chunk's edges into
+ * HBM on its own copy stream, overlapped with the previous chunk's kernels) or
+ * device memory (a later layer whose input is the previous layer's output:
+ * only the edges are staged), the same kind for every chunk of the layer.
  * For every out-edge (u, v): acc[v] += g(u) h_u and pending[v] -= 1; v joins
  * the ready list when its count reaches zero.  Chunks must arrive in ascending
  * contiguous order starting at 0 ("strictly ordered", Sec. 3.4).  Only

@@ -166,6 +166,8 @@ struct atlas_layer {
     bool planned_only = false;         // every chunk runs from the plan: no accumulator zero fill
     bool emb_resident = false;         // own rows are read from the caller's matrix
     const char *x_base = nullptr;      // base of that matrix (set by the first chunk)
+    int emb_on_device = -1;            // PINNED_HOST graphs: the chunks' embeddings are device memory (1), host (0),
+                                       // not yet known (-1); e.g. a later layer whose input is the previous output
 
     int64_t next_src = 0;
     int64_t num_chunks = 0, num_flushes = 0;
@@ -303,8 +305,8 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
     }
     const size_t acc_rows = L->bounded ? static_cast<size_t>(d.hot_slots) : n1;
     HIP_TRY(L->acc.alloc(acc_rows * L->acc_width * sizeof(float)));
-    L->emb_resident = has_self_term(d.model) && (d.flags & ATLAS_FLAG_EMB_RESIDENT) && !L->tf &&
-                      L->g.residency == ATLAS_RESIDENT_DEVICE;
+    // (PINNED_HOST graphs: honoured when the embeddings turn out to be device memory, see the first chunk)
+    L->emb_resident = has_self_term(d.model) && (d.flags & ATLAS_FLAG_EMB_RESIDENT) && !L->tf;
     if (L->tf) {
         const size_t rows = static_cast<size_t>(std::min<int64_t>(d.max_chunk_sources, std::max<int64_t>(n, 1)));
         if (d.model != ATLAS_MODEL_GIN) HIP_TRY(L->tf_z.alloc(rows * d.d_out * sizeof(float)));
@@ -543,6 +545,23 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
     a.counters = L->ctr();
     a.counters64 = static_cast<unsigned long long *>(L->counters64.p);
 
+    if (L->g.residency == ATLAS_RESIDENT_PINNED_HOST) {
+        // where the caller keeps this layer's embeddings: pinned host memory (staged per chunk) or device
+        // memory (a later layer reading the previous layer's output; read in place)
+        hipPointerAttribute_t attr{};
+        int on_device = 0;
+        if (hipPointerGetAttributes(&attr, emb) == hipSuccess) on_device = attr.type == hipMemoryTypeDevice ? 1 : 0;
+        else (void)hipGetLastError();   // pageable memory is unknown to the runtime: host
+        if (L->emb_on_device >= 0 && L->emb_on_device != on_device) return ATLAS_E_STATE;
+        if (L->emb_on_device < 0 && L->emb_resident && !on_device) {
+            // host embeddings cannot be read in place: keep a copy of the own rows after all
+            L->emb_resident = false;
+            const size_t n1 = static_cast<size_t>(std::max<int64_t>(L->n, 1));
+            HIP_TRY(L->self_rows.alloc(n1 * d.d_in * dtype_size(d.in_dtype)));
+        }
+        L->emb_on_device = on_device;
+    }
+    const bool emb_dev = L->g.residency == ATLAS_RESIDENT_DEVICE || L->emb_on_device == 1;
     if (L->emb_resident) {
         const char *base = static_cast<const char *>(emb) - static_cast<size_t>(src_begin) * row_bytes;
         if (L->x_base && base != L->x_base) return ATLAS_E_STATE;
@@ -581,8 +600,12 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         if (L->slot_used[slot]) HIP_TRY(hipStreamWaitEvent(L->copy_stream, L->slot_free[slot], 0));
         int rc = start_span(L, L->t_copy, L->copy_stream);
         if (rc != ATLAS_OK) return rc;
-        void *emb_dst = self_dst ? static_cast<void *>(self_dst) : L->stage_emb[slot].p;
-        HIP_TRY(hipMemcpyAsync(emb_dst, emb, emb_bytes, hipMemcpyHostToDevice, L->copy_stream));
+        const void *emb_dst = emb;   // device-resident embeddings are read where they are
+        if (!emb_dev) {
+            void *stage = self_dst ? static_cast<void *>(self_dst) : L->stage_emb[slot].p;
+            HIP_TRY(hipMemcpyAsync(stage, emb, emb_bytes, hipMemcpyHostToDevice, L->copy_stream));
+            emb_dst = stage;
+        }
         size_t staged_bytes = 0;
         if (pc) {
             // planned chunk: its regrouped edges travel instead of the CSR slice (same 4 bytes per edge)
@@ -621,7 +644,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
             HIP_TRY(launch_unpack24(L->stage_col[slot].p, pc->n_edges, src_begin, static_cast<int32_t *>(L->unpacked.p), s));
             ga.src_sorted = static_cast<const int32_t *>(L->unpacked.p);
         }
-        L->bytes_h2d += static_cast<int64_t>(emb_bytes + staged_bytes);
+        L->bytes_h2d += static_cast<int64_t>((emb_dev ? 0 : emb_bytes) + staged_bytes);
         a.col = static_cast<const int32_t *>(L->stage_col[slot].p);
         a.col_base = e0;
         a.emb = emb_dst;
@@ -634,7 +657,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
     int rc = ATLAS_OK;
     if (L->selfmsg) {
         if ((rc = start_span(L, L->t_self, s)) != ATLAS_OK) return rc;
-        if (self_dst && L->g.residency == ATLAS_RESIDENT_DEVICE)
+        if (self_dst && emb_dev)
             HIP_TRY(hipMemcpyAsync(self_dst, emb, emb_bytes, hipMemcpyDeviceToDevice, s));
         HIP_TRY(launch_self_message(src_begin, src_end, a.pending, a.ready, a.counters, s));
         if ((rc = end_span(L, L->t_self, s)) != ATLAS_OK) return rc;

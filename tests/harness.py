@@ -99,11 +99,14 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
             give_indeg: bool = False, timing: bool = False, max_layers: Optional[int] = None,
             plan: bool = False, plan_chunk: Optional[int] = None, emb_resident: bool = False,
             planned_only: bool = False, hot_slots: int = 0, evict_policy: int = 0,
-            transform_first: bool = False, plan_block: Optional[tuple] = None) -> GpuRun:
+            transform_first: bool = False, plan_block: Optional[tuple] = None,
+            device_later: bool = False) -> GpuRun:
     """Drive all layers through the C ABI.  With pinned_host the graph and the
     layer-0 features stay in pinned host memory and are staged by the library.
     planned_only sets ATLAS_FLAG_PLANNED_ONLY (no zero fill of the accumulators;
-    the buffers then still hold whatever the previous layer or test left there)."""
+    the buffers then still hold whatever the previous layer or test left there).
+    device_later (with pinned_host): layers after the first are given the previous
+    layer's output where it lies in device memory instead of a pinned host copy."""
     dev = torch.device("cuda:0")
     n, e = case.n, case.e
     run = GpuRun()
@@ -188,6 +191,8 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
             if pinned_host:
                 if li == 0:
                     emb = cur_host[b0:b1]
+                elif device_later:
+                    emb = cur_dev[b0:b1]
                 else:  # later layers: stage the device rows through pinned memory
                     emb = cur_dev[b0:b1].cpu().pin_memory()
                     keep.append(emb)

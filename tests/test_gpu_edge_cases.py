@@ -135,6 +135,12 @@ def test_pinned_host_residency(oracle, H, model, store):
     assert case.n * row + case.e * 3 < run3.stats[0]["bytes_copied_h2d"] < case.n * row + case.e * 4 + (case.n + 1) * 8
     run4 = H.run_gpu(case, pinned_host=True, plan=True, flush_every=5, planned_only=True)
     H.check_outputs(oracle, case, run4)
+    # graph in pinned host memory, layer 2 reads layer 1's output in device memory: only edges are staged
+    run5 = H.run_gpu(case, pinned_host=True, plan=True, device_later=True)
+    H.check_outputs(oracle, case, run5)
+    assert run5.stats[1]["bytes_copied_h2d"] < case.e * 4 + (case.n + 1) * 8
+    run6 = H.run_gpu(case, pinned_host=True, device_later=True, emb_resident=True, flush_every=2)
+    H.check_outputs(oracle, case, run6)
 
 
 def test_api_errors(atlas, H):
