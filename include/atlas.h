@@ -332,6 +332,14 @@ int atlas_debug_copy(atlas_layer_t *layer, int what, void *host_dst, int64_t byt
  * beyond fp32 summation order.  Errors: E_RANGE. */
 int atlas_set_tiles_per_run(int tiles);
 
+/* Chunk loader of PINNED_HOST graphs with a plan (Sec. 3.3, the reader that runs
+ * ahead of the aggregation): a planned chunk of at least 2 * `tiles` 64-edge
+ * tiles crosses the host link in pieces of `tiles` tiles, and each piece is
+ * pushed as soon as it has arrived, so a long chunk's copy and kernels overlap.
+ * 0 restores the default (2^21 tiles); small values are for tests.  Applies to
+ * every later atlas_broadcast_chunk of the process.  Errors: E_RANGE. */
+int atlas_set_piece_tiles(int64_t tiles);
+
 /* Free the device buffers the library keeps for reuse between layers. */
 int atlas_release_cache(void);
 

@@ -31,7 +31,7 @@ EXPORTS = [
     "atlas_layer_init", "atlas_attention_prepass", "atlas_broadcast_chunk", "atlas_flush_ready",
     "atlas_layer_finish", "atlas_in_degree", "atlas_reorder_indegree_desc", "atlas_debug_copy",
     "atlas_release_cache", "atlas_strerror", "atlas_last_hip_error", "atlas_plan_create", "atlas_plan_destroy",
-    "atlas_reorder_score_desc", "atlas_sample_in_edges", "atlas_plan_create_blocked", "atlas_set_tiles_per_run",
+    "atlas_reorder_score_desc", "atlas_sample_in_edges", "atlas_plan_create_blocked", "atlas_set_tiles_per_run", "atlas_set_piece_tiles",
 ]
 
 
@@ -101,6 +101,7 @@ def lib() -> ctypes.CDLL:
         L.atlas_sample_in_edges.argtypes = [ctypes.POINTER(atlas_graph_t), vp, i32, vp, vp, ctypes.POINTER(i64)]
         L.atlas_debug_copy.argtypes = [vp, i32, vp, i64]
         L.atlas_set_tiles_per_run.argtypes = [ctypes.c_int]
+        L.atlas_set_piece_tiles.argtypes = [ctypes.c_int64]
         L.atlas_release_cache.argtypes = []
         L.atlas_plan_create.argtypes = [ctypes.POINTER(atlas_graph_t), i64, ctypes.POINTER(vp)]
         L.atlas_plan_create_blocked.argtypes = [ctypes.POINTER(atlas_graph_t), i64, i64, i64, ctypes.POINTER(vp)]
@@ -239,6 +240,10 @@ def atlas_debug_copy(layer: int, what: int, host_array) -> None:
 
 def atlas_set_tiles_per_run(tiles: int) -> None:
     _check(lib().atlas_set_tiles_per_run(int(tiles)), "atlas_set_tiles_per_run")
+
+
+def atlas_set_piece_tiles(tiles: int) -> None:
+    _check(lib().atlas_set_piece_tiles(int(tiles)), "atlas_set_piece_tiles")
 
 
 def atlas_release_cache() -> None:

@@ -8,6 +8,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <mutex>
 #include <new>
 #include <string>
@@ -98,6 +99,8 @@ hipError_t cold_buffer(size_t bytes, void **out) {
 // all layers: HIP spreads streams over a few hardware queues, and a stream
 // created anew for every layer can land on the queue that carries the caller's
 // kernels, which silently serialises the copies with them.
+// tiles per piece of a long pinned-host chunk (atlas_set_piece_tiles); default 2^21 tiles = 2^27 edges
+std::atomic<int64_t> g_piece_tiles{int64_t(1) << 21};
 hipStream_t g_copy_stream = nullptr;
 hipError_t loader_stream(hipStream_t *out) {
     std::lock_guard<std::mutex> lk(g_cache_mu);
@@ -185,6 +188,7 @@ struct atlas_layer {
     hipEvent_t slot_free[kStageSlots] = {};
     bool slot_used[kStageSlots] = {};
     Buf stage_col[kStageSlots], stage_emb[kStageSlots];
+    std::vector<hipEvent_t> piece_ev[kStageSlots];   // a long chunk's edge words arrive in pieces: one event each
 
     std::vector<TimedSpan> t_agg, t_self, t_upd, t_copy, t_init;
     hipStream_t last_stream = nullptr;
@@ -198,6 +202,8 @@ struct atlas_layer {
                        &hs_stamp, &hs_need, &hs_ctr, &hs_keys, &hs_keys_sorted, &hs_sort_temp, &tf_z, &tf_self, &unpacked,
                        &packed_w2})
             b->release();
+        for (auto &v : piece_ev)
+            for (hipEvent_t e : v) (void)hipEventDestroy(e);
         for (Buf &b : stage_col) b.release();
         for (Buf &b : stage_emb) b.release();
         for (auto *v : {&t_agg, &t_self, &t_upd, &t_copy, &t_init})
@@ -581,6 +587,12 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
     GroupedArgs ga{};
 
     int slot = -1;
+    // A long planned chunk crosses the host link in pieces of kPieceTiles tiles, and each piece is pushed
+    // as soon as it has arrived, so the chunk's copy and its kernels overlap (the first chunk of a
+    // degree-ordered graph holds most of the edges).
+    const int64_t kPieceTiles = g_piece_tiles.load(std::memory_order_relaxed);
+    int npieces = 1;
+    bool packed_chunk = false;
     if (L->g.residency == ATLAS_RESIDENT_PINNED_HOST) {
         // Stage the chunk into HBM on the copy stream; the compute stream only
         // waits for this chunk's event, so the copy of chunk k+1 (enqueued by
@@ -614,11 +626,29 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
                          gb = static_cast<size_t>(pc->n_groups) * 4, tb = static_cast<size_t>((pc->n_edges + 63) / 64) * 4;
             char *g_dev = base + round_up(sb, 256), *t_dev = g_dev + round_up(gb, 256);
             if (sb) {
-                const void *words = packed ? static_cast<const void *>(plan->src_packed + pc->packed_off)
-                                           : static_cast<const void *>(plan->src_sorted + pc->edge_base);
-                HIP_TRY(hipMemcpyAsync(base, words, sb, hipMemcpyHostToDevice, L->copy_stream));
+                const char *words = packed ? reinterpret_cast<const char *>(plan->src_packed + pc->packed_off)
+                                           : reinterpret_cast<const char *>(plan->src_sorted + pc->edge_base);
+                // the group arrays first: every piece needs them
                 HIP_TRY(hipMemcpyAsync(g_dev, pc->grp_dst, gb, hipMemcpyHostToDevice, L->copy_stream));
                 HIP_TRY(hipMemcpyAsync(t_dev, pc->tile_grp, tb, hipMemcpyHostToDevice, L->copy_stream));
+                const int64_t ntiles = (pc->n_edges + 63) / 64;
+                // (a planned-only layer whose plan has no list of rows to clear finds them by a scan of the
+                // whole chunk's words: such a chunk is pushed in one piece)
+                if (ntiles >= 2 * kPieceTiles && (!L->planned_only || pc->has_zero_rows))
+                    npieces = static_cast<int>((ntiles + kPieceTiles - 1) / kPieceTiles);
+                auto &evs = L->piece_ev[slot];
+                while (static_cast<int>(evs.size()) < npieces) {
+                    hipEvent_t ev = nullptr;
+                    HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+                    evs.push_back(ev);
+                }
+                const size_t tile_bytes = packed ? 192 : 256;   // 64 words of 3 or 4 bytes
+                for (int p = 0; p < npieces; ++p) {
+                    const size_t lo = static_cast<size_t>(p) * kPieceTiles * tile_bytes;
+                    const size_t hi = p + 1 < npieces ? lo + kPieceTiles * tile_bytes : sb;
+                    HIP_TRY(hipMemcpyAsync(base + lo, words + lo, hi - lo, hipMemcpyHostToDevice, L->copy_stream));
+                    HIP_TRY(hipEventRecord(evs[p], L->copy_stream));
+                }
             }
             ga.src_sorted = reinterpret_cast<const int32_t *>(base);
             ga.grp_dst = reinterpret_cast<const int32_t *>(g_dev);
@@ -632,16 +662,17 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         rc = end_span(L, L->t_copy, L->copy_stream);
         if (rc != ATLAS_OK) return rc;
         HIP_TRY(hipEventRecord(L->slot_loaded[slot], L->copy_stream));
-        HIP_TRY(hipStreamWaitEvent(s, L->slot_loaded[slot], 0));
+        // the compute stream goes on when the rows, the group arrays and the first piece are there
+        HIP_TRY(hipStreamWaitEvent(s, npieces > 1 ? L->piece_ev[slot][0] : L->slot_loaded[slot], 0));
         if (packed && pc->n_edges > 0) {
-            // 24-bit words as they came over the link -> the 32-bit words the kernels read
+            // 24-bit words as they came over the link -> the 32-bit words the kernels read (piece by piece, below)
             const size_t need = static_cast<size_t>((pc->n_edges + 3) / 4) * 16;
             if (!L->unpacked.p || L->unpacked.bytes < need) {
                 HIP_TRY(hipStreamSynchronize(s));   // the previous chunk's kernels may still read the old buffer
                 L->unpacked.release();
                 HIP_TRY(L->unpacked.alloc(need));
             }
-            HIP_TRY(launch_unpack24(L->stage_col[slot].p, pc->n_edges, src_begin, static_cast<int32_t *>(L->unpacked.p), s));
+            packed_chunk = true;
             ga.src_sorted = static_cast<const int32_t *>(L->unpacked.p);
         }
         L->bytes_h2d += static_cast<int64_t>((emb_dev ? 0 : emb_bytes) + staged_bytes);
@@ -800,13 +831,28 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
     }
     if ((rc = start_span(L, L->t_agg, s)) != ATLAS_OK) return rc;
     if (pc) {
-        if (L->planned_only) {
-            if (pc->has_zero_rows)   // (device memory also in plans of pinned-host graphs)
-                HIP_TRY(launch_zero_rows(pc->zero_rows, pc->n_zero_rows, ga.acc, ga.slot_of, ga.d, s));
-            else
-                HIP_TRY(launch_zero_cut_first_rows(ga, s));
+        for (int p = 0; p < npieces; ++p) {
+            if (npieces > 1) {
+                if (p > 0) HIP_TRY(hipStreamWaitEvent(s, L->piece_ev[slot][p], 0));
+                ga.tile_begin = p * kPieceTiles;
+                ga.tile_end = p + 1 < npieces ? (p + 1) * kPieceTiles : -1;
+            }
+            if (packed_chunk) {
+                const int64_t e_lo = ga.tile_begin * 64;
+                const int64_t e_hi = ga.tile_end < 0 ? pc->n_edges : std::min<int64_t>(pc->n_edges, ga.tile_end * 64);
+                HIP_TRY(launch_unpack24(static_cast<const char *>(L->stage_col[slot].p) + e_lo * 3, e_hi - e_lo, src_begin,
+                                        static_cast<int32_t *>(L->unpacked.p) + e_lo, s));
+            }
+            if (L->planned_only) {
+                if (pc->has_zero_rows) {   // the list (device memory, also in plans of pinned-host graphs) covers
+                    if (p == 0)            // the whole chunk: cleared once, before the first piece adds anything
+                        HIP_TRY(launch_zero_rows(pc->zero_rows, pc->n_zero_rows, ga.acc, ga.slot_of, ga.d, s));
+                } else {
+                    HIP_TRY(launch_zero_cut_first_rows(ga, s));   // (one piece, see above)
+                }
+            }
+            HIP_TRY(launch_aggregate_grouped(ga, s));
         }
-        HIP_TRY(launch_aggregate_grouped(ga, s));
     } else {
         HIP_TRY(launch_aggregate(a, s));
     }
@@ -1175,6 +1221,12 @@ int atlas_release_cache(void) {
         g_cold_bytes = 0;
     }
     if (first != hipSuccess) return hip_fail(first, "hipFree");
+    return ATLAS_OK;
+}
+
+int atlas_set_piece_tiles(int64_t tiles) {
+    if (tiles < 0 || tiles > (int64_t(1) << 30)) return ATLAS_E_RANGE;
+    g_piece_tiles.store(tiles == 0 ? int64_t(1) << 21 : tiles, std::memory_order_relaxed);
     return ATLAS_OK;
 }
 

@@ -133,6 +133,10 @@ struct GroupedArgs {
     float *scores = nullptr;    // GAT only: [n_edges][heads] attention logits of the chunk's edges, written
                                 // by the max sweep and read by the aggregation
     int tiles_per_run = 1;      // consecutive 64-edge tiles one wave takes at a time (set by the launcher)
+    int64_t tile_begin = 0;     // the launch covers tiles [tile_begin, tile_end) of the chunk (tile_end < 0: all).
+    int64_t tile_end = -1;      // A chunk that arrives over the host link in pieces is pushed piece by piece;
+                                // a group cut by a piece boundary is added with atomics like one cut by a run.
+                                // (launch_zero_cut_first_rows always examines the whole chunk)
 };
 
 // forced run length of the grouped aggregation, 0 = chosen per launch

@@ -455,8 +455,14 @@ void k_aggregate_grouped(GroupedArgs a) {
     __shared__ float wgt_all[MODEL == 2 ? (kBlock / kWave) * kTileEdges * kMaxHeads : 1];
     float *wl = wgt_all + (MODEL == 2 ? (threadIdx.x >> 6) * kTileEdges * kMaxHeads : 0);
 
-    if (wave == 0 && lane == 0)
-        atomicAdd(&a.counters64[CTR64_EDGES], static_cast<unsigned long long>(a.n_edges));
+    // the launch's share of the chunk's tiles
+    const int t_lo = static_cast<int>(a.tile_begin);
+    const int t_hi = a.tile_end < 0 || a.tile_end > ntiles ? ntiles : static_cast<int>(a.tile_end);
+    if (wave == 0 && lane == 0) {
+        const int64_t e_lo = static_cast<int64_t>(t_lo) * kTileEdges;
+        const int64_t e_hi = t_hi == ntiles ? a.n_edges : static_cast<int64_t>(t_hi) * kTileEdges;
+        atomicAdd(&a.counters64[CTR64_EDGES], static_cast<unsigned long long>(e_hi > e_lo ? e_hi - e_lo : 0));
+    }
 
     // A wave takes runs of `run` consecutive tiles.  A group that is open at
     // the end of a tile stays in the wave's registers when the next tile is
@@ -468,7 +474,7 @@ void k_aggregate_grouped(GroupedArgs a) {
     // the next tile, so that the only memory waits on the wave's critical
     // path are those of the row gathers.
     const int run = a.tiles_per_run;
-    const int nruns = (ntiles + run - 1) / run;
+    const int nruns = t_hi > t_lo ? (t_hi - t_lo + run - 1) / run : 0;
     float sum[VPL];
 #pragma unroll
     for (int i = 0; i < VPL; ++i) sum[i] = 0.f;
@@ -480,8 +486,8 @@ void k_aggregate_grouped(GroupedArgs a) {
 
     // the tile in hand (fetched ahead)
     int rn = wave;
-    int t = rn < nruns ? rn * run : -1;
-    int t_end = t + run < ntiles ? t + run : ntiles;
+    int t = rn < nruns ? t_lo + rn * run : -1;
+    int t_end = t + run < t_hi ? t + run : t_hi;
     bool run_start = true;
     int32_t s = 0, g0 = 0, prev_word = -1, gd = 0;
     if (t >= 0) {
@@ -505,8 +511,8 @@ void k_aggregate_grouped(GroupedArgs a) {
         bool run_start_n = false;
         if (t_n == t_end) {
             rn_n = rn + nwaves;
-            t_n = rn_n < nruns ? rn_n * run : -1;
-            t_end_n = t_n + run < ntiles ? t_n + run : ntiles;
+            t_n = rn_n < nruns ? t_lo + rn_n * run : -1;
+            t_end_n = t_n + run < t_hi ? t_n + run : t_hi;
             run_start_n = true;
         }
         int32_t s_n = 0, g0_n = 0, prev_word_n = -1, gd_n = 0;
@@ -847,7 +853,10 @@ hipError_t launch_grouped_vpl(const GroupedArgs &a_in, int grid, hipStream_t s) 
     // runs of several tiles only where every wave still gets many runs
     const int64_t ntiles = (a.n_edges + kTileEdges - 1) / kTileEdges;
     const int64_t nwaves = static_cast<int64_t>(grid) * (kBlock / kWave);
-    const int64_t fit = ntiles / (4 * nwaves);
+    const int64_t mine = (a.tile_end < 0 || a.tile_end > ntiles ? ntiles : a.tile_end) - a.tile_begin;
+    if (a.tile_begin < 0 || mine < 0) return hipErrorInvalidValue;
+    if (mine == 0) return hipSuccess;
+    const int64_t fit = mine / (4 * nwaves);
     a.tiles_per_run = static_cast<int>(fit < 1 ? 1 : fit > kMaxTilesPerRun ? kMaxTilesPerRun : fit);
     const int forced = g_tiles_per_run.load(std::memory_order_relaxed);
     if (forced > 0) a.tiles_per_run = forced;

@@ -298,3 +298,34 @@ def test_non_default_stream(oracle, H):
         slots = int((np.bincount(rnd.col.numpy(), minlength=rnd.n) > 0).sum()) // 2
         print("side stream bounded", H.check_outputs(oracle, rnd, H.run_gpu(rnd, plan=True, hot_slots=slots)))
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("model,store", [("sage", torch.bfloat16), ("gcn", torch.float32), ("gin", torch.float32)])
+@pytest.mark.parametrize("piece", [1, 3, 16])
+def test_pinned_chunk_in_pieces(oracle, H, atlas, model, store, piece):
+    """atlas_set_piece_tiles: a planned chunk of a pinned-host graph arrives in
+    pieces of a few tiles and is pushed piece by piece (groups cut by a piece
+    boundary, first-touch groups cleared once, ragged last piece), with and
+    without the zero-fill-free layer start, source-blocked plans included.
+    Degree-ordered R-MAT scale 12, so the first chunk's hub groups span pieces."""
+    g = gen.rmat_graph(SEED + 41, 12, 16, self_loops=(model == "gcn"))
+    off, col = gen.build_csr(g)
+    new_of_old, _ = oracle.reorder_indegree_desc(oracle.in_degree(g.n, col.numpy()))
+    g = g.with_relabel(torch.from_numpy(new_of_old.astype(np.int64)))
+    case = H.make_case(model, g, SEED + 41, [128, 128, 64], 1024, store=store,
+                       feat="normal" if store == torch.float32 else "uniform", eps=0.25 if model == "gin" else 0.0)
+    atlas.atlas_set_piece_tiles(piece)
+    try:
+        run = H.run_gpu(case, snapshots=True, pinned_host=True, plan=True)
+        H.check_integers(oracle, case, run)
+        print("pieces of", piece, model, H.check_outputs(oracle, case, run))
+        H.check_outputs(oracle, case, H.run_gpu(case, pinned_host=True, plan=True, planned_only=True, device_later=True,
+                                                flush_every=3))
+        H.check_outputs(oracle, case, H.run_gpu(case, pinned_host=True, plan=True, planned_only=True, plan_block=(64, 8)))
+        for st in run.stats:
+            assert st["edges_processed"] == case.e and st["vertices_flushed"] == case.n
+    finally:
+        atlas.atlas_set_piece_tiles(0)
+    with pytest.raises(atlas.AtlasError) as ei:
+        atlas.atlas_set_piece_tiles(-1)
+    assert ei.value.status == atlas.E_RANGE
