@@ -168,6 +168,8 @@ enum atlas_evict_policy {
  *              (self-concatenation, Sec. 4.3);  y = [h_v || mean] W + bias.
  *   GCN_SYM:   W is [d_in][d_out];  y = (sum_u h_u / sqrt(D_u D_v)) W + bias,
  *              D = in-degree of the graph as given (self-edges already added).
+ *              Defined for graphs in which every vertex that sends a message
+ *              has an in-edge itself (D_u > 0), as after adding the self-edges.
  *   GAT:       W is [d_in][d_out], head k owns columns k*dh..(k+1)*dh-1,
  *              attn_src / attn_dst are [heads][dh].
  *   GIN:       W is [d_in][d_out]; y = ((1 + gin_eps) x_v + sum of in-neighbours) W + b.

@@ -1,0 +1,95 @@
+"""Seeded random combinations of graph shape, layer type, storage type, chunk
+size and the library's options (plan kind, residency, zero-fill-free start,
+flush cadence, run length, piece size, transform-first, bounded store), each
+checked against the oracle: outputs to the storage type's tolerance and the
+layer counters exactly.  The single-option cases live in the other files; this
+one looks for interactions."""
+import numpy as np
+import pytest
+import torch
+
+import gen
+
+pytestmark = pytest.mark.gpu
+
+SEED = 0x5EED0300
+
+
+@pytest.fixture(scope="module")
+def H():
+    import harness
+    return harness
+
+
+def _draw(rng, oracle, H, idx):
+    model = ["sage", "gcn", "gin"][int(rng.integers(3))]
+    store = [torch.float32, torch.bfloat16, torch.float16][int(rng.integers(3))]
+    scale = int(rng.integers(8, 12))
+    if rng.random() < 0.3 and model != "gcn":   # (GCN is defined on graphs where every vertex has an in-edge)
+        n = int(rng.integers(200, 3000))
+        g = gen.uniform_graph(SEED + idx, n, int(n * rng.integers(2, 20)))
+    else:
+        g = gen.rmat_graph(SEED + idx, scale, int(rng.integers(4, 24)), random_ids=bool(rng.random() < 0.4),
+                           self_loops=(model == "gcn"))
+    if rng.random() < 0.5:   # degree order: hubs first, long groups
+        off, col = gen.build_csr(g)
+        new_of_old, _ = oracle.reorder_indegree_desc(oracle.in_degree(g.n, col.numpy()))
+        g = g.with_relabel(torch.from_numpy(new_of_old.astype(np.int64)))
+    d_in = int(rng.choice([64, 128, 192, 256]))
+    if model == "sage" and store == torch.float32:
+        d_in = min(d_in, 256)
+    dims = [d_in, int(rng.choice([64, 128])), int(rng.choice([16, 48, 64]))]
+    chunk = int(rng.integers(37, max(38, g.n // 2)))
+    opts = {}
+    plan_kind = int(rng.integers(3))          # 0 none, 1 plain, 2 source-blocked
+    pinned = bool(rng.random() < 0.4)
+    tf = bool(rng.random() < 0.25) and not pinned
+    if model == "gin" and store == torch.float16:
+        tf, pinned = True, False              # half-precision GIN runs transform-first only (device graphs)
+    if tf:
+        dims[1] = 64 if dims[1] not in (64, 128) else dims[1]
+        dims[2] = 64                          # transform-first needs output widths that are multiples of 64
+        opts["transform_first"] = True
+    if plan_kind:
+        opts["plan"] = True
+        if plan_kind == 2:
+            opts["plan_block"] = (int(rng.choice([16, 64, 128])), int(rng.choice([4, 8, 24])))
+        if rng.random() < 0.5:
+            opts["planned_only"] = True
+    if pinned:
+        opts["pinned_host"] = True
+        if plan_kind and rng.random() < 0.5:
+            opts["device_later"] = True
+    opts["flush_every"] = int(rng.choice([1, 1, 2, 5]))
+    case = H.make_case(model, g, SEED + idx, dims, chunk, store=store,
+                       feat="normal" if store == torch.float32 else "uniform", eps=0.5 if model == "gin" else 0.0)
+    knobs = {"run": int(rng.choice([0, 0, 2, 5])), "piece": int(rng.choice([0, 1, 4]))}
+    if plan_kind == 1 and not pinned and not tf and rng.random() < 0.4:   # bounded store where the chunks fit
+        started = int((np.bincount(case.col.numpy(), minlength=case.n) > 0).sum())
+        slots = max(1, int(started * rng.uniform(0.6, 0.95)))
+        try:
+            oracle.hot_store_trace(case.off.numpy(), case.col.numpy(), chunk, slots, model in ("sage", "gin"))
+            opts["hot_slots"] = slots
+        except ValueError:
+            pass
+    return case, opts, knobs
+
+
+@pytest.mark.parametrize("idx", range(32))
+def test_random_configuration(oracle, H, idx):
+    import paper_2605_09402_amd as atlas
+    rng = np.random.default_rng(SEED + 1000 + idx)
+    case, opts, knobs = _draw(rng, oracle, H, idx)
+    print("config %d: %s %s n=%d e=%d dims=%s chunk=%d %s %s" % (idx, case.model, case.store, case.n, case.e, case.dims,
+                                                                case.chunk, opts, knobs), flush=True)
+    atlas.atlas_set_tiles_per_run(knobs["run"])
+    atlas.atlas_set_piece_tiles(knobs["piece"])
+    try:
+        run = H.run_gpu(case, **opts)
+        print("  errors", H.check_outputs(oracle, case, run), flush=True)
+        for st in run.stats:
+            assert st["edges_processed"] == case.e and st["vertices_flushed"] == case.n
+            assert st["vertices_completed"] == case.n and st["sources_processed"] == case.n
+    finally:
+        atlas.atlas_set_tiles_per_run(0)
+        atlas.atlas_set_piece_tiles(0)
