@@ -70,6 +70,7 @@ def _draw(rng, oracle, H, idx):
         try:
             oracle.hot_store_trace(case.off.numpy(), case.col.numpy(), chunk, slots, model in ("sage", "gin"))
             opts["hot_slots"] = slots
+            opts["flush_every"] = 1       # the replay flushes after every chunk; later flushes hold rows longer
         except ValueError:
             pass
     return case, opts, knobs
