@@ -21,9 +21,51 @@ def H():
     return harness
 
 
+def _degree_ordered(oracle, g):
+    off, col = gen.build_csr(g)
+    new_of_old, _ = oracle.reorder_indegree_desc(oracle.in_degree(g.n, col.numpy()))
+    return g.with_relabel(torch.from_numpy(new_of_old.astype(np.int64)))
+
+
+def _draw_gat(rng, oracle, H, idx):
+    """GAT: fp32 embeddings on a device graph, plain plan or none."""
+    g = gen.rmat_graph(SEED + idx, int(rng.integers(8, 12)), int(rng.integers(4, 20)), random_ids=bool(rng.random() < 0.5))
+    if rng.random() < 0.5:
+        g = _degree_ordered(oracle, g)
+    heads = int(rng.choice([1, 2, 4]))
+    dims = [int(rng.choice([64, 128])), int(rng.choice([64, 128])), int(rng.choice([64, 128]))]
+    case = H.make_case("gat", g, SEED + idx, dims, int(rng.integers(37, max(38, g.n // 2))), feat="normal", act="elu",
+                       heads=heads)
+    opts = {"flush_every": int(rng.choice([1, 2, 5]))}
+    if rng.random() < 0.6:
+        opts["plan"] = True
+    return case, opts, {"run": int(rng.choice([0, 2, 5])), "piece": 0}
+
+
+def _draw_sgc(rng, oracle, H, idx, store):
+    """SGC: two propagation-only hops and a final GCN layer on a graph with self loops."""
+    if store == torch.float16:
+        store = torch.bfloat16
+    g = gen.rmat_graph(SEED + idx, int(rng.integers(8, 12)), int(rng.integers(4, 20)), random_ids=True, self_loops=True)
+    d = int(rng.choice([64, 128, 256]))
+    case = H.make_case("sgc", g, SEED + idx, [d, d, d, int(rng.choice([16, 48, 64]))],
+                       int(rng.integers(37, max(38, g.n // 2))), store=store,
+                       feat="normal" if store == torch.float32 else "uniform")
+    opts = {"flush_every": int(rng.choice([1, 2, 5]))}
+    if rng.random() < 0.6:
+        opts["plan"] = True
+        if rng.random() < 0.5:
+            opts["planned_only"] = True
+    return case, opts, {"run": int(rng.choice([0, 2, 5])), "piece": 0}
+
+
 def _draw(rng, oracle, H, idx):
-    model = ["sage", "gcn", "gin"][int(rng.integers(3))]
+    model = ["sage", "gcn", "gin", "gat", "sgc"][int(rng.integers(5))]
     store = [torch.float32, torch.bfloat16, torch.float16][int(rng.integers(3))]
+    if model == "gat":
+        return _draw_gat(rng, oracle, H, idx)
+    if model == "sgc":
+        return _draw_sgc(rng, oracle, H, idx, store)
     scale = int(rng.integers(8, 12))
     if rng.random() < 0.3 and model != "gcn":   # (GCN is defined on graphs where every vertex has an in-edge)
         n = int(rng.integers(200, 3000))
@@ -76,7 +118,7 @@ def _draw(rng, oracle, H, idx):
     return case, opts, knobs
 
 
-@pytest.mark.parametrize("idx", range(32))
+@pytest.mark.parametrize("idx", range(48))
 def test_random_configuration(oracle, H, idx):
     import paper_2605_09402_amd as atlas
     rng = np.random.default_rng(SEED + 1000 + idx)
