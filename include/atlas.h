@@ -121,7 +121,7 @@ typedef struct {
 
 /* Layer shape.  d_in must be a multiple of 64 (one wavefront holds a row),
  * at most 512 (fp32 SAGE_MEAN: at most 256); d_out a multiple of 16, at most
- * 256.  GAT: fp32 embeddings on a DEVICE graph, 1 <= heads <= 8, d_out a
+ * 256.  GAT: a DEVICE graph, 1 <= heads <= 8, d_out a
  * multiple of 64 and of heads, and (d_out / heads) a multiple of (d_out / 64).
  * SGC_HOP: d_out == d_in (up to 512), activation NONE. */
 typedef struct {

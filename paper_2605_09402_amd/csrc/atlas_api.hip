@@ -242,9 +242,8 @@ int check_dims(const atlas_dims_t &d, const atlas_weights_t &w, int residency) {
         return ATLAS_E_NULL;
     }
     if (d.model == ATLAS_MODEL_GAT) {
-        // fp32 embeddings in HBM; a wave holds a transformed row and each lane's
-        // elements must fall into one head
-        if (residency != ATLAS_RESIDENT_DEVICE || d.in_dtype != ATLAS_DTYPE_F32) return ATLAS_E_BAD_DIMS;
+        // embeddings in HBM; a wave holds a transformed row and each lane's elements must fall into one head
+        if (residency != ATLAS_RESIDENT_DEVICE) return ATLAS_E_BAD_DIMS;
         if (d.heads < 1 || d.heads > 8 || d.d_out % 64 != 0 || d.d_out % d.heads != 0) return ATLAS_E_BAD_DIMS;
         if ((d.d_out / d.heads) % (d.d_out / 64) != 0) return ATLAS_E_BAD_DIMS;
         if (!w.attn_src || !w.attn_dst) return ATLAS_E_NULL;
@@ -516,7 +515,7 @@ int atlas_attention_prepass(atlas_layer_t *L, int64_t src_begin, int64_t src_end
     if (src_begin != L->prepass_next) return ATLAS_E_ORDER;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     L->last_stream = s;
-    HIP_TRY(launch_gat_prepass(emb, 0, src_begin, src_end, L->dims.d_in, static_cast<const float *>(L->gat_wa.p),
+    HIP_TRY(launch_gat_prepass(emb, L->dims.in_dtype, src_begin, src_end, L->dims.d_in, static_cast<const float *>(L->gat_wa.p),
                                L->dims.heads, static_cast<float *>(L->gat_el.p), static_cast<float *>(L->gat_er.p), s));
     L->prepass_next = src_end;
     return ATLAS_OK;
@@ -751,11 +750,18 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         // maxima with the chunk's logits, move the touched destinations to them
         if ((rc = start_span(L, L->t_self, s)) != ATLAS_OK) return rc;
         UpdateArgs u{};
-        u.model = 2;
         u.d_in = d.d_in;
         u.d_out = d.d_out;
         u.K = L->K;
-        u.acc = static_cast<const float *>(emb);
+        if (d.in_dtype == ATLAS_DTYPE_F32) {
+            u.model = 2;                       // plain fp32 rows
+            u.acc = static_cast<const float *>(emb);
+        } else {
+            u.model = 4;                       // plain rows in the 16-bit storage type, 16-bit matrix instructions
+            u.self_rows = emb;
+            u.in_dt = d.in_dtype;
+            u.compute_dt = L->compute_dt;
+        }
         u.counters = L->ctr();
         u.packed_w = L->packed_w.p;
         u.out = L->gat_z.p;

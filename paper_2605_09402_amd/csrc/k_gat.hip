@@ -16,6 +16,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 namespace atlas {
 namespace {
 
@@ -59,6 +61,14 @@ __global__ __launch_bounds__(kBlock) void k_gat_fold_attention(const void *W, co
 // halving butterfly: at each of the first four steps a lane hands half of its
 // values to its partner and keeps the other half, so 15 + 2 shuffles replace
 // 16 x 6.
+// element c of a row stored as fp32, bf16 (uint16_t) or IEEE half
+template <typename T>
+__device__ __forceinline__ float row_elem(const T *row, int c) {
+    if constexpr (std::is_same<T, _Float16>::value) return static_cast<float>(row[c]);
+    else if constexpr (sizeof(T) == 2) return __uint_as_float(static_cast<uint32_t>(row[c]) << 16);
+    else return row[c];
+}
+
 template <typename T>
 __global__ __launch_bounds__(kBlock) void k_gat_prepass(const T *__restrict__ emb, int64_t src_begin, int64_t src_end,
                                                         int d_in, const float *__restrict__ wa, int heads, float *el,
@@ -88,17 +98,12 @@ __global__ __launch_bounds__(kBlock) void k_gat_prepass(const T *__restrict__ em
         for (int i = 0; i < kRegCols; ++i) {
             const int c = lane + 64 * i;
             float x = 0.f;
-            if (c < d_in) {
-                if constexpr (sizeof(T) == 2) x = __uint_as_float(static_cast<uint32_t>(row[c]) << 16);
-                else x = row[c];
-            }
+            if (c < d_in) x = row_elem(row, c);
 #pragma unroll
             for (int k = 0; k < 16; ++k) part[k] += x * wreg[i][k];
         }
         for (int c = lane + 64 * kRegCols; c < d_in; c += 64) {  // wider rows: the rest from memory
-            float x;
-            if constexpr (sizeof(T) == 2) x = __uint_as_float(static_cast<uint32_t>(row[c]) << 16);
-            else x = row[c];
+            const float x = row_elem(row, c);
 #pragma unroll
             for (int k = 0; k < 16; ++k)
                 if (k < H2) part[k] += x * wa[c * H2 + k];
@@ -264,7 +269,10 @@ hipError_t launch_gat_prepass(const void *emb, int in_dt, int64_t src_begin, int
     if (src_end <= src_begin) return hipSuccess;
     if (heads > 8) return hipErrorInvalidValue;
     const int grid = grid_for_waves(src_end - src_begin);
-    if (in_dt)
+    if (in_dt == 2)
+        hipLaunchKernelGGL(k_gat_prepass<_Float16>, dim3(grid), dim3(kBlock), 0, s,
+                           static_cast<const _Float16 *>(emb), src_begin, src_end, d_in, wa, heads, el, er);
+    else if (in_dt == 1)
         hipLaunchKernelGGL(k_gat_prepass<uint16_t>, dim3(grid), dim3(kBlock), 0, s,
                            static_cast<const uint16_t *>(emb), src_begin, src_end, d_in, wa, heads, el, er);
     else

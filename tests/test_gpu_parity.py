@@ -326,3 +326,18 @@ def test_odd_widths(oracle, H, model, store, dims, plan):
     run = H.run_gpu(case, snapshots=True, plan=plan)
     H.check_integers(oracle, case, run, layer=0)
     print("odd widths", model, dims, H.check_outputs(oracle, case, run))
+
+
+@pytest.mark.parametrize("store", [torch.bfloat16, torch.float16], ids=["bf16", "f16"])
+@pytest.mark.parametrize("plan", [False, True], ids=["csr_stream", "planned"])
+def test_gat_16bit_storage(oracle, H, plan, store):
+    """GAT with 16-bit embeddings, weights and outputs: the attention terms and the
+    running softmax stay fp32, the chunk transform runs on the 16-bit matrix
+    instructions.  R-MAT scale 12, 128 -> 4x32 -> 4x32, and 64 -> 2x32."""
+    g = gen.rmat_graph(SEED + 19, 12, 16)
+    case = H.make_case("gat", g, SEED + 19, [128, 128, 128], 600, store=store, feat="uniform", act="elu", heads=4)
+    run = H.run_gpu(case, snapshots=True, plan=plan)
+    H.check_integers(oracle, case, run)
+    print("gat", store, H.check_outputs(oracle, case, run))
+    case = H.make_case("gat", g, SEED + 19, [64, 64], 333, store=store, feat="uniform", act="elu", heads=2)
+    print("gat", store, H.check_outputs(oracle, case, H.run_gpu(case, plan=plan, flush_every=3)))

@@ -28,14 +28,15 @@ def _degree_ordered(oracle, g):
 
 
 def _draw_gat(rng, oracle, H, idx):
-    """GAT: fp32 embeddings on a device graph, plain plan or none."""
+    """GAT: a device graph, plain plan or none."""
     g = gen.rmat_graph(SEED + idx, int(rng.integers(8, 12)), int(rng.integers(4, 20)), random_ids=bool(rng.random() < 0.5))
     if rng.random() < 0.5:
         g = _degree_ordered(oracle, g)
     heads = int(rng.choice([1, 2, 4]))
     dims = [int(rng.choice([64, 128])), int(rng.choice([64, 128])), int(rng.choice([64, 128]))]
-    case = H.make_case("gat", g, SEED + idx, dims, int(rng.integers(37, max(38, g.n // 2))), feat="normal", act="elu",
-                       heads=heads)
+    store = [torch.float32, torch.float32, torch.bfloat16, torch.float16][int(rng.integers(4))]
+    case = H.make_case("gat", g, SEED + idx, dims, int(rng.integers(37, max(38, g.n // 2))), store=store,
+                       feat="normal" if store == torch.float32 else "uniform", act="elu", heads=heads)
     opts = {"flush_every": int(rng.choice([1, 2, 5]))}
     if rng.random() < 0.6:
         opts["plan"] = True
