@@ -95,12 +95,13 @@ hipError_t cold_buffer(size_t bytes, void **out) {
     return hipSuccess;
 }
 
+// tiles per piece of a long pinned-host chunk (atlas_set_piece_tiles); default 2^21 tiles = 2^27 edges
+std::atomic<int64_t> g_piece_tiles{int64_t(1) << 21};
+
 // The chunk loader's copy stream is created once per process and shared by
 // all layers: HIP spreads streams over a few hardware queues, and a stream
 // created anew for every layer can land on the queue that carries the caller's
 // kernels, which silently serialises the copies with them.
-// tiles per piece of a long pinned-host chunk (atlas_set_piece_tiles); default 2^21 tiles = 2^27 edges
-std::atomic<int64_t> g_piece_tiles{int64_t(1) << 21};
 hipStream_t g_copy_stream = nullptr;
 hipError_t loader_stream(hipStream_t *out) {
     std::lock_guard<std::mutex> lk(g_cache_mu);
@@ -314,7 +315,7 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
     L->emb_resident = has_self_term(d.model) && (d.flags & ATLAS_FLAG_EMB_RESIDENT) && !L->tf;
     if (L->tf) {
         const size_t rows = static_cast<size_t>(std::min<int64_t>(d.max_chunk_sources, std::max<int64_t>(n, 1)));
-        if (d.model != ATLAS_MODEL_GIN) HIP_TRY(L->tf_z.alloc(rows * d.d_out * sizeof(float)));
+        if (d.model != ATLAS_MODEL_GIN) HIP_TRY(L->tf_z.alloc(rows * d.d_out * dtype_size(d.in_dtype)));
         if (has_self_term(d.model)) HIP_TRY(L->tf_self.alloc(n1 * d.d_out * sizeof(float)));
         // SAGE: W_neigh and W_self side by side in one fragment-ordered buffer (column blocks of the
         // first, then of the second), so that one pass over the chunk's rows yields both products
@@ -388,13 +389,7 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
             L->off_dev = static_cast<const int64_t *>(L->dev_off.p);
             L->bytes_h2d += (n + 1) * static_cast<int64_t>(sizeof(int64_t));
         }
-        // edge staging slots are allocated by the first chunk that uses them (atlas_broadcast_chunk)
-        if (!has_self_term(d.model)) {
-            const int64_t C = d.max_chunk_sources;
-            for (int i = 0; i < atlas_layer::kStageSlots; ++i)
-                HIP_TRY(L->stage_emb[i].alloc(static_cast<size_t>(std::min(C, std::max<int64_t>(n, 1))) * d.d_in *
-                                              dtype_size(d.in_dtype)));
-        }
+        // staging slots are allocated by the first chunk that uses them (atlas_broadcast_chunk)
     } else {
         L->off_dev = L->g.row_offsets;
     }
@@ -449,6 +444,20 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
     return ATLAS_OK;
 }
 
+
+GatState gat_state(atlas_layer *L) {
+    GatState g;
+    g.el = static_cast<const float *>(L->gat_el.p);
+    g.er = static_cast<const float *>(L->gat_er.p);
+    g.m_cur = static_cast<int32_t *>(L->gat_mcur.p);
+    g.m_next = static_cast<int32_t *>(L->gat_mnext.p);
+    g.l = static_cast<float *>(L->gat_l.p);
+    g.heads = L->dims.heads;
+    g.dh = L->dims.d_out / L->dims.heads;
+    g.slope = L->dims.neg_slope;
+    return g;
+}
+
 }  // namespace
 
 extern "C" {
@@ -489,21 +498,6 @@ int atlas_layer_init(const atlas_graph_t *graph, const atlas_dims_t *dims, const
     *out = L;
     return ATLAS_OK;
 }
-
-namespace {
-GatState gat_state(atlas_layer *L) {
-    GatState g;
-    g.el = static_cast<const float *>(L->gat_el.p);
-    g.er = static_cast<const float *>(L->gat_er.p);
-    g.m_cur = static_cast<int32_t *>(L->gat_mcur.p);
-    g.m_next = static_cast<int32_t *>(L->gat_mnext.p);
-    g.l = static_cast<float *>(L->gat_l.p);
-    g.heads = L->dims.heads;
-    g.dh = L->dims.d_out / L->dims.heads;
-    g.slope = L->dims.neg_slope;
-    return g;
-}
-}  // namespace
 
 int atlas_attention_prepass(atlas_layer_t *L, int64_t src_begin, int64_t src_end, const void *emb,
                             void *hip_stream) {
@@ -613,6 +607,9 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         if (rc != ATLAS_OK) return rc;
         const void *emb_dst = emb;   // device-resident embeddings are read where they are
         if (!emb_dev) {
+            if (!self_dst && !L->stage_emb[slot].p)   // every chunk fits a slot of the layer's largest chunk
+                HIP_TRY(L->stage_emb[slot].alloc(static_cast<size_t>(std::min<int64_t>(d.max_chunk_sources,
+                                                                                      std::max<int64_t>(L->n, 1))) * row_bytes));
             void *stage = self_dst ? static_cast<void *>(self_dst) : L->stage_emb[slot].p;
             HIP_TRY(hipMemcpyAsync(stage, emb, emb_bytes, hipMemcpyHostToDevice, L->copy_stream));
             emb_dst = stage;
