@@ -121,8 +121,8 @@ typedef struct {
 
 /* Layer shape.  d_in must be a multiple of 64 (one wavefront holds a row),
  * at most 512 (fp32 SAGE_MEAN: at most 256); d_out a multiple of 16, at most
- * 256.  GAT: a DEVICE graph, 1 <= heads <= 8, d_out a
- * multiple of 64 and of heads, and (d_out / heads) a multiple of (d_out / 64).
+ * 256.  GAT: 1 <= heads <= 8, d_out a multiple of 64 and of heads, and
+ * (d_out / heads) a multiple of (d_out / 64); no bounded accumulator store.
  * SGC_HOP: d_out == d_in (up to 512), activation NONE. */
 typedef struct {
     int32_t model;             /* atlas_model                                              */
@@ -214,7 +214,8 @@ int atlas_layer_init(const atlas_graph_t *graph, const atlas_dims_t *dims,
  * of rows [src_begin, src_end).  Every row must have been through this call
  * before the first atlas_broadcast_chunk (a destination's term is needed when
  * its first message arrives).  Same chunk rules and `emb` meaning as
- * atlas_broadcast_chunk.  E_STATE for other models. */
+ * atlas_broadcast_chunk; host rows of a PINNED_HOST graph therefore cross the
+ * link twice per layer, here and in their broadcast.  E_STATE for other models. */
 int atlas_attention_prepass(atlas_layer_t *layer, int64_t src_begin, int64_t src_end,
                             const void *emb, void *hip_stream);
 

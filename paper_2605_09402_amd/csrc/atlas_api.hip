@@ -150,7 +150,7 @@ struct atlas_layer {
     Buf indeg_own, pending, ready, counters, counters64, acc, self_rows, packed_w, bias, dev_off;
     Buf gat_el, gat_er, gat_mcur, gat_mnext, gat_l, gat_wa, gat_z;   // GAT state
     Buf gat_scores;                                                  // GAT, planned chunks: per-edge logits
-    int64_t prepass_next = 0;
+    int64_t prepass_next = 0, num_prepass = 0;
     const int32_t *indeg = nullptr;
     const int64_t *off_dev = nullptr;  // device-visible row offsets
 
@@ -243,8 +243,7 @@ int check_dims(const atlas_dims_t &d, const atlas_weights_t &w, int residency) {
         return ATLAS_E_NULL;
     }
     if (d.model == ATLAS_MODEL_GAT) {
-        // embeddings in HBM; a wave holds a transformed row and each lane's elements must fall into one head
-        if (residency != ATLAS_RESIDENT_DEVICE) return ATLAS_E_BAD_DIMS;
+        // a wave holds a transformed row and each lane's elements must fall into one head
         if (d.heads < 1 || d.heads > 8 || d.d_out % 64 != 0 || d.d_out % d.heads != 0) return ATLAS_E_BAD_DIMS;
         if ((d.d_out / d.heads) % (d.d_out / 64) != 0) return ATLAS_E_BAD_DIMS;
         if (!w.attn_src || !w.attn_dst) return ATLAS_E_NULL;
@@ -445,6 +444,26 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
 }
 
 
+// PINNED_HOST graphs: the caller's embeddings are pinned host memory (staged per chunk) or device memory
+// (a later layer reading the previous layer's output: read in place).  One kind per layer.
+int note_emb_location(atlas_layer *L, const void *emb) {
+    hipPointerAttribute_t attr{};
+    int on_device = 0;
+    if (hipPointerGetAttributes(&attr, emb) == hipSuccess) on_device = attr.type == hipMemoryTypeDevice ? 1 : 0;
+    else (void)hipGetLastError();   // pageable memory is unknown to the runtime: host
+    if (L->emb_on_device >= 0 && L->emb_on_device != on_device) return ATLAS_E_STATE;
+    L->emb_on_device = on_device;
+    return ATLAS_OK;
+}
+
+// Rows of a staging slot of the chunk loader, allocated at first use (every chunk fits the layer's largest).
+int stage_emb_slot(atlas_layer *L, int slot) {
+    if (L->stage_emb[slot].p) return ATLAS_OK;
+    const size_t rows = static_cast<size_t>(std::min<int64_t>(L->dims.max_chunk_sources, std::max<int64_t>(L->n, 1)));
+    HIP_TRY(L->stage_emb[slot].alloc(rows * L->dims.d_in * dtype_size(L->dims.in_dtype)));
+    return ATLAS_OK;
+}
+
 GatState gat_state(atlas_layer *L) {
     GatState g;
     g.el = static_cast<const float *>(L->gat_el.p);
@@ -509,8 +528,34 @@ int atlas_attention_prepass(atlas_layer_t *L, int64_t src_begin, int64_t src_end
     if (src_begin != L->prepass_next) return ATLAS_E_ORDER;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     L->last_stream = s;
-    HIP_TRY(launch_gat_prepass(emb, L->dims.in_dtype, src_begin, src_end, L->dims.d_in, static_cast<const float *>(L->gat_wa.p),
+    const void *rows = emb;
+    int slot = -1;
+    if (L->g.residency == ATLAS_RESIDENT_PINNED_HOST) {
+        int rc = note_emb_location(L, emb);
+        if (rc != ATLAS_OK) return rc;
+        if (!L->emb_on_device) {
+            // host rows cross the link here and once more when their chunk is broadcast: the attention
+            // terms of all vertices must exist before the first message (Sec. 3.9)
+            slot = static_cast<int>(L->num_prepass % atlas_layer::kStageSlots);
+            if ((rc = stage_emb_slot(L, slot)) != ATLAS_OK) return rc;
+            if (L->slot_used[slot]) HIP_TRY(hipStreamWaitEvent(L->copy_stream, L->slot_free[slot], 0));
+            const size_t bytes = static_cast<size_t>(src_end - src_begin) * L->dims.d_in * dtype_size(L->dims.in_dtype);
+            if ((rc = start_span(L, L->t_copy, L->copy_stream)) != ATLAS_OK) return rc;
+            HIP_TRY(hipMemcpyAsync(L->stage_emb[slot].p, emb, bytes, hipMemcpyHostToDevice, L->copy_stream));
+            if ((rc = end_span(L, L->t_copy, L->copy_stream)) != ATLAS_OK) return rc;
+            HIP_TRY(hipEventRecord(L->slot_loaded[slot], L->copy_stream));
+            HIP_TRY(hipStreamWaitEvent(s, L->slot_loaded[slot], 0));
+            L->bytes_h2d += static_cast<int64_t>(bytes);
+            rows = L->stage_emb[slot].p;
+        }
+    }
+    HIP_TRY(launch_gat_prepass(rows, L->dims.in_dtype, src_begin, src_end, L->dims.d_in, static_cast<const float *>(L->gat_wa.p),
                                L->dims.heads, static_cast<float *>(L->gat_el.p), static_cast<float *>(L->gat_er.p), s));
+    if (slot >= 0) {
+        HIP_TRY(hipEventRecord(L->slot_free[slot], s));
+        L->slot_used[slot] = true;
+    }
+    L->num_prepass += 1;
     L->prepass_next = src_end;
     return ATLAS_OK;
 }
@@ -547,18 +592,14 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
     if (L->g.residency == ATLAS_RESIDENT_PINNED_HOST) {
         // where the caller keeps this layer's embeddings: pinned host memory (staged per chunk) or device
         // memory (a later layer reading the previous layer's output; read in place)
-        hipPointerAttribute_t attr{};
-        int on_device = 0;
-        if (hipPointerGetAttributes(&attr, emb) == hipSuccess) on_device = attr.type == hipMemoryTypeDevice ? 1 : 0;
-        else (void)hipGetLastError();   // pageable memory is unknown to the runtime: host
-        if (L->emb_on_device >= 0 && L->emb_on_device != on_device) return ATLAS_E_STATE;
-        if (L->emb_on_device < 0 && L->emb_resident && !on_device) {
+        int rc = note_emb_location(L, emb);
+        if (rc != ATLAS_OK) return rc;
+        if (L->emb_resident && !L->emb_on_device) {
             // host embeddings cannot be read in place: keep a copy of the own rows after all
             L->emb_resident = false;
             const size_t n1 = static_cast<size_t>(std::max<int64_t>(L->n, 1));
             HIP_TRY(L->self_rows.alloc(n1 * d.d_in * dtype_size(d.in_dtype)));
         }
-        L->emb_on_device = on_device;
     }
     const bool emb_dev = L->g.residency == ATLAS_RESIDENT_DEVICE || L->emb_on_device == 1;
     if (L->emb_resident) {
@@ -607,9 +648,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         if (rc != ATLAS_OK) return rc;
         const void *emb_dst = emb;   // device-resident embeddings are read where they are
         if (!emb_dev) {
-            if (!self_dst && !L->stage_emb[slot].p)   // every chunk fits a slot of the layer's largest chunk
-                HIP_TRY(L->stage_emb[slot].alloc(static_cast<size_t>(std::min<int64_t>(d.max_chunk_sources,
-                                                                                      std::max<int64_t>(L->n, 1))) * row_bytes));
+            if (!self_dst && (rc = stage_emb_slot(L, slot)) != ATLAS_OK) return rc;
             void *stage = self_dst ? static_cast<void *>(self_dst) : L->stage_emb[slot].p;
             HIP_TRY(hipMemcpyAsync(stage, emb, emb_bytes, hipMemcpyHostToDevice, L->copy_stream));
             emb_dst = stage;
@@ -630,7 +669,8 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
                 const int64_t ntiles = (pc->n_edges + 63) / 64;
                 // (a planned-only layer whose plan has no list of rows to clear finds them by a scan of the
                 // whole chunk's words: such a chunk is pushed in one piece)
-                if (ntiles >= 2 * kPieceTiles && (!L->planned_only || pc->has_zero_rows))
+                // (so is a GAT chunk: its maximum sweep reads all of the chunk's edges before the push)
+                if (ntiles >= 2 * kPieceTiles && (!L->planned_only || pc->has_zero_rows) && d.model != ATLAS_MODEL_GAT)
                     npieces = static_cast<int>((ntiles + kPieceTiles - 1) / kPieceTiles);
                 auto &evs = L->piece_ev[slot];
                 while (static_cast<int>(evs.size()) < npieces) {
@@ -670,6 +710,9 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
             }
             packed_chunk = true;
             ga.src_sorted = static_cast<const int32_t *>(L->unpacked.p);
+            if (npieces == 1)
+                HIP_TRY(launch_unpack24(static_cast<const char *>(L->stage_col[slot].p), pc->n_edges, src_begin,
+                                        static_cast<int32_t *>(L->unpacked.p), s));
         }
         L->bytes_h2d += static_cast<int64_t>((emb_dev ? 0 : emb_bytes) + staged_bytes);
         a.col = static_cast<const int32_t *>(L->stage_col[slot].p);
@@ -752,10 +795,10 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         u.K = L->K;
         if (d.in_dtype == ATLAS_DTYPE_F32) {
             u.model = 2;                       // plain fp32 rows
-            u.acc = static_cast<const float *>(emb);
+            u.acc = static_cast<const float *>(a.emb);
         } else {
             u.model = 4;                       // plain rows in the 16-bit storage type, 16-bit matrix instructions
-            u.self_rows = emb;
+            u.self_rows = a.emb;
             u.in_dt = d.in_dtype;
             u.compute_dt = L->compute_dt;
         }
@@ -840,7 +883,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
                 ga.tile_begin = p * kPieceTiles;
                 ga.tile_end = p + 1 < npieces ? (p + 1) * kPieceTiles : -1;
             }
-            if (packed_chunk) {
+            if (packed_chunk && npieces > 1) {
                 const int64_t e_lo = ga.tile_begin * 64;
                 const int64_t e_hi = ga.tile_end < 0 ? pc->n_edges : std::min<int64_t>(pc->n_edges, ga.tile_end * 64);
                 HIP_TRY(launch_unpack24(static_cast<const char *>(L->stage_col[slot].p) + e_lo * 3, e_hi - e_lo, src_begin,

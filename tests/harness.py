@@ -179,26 +179,24 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
             else:
                 atlas.atlas_flush_ready(h, out, stream)
 
+        def chunk_rows(b0, b1):
+            if not pinned_host or (li > 0 and device_later):
+                return cur_dev[b0:b1]
+            if li == 0:
+                return cur_host[b0:b1]
+            emb = cur_dev[b0:b1].cpu().pin_memory()  # later layers: stage the device rows through pinned memory
+            keep.append(emb)
+            return emb
+
         if case.model == "gat":
             for b0 in range(0, n, case.chunk):
                 b1 = min(n, b0 + case.chunk)
-                src = cur_host if (pinned_host and li == 0) else cur_dev
-                atlas.atlas_attention_prepass(h, b0, b1, src[b0:b1], stream)
+                atlas.atlas_attention_prepass(h, b0, b1, chunk_rows(b0, b1), stream)
         flush()  # vertices that are complete at layer start
         ci = 0
         for b0 in range(0, n, case.chunk):
             b1 = min(n, b0 + case.chunk)
-            if pinned_host:
-                if li == 0:
-                    emb = cur_host[b0:b1]
-                elif device_later:
-                    emb = cur_dev[b0:b1]
-                else:  # later layers: stage the device rows through pinned memory
-                    emb = cur_dev[b0:b1].cpu().pin_memory()
-                    keep.append(emb)
-            else:
-                emb = cur_dev[b0:b1]
-            atlas.atlas_broadcast_chunk(h, b0, b1, emb, stream)
+            atlas.atlas_broadcast_chunk(h, b0, b1, chunk_rows(b0, b1), stream)
             ci += 1
             if snapshots:
                 pend = np.empty(n, dtype=np.int32)

@@ -341,3 +341,22 @@ def test_gat_16bit_storage(oracle, H, plan, store):
     print("gat", store, H.check_outputs(oracle, case, run))
     case = H.make_case("gat", g, SEED + 19, [64, 64], 333, store=store, feat="uniform", act="elu", heads=2)
     print("gat", store, H.check_outputs(oracle, case, H.run_gpu(case, plan=plan, flush_every=3)))
+
+
+@pytest.mark.parametrize("store", [torch.float32, torch.bfloat16], ids=["fp32", "bf16"])
+@pytest.mark.parametrize("plan", [False, True], ids=["csr_stream", "planned"])
+def test_gat_pinned_host_graph(oracle, H, plan, store):
+    """GAT with graph and layer-0 embeddings in pinned host memory: the rows are
+    staged once for the attention terms and once for their broadcast; planned
+    chunks arrive as 24-bit words and are unpacked before the maximum sweep.
+    Later layers read pinned copies, or (second run) the previous output in HBM."""
+    g = gen.rmat_graph(SEED + 23, 12, 16)
+    case = H.make_case("gat", g, SEED + 23, [128, 128, 64], 600, store=store, feat="uniform", act="elu", heads=4)
+    run = H.run_gpu(case, snapshots=True, plan=plan, pinned_host=True)
+    H.check_integers(oracle, case, run, layer=0)
+    H.check_integers(oracle, case, run, layer=1)
+    print("gat pinned", store, H.check_outputs(oracle, case, run))
+    assert run.stats[0]["bytes_copied_h2d"] >= 2 * case.n * 128 * (4 if store == torch.float32 else 2)
+    run = H.run_gpu(case, plan=plan, pinned_host=True, device_later=True, flush_every=3)
+    print("gat pinned, later layers in HBM", store, H.check_outputs(oracle, case, run))
+

@@ -28,7 +28,7 @@ def _degree_ordered(oracle, g):
 
 
 def _draw_gat(rng, oracle, H, idx):
-    """GAT: a device graph, plain plan or none."""
+    """GAT: plain plan or none, graph in HBM or in pinned host memory."""
     g = gen.rmat_graph(SEED + idx, int(rng.integers(8, 12)), int(rng.integers(4, 20)), random_ids=bool(rng.random() < 0.5))
     if rng.random() < 0.5:
         g = _degree_ordered(oracle, g)
@@ -40,6 +40,9 @@ def _draw_gat(rng, oracle, H, idx):
     opts = {"flush_every": int(rng.choice([1, 2, 5]))}
     if rng.random() < 0.6:
         opts["plan"] = True
+    if rng.random() < 0.4:
+        opts["pinned_host"] = True
+        opts["device_later"] = bool(rng.random() < 0.5)
     return case, opts, {"run": int(rng.choice([0, 2, 5])), "piece": 0}
 
 
