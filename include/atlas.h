@@ -90,7 +90,7 @@ enum atlas_flags {
                                     of a vertex without in-edges is never read.  Ignored without
                                     a plan and for GAT.  With it, ATLAS_DBG_ACC rows of vertices
                                     that have received nothing yet are undefined. */
-    ATLAS_FLAG_TRANSFORM_FIRST = 8 /* SAGE_MEAN / GCN_SYM / GIN on a DEVICE graph: the weight matrix is
+    ATLAS_FLAG_TRANSFORM_FIRST = 8 /* SAGE_MEAN / GCN_SYM / GIN: the weight matrix is
                                     applied to each chunk's rows before they are pushed (the linear map
                                     commutes with the neighbour sum), so messages and accumulators are
                                     d_out wide instead of d_in.  Pays when d_out is well below d_in (wide
@@ -98,8 +98,8 @@ enum atlas_flags {
                                     and d_out must be a multiple of 64.  The pushed products are messages
                                     and travel in the embeddings' storage type (SAGE_MEAN, GCN_SYM; GIN
                                     pushes fp32), sums stay fp32: results equal the default order up to
-                                    one rounding of each product to that type.  Ignored for other models
-                                    and residencies. */
+                                    one rounding of each product to that type.  Ignored for other
+                                    models. */
 };
 
 /* The graph: CSR by SOURCE vertex (paper Sec. 3.2: out-edges, read sequentially

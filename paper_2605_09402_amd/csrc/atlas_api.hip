@@ -221,8 +221,8 @@ namespace {
 // Transform first (ATLAS_FLAG_TRANSFORM_FIRST): the linear map commutes with the
 // sum, so each chunk's rows are multiplied by W before they are pushed and the
 // accumulators are d_out wide.
-bool transform_first(const atlas_dims_t &d, int residency) {
-    return (d.flags & ATLAS_FLAG_TRANSFORM_FIRST) && residency == ATLAS_RESIDENT_DEVICE &&
+bool transform_first(const atlas_dims_t &d) {
+    return (d.flags & ATLAS_FLAG_TRANSFORM_FIRST) &&
            (d.model == ATLAS_MODEL_SAGE_MEAN || d.model == ATLAS_MODEL_GCN_SYM || d.model == ATLAS_MODEL_GIN);
 }
 
@@ -248,7 +248,7 @@ int check_dims(const atlas_dims_t &d, const atlas_weights_t &w, int residency) {
         if ((d.d_out / d.heads) % (d.d_out / 64) != 0) return ATLAS_E_BAD_DIMS;
         if (!w.attn_src || !w.attn_dst) return ATLAS_E_NULL;
     }
-    const bool tf = transform_first(d, residency);
+    const bool tf = transform_first(d);
     if (d.d_in <= 0 || d.d_in % 64 != 0 || d.d_in > (tf ? 1024 : 512)) return ATLAS_E_BAD_DIMS;
     if (tf && d.d_out % 64 != 0) return ATLAS_E_BAD_DIMS;   // a wave holds one d_out-wide product row
     if (d.d_out <= 0 || d.d_out % 16 != 0 || (d.d_out > 256 && d.model != ATLAS_MODEL_SGC_HOP))
@@ -499,7 +499,7 @@ int atlas_layer_init(const atlas_graph_t *graph, const atlas_dims_t *dims, const
     L->n = graph->num_vertices;
     L->e = graph->num_edges;
     L->selfmsg = has_self_term(dims->model) ? 1 : 0;
-    L->tf = transform_first(*dims, graph->residency);
+    L->tf = transform_first(*dims);
     L->K = dims->model == ATLAS_MODEL_SAGE_MEAN && !L->tf ? 2 * dims->d_in : dims->d_in;
     L->compute_dt = dims->in_dtype;
     L->acc_width = dims->model == ATLAS_MODEL_GAT || L->tf ? dims->d_out : dims->d_in;

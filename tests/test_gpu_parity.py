@@ -194,6 +194,11 @@ def test_transform_first(oracle, H, model, store, dims, plan):
     H.check_integers(oracle, case, run, layer=0)
     H.check_integers(oracle, case, run, layer=1)
     print("transform first", model, dims, H.check_outputs(oracle, case, run))
+    # graph and layer-0 rows in pinned host memory: the staged rows are what is transformed
+    run = H.run_gpu(case, plan=plan, planned_only=plan, transform_first=True, pinned_host=True, flush_every=2)
+    print("transform first, pinned host", model, dims, H.check_outputs(oracle, case, run))
+    run = H.run_gpu(case, plan=plan, transform_first=True, pinned_host=True, device_later=True)
+    print("transform first, pinned host, later layers in HBM", model, dims, H.check_outputs(oracle, case, run))
 
 
 @pytest.mark.parametrize("plan", [False, True], ids=["csr_stream", "planned"])

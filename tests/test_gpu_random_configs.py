@@ -89,9 +89,9 @@ def _draw(rng, oracle, H, idx):
     opts = {}
     plan_kind = int(rng.integers(3))          # 0 none, 1 plain, 2 source-blocked
     pinned = bool(rng.random() < 0.4)
-    tf = bool(rng.random() < 0.25) and not pinned
+    tf = bool(rng.random() < 0.25)
     if model == "gin" and store == torch.float16:
-        tf, pinned = True, False              # half-precision GIN runs transform-first only (device graphs)
+        tf = True                             # half-precision GIN runs transform-first only
     if tf:
         dims[1] = 64 if dims[1] not in (64, 128) else dims[1]
         dims[2] = 64                          # transform-first needs output widths that are multiples of 64
