@@ -153,9 +153,10 @@ typedef struct {
  * (the chunk is then partly marked and the layer can only be finished, which
  * frees it; a smaller chunk size, more rows or an order that completes vertices
  * sooner, such as atlas_reorder_score_desc, is the remedy).
- * Requires a DEVICE graph with a plan and chunks that coincide with the planned
- * ones (as with ATLAS_FLAG_PLANNED_ONLY); not available for GAT.  Each chunk
- * costs one wait for the stream (the host reads the slot counts). */
+ * Requires a graph with a plan and chunks that coincide with the planned ones
+ * (as with ATLAS_FLAG_PLANNED_ONLY); not available for GAT.  Each chunk costs
+ * one wait for the stream (the host reads the slot counts).  On a PINNED_HOST
+ * graph the evicted rows share the host link with the chunk loader's copies. */
 enum atlas_evict_policy {
     ATLAS_EVICT_MIN_PENDING = 0, /* fewest pending messages first (the paper's policy)      */
     ATLAS_EVICT_MAX_PENDING = 1  /* most pending messages first (for comparison)            */

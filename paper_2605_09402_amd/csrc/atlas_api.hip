@@ -234,7 +234,7 @@ int aggregate_kind(int model) {
     return model == ATLAS_MODEL_GAT ? 2 : 0;
 }
 
-int check_dims(const atlas_dims_t &d, const atlas_weights_t &w, int residency) {
+int check_dims(const atlas_dims_t &d, const atlas_weights_t &w) {
     if (d.model < ATLAS_MODEL_SAGE_MEAN || d.model > ATLAS_MODEL_SGC_HOP) return ATLAS_E_BAD_DIMS;
     if (d.model == ATLAS_MODEL_SGC_HOP) {
         // propagation only: no weights, the output row is the scaled accumulator row
@@ -259,7 +259,7 @@ int check_dims(const atlas_dims_t &d, const atlas_weights_t &w, int residency) {
     if (d.max_chunk_sources <= 0) return ATLAS_E_BAD_DIMS;
     if (d.hot_slots < 0 || d.evict_policy < ATLAS_EVICT_MIN_PENDING || d.evict_policy > ATLAS_EVICT_MAX_PENDING)
         return ATLAS_E_BAD_DIMS;
-    if (d.hot_slots > 0 && (d.model == ATLAS_MODEL_GAT || residency != ATLAS_RESIDENT_DEVICE)) return ATLAS_E_BAD_DIMS;
+    if (d.hot_slots > 0 && d.model == ATLAS_MODEL_GAT) return ATLAS_E_BAD_DIMS;
     const int K = d.model == ATLAS_MODEL_SAGE_MEAN && !tf ? 2 * d.d_in : d.d_in;
     // GIN forms (1 + eps) x_v + sum in the compute type before the contraction: a hub's sum leaves the
     // range of IEEE half, so half-precision GIN runs transform-first only (products summed in fp32)
@@ -305,7 +305,8 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
     L->bounded = d.hot_slots > 0 && d.hot_slots < n;
     if (L->bounded) {
         const atlas_plan *pl = L->g.plan;
-        if (!pl || pl->host || pl->n != n || pl->e != L->e) return ATLAS_E_STATE;
+        if (!pl || pl->host != (L->g.residency == ATLAS_RESIDENT_PINNED_HOST) || pl->n != n || pl->e != L->e)
+            return ATLAS_E_STATE;
         if (d.hot_slots >= (int64_t(1) << 31)) return ATLAS_E_OVERFLOW;
     }
     const size_t acc_rows = L->bounded ? static_cast<size_t>(d.hot_slots) : n1;
@@ -489,7 +490,7 @@ int atlas_layer_init(const atlas_graph_t *graph, const atlas_dims_t *dims, const
     if (!graph->row_offsets || (graph->num_edges > 0 && !graph->col_indices)) return ATLAS_E_NULL;
     if (graph->residency != ATLAS_RESIDENT_DEVICE && graph->residency != ATLAS_RESIDENT_PINNED_HOST)
         return ATLAS_E_BAD_DIMS;
-    int rc = check_dims(*dims, *weights, graph->residency);
+    int rc = check_dims(*dims, *weights);
     if (rc != ATLAS_OK) return rc;
 
     atlas_layer *L = new (std::nothrow) atlas_layer();

@@ -68,6 +68,12 @@ def test_bounded_store_matches_replay(oracle, H, model, store, policy):
     for st in run.stats:
         assert (st["hot_evictions"], st["hot_reloads"], st["hot_peak_slots"]) == (sum(ev), sum(rl), peak)
         assert st["vertices_flushed"] == case.n
+    # graph, plan and layer-0 rows in pinned host memory (the paper's setting: everything streamed, a bounded
+    # store on the device): the same evictions, the same outputs
+    run = H.run_gpu(case, plan=True, hot_slots=slots, evict_policy=policy, pinned_host=True, device_later=policy == 1)
+    H.check_outputs(oracle, case, run)
+    for st in run.stats:
+        assert (st["hot_evictions"], st["hot_reloads"], st["hot_peak_slots"]) == (sum(ev), sum(rl), peak)
 
 
 def test_minimum_pending_evicts_less_than_maximum_pending(oracle, H):

@@ -110,7 +110,7 @@ def _draw(rng, oracle, H, idx):
     case = H.make_case(model, g, SEED + idx, dims, chunk, store=store,
                        feat="normal" if store == torch.float32 else "uniform", eps=0.5 if model == "gin" else 0.0)
     knobs = {"run": int(rng.choice([0, 0, 2, 5])), "piece": int(rng.choice([0, 1, 4]))}
-    if plan_kind == 1 and not pinned and not tf and rng.random() < 0.4:   # bounded store where the chunks fit
+    if plan_kind == 1 and not tf and rng.random() < 0.4:   # bounded store where the chunks fit
         started = int((np.bincount(case.col.numpy(), minlength=case.n) > 0).sum())
         slots = max(1, int(started * rng.uniform(0.6, 0.95)))
         try:
