@@ -17,9 +17,12 @@
  *   atlas_layer_finish     exactly-once check, statistics, release (Sec. 3.1:
  *                          every embedding is consumed exactly once per layer)
  *
- * All work runs in HIP kernels on the current device.  Nothing here allocates
- * or touches torch objects; every pointer is a plain address whose residency
- * (device / pinned host / pageable host) is stated per argument.  No function
+ * All work runs in HIP kernels on the current device; a process uses the
+ * library with one device (its cache of device buffers, freed by
+ * atlas_release_cache, and the chunk loader's copy stream belong to the device
+ * that was current when they were first needed).  Every pointer is a plain
+ * address whose residency (device / pinned host / pageable host) is stated
+ * per argument; layer state is allocated by the library with hipMalloc.  No function
  * throws or aborts; every function returns ATLAS_OK (0) or a negative
  * atlas_status code and has no partial effect when it rejects its arguments.
  * A layer object must be used from one host thread at a time, and all calls on
