@@ -319,13 +319,18 @@ def main() -> int:
     n_with_in = int((indeg > 0).sum().item())
     upd_flops = 2.0 * n * K * wl.dims[1]      # SAGE / GCN: the flush GEMM; GAT: the per-chunk transform (in ms_self)
     upd_s = upd_ms / args.steps / 1e3
+    upd_bytes = n_with_in * 4 * d + n * ((s_in * d if wl.model in ("sage", "gin") else 0) + s_in * wl.dims[1])
+    mfma_peak = 2.5e15 if sdt in (atlas.DTYPE_BF16, atlas.DTYPE_F16) else 157.3e12
+    # the contraction's ceiling at this shape: the MFMA peak, or its flops in the time its bytes need at the HBM peak
+    upd_ceiling = min(mfma_peak, upd_flops / (upd_bytes / 8e12))
     update = {
         "kernel": "k_update", "tflops": round(upd_flops / upd_s / 1e12, 2),
-        "mfma_peak_tflops": 2500.0 if sdt in (atlas.DTYPE_BF16, atlas.DTYPE_F16) else 157.3,
-        "frac_of_mfma_peak": round(upd_flops / upd_s / (2.5e15 if sdt in (atlas.DTYPE_BF16, atlas.DTYPE_F16) else 157.3e12), 4),
+        "mfma_peak_tflops": mfma_peak / 1e12,
+        "frac_of_mfma_peak": round(upd_flops / upd_s / mfma_peak, 4),
         # accumulator rows are read only for vertices that received something
-        "hbm_GBps": round((n_with_in * 4 * d + n * ((s_in * d if wl.model in ("sage", "gin") else 0) + s_in * wl.dims[1]))
-                          / upd_s / 1e9, 1),
+        "hbm_GBps": round(upd_bytes / upd_s / 1e9, 1),
+        "ceiling_tflops": round(upd_ceiling / 1e12, 1),
+        "frac_of_ceiling": round(upd_flops / upd_s / upd_ceiling, 4),
         "rows_with_in_edges": n_with_in,
         "ms_per_layer": round(upd_ms / args.steps, 3),
     }
