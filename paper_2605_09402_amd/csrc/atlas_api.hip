@@ -174,6 +174,7 @@ struct atlas_layer {
                                        // not yet known (-1); e.g. a later layer whose input is the previous output
 
     int64_t next_src = 0;
+    uint32_t run_tickets = 0;          // tickets drawn so far from the grouped aggregation's run counter
     int64_t num_chunks = 0, num_flushes = 0;
     int64_t bytes_h2d = 0;
 
@@ -898,7 +899,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
                     HIP_TRY(launch_zero_cut_first_rows(ga, s));   // (one piece, see above)
                 }
             }
-            HIP_TRY(launch_aggregate_grouped(ga, s));
+            HIP_TRY(launch_aggregate_grouped(ga, &L->run_tickets, s));
         }
     } else {
         HIP_TRY(launch_aggregate(a, s));

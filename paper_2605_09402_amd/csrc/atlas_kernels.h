@@ -11,6 +11,7 @@ enum Counter {
     CTR_READY_TAIL = 0,  // ready-list length (vertices completed so far)
     CTR_READY_HEAD = 1,  // ready-list prefix already flushed
     CTR_NUM_FLUSHES = 2,
+    CTR_NEXT_RUN = 32,   // ticket counter of the grouped aggregation's dynamically assigned runs (its own cache line)
     CTR_COUNT = 64
 };
 
@@ -137,6 +138,10 @@ struct GroupedArgs {
     int64_t tile_end = -1;      // A chunk that arrives over the host link in pieces is pushed piece by piece;
                                 // a group cut by a piece boundary is added with atomics like one cut by a run.
                                 // (launch_zero_cut_first_rows always examines the whole chunk)
+    // set by the launcher:
+    int nruns = 0;              // runs of tiles_per_run tiles in [tile_begin, tile_end)
+    int dynamic = 0;            // 1: a wave's runs after its first are handed out by counters[CTR_NEXT_RUN]
+    uint32_t run_base = 0;      // value of that counter when the launch begins
 };
 
 // forced run length of the grouped aggregation, 0 = chosen per launch
@@ -145,7 +150,9 @@ constexpr int kMaxTilesPerRun = 16;
 
 // S2+S3+S4 over a planned chunk: per-destination register sums, one row update
 // and one pending decrement per (chunk, destination) group.
-hipError_t launch_aggregate_grouped(const GroupedArgs &a, hipStream_t s);
+// `run_tickets`: the layer's count of tickets drawn from counters[CTR_NEXT_RUN] so far (starts at 0 with the
+// zeroed counter); every launch that hands out runs dynamically draws exactly one ticket per run and advances it.
+hipError_t launch_aggregate_grouped(const GroupedArgs &a, uint32_t *run_tickets, hipStream_t s);
 
 // Plan construction for one chunk (synchronous).  off_dev is addressed by global
 // source id and col_dev by global edge number (only [src_begin, src_end] and

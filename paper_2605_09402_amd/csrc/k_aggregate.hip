@@ -473,8 +473,16 @@ void k_aggregate_grouped(GroupedArgs a) {
     // rows, and the result of a tile's pending-count reads is consumed during
     // the next tile, so that the only memory waits on the wave's critical
     // path are those of the row gathers.
+    //
+    // Waves do not advance at the same speed: a CU issues for its oldest waves
+    // first, and with equal shares the workgroup that reached a CU first is
+    // done a third earlier than the one that came last, which then works on
+    // with few waves left to hide its gathers.  Long launches therefore hand
+    // out the runs after a wave's first through a ticket counter (one atomic
+    // per run, fetched a run ahead); short ones, where one atomic per tile or
+    // two would be more than one address sustains, keep the fixed stride.
     const int run = a.tiles_per_run;
-    const int nruns = t_hi > t_lo ? (t_hi - t_lo + run - 1) / run : 0;
+    const int nruns = a.nruns;
     float sum[VPL];
 #pragma unroll
     for (int i = 0; i < VPL; ++i) sum[i] = 0.f;
@@ -489,6 +497,8 @@ void k_aggregate_grouped(GroupedArgs a) {
     int t = rn < nruns ? t_lo + rn * run : -1;
     int t_end = t + run < t_hi ? t + run : t_hi;
     bool run_start = true;
+    int32_t ticket = 0;   // lane 0: counter value drawn for the wave's next run
+    if (a.dynamic && t >= 0 && lane == 0) ticket = atomicAdd(&a.counters[CTR_NEXT_RUN], 1);
     int32_t s = 0, g0 = 0, prev_word = -1, gd = 0;
     if (t >= 0) {
         const int64_t e0 = static_cast<int64_t>(t) * kTileEdges;
@@ -510,10 +520,18 @@ void k_aggregate_grouped(GroupedArgs a) {
         int rn_n = rn, t_n = t + 1, t_end_n = t_end;
         bool run_start_n = false;
         if (t_n == t_end) {
-            rn_n = rn + nwaves;
+            if (a.dynamic) {
+                // tickets count up from run_base; ticket k stands for run nwaves + k
+                const uint32_t k = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(ticket)) - a.run_base;
+                rn_n = k < static_cast<uint32_t>(nruns) ? nwaves + static_cast<int>(k) : nruns;
+            } else {
+                rn_n = rn + nwaves;
+            }
             t_n = rn_n < nruns ? t_lo + rn_n * run : -1;
             t_end_n = t_n + run < t_hi ? t_n + run : t_hi;
             run_start_n = true;
+            // a wave draws until a ticket lies beyond the last run: one ticket per run over the whole launch
+            if (a.dynamic && t_n >= 0 && lane == 0) ticket = atomicAdd(&a.counters[CTR_NEXT_RUN], 1);
         }
         int32_t s_n = 0, g0_n = 0, prev_word_n = -1, gd_n = 0;
         int cnt_n = 0;
@@ -846,9 +864,10 @@ __global__ __launch_bounds__(kBlock) void k_zero_rows(const int32_t *__restrict_
 }
 
 std::atomic<int> g_tiles_per_run{0};
+constexpr int kMinDynamicRun = 4;
 
 template <typename T, int MODEL>
-hipError_t launch_grouped_vpl(const GroupedArgs &a_in, int grid, hipStream_t s) {
+hipError_t launch_grouped_vpl(const GroupedArgs &a_in, int grid, uint32_t *run_tickets, hipStream_t s) {
     GroupedArgs a = a_in;
     // runs of several tiles only where every wave still gets many runs
     const int64_t ntiles = (a.n_edges + kTileEdges - 1) / kTileEdges;
@@ -861,6 +880,14 @@ hipError_t launch_grouped_vpl(const GroupedArgs &a_in, int grid, hipStream_t s) 
     const int forced = g_tiles_per_run.load(std::memory_order_relaxed);
     if (forced > 0) a.tiles_per_run = forced;
     if (ntiles > 0x7fffffff) return hipErrorInvalidValue;   // tile indices are 32-bit in the kernel
+    a.nruns = static_cast<int>((mine + a.tiles_per_run - 1) / a.tiles_per_run);
+    // runs by ticket where a run is long enough to hide the counter's latency and the launch's
+    // tickets (one per run) stay well below what one address sustains
+    a.dynamic = run_tickets && a.tiles_per_run >= kMinDynamicRun ? 1 : 0;
+    if (a.dynamic) {
+        a.run_base = *run_tickets;
+        *run_tickets += static_cast<uint32_t>(a.nruns);
+    }
     switch (a.d / kWave) {
         case 1: hipLaunchKernelGGL((k_aggregate_grouped<T, 1, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
         case 2: hipLaunchKernelGGL((k_aggregate_grouped<T, 2, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
@@ -955,19 +982,19 @@ hipError_t launch_gat_chunk_max(const AggregateArgs &a, hipStream_t s) {
     return hipGetLastError();
 }
 
-hipError_t launch_aggregate_grouped(const GroupedArgs &a, hipStream_t s) {
+hipError_t launch_aggregate_grouped(const GroupedArgs &a, uint32_t *run_tickets, hipStream_t s) {
     if (a.d % kWave != 0) return hipErrorInvalidValue;
     if (a.n_edges <= 0) return hipSuccess;
     const int grid = persistent_grid(8);
     if (a.model == 2) {
         if (a.in_dt || a.gat.dh % (a.d / kWave) != 0) return hipErrorInvalidValue;
-        return launch_grouped_vpl<float, 2>(a, grid, s);
+        return launch_grouped_vpl<float, 2>(a, grid, run_tickets, s);
     }
     if (a.in_dt == 2)
-        return a.model == 1 ? launch_grouped_vpl<_Float16, 1>(a, grid, s) : launch_grouped_vpl<_Float16, 0>(a, grid, s);
+        return a.model == 1 ? launch_grouped_vpl<_Float16, 1>(a, grid, run_tickets, s) : launch_grouped_vpl<_Float16, 0>(a, grid, run_tickets, s);
     if (a.in_dt == 1)
-        return a.model == 1 ? launch_grouped_vpl<uint16_t, 1>(a, grid, s) : launch_grouped_vpl<uint16_t, 0>(a, grid, s);
-    return a.model == 1 ? launch_grouped_vpl<float, 1>(a, grid, s) : launch_grouped_vpl<float, 0>(a, grid, s);
+        return a.model == 1 ? launch_grouped_vpl<uint16_t, 1>(a, grid, run_tickets, s) : launch_grouped_vpl<uint16_t, 0>(a, grid, run_tickets, s);
+    return a.model == 1 ? launch_grouped_vpl<float, 1>(a, grid, run_tickets, s) : launch_grouped_vpl<float, 0>(a, grid, run_tickets, s);
 }
 
 hipError_t launch_self_message(int64_t b, int64_t e, int32_t *pending, int32_t *ready,
