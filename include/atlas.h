@@ -335,8 +335,11 @@ int atlas_debug_copy(atlas_layer_t *layer, int what, void *host_dst, int64_t byt
  * in registers from one tile of a run to the next.  0 (the default) lets the
  * library choose from the chunk's size (1 for small chunks, up to 16); 1..16
  * forces that length for every later launch of the process, which is how the
- * tests reach the long-run path on small graphs.  Results do not depend on it
- * beyond fp32 summation order.  Errors: E_RANGE. */
+ * tests reach the long-run path on small graphs.  With runs of 4 tiles or more
+ * the runs after a wave's first are handed out by a counter instead of a fixed
+ * stride, with 8 or more the launch's last tiles go out in runs a quarter as
+ * long.  Results do not depend on any of this beyond fp32 summation order.
+ * Errors: E_RANGE. */
 int atlas_set_tiles_per_run(int tiles);
 
 /* Chunk loader of PINNED_HOST graphs with a plan (Sec. 3.3, the reader that runs

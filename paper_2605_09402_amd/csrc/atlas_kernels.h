@@ -139,7 +139,9 @@ struct GroupedArgs {
                                 // a group cut by a piece boundary is added with atomics like one cut by a run.
                                 // (launch_zero_cut_first_rows always examines the whole chunk)
     // set by the launcher:
-    int nruns = 0;              // runs of tiles_per_run tiles in [tile_begin, tile_end)
+    int nruns = 0;              // runs in [tile_begin, tile_end): the first big_runs of tiles_per_run tiles,
+    int big_runs = 0;           // the others (the launch's last tiles, taken when most waves are about to
+    int small_run = 1;          // finish) of small_run tiles
     int dynamic = 0;            // 1: a wave's runs after its first are handed out by counters[CTR_NEXT_RUN]
     uint32_t run_base = 0;      // value of that counter when the launch begins
 };

@@ -481,8 +481,13 @@ void k_aggregate_grouped(GroupedArgs a) {
     // out the runs after a wave's first through a ticket counter (one atomic
     // per run, fetched a run ahead); short ones, where one atomic per tile or
     // two would be more than one address sustains, keep the fixed stride.
+    // The launch's last tiles go out in shorter runs, so that the waves end
+    // within a short run's time of each other.
     const int run = a.tiles_per_run;
     const int nruns = a.nruns;
+    const int big = a.big_runs;
+    const int t_small = t_lo + big * run;   // first tile of the short runs
+    const int small = a.small_run;
     float sum[VPL];
 #pragma unroll
     for (int i = 0; i < VPL; ++i) sum[i] = 0.f;
@@ -494,8 +499,9 @@ void k_aggregate_grouped(GroupedArgs a) {
 
     // the tile in hand (fetched ahead)
     int rn = wave;
-    int t = rn < nruns ? t_lo + rn * run : -1;
-    int t_end = t + run < t_hi ? t + run : t_hi;
+    int t = rn >= nruns ? -1 : rn < big ? t_lo + rn * run : t_small + (rn - big) * small;
+    int t_end = t + (rn < big ? run : small);
+    t_end = t_end < t_hi ? t_end : t_hi;
     bool run_start = true;
     int32_t ticket = 0;   // lane 0: counter value drawn for the wave's next run
     if (a.dynamic && t >= 0 && lane == 0) ticket = atomicAdd(&a.counters[CTR_NEXT_RUN], 1);
@@ -527,8 +533,9 @@ void k_aggregate_grouped(GroupedArgs a) {
             } else {
                 rn_n = rn + nwaves;
             }
-            t_n = rn_n < nruns ? t_lo + rn_n * run : -1;
-            t_end_n = t_n + run < t_hi ? t_n + run : t_hi;
+            t_n = rn_n >= nruns ? -1 : rn_n < big ? t_lo + rn_n * run : t_small + (rn_n - big) * small;
+            t_end_n = t_n + (rn_n < big ? run : small);
+            t_end_n = t_end_n < t_hi ? t_end_n : t_hi;
             run_start_n = true;
             // a wave draws until a ticket lies beyond the last run: one ticket per run over the whole launch
             if (a.dynamic && t_n >= 0 && lane == 0) ticket = atomicAdd(&a.counters[CTR_NEXT_RUN], 1);
@@ -865,6 +872,7 @@ __global__ __launch_bounds__(kBlock) void k_zero_rows(const int32_t *__restrict_
 
 std::atomic<int> g_tiles_per_run{0};
 constexpr int kMinDynamicRun = 4;
+constexpr int kMinSplitRun = 8;
 
 template <typename T, int MODEL>
 hipError_t launch_grouped_vpl(const GroupedArgs &a_in, int grid, uint32_t *run_tickets, hipStream_t s) {
@@ -881,9 +889,19 @@ hipError_t launch_grouped_vpl(const GroupedArgs &a_in, int grid, uint32_t *run_t
     if (forced > 0) a.tiles_per_run = forced;
     if (ntiles > 0x7fffffff) return hipErrorInvalidValue;   // tile indices are 32-bit in the kernel
     a.nruns = static_cast<int>((mine + a.tiles_per_run - 1) / a.tiles_per_run);
+    a.big_runs = a.nruns;
+    a.small_run = a.tiles_per_run;
     // runs by ticket where a run is long enough to hide the counter's latency and the launch's
     // tickets (one per run) stay well below what one address sustains
     a.dynamic = run_tickets && a.tiles_per_run >= kMinDynamicRun ? 1 : 0;
+    if (a.dynamic && a.tiles_per_run >= kMinSplitRun) {
+        // the last run of every wave, in quarters
+        const int64_t whole = mine / a.tiles_per_run;
+        a.big_runs = static_cast<int>(whole > nwaves ? whole - nwaves : 0);
+        a.small_run = a.tiles_per_run / 4;
+        const int64_t rest = mine - static_cast<int64_t>(a.big_runs) * a.tiles_per_run;
+        a.nruns = a.big_runs + static_cast<int>((rest + a.small_run - 1) / a.small_run);
+    }
     if (a.dynamic) {
         a.run_base = *run_tickets;
         *run_tickets += static_cast<uint32_t>(a.nruns);

@@ -309,6 +309,29 @@ def test_runs_of_consecutive_tiles(oracle, H, model, store, tiles):
     assert ei.value.status == atlas.E_RANGE
 
 
+def test_long_launch_with_ticketed_runs(oracle, H):
+    """A launch long enough that runs are handed out by the ticket counter and
+    its last tiles go out in short runs: degree-ordered R-MAT scale 18 with 6.3 M
+    edges, almost all of them in the first of two chunks (98 K tiles: with runs of
+    8 tiles, 4 K long runs by ticket after the waves' first, then 32 K runs of 2)."""
+    import paper_2605_09402_amd as atlas
+    g = gen.rmat_graph(SEED + 29, 18, 24)
+    off, col = gen.build_csr(g)
+    new_of_old, _ = oracle.reorder_indegree_desc(oracle.in_degree(g.n, col.numpy()))
+    g = g.with_relabel(torch.from_numpy(new_of_old.astype(np.int64)))
+    case = H.make_case("sage", g, SEED + 29, [64, 64, 16], (1 << 18) - 4097, store=torch.bfloat16, feat="uniform")
+    atlas.atlas_set_tiles_per_run(8)
+    try:
+        run = H.run_gpu(case, snapshots=True, plan=True, planned_only=True)
+        H.check_integers(oracle, case, run, layer=0)
+        H.check_integers(oracle, case, run, layer=1)
+        print("ticketed runs", H.check_outputs(oracle, case, run))
+        run = H.run_gpu(case, plan=True, plan_block=(4096, 64), pinned_host=True, device_later=True)
+        print("ticketed runs, blocked plan, pinned host", H.check_outputs(oracle, case, run))
+    finally:
+        atlas.atlas_set_tiles_per_run(0)
+
+
 @pytest.mark.parametrize("model,store,dims", [
     ("sage", torch.bfloat16, [192, 64, 48]),
     ("sage", torch.bfloat16, [320, 128, 80]),
