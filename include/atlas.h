@@ -27,6 +27,8 @@
  * atlas_status code and has no partial effect when it rejects its arguments.
  * A layer object must be used from one host thread at a time, and all calls on
  * one layer must be given the same HIP stream (or streams the caller orders).
+ * The calls are not meant for HIP graph capture: atlas_layer_init allocates,
+ * and the kernel arguments of a launch carry state of the layer at that call.
  * The functions documented as "Synchronous" (plans, orderings, sampling) take
  * no stream: they work on the default stream and return when their result is
  * complete, but they do not wait for work the caller has queued on other
