@@ -43,7 +43,7 @@ def _draw_gat(rng, oracle, H, idx):
     if rng.random() < 0.4:
         opts["pinned_host"] = True
         opts["device_later"] = bool(rng.random() < 0.5)
-    return case, opts, {"run": int(rng.choice([0, 2, 5])), "piece": 0}
+    return case, opts, {"run": int(rng.choice([0, 2, 5, 8])), "piece": 0}
 
 
 def _draw_sgc(rng, oracle, H, idx, store):
@@ -60,7 +60,7 @@ def _draw_sgc(rng, oracle, H, idx, store):
         opts["plan"] = True
         if rng.random() < 0.5:
             opts["planned_only"] = True
-    return case, opts, {"run": int(rng.choice([0, 2, 5])), "piece": 0}
+    return case, opts, {"run": int(rng.choice([0, 2, 5, 8])), "piece": 0}
 
 
 def _draw(rng, oracle, H, idx):
@@ -109,7 +109,7 @@ def _draw(rng, oracle, H, idx):
     opts["flush_every"] = int(rng.choice([1, 1, 2, 5]))
     case = H.make_case(model, g, SEED + idx, dims, chunk, store=store,
                        feat="normal" if store == torch.float32 else "uniform", eps=0.5 if model == "gin" else 0.0)
-    knobs = {"run": int(rng.choice([0, 0, 2, 5])), "piece": int(rng.choice([0, 1, 4]))}
+    knobs = {"run": int(rng.choice([0, 0, 2, 5, 8, 16])), "piece": int(rng.choice([0, 1, 4]))}
     if plan_kind == 1 and not tf and rng.random() < 0.4:   # bounded store where the chunks fit
         started = int((np.bincount(case.col.numpy(), minlength=case.n) > 0).sum())
         slots = max(1, int(started * rng.uniform(0.6, 0.95)))
