@@ -60,8 +60,24 @@ template <> __device__ __forceinline__ uint16_t to_elem<2>(float f) { return f32
 
 __host__ __device__ constexpr int lds_pad(bool sixteen_bit) { return sixteen_bit ? 8 : 1; }
 
+// Output column that row m (0..31) of a 32x32 block computed as D^T stands for.
+// A lane of the result holds rows m = 8q + 4h + t (q, t < 4; h = lane / 32).
+// fp32 operands: the identity, a lane's four runs of four columns are 16-byte
+// stores and the two halves of the wave complete 32 bytes of a row per store.
+// 16-bit operands: rows are assigned so that a lane holds two runs of EIGHT
+// consecutive columns (16 + 16 bytes of a 16-bit output row) and the halves
+// again sit side by side: column 16 (q / 2) + 8 h + 4 (q % 2) + t.  The 8-byte
+// stores of the identity order cost four store instructions per block, each
+// touching 32 rows; the texture unit spends a cycle per row and instruction.
+template <int CT>
+__host__ __device__ constexpr int block_column(int m) {
+    if (CT == 0) return m;
+    const int q = m >> 3, h = (m >> 2) & 1, t = m & 3;
+    return 16 * (q >> 1) + 8 * h + 4 * (q & 1) + t;
+}
+
 // Packed-W element index.  bf16: fragment (nb, kk) is 64 lanes x 8 values,
-// value t of lane l is W[kk*16 + (l/32)*8 + t][nb*32 + l%32].
+// value t of lane l is W[kk*16 + (l/32)*8 + t][nb*32 + block_column(l%32)].
 // fp32: fragment (nb, kk) is 64 lanes x 1 value, W[kk*2 + l/32][nb*32 + l%32].
 template <int CT>
 __global__ __launch_bounds__(kBlock) void k_pack_weights(const void *W, int w_dt, int K, int d_out,
@@ -79,7 +95,7 @@ __global__ __launch_bounds__(kBlock) void k_pack_weights(const void *W, int w_dt
     const int kk = static_cast<int>(frag % KS);
     const int nb = static_cast<int>(frag / KS);
     const int k = kk * kStepK + (l / 32) * kPerLane + t;
-    const int j = nb * 32 + (l % 32);
+    const int j = nb * 32 + block_column<CT>(l % 32);
     float w = 0.f;
     if (j < d_out) {
         const int64_t src = static_cast<int64_t>(k) * d_out + j;
@@ -133,12 +149,12 @@ __device__ __forceinline__ float apply_activation(float y, int act) {
 }
 
 // Epilogue of one 32x32 block computed as D^T (W fragment as the first MFMA
-// operand): lane l then holds, for tile row l%32, the sixteen output columns
-// nbase + 8q + t (q, t < 4) with nbase = 32 nb + 4 (l/32) -- four runs of four
-// consecutive columns, written as 8-byte (bf16) or 16-byte (fp32) stores.
+// operand): lane l then holds, for tile row l%32, sixteen output columns of
+// block nb, value 4q + t being column 32 nb + block_column(8q + 4 (l/32) + t).
+// `half` = l / 32.
 template <bool ADD_BIAS>
 __device__ __forceinline__ void store_block_row(const UpdateArgs &a, const f32x16_t &c, int64_t out_row,
-                                                int nbase, const float *bias16) {
+                                                int nb, int half, const float *bias16) {
     float y[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) y[r] = ADD_BIAS ? c[r] + bias16[r] : c[r];
@@ -153,37 +169,59 @@ __device__ __forceinline__ void store_block_row(const UpdateArgs &a, const f32x1
     void *outp = a.out;
     int cols = a.d_out;
     int odt = a.out_dt;
+    int base = nb * 32;
     if (a.split > 0) {
         cols = a.split;
-        if (nbase >= a.split) {
+        if (base >= a.split) {
             outp = a.out2;
             odt = a.out2_dt;
-            nbase -= a.split;
+            base -= a.split;
         }
     }
     const int limit = a.split > 0 ? a.split : a.d_out;
-    if (odt) {
-        uint16_t *o = static_cast<uint16_t *>(outp) + out_row * cols + nbase;
+    if (a.compute_dt != 0) {
+        // two runs of eight columns: 16 s + 8 half + (0..7), values 8 s .. 8 s + 7
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-            if (nbase + 8 * q < limit)
-                *reinterpret_cast<uint2 *>(o + 8 * q) =
-                    make_uint2(pack2_dt(odt, y[4 * q], y[4 * q + 1]), pack2_dt(odt, y[4 * q + 2], y[4 * q + 3]));
+        for (int s2 = 0; s2 < 2; ++s2) {
+            const int col = base + 16 * s2 + 8 * half;
+            if (col >= limit) continue;
+            const float *v = y + 8 * s2;
+            if (odt) {
+                uint16_t *o = static_cast<uint16_t *>(outp) + out_row * cols + col;
+                *reinterpret_cast<uint4 *>(o) = make_uint4(pack2_dt(odt, v[0], v[1]), pack2_dt(odt, v[2], v[3]),
+                                                           pack2_dt(odt, v[4], v[5]), pack2_dt(odt, v[6], v[7]));
+            } else {
+                float *o = static_cast<float *>(outp) + out_row * cols + col;
+                *reinterpret_cast<float4 *>(o) = make_float4(v[0], v[1], v[2], v[3]);
+                *reinterpret_cast<float4 *>(o + 4) = make_float4(v[4], v[5], v[6], v[7]);
+            }
+        }
     } else {
-        float *o = static_cast<float *>(outp) + out_row * cols + nbase;
+        // four runs of four columns: 8 q + 4 half + (0..3)
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-            if (nbase + 8 * q < limit)
-                *reinterpret_cast<float4 *>(o + 8 * q) = make_float4(y[4 * q], y[4 * q + 1], y[4 * q + 2], y[4 * q + 3]);
+        for (int q = 0; q < 4; ++q) {
+            const int col = base + 8 * q + 4 * half;
+            if (col >= limit) continue;
+            if (odt) {
+                uint16_t *o = static_cast<uint16_t *>(outp) + out_row * cols + col;
+                *reinterpret_cast<uint2 *>(o) =
+                    make_uint2(pack2_dt(odt, y[4 * q], y[4 * q + 1]), pack2_dt(odt, y[4 * q + 2], y[4 * q + 3]));
+            } else {
+                float *o = static_cast<float *>(outp) + out_row * cols + col;
+                *reinterpret_cast<float4 *>(o) = make_float4(y[4 * q], y[4 * q + 1], y[4 * q + 2], y[4 * q + 3]);
+            }
+        }
     }
 }
 
-__device__ __forceinline__ void load_bias16(const UpdateArgs &a, int nbase, float (&bias16)[16]) {
+// the bias of the sixteen columns a lane holds, in the order of its values
+__device__ __forceinline__ void load_bias16(const UpdateArgs &a, int nb, int half, float (&bias16)[16]) {
 #pragma unroll
     for (int q = 0; q < 4; ++q)
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const int n = nbase + 8 * q + t;
+            const int m = 8 * q + 4 * half + t;
+            const int n = nb * 32 + (a.compute_dt != 0 ? block_column<1>(m) : m);
             bias16[4 * q + t] = (a.bias && n < a.d_out) ? a.bias[n] : 0.f;
         }
 }
@@ -424,7 +462,7 @@ __global__ __launch_bounds__(kGenBlock, 4) void k_update(UpdateArgs a) {
         f32x16_t c[kMB];
         {
             float b16[16];   // re-read per tile (cache hit) rather than held in registers
-            load_bias16(a, nbc * 32 + 4 * (lane >> 5), b16);
+            load_bias16(a, nbc, lane >> 5, b16);
 #pragma unroll
             for (int m = 0; m < kMB; ++m)
 #pragma unroll
@@ -451,7 +489,7 @@ __global__ __launch_bounds__(kGenBlock, 4) void k_update(UpdateArgs a) {
 #pragma unroll
             for (int m = 0; m < kMB; ++m) {
                 const int32_t id = ids[(mb0 + m) * 32 + (lane & 31)];
-                if (id >= 0) store_block_row<false>(a, c[m], id, nb * 32 + 4 * (lane >> 5), nullptr);
+                if (id >= 0) store_block_row<false>(a, c[m], id, nb, lane >> 5, nullptr);
             }
         }
     }
@@ -554,7 +592,7 @@ __global__ __launch_bounds__(kDenseBlock, 2) void k_dense_transform(UpdateArgs a
 #pragma unroll
             for (int m = 0; m < kDenseMB; ++m) {
                 const int64_t row = row0 + m * 32 + (lane & 31);
-                if (row < n) store_block_row<false>(a, c[m], row, nb * 32 + 4 * (lane >> 5), nullptr);
+                if (row < n) store_block_row<false>(a, c[m], row, nb, lane >> 5, nullptr);
             }
         }
     }
@@ -780,7 +818,7 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
         const int p = w + 8 * i;
         const int nb = p % NB, mb = (p / NB) & 1;   // waves past the last block compute and discard
         float b16[16];
-        load_bias16(a, nb * 32 + 4 * (lane >> 5), b16);
+        load_bias16(a, nb, lane >> 5, b16);
 #pragma unroll
         for (int r = 0; r < 16; ++r) bj[i][r] = b16[r];
         if constexpr (CT) {
@@ -845,7 +883,7 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
             if (p >= 2 * NB) continue;
             const int nb = p % NB, mb = p / NB;
             const int32_t id = tids[mb * 32 + (lane & 31)];
-            if (id >= 0) store_block_row<false>(a, c[i], id, nb * 32 + 4 * (lane >> 5), nullptr);
+            if (id >= 0) store_block_row<false>(a, c[i], id, nb, lane >> 5, nullptr);
         }
     };
 
