@@ -903,6 +903,10 @@ hipError_t launch_grouped_vpl(const GroupedArgs &a_in, int grid, uint32_t *run_t
         a.nruns = a.big_runs + static_cast<int>((rest + a.small_run - 1) / a.small_run);
     }
     if (a.dynamic) {
+        // Tickets drawn by the launch: the counter hands out consecutive values, ticket k stands for run
+        // nwaves + k, so the first max(nruns - nwaves, 0) drawn are valid and every later one is not.  A wave
+        // that has a first run (min(nwaves, nruns) of them) draws once at its start, once more after every
+        // valid ticket and stops at its first invalid one: valid tickets + one per such wave = nruns.
         a.run_base = *run_tickets;
         *run_tickets += static_cast<uint32_t>(a.nruns);
     }

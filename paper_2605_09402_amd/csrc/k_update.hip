@@ -231,7 +231,8 @@ __device__ __forceinline__ void load_bias16(const UpdateArgs &a, int nb, int hal
 // unconditionally (rows past the end of the ready list, lanes past the row
 // width and vertices without in-edges read a valid dummy location whose value
 // is dropped) and kept raw in registers, so all loads of the wave are in flight
-// together before the first is used.  d_in <= 512: at most 16 items.
+// together before the first is used (skipping the dummy loads with a wave-uniform
+// branch was measured: 2.69 against 2.58 ms at d = 256).  d_in <= 512: at most 16 items.
 template <int CT> struct OwnRaw4 { using type = float4; };
 template <> struct OwnRaw4<1> { using type = uint2; };
 template <> struct OwnRaw4<2> { using type = uint2; };
@@ -640,10 +641,12 @@ __device__ __forceinline__ int32_t quad_bcast(int32_t v, int i) {
 
 // Issue the loads of the wave's 8 rows: lanes 0..31 take row 2i, lanes 32..63
 // row 2i+1 in round i.  `idv` / `degv` hold, in lane l, the values of row
-// 2 (l % 4) + l / 32.  Straight-line code: rows past the end of the ready list
-// read row 0 and are dropped when the tile is stored; so do the accumulator
-// loads of vertices without in-edges (nothing was ever added to their rows,
-// and the one shared address stays in cache).
+// 2 (l % 4) + l / 32.  Rows past the end of the ready list read row 0 and are
+// dropped when the tile is stored.  The accumulator of a vertex without
+// in-edges is not loaded (nothing was ever added to its row): the half-wave
+// of that row is masked off for the load, which costs no wait, while a dummy
+// load of a cached row still took its 512 bytes of the CU's load path (half
+// of all vertices at scale 26: 11.2 -> 10.6 ms per layer).
 template <int CT, int OWN>
 __device__ __forceinline__ void pipe_issue_rows(const UpdateArgs &a, int32_t idv, int32_t degv, int32_t slotv,
                                                 int lane, RowRegs<CT> &r) {
@@ -655,8 +658,9 @@ __device__ __forceinline__ void pipe_issue_rows(const UpdateArgs &a, int32_t idv
         const int32_t id = quad_bcast(idv, i);
         const int32_t dg = quad_bcast(degv, i);
         const int32_t row = id >= 0 ? id : 0;
-        const int32_t arow = dg > 0 ? (a.slot_of ? quad_bcast(slotv, i) : row) : 0;
-        r.acc[i] = *reinterpret_cast<const float4 *>(a.acc + static_cast<int64_t>(arow) * d + col);
+        const int32_t arow = a.slot_of ? quad_bcast(slotv, i) : row;
+        r.acc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (dg > 0) r.acc[i] = *reinterpret_cast<const float4 *>(a.acc + static_cast<int64_t>(arow) * d + col);
         if constexpr (OWN != 0) {
             const int64_t o = static_cast<int64_t>(row) * d + col;
             if constexpr (CT) r.own[i] = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(a.self_rows) + o);
