@@ -47,9 +47,10 @@ def _per_kernel(path):
         if "atlas" not in r["Kernel_Name"]:
             continue
         name = re.sub(r"[<(].*", "", r["Kernel_Name"].replace("void ", "").replace("atlas::(anonymous namespace)::", ""))
-        ent = out.setdefault(name, {"launches": 0, "kib": 0.0})
+        ent = out.setdefault(name, {"launches": 0, "kib": 0.0, "each": []})
         ent["launches"] += 1
         ent["kib"] += float(r["Counter_Value"])
+        ent["each"].append(float(r["Counter_Value"]))
     return scale, out
 
 
@@ -64,6 +65,10 @@ def traffic(fetch_csv: str, write_csv: str, out_json: str) -> None:
         wr = wk[name]["kib"] * ws * 1024.0
         kernels[name] = {"launches": fk[name]["launches"], "read_bytes": round(rd), "write_bytes": round(wr),
                          "bytes_per_launch": round((rd + wr) / max(1, fk[name]["launches"]))}
+        if name == "k_aggregate_grouped" and len(fk[name]["each"]) == len(wk[name]["each"]):
+            # the counter runs execute one layer: launch i is chunk i
+            kernels[name]["read_bytes_by_launch"] = [round(v * fs * 1024.0) for v in fk[name]["each"]]
+            kernels[name]["write_bytes_by_launch"] = [round(v * ws * 1024.0) for v in wk[name]["each"]]
     doc = {"what": "HBM-side bytes (L2 <-> fabric) of one layer of bench.py's workload, from rocprofv3 --pmc "
                    "FETCH_SIZE and WRITE_SIZE, each scaled by the same counter's reading for a plain 4 GiB copy",
            "fetch_scale": round(fs, 4), "write_scale": round(ws, 4), "kernel_source_hash": kernel_source_hash(),
@@ -135,6 +140,16 @@ def kernels_md(stats_csv: str, trace_csv: str, bench_json: str, traffic_json: st
                "k_update_pipelined %.1f GB in %.2f ms = %.2f TB/s.\n"
                % (agg_gb, lm["aggregate"], agg_gb / lm["aggregate"], agg_gb / lm["aggregate"] / 8 * 100,
                   upd_gb, lm["update"], upd_gb / lm["update"]))
+    ag = t.get("k_aggregate_grouped", {})
+    d = [(int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e6 for r in trace if "k_aggregate_grouped" in r["Kernel_Name"]]
+    d = d[nchunks:2 * nchunks]
+    if "read_bytes_by_launch" in ag and len(ag["read_bytes_by_launch"]) == len(d) == nchunks:
+        out.append("k_aggregate_grouped by launch (bytes from the counter runs, time from the trace above): with later "
+                   "chunks the share of\naccumulator read-add-writes grows, and with the share of writes the rate "
+                   "falls towards that of a plain copy.\n")
+        out.append("| chunk | read GB | written GB | ms | TB/s |\n|---|---|---|---|---|\n" + "\n".join(
+            "| %d | %.2f | %.2f | %.3f | %.2f |" % (i, r / 1e9, w / 1e9, d[i], (r + w) / 1e9 / d[i])
+            for i, (r, w) in enumerate(zip(ag["read_bytes_by_launch"], ag["write_bytes_by_launch"]))) + "\n")
     with open(out_md, "w") as f:
         f.write("\n".join(out))
 
