@@ -466,6 +466,197 @@ int stage_emb_slot(atlas_layer *L, int slot) {
     return ATLAS_OK;
 }
 
+// What atlas_broadcast_chunk knows about a chunk staged from pinned host memory.
+struct StagedChunk {
+    int slot = -1;            // staging slot of the ring (-1: DEVICE graph, nothing staged)
+    int npieces = 1;          // a long planned chunk crosses the host link, and is pushed, in pieces
+    int64_t piece_tiles = 0;  // 64-edge tiles per piece
+    bool packed = false;      // its edge words travel in 3 bytes and are unpacked piece by piece
+};
+
+// S1, the chunk loader (Sec. 3.3): stage the chunk into HBM on the copy stream; the compute
+// stream only waits for this chunk's event, so the copy of chunk k+1 (enqueued by the next call)
+// overlaps the kernels of chunk k.  Fills the staged addresses into `a` (CSR slice) and `ga`
+// (planned chunk).
+int stage_pinned_chunk(atlas_layer *L, const atlas_plan *plan, const PlanChunk *pc, int64_t src_begin,
+                       int64_t src_end, const void *emb, size_t emb_bytes, bool emb_dev, char *self_dst,
+                       hipStream_t s, AggregateArgs &a, GroupedArgs &ga, StagedChunk &st) {
+    const atlas_dims_t &d = L->dims;
+    const int slot = st.slot = static_cast<int>(L->num_chunks % atlas_layer::kStageSlots);
+    const int64_t e0 = L->g.row_offsets[src_begin], e1 = L->g.row_offsets[src_end];
+    const bool packed = pc && plan->src_packed;
+    const size_t col_bytes = pc ? stage_bytes_of(*pc, packed) : static_cast<size_t>(e1 - e0) * sizeof(int32_t);
+    if (!L->stage_col[slot].p || col_bytes > L->stage_col[slot].bytes) {
+        // first use of the slot, or a chunk larger than those it has held: wait for the slot, then grow it
+        if (L->slot_used[slot]) HIP_TRY(hipEventSynchronize(L->slot_free[slot]));
+        Buf bigger;
+        HIP_TRY(bigger.alloc(col_bytes));
+        L->stage_col[slot].release();
+        L->stage_col[slot] = bigger;
+    }
+    if (L->slot_used[slot]) HIP_TRY(hipStreamWaitEvent(L->copy_stream, L->slot_free[slot], 0));
+    int rc = start_span(L, L->t_copy, L->copy_stream);
+    if (rc != ATLAS_OK) return rc;
+    const void *emb_dst = emb;   // device-resident embeddings are read where they are
+    if (!emb_dev) {
+        if (!self_dst && (rc = stage_emb_slot(L, slot)) != ATLAS_OK) return rc;
+        void *stage = self_dst ? static_cast<void *>(self_dst) : L->stage_emb[slot].p;
+        HIP_TRY(hipMemcpyAsync(stage, emb, emb_bytes, hipMemcpyHostToDevice, L->copy_stream));
+        emb_dst = stage;
+    }
+    size_t staged_bytes = 0;
+    if (pc) {
+        // planned chunk: its regrouped edges travel instead of the CSR slice (3 or 4 bytes per edge)
+        char *base = static_cast<char *>(L->stage_col[slot].p);
+        const size_t sb = packed ? packed24_bytes(pc->n_edges) : static_cast<size_t>(pc->n_edges) * 4,
+                     gb = static_cast<size_t>(pc->n_groups) * 4, tb = static_cast<size_t>((pc->n_edges + 63) / 64) * 4;
+        char *g_dev = base + round_up(sb, 256), *t_dev = g_dev + round_up(gb, 256);
+        if (sb) {
+            const char *words = packed ? reinterpret_cast<const char *>(plan->src_packed + pc->packed_off)
+                                       : reinterpret_cast<const char *>(plan->src_sorted + pc->edge_base);
+            // the group arrays first: every piece needs them
+            HIP_TRY(hipMemcpyAsync(g_dev, pc->grp_dst, gb, hipMemcpyHostToDevice, L->copy_stream));
+            HIP_TRY(hipMemcpyAsync(t_dev, pc->tile_grp, tb, hipMemcpyHostToDevice, L->copy_stream));
+            const int64_t ntiles = (pc->n_edges + 63) / 64;
+            // (a planned-only layer whose plan has no list of rows to clear finds them by a scan of the
+            // whole chunk's words: such a chunk is pushed in one piece)
+            // (so is a GAT chunk: its maximum sweep reads all of the chunk's edges before the push)
+            if (ntiles >= 2 * st.piece_tiles && (!L->planned_only || pc->has_zero_rows) && d.model != ATLAS_MODEL_GAT)
+                st.npieces = static_cast<int>((ntiles + st.piece_tiles - 1) / st.piece_tiles);
+            auto &evs = L->piece_ev[slot];
+            while (static_cast<int>(evs.size()) < st.npieces) {
+                hipEvent_t ev = nullptr;
+                HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+                evs.push_back(ev);
+            }
+            const size_t tile_bytes = packed ? 192 : 256;   // 64 words of 3 or 4 bytes
+            for (int p = 0; p < st.npieces; ++p) {
+                const size_t lo = static_cast<size_t>(p) * st.piece_tiles * tile_bytes;
+                const size_t hi = p + 1 < st.npieces ? lo + st.piece_tiles * tile_bytes : sb;
+                HIP_TRY(hipMemcpyAsync(base + lo, words + lo, hi - lo, hipMemcpyHostToDevice, L->copy_stream));
+                HIP_TRY(hipEventRecord(evs[p], L->copy_stream));
+            }
+        }
+        ga.src_sorted = reinterpret_cast<const int32_t *>(base);
+        ga.grp_dst = reinterpret_cast<const int32_t *>(g_dev);
+        ga.tile_grp = reinterpret_cast<const int32_t *>(t_dev);
+        staged_bytes = sb + gb + tb;
+    } else if (col_bytes) {
+        HIP_TRY(hipMemcpyAsync(L->stage_col[slot].p, L->g.col_indices + e0, col_bytes, hipMemcpyHostToDevice,
+                               L->copy_stream));
+        staged_bytes = col_bytes;
+    }
+    rc = end_span(L, L->t_copy, L->copy_stream);
+    if (rc != ATLAS_OK) return rc;
+    HIP_TRY(hipEventRecord(L->slot_loaded[slot], L->copy_stream));
+    // the compute stream goes on when the rows, the group arrays and the first piece are there
+    HIP_TRY(hipStreamWaitEvent(s, st.npieces > 1 ? L->piece_ev[slot][0] : L->slot_loaded[slot], 0));
+    if (packed && pc->n_edges > 0) {
+        // 24-bit words as they came over the link -> the 32-bit words the kernels read (piece by piece, below)
+        const size_t need = static_cast<size_t>((pc->n_edges + 3) / 4) * 16;
+        if (!L->unpacked.p || L->unpacked.bytes < need) {
+            HIP_TRY(hipStreamSynchronize(s));   // the previous chunk's kernels may still read the old buffer
+            L->unpacked.release();
+            HIP_TRY(L->unpacked.alloc(need));
+        }
+        st.packed = true;
+        ga.src_sorted = static_cast<const int32_t *>(L->unpacked.p);
+        if (st.npieces == 1)
+            HIP_TRY(launch_unpack24(static_cast<const char *>(L->stage_col[slot].p), pc->n_edges, src_begin,
+                                    static_cast<int32_t *>(L->unpacked.p), s));
+    }
+    L->bytes_h2d += static_cast<int64_t>((emb_dev ? 0 : emb_bytes) + staged_bytes);
+    a.col = static_cast<const int32_t *>(L->stage_col[slot].p);
+    a.col_base = e0;
+    a.emb = emb_dst;
+    return ATLAS_OK;
+}
+
+// Transform-first layers: multiply the chunk's rows by W on the matrix cores; the products are
+// what is pushed (`a` is pointed at them).
+int transform_chunk_first(atlas_layer *L, int64_t src_begin, int64_t src_end, hipStream_t s, AggregateArgs &a) {
+    const atlas_dims_t &d = L->dims;
+    int rc = start_span(L, L->t_self, s);
+    if (rc != ATLAS_OK) return rc;
+    UpdateArgs u{};
+    u.model = 4;
+    u.d_in = d.d_in;
+    u.d_out = d.d_out;
+    u.K = L->K;
+    u.in_dt = d.in_dtype;
+    u.compute_dt = L->compute_dt;
+    u.self_rows = a.emb;
+    u.counters = L->ctr();
+    u.n = src_end - src_begin;
+    u.identity_rows = src_end - src_begin;
+    float *self_rows_out = L->tf_self.p ? static_cast<float *>(L->tf_self.p) + static_cast<size_t>(src_begin) * d.d_out
+                                        : nullptr;
+    // The products that are pushed are messages: they travel in the storage type of the embeddings
+    // (half the bytes per edge for 16-bit storage).  A vertex's own product is read once and stays
+    // fp32; GIN pushes that same buffer.
+    const int push_dt = d.model == ATLAS_MODEL_GIN ? 0 : d.in_dtype;
+    if (d.model == ATLAS_MODEL_SAGE_MEAN) {
+        const size_t half = packed_weight_bytes(L->K, d.d_out, L->compute_dt);
+        if (d.d_out % 32 == 0 && 2 * d.d_out <= 256) {
+            // one pass over the rows: [x W_neigh | x W_self], the halves go to the two buffers
+            u.packed_w = L->packed_w2.p;
+            u.d_out = 2 * d.d_out;
+            u.split = d.d_out;
+            u.out = L->tf_z.p;
+            u.out_dt = push_dt;
+            u.out2 = self_rows_out;
+            u.out2_dt = 0;
+            HIP_TRY(launch_update(u, s));
+        } else {
+            u.packed_w = L->packed_w2.p;
+            u.out = L->tf_z.p;
+            u.out_dt = push_dt;
+            HIP_TRY(launch_update(u, s));
+            u.packed_w = static_cast<char *>(L->packed_w2.p) + half;
+            u.out = self_rows_out;
+            u.out_dt = 0;
+            HIP_TRY(launch_update(u, s));
+        }
+    } else {
+        u.packed_w = L->packed_w.p;
+        u.out = d.model == ATLAS_MODEL_GIN ? static_cast<void *>(self_rows_out) : L->tf_z.p;
+        u.out_dt = push_dt;
+        HIP_TRY(launch_update(u, s));
+    }
+    if ((rc = end_span(L, L->t_self, s)) != ATLAS_OK) return rc;
+    a.emb = d.model == ATLAS_MODEL_GIN ? static_cast<const void *>(self_rows_out) : L->tf_z.p;
+    a.d = d.d_out;
+    a.in_dt = push_dt;
+    return ATLAS_OK;
+}
+
+// Bounded accumulator store (Sec. 3.5): every vertex this chunk addresses gets a slot before the
+// chunk is pushed; the counts come back to the host, which sizes the eviction and checks that
+// the chunk fits.
+int make_room_for_chunk(atlas_layer *L, const PlanChunk *pc, int64_t src_begin, int64_t src_end, hipStream_t s,
+                        const AggregateArgs &a, GroupedArgs &ga) {
+    const atlas_dims_t &d = L->dims;
+    const int32_t stamp = static_cast<int32_t>(L->num_chunks + 1);
+    HIP_TRY(hot_mark(L->hs, ga.grp_dst, 0x7fffffff & ~ga.multi_bit, pc->n_groups, src_begin, L->selfmsg ? src_end - src_begin : 0, stamp, s));
+    int32_t hc[HS_COUNT];
+    HIP_TRY(hipMemcpyAsync(hc, L->hs.ctr, sizeof(hc), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    if (hc[HS_OVERFLOW]) return ATLAS_E_NOMEM;
+    const int64_t need = hc[HS_NEED], free_slots = hc[HS_FREE_TOP];
+    if (need > free_slots) {
+        const int64_t n_evict = need - free_slots;
+        HIP_TRY(hot_build_keys(L->hs, a.pending, stamp, d.evict_policy, s));
+        HIP_TRY(hipMemcpyAsync(hc, L->hs.ctr, sizeof(hc), hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        if (hc[HS_CANDIDATES] < n_evict) return ATLAS_E_NOMEM;   // the chunk's destinations do not fit the slots
+        HIP_TRY(hot_evict(L->hs, n_evict, L->hs_sort_temp.p, L->hs_sort_temp.bytes, s));
+        L->hot_evictions += n_evict;
+    }
+    HIP_TRY(hot_assign(L->hs, need, s));
+    ga.slot_of = L->hs.slot_of;
+    return ATLAS_OK;
+}
+
 GatState gat_state(atlas_layer *L) {
     GatState g;
     g.el = static_cast<const float *>(L->gat_el.p);
@@ -622,104 +813,14 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
     if (L->planned_only && !pc) return ATLAS_E_RANGE;  // the layer promised planned chunks only
     GroupedArgs ga{};
 
-    int slot = -1;
-    // A long planned chunk crosses the host link in pieces of kPieceTiles tiles, and each piece is pushed
-    // as soon as it has arrived, so the chunk's copy and its kernels overlap (the first chunk of a
-    // degree-ordered graph holds most of the edges).
-    const int64_t kPieceTiles = g_piece_tiles.load(std::memory_order_relaxed);
-    int npieces = 1;
-    bool packed_chunk = false;
+    // A long planned chunk crosses the host link in pieces, and each piece is pushed as soon as it has
+    // arrived, so the chunk's copy and its kernels overlap (the first chunk of a degree-ordered graph
+    // holds most of the edges).
+    StagedChunk st;
+    st.piece_tiles = g_piece_tiles.load(std::memory_order_relaxed);
     if (L->g.residency == ATLAS_RESIDENT_PINNED_HOST) {
-        // Stage the chunk into HBM on the copy stream; the compute stream only
-        // waits for this chunk's event, so the copy of chunk k+1 (enqueued by
-        // the next call) overlaps the kernels of chunk k.
-        slot = static_cast<int>(L->num_chunks % atlas_layer::kStageSlots);
-        const int64_t e0 = L->g.row_offsets[src_begin], e1 = L->g.row_offsets[src_end];
-        const bool packed = pc && plan->src_packed;
-        const size_t col_bytes = pc ? stage_bytes_of(*pc, packed) : static_cast<size_t>(e1 - e0) * sizeof(int32_t);
-        if (!L->stage_col[slot].p || col_bytes > L->stage_col[slot].bytes) {
-            // first use of the slot, or a chunk larger than those it has held: wait for the slot, then grow it
-            if (L->slot_used[slot]) HIP_TRY(hipEventSynchronize(L->slot_free[slot]));
-            Buf bigger;
-            HIP_TRY(bigger.alloc(col_bytes));
-            L->stage_col[slot].release();
-            L->stage_col[slot] = bigger;
-        }
-        if (L->slot_used[slot]) HIP_TRY(hipStreamWaitEvent(L->copy_stream, L->slot_free[slot], 0));
-        int rc = start_span(L, L->t_copy, L->copy_stream);
+        int rc = stage_pinned_chunk(L, plan, pc, src_begin, src_end, emb, emb_bytes, emb_dev, self_dst, s, a, ga, st);
         if (rc != ATLAS_OK) return rc;
-        const void *emb_dst = emb;   // device-resident embeddings are read where they are
-        if (!emb_dev) {
-            if (!self_dst && (rc = stage_emb_slot(L, slot)) != ATLAS_OK) return rc;
-            void *stage = self_dst ? static_cast<void *>(self_dst) : L->stage_emb[slot].p;
-            HIP_TRY(hipMemcpyAsync(stage, emb, emb_bytes, hipMemcpyHostToDevice, L->copy_stream));
-            emb_dst = stage;
-        }
-        size_t staged_bytes = 0;
-        if (pc) {
-            // planned chunk: its regrouped edges travel instead of the CSR slice (same 4 bytes per edge)
-            char *base = static_cast<char *>(L->stage_col[slot].p);
-            const size_t sb = packed ? packed24_bytes(pc->n_edges) : static_cast<size_t>(pc->n_edges) * 4,
-                         gb = static_cast<size_t>(pc->n_groups) * 4, tb = static_cast<size_t>((pc->n_edges + 63) / 64) * 4;
-            char *g_dev = base + round_up(sb, 256), *t_dev = g_dev + round_up(gb, 256);
-            if (sb) {
-                const char *words = packed ? reinterpret_cast<const char *>(plan->src_packed + pc->packed_off)
-                                           : reinterpret_cast<const char *>(plan->src_sorted + pc->edge_base);
-                // the group arrays first: every piece needs them
-                HIP_TRY(hipMemcpyAsync(g_dev, pc->grp_dst, gb, hipMemcpyHostToDevice, L->copy_stream));
-                HIP_TRY(hipMemcpyAsync(t_dev, pc->tile_grp, tb, hipMemcpyHostToDevice, L->copy_stream));
-                const int64_t ntiles = (pc->n_edges + 63) / 64;
-                // (a planned-only layer whose plan has no list of rows to clear finds them by a scan of the
-                // whole chunk's words: such a chunk is pushed in one piece)
-                // (so is a GAT chunk: its maximum sweep reads all of the chunk's edges before the push)
-                if (ntiles >= 2 * kPieceTiles && (!L->planned_only || pc->has_zero_rows) && d.model != ATLAS_MODEL_GAT)
-                    npieces = static_cast<int>((ntiles + kPieceTiles - 1) / kPieceTiles);
-                auto &evs = L->piece_ev[slot];
-                while (static_cast<int>(evs.size()) < npieces) {
-                    hipEvent_t ev = nullptr;
-                    HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
-                    evs.push_back(ev);
-                }
-                const size_t tile_bytes = packed ? 192 : 256;   // 64 words of 3 or 4 bytes
-                for (int p = 0; p < npieces; ++p) {
-                    const size_t lo = static_cast<size_t>(p) * kPieceTiles * tile_bytes;
-                    const size_t hi = p + 1 < npieces ? lo + kPieceTiles * tile_bytes : sb;
-                    HIP_TRY(hipMemcpyAsync(base + lo, words + lo, hi - lo, hipMemcpyHostToDevice, L->copy_stream));
-                    HIP_TRY(hipEventRecord(evs[p], L->copy_stream));
-                }
-            }
-            ga.src_sorted = reinterpret_cast<const int32_t *>(base);
-            ga.grp_dst = reinterpret_cast<const int32_t *>(g_dev);
-            ga.tile_grp = reinterpret_cast<const int32_t *>(t_dev);
-            staged_bytes = sb + gb + tb;
-        } else if (col_bytes) {
-            HIP_TRY(hipMemcpyAsync(L->stage_col[slot].p, L->g.col_indices + e0, col_bytes, hipMemcpyHostToDevice,
-                                   L->copy_stream));
-            staged_bytes = col_bytes;
-        }
-        rc = end_span(L, L->t_copy, L->copy_stream);
-        if (rc != ATLAS_OK) return rc;
-        HIP_TRY(hipEventRecord(L->slot_loaded[slot], L->copy_stream));
-        // the compute stream goes on when the rows, the group arrays and the first piece are there
-        HIP_TRY(hipStreamWaitEvent(s, npieces > 1 ? L->piece_ev[slot][0] : L->slot_loaded[slot], 0));
-        if (packed && pc->n_edges > 0) {
-            // 24-bit words as they came over the link -> the 32-bit words the kernels read (piece by piece, below)
-            const size_t need = static_cast<size_t>((pc->n_edges + 3) / 4) * 16;
-            if (!L->unpacked.p || L->unpacked.bytes < need) {
-                HIP_TRY(hipStreamSynchronize(s));   // the previous chunk's kernels may still read the old buffer
-                L->unpacked.release();
-                HIP_TRY(L->unpacked.alloc(need));
-            }
-            packed_chunk = true;
-            ga.src_sorted = static_cast<const int32_t *>(L->unpacked.p);
-            if (npieces == 1)
-                HIP_TRY(launch_unpack24(static_cast<const char *>(L->stage_col[slot].p), pc->n_edges, src_begin,
-                                        static_cast<int32_t *>(L->unpacked.p), s));
-        }
-        L->bytes_h2d += static_cast<int64_t>((emb_dev ? 0 : emb_bytes) + staged_bytes);
-        a.col = static_cast<const int32_t *>(L->stage_col[slot].p);
-        a.col_base = e0;
-        a.emb = emb_dst;
     } else {
         a.col = L->g.col_indices;
         a.col_base = 0;
@@ -734,59 +835,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         HIP_TRY(launch_self_message(src_begin, src_end, a.pending, a.ready, a.counters, s));
         if ((rc = end_span(L, L->t_self, s)) != ATLAS_OK) return rc;
     }
-    if (L->tf) {
-        // multiply the chunk's rows by W on the matrix cores; the products are what is pushed
-        if ((rc = start_span(L, L->t_self, s)) != ATLAS_OK) return rc;
-        UpdateArgs u{};
-        u.model = 4;
-        u.d_in = d.d_in;
-        u.d_out = d.d_out;
-        u.K = L->K;
-        u.in_dt = d.in_dtype;
-        u.compute_dt = L->compute_dt;
-        u.self_rows = a.emb;
-        u.counters = L->ctr();
-        u.n = src_end - src_begin;
-        u.identity_rows = src_end - src_begin;
-        float *self_rows_out = L->tf_self.p ? static_cast<float *>(L->tf_self.p) + static_cast<size_t>(src_begin) * d.d_out
-                                            : nullptr;
-        // The products that are pushed are messages: they travel in the storage type of the embeddings
-        // (half the bytes per edge for 16-bit storage).  A vertex's own product is read once and stays
-        // fp32; GIN pushes that same buffer.
-        const int push_dt = d.model == ATLAS_MODEL_GIN ? 0 : d.in_dtype;
-        if (d.model == ATLAS_MODEL_SAGE_MEAN) {
-            const size_t half = packed_weight_bytes(L->K, d.d_out, L->compute_dt);
-            if (d.d_out % 32 == 0 && 2 * d.d_out <= 256) {
-                // one pass over the rows: [x W_neigh | x W_self], the halves go to the two buffers
-                u.packed_w = L->packed_w2.p;
-                u.d_out = 2 * d.d_out;
-                u.split = d.d_out;
-                u.out = L->tf_z.p;
-                u.out_dt = push_dt;
-                u.out2 = self_rows_out;
-                u.out2_dt = 0;
-                HIP_TRY(launch_update(u, s));
-            } else {
-                u.packed_w = L->packed_w2.p;
-                u.out = L->tf_z.p;
-                u.out_dt = push_dt;
-                HIP_TRY(launch_update(u, s));
-                u.packed_w = static_cast<char *>(L->packed_w2.p) + half;
-                u.out = self_rows_out;
-                u.out_dt = 0;
-                HIP_TRY(launch_update(u, s));
-            }
-        } else {
-            u.packed_w = L->packed_w.p;
-            u.out = d.model == ATLAS_MODEL_GIN ? static_cast<void *>(self_rows_out) : L->tf_z.p;
-            u.out_dt = push_dt;
-            HIP_TRY(launch_update(u, s));
-        }
-        if ((rc = end_span(L, L->t_self, s)) != ATLAS_OK) return rc;
-        a.emb = d.model == ATLAS_MODEL_GIN ? static_cast<const void *>(self_rows_out) : L->tf_z.p;
-        a.d = d.d_out;
-        a.in_dt = push_dt;
-    }
+    if (L->tf && (rc = transform_chunk_first(L, src_begin, src_end, s, a)) != ATLAS_OK) return rc;
     if (d.model == ATLAS_MODEL_GAT) {
         // transform the chunk (z = x W on the matrix cores), raise the running
         // maxima with the chunk's logits, move the touched destinations to them
@@ -855,40 +904,19 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         }
         if ((rc = end_span(L, L->t_self, s)) != ATLAS_OK) return rc;
     }
-    if (L->bounded) {
-        // Every vertex this chunk addresses gets a slot first (Sec. 3.5); the counts come back to the
-        // host, which sizes the eviction and checks that the chunk fits.
-        const int32_t stamp = static_cast<int32_t>(L->num_chunks + 1);
-        HIP_TRY(hot_mark(L->hs, ga.grp_dst, 0x7fffffff & ~ga.multi_bit, pc->n_groups, src_begin, L->selfmsg ? src_end - src_begin : 0, stamp, s));
-        int32_t hc[HS_COUNT];
-        HIP_TRY(hipMemcpyAsync(hc, L->hs.ctr, sizeof(hc), hipMemcpyDeviceToHost, s));
-        HIP_TRY(hipStreamSynchronize(s));
-        if (hc[HS_OVERFLOW]) return ATLAS_E_NOMEM;
-        const int64_t need = hc[HS_NEED], free_slots = hc[HS_FREE_TOP];
-        if (need > free_slots) {
-            const int64_t n_evict = need - free_slots;
-            HIP_TRY(hot_build_keys(L->hs, a.pending, stamp, d.evict_policy, s));
-            HIP_TRY(hipMemcpyAsync(hc, L->hs.ctr, sizeof(hc), hipMemcpyDeviceToHost, s));
-            HIP_TRY(hipStreamSynchronize(s));
-            if (hc[HS_CANDIDATES] < n_evict) return ATLAS_E_NOMEM;   // the chunk's destinations do not fit the slots
-            HIP_TRY(hot_evict(L->hs, n_evict, L->hs_sort_temp.p, L->hs_sort_temp.bytes, s));
-            L->hot_evictions += n_evict;
-        }
-        HIP_TRY(hot_assign(L->hs, need, s));
-        ga.slot_of = L->hs.slot_of;
-    }
+    if (L->bounded && (rc = make_room_for_chunk(L, pc, src_begin, src_end, s, a, ga)) != ATLAS_OK) return rc;
     if ((rc = start_span(L, L->t_agg, s)) != ATLAS_OK) return rc;
     if (pc) {
-        for (int p = 0; p < npieces; ++p) {
-            if (npieces > 1) {
-                if (p > 0) HIP_TRY(hipStreamWaitEvent(s, L->piece_ev[slot][p], 0));
-                ga.tile_begin = p * kPieceTiles;
-                ga.tile_end = p + 1 < npieces ? (p + 1) * kPieceTiles : -1;
+        for (int p = 0; p < st.npieces; ++p) {
+            if (st.npieces > 1) {
+                if (p > 0) HIP_TRY(hipStreamWaitEvent(s, L->piece_ev[st.slot][p], 0));
+                ga.tile_begin = p * st.piece_tiles;
+                ga.tile_end = p + 1 < st.npieces ? (p + 1) * st.piece_tiles : -1;
             }
-            if (packed_chunk && npieces > 1) {
+            if (st.packed && st.npieces > 1) {
                 const int64_t e_lo = ga.tile_begin * 64;
                 const int64_t e_hi = ga.tile_end < 0 ? pc->n_edges : std::min<int64_t>(pc->n_edges, ga.tile_end * 64);
-                HIP_TRY(launch_unpack24(static_cast<const char *>(L->stage_col[slot].p) + e_lo * 3, e_hi - e_lo, src_begin,
+                HIP_TRY(launch_unpack24(static_cast<const char *>(L->stage_col[st.slot].p) + e_lo * 3, e_hi - e_lo, src_begin,
                                         static_cast<int32_t *>(L->unpacked.p) + e_lo, s));
             }
             if (L->planned_only) {
@@ -906,9 +934,9 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
     }
     rc = end_span(L, L->t_agg, s);
     if (rc != ATLAS_OK) return rc;
-    if (slot >= 0) {
-        HIP_TRY(hipEventRecord(L->slot_free[slot], s));
-        L->slot_used[slot] = true;
+    if (st.slot >= 0) {
+        HIP_TRY(hipEventRecord(L->slot_free[st.slot], s));
+        L->slot_used[st.slot] = true;
     }
     L->next_src = src_end;
     L->num_chunks += 1;
