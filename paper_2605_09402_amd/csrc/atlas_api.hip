@@ -919,10 +919,14 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
                 HIP_TRY(launch_unpack24(static_cast<const char *>(L->stage_col[st.slot].p) + e_lo * 3, e_hi - e_lo, src_begin,
                                         static_cast<int32_t *>(L->unpacked.p) + e_lo, s));
             }
+            // a chunk pushed in one launch: its runs are chosen here, so that the rows of groups that stay
+            // within one run need not be cleared
+            if (st.npieces == 1 && ga.n_edges > 0) HIP_TRY(plan_runs(ga));
             if (L->planned_only) {
                 if (pc->has_zero_rows) {   // the list (device memory, also in plans of pinned-host graphs) covers
                     if (p == 0)            // the whole chunk: cleared once, before the first piece adds anything
-                        HIP_TRY(launch_zero_rows(pc->zero_rows, pc->n_zero_rows, ga.acc, ga.slot_of, ga.d, s));
+                        HIP_TRY(launch_zero_rows(pc->zero_rows, pc->zero_span, pc->n_zero_rows, ga.acc, ga.slot_of,
+                                                 ga.d, st.npieces == 1 ? &ga : nullptr, s));
                 } else {
                     HIP_TRY(launch_zero_cut_first_rows(ga, s));   // (one piece, see above)
                 }
@@ -1201,6 +1205,7 @@ int atlas_plan_destroy(atlas_plan_t *P) {
         if (c.grp_dst) (void)(P->host ? hipHostFree(c.grp_dst) : hipFree(c.grp_dst));
         if (c.tile_grp) (void)(P->host ? hipHostFree(c.tile_grp) : hipFree(c.tile_grp));
         if (c.zero_rows) (void)hipFree(c.zero_rows);
+        if (c.zero_span) (void)hipFree(c.zero_span);
     }
     if (P->src_sorted) (void)(P->host ? hipHostFree(P->src_sorted) : hipFree(P->src_sorted));
     if (P->src_packed) (void)hipHostFree(P->src_packed);

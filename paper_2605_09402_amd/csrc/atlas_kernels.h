@@ -100,6 +100,9 @@ struct PlanChunk {
     bool blocked = false;         // source-blocked order: grp_dst bit 30 marks destinations with several groups
     int32_t *zero_rows = nullptr; // device plans: destinations a planned-only layer clears before this chunk (their
     int64_t n_zero_rows = 0;      // first group is added to with atomics by several waves); may hold duplicates
+    int32_t *zero_span = nullptr; // [n_zero_rows][2] first and last 64-edge tile of that first group, or {-1, -1}
+                                  // for a destination with several groups: a launch whose runs keep the group
+                                  // within one wave need not clear the row
     bool has_zero_rows = false;   // false: not precomputed, the launch scans the tile boundaries instead
     int64_t packed_off = 0;       // plans with 24-bit edge words: byte offset of the chunk's words in the plan's array
 };
@@ -155,6 +158,9 @@ constexpr int kMaxTilesPerRun = 16;
 // `run_tickets`: the layer's count of tickets drawn from counters[CTR_NEXT_RUN] so far (starts at 0 with the
 // zeroed counter); every launch that hands out runs dynamically draws exactly one ticket per run and advances it.
 hipError_t launch_aggregate_grouped(const GroupedArgs &a, uint32_t *run_tickets, hipStream_t s);
+// Choose the launch's runs (tiles_per_run, nruns, big_runs, small_run, dynamic) ahead of the launch, for
+// launch_zero_rows; a launch whose nruns is still 0 chooses them itself.
+hipError_t plan_runs(GroupedArgs &a);
 
 // Plan construction for one chunk (synchronous).  off_dev is addressed by global
 // source id and col_dev by global edge number (only [src_begin, src_end] and
@@ -200,9 +206,11 @@ hipError_t launch_gat_finalize(const GatFinalizeArgs &a, hipStream_t s);
 // their first group.  A first group cut by a tile boundary is added with
 // atomics from several tiles, so its row is zeroed here before the chunk runs.
 hipError_t launch_zero_cut_first_rows(const GroupedArgs &a, hipStream_t s);
-// The same from a list of rows precomputed with the plan.
-hipError_t launch_zero_rows(const int32_t *rows, int64_t n_rows, float *acc, const int32_t *slot_of, int d,
-                            hipStream_t s);
+// The same from a list of rows precomputed with the plan.  With `spans` and the runs of the launch that
+// follows (`runs`, after plan_runs; nullptr: unknown, e.g. a chunk pushed in pieces) a row is left alone when
+// its group lies inside one run: the run's wave then holds the whole sum and stores it.
+hipError_t launch_zero_rows(const int32_t *rows, const int32_t *spans, int64_t n_rows, float *acc,
+                            const int32_t *slot_of, int d, const GroupedArgs *runs, hipStream_t s);
 
 // SAGE self message of sources [b, e): pending[u] -= 1 with ready compaction.
 hipError_t launch_self_message(int64_t b, int64_t e, int32_t *pending, int32_t *ready,

@@ -856,17 +856,40 @@ __global__ __launch_bounds__(kBlock) void k_zero_cut_first_rows(GroupedArgs a) {
     }
 }
 
-// One wave per listed row.
-__global__ __launch_bounds__(kBlock) void k_zero_rows(const int32_t *__restrict__ rows, int64_t n_rows, float *acc,
-                                                     const int32_t *__restrict__ slot_of, int d) {
+// A wave takes 64 listed rows at a time, one per lane for the test, then clears those that need it
+// together.  run > 0: the runs of the launch that follows are known (the first `big` of `run` tiles,
+// then runs of `small`); a group whose first and last tile fall into one run needs no clearing.
+__global__ __launch_bounds__(kBlock) void k_zero_rows(const int32_t *__restrict__ rows,
+                                                     const int32_t *__restrict__ spans, int64_t n_rows, float *acc,
+                                                     const int32_t *__restrict__ slot_of, int d, int run, int big,
+                                                     int small) {
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t wave = static_cast<int64_t>(blockIdx.x) * (kBlock / kWave) + (threadIdx.x >> 6);
     const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (kBlock / kWave);
-    for (int64_t i = wave; i < n_rows; i += nwaves) {
-        int64_t v = rows[i];
-        if (slot_of) v = slot_of[v];
-        float *row = acc + v * d;
-        for (int c = lane; c < d; c += kWave) row[c] = 0.f;
+    const int t_small = big * run;
+    for (int64_t base = wave * kWave; base < n_rows; base += nwaves * kWave) {
+        const int64_t i = base + lane;
+        bool need = i < n_rows;
+        int32_t v = 0;
+        if (need && run > 0) {
+            const int t0 = spans[2 * i], t1 = spans[2 * i + 1];
+            if (t0 >= 0) {
+                const int r0 = t0 < t_small ? t0 / run : big + (t0 - t_small) / small;
+                const int r1 = t1 < t_small ? t1 / run : big + (t1 - t_small) / small;
+                need = r0 != r1;
+            }
+        }
+        if (need) {
+            v = rows[i];
+            if (slot_of) v = slot_of[v];
+        }
+        uint64_t todo = __ballot(need);
+        while (todo) {
+            const int j = __ffsll(static_cast<unsigned long long>(todo)) - 1;
+            todo &= todo - 1;
+            float *row = acc + static_cast<int64_t>(__builtin_amdgcn_readlane(v, j)) * d;
+            for (int c = lane; c < d; c += kWave) row[c] = 0.f;
+        }
     }
 }
 
@@ -874,14 +897,14 @@ std::atomic<int> g_tiles_per_run{0};
 constexpr int kMinDynamicRun = 4;
 constexpr int kMinSplitRun = 8;
 
-template <typename T, int MODEL>
-hipError_t launch_grouped_vpl(const GroupedArgs &a_in, int grid, uint32_t *run_tickets, hipStream_t s) {
-    GroupedArgs a = a_in;
+// The runs of a launch over tiles [tile_begin, tile_end) on a grid of `grid` workgroups.
+hipError_t plan_runs_on(GroupedArgs &a, int grid) {
     // runs of several tiles only where every wave still gets many runs
     const int64_t ntiles = (a.n_edges + kTileEdges - 1) / kTileEdges;
     const int64_t nwaves = static_cast<int64_t>(grid) * (kBlock / kWave);
     const int64_t mine = (a.tile_end < 0 || a.tile_end > ntiles ? ntiles : a.tile_end) - a.tile_begin;
     if (a.tile_begin < 0 || mine < 0) return hipErrorInvalidValue;
+    a.nruns = 0;
     if (mine == 0) return hipSuccess;
     const int64_t fit = mine / (4 * nwaves);
     a.tiles_per_run = static_cast<int>(fit < 1 ? 1 : fit > kMaxTilesPerRun ? kMaxTilesPerRun : fit);
@@ -893,7 +916,7 @@ hipError_t launch_grouped_vpl(const GroupedArgs &a_in, int grid, uint32_t *run_t
     a.small_run = a.tiles_per_run;
     // runs by ticket where a run is long enough to hide the counter's latency and the launch's
     // tickets (one per run) stay well below what one address sustains
-    a.dynamic = run_tickets && a.tiles_per_run >= kMinDynamicRun ? 1 : 0;
+    a.dynamic = a.tiles_per_run >= kMinDynamicRun ? 1 : 0;
     if (a.dynamic && a.tiles_per_run >= kMinSplitRun) {
         // the last run of every wave, in quarters
         const int64_t whole = mine / a.tiles_per_run;
@@ -901,6 +924,18 @@ hipError_t launch_grouped_vpl(const GroupedArgs &a_in, int grid, uint32_t *run_t
         a.small_run = a.tiles_per_run / 4;
         const int64_t rest = mine - static_cast<int64_t>(a.big_runs) * a.tiles_per_run;
         a.nruns = a.big_runs + static_cast<int>((rest + a.small_run - 1) / a.small_run);
+    }
+    return hipSuccess;
+}
+
+template <typename T, int MODEL>
+hipError_t launch_grouped_vpl(const GroupedArgs &a_in, int grid, uint32_t *run_tickets, hipStream_t s) {
+    GroupedArgs a = a_in;
+    if (!run_tickets) return hipErrorInvalidValue;
+    if (a.nruns == 0) {
+        const hipError_t e = plan_runs_on(a, grid);
+        if (e != hipSuccess) return e;
+        if (a.nruns == 0) return hipSuccess;   // no tiles
     }
     if (a.dynamic) {
         // Tickets drawn by the launch: the counter hands out consecutive values, ticket k stands for run
@@ -979,13 +1014,19 @@ hipError_t launch_gat_group_max(const GroupedArgs &a, hipStream_t s) {
     return hipGetLastError();
 }
 
-hipError_t launch_zero_rows(const int32_t *rows, int64_t n_rows, float *acc, const int32_t *slot_of, int d,
-                            hipStream_t s) {
+hipError_t plan_runs(GroupedArgs &a) { return plan_runs_on(a, persistent_grid(8)); }
+
+hipError_t launch_zero_rows(const int32_t *rows, const int32_t *spans, int64_t n_rows, float *acc,
+                            const int32_t *slot_of, int d, const GroupedArgs *runs, hipStream_t s) {
     if (n_rows <= 0) return hipSuccess;
-    int64_t blocks = (n_rows + (kBlock / kWave) - 1) / (kBlock / kWave);
+    // the runs are counted from the chunk's first tile: only for a launch over the whole chunk
+    const bool known = runs && spans && runs->nruns > 0 && runs->tile_begin == 0 && runs->small_run > 0;
+    int64_t blocks = (n_rows + kBlock - 1) / kBlock;   // 64 listed rows per wave and round
     const int cap = persistent_grid(8);
     if (blocks > cap) blocks = cap;
-    hipLaunchKernelGGL(k_zero_rows, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, s, rows, n_rows, acc, slot_of, d);
+    hipLaunchKernelGGL(k_zero_rows, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, s, rows, spans, n_rows, acc,
+                       slot_of, d, known ? runs->tiles_per_run : 0, known ? runs->big_runs : 0,
+                       known ? runs->small_run : 1);
     return hipGetLastError();
 }
 

@@ -123,7 +123,8 @@ __global__ void k_group_starts_only(const uint32_t *__restrict__ gidx, int64_t n
 // layer is added to with atomics by more than one wave -- it is cut by a 64-edge tile boundary, or the
 // destination has one group per source block.  One thread per group; duplicates are harmless.
 __global__ void k_collect_zero_rows(const int32_t *__restrict__ grp_dst, const uint32_t *__restrict__ gstart_of_group,
-                                    int64_t n_groups, int64_t n_edges, int32_t *rows, unsigned int *count) {
+                                    int64_t n_groups, int64_t n_edges, int32_t *rows, int32_t *spans,
+                                    unsigned int *count) {
     const int64_t g = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
     if (g >= n_groups) return;
     const int32_t gd = grp_dst[g];
@@ -131,7 +132,14 @@ __global__ void k_collect_zero_rows(const int32_t *__restrict__ grp_dst, const u
     const int64_t b = gstart_of_group[g];
     const int64_t e = g + 1 < n_groups ? gstart_of_group[g + 1] : n_edges;   // one past the group's last edge
     const bool cut = (b >> 6) != ((e - 1) >> 6);
-    if (cut || (gd & 0x40000000)) rows[atomicAdd(count, 1u)] = gd & 0x3fffffff;
+    if (cut || (gd & 0x40000000)) {
+        const unsigned int k = atomicAdd(count, 1u);
+        rows[k] = gd & 0x3fffffff;
+        // first and last tile of the group; a destination with one group per source block: always cleared
+        const bool multi = (gd & 0x40000000) != 0;
+        spans[2 * k] = multi ? -1 : static_cast<int32_t>(b >> 6);
+        spans[2 * k + 1] = multi ? -1 : static_cast<int32_t>((e - 1) >> 6);
+    }
 }
 
 struct MaxOp {
@@ -250,16 +258,20 @@ hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int6
         if ((err = hipMalloc(&cnt, sizeof(unsigned int))) != hipSuccess) goto done;
         if ((err = hipMemsetAsync(cnt, 0, sizeof(unsigned int), nullptr)) != hipSuccess) { (void)hipFree(cnt); goto done; }
         // worst case one row per group; the list is trimmed below
-        int32_t *rows = nullptr;
-        if ((err = hipMalloc(&rows, static_cast<size_t>(last) * 4)) != hipSuccess) { (void)hipFree(cnt); goto done; }
+        int32_t *rows = nullptr;   // [last] rows, then [last][2] spans
+        if ((err = hipMalloc(&rows, static_cast<size_t>(last) * 12)) != hipSuccess) { (void)hipFree(cnt); goto done; }
+        int32_t *spans = rows + last;
         hipLaunchKernelGGL(k_collect_zero_rows, dim3(blocks_for(last)), dim3(kBlock), 0, nullptr, out->grp_dst, gs,
-                           static_cast<int64_t>(last), ne, rows, cnt);
+                           static_cast<int64_t>(last), ne, rows, spans, cnt);
         err = hipMemcpy(&n_zero, cnt, sizeof(unsigned int), hipMemcpyDeviceToHost);
         (void)hipFree(cnt);
         if (err == hipSuccess && n_zero > 0) {
             err = hipMalloc(&out->zero_rows, static_cast<size_t>(n_zero) * 4);
             if (err == hipSuccess)
                 err = hipMemcpy(out->zero_rows, rows, static_cast<size_t>(n_zero) * 4, hipMemcpyDeviceToDevice);
+            if (err == hipSuccess) err = hipMalloc(&out->zero_span, static_cast<size_t>(n_zero) * 8);
+            if (err == hipSuccess)
+                err = hipMemcpy(out->zero_span, spans, static_cast<size_t>(n_zero) * 8, hipMemcpyDeviceToDevice);
         }
         (void)hipFree(rows);
         if (err != hipSuccess) goto done;
@@ -279,9 +291,11 @@ done:
         if (out->grp_dst) (void)hipFree(out->grp_dst);
         if (out->tile_grp) (void)hipFree(out->tile_grp);
         if (out->zero_rows) (void)hipFree(out->zero_rows);
+        if (out->zero_span) (void)hipFree(out->zero_span);
         out->grp_dst = nullptr;
         out->tile_grp = nullptr;
         out->zero_rows = nullptr;
+        out->zero_span = nullptr;
     }
     return err;
 }
