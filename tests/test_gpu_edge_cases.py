@@ -329,3 +329,27 @@ def test_pinned_chunk_in_pieces(oracle, H, atlas, model, store, piece):
     with pytest.raises(atlas.AtlasError) as ei:
         atlas.atlas_set_piece_tiles(-1)
     assert ei.value.status == atlas.E_RANGE
+
+
+@pytest.mark.parametrize("piece", [0, 3])
+def test_pinned_plan_with_four_byte_words(oracle, H, atlas, piece):
+    """A plan of a pinned-host graph keeps its edge words in 3 bytes only for
+    chunks of at most 2^23 sources; with a larger chunk size (here one chunk over
+    the whole graph) the 4-byte words travel and are read where they were
+    staged, whole or in pieces."""
+    g = gen.rmat_graph(SEED + 43, 12, 16)
+    off, col = gen.build_csr(g)
+    new_of_old, _ = oracle.reorder_indegree_desc(oracle.in_degree(g.n, col.numpy()))
+    g = g.with_relabel(torch.from_numpy(new_of_old.astype(np.int64)))
+    case = H.make_case("sage", g, SEED + 43, [128, 64, 64], (1 << 23) + 1, store=torch.bfloat16, feat="uniform")
+    atlas.atlas_set_piece_tiles(piece)
+    try:
+        run = H.run_gpu(case, snapshots=True, pinned_host=True, plan=True)
+        H.check_integers(oracle, case, run)
+        print("4-byte words, pieces of", piece, H.check_outputs(oracle, case, run))
+        assert run.stats[0]["bytes_copied_h2d"] >= case.e * 4 + case.n * 256
+        H.check_outputs(oracle, case, H.run_gpu(case, pinned_host=True, plan=True, planned_only=True, device_later=True))
+        H.check_outputs(oracle, case, H.run_gpu(case, pinned_host=True, plan=True, planned_only=True, plan_block=(64, 8)))
+    finally:
+        atlas.atlas_set_piece_tiles(0)
+
