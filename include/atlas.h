@@ -93,7 +93,8 @@ enum atlas_flags {
                                     then skips the zero fill of the accumulators: a row is first
                                     written by its destination's first group, and the accumulator
                                     of a vertex without in-edges is never read.  Ignored without
-                                    a plan and for GAT.  With it, ATLAS_DBG_ACC rows of vertices
+                                    a plan, for GAT and for graphs of 2^30 vertices or more (their
+                                    plans lack the list of rows to clear).  With it, ATLAS_DBG_ACC rows of vertices
                                     that have received nothing yet are undefined. */
     ATLAS_FLAG_TRANSFORM_FIRST = 8 /* SAGE_MEAN / GCN_SYM / GIN: the weight matrix is
                                     applied to each chunk's rows before they are pushed (the linear map
@@ -161,7 +162,8 @@ typedef struct {
  * Requires a graph with a plan and chunks that coincide with the planned ones
  * (as with ATLAS_FLAG_PLANNED_ONLY); not available for GAT.  Each chunk costs
  * one wait for the stream (the host reads the slot counts).  On a PINNED_HOST
- * graph the evicted rows share the host link with the chunk loader's copies. */
+ * graph the evicted rows share the host link with the chunk loader's copies.
+ * N < 2^30 (E_OVERFLOW at atlas_layer_init otherwise). */
 enum atlas_evict_policy {
     ATLAS_EVICT_MIN_PENDING = 0, /* fewest pending messages first (the paper's policy)      */
     ATLAS_EVICT_MAX_PENDING = 1  /* most pending messages first (for comparison)            */

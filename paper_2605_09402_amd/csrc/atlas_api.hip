@@ -308,7 +308,8 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
         const atlas_plan *pl = L->g.plan;
         if (!pl || pl->host != (L->g.residency == ATLAS_RESIDENT_PINNED_HOST) || pl->n != n || pl->e != L->e)
             return ATLAS_E_STATE;
-        if (d.hot_slots >= (int64_t(1) << 31)) return ATLAS_E_OVERFLOW;
+        // slots are never zero-filled: the store relies on the plan's list of rows to clear
+        if (d.hot_slots >= (int64_t(1) << 31) || n >= (int64_t(1) << 30)) return ATLAS_E_OVERFLOW;
     }
     const size_t acc_rows = L->bounded ? static_cast<size_t>(d.hot_slots) : n1;
     HIP_TRY(L->acc.alloc(acc_rows * L->acc_width * sizeof(float)));
@@ -333,7 +334,8 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
     // its accumulators and keeps the fill.
     L->planned_only = ((d.flags & ATLAS_FLAG_PLANNED_ONLY) || L->bounded) && L->g.plan && d.model != ATLAS_MODEL_GAT &&
                       L->g.plan->host == (L->g.residency == ATLAS_RESIDENT_PINNED_HOST) &&
-                      L->g.plan->n == n && L->g.plan->e == L->e;
+                      L->g.plan->n == n && L->g.plan->e == L->e &&
+                      n < (int64_t(1) << 30);   // the plan lists the rows to clear only below 2^30 vertices
     if (!L->planned_only)
         HIP_TRY(launch_fill_zero(L->acc.p, static_cast<size_t>(n) * L->acc_width * sizeof(float), s));
     if (L->bounded) {
@@ -518,10 +520,8 @@ int stage_pinned_chunk(atlas_layer *L, const atlas_plan *plan, const PlanChunk *
             HIP_TRY(hipMemcpyAsync(g_dev, pc->grp_dst, gb, hipMemcpyHostToDevice, L->copy_stream));
             HIP_TRY(hipMemcpyAsync(t_dev, pc->tile_grp, tb, hipMemcpyHostToDevice, L->copy_stream));
             const int64_t ntiles = (pc->n_edges + 63) / 64;
-            // (a planned-only layer whose plan has no list of rows to clear finds them by a scan of the
-            // whole chunk's words: such a chunk is pushed in one piece)
-            // (so is a GAT chunk: its maximum sweep reads all of the chunk's edges before the push)
-            if (ntiles >= 2 * st.piece_tiles && (!L->planned_only || pc->has_zero_rows) && d.model != ATLAS_MODEL_GAT)
+            // (a GAT chunk is pushed in one piece: its maximum sweep reads all of the chunk's edges first)
+            if (ntiles >= 2 * st.piece_tiles && d.model != ATLAS_MODEL_GAT)
                 st.npieces = static_cast<int>((ntiles + st.piece_tiles - 1) / st.piece_tiles);
             auto &evs = L->piece_ev[slot];
             while (static_cast<int>(evs.size()) < st.npieces) {
@@ -922,15 +922,11 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
             // a chunk pushed in one launch: its runs are chosen here, so that the rows of groups that stay
             // within one run need not be cleared
             if (st.npieces == 1 && ga.n_edges > 0) HIP_TRY(plan_runs(ga));
-            if (L->planned_only) {
-                if (pc->has_zero_rows) {   // the list (device memory, also in plans of pinned-host graphs) covers
-                    if (p == 0)            // the whole chunk: cleared once, before the first piece adds anything
-                        HIP_TRY(launch_zero_rows(pc->zero_rows, pc->zero_span, pc->n_zero_rows, ga.acc, ga.slot_of,
-                                                 ga.d, st.npieces == 1 ? &ga : nullptr, s));
-                } else {
-                    HIP_TRY(launch_zero_cut_first_rows(ga, s));   // (one piece, see above)
-                }
-            }
+            // the list (device memory, also in plans of pinned-host graphs) covers the whole chunk: cleared
+            // once, before the first piece adds anything
+            if (L->planned_only && p == 0)
+                HIP_TRY(launch_zero_rows(pc->zero_rows, pc->zero_span, pc->n_zero_rows, ga.acc, ga.slot_of, ga.d,
+                                         st.npieces == 1 ? &ga : nullptr, s));
             HIP_TRY(launch_aggregate_grouped(ga, &L->run_tickets, s));
         }
     } else {

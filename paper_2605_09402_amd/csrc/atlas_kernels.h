@@ -103,7 +103,8 @@ struct PlanChunk {
     int32_t *zero_span = nullptr; // [n_zero_rows][2] first and last 64-edge tile of that first group, or {-1, -1}
                                   // for a destination with several groups: a launch whose runs keep the group
                                   // within one wave need not clear the row
-    bool has_zero_rows = false;   // false: not precomputed, the launch scans the tile boundaries instead
+    bool has_zero_rows = false;   // the list exists (plans of graphs with fewer than 2^30 vertices): planned-only
+                                  // layers need it
     int64_t packed_off = 0;       // plans with 24-bit edge words: byte offset of the chunk's words in the plan's array
 };
 
@@ -140,7 +141,7 @@ struct GroupedArgs {
     int64_t tile_begin = 0;     // the launch covers tiles [tile_begin, tile_end) of the chunk (tile_end < 0: all).
     int64_t tile_end = -1;      // A chunk that arrives over the host link in pieces is pushed piece by piece;
                                 // a group cut by a piece boundary is added with atomics like one cut by a run.
-                                // (launch_zero_cut_first_rows always examines the whole chunk)
+                                // (launch_zero_rows covers the whole chunk: once, before the first piece)
     // set by the launcher:
     int nruns = 0;              // runs in [tile_begin, tile_end): the first big_runs of tiles_per_run tiles,
     int big_runs = 0;           // the others (the launch's last tiles, taken when most waves are about to
@@ -203,10 +204,10 @@ struct GatFinalizeArgs {
 hipError_t launch_gat_finalize(const GatFinalizeArgs &a, hipStream_t s);
 
 // Planned-only layers skip the accumulator zero fill: rows are first written by
-// their first group.  A first group cut by a tile boundary is added with
-// atomics from several tiles, so its row is zeroed here before the chunk runs.
-hipError_t launch_zero_cut_first_rows(const GroupedArgs &a, hipStream_t s);
-// The same from a list of rows precomputed with the plan.  With `spans` and the runs of the launch that
+// their first group.  A first group that several waves add to with atomics (it
+// is cut by a run boundary, or its destination has one group per source block)
+// has its row zeroed here before the chunk runs, from the list of candidates
+// precomputed with the plan.  With `spans` and the runs of the launch that
 // follows (`runs`, after plan_runs; nullptr: unknown, e.g. a chunk pushed in pieces) a row is left alone when
 // its group lies inside one run: the run's wave then holds the whole sum and stores it.
 hipError_t launch_zero_rows(const int32_t *rows, const int32_t *spans, int64_t n_rows, float *acc,

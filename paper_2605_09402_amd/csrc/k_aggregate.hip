@@ -812,50 +812,6 @@ __global__ __launch_bounds__(kBlock) void k_gat_rescale_cut_groups(GroupedArgs a
     }
 }
 
-// One lane per tile boundary: if the boundary cuts a group and that group is
-// its destination's first, the wave zeroes the destination's row together
-// (see launch_zero_cut_first_rows).
-__global__ __launch_bounds__(kBlock) void k_zero_cut_first_rows(GroupedArgs a) {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int64_t ntiles = (a.n_edges + kTileEdges - 1) / kTileEdges;
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
-    // every lane of a wave runs the same number of rounds (t0 is wave-uniform)
-    for (int64_t t0 = 1 + static_cast<int64_t>(blockIdx.x) * kBlock + (threadIdx.x & ~(kWave - 1)); t0 < ntiles;
-         t0 += stride) {
-        const int64_t t = t0 + lane;
-        int32_t gd = 0;
-        if (t < ntiles && a.src_sorted[t * kTileEdges - 1] >= 0)  // the previous tile ends inside a group
-            gd = a.grp_dst[a.tile_grp[t]];                        // group of the tile's first edge = the cut one
-        uint64_t todo = __ballot(gd < 0);
-        while (todo) {
-            const int j = __ffsll(static_cast<unsigned long long>(todo)) - 1;
-            todo &= todo - 1;
-            int64_t v = __builtin_amdgcn_readlane(gd, j) & 0x7fffffff & ~a.multi_bit;
-            if (a.slot_of) v = a.slot_of[v];   // bounded store: the destination's slot
-            float *row = a.acc + v * a.d;
-            for (int c = lane; c < a.d; c += kWave) row[c] = 0.f;
-        }
-    }
-    if (!a.multi_bit) return;
-    // source-blocked chunk: a destination with several groups is added to with atomics by all of them;
-    // its first group of the layer (one per destination) has the row cleared here
-    for (int64_t g0 = static_cast<int64_t>(blockIdx.x) * kBlock + (threadIdx.x & ~(kWave - 1)); g0 < a.n_groups;
-         g0 += stride) {
-        const int64_t g = g0 + lane;
-        int32_t gd = 0;
-        if (g < a.n_groups) gd = a.grp_dst[g];
-        uint64_t todo = __ballot(gd < 0 && (gd & a.multi_bit) != 0);
-        while (todo) {
-            const int j = __ffsll(static_cast<unsigned long long>(todo)) - 1;
-            todo &= todo - 1;
-            int64_t v = __builtin_amdgcn_readlane(gd, j) & 0x7fffffff & ~a.multi_bit;
-            if (a.slot_of) v = a.slot_of[v];
-            float *row = a.acc + v * a.d;
-            for (int c = lane; c < a.d; c += kWave) row[c] = 0.f;
-        }
-    }
-}
-
 // A wave takes 64 listed rows at a time, one per lane for the test, then clears those that need it
 // together.  run > 0: the runs of the launch that follows are known (the first `big` of `run` tiles,
 // then runs of `small`); a group whose first and last tile fall into one run needs no clearing.
@@ -995,17 +951,6 @@ hipError_t launch_aggregate(const AggregateArgs &a, hipStream_t s) {
     if (a.in_dt == 2) return a.model == 1 ? launch_vpl<_Float16, 1>(a, grid, s) : launch_vpl<_Float16, 0>(a, grid, s);
     if (a.in_dt == 1) return a.model == 1 ? launch_vpl<uint16_t, 1>(a, grid, s) : launch_vpl<uint16_t, 0>(a, grid, s);
     return a.model == 1 ? launch_vpl<float, 1>(a, grid, s) : launch_vpl<float, 0>(a, grid, s);
-}
-
-hipError_t launch_zero_cut_first_rows(const GroupedArgs &a, hipStream_t s) {
-    const int64_t ntiles = (a.n_edges + kTileEdges - 1) / kTileEdges;
-    if (ntiles <= 1 && !a.multi_bit) return hipSuccess;
-    int64_t blocks = (std::max(ntiles, a.multi_bit ? a.n_groups : int64_t(0)) + kBlock - 1) / kBlock;
-    if (blocks < 1) blocks = 1;
-    const int cap = persistent_grid(8);
-    if (blocks > cap) blocks = cap;
-    hipLaunchKernelGGL(k_zero_cut_first_rows, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, s, a);
-    return hipGetLastError();
 }
 
 hipError_t launch_gat_group_max(const GroupedArgs &a, hipStream_t s) {
