@@ -118,7 +118,7 @@ def kernels_md(stats_csv: str, trace_csv: str, bench_json: str, traffic_json: st
     out.append("| kernel | calls | total ms | avg us | min us | max us |\n|---|---|---|---|---|---|\n" + rows + "\n")
     out.append("k_aggregate_grouped: average launch %.3f ms over %s launches; bench.py's HIP-event figure for the "
                "timed launches of the\nsame run: %.2f ms per layer / %d = %.2f ms (the event span also covers "
-               "k_zero_cut_first_rows).\n" % (float(agg["AverageNs"]) / 1e6, agg["Calls"], lm["aggregate"], nchunks,
+               "k_zero_rows).\n" % (float(agg["AverageNs"]) / 1e6, agg["Calls"], lm["aggregate"], nchunks,
                                                b["roofline"]["avg_launch_ms"]))
     out.append("Launch times of one layer (ms), chunk 0 first; with in-degree-descending ids chunk 0 holds the hot "
                "sources and most edges.\nk_aggregate_grouped:\n\n    %s\n\nk_update_pipelined:\n\n    %s\n"
