@@ -26,6 +26,16 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+def cpu_model() -> str:
+    try:
+        for ln in open("/proc/cpuinfo"):
+            if ln.lower().startswith("model name"):
+                return ln.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def log(*a):
     print("[bench]", *a, file=sys.stderr, flush=True)
 
@@ -368,7 +378,8 @@ def main() -> int:
                "kind": "oracle",
                "sample": "%d destinations (%d random + the 1,024 highest in-degree) with all %d of their in-edges, "
                          "layer 1 aggregate + update in fp64" % (pick.numel(), args.sample_dst, sample_edges),
-               "seconds": round(t_or, 3), "sampled_parity_max_rel_err": err}
+               "seconds": round(t_or, 3), "sampled_parity_max_rel_err": err,
+               "cpu_model": cpu_model(), "host_cpus": os.cpu_count()}
 
     if plan is not None:
         atlas.atlas_plan_destroy(plan)
