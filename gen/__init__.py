@@ -383,3 +383,24 @@ def in_edges_of(off: torch.Tensor, col: torch.Tensor, dst_ids: torch.Tensor,
     in_off = torch.zeros(dst_ids.numel() + 1, dtype=torch.int64, device=dev)
     torch.cumsum(cnt, 0, out=in_off[1:])
     return in_off, src.to(torch.int32)
+
+
+def sample_subgraph(off: torch.Tensor, col: torch.Tensor, dst_ids: torch.Tensor):
+    """The in-edges of a few destinations as a small self-contained problem.
+
+    Returns (in_off, in_src_local, need, dst_local): `need` lists, ascending, the
+    vertices that occur as a picked destination or as one of their in-neighbours;
+    rows of per-vertex arrays are taken at `need` (X[need], indeg[need]) and every
+    id is renumbered to its position in `need`: in_src_local holds the sources of
+    in_edges_of(off, col, dst_ids) in that numbering, dst_local the destinations.
+    Pure data movement, like in_edges_of: no degree, sum or normalisation is
+    computed here.
+    """
+    dev = col.device
+    n = off.numel() - 1
+    dst_ids = dst_ids.to(device=dev, dtype=torch.int64)
+    in_off, in_src = in_edges_of(off, col, dst_ids)
+    need = torch.unique(torch.cat([in_src.to(torch.int64), dst_ids]))
+    local = torch.full((n,), -1, dtype=torch.int64, device=dev)
+    local[need] = torch.arange(need.numel(), dtype=torch.int64, device=dev)
+    return in_off, local[in_src.to(torch.int64)].to(torch.int32), need, local[dst_ids]

@@ -182,16 +182,18 @@ def round_storage(Y: np.ndarray, fmt: int) -> np.ndarray:
 
 
 def completion_chunk(il: InLists, selfmsg: bool, C: int) -> np.ndarray:
+    """Chunk (of C sources) whose broadcast completes each destination of `il`, -1: complete at layer
+    start.  With il.dst_ids the lists belong to those vertices and in_src holds streaming ids."""
     cc = np.empty(il.n_dst, dtype=np.int64)
-    lib().ao_completion_chunk(_i64(il.n_dst), _p(il.in_off), _p(il.in_src), ctypes.c_int(int(selfmsg)),
-                              _i64(C), _p(cc))
+    lib().ao_completion_chunk(_i64(il.n_dst), _p(il.dst_ids), _p(il.in_off), _p(il.in_src),
+                              ctypes.c_int(int(selfmsg)), _i64(C), _p(cc))
     return cc
 
 
 def pending_after(il: InLists, selfmsg: bool, bound: int) -> np.ndarray:
     out = np.empty(il.n_dst, dtype=np.int64)
-    lib().ao_pending_after(_i64(il.n_dst), _p(il.in_off), _p(il.in_src), ctypes.c_int(int(selfmsg)),
-                           _i64(bound), _p(out))
+    lib().ao_pending_after(_i64(il.n_dst), _p(il.dst_ids), _p(il.in_off), _p(il.in_src),
+                           ctypes.c_int(int(selfmsg)), _i64(bound), _p(out))
     return out
 
 

@@ -34,8 +34,11 @@
  * bf16 and IEEE half precision (the paper's largest feature set is stored in
  * FP16, Sec. 4.1), each a single round-to-nearest-even of the fp64 result.
  *
- * Pins: see tests/test_oracle_*.py (dense adjacency brute force, the Fig. 2
- * worked example, closed forms, permutation invariance, counter invariants).
+ * Pins: tests/test_oracle_pins.py (dense adjacency brute force, the Fig. 2 worked
+ * example, closed forms, permutation invariance, counter invariants) and
+ * tests/test_oracle_subset_pins.py (the same functions called on a subset of the
+ * destinations with renumbered ids, against the dense brute force; the placement
+ * of the activation in a chain of layers; planted slips that the pins must catch).
  */
 #include <math.h>
 #include <stdint.h>
@@ -277,28 +280,32 @@ void ao_round_storage(int64_t count, double *Y, int fmt) {
     }
 }
 
-/* completion_chunk[v] = floor(max(in-neighbours of v, and v itself when the
- * model sends a self message) / C); -1 when that set is empty (complete at
- * layer start). */
-void ao_completion_chunk(int64_t n, const int64_t *in_off, const int32_t *in_src,
-                         int selfmsg, int64_t C, int64_t *cc) {
-    for (int64_t v = 0; v < n; ++v) {
+/* completion_chunk[i] = floor(max(in-neighbours of v, and v itself when the
+ * model sends a self message) / C) for destination i = vertex v = dst_ids[i]
+ * (or i); -1 when that set is empty (complete at layer start).  Source ids in
+ * in_src are the ids the chunks are streamed in. */
+void ao_completion_chunk(int64_t n_dst, const int64_t *dst_ids, const int64_t *in_off,
+                         const int32_t *in_src, int selfmsg, int64_t C, int64_t *cc) {
+    for (int64_t i = 0; i < n_dst; ++i) {
+        int64_t v = dst_id(dst_ids, i);
         int64_t last = selfmsg ? v : -1;
-        for (int64_t p = in_off[v]; p < in_off[v + 1]; ++p)
+        for (int64_t p = in_off[i]; p < in_off[i + 1]; ++p)
             if (in_src[p] > last) last = in_src[p];
-        cc[v] = last < 0 ? -1 : last / C;
+        cc[i] = last < 0 ? -1 : last / C;
     }
 }
 
-/* pending[v] after all sources < bound have been broadcast:
+/* pending of destination i (vertex v = dst_ids[i] or i) after all sources < bound
+ * have been broadcast:
  * d_in(v) + selfmsg - #{in-neighbours u < bound} - [selfmsg and v < bound]. */
-void ao_pending_after(int64_t n, const int64_t *in_off, const int32_t *in_src, int selfmsg,
-                      int64_t bound, int64_t *pending) {
-    for (int64_t v = 0; v < n; ++v) {
+void ao_pending_after(int64_t n_dst, const int64_t *dst_ids, const int64_t *in_off,
+                      const int32_t *in_src, int selfmsg, int64_t bound, int64_t *pending) {
+    for (int64_t i = 0; i < n_dst; ++i) {
+        int64_t v = dst_id(dst_ids, i);
         int64_t got = 0;
-        for (int64_t p = in_off[v]; p < in_off[v + 1]; ++p) got += in_src[p] < bound;
+        for (int64_t p = in_off[i]; p < in_off[i + 1]; ++p) got += in_src[p] < bound;
         if (selfmsg && v < bound) got += 1;
-        pending[v] = (in_off[v + 1] - in_off[v]) + (selfmsg ? 1 : 0) - got;
+        pending[i] = (in_off[i + 1] - in_off[i]) + (selfmsg ? 1 : 0) - got;
     }
 }
 
