@@ -144,7 +144,24 @@ typedef struct {
     int64_t hot_slots;         /* 0 (or >= N): one accumulator row per vertex.  0 < hot_slots < N:
                                   bounded accumulator store with that many rows, see below  */
     int32_t evict_policy;      /* atlas_evict_policy of the bounded store                   */
+    int32_t tiles_per_run;     /* launch shape of the planned aggregation, see below; 0: the
+                                  library chooses per launch                                */
+    int64_t piece_tiles;       /* chunk loader of PINNED_HOST graphs with a plan, see below;
+                                  0: the library's default (2^21 tiles)                     */
 } atlas_dims_t;
+
+/* The two launch-shape fields of atlas_dims_t.  Results do not depend on either beyond the
+ * order of fp32 additions; 0 is the right value outside tests and tuning runs.
+ *   tiles_per_run (0..16, else E_BAD_DIMS): in the planned aggregation each wave takes runs of
+ *     that many consecutive 64-edge tiles of the chunk's destination-ordered edge list and
+ *     keeps a destination's partial sum in registers from one tile of a run to the next.  0:
+ *     chosen from the chunk's size (1 for small chunks, up to 16).  With runs of 4 tiles or
+ *     more the runs after a wave's first are handed out by a counter instead of a fixed
+ *     stride; with 8 or more the launch's last tiles go out in runs a quarter as long.
+ *   piece_tiles (0..2^30, else E_BAD_DIMS): a planned chunk of at least 2 * piece_tiles tiles
+ *     crosses the host link in pieces of piece_tiles tiles and each piece is pushed as soon as
+ *     it has arrived, so that a long chunk's copy and kernels overlap (Sec. 3.3: the reader
+ *     runs ahead of the aggregation). */
 
 /* Bounded accumulator store (the paper's memory manager, Sec. 3.5, with HBM as the
  * hot tier and library-owned pinned host memory as the cold tier).  Only vertices
@@ -205,6 +222,11 @@ typedef struct {
     int64_t hot_evictions;      /* bounded store: rows written to the cold tier             */
     int64_t hot_reloads;        /* bounded store: rows read back from the cold tier         */
     int64_t hot_peak_slots;     /* bounded store: most rows in use at once                  */
+    int64_t chunks_planned;     /* chunks pushed from the plan (destination-grouped edges)  */
+    int64_t chunks_csr_stream;  /* chunks pushed straight from the CSR with fp32 atomics: no
+                                   plan, or a range that is not one of the plan's chunks.
+                                   About ten times slower per edge; chunks_planned +
+                                   chunks_csr_stream == num_chunks                          */
 } atlas_layer_stats_t;
 
 /* Create the state of one layer (Sec. 3.4: pending-message tracker and
@@ -212,7 +234,9 @@ typedef struct {
  * pending0[v] = d_in(v) (+1 for SAGE_MEAN and GIN: the vertex's own embedding is a
  * message to itself that arrives with its own chunk).  Vertices with
  * pending0 == 0 are placed on the ready list here.  Accumulators are zeroed.
- * Enqueues on `hip_stream` (a hipStream_t, NULL = default stream) and returns
+ * Enqueues on `hip_stream` (a hipStream_t, NULL = default stream; the set-up kernels
+ * are ordered with the chunk and flush calls that follow, which is why the call takes
+ * the stream although the layer's definition has no use for one) and returns
  * without waiting.  *out receives the layer.  Errors: E_NULL, E_BAD_DIMS,
  * E_OVERFLOW, E_NOMEM, E_HIP. */
 int atlas_layer_init(const atlas_graph_t *graph, const atlas_dims_t *dims,
@@ -333,28 +357,11 @@ enum atlas_debug_what {
 };
 int atlas_debug_copy(atlas_layer_t *layer, int what, void *host_dst, int64_t bytes);
 
-/* Launch shape of the planned aggregation (Sec. 3.3, the push of one chunk's
- * messages): each wave takes runs of `tiles` consecutive 64-edge tiles of the
- * chunk's destination-ordered edge list and keeps a destination's partial sum
- * in registers from one tile of a run to the next.  0 (the default) lets the
- * library choose from the chunk's size (1 for small chunks, up to 16); 1..16
- * forces that length for every later launch of the process, which is how the
- * tests reach the long-run path on small graphs.  With runs of 4 tiles or more
- * the runs after a wave's first are handed out by a counter instead of a fixed
- * stride, with 8 or more the launch's last tiles go out in runs a quarter as
- * long.  Results do not depend on any of this beyond fp32 summation order.
- * Errors: E_RANGE. */
-int atlas_set_tiles_per_run(int tiles);
-
-/* Chunk loader of PINNED_HOST graphs with a plan (Sec. 3.3, the reader that runs
- * ahead of the aggregation): a planned chunk of at least 2 * `tiles` 64-edge
- * tiles crosses the host link in pieces of `tiles` tiles, and each piece is
- * pushed as soon as it has arrived, so a long chunk's copy and kernels overlap.
- * 0 restores the default (2^21 tiles); small values are for tests.  Applies to
- * every later atlas_broadcast_chunk of the process.  Errors: E_RANGE. */
-int atlas_set_piece_tiles(int64_t tiles);
-
-/* Free the device buffers the library keeps for reuse between layers. */
+/* Free what the library keeps for reuse between layers: its cache of device buffers, the
+ * bounded store's pinned cold tier, and the chunk loader's copy stream (created again when
+ * next needed).  Call it when no layer is alive, e.g. before the process ends: the HIP
+ * runtime may already be shutting down when static destructors run, so the library frees
+ * nothing by itself at exit. */
 int atlas_release_cache(void);
 
 const char *atlas_strerror(int status);

@@ -31,7 +31,7 @@ EXPORTS = [
     "atlas_layer_init", "atlas_attention_prepass", "atlas_broadcast_chunk", "atlas_flush_ready",
     "atlas_layer_finish", "atlas_in_degree", "atlas_reorder_indegree_desc", "atlas_debug_copy",
     "atlas_release_cache", "atlas_strerror", "atlas_last_hip_error", "atlas_plan_create", "atlas_plan_destroy",
-    "atlas_reorder_score_desc", "atlas_sample_in_edges", "atlas_plan_create_blocked", "atlas_set_tiles_per_run", "atlas_set_piece_tiles",
+    "atlas_reorder_score_desc", "atlas_sample_in_edges", "atlas_plan_create_blocked",
 ]
 
 
@@ -47,7 +47,8 @@ class atlas_dims_t(ctypes.Structure):
                 ("heads", ctypes.c_int32), ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
                 ("activation", ctypes.c_int32), ("neg_slope", ctypes.c_float),
                 ("max_chunk_sources", ctypes.c_int64), ("flags", ctypes.c_int32), ("gin_eps", ctypes.c_float),
-                ("hot_slots", ctypes.c_int64), ("evict_policy", ctypes.c_int32)]
+                ("hot_slots", ctypes.c_int64), ("evict_policy", ctypes.c_int32),
+                ("tiles_per_run", ctypes.c_int32), ("piece_tiles", ctypes.c_int64)]
 
 
 class atlas_weights_t(ctypes.Structure):
@@ -62,7 +63,8 @@ class atlas_layer_stats_t(ctypes.Structure):
                 ("bytes_copied_h2d", ctypes.c_int64), ("ms_aggregate", ctypes.c_float),
                 ("ms_self", ctypes.c_float), ("ms_update", ctypes.c_float), ("ms_copy", ctypes.c_float),
                 ("ms_init", ctypes.c_float), ("hot_evictions", ctypes.c_int64), ("hot_reloads", ctypes.c_int64),
-                ("hot_peak_slots", ctypes.c_int64)]
+                ("hot_peak_slots", ctypes.c_int64), ("chunks_planned", ctypes.c_int64),
+                ("chunks_csr_stream", ctypes.c_int64)]
 
 
 class AtlasError(RuntimeError):
@@ -100,8 +102,6 @@ def lib() -> ctypes.CDLL:
         L.atlas_reorder_score_desc.argtypes = [ctypes.POINTER(atlas_graph_t), vp, vp]
         L.atlas_sample_in_edges.argtypes = [ctypes.POINTER(atlas_graph_t), vp, i32, vp, vp, ctypes.POINTER(i64)]
         L.atlas_debug_copy.argtypes = [vp, i32, vp, i64]
-        L.atlas_set_tiles_per_run.argtypes = [ctypes.c_int]
-        L.atlas_set_piece_tiles.argtypes = [ctypes.c_int64]
         L.atlas_release_cache.argtypes = []
         L.atlas_plan_create.argtypes = [ctypes.POINTER(atlas_graph_t), i64, ctypes.POINTER(vp)]
         L.atlas_plan_create_blocked.argtypes = [ctypes.POINTER(atlas_graph_t), i64, i64, i64, ctypes.POINTER(vp)]
@@ -149,9 +149,10 @@ def make_graph(num_vertices: int, num_edges: int, row_offsets, col_indices, in_d
 
 def make_dims(model: int, d_in: int, d_out: int, in_dtype: int, out_dtype: int, activation: int,
               max_chunk_sources: int, heads: int = 1, neg_slope: float = 0.2, flags: int = 0,
-              gin_eps: float = 0.0, hot_slots: int = 0, evict_policy: int = 0) -> atlas_dims_t:
+              gin_eps: float = 0.0, hot_slots: int = 0, evict_policy: int = 0, tiles_per_run: int = 0,
+              piece_tiles: int = 0) -> atlas_dims_t:
     return atlas_dims_t(model, d_in, d_out, heads, in_dtype, out_dtype, activation, neg_slope,
-                        max_chunk_sources, flags, gin_eps, hot_slots, evict_policy)
+                        max_chunk_sources, flags, gin_eps, hot_slots, evict_policy, tiles_per_run, piece_tiles)
 
 
 def make_weights(W, bias, dtype: int, attn_src=None, attn_dst=None) -> atlas_weights_t:
@@ -236,14 +237,6 @@ def atlas_sample_in_edges(graph: atlas_graph_t, edge_key, fanout: int, out_row_o
 def atlas_debug_copy(layer: int, what: int, host_array) -> None:
     """host_array: a numpy array (contiguous) that receives the bytes."""
     _check(lib().atlas_debug_copy(layer, what, host_array.ctypes.data, host_array.nbytes), "atlas_debug_copy")
-
-
-def atlas_set_tiles_per_run(tiles: int) -> None:
-    _check(lib().atlas_set_tiles_per_run(int(tiles)), "atlas_set_tiles_per_run")
-
-
-def atlas_set_piece_tiles(tiles: int) -> None:
-    _check(lib().atlas_set_piece_tiles(int(tiles)), "atlas_set_piece_tiles")
 
 
 def atlas_release_cache() -> None:

@@ -8,7 +8,6 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
-#include <atomic>
 #include <mutex>
 #include <new>
 #include <string>
@@ -95,8 +94,8 @@ hipError_t cold_buffer(size_t bytes, void **out) {
     return hipSuccess;
 }
 
-// tiles per piece of a long pinned-host chunk (atlas_set_piece_tiles); default 2^21 tiles = 2^27 edges
-std::atomic<int64_t> g_piece_tiles{int64_t(1) << 21};
+// tiles per piece of a long pinned-host chunk unless dims.piece_tiles says otherwise: 2^21 tiles = 2^27 edges
+constexpr int64_t kDefaultPieceTiles = int64_t(1) << 21;
 
 // The chunk loader's copy stream is created once per process and shared by
 // all layers: HIP spreads streams over a few hardware queues, and a stream
@@ -176,6 +175,7 @@ struct atlas_layer {
     int64_t next_src = 0;
     uint32_t run_tickets = 0;          // tickets drawn so far from the grouped aggregation's run counter
     int64_t num_chunks = 0, num_flushes = 0;
+    int64_t chunks_planned = 0, chunks_csr = 0;   // which aggregation path each chunk took
     int64_t bytes_h2d = 0;
 
     // pinned-host loader
@@ -261,6 +261,8 @@ int check_dims(const atlas_dims_t &d, const atlas_weights_t &w) {
     if (d.hot_slots < 0 || d.evict_policy < ATLAS_EVICT_MIN_PENDING || d.evict_policy > ATLAS_EVICT_MAX_PENDING)
         return ATLAS_E_BAD_DIMS;
     if (d.hot_slots > 0 && d.model == ATLAS_MODEL_GAT) return ATLAS_E_BAD_DIMS;
+    if (d.tiles_per_run < 0 || d.tiles_per_run > atlas::kMaxTilesPerRun) return ATLAS_E_BAD_DIMS;
+    if (d.piece_tiles < 0 || d.piece_tiles > (int64_t(1) << 30)) return ATLAS_E_BAD_DIMS;
     const int K = d.model == ATLAS_MODEL_SAGE_MEAN && !tf ? 2 * d.d_in : d.d_in;
     // GIN forms (1 + eps) x_v + sum in the compute type before the contraction: a hub's sum leaves the
     // range of IEEE half, so half-precision GIN runs transform-first only (products summed in fp32)
@@ -817,7 +819,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
     // arrived, so the chunk's copy and its kernels overlap (the first chunk of a degree-ordered graph
     // holds most of the edges).
     StagedChunk st;
-    st.piece_tiles = g_piece_tiles.load(std::memory_order_relaxed);
+    st.piece_tiles = d.piece_tiles > 0 ? d.piece_tiles : kDefaultPieceTiles;
     if (L->g.residency == ATLAS_RESIDENT_PINNED_HOST) {
         int rc = stage_pinned_chunk(L, plan, pc, src_begin, src_end, emb, emb_bytes, emb_dev, self_dst, s, a, ga, st);
         if (rc != ATLAS_OK) return rc;
@@ -885,6 +887,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         ga.ready = a.ready;
         ga.counters = a.counters;
         ga.counters64 = a.counters64;
+        ga.forced_run = d.tiles_per_run;
     }
     if (d.model == ATLAS_MODEL_GAT) {
         if (pc) {
@@ -940,6 +943,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
     }
     L->next_src = src_end;
     L->num_chunks += 1;
+    (pc ? L->chunks_planned : L->chunks_csr) += 1;
     return ATLAS_OK;
 }
 
@@ -1041,6 +1045,8 @@ int atlas_layer_finish(atlas_layer_t *L, atlas_layer_stats_t *stats) {
         stats->num_chunks = L->num_chunks;
         stats->num_flushes = L->num_flushes;
         stats->bytes_copied_h2d = L->bytes_h2d;
+        stats->chunks_planned = L->chunks_planned;
+        stats->chunks_csr_stream = L->chunks_csr;
         if (L->bounded) {
             int32_t hc[HS_COUNT] = {0};
             if (hipMemcpy(hc, L->hs.ctr, sizeof(hc), hipMemcpyDeviceToHost) == hipSuccess) {
@@ -1297,19 +1303,14 @@ int atlas_release_cache(void) {
         g_cold = nullptr;
         g_cold_bytes = 0;
     }
+    if (g_copy_stream) {
+        // no layer is alive (the caller's promise), so nothing is queued on it any more
+        hipError_t e = hipStreamSynchronize(g_copy_stream);
+        if (e == hipSuccess) e = hipStreamDestroy(g_copy_stream);
+        if (e != hipSuccess && first == hipSuccess) first = e;
+        g_copy_stream = nullptr;
+    }
     if (first != hipSuccess) return hip_fail(first, "hipFree");
-    return ATLAS_OK;
-}
-
-int atlas_set_piece_tiles(int64_t tiles) {
-    if (tiles < 0 || tiles > (int64_t(1) << 30)) return ATLAS_E_RANGE;
-    g_piece_tiles.store(tiles == 0 ? int64_t(1) << 21 : tiles, std::memory_order_relaxed);
-    return ATLAS_OK;
-}
-
-int atlas_set_tiles_per_run(int tiles) {
-    if (tiles < 0 || tiles > atlas::kMaxTilesPerRun) return ATLAS_E_RANGE;
-    atlas::set_tiles_per_run(tiles);
     return ATLAS_OK;
 }
 

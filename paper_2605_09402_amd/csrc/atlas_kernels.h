@@ -137,6 +137,7 @@ struct GroupedArgs {
                                 // several groups in this chunk (all of them add with atomics); else 0
     float *scores = nullptr;    // GAT only: [n_edges][heads] attention logits of the chunk's edges, written
                                 // by the max sweep and read by the aggregation
+    int forced_run = 0;         // the layer's run length (1..kMaxTilesPerRun), 0: chosen per launch
     int tiles_per_run = 1;      // consecutive 64-edge tiles one wave takes at a time (set by the launcher)
     int64_t tile_begin = 0;     // the launch covers tiles [tile_begin, tile_end) of the chunk (tile_end < 0: all).
     int64_t tile_end = -1;      // A chunk that arrives over the host link in pieces is pushed piece by piece;
@@ -150,8 +151,6 @@ struct GroupedArgs {
     uint32_t run_base = 0;      // value of that counter when the launch begins
 };
 
-// forced run length of the grouped aggregation, 0 = chosen per launch
-void set_tiles_per_run(int tiles);
 constexpr int kMaxTilesPerRun = 16;
 
 // S2+S3+S4 over a planned chunk: per-destination register sums, one row update

@@ -15,7 +15,6 @@
 #include "atlas_kernels.h"
 
 #include <hip/hip_runtime.h>
-#include <atomic>
 #include <type_traits>
 
 namespace atlas {
@@ -849,7 +848,6 @@ __global__ __launch_bounds__(kBlock) void k_zero_rows(const int32_t *__restrict_
     }
 }
 
-std::atomic<int> g_tiles_per_run{0};
 constexpr int kMinDynamicRun = 4;
 constexpr int kMinSplitRun = 8;
 
@@ -864,8 +862,7 @@ hipError_t plan_runs_on(GroupedArgs &a, int grid) {
     if (mine == 0) return hipSuccess;
     const int64_t fit = mine / (4 * nwaves);
     a.tiles_per_run = static_cast<int>(fit < 1 ? 1 : fit > kMaxTilesPerRun ? kMaxTilesPerRun : fit);
-    const int forced = g_tiles_per_run.load(std::memory_order_relaxed);
-    if (forced > 0) a.tiles_per_run = forced;
+    if (a.forced_run > 0) a.tiles_per_run = a.forced_run > kMaxTilesPerRun ? kMaxTilesPerRun : a.forced_run;
     if (ntiles > 0x7fffffff) return hipErrorInvalidValue;   // tile indices are 32-bit in the kernel
     a.nruns = static_cast<int>((mine + a.tiles_per_run - 1) / a.tiles_per_run);
     a.big_runs = a.nruns;
@@ -940,8 +937,6 @@ int persistent_grid(int blocks_per_cu) {
 }
 
 }  // namespace
-
-void set_tiles_per_run(int tiles) { g_tiles_per_run.store(tiles, std::memory_order_relaxed); }
 
 hipError_t launch_aggregate(const AggregateArgs &a, hipStream_t s) {
     if (a.d % kWave != 0) return hipErrorInvalidValue;

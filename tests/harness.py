@@ -100,13 +100,14 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
             plan: bool = False, plan_chunk: Optional[int] = None, emb_resident: bool = False,
             planned_only: bool = False, hot_slots: int = 0, evict_policy: int = 0,
             transform_first: bool = False, plan_block: Optional[tuple] = None,
-            device_later: bool = False) -> GpuRun:
+            device_later: bool = False, tiles_per_run: int = 0, piece_tiles: int = 0) -> GpuRun:
     """Drive all layers through the C ABI.  With pinned_host the graph and the
     layer-0 features stay in pinned host memory and are staged by the library.
     planned_only sets ATLAS_FLAG_PLANNED_ONLY (no zero fill of the accumulators;
     the buffers then still hold whatever the previous layer or test left there).
     device_later (with pinned_host): layers after the first are given the previous
-    layer's output where it lies in device memory instead of a pinned host copy."""
+    layer's output where it lies in device memory instead of a pinned host copy.
+    tiles_per_run / piece_tiles: the launch-shape fields of atlas_dims_t (0: the library's choice)."""
     dev = torch.device("cuda:0")
     n, e = case.n, case.e
     run = GpuRun()
@@ -154,7 +155,8 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
                                evict_policy=evict_policy, flags=(atlas.FLAG_TIMING if timing else 0) |
                                (atlas.FLAG_EMB_RESIDENT if emb_resident else 0) |
                                (atlas.FLAG_PLANNED_ONLY if planned_only else 0) |
-                               (atlas.FLAG_TRANSFORM_FIRST if transform_first else 0))
+                               (atlas.FLAG_TRANSFORM_FIRST if transform_first else 0),
+                               tiles_per_run=tiles_per_run, piece_tiles=piece_tiles)
         weights = atlas.make_weights(W, b, sdt, a_s, a_d)
         h = atlas.atlas_layer_init(graph, dims, weights, stream)
         out = torch.full((max(n, 1), d_out), float("nan"), dtype=case.store, device=dev)

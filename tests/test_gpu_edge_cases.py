@@ -303,7 +303,7 @@ def test_non_default_stream(oracle, H):
 @pytest.mark.parametrize("model,store", [("sage", torch.bfloat16), ("gcn", torch.float32), ("gin", torch.float32)])
 @pytest.mark.parametrize("piece", [1, 3, 16])
 def test_pinned_chunk_in_pieces(oracle, H, atlas, model, store, piece):
-    """atlas_set_piece_tiles: a planned chunk of a pinned-host graph arrives in
+    """dims.piece_tiles: a planned chunk of a pinned-host graph arrives in
     pieces of a few tiles and is pushed piece by piece (groups cut by a piece
     boundary, first-touch groups cleared once, ragged last piece), with and
     without the zero-fill-free layer start, source-blocked plans included.
@@ -314,21 +314,19 @@ def test_pinned_chunk_in_pieces(oracle, H, atlas, model, store, piece):
     g = g.with_relabel(torch.from_numpy(new_of_old.astype(np.int64)))
     case = H.make_case(model, g, SEED + 41, [128, 128, 64], 1024, store=store,
                        feat="normal" if store == torch.float32 else "uniform", eps=0.25 if model == "gin" else 0.0)
-    atlas.atlas_set_piece_tiles(piece)
-    try:
-        run = H.run_gpu(case, snapshots=True, pinned_host=True, plan=True)
-        H.check_integers(oracle, case, run)
-        print("pieces of", piece, model, H.check_outputs(oracle, case, run))
-        H.check_outputs(oracle, case, H.run_gpu(case, pinned_host=True, plan=True, planned_only=True, device_later=True,
-                                                flush_every=3))
-        H.check_outputs(oracle, case, H.run_gpu(case, pinned_host=True, plan=True, planned_only=True, plan_block=(64, 8)))
-        for st in run.stats:
-            assert st["edges_processed"] == case.e and st["vertices_flushed"] == case.n
-    finally:
-        atlas.atlas_set_piece_tiles(0)
+    run = H.run_gpu(case, snapshots=True, pinned_host=True, plan=True, piece_tiles=piece)
+    H.check_integers(oracle, case, run)
+    print("pieces of", piece, model, H.check_outputs(oracle, case, run))
+    H.check_outputs(oracle, case, H.run_gpu(case, pinned_host=True, plan=True, planned_only=True, device_later=True,
+                                            flush_every=3, piece_tiles=piece))
+    H.check_outputs(oracle, case, H.run_gpu(case, pinned_host=True, plan=True, planned_only=True, plan_block=(64, 8),
+                                            piece_tiles=piece))
+    for st in run.stats:
+        assert st["edges_processed"] == case.e and st["vertices_flushed"] == case.n
+        assert st["chunks_planned"] == st["num_chunks"]
     with pytest.raises(atlas.AtlasError) as ei:
-        atlas.atlas_set_piece_tiles(-1)
-    assert ei.value.status == atlas.E_RANGE
+        H.run_gpu(case, pinned_host=True, plan=True, piece_tiles=-1)
+    assert ei.value.status == atlas.E_BAD_DIMS
 
 
 @pytest.mark.parametrize("piece", [0, 3])
@@ -342,14 +340,12 @@ def test_pinned_plan_with_four_byte_words(oracle, H, atlas, piece):
     new_of_old, _ = oracle.reorder_indegree_desc(oracle.in_degree(g.n, col.numpy()))
     g = g.with_relabel(torch.from_numpy(new_of_old.astype(np.int64)))
     case = H.make_case("sage", g, SEED + 43, [128, 64, 64], (1 << 23) + 1, store=torch.bfloat16, feat="uniform")
-    atlas.atlas_set_piece_tiles(piece)
-    try:
-        run = H.run_gpu(case, snapshots=True, pinned_host=True, plan=True)
-        H.check_integers(oracle, case, run)
-        print("4-byte words, pieces of", piece, H.check_outputs(oracle, case, run))
-        assert run.stats[0]["bytes_copied_h2d"] >= case.e * 4 + case.n * 256
-        H.check_outputs(oracle, case, H.run_gpu(case, pinned_host=True, plan=True, planned_only=True, device_later=True))
-        H.check_outputs(oracle, case, H.run_gpu(case, pinned_host=True, plan=True, planned_only=True, plan_block=(64, 8)))
-    finally:
-        atlas.atlas_set_piece_tiles(0)
+    run = H.run_gpu(case, snapshots=True, pinned_host=True, plan=True, piece_tiles=piece)
+    H.check_integers(oracle, case, run)
+    print("4-byte words, pieces of", piece, H.check_outputs(oracle, case, run))
+    assert run.stats[0]["bytes_copied_h2d"] >= case.e * 4 + case.n * 256
+    H.check_outputs(oracle, case, H.run_gpu(case, pinned_host=True, plan=True, planned_only=True, device_later=True,
+                                            piece_tiles=piece))
+    H.check_outputs(oracle, case, H.run_gpu(case, pinned_host=True, plan=True, planned_only=True, plan_block=(64, 8),
+                                            piece_tiles=piece))
 

@@ -276,7 +276,7 @@ def test_source_blocked_plan_other_paths(oracle, H):
 @pytest.mark.parametrize("model,store", [("sage", torch.bfloat16), ("gcn", torch.float32), ("gat", torch.float32),
                                          ("gin", torch.float32)])
 def test_runs_of_consecutive_tiles(oracle, H, model, store, tiles):
-    """atlas_set_tiles_per_run: a wave keeps a destination's partial sum in
+    """dims.tiles_per_run: a wave keeps a destination's partial sum in
     registers across the tiles of a run.  Degree-ordered R-MAT scale 13 with one
     chunk of 4096 sources first, so hub groups span many runs, small groups
     straddle tile boundaries inside a run, and the last run is ragged; integer
@@ -290,23 +290,21 @@ def test_runs_of_consecutive_tiles(oracle, H, model, store, tiles):
     dims = [128, 128, 64] if model != "gat" else [128, 128, 128]
     case = H.make_case(model, g, SEED + 13, dims, 4096, store=store,
                        feat="normal" if store == torch.float32 else "uniform", heads=4 if model == "gat" else 1)
-    atlas.atlas_set_tiles_per_run(tiles)
-    try:
-        run = H.run_gpu(case, snapshots=True, plan=True)
-        H.check_integers(oracle, case, run, layer=0)
-        print("runs of", tiles, model, H.check_outputs(oracle, case, run))
-        for st in run.stats:
-            assert st["edges_processed"] == case.e and st["vertices_flushed"] == case.n
-        if model == "sage":
-            H.check_outputs(oracle, case, H.run_gpu(case, plan=True, plan_block=(128, 24)))
-            case2 = H.make_case("sage", gen.rmat_graph(SEED + 13, 12, 16, random_ids=True), SEED + 13, [128, 64], 64)
-            slots = int((np.bincount(case2.col.numpy(), minlength=case2.n) > 0).sum()) // 2
-            H.check_outputs(oracle, case2, H.run_gpu(case2, plan=True, hot_slots=slots))
-    finally:
-        atlas.atlas_set_tiles_per_run(0)
-    with pytest.raises(atlas.AtlasError) as ei:
-        atlas.atlas_set_tiles_per_run(17)
-    assert ei.value.status == atlas.E_RANGE
+    run = H.run_gpu(case, snapshots=True, plan=True, tiles_per_run=tiles)
+    H.check_integers(oracle, case, run, layer=0)
+    print("runs of", tiles, model, H.check_outputs(oracle, case, run))
+    for st in run.stats:
+        assert st["edges_processed"] == case.e and st["vertices_flushed"] == case.n
+        assert st["chunks_planned"] == st["num_chunks"] and st["chunks_csr_stream"] == 0
+    if model == "sage":
+        H.check_outputs(oracle, case, H.run_gpu(case, plan=True, plan_block=(128, 24), tiles_per_run=tiles))
+        case2 = H.make_case("sage", gen.rmat_graph(SEED + 13, 12, 16, random_ids=True), SEED + 13, [128, 64], 64)
+        slots = int((np.bincount(case2.col.numpy(), minlength=case2.n) > 0).sum()) // 2
+        H.check_outputs(oracle, case2, H.run_gpu(case2, plan=True, hot_slots=slots, tiles_per_run=tiles))
+    for bad in (17, -1):
+        with pytest.raises(atlas.AtlasError) as ei:
+            H.run_gpu(case, plan=True, tiles_per_run=bad)
+        assert ei.value.status == atlas.E_BAD_DIMS
 
 
 def test_long_launch_with_ticketed_runs(oracle, H):
@@ -320,16 +318,12 @@ def test_long_launch_with_ticketed_runs(oracle, H):
     new_of_old, _ = oracle.reorder_indegree_desc(oracle.in_degree(g.n, col.numpy()))
     g = g.with_relabel(torch.from_numpy(new_of_old.astype(np.int64)))
     case = H.make_case("sage", g, SEED + 29, [64, 64, 16], (1 << 18) - 4097, store=torch.bfloat16, feat="uniform")
-    atlas.atlas_set_tiles_per_run(8)
-    try:
-        run = H.run_gpu(case, snapshots=True, plan=True, planned_only=True)
-        H.check_integers(oracle, case, run, layer=0)
-        H.check_integers(oracle, case, run, layer=1)
-        print("ticketed runs", H.check_outputs(oracle, case, run))
-        run = H.run_gpu(case, plan=True, plan_block=(4096, 64), pinned_host=True, device_later=True)
-        print("ticketed runs, blocked plan, pinned host", H.check_outputs(oracle, case, run))
-    finally:
-        atlas.atlas_set_tiles_per_run(0)
+    run = H.run_gpu(case, snapshots=True, plan=True, planned_only=True, tiles_per_run=8)
+    H.check_integers(oracle, case, run, layer=0)
+    H.check_integers(oracle, case, run, layer=1)
+    print("ticketed runs", H.check_outputs(oracle, case, run))
+    run = H.run_gpu(case, plan=True, plan_block=(4096, 64), pinned_host=True, device_later=True, tiles_per_run=8)
+    print("ticketed runs, blocked plan, pinned host", H.check_outputs(oracle, case, run))
 
 
 @pytest.mark.parametrize("model,store,dims", [

@@ -129,14 +129,9 @@ def test_random_configuration(oracle, H, idx):
     case, opts, knobs = _draw(rng, oracle, H, idx)
     print("config %d: %s %s n=%d e=%d dims=%s chunk=%d %s %s" % (idx, case.model, case.store, case.n, case.e, case.dims,
                                                                 case.chunk, opts, knobs), flush=True)
-    atlas.atlas_set_tiles_per_run(knobs["run"])
-    atlas.atlas_set_piece_tiles(knobs["piece"])
-    try:
-        run = H.run_gpu(case, **opts)
-        print("  errors", H.check_outputs(oracle, case, run), flush=True)
-        for st in run.stats:
-            assert st["edges_processed"] == case.e and st["vertices_flushed"] == case.n
-            assert st["vertices_completed"] == case.n and st["sources_processed"] == case.n
-    finally:
-        atlas.atlas_set_tiles_per_run(0)
-        atlas.atlas_set_piece_tiles(0)
+    run = H.run_gpu(case, tiles_per_run=knobs["run"], piece_tiles=knobs["piece"], **opts)
+    print("  errors", H.check_outputs(oracle, case, run), flush=True)
+    for st in run.stats:
+        assert st["edges_processed"] == case.e and st["vertices_flushed"] == case.n
+        assert st["vertices_completed"] == case.n and st["sources_processed"] == case.n
+        assert st["chunks_planned"] + st["chunks_csr_stream"] == st["num_chunks"]
