@@ -57,7 +57,8 @@ enum atlas_status {
     ATLAS_E_OVERFLOW = -6,   /* N >= 2^31 (vertex ids and counts are int32)                 */
     ATLAS_E_HIP = -7,        /* a HIP call failed; see atlas_last_hip_error()               */
     ATLAS_E_NOMEM = -8,      /* device or host allocation failed                            */
-    ATLAS_E_STATE = -9       /* call not valid in the layer's current state                 */
+    ATLAS_E_STATE = -9,      /* call not valid in the layer's current state                 */
+    ATLAS_E_TOO_LARGE = -10  /* input exceeds the fixed scratch of a no-allocation entry point */
 };
 
 enum atlas_residency { ATLAS_RESIDENT_DEVICE = 0, ATLAS_RESIDENT_PINNED_HOST = 1 };
@@ -326,6 +327,22 @@ int atlas_in_degree(const atlas_graph_t *graph, int32_t *in_degree, void *hip_st
  * Synchronous. */
 int atlas_reorder_indegree_desc(const atlas_graph_t *graph, int32_t *new_of_old,
                                 int32_t *old_of_new);
+
+/* atlas_reorder_indegree_desc for callers that cannot allocate device memory (tight serving
+ * loops that re-order a small graph per request, harnesses that forbid hipMalloc): the same
+ * permutation, bit for bit, computed without any allocation.  The sort's scratch (sorted keys,
+ * ids, workspace) lies in a fixed 24 MiB array in device memory that every GPU the library runs
+ * on holds until the process ends; inputs and outputs are the caller's as above.
+ * num_vertices <= ATLAS_NOALLOC_MAX_VERTICES, else E_TOO_LARGE and nothing is launched.
+ * Enqueues on hip_stream (NULL = default stream) and returns without waiting; the outputs are
+ * complete when the stream has passed this point.  All calls on one GPU share that GPU's
+ * scratch: calls that overlap on one GPU (two streams, two threads) race; calls on one stream
+ * are ordered and need no clearing in between (every scratch word is written before it is
+ * read).  The library sort it uses clears its counters with asynchronous memsets, so the call
+ * is not meant for stream capture.  Errors: E_NULL, E_RANGE, E_TOO_LARGE, E_HIP. */
+#define ATLAS_NOALLOC_MAX_VERTICES (1 << 20)
+int atlas_reorder_indegree_desc_noalloc(const atlas_graph_t *graph, int32_t *new_of_old, int32_t *old_of_new,
+                                        void *hip_stream);
 
 /* The paper's greedy ordering (Sec. 3.8): vertices by decreasing
  * Score(u) = (sum_{v in Out(u)} 1/d_in(v)) / d_out(u) (0 without out-edges),

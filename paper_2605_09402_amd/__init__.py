@@ -15,7 +15,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libatlas.so")
 
 OK = 0
-E_NULL, E_BAD_DIMS, E_RANGE, E_ORDER, E_INCOMPLETE, E_OVERFLOW, E_HIP, E_NOMEM, E_STATE = range(-1, -10, -1)
+E_NULL, E_BAD_DIMS, E_RANGE, E_ORDER, E_INCOMPLETE, E_OVERFLOW, E_HIP, E_NOMEM, E_STATE, E_TOO_LARGE = range(-1, -11, -1)
+NOALLOC_MAX_VERTICES = 1 << 20
 RESIDENT_DEVICE, RESIDENT_PINNED_HOST = 0, 1
 MODEL_SAGE_MEAN, MODEL_GCN_SYM, MODEL_GAT, MODEL_GIN, MODEL_SGC_HOP = 0, 1, 2, 3, 4
 DTYPE_F32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
@@ -32,6 +33,7 @@ EXPORTS = [
     "atlas_layer_finish", "atlas_in_degree", "atlas_reorder_indegree_desc", "atlas_debug_copy",
     "atlas_release_cache", "atlas_strerror", "atlas_last_hip_error", "atlas_plan_create", "atlas_plan_destroy",
     "atlas_reorder_score_desc", "atlas_sample_in_edges", "atlas_plan_create_blocked",
+    "atlas_reorder_indegree_desc_noalloc",
 ]
 
 
@@ -99,6 +101,7 @@ def lib() -> ctypes.CDLL:
         L.atlas_layer_finish.argtypes = [vp, ctypes.POINTER(atlas_layer_stats_t)]
         L.atlas_in_degree.argtypes = [ctypes.POINTER(atlas_graph_t), vp, vp]
         L.atlas_reorder_indegree_desc.argtypes = [ctypes.POINTER(atlas_graph_t), vp, vp]
+        L.atlas_reorder_indegree_desc_noalloc.argtypes = [ctypes.POINTER(atlas_graph_t), vp, vp, vp]
         L.atlas_reorder_score_desc.argtypes = [ctypes.POINTER(atlas_graph_t), vp, vp]
         L.atlas_sample_in_edges.argtypes = [ctypes.POINTER(atlas_graph_t), vp, i32, vp, vp, ctypes.POINTER(i64)]
         L.atlas_debug_copy.argtypes = [vp, i32, vp, i64]
@@ -219,6 +222,11 @@ def atlas_in_degree(graph: atlas_graph_t, in_degree, stream=None) -> None:
 def atlas_reorder_indegree_desc(graph: atlas_graph_t, new_of_old, old_of_new) -> None:
     _check(lib().atlas_reorder_indegree_desc(ctypes.byref(graph), _ptr(new_of_old), _ptr(old_of_new)),
            "atlas_reorder_indegree_desc")
+
+
+def atlas_reorder_indegree_desc_noalloc(graph: atlas_graph_t, new_of_old, old_of_new, stream=None) -> None:
+    _check(lib().atlas_reorder_indegree_desc_noalloc(ctypes.byref(graph), _ptr(new_of_old), _ptr(old_of_new),
+                                                     _stream(stream)), "atlas_reorder_indegree_desc_noalloc")
 
 
 def atlas_reorder_score_desc(graph: atlas_graph_t, new_of_old, old_of_new) -> None:

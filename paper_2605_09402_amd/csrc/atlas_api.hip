@@ -1234,6 +1234,18 @@ int atlas_reorder_indegree_desc(const atlas_graph_t *graph, int32_t *new_of_old,
     return ATLAS_OK;
 }
 
+int atlas_reorder_indegree_desc_noalloc(const atlas_graph_t *graph, int32_t *new_of_old, int32_t *old_of_new,
+                                        void *hip_stream) {
+    if (!graph || !new_of_old || !old_of_new || !graph->in_degree) return ATLAS_E_NULL;
+    if (graph->num_vertices < 0) return ATLAS_E_RANGE;
+    static_assert(atlas::kNoAllocMaxVertices == ATLAS_NOALLOC_MAX_VERTICES, "header and kernel limit differ");
+    if (graph->num_vertices > ATLAS_NOALLOC_MAX_VERTICES) return ATLAS_E_TOO_LARGE;
+    bool too_large = false;
+    HIP_TRY(reorder_indegree_desc_noalloc(graph->in_degree, graph->num_vertices, new_of_old, old_of_new,
+                                          static_cast<hipStream_t>(hip_stream), &too_large));
+    return too_large ? ATLAS_E_TOO_LARGE : ATLAS_OK;
+}
+
 int atlas_reorder_score_desc(const atlas_graph_t *graph, int32_t *new_of_old, int32_t *old_of_new) {
     if (!graph || !new_of_old || !old_of_new || !graph->in_degree || !graph->row_offsets) return ATLAS_E_NULL;
     if (graph->num_edges > 0 && !graph->col_indices) return ATLAS_E_NULL;
@@ -1326,6 +1338,7 @@ const char *atlas_strerror(int status) {
         case ATLAS_E_HIP: return "HIP call failed";
         case ATLAS_E_NOMEM: return "out of memory";
         case ATLAS_E_STATE: return "call not valid in this state";
+        case ATLAS_E_TOO_LARGE: return "input exceeds the fixed scratch of the no-allocation entry point";
         default: return "unknown status";
     }
 }

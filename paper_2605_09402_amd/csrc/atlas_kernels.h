@@ -281,6 +281,12 @@ hipError_t launch_advance_head(int32_t *counters, hipStream_t s);
 // Degree ordering.
 hipError_t reorder_indegree_desc(const int32_t *indeg, int64_t n, int32_t *new_of_old,
                                  int32_t *old_of_new);
+// The same order computed without any allocation, out of a fixed scratch array in device memory; enqueues
+// on `s` and does not wait.  *too_large is set (and nothing is launched) when n exceeds
+// kNoAllocMaxVertices or the sort's workspace would not fit the scratch.
+constexpr int64_t kNoAllocMaxVertices = int64_t(1) << 20;
+hipError_t reorder_indegree_desc_noalloc(const int32_t *indeg, int64_t n, int32_t *new_of_old, int32_t *old_of_new,
+                                         hipStream_t s, bool *too_large);
 hipError_t reorder_score_desc(const int64_t *off, const int32_t *col, const int32_t *indeg, int64_t n,
                               int32_t *new_of_old, int32_t *old_of_new);
 
