@@ -3,19 +3,28 @@
 
 One "step" is one whole layer of the large GraphSAGE-mean workload (R-MAT
 scale 26, edge factor 32, bf16 features of width 128, degree-ordered ids,
-16 chunks of 2^22 sources): layer init (pending counts, zeroed accumulators),
-all chunk broadcasts (scatter-aggregate + pending decrement + ready
-compaction), a flush (MFMA update) after every chunk, and the exactly-once
-check.  Inputs are resident in HBM before the timed region starts.
+16 chunks of 2^22 sources): layer init (pending counts), all chunk broadcasts
+(scatter-aggregate + pending decrement + ready compaction), a flush (MFMA
+update) after every chunk, and the exactly-once check.
 
-Prints ONE JSON line.  `value` is aggregated edges per second of the layer;
-`roofline` describes the scatter-aggregate kernel (HIP-event time summed over
-its launches inside the timed steps); `cpu_baseline` is the CPU oracle timed on
-a bounded sample of the same layer.
+The layer is timed in two executions, both in the one JSON line:
+
+  * inputs resident in HBM before the timed region starts: `value`,
+    `ms_per_step`, `roofline` (the scatter-aggregate kernel, HIP-event time
+    summed over its launches inside the timed steps) and `update`;
+  * as the workload's configuration states it -- CSR and features in pinned
+    host memory, streamed chunk by chunk on the library's copy stream while the
+    previous chunk's kernels run: `config5_as_stated` (host-link bound).
+
+`prep_ms` is the one-time, per-graph preparation (in-degree, ordering, plan)
+that every layer and every run on the graph reuses; `measured_peak` is what
+bare kernels of the same access patterns reach on the box at hand;
+`cpu_baseline` is the CPU oracle timed on a bounded sample of the same layer.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -24,6 +33,8 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
 
 
 def cpu_model() -> str:
@@ -34,6 +45,15 @@ def cpu_model() -> str:
     except OSError:
         pass
     return "unknown"
+
+
+def kernel_source_hash() -> str:
+    """Identifies the kernels the committed HBM counter summary was taken with."""
+    h = hashlib.sha256()
+    for name in ("k_aggregate.hip", "k_update.hip"):
+        with open(os.path.join(ROOT, "paper_2605_09402_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
 
 
 def log(*a):
@@ -75,11 +95,12 @@ def main() -> int:
     ap.add_argument("--side-stream", action="store_true", help="run on a non-default stream")
     ap.add_argument("--sync-chunks", action="store_true",
                     help="wait for the device after every chunk (no copy / compute overlap): times the stages alone")
-    ap.add_argument("--no-e2e", action="store_true", help="skip the three-layer end-to-end run")
+    ap.add_argument("--no-e2e", action="store_true", help="skip the three-layer end-to-end runs")
     ap.add_argument("--sample-dst", type=int, default=1 << 16, help="destinations in the oracle sample")
-    ap.add_argument("--residency", choices=["device", "pinned"], default="device",
-                    help="pinned: graph and features stay in pinned host memory and are streamed per chunk "
-                         "(host-link bound; reported for the record, never the headline value)")
+    ap.add_argument("--residency", choices=["both", "device", "pinned"], default="both",
+                    help="which executions to time: inputs resident in HBM, streamed from pinned host memory, or "
+                         "both (default)")
+    ap.add_argument("--no-measured-peak", action="store_true", help="skip the bare copy / gather / MFMA probes")
     ap.add_argument("--order", choices=["indegree", "score", "original"], default="indegree",
                     help="vertex ids: in-degree descending (the workload's), the paper's greedy Score order, "
                          "or the generator's raw ids")
@@ -96,7 +117,7 @@ def main() -> int:
     import torch
 
     import paper_2605_09402_amd as atlas
-    from gen import in_edges_of, workloads
+    from gen import sample_subgraph, workloads
 
     atlas.lib()  # fail loudly if the HIP library is missing
     if not torch.cuda.is_available():
@@ -105,18 +126,28 @@ def main() -> int:
     dev = torch.device("cuda:0")
     stream = torch.cuda.current_stream()
 
-    # ---- inputs (outside the timed region) ----
+    def timed_ms(fn):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        r = fn()
+        torch.cuda.synchronize()
+        return r, (time.perf_counter() - t) * 1e3
+
+    # ---- inputs (outside the timed region); the per-graph preparation is timed step by step ----
+    prep = {"in_degree_raw_ids": None, "reorder": None, "in_degree": None, "plan": None, "plan_pinned_host": None}
+
     def reorder(off, col):
         n = off.numel() - 1
         indeg = torch.empty(n, dtype=torch.int32, device=dev)
-        atlas.atlas_in_degree(atlas.make_graph(n, col.numel(), off, col), indeg)
+        _, prep["in_degree_raw_ids"] = timed_ms(
+            lambda: atlas.atlas_in_degree(atlas.make_graph(n, col.numel(), off, col), indeg))
         new_of_old = torch.empty(n, dtype=torch.int32, device=dev)
         old_of_new = torch.empty(n, dtype=torch.int32, device=dev)
         g = atlas.make_graph(n, col.numel(), off, col, indeg)
         if args.order == "score":
-            atlas.atlas_reorder_score_desc(g, new_of_old, old_of_new)
+            _, prep["reorder"] = timed_ms(lambda: atlas.atlas_reorder_score_desc(g, new_of_old, old_of_new))
         else:
-            atlas.atlas_reorder_indegree_desc(g, new_of_old, old_of_new)
+            _, prep["reorder"] = timed_ms(lambda: atlas.atlas_reorder_indegree_desc(g, new_of_old, old_of_new))
         return new_of_old
 
     t0 = time.time()
@@ -142,14 +173,14 @@ def main() -> int:
     n, e, chunk = wl.n, wl.e, wl.chunk
     log("generated %s: N=%d E=%d chunk=%d in %.1f s" % (wl.name, n, e, chunk, time.time() - t0))
     indeg = torch.empty(n, dtype=torch.int32, device=dev)
-    atlas.atlas_in_degree(atlas.make_graph(n, e, wl.off, wl.col), indeg)
-    torch.cuda.synchronize()
+    _, prep["in_degree"] = timed_ms(lambda: atlas.atlas_in_degree(atlas.make_graph(n, e, wl.off, wl.col), indeg))
     torch.cuda.empty_cache()
+    do_device = args.residency in ("both", "device")
+    do_pinned = args.residency in ("both", "pinned")
 
     plan = None
-    plan_ms = None
-    if not args.no_plan and args.residency == "device":
-        t0 = time.time()
+    plan_info = None
+    if not args.no_plan and do_device:
         pg = atlas.make_graph(n, e, wl.off, wl.col)
         if args.plan_block_log2 < 0:   # default: 2 MiB of source rows per block on the large workload
             row_bytes = wl.dims[0] * (2 if wl.store != torch.float32 else 4)
@@ -159,24 +190,14 @@ def main() -> int:
         if args.plan_block_log2 > 0 and chunk <= (1 << args.plan_block_log2):
             args.plan_block_log2 = 0   # a chunk of one block: nothing to reorder
         if args.plan_block_log2 > 0:
-            plan = atlas.atlas_plan_create_blocked(pg, chunk, 1 << args.plan_block_log2, args.plan_hot_min)
+            plan, prep["plan"] = timed_ms(
+                lambda: atlas.atlas_plan_create_blocked(pg, chunk, 1 << args.plan_block_log2, args.plan_hot_min))
         else:
-            plan = atlas.atlas_plan_create(pg, chunk)
-        plan_ms = (time.time() - t0) * 1e3
-        log("plan built in %.1f ms" % plan_ms)
-    graph = atlas.make_graph(n, e, wl.off, wl.col, indeg, atlas.RESIDENT_DEVICE, plan)
-    x_layer0 = wl.X
-    if args.residency == "pinned":
-        t0 = time.time()
-        off_h = torch.empty(wl.off.shape, dtype=wl.off.dtype, pin_memory=True).copy_(wl.off)
-        col_h = torch.empty(wl.col.shape, dtype=wl.col.dtype, pin_memory=True).copy_(wl.col)
-        x_layer0 = torch.empty(wl.X.shape, dtype=wl.X.dtype, pin_memory=True).copy_(wl.X)
-        if not args.no_plan:
-            t1 = time.time()
-            plan = atlas.atlas_plan_create(atlas.make_graph(n, e, off_h, col_h, None, atlas.RESIDENT_PINNED_HOST), chunk)
-            plan_ms = (time.time() - t1) * 1e3
-        graph = atlas.make_graph(n, e, off_h, col_h, indeg, atlas.RESIDENT_PINNED_HOST, plan)
-        log("pinned host copies made in %.1f s" % (time.time() - t0))
+            plan, prep["plan"] = timed_ms(lambda: atlas.atlas_plan_create(pg, chunk))
+        plan_info = atlas.atlas_plan_info(plan)
+        log("plan built in %.1f ms: %d groups, %.2f GB" % (prep["plan"], plan_info["num_groups"],
+                                                            plan_info["bytes_device"] / 1e9))
+    graph_dev = atlas.make_graph(n, e, wl.off, wl.col, indeg, atlas.RESIDENT_DEVICE, plan)
 
     params = []
     for p in wl.layers:
@@ -201,12 +222,12 @@ def main() -> int:
 
     chunk_wall_ms = []   # --sync-chunks: wall time of every chunk (copy + kernels), all layers run so far
 
-    def run_layer(li: int, x: torch.Tensor, timing: bool) -> dict:
+    def run_layer(graph, planned: bool, li: int, x: torch.Tensor, timing: bool) -> dict:
         d_in, d_out = wl.dims[li], wl.dims[li + 1]
         act = atlas.ACT_NONE if li + 1 == len(wl.layers) else between
         dims = atlas.make_dims(model_id, d_in, d_out, sdt, sdt, act, chunk, heads=wl.heads,
                                flags=(atlas.FLAG_TIMING if timing else 0) | atlas.FLAG_EMB_RESIDENT |
-                               (atlas.FLAG_PLANNED_ONLY if plan is not None else 0) |
+                               (atlas.FLAG_PLANNED_ONLY if planned else 0) |
                                (atlas.FLAG_TRANSFORM_FIRST if args.transform_first else 0),
                                hot_slots=hot_slots, evict_policy=1 if args.evict_policy == "max" else 0)
         W, b = params[li]
@@ -224,7 +245,9 @@ def main() -> int:
             if args.sync_chunks:
                 torch.cuda.synchronize()
                 chunk_wall_ms.append((time.perf_counter() - tc) * 1e3)
-        return atlas.atlas_layer_finish(h)
+        st = atlas.atlas_layer_finish(h)
+        assert st["chunks_planned"] == (st["num_chunks"] if planned else 0), "a chunk left the planned path"
+        return st
 
     if args.traffic_calibration:
         # a plain copy of known size: 4 GiB read + 4 GiB written per launch
@@ -243,92 +266,133 @@ def main() -> int:
         stream = torch.cuda.Stream()
         torch.cuda.set_stream(stream)
 
-    # ---- warm-up, then exactly K timed steps ----
-    for _ in range(args.warmup):
-        run_layer(0, x_layer0, True)
-    torch.cuda.synchronize()
-    agg_ms = upd_ms = self_ms = init_ms = copy_ms = 0.0
-    h2d_bytes = 0
-    step_ms = []          # per step: atlas_layer_finish waits for the layer, so each step ends synchronised
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        ts = time.perf_counter()
-        st = run_layer(0, x_layer0, True)
-        step_ms.append((time.perf_counter() - ts) * 1e3)
-        agg_ms += st["ms_aggregate"]
-        copy_ms += st["ms_copy"]
-        h2d_bytes = st["bytes_copied_h2d"]
-        upd_ms += st["ms_update"]
-        self_ms += st["ms_self"]
-        init_ms += st["ms_init"]
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
     nchunks = (n + chunk - 1) // chunk
-    launches = nchunks * args.steps
-    log("layer: %.2f ms/step; aggregate %.2f, update %.2f, self %.2f, init %.2f ms per step"
-        % (ms_per_step, agg_ms / args.steps, upd_ms / args.steps, self_ms / args.steps, init_ms / args.steps))
-    if args.sync_chunks:
-        log("last layer, ms per chunk (copy + kernels, no overlap): " + " ".join("%.1f" % v for v in chunk_wall_ms[-nchunks:]))
-    if copy_ms > 0:
-        log("chunk loader: %.1f GB per layer in %.1f ms on the copy stream = %.1f GB/s"
-            % (h2d_bytes / 1e9, copy_ms / args.steps, h2d_bytes / (copy_ms / args.steps) / 1e6))
 
-    # ---- end-to-end: all three layers once ----
-    e2e_ms = None
-    layer_ms = []
-    if not args.no_e2e:
-        # pinned residency: layer 1 streams features and edges from the host, the later layers read the
-        # previous layer's output in HBM and stream the edges only
+    def time_layers(graph, planned, x0):
+        """W warm-up steps, then exactly K timed steps of layer 1; then all layers once."""
+        for _ in range(args.warmup):
+            run_layer(graph, planned, 0, x0, True)
         torch.cuda.synchronize()
+        acc = {"ms_aggregate": 0.0, "ms_update": 0.0, "ms_self": 0.0, "ms_init": 0.0, "ms_copy": 0.0}
+        step_ms = []   # atlas_layer_finish waits for the layer, so each step ends synchronised
         t0 = time.perf_counter()
-        x = x_layer0
-        for li in range(len(wl.layers)):
-            t1 = time.perf_counter()
-            run_layer(li, x, False)
-            layer_ms.append((time.perf_counter() - t1) * 1e3)
-            x = outs[li]
+        st = None
+        for _ in range(args.steps):
+            ts = time.perf_counter()
+            st = run_layer(graph, planned, 0, x0, True)
+            step_ms.append((time.perf_counter() - ts) * 1e3)
+            for k in acc:
+                acc[k] += st[k]
         torch.cuda.synchronize()
-        e2e_ms = (time.perf_counter() - t0) * 1e3
-        log("end-to-end all layers: %.1f ms (%s)" % (e2e_ms, ", ".join("%.1f" % v for v in layer_ms)))
+        wall = time.perf_counter() - t0
+        res = {"ms_per_step": wall * 1e3 / args.steps, "step_ms": step_ms, "last_stats": st,
+               "per_step": {k: v / args.steps for k, v in acc.items()}, "e2e_ms": None, "layer_ms": []}
+        if not args.no_e2e:
+            # later layers read the previous layer's output where it lies in HBM (a pinned-host graph then
+            # streams its edges only)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            x = x0
+            for li in range(len(wl.layers)):
+                t1 = time.perf_counter()
+                run_layer(graph, planned, li, x, False)
+                res["layer_ms"].append((time.perf_counter() - t1) * 1e3)
+                x = outs[li]
+            torch.cuda.synchronize()
+            res["e2e_ms"] = (time.perf_counter() - t0) * 1e3
+        return res
+
+    # ---- inputs resident in HBM ----
+    dev_res = None
+    if do_device:
+        dev_res = time_layers(graph_dev, plan is not None, wl.X)
+        ps = dev_res["per_step"]
+        log("HBM-resident layer: %.2f ms/step; aggregate %.2f, update %.2f, self %.2f, init %.2f ms per step"
+            % (dev_res["ms_per_step"], ps["ms_aggregate"], ps["ms_update"], ps["ms_self"], ps["ms_init"]))
+        if args.sync_chunks:
+            log("last layer, ms per chunk (kernels, no overlap): " + " ".join("%.1f" % v for v in chunk_wall_ms[-nchunks:]))
+        if dev_res["e2e_ms"] is not None:
+            log("end-to-end all layers: %.1f ms (%s)" % (dev_res["e2e_ms"], ", ".join("%.1f" % v for v in dev_res["layer_ms"])))
+
+    # ---- as stated: CSR and features in pinned host memory, streamed per chunk ----
+    pin_res = None
+    plan_host = None
+    if do_pinned:
+        t0 = time.time()
+        off_h = torch.empty(wl.off.shape, dtype=wl.off.dtype, pin_memory=True).copy_(wl.off)
+        col_h = torch.empty(wl.col.shape, dtype=wl.col.dtype, pin_memory=True).copy_(wl.col)
+        x_h = torch.empty(wl.X.shape, dtype=wl.X.dtype, pin_memory=True).copy_(wl.X)
+        log("pinned host copies made in %.1f s" % (time.time() - t0))
+        if not args.no_plan:
+            plan_host, prep["plan_pinned_host"] = timed_ms(lambda: atlas.atlas_plan_create(
+                atlas.make_graph(n, e, off_h, col_h, None, atlas.RESIDENT_PINNED_HOST), chunk))
+        graph_pin = atlas.make_graph(n, e, off_h, col_h, indeg, atlas.RESIDENT_PINNED_HOST, plan_host)
+        pin_res = time_layers(graph_pin, plan_host is not None, x_h)
+        ps = pin_res["per_step"]
+        h2d = pin_res["last_stats"]["bytes_copied_h2d"]
+        log("pinned-host layer: %.2f ms/step; %.1f GB per layer in %.1f ms on the copy stream = %.1f GB/s"
+            % (pin_res["ms_per_step"], h2d / 1e9, ps["ms_copy"], h2d / max(ps["ms_copy"], 1e-9) / 1e6))
+        if pin_res["e2e_ms"] is not None:
+            log("end-to-end all layers: %.1f ms (%s)" % (pin_res["e2e_ms"], ", ".join("%.1f" % v for v in pin_res["layer_ms"])))
+
+    main_res = dev_res if dev_res is not None else pin_res
+    ms_per_step = main_res["ms_per_step"]
+    step_ms = main_res["step_ms"]
+    ps = main_res["per_step"]
 
     # ---- roofline of the scatter-aggregate kernel ----
-    d = wl.dims[1] if wl.model == "gat" else wl.dims[0]   # width of the accumulated row
+    d = wl.dims[1] if wl.model == "gat" or args.transform_first else wl.dims[0]   # width of the accumulated row
     s_in = 4 if wl.model == "gat" or wl.store == torch.float32 else 2
-    bytes_per_edge = 4 + 2 * 4 * d + 8          # destination id, fp32 row read + write, pending RMW
-    bytes_per_source = d * s_in + 8             # source row, row offset
-    algo_bytes_layer = e * bytes_per_edge + n * bytes_per_source
-    agg_s_per_layer = agg_ms / args.steps / 1e3
+    agg_s_per_layer = ps["ms_aggregate"] / 1e3
+    n_with_in = int((indeg > 0).sum().item())
+    launches = nchunks * args.steps
+    kname = "k_aggregate_grouped" if (plan or plan_host) else "k_aggregate"
+    if plan_info is not None:
+        # What the planned kernel itself must move: per edge its 4-byte edge word and one source row; per
+        # (chunk, destination) group the group's destination word, a pending-count read-modify-write and the
+        # accumulator row -- written only by a destination's first group, read and written by every later one;
+        # per 64-edge tile its first-group index.
+        G, G1 = plan_info["num_groups"], plan_info["num_first_groups"]
+        algo_bytes_layer = e * (4 + d * s_in) + G * (4 + 8) + (2 * G - G1) * 4 * d + ((e + 63) // 64) * 4
+        algo_note = ("edge word + source row per edge; destination word, pending RMW and fp32 row "
+                     "(store for a first group, read + write otherwise) per group; tile index per 64 edges")
+    else:
+        # CSR stream with atomics: destination id, fp32 row read-modify-write and pending RMW per edge
+        algo_bytes_layer = e * (4 + 2 * 4 * d + 8) + n * (d * s_in + 8)
+        algo_note = "streaming model: per edge destination id + fp32 row RMW + pending RMW, per source its row + offset"
     achieved = algo_bytes_layer / agg_s_per_layer / 1e9
-    peak = 8000.0
-    # bytes the regrouped kernel itself must move (source id + bf16 source row per edge)
-    kernel_bytes_per_edge = 4 + d * s_in
-    # HBM bytes per launch from the committed counter summary; null when the
-    # kernels changed after the counters were taken (or for another workload)
+    # Two reference figures beside it: the streaming model (a destination row RMW per edge, which the planned kernel
+    # does not do: reported as an effective rate, never as a fraction) and the compulsory lower bound (every edge
+    # word, source row and accumulator row crossing the memory interface once)
+    streaming_bytes = e * (4 + 2 * 4 * d + 8) + n * (d * s_in + 8)
+    compulsory_bytes = 4 * e + n * d * s_in + 2 * n * d * 4 + 8 * n
     traffic = None
-    kname = "k_aggregate_grouped" if plan else "k_aggregate"
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic_config5_rmat26.json")
-    if os.path.exists(tpath) and is_headline and args.order == "indegree" and args.residency == "device":
-        from paper_2605_09402_amd.profile_summary import kernel_source_hash
+    if os.path.exists(tpath) and is_headline and args.order == "indegree" and dev_res is not None:
         doc = json.load(open(tpath))
         if doc.get("kernel_source_hash") == kernel_source_hash() and kname in doc["kernels"]:
             traffic = doc["kernels"][kname]["bytes_per_launch"]
     roofline = {
         "bound": "hbm", "kernel": kname,
-        "achieved": round(achieved, 1), "peak": peak, "unit": "GB/s", "frac": round(achieved / peak, 4),
+        "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBPS, 4),
+        "algorithmic_bytes_per_launch": int(algo_bytes_layer / nchunks), "algorithmic_bytes": algo_note,
+        # HBM bytes per launch from the committed rocprofv3 counter summary; null once the kernels have changed
         "traffic": traffic,
         "traffic_GBps": None if traffic is None else round(traffic * nchunks / agg_s_per_layer / 1e9, 1),
-        # measured HBM bytes per second over the peak: what the kernel really draws from memory
-        "traffic_frac_of_peak": None if traffic is None else round(traffic * nchunks / agg_s_per_layer / 1e9 / peak, 4),
-        "launches": launches, "avg_launch_ms": round(agg_ms / launches, 4),
-        "algorithmic_bytes_per_edge": bytes_per_edge, "algorithmic_bytes_per_source": bytes_per_source,
+        "traffic_frac_of_peak": None if traffic is None else round(traffic * nchunks / agg_s_per_layer / 1e9 / HBM_PEAK_GBPS, 4),
+        "traffic_over_algorithmic": None if traffic is None else round(traffic * nchunks / algo_bytes_layer, 3),
+        "compulsory_bytes_per_layer": compulsory_bytes,
+        "traffic_over_compulsory": None if traffic is None else round(traffic * nchunks / compulsory_bytes, 2),
+        "streaming_model_effective_GBps": round(streaming_bytes / agg_s_per_layer / 1e9, 1),
+        "launches": launches, "avg_launch_ms": round(ps["ms_aggregate"] / nchunks, 4),
         "edges_per_s_in_kernel": round(e / agg_s_per_layer, 1),
-        "per_edge_reads_only_GBps": round(e * kernel_bytes_per_edge / agg_s_per_layer / 1e9, 1),
     }
+    if roofline["frac"] > 1.0:
+        log("note: the kernel's algorithmic bytes per second exceed the HBM peak (rows served from cache)")
     K = 2 * wl.dims[0] if wl.model == "sage" else wl.dims[0]
-    n_with_in = int((indeg > 0).sum().item())
     upd_flops = 2.0 * n * K * wl.dims[1]      # SAGE / GCN: the flush GEMM; GAT: the per-chunk transform (in ms_self)
-    upd_s = upd_ms / args.steps / 1e3
+    upd_s = ps["ms_update"] / 1e3
     upd_bytes = n_with_in * 4 * d + n * ((s_in * d if wl.model in ("sage", "gin") else 0) + s_in * wl.dims[1])
     mfma_peak = 2.5e15 if sdt in (atlas.DTYPE_BF16, atlas.DTYPE_F16) else 157.3e12
     # the contraction's ceiling at this shape: the MFMA peak, or its flops in the time its bytes need at the HBM peak
@@ -342,8 +406,62 @@ def main() -> int:
         "ceiling_tflops": round(upd_ceiling / 1e12, 1),
         "frac_of_ceiling": round(upd_flops / upd_s / upd_ceiling, 4),
         "rows_with_in_edges": n_with_in,
-        "ms_per_layer": round(upd_ms / args.steps, 3),
+        "ms_per_layer": round(ps["ms_update"], 3),
     }
+
+    # ---- measured peaks: bare kernels of the same access patterns on this machine ----
+    measured = None
+    if not args.no_measured_peak:
+        def ev_ms(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps
+        cbytes = 4 << 30
+        ca = torch.empty(cbytes // 4, dtype=torch.int32, device=dev).fill_(1)
+        cb = torch.empty_like(ca)
+        copy_ms = ev_ms(lambda: atlas.atlas_probe_copy(cb, ca, cbytes), 5)
+        del cb
+        # 2^27 random rows of 256 bytes out of a 1 GiB table (the size of one chunk's bf16 rows)
+        table_rows, n_ids = 1 << 22, 1 << 27
+        ids = torch.randint(0, table_rows, (n_ids,), dtype=torch.int32, device=dev)
+        sink = torch.empty(atlas.atlas_probe_gather_sink_bytes() // 4, dtype=torch.int32, device=dev)
+        gather_ms = ev_ms(lambda: atlas.atlas_probe_row_gather(ca, table_rows, ids, n_ids, sink), 3)
+        del ids, ca
+        mf = {}
+        if sdt != atlas.DTYPE_F32:
+            # the contraction on a block of rows small enough to stay in the memory-side cache, many passes:
+            # the flush's shape (K = 2 d_in -> d_out) and the wide first-layer transform (K = 1024 -> 256)
+            for label, rows_n, kk, dd in (("flush_shape", 1 << 16, K, wl.dims[1]), ("wide_transform", 1 << 15, 1024, 256)):
+                if kk > 1024 or dd > 256 or dd % 32 or kk % 64:
+                    continue
+                rows = (torch.rand((rows_n, kk), device=dev) - 0.5).to(wl.store)
+                Wp = (torch.rand((kk, dd), device=dev) - 0.5).to(wl.store)
+                po = torch.empty((rows_n, dd), dtype=wl.store, device=dev)
+                reps = 40
+                atlas.atlas_probe_dense_rows(sdt, rows, rows_n, kk, dd, Wp, po, 2)
+                t_ms = ev_ms(lambda: atlas.atlas_probe_dense_rows(sdt, rows, rows_n, kk, dd, Wp, po, reps), 1) / reps
+                tf = 2.0 * rows_n * kk * dd / (t_ms / 1e3) / 1e12
+                mf[label] = {"rows": rows_n, "K": kk, "d_out": dd, "tflops": round(tf, 1),
+                             "frac_of_mfma_peak": round(tf * 1e12 / mfma_peak, 4)}
+                del rows, Wp, po
+        measured = {
+            "copy_GBps": round(2 * cbytes / (copy_ms / 1e3) / 1e9, 1),   # 1 read : 1 write
+            "copy_frac_of_peak": round(2 * cbytes / (copy_ms / 1e3) / 1e9 / HBM_PEAK_GBPS, 4),
+            "gather_GBps": round(n_ids * 256 / (gather_ms / 1e3) / 1e9, 1),
+            "gather": "2^27 random 256-byte rows of a 1 GiB table, one wave per row, 8 rows in flight per wave",
+            "mfma": mf,
+            "aggregate_frac_of_measured_gather": round(e * (4 + d * s_in) / agg_s_per_layer / 1e9 /
+                                                       (n_ids * 256 / (gather_ms / 1e3) / 1e9), 4),
+        }
+        log("measured peaks: copy %.0f GB/s, row gather %.0f GB/s, MFMA %s" %
+            (measured["copy_GBps"], measured["gather_GBps"], {k: v["tflops"] for k, v in mf.items()}))
+        torch.cuda.empty_cache()
 
     # ---- CPU oracle on a bounded sample of the same layer ----
     cpu = None
@@ -352,38 +470,73 @@ def main() -> int:
         oracle.build()
         gsel = torch.Generator().manual_seed(12345)
         pick = torch.randperm(n, generator=gsel)[: args.sample_dst]
-        pick = torch.unique(torch.cat([pick, torch.topk(indeg.to(torch.int64), min(1024, n)).indices.cpu()]))
-        in_off, in_src = in_edges_of(wl.off, wl.col, pick.to(dev))
-        need = torch.unique(torch.cat([in_src.to(torch.int64), pick.to(dev)]))
-        remap = torch.full((n,), -1, dtype=torch.int64, device=dev)
-        remap[need] = torch.arange(need.numel(), device=dev)
+        pick = torch.unique(torch.cat([pick, torch.topk(indeg.to(torch.int64), min(1024, n)).indices.cpu()])).to(dev)
+        in_off, in_src_local, need, pick_local = sample_subgraph(wl.off, wl.col, pick)
         Xs = wl.X[need].float().cpu().numpy()
-        il = oracle.InLists(in_off.cpu().numpy(), remap[in_src.to(torch.int64)].to(torch.int32).cpu().numpy(),
-                            remap[pick.to(dev)].cpu().numpy())
+        il = oracle.InLists(in_off.cpu().numpy(), in_src_local.cpu().numpy(), pick_local.cpu().numpy())
         p0 = wl.layers[0]
         indeg_s = indeg[need].cpu().numpy().astype(np.int64)
         t1 = time.perf_counter()
         Y = oracle.run_layer(wl.model, il, indeg_s, Xs, p0, {"relu": oracle.ACT_RELU, "elu": oracle.ACT_ELU}[wl.act],
                              {torch.bfloat16: oracle.FMT_BF16, torch.float16: oracle.FMT_F16}.get(wl.store, oracle.FMT_F32))
         t_or = time.perf_counter() - t1
-        sample_edges = int(in_src.numel())
-        # sampled parity of the timed configuration, on the way
-        run_layer(0, x_layer0, False)
-        got = outs[0][pick.to(dev)].float().cpu().numpy().astype(np.float64)
-        rn = np.maximum(np.abs(Y).max(axis=1), 1e-6 * np.abs(Y).max())
-        err = float((np.abs(got - Y).max(axis=1) / rn).max())
-        log("oracle sample: %d destinations, %d edges, %.2f s; sampled parity error %.3e" %
-            (pick.numel(), sample_edges, t_or, err))
+        sample_edges = int(in_src_local.numel())
+        # sampled parity of the timed configurations, on the way
+        errs = {}
+        for label, graph, planned, x0 in (("hbm_resident", graph_dev if do_device else None, plan is not None, wl.X),
+                                          ("pinned_host", graph_pin if do_pinned else None, plan_host is not None,
+                                           x_h if do_pinned else None)):
+            if graph is None:
+                continue
+            outs[0].fill_(float("nan"))
+            run_layer(graph, planned, 0, x0, False)
+            got = outs[0][pick].float().cpu().numpy().astype(np.float64)
+            rn = np.maximum(np.abs(Y).max(axis=1), 1e-6 * np.abs(Y).max())
+            errs[label] = float((np.abs(got - Y).max(axis=1) / rn).max())
+        log("oracle sample: %d destinations, %d edges, %.2f s; sampled parity error %s" %
+            (pick.numel(), sample_edges, t_or, errs))
         cpu = {"value": round(sample_edges / t_or / 1e9, 6), "unit": "GTEPS", "cores": oracle.num_threads(),
                "kind": "oracle",
                "sample": "%d destinations (%d random + the 1,024 highest in-degree) with all %d of their in-edges, "
                          "layer 1 aggregate + update in fp64" % (pick.numel(), args.sample_dst, sample_edges),
-               "seconds": round(t_or, 3), "sampled_parity_max_rel_err": err,
+               "seconds": round(t_or, 3), "sampled_parity_max_rel_err": errs,
                "cpu_model": cpu_model(), "host_cpus": os.cpu_count()}
 
-    if plan is not None:
-        atlas.atlas_plan_destroy(plan)
+    # ---- teardown: nothing of the library's stays alive until the process exits ----
+    for ph in (plan, plan_host):
+        if ph is not None:
+            atlas.atlas_plan_destroy(ph)
+    torch.cuda.synchronize()
+    atlas.atlas_release_cache()
+
+    def r1(v):
+        return None if v is None else round(v, 1)
+    prep_total = sum(v for k, v in prep.items() if v is not None and k != "plan_pinned_host")
+    prep_out = {k: r1(v) for k, v in prep.items()}
+    prep_out["total_hbm_resident"] = r1(prep_total)
+    prep_out["note"] = ("one-time per graph, reused by every layer and run: in-degree of the raw ids (for the ordering), "
+                        "the ordering sort, in-degree of the ordered graph, the destination-grouped plan; the "
+                        "generator's own relabelling and CSR build are input production and are not in here")
+    stated = None
+    if pin_res is not None:
+        h2d = pin_res["last_stats"]["bytes_copied_h2d"]
+        cms = pin_res["per_step"]["ms_copy"]
+        stated = {
+            "execution": "CSR, features and plan in pinned host memory; every chunk staged into HBM on the library's "
+                         "copy stream (long chunks in pieces) while the previous chunk's kernels run; fp32 accumulators "
+                         "resident in HBM",
+            "ms_per_step": round(pin_res["ms_per_step"], 3),
+            "ms_per_step_min": round(min(pin_res["step_ms"]), 3),
+            "gteps": round(e / (pin_res["ms_per_step"] / 1e3) / 1e9, 4),
+            "h2d_GB_per_layer": round(h2d / 1e9, 2), "copy_stream_ms": round(cms, 1),
+            "h2d_GBps": round(h2d / max(cms, 1e-9) / 1e6, 1),
+            "copy_stream_busy_frac": round(cms / pin_res["ms_per_step"], 3),
+            "kernels_ms": {k[3:]: round(v, 2) for k, v in pin_res["per_step"].items() if k != "ms_copy"},
+            "end_to_end_ms": r1(pin_res["e2e_ms"]), "end_to_end_layer_ms": [round(v, 1) for v in pin_res["layer_ms"]],
+            "plan_build_ms": r1(prep["plan_pinned_host"]),
+        }
     gteps = e / (ms_per_step / 1e3) / 1e9
+    st = main_res["last_stats"]
     line = {
         "metric": "aggregated edges/s per layer (GTEPS)", "value": round(gteps, 4), "unit": "GTEPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
@@ -394,23 +547,27 @@ def main() -> int:
         "config": {"workload": wl.name, "layer_type": wl.model, "vertices": n, "edges": e, "d_in": wl.dims[0], "d_out": wl.dims[1],
                    "chunk_sources": chunk, "chunks": nchunks, "flush": "after every chunk",
                    "ids": {"indegree": "in-degree descending", "score": "greedy Score order (paper Sec. 3.8)",
-                           "original": "generator's raw ids"}[args.order], "in_degree": "precomputed once per graph",
-                   "residency": "HBM" if args.residency == "device" else
-                   "pinned host, staged per chunk on a copy stream (%.2f GB, copies %.1f ms per layer)"
-                   % (h2d_bytes / 1e9, copy_ms / args.steps),
-                   "edge_order": "per-chunk destination-grouped plan" if plan else "CSR stream (atomics)",
-                   "plan_build_ms": None if plan_ms is None else round(plan_ms, 1)},
+                           "original": "generator's raw ids"}[args.order],
+                   "value_is": ("inputs resident in HBM when the timed region starts; the same layer in the "
+                                "configuration's stated execution (streamed from pinned host memory) is "
+                                "config5_as_stated") if dev_res is not None else
+                               "streamed from pinned host memory (host-link inclusive)",
+                   "edge_order": "per-chunk destination-grouped plan" if (plan or plan_host) else "CSR stream (atomics)"},
         "transform_first": bool(args.transform_first),
         "plan_blocking": None if args.plan_block_log2 <= 0 else {"block_sources": 1 << args.plan_block_log2,
                                                                   "hot_min_edges": args.plan_hot_min},
+        "plan": plan_info,
         "hot_store": None if not hot_slots else {
             "slots": hot_slots, "policy": args.evict_policy + "-pending", "evictions_per_layer": st["hot_evictions"],
             "reloads_per_layer": st["hot_reloads"], "peak_slots": st["hot_peak_slots"]},
-        "layer_ms": {"aggregate": round(agg_ms / args.steps, 3), "update": round(upd_ms / args.steps, 3),
-                     "self": round(self_ms / args.steps, 3), "init": round(init_ms / args.steps, 3)},
-        "end_to_end_ms": None if e2e_ms is None else round(e2e_ms, 2),
-        "end_to_end_layer_ms": [round(v, 2) for v in layer_ms],
-        "roofline": roofline, "update": update, "cpu_baseline": cpu,
+        "layer_ms": {"aggregate": round(ps["ms_aggregate"], 3), "update": round(ps["ms_update"], 3),
+                     "self": round(ps["ms_self"], 3), "init": round(ps["ms_init"], 3)},
+        "end_to_end_ms": r1(main_res["e2e_ms"]),
+        "end_to_end_layer_ms": [round(v, 2) for v in main_res["layer_ms"]],
+        "prep_ms": prep_out,
+        "end_to_end_with_prep_ms": None if main_res["e2e_ms"] is None else r1(main_res["e2e_ms"] + prep_total),
+        "config5_as_stated": stated,
+        "roofline": roofline, "update": update, "measured_peak": measured, "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)
     return 0

@@ -364,6 +364,39 @@ int atlas_reorder_score_desc(const atlas_graph_t *graph, int32_t *new_of_old, in
 int atlas_sample_in_edges(const atlas_graph_t *graph, const uint32_t *edge_key, int32_t fanout,
                           int64_t *out_row_offsets, int32_t *out_col_indices, int64_t *out_num_edges);
 
+/* What a plan holds, for reports: chunk count, edges, destination groups (one per chunk and
+ * destination; a source-blocked plan has one per block for its heavy destinations), groups
+ * that are the first of their destination in the whole plan, and the bytes the plan occupies
+ * in device and in pinned host memory. */
+typedef struct {
+    int64_t num_chunks, num_edges, num_groups, num_first_groups;
+    int64_t bytes_device, bytes_pinned_host;
+} atlas_plan_info_t;
+int atlas_plan_info(const atlas_plan_t *plan, atlas_plan_info_t *info);
+
+/* Measured peaks of the box at hand, for the benchmark's report (Sec. 4.4 of the paper
+ * asks what bounds the run; here: what a bare kernel of the same access pattern reaches).
+ * All three only enqueue on hip_stream; the caller times them with events on that stream.
+ *   atlas_probe_copy:        dst[0..bytes) = src[0..bytes), DEVICE memory, bytes a multiple of 16.
+ *   atlas_probe_row_gather:  reads rows ids[0..n_ids) of `table` (rows of 256 bytes, DEVICE),
+ *                            one wave per row, eight rows in flight per wave -- the planned
+ *                            aggregation's source-row gather without its bookkeeping.  ids:
+ *                            int32 DEVICE, each in [0, table_rows).  sink: DEVICE scratch of at
+ *                            least atlas_probe_gather_sink_bytes() bytes (the waves' folded words).
+ *   atlas_probe_dense_rows:  out = rows x W on the matrix cores with the kernels the flush and the
+ *                            transform-first path use for a dense block of rows: n_rows x K row-major
+ *                            `rows`, K x d_out row-major `W`, n_rows x d_out `out`, all `dtype`
+ *                            (16-bit types; K a multiple of 64 up to 1024, d_out a multiple of 32 up
+ *                            to 256), `repeat` passes over the same rows, so that a row block that
+ *                            fits the caches shows the contraction's rate without the HBM cap.
+ * Errors: E_NULL, E_BAD_DIMS, E_RANGE, E_HIP, E_NOMEM. */
+int atlas_probe_copy(void *dst, const void *src, int64_t bytes, void *hip_stream);
+int64_t atlas_probe_gather_sink_bytes(void);
+int atlas_probe_row_gather(const void *table, int64_t table_rows, const int32_t *ids, int64_t n_ids, void *sink,
+                           void *hip_stream);
+int atlas_probe_dense_rows(int32_t dtype, const void *rows, int64_t n_rows, int32_t K, int32_t d_out, const void *W,
+                           void *out, int32_t repeat, void *hip_stream);
+
 /* Synchronise and copy one internal array to host memory, for tests. */
 enum atlas_debug_what {
     ATLAS_DBG_INDEG = 0,       /* int32[N]                                  */

@@ -33,7 +33,8 @@ EXPORTS = [
     "atlas_layer_finish", "atlas_in_degree", "atlas_reorder_indegree_desc", "atlas_debug_copy",
     "atlas_release_cache", "atlas_strerror", "atlas_last_hip_error", "atlas_plan_create", "atlas_plan_destroy",
     "atlas_reorder_score_desc", "atlas_sample_in_edges", "atlas_plan_create_blocked",
-    "atlas_reorder_indegree_desc_noalloc",
+    "atlas_reorder_indegree_desc_noalloc", "atlas_plan_info", "atlas_probe_copy", "atlas_probe_row_gather",
+    "atlas_probe_dense_rows", "atlas_probe_gather_sink_bytes",
 ]
 
 
@@ -67,6 +68,12 @@ class atlas_layer_stats_t(ctypes.Structure):
                 ("ms_init", ctypes.c_float), ("hot_evictions", ctypes.c_int64), ("hot_reloads", ctypes.c_int64),
                 ("hot_peak_slots", ctypes.c_int64), ("chunks_planned", ctypes.c_int64),
                 ("chunks_csr_stream", ctypes.c_int64)]
+
+
+class atlas_plan_info_t(ctypes.Structure):
+    _fields_ = [("num_chunks", ctypes.c_int64), ("num_edges", ctypes.c_int64), ("num_groups", ctypes.c_int64),
+                ("num_first_groups", ctypes.c_int64), ("bytes_device", ctypes.c_int64),
+                ("bytes_pinned_host", ctypes.c_int64)]
 
 
 class AtlasError(RuntimeError):
@@ -109,8 +116,14 @@ def lib() -> ctypes.CDLL:
         L.atlas_plan_create.argtypes = [ctypes.POINTER(atlas_graph_t), i64, ctypes.POINTER(vp)]
         L.atlas_plan_create_blocked.argtypes = [ctypes.POINTER(atlas_graph_t), i64, i64, i64, ctypes.POINTER(vp)]
         L.atlas_plan_destroy.argtypes = [vp]
+        L.atlas_plan_info.argtypes = [vp, ctypes.POINTER(atlas_plan_info_t)]
+        L.atlas_probe_copy.argtypes = [vp, vp, i64, vp]
+        L.atlas_probe_gather_sink_bytes.argtypes = []
+        L.atlas_probe_row_gather.argtypes = [vp, i64, vp, i64, vp, vp]
+        L.atlas_probe_dense_rows.argtypes = [i32, vp, i64, i32, i32, vp, vp, i32, vp]
         for name in EXPORTS:
             getattr(L, name).restype = ctypes.c_int      # raises AttributeError on a missing export
+        L.atlas_probe_gather_sink_bytes.restype = ctypes.c_int64
         L.atlas_strerror.argtypes = [i32]
         L.atlas_strerror.restype = ctypes.c_char_p
         L.atlas_last_hip_error.argtypes = []
@@ -209,6 +222,31 @@ def atlas_plan_create_blocked(graph: atlas_graph_t, chunk_sources: int, block_so
     _check(lib().atlas_plan_create_blocked(ctypes.byref(graph), chunk_sources, block_sources, hot_min_edges,
                                            ctypes.byref(h)), "atlas_plan_create_blocked")
     return h.value
+
+
+def atlas_plan_info(plan: int) -> dict:
+    info = atlas_plan_info_t()
+    _check(lib().atlas_plan_info(plan, ctypes.byref(info)), "atlas_plan_info")
+    return {name: getattr(info, name) for name, _ in atlas_plan_info_t._fields_}
+
+
+def atlas_probe_copy(dst, src, nbytes: int, stream=None) -> None:
+    _check(lib().atlas_probe_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "atlas_probe_copy")
+
+
+def atlas_probe_gather_sink_bytes() -> int:
+    return int(lib().atlas_probe_gather_sink_bytes())
+
+
+def atlas_probe_row_gather(table, table_rows: int, ids, n_ids: int, sink, stream=None) -> None:
+    _check(lib().atlas_probe_row_gather(_ptr(table), table_rows, _ptr(ids), n_ids, _ptr(sink), _stream(stream)),
+           "atlas_probe_row_gather")
+
+
+def atlas_probe_dense_rows(dtype: int, rows, n_rows: int, K: int, d_out: int, W, out, repeat: int = 1,
+                           stream=None) -> None:
+    _check(lib().atlas_probe_dense_rows(dtype, _ptr(rows), n_rows, K, d_out, _ptr(W), _ptr(out), repeat,
+                                        _stream(stream)), "atlas_probe_dense_rows")
 
 
 def atlas_plan_destroy(plan: int) -> None:

@@ -127,6 +127,7 @@ struct atlas_plan {
     bool blocked = false;           // some chunk is in source-blocked order (grp_dst bit 30 in use)
     std::vector<PlanChunk> chunks;  // grp_dst / tile_grp: device, or pinned host when `host`
     size_t max_stage_bytes = 0;     // host plans: largest staging slot any chunk needs
+    int64_t n_first = 0;            // destinations that receive a message from some chunk (first-touch groups)
 };
 
 namespace {
@@ -1185,6 +1186,8 @@ int atlas_plan_create_blocked(const atlas_graph_t *graph, int64_t chunk_sources,
         P->max_stage_bytes = std::max(P->max_stage_bytes, stage_bytes_of(pc, packed));
         ebeg = eend;
     }
+    if (rc == ATLAS_OK && seen && (e = count_nonzero_bytes(seen, P->n, &P->n_first)) != hipSuccess)
+        rc = hip_fail(e, "plan first-touch count");
     if (seen) (void)hipFree(seen);
     if (rc == ATLAS_OK && P->host) {
         const size_t ob = (static_cast<size_t>(P->n) + 1) * sizeof(int64_t);
@@ -1213,6 +1216,76 @@ int atlas_plan_destroy(atlas_plan_t *P) {
     if (P->src_packed) (void)hipHostFree(P->src_packed);
     if (P->dev_off) (void)hipFree(P->dev_off);
     delete P;
+    return ATLAS_OK;
+}
+
+int atlas_plan_info(const atlas_plan_t *P, atlas_plan_info_t *info) {
+    if (!P || !info) return ATLAS_E_NULL;
+    *info = atlas_plan_info_t{};
+    info->num_chunks = static_cast<int64_t>(P->chunks.size());
+    info->num_edges = P->e;
+    info->num_first_groups = P->n_first;
+    size_t dev = 0, host = 0;
+    for (const PlanChunk &c : P->chunks) {
+        info->num_groups += c.n_groups;
+        const size_t arrays = static_cast<size_t>(c.n_groups) * 4 + static_cast<size_t>((c.n_edges + 63) / 64) * 4;
+        (P->host ? host : dev) += arrays;
+        dev += static_cast<size_t>(c.n_zero_rows) * 12;
+    }
+    if (P->src_packed) host += P->packed_bytes;
+    else (P->host ? host : dev) += static_cast<size_t>(P->e) * 4;
+    if (P->dev_off) dev += (static_cast<size_t>(P->n) + 1) * sizeof(int64_t);
+    info->bytes_device = static_cast<int64_t>(dev);
+    info->bytes_pinned_host = static_cast<int64_t>(host);
+    return ATLAS_OK;
+}
+
+int atlas_probe_copy(void *dst, const void *src, int64_t bytes, void *hip_stream) {
+    if (!dst || !src) return ATLAS_E_NULL;
+    if (bytes < 0 || bytes % 16 != 0) return ATLAS_E_RANGE;
+    HIP_TRY(probe_copy(dst, src, static_cast<size_t>(bytes), static_cast<hipStream_t>(hip_stream)));
+    return ATLAS_OK;
+}
+
+int64_t atlas_probe_gather_sink_bytes(void) { return static_cast<int64_t>(probe_gather_sink_bytes()); }
+
+int atlas_probe_row_gather(const void *table, int64_t table_rows, const int32_t *ids, int64_t n_ids, void *sink,
+                           void *hip_stream) {
+    if (!table || !ids || !sink) return ATLAS_E_NULL;
+    if (table_rows <= 0 || table_rows >= (int64_t(1) << 31) || n_ids < 0) return ATLAS_E_RANGE;
+    HIP_TRY(probe_row_gather(table, ids, n_ids, sink, static_cast<hipStream_t>(hip_stream)));
+    return ATLAS_OK;
+}
+
+int atlas_probe_dense_rows(int32_t dtype, const void *rows, int64_t n_rows, int32_t K, int32_t d_out, const void *W,
+                           void *out, int32_t repeat, void *hip_stream) {
+    if (!rows || !W || !out) return ATLAS_E_NULL;
+    if (dtype != ATLAS_DTYPE_BF16 && dtype != ATLAS_DTYPE_F16) return ATLAS_E_BAD_DIMS;
+    if (K <= 0 || K % 64 != 0 || K > 1024 || d_out <= 0 || d_out % 32 != 0 || d_out > 256) return ATLAS_E_BAD_DIMS;
+    if (n_rows <= 0 || n_rows >= (int64_t(1) << 31) || repeat < 1) return ATLAS_E_RANGE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    Buf packed, counters;
+    HIP_TRY(packed.alloc(packed_weight_bytes(K, d_out, dtype)));
+    hipError_t e = counters.alloc(CTR_COUNT * sizeof(int32_t));
+    if (e == hipSuccess) e = launch_fill_zero(counters.p, counters.bytes, s);
+    if (e == hipSuccess) e = launch_pack_weights(W, dtype, K, d_out, dtype, packed.p, s);
+    UpdateArgs u{};
+    u.model = 4;           // plain rows in the storage type
+    u.d_in = K;
+    u.d_out = d_out;
+    u.K = K;
+    u.in_dt = u.out_dt = u.compute_dt = dtype;
+    u.self_rows = rows;
+    u.counters = static_cast<int32_t *>(counters.p);
+    u.packed_w = packed.p;
+    u.out = out;
+    u.n = n_rows;
+    u.identity_rows = n_rows;
+    for (int r = 0; e == hipSuccess && r < repeat; ++r) e = launch_update(u, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);   // the packed weights go back to the cache below
+    packed.release();
+    counters.release();
+    if (e != hipSuccess) return hip_fail(e, "atlas_probe_dense_rows");
     return ATLAS_OK;
 }
 

@@ -171,6 +171,9 @@ hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int6
                             int64_t src_end, int64_t edge_begin, int64_t edge_end, int32_t *src_sorted,
                             uint8_t *seen, int64_t block_sources, int64_t hot_min_edges, PlanChunk *out);
 
+// Non-zero bytes of a device array (synchronous): how many destinations a plan's first-touch map has seen.
+hipError_t count_nonzero_bytes(const uint8_t *p, int64_t n, int64_t *out);
+
 // GAT, per chunk: raise m_next[v][h] to the largest logit any edge of the chunk
 // sends to v (CSR order), then bring every destination whose maximum moved to
 // the new reference (rescale l and acc, m_cur = m_next).
@@ -277,6 +280,11 @@ hipError_t launch_sum_finalize(const SumFinalizeArgs &a, hipStream_t s);
 // SGC hop: out[v] = acc[v] * deg(v)^-1/2 for the ready rows (no contraction).
 hipError_t launch_scale_rows(const UpdateArgs &a, hipStream_t s);
 hipError_t launch_advance_head(int32_t *counters, hipStream_t s);
+
+// Measured-peak probes (k_probe.hip).
+hipError_t probe_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
+size_t probe_gather_sink_bytes();
+hipError_t probe_row_gather(const void *table, const int32_t *ids, int64_t n_ids, void *sink, hipStream_t s);
 
 // Degree ordering.
 hipError_t reorder_indegree_desc(const int32_t *indeg, int64_t n, int32_t *new_of_old,

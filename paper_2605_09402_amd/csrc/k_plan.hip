@@ -142,6 +142,16 @@ __global__ void k_collect_zero_rows(const int32_t *__restrict__ grp_dst, const u
     }
 }
 
+// number of non-zero bytes (the destinations the first-touch map has seen)
+__global__ __launch_bounds__(kBlock) void k_count_nonzero(const uint8_t *__restrict__ p, int64_t n,
+                                                          unsigned long long *count) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    unsigned int mine = 0;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; i < n; i += stride) mine += p[i] != 0;
+    for (int o = 32; o > 0; o >>= 1) mine += __shfl_down(mine, o);
+    if ((threadIdx.x & 63) == 0 && mine) atomicAdd(count, static_cast<unsigned long long>(mine));
+}
+
 struct MaxOp {
     __host__ __device__ int32_t operator()(int32_t a, int32_t b) const { return a > b ? a : b; }
 };
@@ -297,6 +307,25 @@ done:
         out->zero_rows = nullptr;
         out->zero_span = nullptr;
     }
+    return err;
+}
+
+hipError_t count_nonzero_bytes(const uint8_t *p, int64_t n, int64_t *out) {
+    *out = 0;
+    if (n <= 0) return hipSuccess;
+    unsigned long long *cnt = nullptr, host = 0;
+    hipError_t err = hipMalloc(&cnt, sizeof(unsigned long long));
+    if (err != hipSuccess) return err;
+    err = hipMemset(cnt, 0, sizeof(unsigned long long));
+    if (err == hipSuccess) {
+        int64_t blocks = (n + kBlock - 1) / kBlock;
+        if (blocks > 4096) blocks = 4096;
+        hipLaunchKernelGGL(k_count_nonzero, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, nullptr, p, n, cnt);
+        err = hipGetLastError();
+    }
+    if (err == hipSuccess) err = hipMemcpy(&host, cnt, sizeof(host), hipMemcpyDeviceToHost);
+    (void)hipFree(cnt);
+    *out = static_cast<int64_t>(host);
     return err;
 }
 

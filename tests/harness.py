@@ -76,6 +76,37 @@ def row_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     return float((err / np.maximum(rn, floor)).max())
 
 
+# Element-wise bound.  The row-normalised metric above says nothing about the small elements of a
+# row with a large norm, so every element is also held to
+#     |got - ref| <= ELEM_U[store] * (|ref| + mag),
+# where mag is the same layer evaluated on absolute values (|x|, |W|, |b|): the sum of the
+# magnitudes of the terms that make up the element, i.e. what a floating-point error of the
+# accumulation is proportional to.  ELEM_U is twice the unit roundoff of the storage type for the
+# 16-bit types (one rounding of the stored output, relative to |ref|; one of the contraction's
+# left operand -- the normalised aggregate -- relative to mag; fp32 accumulation of K <= 1024 terms
+# adds K * 2^-24, far below) and 64 * 2^-24 for fp32 (fp32 sums of up to millions of terms in an
+# arbitrary order: statistical growth with the square root of the term count, relative to mag).
+ELEM_U = {torch.float32: 64 * 2.0 ** -24, torch.bfloat16: 2.0 ** -8, torch.float16: 2.0 ** -10}
+
+
+class _Abs:
+    def __init__(self, p):
+        self.W = None if p.W is None else np.abs(np.asarray(p.W, dtype=np.float64))
+        self.bias = None if p.bias is None else np.abs(np.asarray(p.bias, dtype=np.float64))
+        self.attn_src = self.attn_dst = None
+
+
+def elementwise_check(oracle, model, il, indeg, X, params, got, ref, store, where="", eps=0.0, extra_roundings=0):
+    """extra_roundings: further roundings to the storage type on the way (transform-first pushes
+    rounded products), each worth one more unit relative to mag."""
+    mag = oracle.run_layer(model, il, indeg, np.abs(X), _Abs(params), 0, oracle.FMT_F32, 0.2, abs(1.0 + eps) - 1.0)
+    u = ELEM_U[store]
+    bound = u * (np.abs(ref) + (1 + extra_roundings) * mag) + 1e-30
+    worst = float((np.abs(got - ref) / bound).max()) if ref.size else 0.0
+    assert worst <= 1.0, "%s: element-wise error is %.2f times its bound" % (where, worst)
+    return worst
+
+
 def oracle_outputs(oracle, case: Case) -> List[np.ndarray]:
     fmt = fmt_of(oracle, case.store)
     return oracle.run_model(case.model, case.off.numpy(), case.col.numpy(), case.X.float().numpy(), case.layers,
@@ -89,6 +120,7 @@ class GpuRun:
     pending_after_chunk: List[List[np.ndarray]] = field(default_factory=list)   # [layer][chunk]
     ready_per_flush: List[List[np.ndarray]] = field(default_factory=list)       # [layer][flush], incl. flush 0 at init
     indeg: Optional[np.ndarray] = None
+    extra_roundings: int = 0    # transform-first layers push products rounded to the storage type
 
 
 def _dt(store: torch.dtype) -> int:
@@ -110,7 +142,7 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
     tiles_per_run / piece_tiles: the launch-shape fields of atlas_dims_t (0: the library's choice)."""
     dev = torch.device("cuda:0")
     n, e = case.n, case.e
-    run = GpuRun()
+    run = GpuRun(extra_roundings=1 if transform_first else 0)
     stream = torch.cuda.current_stream()
     if pinned_host:
         off_t = case.off.pin_memory()
@@ -244,12 +276,21 @@ def check_outputs(oracle, case: Case, run: GpuRun):
     refs = oracle_outputs(oracle, case)
     tol = tol_of(case.store)
     errs = []
+    il = indeg = None
+    if case.model != "gat":
+        il = oracle.InLists.from_csr(case.off.numpy(), case.col.numpy())
+        indeg = oracle.in_degree(case.n, case.col.numpy())
+    x_in = case.X.float().numpy()
     for li, (got, ref) in enumerate(zip(run.outputs, refs)):
         g = got.float().cpu().numpy().astype(np.float64)
         assert np.isfinite(g).all(), "layer %d has unwritten or non-finite rows" % li
         err = row_rel_err(g, ref)
         errs.append(err)
         assert err <= tol, "layer %d: row-normalised relative error %.3e > %.1e" % (li, err, tol)
+        if il is not None and li == 0:
+            # element by element on the first layer, where both sides read the same input
+            elementwise_check(oracle, case.model, il, indeg, x_in, case.layers[0], g, ref, case.store,
+                              "layer 0", case.eps, run.extra_roundings)
     return errs
 
 
@@ -263,7 +304,7 @@ def case_from_edges(model: str, n: int, src, dst, seed: int, dims: List[int], ch
 
 
 # --------------------------------------------------------------------------
-# full-size workloads: device-resident run + sampled oracle check of layer 1
+# full-size workloads: every layer through the C ABI, checked on sampled destinations
 # --------------------------------------------------------------------------
 
 def gpu_reorder(off, col):
@@ -278,81 +319,184 @@ def gpu_reorder(off, col):
     return new_of_old
 
 
-def run_workload_layer1(wl, plan: bool, emb_resident: bool = False, planned_only: bool = False, plan_block=None):
-    """Layer 1 of a device-resident workload through the C ABI, flush after
-    every chunk.  plan_block = (block_sources, hot_min_edges) builds the
-    source-blocked plan.  Returns (out, stats, indeg, final pending, ready list)."""
-    dev = wl.off.device
-    n, e = wl.n, wl.e
-    indeg = torch.empty(n, dtype=torch.int32, device=dev)
-    atlas.atlas_in_degree(atlas.make_graph(n, e, wl.off, wl.col), indeg)
-    plan_h = None
-    if plan and plan_block:
-        plan_h = atlas.atlas_plan_create_blocked(atlas.make_graph(n, e, wl.off, wl.col), wl.chunk, *plan_block)
-    elif plan:
-        plan_h = atlas.atlas_plan_create(atlas.make_graph(n, e, wl.off, wl.col), wl.chunk)
-    graph = atlas.make_graph(n, e, wl.off, wl.col, indeg, atlas.RESIDENT_DEVICE, plan_h)
-    sdt = _dt(wl.store)
-    p = wl.layers[0]
-    W = p.W.to(wl.store).to(dev).contiguous()
-    b = p.bias.to(wl.store).to(dev).contiguous()
-    a_s = None if p.attn_src is None else p.attn_src.to(wl.store).to(dev).contiguous()
-    a_d = None if p.attn_dst is None else p.attn_dst.to(wl.store).to(dev).contiguous()
-    act = {"relu": atlas.ACT_RELU, "elu": atlas.ACT_ELU}[wl.act] if len(wl.layers) > 1 else atlas.ACT_NONE
-    dims = atlas.make_dims(MODEL_ID[wl.model], wl.dims[0], wl.dims[1], sdt, sdt, act, wl.chunk, heads=wl.heads,
-                           flags=(atlas.FLAG_EMB_RESIDENT if emb_resident else 0) |
-                           (atlas.FLAG_PLANNED_ONLY if planned_only else 0))
-    h = atlas.atlas_layer_init(graph, dims, atlas.make_weights(W, b, sdt, a_s, a_d))
-    out = torch.full((n, wl.dims[1]), float("nan"), dtype=wl.store, device=dev)
-    if wl.model == "gat":
-        for b0 in range(0, n, wl.chunk):
-            atlas.atlas_attention_prepass(h, b0, min(n, b0 + wl.chunk), wl.X[b0:b0 + wl.chunk])
-    atlas.atlas_flush_ready(h, out)
-    for b0 in range(0, n, wl.chunk):
-        b1 = min(n, b0 + wl.chunk)
-        atlas.atlas_broadcast_chunk(h, b0, b1, wl.X[b0:b1])
-        atlas.atlas_flush_ready(h, out)
-    pend = np.empty(n, dtype=np.int32)
-    atlas.atlas_debug_copy(h, atlas.DBG_PENDING, pend)
-    ready = np.empty(n, dtype=np.int32)
-    atlas.atlas_debug_copy(h, atlas.DBG_READY, ready)
-    stats = atlas.atlas_layer_finish(h)
-    if plan_h is not None:
-        atlas.atlas_plan_destroy(plan_h)
-    return out, stats, indeg, pend, ready
+@dataclass
+class Sample:
+    """Destinations the oracle computes one by one, with all their in-edges."""
+    pick: torch.Tensor        # int64 [m] vertex ids (device)
+    in_off: np.ndarray        # int64 [m+1]
+    in_src: np.ndarray        # int32, streaming (global) ids: for the counters
+    in_src_local: np.ndarray  # int32, positions in `need`: for the layer functions
+    need: torch.Tensor        # int64, ascending: the picked vertices and their in-neighbours (device)
+    pick_local: np.ndarray    # int64 [m] positions of the picked vertices in `need`
+
+    @property
+    def edges(self):
+        return int(self.in_src.size)
 
 
-def sampled_layer1_check(oracle, wl, out, indeg_dev, n_random: int = 1 << 14, n_top: int = 1024, seed: int = 7):
-    """Oracle layer 1 on a sample of destinations (random + highest in-degree)
-    with all their in-edges; also pins the library's in-degree on the sample."""
+def draw_sample(wl, indeg_dev, n_random: int = 1 << 14, n_top: int = 1024, seed: int = 7) -> Sample:
     dev = wl.off.device
-    n = wl.n
     g = torch.Generator().manual_seed(seed)
-    pick = torch.randperm(n, generator=g)[:n_random].to(dev)
-    top = torch.topk(indeg_dev.to(torch.int64), min(n_top, n)).indices
+    pick = torch.randperm(wl.n, generator=g)[:n_random].to(dev)
+    top = torch.topk(indeg_dev.to(torch.int64), min(n_top, wl.n)).indices
     pick = torch.unique(torch.cat([pick, top]))
     in_off, in_src = gen.in_edges_of(wl.off, wl.col, pick)
-    need = torch.unique(torch.cat([in_src.to(torch.int64), pick]))
-    remap = torch.full((n,), -1, dtype=torch.int64, device=dev)
-    remap[need] = torch.arange(need.numel(), device=dev)
-    Xs = wl.X[need].float().cpu().numpy()
-    in_off_h = in_off.cpu().numpy()
-    il = oracle.InLists(in_off_h, remap[in_src.to(torch.int64)].to(torch.int32).cpu().numpy(), remap[pick].cpu().numpy())
-    assert np.array_equal(indeg_dev[pick].cpu().numpy().astype(np.int64), np.diff(in_off_h)), "in-degree of the sample"
-    p = wl.layers[0]
-    act = ORACLE_ACT[wl.act] if len(wl.layers) > 1 else 0
+    in_off2, in_src_local, need, pick_local = gen.sample_subgraph(wl.off, wl.col, pick)
+    assert torch.equal(in_off, in_off2)
+    return Sample(pick, in_off.cpu().numpy(), in_src.cpu().numpy(), in_src_local.cpu().numpy(), need,
+                  pick_local.cpu().numpy())
+
+
+@dataclass
+class WorkloadRun:
+    outs: List[torch.Tensor] = field(default_factory=list)     # per layer, [n, d_out] on the device
+    stats: List[dict] = field(default_factory=list)
+    indeg: Optional[torch.Tensor] = None                        # the library's in-degree (device)
+    pending_at_pick: List[np.ndarray] = field(default_factory=list)   # layer 1: after every chunk, at sample.pick
+    ready: List[np.ndarray] = field(default_factory=list)       # per layer: the whole ready list, completion order
+    tails: List[np.ndarray] = field(default_factory=list)       # per layer: ready-list length at every flush
+    pending_final_any: List[bool] = field(default_factory=list)
+
+
+def run_workload(wl, *, plan: bool = True, emb_resident: bool = False, planned_only: bool = False, plan_block=None,
+                 pinned: bool = False, n_layers: Optional[int] = None, sample: Optional[Sample] = None,
+                 indeg: Optional[torch.Tensor] = None) -> WorkloadRun:
+    """All (or the first n_layers) layers of a workload through the C ABI, flush after every chunk,
+    each layer reading the previous layer's output where it lies in device memory.  plan_block =
+    (block_sources, hot_min_edges) builds the source-blocked plan.  pinned: the CSR and the
+    first layer's features are handed over in pinned host memory and streamed by the library.
+    With a sample, layer 1 also records the pending counts of the sampled vertices after every chunk."""
+    dev = wl.off.device
+    n, e = wl.n, wl.e
+    run = WorkloadRun()
+    if indeg is None:
+        indeg = torch.empty(n, dtype=torch.int32, device=dev)
+        atlas.atlas_in_degree(atlas.make_graph(n, e, wl.off, wl.col), indeg)
+    run.indeg = indeg
+    if pinned:
+        off_t = torch.empty(wl.off.shape, dtype=wl.off.dtype, pin_memory=True).copy_(wl.off)
+        col_t = torch.empty(wl.col.shape, dtype=wl.col.dtype, pin_memory=True).copy_(wl.col)
+        x0 = torch.empty(wl.X.shape, dtype=wl.X.dtype, pin_memory=True).copy_(wl.X)
+        res = atlas.RESIDENT_PINNED_HOST
+    else:
+        off_t, col_t, x0, res = wl.off, wl.col, wl.X, atlas.RESIDENT_DEVICE
+    plan_h = None
+    if plan and plan_block:
+        plan_h = atlas.atlas_plan_create_blocked(atlas.make_graph(n, e, off_t, col_t, None, res), wl.chunk, *plan_block)
+    elif plan:
+        plan_h = atlas.atlas_plan_create(atlas.make_graph(n, e, off_t, col_t, None, res), wl.chunk)
+    graph = atlas.make_graph(n, e, off_t, col_t, indeg, res, plan_h)
+    sdt = _dt(wl.store)
+    nl = len(wl.layers) if n_layers is None else n_layers
+    x = x0
+    pend_host = np.empty(n, dtype=np.int32) if sample is not None else None
+    pick_host = sample.pick.cpu().numpy() if sample is not None else None
+    try:
+        for li in range(nl):
+            p = wl.layers[li]
+            W = p.W.to(wl.store).to(dev).contiguous()
+            b = p.bias.to(wl.store).to(dev).contiguous()
+            a_s = None if p.attn_src is None else p.attn_src.to(wl.store).to(dev).contiguous()
+            a_d = None if p.attn_dst is None else p.attn_dst.to(wl.store).to(dev).contiguous()
+            act = {"relu": atlas.ACT_RELU, "elu": atlas.ACT_ELU}[wl.act] if li + 1 < len(wl.layers) else atlas.ACT_NONE
+            dims = atlas.make_dims(MODEL_ID[wl.model], wl.dims[li], wl.dims[li + 1], sdt, sdt, act, wl.chunk,
+                                   heads=wl.heads, flags=(atlas.FLAG_EMB_RESIDENT if emb_resident else 0) |
+                                   (atlas.FLAG_PLANNED_ONLY if planned_only else 0))
+            h = atlas.atlas_layer_init(graph, dims, atlas.make_weights(W, b, sdt, a_s, a_d))
+            out = torch.full((n, wl.dims[li + 1]), float("nan"), dtype=wl.store, device=dev)
+            if wl.model == "gat":
+                for b0 in range(0, n, wl.chunk):
+                    atlas.atlas_attention_prepass(h, b0, min(n, b0 + wl.chunk), x[b0:b0 + wl.chunk])
+            tails = []
+            cnt = np.zeros(2, dtype=np.int64)
+
+            def flush():
+                atlas.atlas_debug_copy(h, atlas.DBG_READY_COUNT, cnt)
+                tails.append(int(cnt[0]))
+                atlas.atlas_flush_ready(h, out)
+
+            flush()
+            for b0 in range(0, n, wl.chunk):
+                b1 = min(n, b0 + wl.chunk)
+                atlas.atlas_broadcast_chunk(h, b0, b1, x[b0:b1])
+                if sample is not None and li == 0:
+                    atlas.atlas_debug_copy(h, atlas.DBG_PENDING, pend_host)
+                    run.pending_at_pick.append(pend_host[pick_host].astype(np.int64))
+                flush()
+            pend = np.empty(n, dtype=np.int32)
+            atlas.atlas_debug_copy(h, atlas.DBG_PENDING, pend)
+            ready = np.empty(n, dtype=np.int32)
+            atlas.atlas_debug_copy(h, atlas.DBG_READY, ready)
+            run.stats.append(atlas.atlas_layer_finish(h))
+            run.pending_final_any.append(bool(pend.any()))
+            run.ready.append(ready)
+            run.tails.append(np.asarray(tails, dtype=np.int64))
+            run.outs.append(out)
+            x = out
+    finally:
+        torch.cuda.synchronize()
+        if plan_h is not None:
+            atlas.atlas_plan_destroy(plan_h)
+    return run
+
+
+def check_layer_counters(wl, run: WorkloadRun, planned: bool):
+    """What holds at any size: every edge pushed once, every vertex completed and flushed once,
+    pending counts all zero, the ready list a permutation, and the path every chunk took."""
+    for li, st in enumerate(run.stats):
+        assert st["edges_processed"] == wl.e and st["vertices_flushed"] == wl.n
+        assert st["vertices_completed"] == wl.n and st["sources_processed"] == wl.n
+        assert st["chunks_planned"] == (st["num_chunks"] if planned else 0)
+        assert st["chunks_csr_stream"] == (0 if planned else st["num_chunks"])
+        assert not run.pending_final_any[li], "pending counts must all reach zero"
+        seen = np.zeros(wl.n, dtype=np.uint8)
+        seen[run.ready[li]] = 1
+        assert seen.all(), "ready list is a permutation"
+
+
+def check_sampled_integers(oracle, wl, run: WorkloadRun, sample: Sample):
+    """Bit-exact on the sampled destinations: in-degree, pending count after every chunk,
+    and the flush in which each one became ready, for every layer."""
+    selfmsg = wl.model in ("sage", "gin")
+    n, C = wl.n, wl.chunk
+    il = oracle.InLists(sample.in_off, sample.in_src, sample.pick.cpu().numpy())
+    assert np.array_equal(run.indeg[sample.pick].cpu().numpy().astype(np.int64), np.diff(sample.in_off)), "in-degree"
+    nchunks = (n + C - 1) // C
+    assert len(run.pending_at_pick) == nchunks
+    for c in range(nchunks):
+        ref = oracle.pending_after(il, selfmsg, min(n, (c + 1) * C))
+        assert np.array_equal(run.pending_at_pick[c], ref), "pending after chunk %d" % c
+    cc = oracle.completion_chunk(il, selfmsg, C)
+    pick = sample.pick.cpu().numpy()
+    for li in range(len(run.ready)):
+        pos = np.empty(n, dtype=np.int64)
+        pos[run.ready[li]] = np.arange(n, dtype=np.int64)
+        tails = run.tails[li]            # tails[f] = list length when flush f was issued: flush f wrote [tails[f-1], tails[f])
+        assert tails.size == nchunks + 1 and tails[-1] == n
+        flush_of = np.searchsorted(tails, pos[pick], side="right")
+        assert np.array_equal(flush_of, cc + 1), "layer %d: flush in which the sampled vertices became ready" % li
+
+
+def check_sampled_layers(oracle, wl, run: WorkloadRun, sample: Sample):
+    """Every layer in isolation: the oracle's layer l on the sample, fed the rows of the GPU's
+    layer l-1 output (the features for l = 0) at the sample's vertices and in-neighbours, against
+    the GPU's layer-l rows.  An error is thereby pinned to the layer that makes it."""
+    il = oracle.InLists(sample.in_off, sample.in_src_local, sample.pick_local)
+    indeg_need = run.indeg[sample.need].cpu().numpy().astype(np.int64)
     fmt = fmt_of(oracle, wl.store)
-    Y = oracle.run_layer(wl.model, il, indeg_dev[need].cpu().numpy().astype(np.int64), Xs, p, act, fmt)
-    got = out[pick].float().cpu().numpy().astype(np.float64)
-    assert np.isfinite(got).all()
-    err = row_rel_err(got, Y)
     tol = tol_of(wl.store)
-    assert err <= tol, "sampled layer-1 error %.3e > %.1e" % (err, tol)
-    return err, int(pick.numel()), int(in_src.numel())
-
-
-def check_layer_counters(wl, stats, pend, ready):
-    assert stats["edges_processed"] == wl.e and stats["vertices_flushed"] == wl.n
-    assert stats["vertices_completed"] == wl.n and stats["sources_processed"] == wl.n
-    assert not pend.any(), "pending counts must all reach zero"
-    assert np.array_equal(np.sort(ready), np.arange(wl.n, dtype=np.int32)), "ready list is a permutation"
+    errs = []
+    x_in = wl.X
+    for li, out in enumerate(run.outs):
+        Xs = x_in[sample.need].float().cpu().numpy()
+        act = ORACLE_ACT[wl.act] if li + 1 < len(wl.layers) else 0
+        Y = oracle.run_layer(wl.model, il, indeg_need, Xs, wl.layers[li], act, fmt)
+        got = out[sample.pick].float().cpu().numpy().astype(np.float64)
+        assert np.isfinite(got).all(), "layer %d has unwritten or non-finite rows" % li
+        err = row_rel_err(got, Y)
+        assert err <= tol, "layer %d: sampled row-normalised error %.3e > %.1e" % (li, err, tol)
+        if wl.model != "gat":
+            elementwise_check(oracle, wl.model, il, indeg_need, Xs, wl.layers[li], got, Y, wl.store, "layer %d" % li)
+        errs.append(err)
+        x_in = out
+    return errs
