@@ -318,8 +318,18 @@ int atlas_plan_destroy(atlas_plan_t *plan);
 
 /* In-degree of every vertex (histogram of col_indices), int32[N] in DEVICE
  * memory.  Works for both residencies (a PINNED_HOST edge array is read over
- * the host link).  Enqueues on hip_stream. */
+ * the host link, once).  Enqueues on hip_stream; for DEVICE graphs of more
+ * than 2^15 vertices and 2^22 edges it also waits for the result (such graphs
+ * are counted bucket by bucket in LDS, with two bytes of scratch per edge that
+ * the call takes from, and returns to, the library's buffer cache). */
 int atlas_in_degree(const atlas_graph_t *graph, int32_t *in_degree, void *hip_stream);
+
+/* The same in-degrees read off a plan of the graph whose arrays are in DEVICE memory (a group's
+ * size is what its destination receives from the chunk): one pass over the plan's 4-byte edge
+ * words instead of one counter update per edge.  atlas_layer_init does this by itself when the
+ * graph has such a plan and no in_degree.  Enqueues on hip_stream.  E_STATE for plans of
+ * PINNED_HOST graphs (count from the graph instead). */
+int atlas_plan_in_degree(const atlas_plan_t *plan, int32_t *in_degree, void *hip_stream);
 
 /* In-degree-descending vertex order, ties by smaller old id first:
  * old_of_new[i] is the vertex placed at position i, new_of_old its inverse.

@@ -33,7 +33,7 @@ EXPORTS = [
     "atlas_layer_finish", "atlas_in_degree", "atlas_reorder_indegree_desc", "atlas_debug_copy",
     "atlas_release_cache", "atlas_strerror", "atlas_last_hip_error", "atlas_plan_create", "atlas_plan_destroy",
     "atlas_reorder_score_desc", "atlas_sample_in_edges", "atlas_plan_create_blocked",
-    "atlas_reorder_indegree_desc_noalloc", "atlas_plan_info", "atlas_probe_copy", "atlas_probe_row_gather",
+    "atlas_reorder_indegree_desc_noalloc", "atlas_plan_info", "atlas_plan_in_degree", "atlas_probe_copy", "atlas_probe_row_gather",
     "atlas_probe_dense_rows", "atlas_probe_gather_sink_bytes",
 ]
 
@@ -117,6 +117,7 @@ def lib() -> ctypes.CDLL:
         L.atlas_plan_create_blocked.argtypes = [ctypes.POINTER(atlas_graph_t), i64, i64, i64, ctypes.POINTER(vp)]
         L.atlas_plan_destroy.argtypes = [vp]
         L.atlas_plan_info.argtypes = [vp, ctypes.POINTER(atlas_plan_info_t)]
+        L.atlas_plan_in_degree.argtypes = [vp, vp, vp]
         L.atlas_probe_copy.argtypes = [vp, vp, i64, vp]
         L.atlas_probe_gather_sink_bytes.argtypes = []
         L.atlas_probe_row_gather.argtypes = [vp, i64, vp, i64, vp, vp]
@@ -228,6 +229,10 @@ def atlas_plan_info(plan: int) -> dict:
     info = atlas_plan_info_t()
     _check(lib().atlas_plan_info(plan, ctypes.byref(info)), "atlas_plan_info")
     return {name: getattr(info, name) for name, _ in atlas_plan_info_t._fields_}
+
+
+def atlas_plan_in_degree(plan: int, in_degree, stream=None) -> None:
+    _check(lib().atlas_plan_in_degree(plan, _ptr(in_degree), _stream(stream)), "atlas_plan_in_degree")
 
 
 def atlas_probe_copy(dst, src, nbytes: int, stream=None) -> None:

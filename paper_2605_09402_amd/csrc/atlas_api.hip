@@ -147,6 +147,7 @@ struct atlas_layer {
     int selfmsg = 0;
     int acc_width = 0;
 
+    Buf indeg_scratch;   // scratch of the in-degree count when the library counts (large DEVICE graphs)
     Buf indeg_own, pending, ready, counters, counters64, acc, self_rows, packed_w, bias, dev_off;
     Buf gat_el, gat_er, gat_mcur, gat_mnext, gat_l, gat_wa, gat_z;   // GAT state
     Buf gat_scores;                                                  // GAT, planned chunks: per-edge logits
@@ -199,7 +200,7 @@ struct atlas_layer {
     int32_t *ctr() { return static_cast<int32_t *>(counters.p); }
 
     void destroy() {
-        for (Buf *b : {&indeg_own, &pending, &ready, &counters, &counters64, &acc, &self_rows, &packed_w, &bias,
+        for (Buf *b : {&indeg_scratch, &indeg_own, &pending, &ready, &counters, &counters64, &acc, &self_rows, &packed_w, &bias,
                        &dev_off, &gat_el, &gat_er,
                        &gat_mcur, &gat_mnext, &gat_l, &gat_wa, &gat_z, &gat_scores, &hs_slot_of, &hs_owner, &hs_free,
                        &hs_stamp, &hs_need, &hs_ctr, &hs_keys, &hs_keys_sorted, &hs_sort_temp, &tf_z, &tf_self, &unpacked,
@@ -404,8 +405,21 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
         L->indeg = L->g.in_degree;
     } else {
         HIP_TRY(L->indeg_own.alloc(n1 * sizeof(int32_t)));
-        HIP_TRY(launch_in_degree(L->g.col_indices, L->e, static_cast<int32_t *>(L->indeg_own.p), n, s));
-        L->indeg = static_cast<const int32_t *>(L->indeg_own.p);
+        const atlas_plan *pl = L->g.plan;
+        if (pl && !pl->host && pl->n == n && pl->e == L->e && n > 0) {
+            // the plan already has every destination's messages side by side: group sizes, no pass over the CSR
+            int rc = atlas_plan_in_degree(pl, static_cast<int32_t *>(L->indeg_own.p), s);
+            if (rc != ATLAS_OK) return rc;
+            L->indeg = static_cast<const int32_t *>(L->indeg_own.p);
+        } else {
+            // an edge array in host memory is read over the link once, with one atomic per edge; in device
+            // memory large graphs are counted bucket by bucket (scratch: two bytes per edge, kept until finish)
+            const size_t sb = L->g.residency == ATLAS_RESIDENT_DEVICE ? in_degree_scratch_bytes(n, L->e) : 0;
+            if (sb) HIP_TRY(L->indeg_scratch.alloc(sb));
+            HIP_TRY(launch_in_degree(L->g.col_indices, L->e, static_cast<int32_t *>(L->indeg_own.p), n,
+                                     L->indeg_scratch.p, sb, s));
+            L->indeg = static_cast<const int32_t *>(L->indeg_own.p);
+        }
     }
     if (d.model == ATLAS_MODEL_GAT) {
         // the attention sweeps assume one group per destination and chunk
@@ -1240,6 +1254,16 @@ int atlas_plan_info(const atlas_plan_t *P, atlas_plan_info_t *info) {
     return ATLAS_OK;
 }
 
+int atlas_plan_in_degree(const atlas_plan_t *P, int32_t *in_degree, void *hip_stream) {
+    if (!P || !in_degree) return ATLAS_E_NULL;
+    if (P->host) return ATLAS_E_STATE;   // the plan's arrays are in host memory: count from the graph instead
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    HIP_TRY(launch_fill_zero(in_degree, static_cast<size_t>(P->n) * sizeof(int32_t), s));
+    for (const PlanChunk &c : P->chunks)
+        HIP_TRY(launch_plan_chunk_in_degree(c, P->src_sorted + c.edge_base, in_degree, s));
+    return ATLAS_OK;
+}
+
 int atlas_probe_copy(void *dst, const void *src, int64_t bytes, void *hip_stream) {
     if (!dst || !src) return ATLAS_E_NULL;
     if (bytes < 0 || bytes % 16 != 0) return ATLAS_E_RANGE;
@@ -1294,8 +1318,18 @@ int atlas_in_degree(const atlas_graph_t *graph, int32_t *in_degree, void *hip_st
     if (graph->num_edges > 0 && !graph->col_indices) return ATLAS_E_NULL;
     if (graph->num_vertices < 0 || graph->num_edges < 0) return ATLAS_E_RANGE;
     if (graph->num_vertices >= (int64_t(1) << 31)) return ATLAS_E_OVERFLOW;
-    HIP_TRY(launch_in_degree(graph->col_indices, graph->num_edges, in_degree, graph->num_vertices,
-                             static_cast<hipStream_t>(hip_stream)));
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const size_t sb = graph->residency == ATLAS_RESIDENT_DEVICE
+                          ? in_degree_scratch_bytes(graph->num_vertices, graph->num_edges) : 0;
+    Buf scratch;
+    if (sb) HIP_TRY(scratch.alloc(sb));
+    hipError_t e = launch_in_degree(graph->col_indices, graph->num_edges, in_degree, graph->num_vertices, scratch.p, sb, s);
+    if (sb) {
+        // the scratch goes back to the library's cache: the count must be over first
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        scratch.release();
+    }
+    if (e != hipSuccess) return hip_fail(e, "atlas_in_degree");
     return ATLAS_OK;
 }
 

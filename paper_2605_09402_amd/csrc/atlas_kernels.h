@@ -171,6 +171,10 @@ hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int6
                             int64_t src_end, int64_t edge_begin, int64_t edge_end, int32_t *src_sorted,
                             uint8_t *seen, int64_t block_sources, int64_t hot_min_edges, PlanChunk *out);
 
+// indeg[v] += messages the chunk sends to v, for every destination of a planned chunk whose arrays are in
+// device memory (src_sorted: the chunk's slice).  indeg must have been zeroed before the first chunk.
+hipError_t launch_plan_chunk_in_degree(const PlanChunk &c, const int32_t *src_sorted, int32_t *indeg, hipStream_t s);
+
 // Non-zero bytes of a device array (synchronous): how many destinations a plan's first-touch map has seen.
 hipError_t count_nonzero_bytes(const uint8_t *p, int64_t n, int64_t *out);
 
@@ -220,8 +224,13 @@ hipError_t launch_self_message(int64_t b, int64_t e, int32_t *pending, int32_t *
                                int32_t *counters, hipStream_t s);
 
 // S0 pieces.
-hipError_t launch_in_degree(const int32_t *col, int64_t num_edges, int32_t *indeg, int64_t n,
-                            hipStream_t s);
+// In-degree of every vertex.  With `scratch` of at least in_degree_scratch_bytes(n, num_edges) bytes of
+// DEVICE memory (0: the graph is small, no scratch needed) and `col` in device memory, large graphs are
+// counted bucket by bucket in LDS; without it (or for an edge array in host memory: pass nullptr) one
+// atomic per edge.  The scratch must stay valid until the stream has passed the call.
+size_t in_degree_scratch_bytes(int64_t n, int64_t num_edges);
+hipError_t launch_in_degree(const int32_t *col, int64_t num_edges, int32_t *indeg, int64_t n, void *scratch,
+                            size_t scratch_bytes, hipStream_t s);
 hipError_t launch_init_pending(const int32_t *indeg, int32_t selfmsg, int64_t n, int32_t *pending,
                                int32_t *ready, int32_t *counters, hipStream_t s);
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);

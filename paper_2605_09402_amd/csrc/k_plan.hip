@@ -310,6 +310,45 @@ done:
     return err;
 }
 
+// In-degree from a planned chunk: a group's size is the number of messages its destination
+// receives from the chunk.  One wave per 64-edge tile; every piece of a group inside the tile
+// (its last edge, or the tile's last edge) adds its length.
+namespace {
+__global__ __launch_bounds__(kBlock) void k_plan_chunk_in_degree(const int32_t *__restrict__ src_sorted,
+                                                                 const int32_t *__restrict__ grp_dst,
+                                                                 const int32_t *__restrict__ tile_grp, int64_t n_edges,
+                                                                 int32_t id_mask, int32_t *indeg) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = static_cast<int64_t>(blockIdx.x) * (kBlock / 64) + (threadIdx.x >> 6);
+    const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (kBlock / 64);
+    const int64_t ntiles = (n_edges + 63) / 64;
+    for (int64_t t = wave; t < ntiles; t += nwaves) {
+        const int64_t e0 = t * 64;
+        const int64_t left = n_edges - e0;
+        const int cnt = left < 64 ? static_cast<int>(left) : 64;
+        int32_t s = 0;
+        if (lane < cnt) s = src_sorted[e0 + lane];
+        const bool is_end = lane < cnt && s < 0;
+        const uint64_t below = __ballot(is_end) & ((1ull << lane) - 1ull);
+        if (is_end || lane == cnt - 1) {
+            const int32_t v = grp_dst[tile_grp[t] + __popcll(below)] & id_mask;
+            const int prev_end = below ? 63 - __clzll(static_cast<long long>(below)) : -1;
+            atomicAdd(&indeg[v], lane - prev_end);
+        }
+    }
+}
+}  // namespace
+
+hipError_t launch_plan_chunk_in_degree(const PlanChunk &c, const int32_t *src_sorted, int32_t *indeg, hipStream_t s) {
+    if (c.n_edges <= 0) return hipSuccess;
+    const int64_t ntiles = (c.n_edges + 63) / 64;
+    int64_t blocks = (ntiles + (kBlock / 64) - 1) / (kBlock / 64);
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_plan_chunk_in_degree, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, s, src_sorted,
+                       c.grp_dst, c.tile_grp, c.n_edges, c.blocked ? 0x3fffffff : 0x7fffffff, indeg);
+    return hipGetLastError();
+}
+
 hipError_t count_nonzero_bytes(const uint8_t *p, int64_t n, int64_t *out) {
     *out = 0;
     if (n <= 0) return hipSuccess;

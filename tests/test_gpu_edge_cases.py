@@ -349,3 +349,72 @@ def test_pinned_plan_with_four_byte_words(oracle, H, atlas, piece):
     H.check_outputs(oracle, case, H.run_gpu(case, pinned_host=True, plan=True, planned_only=True, plan_block=(64, 8),
                                             piece_tiles=piece))
 
+
+
+@pytest.mark.parametrize("ids", ["raw", "degree_ordered", "one_hub"])
+@pytest.mark.parametrize("residency", ["device", "pinned_host"])
+def test_in_degree_of_a_large_graph(oracle, atlas, ids, residency):
+    """Graphs above 2^15 vertices and 2^22 edges in device memory are counted bucket by bucket
+    in LDS (buckets of 2^15 ids; a heavy bucket is counted in several slices and merged), host
+    edge arrays with one atomic per edge: the whole array against the oracle, bit-exact, with a
+    vertex count that is no multiple of the bucket size, with degree-ordered ids (first bucket
+    far heavier than the rest), and with every edge pointing at one vertex of the last bucket."""
+    dev = torch.device("cuda:0")
+    g = gen.rmat_graph(SEED + 61, 18, 20)
+    off, col = gen.build_csr(g)
+    n = g.n - 12_345                                    # ragged last bucket
+    col = col[col < n].contiguous()
+    if ids == "degree_ordered":
+        new_of_old, _ = oracle.reorder_indegree_desc(oracle.in_degree(n, col.numpy()))
+        col = torch.from_numpy(new_of_old)[col.to(torch.int64)].contiguous()
+    elif ids == "one_hub":
+        col = torch.full_like(col, n - 1)
+    e = col.numel()
+    assert n > (1 << 15) and e >= (1 << 22)
+    col_t = col.to(dev) if residency == "device" else col.pin_memory()
+    res = atlas.RESIDENT_DEVICE if residency == "device" else atlas.RESIDENT_PINNED_HOST
+    indeg = torch.full((n,), -7, dtype=torch.int32, device=dev)
+    atlas.atlas_in_degree(atlas.make_graph(n, e, None, col_t, None, res), indeg)
+    torch.cuda.synchronize()
+    assert np.array_equal(indeg.cpu().numpy().astype(np.int64), oracle.in_degree(n, col.numpy()))
+    # twice in a row: the scratch comes back from the library's cache with the first call's contents
+    atlas.atlas_in_degree(atlas.make_graph(n, e, None, col_t, None, res), indeg)
+    torch.cuda.synchronize()
+    assert np.array_equal(indeg.cpu().numpy().astype(np.int64), oracle.in_degree(n, col.numpy()))
+
+
+@pytest.mark.parametrize("plan_block", [None, (256, 16)])
+def test_in_degree_from_the_plan(oracle, H, atlas, plan_block):
+    """atlas_plan_in_degree: group sizes summed over the chunks equal the oracle's in-degree, for
+    plain and source-blocked plans (several groups per destination and chunk); a layer on a graph
+    with a plan and no in_degree counts this way (checked through the layer's own array); plans
+    of pinned-host graphs refuse."""
+    dev = torch.device("cuda:0")
+    g = gen.rmat_graph(SEED + 67, 13, 24)
+    off, col = gen.build_csr(g)
+    n, e = g.n, col.numel()
+    off_d, col_d = off.to(dev), col.to(dev)
+    pg = atlas.make_graph(n, e, off_d, col_d)
+    plan = atlas.atlas_plan_create_blocked(pg, 1000, *plan_block) if plan_block else atlas.atlas_plan_create(pg, 1000)
+    try:
+        indeg = torch.full((n,), -3, dtype=torch.int32, device=dev)
+        atlas.atlas_plan_in_degree(plan, indeg)
+        torch.cuda.synchronize()
+        assert np.array_equal(indeg.cpu().numpy().astype(np.int64), oracle.in_degree(n, col.numpy()))
+        info = atlas.atlas_plan_info(plan)
+        assert info["num_edges"] == e and info["num_chunks"] == (n + 999) // 1000
+        assert info["num_first_groups"] == int((oracle.in_degree(n, col.numpy()) > 0).sum())
+    finally:
+        atlas.atlas_plan_destroy(plan)
+    case = H.make_case("sage", g, SEED + 67, [64, 64], 1000)
+    run = H.run_gpu(case, snapshots=True, plan=True, plan_block=plan_block)    # in_degree not given: counted at init
+    H.check_integers(oracle, case, run)
+    H.check_outputs(oracle, case, run)
+    hp = atlas.atlas_plan_create(atlas.make_graph(n, e, off.pin_memory(), col.pin_memory(), None,
+                                                  atlas.RESIDENT_PINNED_HOST), 1000)
+    try:
+        with pytest.raises(atlas.AtlasError) as ei:
+            atlas.atlas_plan_in_degree(hp, indeg)
+        assert ei.value.status == atlas.E_STATE
+    finally:
+        atlas.atlas_plan_destroy(hp)
