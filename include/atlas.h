@@ -97,6 +97,9 @@ enum atlas_flags {
                                     a plan, for GAT and for graphs of 2^30 vertices or more (their
                                     plans lack the list of rows to clear).  With it, ATLAS_DBG_ACC rows of vertices
                                     that have received nothing yet are undefined. */
+    ATLAS_FLAG_CSR_STREAM = 16,  /* never regroup a chunk on the fly: a chunk without a planned chunk is pushed
+                                    straight from the CSR with fp32 atomics, whatever its length (see
+                                    atlas_broadcast_chunk) */
     ATLAS_FLAG_TRANSFORM_FIRST = 8 /* SAGE_MEAN / GCN_SYM / GIN: the weight matrix is
                                     applied to each chunk's rows before they are pushed (the linear map
                                     commutes with the neighbour sum), so messages and accumulators are
@@ -224,10 +227,14 @@ typedef struct {
     int64_t hot_reloads;        /* bounded store: rows read back from the cold tier         */
     int64_t hot_peak_slots;     /* bounded store: most rows in use at once                  */
     int64_t chunks_planned;     /* chunks pushed from the plan (destination-grouped edges)  */
-    int64_t chunks_csr_stream;  /* chunks pushed straight from the CSR with fp32 atomics: no
-                                   plan, or a range that is not one of the plan's chunks.
-                                   About ten times slower per edge; chunks_planned +
-                                   chunks_csr_stream == num_chunks                          */
+    int64_t chunks_csr_stream;  /* chunks pushed straight from the CSR with fp32 atomics (short
+                                   chunks without a planned chunk, or ATLAS_FLAG_CSR_STREAM):
+                                   about ten times slower per edge than the other two       */
+    int64_t chunks_regrouped;   /* chunks without a planned chunk that were regrouped by
+                                   destination on the fly; the three counts add up to
+                                   num_chunks                                               */
+    float ms_regroup;           /* host time of that regrouping (it is synchronous), always
+                                   measured                                                 */
 } atlas_layer_stats_t;
 
 /* Create the state of one layer (Sec. 3.4: pending-message tracker and
@@ -263,6 +270,13 @@ int atlas_attention_prepass(atlas_layer_t *layer, int64_t src_begin, int64_t src
  * the ready list when its count reaches zero.  Chunks must arrive in ascending
  * contiguous order starting at 0 ("strictly ordered", Sec. 3.4).  Only
  * enqueues; `emb` must stay valid until the stream has passed this point.
+ * Which way the chunk's edges are visited: from the graph's plan when the range is
+ * one of its chunks; else, when the chunk has at least 2^20 edges, regrouped by
+ * destination on the spot (the plan's construction for this chunk alone, thrown
+ * away afterwards: the call then waits for the stream and sorts before it
+ * enqueues; about a third of the time of the third way at scale 26); else straight
+ * from the CSR with one fp32 atomic row add per edge.  Results are the same sums in
+ * another order; atlas_layer_stats_t says which way each chunk went.
  * Errors: E_NULL, E_RANGE, E_ORDER, E_STATE, E_HIP. */
 int atlas_broadcast_chunk(atlas_layer_t *layer, int64_t src_begin, int64_t src_end,
                           const void *emb, void *hip_stream);
@@ -289,7 +303,7 @@ int atlas_layer_finish(atlas_layer_t *layer, atlas_layer_stats_t *stats);
  * the group's size in one step.  Results are those of the plain edge stream
  * (same sums up to fp32 rounding order, same counts, same ready sets).
  * atlas_broadcast_chunk uses the plan for chunks that coincide with a planned
- * chunk and falls back to the CSR stream for any other range.
+ * chunk; any other range is regrouped on the fly or pushed from the CSR (see there).
  * Synchronous.  The plan holds about 4 bytes per edge and lives where the graph
  * lives: device memory for DEVICE graphs; library-owned pinned host memory for
  * PINNED_HOST graphs (each chunk's CSR slice is staged into HBM, regrouped

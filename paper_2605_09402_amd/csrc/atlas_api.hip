@@ -8,6 +8,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <chrono>
 #include <mutex>
 #include <new>
 #include <string>
@@ -177,7 +178,13 @@ struct atlas_layer {
     int64_t next_src = 0;
     uint32_t run_tickets = 0;          // tickets drawn so far from the grouped aggregation's run counter
     int64_t num_chunks = 0, num_flushes = 0;
-    int64_t chunks_planned = 0, chunks_csr = 0;   // which aggregation path each chunk took
+    int64_t chunks_planned = 0, chunks_csr = 0, chunks_regrouped = 0;   // which aggregation path each chunk took
+    // Chunks without a planned chunk are regrouped by destination on the fly (the plan's construction, for
+    // this chunk only, thrown away afterwards) when they are long enough to pay for the sort.
+    PlanWork *regroup_work = nullptr;
+    PlanChunk cur_regroup{};          // arrays of the chunk regrouped last; freed before the next one is built
+    Buf regroup_src;                  // its edge words
+    double ms_regroup = 0.0;          // host time spent regrouping (the sort is synchronous)
     int64_t bytes_h2d = 0;
 
     // pinned-host loader
@@ -199,6 +206,12 @@ struct atlas_layer {
 
     int32_t *ctr() { return static_cast<int32_t *>(counters.p); }
 
+    void free_regrouped() {
+        if (cur_regroup.grp_dst) (void)hipFree(cur_regroup.grp_dst);
+        if (cur_regroup.tile_grp) (void)hipFree(cur_regroup.tile_grp);
+        cur_regroup = PlanChunk{};
+    }
+
     void destroy() {
         for (Buf *b : {&indeg_scratch, &indeg_own, &pending, &ready, &counters, &counters64, &acc, &self_rows, &packed_w, &bias,
                        &dev_off, &gat_el, &gat_er,
@@ -206,6 +219,10 @@ struct atlas_layer {
                        &hs_stamp, &hs_need, &hs_ctr, &hs_keys, &hs_keys_sorted, &hs_sort_temp, &tf_z, &tf_self, &unpacked,
                        &packed_w2})
             b->release();
+        free_regrouped();
+        delete regroup_work;
+        regroup_work = nullptr;
+        regroup_src.release();
         for (auto &v : piece_ev)
             for (hipEvent_t e : v) (void)hipEventDestroy(e);
         for (Buf &b : stage_col) b.release();
@@ -674,6 +691,35 @@ int make_room_for_chunk(atlas_layer *L, const PlanChunk *pc, int64_t src_begin, 
     return ATLAS_OK;
 }
 
+// A chunk of at least this many edges that has no planned chunk is regrouped on the fly.
+constexpr int64_t kRegroupMinEdges = int64_t(1) << 20;
+
+// Regroup the edges [e0, e1) of sources [src_begin, src_end) by destination, as a plan would have
+// (Sec. 3.3: the chunk is what is streamed; only the order in which its edges are visited changes).
+// `col` is addressed by global edge number.  Synchronous: the construction sorts on the default stream,
+// and the arrays of the chunk regrouped before this one are released first, so the layer's stream is
+// drained before and the result is complete after.
+int regroup_chunk(atlas_layer *L, int64_t src_begin, int64_t src_end, int64_t e0, int64_t e1, const int32_t *col,
+                  hipStream_t s) {
+    const auto t0 = std::chrono::steady_clock::now();
+    HIP_TRY(hipStreamSynchronize(s));
+    if (L->copy_stream) HIP_TRY(hipStreamSynchronize(L->copy_stream));
+    L->free_regrouped();
+    if (!L->regroup_work) {
+        L->regroup_work = new (std::nothrow) PlanWork();
+        if (!L->regroup_work) return ATLAS_E_NOMEM;
+    }
+    const size_t words = static_cast<size_t>(e1 - e0) * sizeof(int32_t);
+    if (!L->regroup_src.p || L->regroup_src.bytes < words) {
+        L->regroup_src.release();
+        HIP_TRY(L->regroup_src.alloc(words));
+    }
+    HIP_TRY(build_plan_chunk(L->off_dev, col, L->n, src_begin, src_end, e0, e1, static_cast<int32_t *>(L->regroup_src.p),
+                             nullptr, 0, 0, false, *L->regroup_work, &L->cur_regroup));
+    L->ms_regroup += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    return ATLAS_OK;
+}
+
 GatState gat_state(atlas_layer *L) {
     GatState g;
     g.el = static_cast<const float *>(L->gat_el.p);
@@ -845,6 +891,25 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
     }
 
     int rc = ATLAS_OK;
+    bool regrouped = false;
+    if (!pc && !(d.flags & ATLAS_FLAG_CSR_STREAM) && L->n > 0 &&
+        static_cast<double>(src_end - src_begin) * (static_cast<double>(L->e) / static_cast<double>(L->n)) >=
+            static_cast<double>(kRegroupMinEdges)) {
+        // long enough on the graph's average: look at the chunk's real edge count
+        int64_t eb[2] = {0, 0};
+        if (L->g.residency == ATLAS_RESIDENT_PINNED_HOST) {
+            eb[0] = L->g.row_offsets[src_begin];
+            eb[1] = L->g.row_offsets[src_end];
+        } else {
+            HIP_TRY(hipMemcpy(&eb[0], L->g.row_offsets + src_begin, sizeof(int64_t), hipMemcpyDeviceToHost));
+            HIP_TRY(hipMemcpy(&eb[1], L->g.row_offsets + src_end, sizeof(int64_t), hipMemcpyDeviceToHost));
+        }
+        if (eb[1] - eb[0] >= kRegroupMinEdges && eb[1] - eb[0] < (int64_t(1) << 32)) {
+            if ((rc = regroup_chunk(L, src_begin, src_end, eb[0], eb[1], a.col - a.col_base, s)) != ATLAS_OK) return rc;
+            pc = &L->cur_regroup;
+            regrouped = true;
+        }
+    }
     if (L->selfmsg) {
         if ((rc = start_span(L, L->t_self, s)) != ATLAS_OK) return rc;
         if (self_dst && emb_dev)
@@ -882,7 +947,11 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         a.in_dt = 0;
     }
     if (pc) {
-        if (!plan->host) {
+        if (regrouped) {
+            ga.src_sorted = static_cast<const int32_t *>(L->regroup_src.p);
+            ga.grp_dst = pc->grp_dst;
+            ga.tile_grp = pc->tile_grp;
+        } else if (!plan->host) {
             ga.src_sorted = plan->src_sorted + pc->edge_base;
             ga.grp_dst = pc->grp_dst;
             ga.tile_grp = pc->tile_grp;
@@ -958,7 +1027,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
     }
     L->next_src = src_end;
     L->num_chunks += 1;
-    (pc ? L->chunks_planned : L->chunks_csr) += 1;
+    (regrouped ? L->chunks_regrouped : pc ? L->chunks_planned : L->chunks_csr) += 1;
     return ATLAS_OK;
 }
 
@@ -1062,6 +1131,8 @@ int atlas_layer_finish(atlas_layer_t *L, atlas_layer_stats_t *stats) {
         stats->bytes_copied_h2d = L->bytes_h2d;
         stats->chunks_planned = L->chunks_planned;
         stats->chunks_csr_stream = L->chunks_csr;
+        stats->chunks_regrouped = L->chunks_regrouped;
+        stats->ms_regroup = static_cast<float>(L->ms_regroup);
         if (L->bounded) {
             int32_t hc[HS_COUNT] = {0};
             if (hipMemcpy(hc, L->hs.ctr, sizeof(hc), hipMemcpyDeviceToHost) == hipSuccess) {
@@ -1138,6 +1209,8 @@ int atlas_plan_create_blocked(const atlas_graph_t *graph, int64_t chunk_sources,
             rc = hip_fail(e, "alloc(plan first-touch map)");
     }
     int64_t ebeg = 0;
+    PlanWork work;   // freed when this function returns
+    GrowBuf off_stage, col_stage, src_stage;   // host plans: the chunk's CSR slice and regrouped words in HBM
     if (rc == ATLAS_OK && nchunks > 0 && (e = offset_at(0, &ebeg)) != hipSuccess) rc = hip_fail(e, "row_offsets");
     for (int64_t k = 0; rc == ATLAS_OK && k < nchunks; ++k) {
         const int64_t b = k * chunk_sources, en = std::min(P->n, b + chunk_sources);
@@ -1147,21 +1220,23 @@ int atlas_plan_create_blocked(const atlas_graph_t *graph, int64_t chunk_sources,
         PlanChunk pc;
         if (!P->host) {
             e = build_plan_chunk(graph->row_offsets, graph->col_indices, P->n, b, en, ebeg, eend,
-                                 P->src_sorted + ebeg, seen, block_sources, hot_min_edges, &pc);
+                                 P->src_sorted + ebeg, seen, block_sources, hot_min_edges, true, work, &pc);
             if (e != hipSuccess) { rc = hip_fail(e, "build_plan_chunk"); break; }
         } else {
             // stage the chunk's CSR slice into HBM, regroup there, bring the result back
-            int64_t *off_tmp = nullptr;
-            int32_t *col_tmp = nullptr, *src_tmp = nullptr;
             const size_t nsrc = static_cast<size_t>(en - b);
             const size_t ne1 = static_cast<size_t>(std::max<int64_t>(ne, 1));
-            if ((e = hipMalloc(reinterpret_cast<void **>(&off_tmp), (nsrc + 1) * sizeof(int64_t))) == hipSuccess &&
-                (e = hipMalloc(reinterpret_cast<void **>(&col_tmp), (ne1 + 3) * 4)) == hipSuccess &&   // also holds the packed words
-                (e = hipMalloc(reinterpret_cast<void **>(&src_tmp), ne1 * 4)) == hipSuccess &&
-                (e = hipMemcpy(off_tmp, graph->row_offsets + b, (nsrc + 1) * sizeof(int64_t), hipMemcpyHostToDevice)) == hipSuccess &&
-                (ne == 0 || (e = hipMemcpy(col_tmp, graph->col_indices + ebeg, static_cast<size_t>(ne) * 4, hipMemcpyHostToDevice)) == hipSuccess)) {
-                e = build_plan_chunk(off_tmp - b, col_tmp - ebeg, P->n, b, en, ebeg, eend, src_tmp, seen, block_sources,
-                                     hot_min_edges, &pc);
+            if ((e = off_stage.need((nsrc + 1) * sizeof(int64_t))) == hipSuccess &&
+                (e = col_stage.need((ne1 + 3) * 4)) == hipSuccess &&   // also holds the packed words
+                (e = src_stage.need(ne1 * 4)) == hipSuccess) {
+                int64_t *off_tmp = static_cast<int64_t *>(off_stage.p);
+                int32_t *col_tmp = static_cast<int32_t *>(col_stage.p), *src_tmp = static_cast<int32_t *>(src_stage.p);
+                e = hipMemcpy(off_tmp, graph->row_offsets + b, (nsrc + 1) * sizeof(int64_t), hipMemcpyHostToDevice);
+                if (e == hipSuccess && ne > 0)
+                    e = hipMemcpy(col_tmp, graph->col_indices + ebeg, static_cast<size_t>(ne) * 4, hipMemcpyHostToDevice);
+                if (e == hipSuccess)
+                    e = build_plan_chunk(off_tmp - b, col_tmp - ebeg, P->n, b, en, ebeg, eend, src_tmp, seen, block_sources,
+                                         hot_min_edges, true, work, &pc);
                 if (e == hipSuccess && ne > 0 && packed) {
                     // the CSR slice is no longer needed: its buffer takes the packed words
                     const size_t pb = packed24_bytes(ne);
@@ -1186,9 +1261,6 @@ int atlas_plan_create_blocked(const atlas_graph_t *graph, int64_t chunk_sources,
                     pc.tile_grp = t_h;
                 }
             }
-            if (off_tmp) (void)hipFree(off_tmp);
-            if (col_tmp) (void)hipFree(col_tmp);
-            if (src_tmp) (void)hipFree(src_tmp);
             if (e != hipSuccess) {
                 P->chunks.push_back(pc);  // so that destroy releases what was allocated
                 rc = hip_fail(e, "build_plan_chunk(host)");
@@ -1200,6 +1272,7 @@ int atlas_plan_create_blocked(const atlas_graph_t *graph, int64_t chunk_sources,
         P->max_stage_bytes = std::max(P->max_stage_bytes, stage_bytes_of(pc, packed));
         ebeg = eend;
     }
+    for (GrowBuf *gb : {&off_stage, &col_stage, &src_stage}) gb->release();
     if (rc == ATLAS_OK && seen && (e = count_nonzero_bytes(seen, P->n, &P->n_first)) != hipSuccess)
         rc = hip_fail(e, "plan first-touch count");
     if (seen) (void)hipFree(seen);

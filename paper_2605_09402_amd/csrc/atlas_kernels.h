@@ -162,14 +162,34 @@ hipError_t launch_aggregate_grouped(const GroupedArgs &a, uint32_t *run_tickets,
 // launch_zero_rows; a launch whose nruns is still 0 chooses them itself.
 hipError_t plan_runs(GroupedArgs &a);
 
-// Plan construction for one chunk (synchronous).  off_dev is addressed by global
+// Work arrays of the plan construction, kept from chunk to chunk (allocating and freeing tens of
+// gigabytes per chunk costs more than some of the passes) and grown when a chunk needs more.
+struct GrowBuf {
+    void *p = nullptr;
+    size_t cap = 0;
+    hipError_t need(size_t bytes);
+    void release();
+};
+struct PlanWork {
+    GrowBuf tmp_src, dst_sorted, heads, temp, bkey, bkey_sorted, bpos, bpos_sorted, gstart, src_new, rows, cnt;
+    PlanWork() = default;
+    PlanWork(const PlanWork &) = delete;
+    PlanWork &operator=(const PlanWork &) = delete;
+    ~PlanWork();
+};
+
+// Plan construction for one chunk (synchronous, on the default stream).  off_dev is addressed by global
 // source id and col_dev by global edge number (only [src_begin, src_end] and
 // [edge_begin, edge_end) are touched); `seen` is the plan-wide N-byte first-touch map
-// (zeroed before the first chunk, chunks built in streaming order); src_sorted receives the chunk's
-// edge_end - edge_begin entries; grp_dst and tile_grp are allocated with hipMalloc.
+// (zeroed before the first chunk, chunks built in streaming order; nullptr: no group is marked as its
+// destination's first, as for a chunk regrouped on its own, whose neighbours may have gone another way);
+// src_sorted receives the chunk's
+// edge_end - edge_begin entries; grp_dst and tile_grp (and, with want_zero_rows, the list of rows a
+// planned-only layer clears) are allocated with hipMalloc.
 hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int64_t n, int64_t src_begin,
                             int64_t src_end, int64_t edge_begin, int64_t edge_end, int32_t *src_sorted,
-                            uint8_t *seen, int64_t block_sources, int64_t hot_min_edges, PlanChunk *out);
+                            uint8_t *seen, int64_t block_sources, int64_t hot_min_edges, bool want_zero_rows,
+                            PlanWork &w, PlanChunk *out);
 
 // indeg[v] += messages the chunk sends to v, for every destination of a planned chunk whose arrays are in
 // device memory (src_sorted: the chunk's slice).  indeg must have been zeroed before the first chunk.

@@ -72,8 +72,9 @@ __global__ void k_emit_groups(const uint32_t *__restrict__ dst_sorted, const uin
     const uint32_t g = gidx[i] - 1u;
     if (i == 0 || gidx[i - 1] != gidx[i]) {
         const uint32_t v = dst_sorted[i];
-        const bool first = seen[v] == 0;
-        seen[v] = 1;
+        // without a first-touch map (a chunk regrouped on its own) no group claims to be its destination's first
+        const bool first = seen && seen[v] == 0;
+        if (seen) seen[v] = 1;
         // source-blocked chunks: the destination has a group in every source block
         const uint32_t multi = (block_key && block_key[i] < n_blocks) ? 0x40000000u : 0u;
         grp_dst[g] = static_cast<int32_t>((first ? (v | 0x80000000u) : v) | multi);
@@ -158,9 +159,30 @@ struct MaxOp {
 
 }  // namespace
 
+PlanWork::~PlanWork() {
+    for (GrowBuf *b : {&tmp_src, &dst_sorted, &heads, &temp, &bkey, &bkey_sorted, &bpos, &bpos_sorted, &gstart, &src_new,
+                       &rows, &cnt})
+        b->release();
+}
+
+hipError_t GrowBuf::need(size_t bytes) {
+    if (bytes <= cap && p) return hipSuccess;
+    release();
+    const hipError_t e = hipMalloc(&p, bytes > 0 ? bytes : 16);
+    if (e != hipSuccess) { p = nullptr; return e; }
+    cap = bytes;
+    return hipSuccess;
+}
+void GrowBuf::release() {
+    if (p) (void)hipFree(p);
+    p = nullptr;
+    cap = 0;
+}
+
 hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int64_t n, int64_t src_begin,
                             int64_t src_end, int64_t edge_begin, int64_t edge_end, int32_t *src_sorted,
-                            uint8_t *seen, int64_t block_sources, int64_t hot_min_edges, PlanChunk *out) {
+                            uint8_t *seen, int64_t block_sources, int64_t hot_min_edges, bool want_zero_rows,
+                            PlanWork &w, PlanChunk *out) {
     *out = PlanChunk{};
     out->edge_base = edge_begin;
     out->n_edges = edge_end - edge_begin;
@@ -173,14 +195,8 @@ hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int6
     const int64_t n_blocks64 = block_sources > 0 ? (src_end - src_begin + block_sources - 1) / block_sources : 0;
     const bool blocked = n_blocks64 > 1;
     const uint32_t n_blocks = static_cast<uint32_t>(n_blocks64);
-    uint32_t *bkey = nullptr, *bkey_sorted = nullptr, *bpos = nullptr, *bpos_sorted = nullptr, *gstart = nullptr;
-    int32_t *src_new = nullptr;
     size_t temp_bsort = 0;
     int bkey_bits = 1;
-    int32_t *tmp_src = nullptr;   // source per edge (CSR order); reused for the group prefix sum
-    uint32_t *dst_sorted = nullptr;
-    uint32_t *heads = nullptr;
-    void *temp = nullptr;
     size_t temp_sort = 0, temp_scan_max = 0, temp_scan_sum = 0, temp_bytes = 0;
     const uint32_t *keys_in = reinterpret_cast<const uint32_t *>(col_dev + edge_begin);
     uint32_t last = 0;
@@ -188,29 +204,42 @@ hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int6
     while (end_bit < 32 && (int64_t(1) << end_bit) < n) ++end_bit;
     const size_t count = static_cast<size_t>(ne);
 
-    if ((err = hipMalloc(&tmp_src, count * 4)) != hipSuccess) goto done;
-    if ((err = hipMalloc(&dst_sorted, count * 4)) != hipSuccess) goto done;
-    if ((err = hipMalloc(&heads, count * 4)) != hipSuccess) goto done;
+    // work arrays: kept from chunk to chunk, grown when a chunk is larger than any before it
+    if ((err = w.tmp_src.need(count * 4)) != hipSuccess) return err;
+    if ((err = w.dst_sorted.need(count * 4)) != hipSuccess) return err;
+    if ((err = w.heads.need(count * 4)) != hipSuccess) return err;
+    int32_t *tmp_src = static_cast<int32_t *>(w.tmp_src.p);   // source per edge (CSR order); reused for the group prefix sum
+    uint32_t *dst_sorted = static_cast<uint32_t *>(w.dst_sorted.p);
+    uint32_t *heads = static_cast<uint32_t *>(w.heads.p);
+    uint32_t *bkey = nullptr, *bkey_sorted = nullptr, *bpos = nullptr, *bpos_sorted = nullptr, *gstart = nullptr;
+    int32_t *src_new = nullptr;
     if ((err = rocprim::radix_sort_pairs(nullptr, temp_sort, keys_in, dst_sorted, tmp_src, src_sorted, count, 0,
-                                         end_bit, nullptr)) != hipSuccess) goto done;
-    if ((err = rocprim::inclusive_scan(nullptr, temp_scan_max, tmp_src, tmp_src, count, MaxOp(), nullptr)) != hipSuccess) goto done;
+                                         end_bit, nullptr)) != hipSuccess) return err;
+    if ((err = rocprim::inclusive_scan(nullptr, temp_scan_max, tmp_src, tmp_src, count, MaxOp(), nullptr)) != hipSuccess) return err;
     if ((err = rocprim::inclusive_scan(nullptr, temp_scan_sum, heads, reinterpret_cast<uint32_t *>(tmp_src), count,
-                                       rocprim::plus<uint32_t>(), nullptr)) != hipSuccess) goto done;
+                                       rocprim::plus<uint32_t>(), nullptr)) != hipSuccess) return err;
     temp_bytes = temp_sort > temp_scan_max ? temp_sort : temp_scan_max;
     if (temp_scan_sum > temp_bytes) temp_bytes = temp_scan_sum;
     if (blocked) {
         while (bkey_bits < 32 && (uint64_t(1) << bkey_bits) <= n_blocks) ++bkey_bits;   // keys 0 .. n_blocks
-        if ((err = hipMalloc(&bkey, count * 4)) != hipSuccess) goto done;
-        if ((err = hipMalloc(&bkey_sorted, count * 4)) != hipSuccess) goto done;
-        if ((err = hipMalloc(&bpos, count * 4)) != hipSuccess) goto done;
-        if ((err = hipMalloc(&bpos_sorted, count * 4)) != hipSuccess) goto done;
-        if ((err = hipMalloc(&gstart, (count + 1) * 4)) != hipSuccess) goto done;
-        if ((err = hipMalloc(&src_new, count * 4)) != hipSuccess) goto done;
+        if ((err = w.bkey.need(count * 4)) != hipSuccess) return err;
+        if ((err = w.bkey_sorted.need(count * 4)) != hipSuccess) return err;
+        if ((err = w.bpos.need(count * 4)) != hipSuccess) return err;
+        if ((err = w.bpos_sorted.need(count * 4)) != hipSuccess) return err;
+        if ((err = w.gstart.need((count + 1) * 4)) != hipSuccess) return err;
+        if ((err = w.src_new.need(count * 4)) != hipSuccess) return err;
+        bkey = static_cast<uint32_t *>(w.bkey.p);
+        bkey_sorted = static_cast<uint32_t *>(w.bkey_sorted.p);
+        bpos = static_cast<uint32_t *>(w.bpos.p);
+        bpos_sorted = static_cast<uint32_t *>(w.bpos_sorted.p);
+        gstart = static_cast<uint32_t *>(w.gstart.p);
+        src_new = static_cast<int32_t *>(w.src_new.p);
         if ((err = rocprim::radix_sort_pairs(nullptr, temp_bsort, bkey, bkey_sorted, bpos, bpos_sorted, count, 0,
-                                             bkey_bits, nullptr)) != hipSuccess) goto done;
+                                             bkey_bits, nullptr)) != hipSuccess) return err;
         if (temp_bsort > temp_bytes) temp_bytes = temp_bsort;
     }
-    if ((err = hipMalloc(&temp, temp_bytes > 0 ? temp_bytes : 16)) != hipSuccess) goto done;
+    if ((err = w.temp.need(temp_bytes > 0 ? temp_bytes : 16)) != hipSuccess) return err;
+    void *temp = w.temp.p;
 
     // 1. source of every edge
     if ((err = hipMemsetAsync(tmp_src, 0, count * 4, nullptr)) != hipSuccess) goto done;
@@ -259,23 +288,23 @@ hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int6
                        reinterpret_cast<const uint32_t *>(tmp_src), ne, out->grp_dst, out->tile_grp, seen,
                        blocked ? bkey_sorted : nullptr, n_blocks);
     if ((err = hipGetLastError()) != hipSuccess) goto done;
-    if (n < (int64_t(1) << 30)) {
+    if (want_zero_rows && n < (int64_t(1) << 30)) {
         // rows to clear for planned-only layers (first groups that several waves add to)
         uint32_t *gs = heads;   // free again: start position of every group
-        unsigned int *cnt = nullptr, n_zero = 0;
+        unsigned int n_zero = 0;
         hipLaunchKernelGGL(k_group_starts_only, dim3(blocks_for(ne)), dim3(kBlock), 0, nullptr,
                            reinterpret_cast<const uint32_t *>(tmp_src), ne, gs);
-        if ((err = hipMalloc(&cnt, sizeof(unsigned int))) != hipSuccess) goto done;
-        if ((err = hipMemsetAsync(cnt, 0, sizeof(unsigned int), nullptr)) != hipSuccess) { (void)hipFree(cnt); goto done; }
+        if ((err = w.cnt.need(sizeof(unsigned int))) != hipSuccess) goto done;
+        unsigned int *cnt = static_cast<unsigned int *>(w.cnt.p);
+        if ((err = hipMemsetAsync(cnt, 0, sizeof(unsigned int), nullptr)) != hipSuccess) goto done;
         // worst case one row per group; the list is trimmed below
-        int32_t *rows = nullptr;   // [last] rows, then [last][2] spans
-        if ((err = hipMalloc(&rows, static_cast<size_t>(last) * 12)) != hipSuccess) { (void)hipFree(cnt); goto done; }
+        if ((err = w.rows.need(static_cast<size_t>(last) * 12)) != hipSuccess) goto done;
+        int32_t *rows = static_cast<int32_t *>(w.rows.p);   // [last] rows, then [last][2] spans
         int32_t *spans = rows + last;
         hipLaunchKernelGGL(k_collect_zero_rows, dim3(blocks_for(last)), dim3(kBlock), 0, nullptr, out->grp_dst, gs,
                            static_cast<int64_t>(last), ne, rows, spans, cnt);
-        err = hipMemcpy(&n_zero, cnt, sizeof(unsigned int), hipMemcpyDeviceToHost);
-        (void)hipFree(cnt);
-        if (err == hipSuccess && n_zero > 0) {
+        if ((err = hipMemcpy(&n_zero, cnt, sizeof(unsigned int), hipMemcpyDeviceToHost)) != hipSuccess) goto done;
+        if (n_zero > 0) {
             err = hipMalloc(&out->zero_rows, static_cast<size_t>(n_zero) * 4);
             if (err == hipSuccess)
                 err = hipMemcpy(out->zero_rows, rows, static_cast<size_t>(n_zero) * 4, hipMemcpyDeviceToDevice);
@@ -283,21 +312,14 @@ hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int6
             if (err == hipSuccess)
                 err = hipMemcpy(out->zero_span, spans, static_cast<size_t>(n_zero) * 8, hipMemcpyDeviceToDevice);
         }
-        (void)hipFree(rows);
         if (err != hipSuccess) goto done;
         out->n_zero_rows = n_zero;
         out->has_zero_rows = true;
     }
     err = hipStreamSynchronize(nullptr);
 done:
-    for (void *p : {static_cast<void *>(bkey), static_cast<void *>(bkey_sorted), static_cast<void *>(bpos),
-                    static_cast<void *>(bpos_sorted), static_cast<void *>(gstart), static_cast<void *>(src_new)})
-        if (p) (void)hipFree(p);
-    if (temp) (void)hipFree(temp);
-    if (heads) (void)hipFree(heads);
-    if (dst_sorted) (void)hipFree(dst_sorted);
-    if (tmp_src) (void)hipFree(tmp_src);
     if (err != hipSuccess) {
+        (void)hipStreamSynchronize(nullptr);
         if (out->grp_dst) (void)hipFree(out->grp_dst);
         if (out->tile_grp) (void)hipFree(out->tile_grp);
         if (out->zero_rows) (void)hipFree(out->zero_rows);

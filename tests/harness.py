@@ -132,14 +132,16 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
             plan: bool = False, plan_chunk: Optional[int] = None, emb_resident: bool = False,
             planned_only: bool = False, hot_slots: int = 0, evict_policy: int = 0,
             transform_first: bool = False, plan_block: Optional[tuple] = None,
-            device_later: bool = False, tiles_per_run: int = 0, piece_tiles: int = 0) -> GpuRun:
+            device_later: bool = False, tiles_per_run: int = 0, piece_tiles: int = 0,
+            csr_stream: bool = False) -> GpuRun:
     """Drive all layers through the C ABI.  With pinned_host the graph and the
     layer-0 features stay in pinned host memory and are staged by the library.
     planned_only sets ATLAS_FLAG_PLANNED_ONLY (no zero fill of the accumulators;
     the buffers then still hold whatever the previous layer or test left there).
     device_later (with pinned_host): layers after the first are given the previous
     layer's output where it lies in device memory instead of a pinned host copy.
-    tiles_per_run / piece_tiles: the launch-shape fields of atlas_dims_t (0: the library's choice)."""
+    tiles_per_run / piece_tiles: the launch-shape fields of atlas_dims_t (0: the library's choice).
+    csr_stream: ATLAS_FLAG_CSR_STREAM, long chunks without a planned chunk are not regrouped on the fly."""
     dev = torch.device("cuda:0")
     n, e = case.n, case.e
     run = GpuRun(extra_roundings=1 if transform_first else 0)
@@ -187,7 +189,8 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
                                evict_policy=evict_policy, flags=(atlas.FLAG_TIMING if timing else 0) |
                                (atlas.FLAG_EMB_RESIDENT if emb_resident else 0) |
                                (atlas.FLAG_PLANNED_ONLY if planned_only else 0) |
-                               (atlas.FLAG_TRANSFORM_FIRST if transform_first else 0),
+                               (atlas.FLAG_TRANSFORM_FIRST if transform_first else 0) |
+                               (atlas.FLAG_CSR_STREAM if csr_stream else 0),
                                tiles_per_run=tiles_per_run, piece_tiles=piece_tiles)
         weights = atlas.make_weights(W, b, sdt, a_s, a_d)
         h = atlas.atlas_layer_init(graph, dims, weights, stream)
@@ -447,7 +450,7 @@ def check_layer_counters(wl, run: WorkloadRun, planned: bool):
         assert st["edges_processed"] == wl.e and st["vertices_flushed"] == wl.n
         assert st["vertices_completed"] == wl.n and st["sources_processed"] == wl.n
         assert st["chunks_planned"] == (st["num_chunks"] if planned else 0)
-        assert st["chunks_csr_stream"] == (0 if planned else st["num_chunks"])
+        assert st["chunks_csr_stream"] + st["chunks_regrouped"] == (0 if planned else st["num_chunks"])
         assert not run.pending_final_any[li], "pending counts must all reach zero"
         seen = np.zeros(wl.n, dtype=np.uint8)
         seen[run.ready[li]] = 1

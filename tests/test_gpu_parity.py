@@ -382,3 +382,35 @@ def test_gat_pinned_host_graph(oracle, H, plan, store):
     run = H.run_gpu(case, plan=plan, pinned_host=True, device_later=True, flush_every=3)
     print("gat pinned, later layers in HBM", store, H.check_outputs(oracle, case, run))
 
+
+
+@pytest.mark.parametrize("model,store", [("sage", torch.bfloat16), ("gcn", torch.float32), ("gat", torch.float32),
+                                         ("gin", torch.float32)])
+def test_long_chunks_without_a_plan_are_regrouped(oracle, H, model, store):
+    """A chunk of at least 2^20 edges that has no planned chunk is regrouped by destination on
+    the fly and pushed like a planned one; shorter chunks of the same layer go straight from the
+    CSR.  Degree-ordered R-MAT scale 16 with 2.6 M edges in two chunks: the first is regrouped,
+    the second is not.  Integer state bit-exact after every chunk, outputs to tolerance, from
+    device memory and from pinned host memory; ATLAS_FLAG_CSR_STREAM keeps every chunk on the CSR."""
+    g = gen.rmat_graph(SEED + 71, 16, 40, self_loops=(model == "gcn"))
+    off, col = gen.build_csr(g)
+    new_of_old, _ = oracle.reorder_indegree_desc(oracle.in_degree(g.n, col.numpy()))
+    g = g.with_relabel(torch.from_numpy(new_of_old.astype(np.int64)))
+    dims = [64, 64, 32] if model != "gat" else [64, 64, 64]
+    case = H.make_case(model, g, SEED + 71, dims, 1 << 15, store=store,
+                       feat="normal" if store == torch.float32 else "uniform", heads=2 if model == "gat" else 1)
+    run = H.run_gpu(case, snapshots=True)
+    H.check_integers(oracle, case, run, layer=0)
+    H.check_integers(oracle, case, run, layer=1)
+    print("regrouped", model, H.check_outputs(oracle, case, run))
+    for st in run.stats:
+        assert st["chunks_planned"] == 0 and st["chunks_regrouped"] >= 1 and st["chunks_csr_stream"] >= 1
+        assert st["chunks_regrouped"] + st["chunks_csr_stream"] == st["num_chunks"] == 2
+        assert st["ms_regroup"] > 0 and st["edges_processed"] == case.e and st["vertices_flushed"] == case.n
+    run = H.run_gpu(case, snapshots=True, pinned_host=True, device_later=True)
+    H.check_integers(oracle, case, run, layer=0)
+    H.check_outputs(oracle, case, run)
+    assert all(st["chunks_regrouped"] >= 1 for st in run.stats)
+    run = H.run_gpu(case, csr_stream=True)
+    H.check_outputs(oracle, case, run)
+    assert all(st["chunks_regrouped"] == 0 and st["chunks_csr_stream"] == 2 for st in run.stats)
