@@ -83,6 +83,9 @@ def main() -> int:
                          "half-precision MFMA in the update)")
     ap.add_argument("--transform-first", action="store_true",
                     help="apply W to each chunk before it is pushed (d_out-wide messages and accumulators)")
+    ap.add_argument("--no-narrow-first", action="store_true",
+                    help="end-to-end runs: do not switch a layer whose output is narrower than its input (the last "
+                         "layer, 128 -> 64) to the transform-first order")
     ap.add_argument("--hot-slots-frac", type=float, default=0.0,
                     help="bounded accumulator store: slots = this fraction of the vertices with an in-edge "
                          "(0: one accumulator row per vertex); needs chunks small enough to fit")
@@ -225,13 +228,16 @@ def main() -> int:
 
     chunk_wall_ms = []   # --sync-chunks: wall time of every chunk (copy + kernels), all layers run so far
 
-    def run_layer(graph, planned: bool, li: int, x: torch.Tensor, timing: bool) -> dict:
+    def run_layer(graph, planned: bool, li: int, x: torch.Tensor, timing: bool, narrow_first: bool = False) -> dict:
         d_in, d_out = wl.dims[li], wl.dims[li + 1]
+        # the linear map commutes with the neighbour sum: a layer that narrows its rows pushes the narrow products
+        tf = args.transform_first or (narrow_first and d_out < d_in and wl.model in ("sage", "gcn", "gin")
+                                      and d_out % 64 == 0)
         act = atlas.ACT_NONE if li + 1 == len(wl.layers) else between
         dims = atlas.make_dims(model_id, d_in, d_out, sdt, sdt, act, chunk, heads=wl.heads,
                                flags=(atlas.FLAG_TIMING if timing else 0) | atlas.FLAG_EMB_RESIDENT |
                                (atlas.FLAG_PLANNED_ONLY if planned else 0) |
-                               (atlas.FLAG_TRANSFORM_FIRST if args.transform_first else 0),
+                               (atlas.FLAG_TRANSFORM_FIRST if tf else 0),
                                hot_slots=hot_slots, evict_policy=1 if args.evict_policy == "max" else 0)
         W, b = params[li]
         h = atlas.atlas_layer_init(graph, dims, atlas.make_weights(W, b, sdt, attn[li][0], attn[li][1]), stream)
@@ -298,7 +304,7 @@ def main() -> int:
             x = x0
             for li in range(len(wl.layers)):
                 t1 = time.perf_counter()
-                run_layer(graph, planned, li, x, False)
+                run_layer(graph, planned, li, x, False, narrow_first=not args.no_narrow_first)
                 res["layer_ms"].append((time.perf_counter() - t1) * 1e3)
                 x = outs[li]
             torch.cuda.synchronize()
@@ -472,11 +478,25 @@ def main() -> int:
         import oracle
         oracle.build()
         gsel = torch.Generator().manual_seed(12345)
-        pick = torch.randperm(n, generator=gsel)[: args.sample_dst]
-        pick = torch.unique(torch.cat([pick, torch.topk(indeg.to(torch.int64), min(1024, n)).indices.cpu()])).to(dev)
+        pick_random = torch.randperm(n, generator=gsel)[: args.sample_dst]
+        pick = torch.unique(torch.cat([pick_random, torch.topk(indeg.to(torch.int64), min(1024, n)).indices.cpu()])).to(dev)
         in_off, in_src_local, need, pick_local = sample_subgraph(wl.off, wl.col, pick)
         Xs = wl.X[need].float().cpu().numpy()
         il = oracle.InLists(in_off.cpu().numpy(), in_src_local.cpu().numpy(), pick_local.cpu().numpy())
+        # How many vertices does an edge message complete (the row then leaves the aggregation kernel and is read
+        # back by the flush of the same call: what a flush fused into the aggregation could hand over directly),
+        # and how many the vertex's own message, long after its last data arrived?  On the random part of the sample.
+        is_random = torch.zeros(n, dtype=torch.bool, device=dev)
+        is_random[pick_random.to(dev)] = True
+        deg_s = in_off[1:] - in_off[:-1]
+        has_in = deg_s > 0
+        last_src = torch.zeros(pick.numel(), dtype=torch.int64, device=dev)
+        last_pos = (in_off[1:] - 1).clamp(min=0)
+        last_src[has_in] = need[in_src_local.to(torch.int64)[last_pos[has_in]]]     # lists ascend: the last is the largest
+        by_edge = has_in & ((last_src // chunk) >= (pick // chunk))
+        sel = is_random[pick]
+        frac_with_in = float((has_in & sel).sum().item()) / max(1, int(sel.sum().item()))
+        frac_by_edge = float((by_edge & sel).sum().item()) / max(1, int(sel.sum().item()))
         p0 = wl.layers[0]
         indeg_s = indeg[need].cpu().numpy().astype(np.int64)
         t1 = time.perf_counter()
@@ -503,6 +523,11 @@ def main() -> int:
                "sample": "%d destinations (%d random + the 1,024 highest in-degree) with all %d of their in-edges, "
                          "layer 1 aggregate + update in fp64" % (pick.numel(), args.sample_dst, sample_edges),
                "seconds": round(t_or, 3), "sampled_parity_max_rel_err": errs,
+               "completion": {"vertices_with_in_edges": round(frac_with_in, 4),
+                              "completed_by_an_edge_message": round(frac_by_edge, 4),
+                              "note": "share of all vertices, estimated on the random part of the sample; only the "
+                                      "second kind could be handed from the aggregation to the update without a "
+                                      "round trip of its accumulator row"} if wl.model in ("sage", "gin") else None,
                "cpu_model": cpu_model(), "host_cpus": os.cpu_count()}
 
     # ---- teardown: nothing of the library's stays alive until the process exits ----
@@ -558,6 +583,8 @@ def main() -> int:
                                "streamed from pinned host memory (host-link inclusive)",
                    "edge_order": "per-chunk destination-grouped plan" if (plan or plan_host) else "CSR stream (atomics)"},
         "transform_first": bool(args.transform_first),
+        "end_to_end_note": None if args.no_narrow_first else
+        "layers whose output is narrower than their input run in the transform-first order (narrow messages)",
         "plan_blocking": None if args.plan_block_log2 <= 0 else {"block_sources": 1 << args.plan_block_log2,
                                                                   "hot_min_edges": args.plan_hot_min},
         "plan": plan_info,
