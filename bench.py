@@ -435,7 +435,9 @@ def main() -> int:
         ca = torch.empty(cbytes // 4, dtype=torch.int32, device=dev).fill_(1)
         cb = torch.empty_like(ca)
         copy_ms = ev_ms(lambda: atlas.atlas_probe_copy(cb, ca, cbytes), 5)
-        del cb
+        cc = torch.empty_like(ca)
+        mix_ms = ev_ms(lambda: atlas.atlas_probe_mix21(cc, ca, cb, cbytes), 5)   # 2 reads : 1 write, the flush's mix
+        del cb, cc
         # 2^27 random rows of 256 bytes out of a 1 GiB table (the size of one chunk's bf16 rows)
         table_rows, n_ids = 1 << 22, 1 << 27
         ids = torch.randint(0, table_rows, (n_ids,), dtype=torch.int32, device=dev)
@@ -462,6 +464,9 @@ def main() -> int:
         measured = {
             "copy_GBps": round(2 * cbytes / (copy_ms / 1e3) / 1e9, 1),   # 1 read : 1 write
             "copy_frac_of_peak": round(2 * cbytes / (copy_ms / 1e3) / 1e9 / HBM_PEAK_GBPS, 4),
+            "mix_2r1w_GBps": round(3 * cbytes / (mix_ms / 1e3) / 1e9, 1),
+            # the flush moves its bytes at this share of what a bare 2:1 stream reaches
+            "update_frac_of_measured_mix": round(upd_bytes / upd_s / 1e9 / (3 * cbytes / (mix_ms / 1e3) / 1e9), 4),
             "gather_GBps": round(n_ids * 256 / (gather_ms / 1e3) / 1e9, 1),
             "gather": "2^27 random 256-byte rows of a 1 GiB table, one wave per row, 8 rows in flight per wave",
             "mfma": mf,

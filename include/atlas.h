@@ -375,9 +375,9 @@ int atlas_reorder_indegree_desc_noalloc(const atlas_graph_t *graph, int32_t *new
  * must be set; outputs are int32[N] DEVICE memory.  Synchronous. */
 int atlas_reorder_score_desc(const atlas_graph_t *graph, int32_t *new_of_old, int32_t *old_of_new);
 
-/* Neighbourhood sampling as a preprocessing pass over the topology (Sec. 3.9:
- * edges that are not required are disabled, the broadcast then runs unchanged
- * on what is left).  Every destination keeps at most `fanout` of its in-edges:
+/* Neighbourhood sampling done on the graph before inference (the route Sec. 3.9
+ * names: the edges a sample drops are switched off, and the broadcast then runs
+ * unchanged on what is left).  Every destination keeps at most `fanout` of its in-edges:
  * those with the smallest edge_key (one caller-drawn uint32 per edge, DEVICE
  * memory, in CSR order), ties by position in the CSR.  out_row_offsets
  * (int64[N+1]) and out_col_indices (int32, room for num_edges) in DEVICE memory
@@ -400,8 +400,10 @@ int atlas_plan_info(const atlas_plan_t *plan, atlas_plan_info_t *info);
 
 /* Measured peaks of the box at hand, for the benchmark's report (Sec. 4.4 of the paper
  * asks what bounds the run; here: what a bare kernel of the same access pattern reaches).
- * All three only enqueue on hip_stream; the caller times them with events on that stream.
+ * They only enqueue on hip_stream; the caller times them with events on that stream.
  *   atlas_probe_copy:        dst[0..bytes) = src[0..bytes), DEVICE memory, bytes a multiple of 16.
+ *   atlas_probe_mix21:       dst[i] = a[i] ^ b[i] over `bytes` bytes of each array: two bytes read per byte
+ *                            written, the flush's mix (accumulator row and own row in, output row out).
  *   atlas_probe_row_gather:  reads rows ids[0..n_ids) of `table` (rows of 256 bytes, DEVICE),
  *                            one wave per row, eight rows in flight per wave -- the planned
  *                            aggregation's source-row gather without its bookkeeping.  ids:
@@ -415,6 +417,7 @@ int atlas_plan_info(const atlas_plan_t *plan, atlas_plan_info_t *info);
  *                            fits the caches shows the contraction's rate without the HBM cap.
  * Errors: E_NULL, E_BAD_DIMS, E_RANGE, E_HIP, E_NOMEM. */
 int atlas_probe_copy(void *dst, const void *src, int64_t bytes, void *hip_stream);
+int atlas_probe_mix21(void *dst, const void *a, const void *b, int64_t bytes, void *hip_stream);
 int64_t atlas_probe_gather_sink_bytes(void);
 int atlas_probe_row_gather(const void *table, int64_t table_rows, const int32_t *ids, int64_t n_ids, void *sink,
                            void *hip_stream);

@@ -35,7 +35,7 @@ EXPORTS = [
     "atlas_release_cache", "atlas_strerror", "atlas_last_hip_error", "atlas_plan_create", "atlas_plan_destroy",
     "atlas_reorder_score_desc", "atlas_sample_in_edges", "atlas_plan_create_blocked",
     "atlas_reorder_indegree_desc_noalloc", "atlas_plan_info", "atlas_plan_in_degree", "atlas_probe_copy", "atlas_probe_row_gather",
-    "atlas_probe_dense_rows", "atlas_probe_gather_sink_bytes",
+    "atlas_probe_dense_rows", "atlas_probe_gather_sink_bytes", "atlas_probe_mix21",
 ]
 
 
@@ -121,6 +121,7 @@ def lib() -> ctypes.CDLL:
         L.atlas_plan_info.argtypes = [vp, ctypes.POINTER(atlas_plan_info_t)]
         L.atlas_plan_in_degree.argtypes = [vp, vp, vp]
         L.atlas_probe_copy.argtypes = [vp, vp, i64, vp]
+        L.atlas_probe_mix21.argtypes = [vp, vp, vp, i64, vp]
         L.atlas_probe_gather_sink_bytes.argtypes = []
         L.atlas_probe_row_gather.argtypes = [vp, i64, vp, i64, vp, vp]
         L.atlas_probe_dense_rows.argtypes = [i32, vp, i64, i32, i32, vp, vp, i32, vp]
@@ -239,6 +240,10 @@ def atlas_plan_in_degree(plan: int, in_degree, stream=None) -> None:
 
 def atlas_probe_copy(dst, src, nbytes: int, stream=None) -> None:
     _check(lib().atlas_probe_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "atlas_probe_copy")
+
+
+def atlas_probe_mix21(dst, a, b, nbytes: int, stream=None) -> None:
+    _check(lib().atlas_probe_mix21(_ptr(dst), _ptr(a), _ptr(b), nbytes, _stream(stream)), "atlas_probe_mix21")
 
 
 def atlas_probe_gather_sink_bytes() -> int:

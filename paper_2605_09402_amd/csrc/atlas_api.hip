@@ -1344,6 +1344,13 @@ int atlas_probe_copy(void *dst, const void *src, int64_t bytes, void *hip_stream
     return ATLAS_OK;
 }
 
+int atlas_probe_mix21(void *dst, const void *a, const void *b, int64_t bytes, void *hip_stream) {
+    if (!dst || !a || !b) return ATLAS_E_NULL;
+    if (bytes < 0 || bytes % 16 != 0) return ATLAS_E_RANGE;
+    HIP_TRY(probe_mix21(dst, a, b, static_cast<size_t>(bytes), static_cast<hipStream_t>(hip_stream)));
+    return ATLAS_OK;
+}
+
 int64_t atlas_probe_gather_sink_bytes(void) { return static_cast<int64_t>(probe_gather_sink_bytes()); }
 
 int atlas_probe_row_gather(const void *table, int64_t table_rows, const int32_t *ids, int64_t n_ids, void *sink,

@@ -312,6 +312,7 @@ hipError_t launch_advance_head(int32_t *counters, hipStream_t s);
 
 // Measured-peak probes (k_probe.hip).
 hipError_t probe_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
+hipError_t probe_mix21(void *dst, const void *a, const void *b, size_t bytes, hipStream_t s);
 size_t probe_gather_sink_bytes();
 hipError_t probe_row_gather(const void *table, const int32_t *ids, int64_t n_ids, void *sink, hipStream_t s);
 

@@ -22,6 +22,17 @@ __global__ __launch_bounds__(kBlock) void k_probe_copy(const uint4 *__restrict__
     for (size_t i = static_cast<size_t>(blockIdx.x) * kBlock + threadIdx.x; i < vecs; i += stride) dst[i] = src[i];
 }
 
+// Two reads for one write (dst = a ^ b): the read/write mix of the flush (accumulator row and own row in,
+// output row out) without its gather or its contraction.
+__global__ __launch_bounds__(kBlock) void k_probe_mix21(const uint4 *__restrict__ a, const uint4 *__restrict__ b,
+                                                        uint4 *__restrict__ dst, size_t vecs) {
+    const size_t stride = static_cast<size_t>(gridDim.x) * kBlock;
+    for (size_t i = static_cast<size_t>(blockIdx.x) * kBlock + threadIdx.x; i < vecs; i += stride) {
+        const uint4 x = a[i], y = b[i];
+        dst[i] = make_uint4(x.x ^ y.x, x.y ^ y.y, x.z ^ y.z, x.w ^ y.w);
+    }
+}
+
 // A wave reads 64 row ids with one coalesced load, then gathers the rows, U at a
 // time: the 64 lanes hold one 256-byte row, 4 bytes each.  The words are folded
 // into one register per lane so that no load can be dropped; each wave writes
@@ -68,6 +79,14 @@ hipError_t probe_copy(void *dst, const void *src, size_t bytes, hipStream_t s) {
     if (vecs == 0) return hipSuccess;
     hipLaunchKernelGGL(k_probe_copy, dim3(cu_count() * 16), dim3(kBlock), 0, s, static_cast<const uint4 *>(src),
                        static_cast<uint4 *>(dst), vecs);
+    return hipGetLastError();
+}
+
+hipError_t probe_mix21(void *dst, const void *a, const void *b, size_t bytes, hipStream_t s) {
+    const size_t vecs = bytes / 16;
+    if (vecs == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_probe_mix21, dim3(cu_count() * 16), dim3(kBlock), 0, s, static_cast<const uint4 *>(a),
+                       static_cast<const uint4 *>(b), static_cast<uint4 *>(dst), vecs);
     return hipGetLastError();
 }
 

@@ -1,6 +1,6 @@
-// Neighbourhood sampling as a preprocessing pass over the topology: the paper
-// notes that sampled inference fits the broadcast model once the edges that are
-// not required are disabled (Sec. 3.9).  Every destination keeps at most
+// Neighbourhood sampling done on the graph ahead of inference: the paper notes
+// that sampled inference fits the broadcast model once the edges a sample
+// drops have been switched off (Sec. 3.9).  Every destination keeps at most
 // `fanout` of its in-edges -- those with the smallest caller-supplied random
 // keys, ties by position in the CSR -- and the kept edges are written out as a
 // new CSR by source in their original order.  Integer work only: one stable
