@@ -83,6 +83,8 @@ def main() -> int:
                          "half-precision MFMA in the update)")
     ap.add_argument("--transform-first", action="store_true",
                     help="apply W to each chunk before it is pushed (d_out-wide messages and accumulators)")
+    ap.add_argument("--no-handover", action="store_true",
+                    help="switch the fused part of the flush off: every finished row takes the fp32 round trip")
     ap.add_argument("--no-narrow-first", action="store_true",
                     help="end-to-end runs: do not switch a layer whose output is narrower than its input (the last "
                          "layer, 128 -> 64) to the transform-first order")
@@ -237,7 +239,8 @@ def main() -> int:
         dims = atlas.make_dims(model_id, d_in, d_out, sdt, sdt, act, chunk, heads=wl.heads,
                                flags=(atlas.FLAG_TIMING if timing else 0) | atlas.FLAG_EMB_RESIDENT |
                                (atlas.FLAG_PLANNED_ONLY if planned else 0) |
-                               (atlas.FLAG_TRANSFORM_FIRST if tf else 0),
+                               (atlas.FLAG_TRANSFORM_FIRST if tf else 0) |
+                               (atlas.FLAG_NO_HANDOVER if args.no_handover else 0),
                                hot_slots=hot_slots, evict_policy=1 if args.evict_policy == "max" else 0)
         W, b = params[li]
         h = atlas.atlas_layer_init(graph, dims, atlas.make_weights(W, b, sdt, attn[li][0], attn[li][1]), stream)
@@ -598,6 +601,9 @@ def main() -> int:
             "reloads_per_layer": st["hot_reloads"], "peak_slots": st["hot_peak_slots"]},
         "layer_ms": {"aggregate": round(ps["ms_aggregate"], 3), "update": round(ps["ms_update"], 3),
                      "self": round(ps["ms_self"], 3), "init": round(ps["ms_init"], 3)},
+        # the fused part of the flush: rows that went from the aggregation to the update as its 16-bit operand
+        "fused_flush": {"rows_handed_over_per_layer": st["rows_handed_over"],
+                        "share_of_vertices": round(st["rows_handed_over"] / max(n, 1), 4)},
         "end_to_end_ms": r1(main_res["e2e_ms"]),
         "end_to_end_layer_ms": [round(v, 2) for v in main_res["layer_ms"]],
         "prep_ms": prep_out,

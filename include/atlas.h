@@ -97,6 +97,7 @@ enum atlas_flags {
                                     a plan, for GAT and for graphs of 2^30 vertices or more (their
                                     plans lack the list of rows to clear).  With it, ATLAS_DBG_ACC rows of vertices
                                     that have received nothing yet are undefined. */
+    ATLAS_FLAG_NO_HANDOVER = 32, /* switch the fused part of the flush off (see atlas_flush_ready); for comparisons */
     ATLAS_FLAG_CSR_STREAM = 16,  /* never regroup a chunk on the fly: a chunk without a planned chunk is pushed
                                     straight from the CSR with fp32 atomics, whatever its length (see
                                     atlas_broadcast_chunk) */
@@ -235,6 +236,8 @@ typedef struct {
                                    num_chunks                                               */
     float ms_regroup;           /* host time of that regrouping (it is synchronous), always
                                    measured                                                 */
+    int64_t rows_handed_over;   /* vertices whose finished row went from the aggregation to the
+                                   update as the update's operand (see atlas_flush_ready)   */
 } atlas_layer_stats_t;
 
 /* Create the state of one layer (Sec. 3.4: pending-message tracker and
@@ -286,7 +289,16 @@ int atlas_broadcast_chunk(atlas_layer_t *layer, int64_t src_begin, int64_t src_e
  * activation and write row v of `out` (DEVICE memory, N x d_out row-major,
  * dims.out_dtype).  Only rows of flushed vertices are written.  If n_flushed is
  * not NULL the call waits for the stream and stores the number of rows written;
- * with NULL it only enqueues.  Errors: E_NULL, E_STATE, E_HIP. */
+ * with NULL it only enqueues.  Errors: E_NULL, E_STATE, E_HIP.
+ * Fused part (Sec. 3.6 hands a vertex to the transform the moment its count reaches zero): in
+ * SAGE_MEAN / GCN_SYM layers with 16-bit embeddings of width 128, a vertex that is completed by
+ * an edge message of a planned or regrouped chunk -- by a group of messages that one wavefront
+ * sums alone -- does not go through an fp32 accumulator round trip: the aggregation writes the
+ * finished row as this call's own left operand (normalised, rounded to the compute type exactly
+ * as this call would have) and marks the vertex's ready-list entry; this call reads half the
+ * bytes for it and skips the normalisation.  Results are bit-identical with and without it
+ * (ATLAS_FLAG_NO_HANDOVER); ATLAS_DBG_ACC rows of such vertices then hold that operand in their
+ * first half. */
 int atlas_flush_ready(atlas_layer_t *layer, void *out, int64_t *n_flushed, void *hip_stream);
 
 /* Wait for the layer's work, verify that all N sources were broadcast and that

@@ -26,6 +26,7 @@ FLAG_EMB_RESIDENT = 2
 FLAG_PLANNED_ONLY = 4
 FLAG_TRANSFORM_FIRST = 8
 FLAG_CSR_STREAM = 16
+FLAG_NO_HANDOVER = 32
 EVICT_MIN_PENDING, EVICT_MAX_PENDING = 0, 1
 DBG_INDEG, DBG_PENDING, DBG_READY, DBG_READY_COUNT, DBG_ACC = range(5)
 
@@ -69,7 +70,7 @@ class atlas_layer_stats_t(ctypes.Structure):
                 ("ms_init", ctypes.c_float), ("hot_evictions", ctypes.c_int64), ("hot_reloads", ctypes.c_int64),
                 ("hot_peak_slots", ctypes.c_int64), ("chunks_planned", ctypes.c_int64),
                 ("chunks_csr_stream", ctypes.c_int64), ("chunks_regrouped", ctypes.c_int64),
-                ("ms_regroup", ctypes.c_float)]
+                ("ms_regroup", ctypes.c_float), ("rows_handed_over", ctypes.c_int64)]
 
 
 class atlas_plan_info_t(ctypes.Structure):

@@ -169,6 +169,7 @@ struct atlas_layer {
     Buf tf_self;    // [N][d_out] fp32: SAGE x_v W_self, GIN x_v W
     Buf packed_w2;  // SAGE: W_self in fragment order
 
+    bool handover = false;             // rows completed inside the grouped aggregation leave as the update's operand
     bool planned_only = false;         // every chunk runs from the plan: no accumulator zero fill
     bool emb_resident = false;         // own rows are read from the caller's matrix
     const char *x_base = nullptr;      // base of that matrix (set by the first chunk)
@@ -359,6 +360,11 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
                       n < (int64_t(1) << 30);   // the plan lists the rows to clear only below 2^30 vertices
     if (!L->planned_only)
         HIP_TRY(launch_fill_zero(L->acc.p, static_cast<size_t>(n) * L->acc_width * sizeof(float), s));
+    // Fused part of the flush: 16-bit SAGE / GCN layers of width 128 whose flush runs the kernel that knows
+    // handed-over rows, accumulators addressed by vertex id.
+    L->handover = !(d.flags & ATLAS_FLAG_NO_HANDOVER) && !L->tf && !L->bounded &&
+                  (d.model == ATLAS_MODEL_SAGE_MEAN || d.model == ATLAS_MODEL_GCN_SYM) &&
+                  update_takes_handed_rows(d.model, d.d_in, L->K, d.d_out, L->compute_dt);
     if (L->bounded) {
         const size_t S = static_cast<size_t>(d.hot_slots);
         HIP_TRY(L->hs_slot_of.alloc(n1 * sizeof(int32_t)));
@@ -972,6 +978,9 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         ga.counters = a.counters;
         ga.counters64 = a.counters64;
         ga.forced_run = d.tiles_per_run;
+        ga.handover = L->handover ? 1 : 0;
+        ga.handover_dt = d.in_dtype;
+        ga.handover_norm = d.model == ATLAS_MODEL_GCN_SYM ? 1 : 0;
     }
     if (d.model == ATLAS_MODEL_GAT) {
         if (pc) {
@@ -1061,6 +1070,7 @@ int atlas_flush_ready(atlas_layer_t *L, void *out, int64_t *n_flushed, void *hip
     u.out = out;
     u.n = L->n;
     u.slot_of = L->bounded ? L->hs.slot_of : nullptr;
+    u.handed_rows = L->handover ? 1 : 0;
     int rc = start_span(L, L->t_upd, s);
     if (rc != ATLAS_OK) return rc;
     if (d.model == ATLAS_MODEL_GAT) {
@@ -1132,6 +1142,7 @@ int atlas_layer_finish(atlas_layer_t *L, atlas_layer_stats_t *stats) {
         stats->chunks_planned = L->chunks_planned;
         stats->chunks_csr_stream = L->chunks_csr;
         stats->chunks_regrouped = L->chunks_regrouped;
+        stats->rows_handed_over = static_cast<int64_t>(c64[CTR64_HANDED]);
         stats->ms_regroup = static_cast<float>(L->ms_regroup);
         if (L->bounded) {
             int32_t hc[HS_COUNT] = {0};
@@ -1485,6 +1496,10 @@ int atlas_debug_copy(atlas_layer_t *L, int what, void *host_dst, int64_t bytes) 
     }
     if (bytes > avail) return ATLAS_E_RANGE;
     if (bytes > 0) HIP_TRY(hipMemcpy(host_dst, src, static_cast<size_t>(bytes), hipMemcpyDeviceToHost));
+    if (what == ATLAS_DBG_READY) {   // bit 31 of an entry says how the row reaches the update, not which vertex
+        int32_t *ids = static_cast<int32_t *>(host_dst);
+        for (int64_t i = 0; i < bytes / 4; ++i) ids[i] &= 0x7fffffff;
+    }
     return ATLAS_OK;
 }
 

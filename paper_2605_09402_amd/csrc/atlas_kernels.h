@@ -16,7 +16,7 @@ enum Counter {
 };
 
 // 64-bit counters (separate block): edges pushed so far.
-enum Counter64 { CTR64_EDGES = 0, CTR64_COUNT = 8 };
+enum Counter64 { CTR64_EDGES = 0, CTR64_HANDED = 1 /* rows handed over to the update */, CTR64_COUNT = 8 };
 
 // Bounded accumulator store (paper Sec. 3.5): a fixed number of slots in HBM,
 // evicted partial states in pinned host memory.
@@ -137,6 +137,10 @@ struct GroupedArgs {
                                 // several groups in this chunk (all of them add with atomics); else 0
     float *scores = nullptr;    // GAT only: [n_edges][heads] attention logits of the chunk's edges, written
                                 // by the max sweep and read by the aggregation
+    int handover = 0;           // 1: a group this wave alone owns that completes its destination writes the finished
+    int handover_dt = 1;        // row as the update's 16-bit operand (type handover_dt: 1 bf16, 2 IEEE half; normalised
+    int handover_norm = 0;      // by 1/deg (0) or deg^-1/2 (1)) into the first half of the accumulator row, and the
+                                // vertex's ready-list entry carries bit 31
     int forced_run = 0;         // the layer's run length (1..kMaxTilesPerRun), 0: chosen per launch
     int tiles_per_run = 1;      // consecutive 64-edge tiles one wave takes at a time (set by the launcher)
     int64_t tile_begin = 0;     // the launch covers tiles [tile_begin, tile_end) of the chunk (tile_end < 0: all).
@@ -283,11 +287,16 @@ struct UpdateArgs {
     int out2_dt;              // element type of out2 (out_dt is that of out)
     int64_t n;
     const int32_t *slot_of;   // bounded store: row of `acc` that holds vertex v (nullptr: row v)
+    int handed_rows;          // 1: ready-list entries may carry bit 31 (rows handed over by the aggregation, see
+                              // GroupedArgs::handover); only flushes for which update_takes_handed_rows() holds
     int64_t identity_rows;    // > 0: no ready list; rows 0..identity_rows-1 of `acc` (a dense
                               // row block, model 2 = plain X W) map to the same rows of `out`
 };
 // S5: gather ready rows, normalise, MFMA GEMM, bias, activation, scatter rows.
 hipError_t launch_update(const UpdateArgs &a, hipStream_t s);
+// Whether that flush (model: UpdateArgs::model) understands ready-list entries with bit 31 set: rows whose
+// finished 16-bit operand the aggregation left in the first half of the accumulator row.
+bool update_takes_handed_rows(int model, int d_in, int K, int d_out, int compute_dt);
 // Transform-first layers: the ready rows' outputs from already-transformed sums,
 // y_v = act(scale(deg_v) * acc[v] + self_scale * self_term[v] + b).
 struct SumFinalizeArgs {

@@ -420,19 +420,63 @@ __device__ __forceinline__ void row_add_shared(float *p, const float (&x)[VPL]) 
     for (int i = 0; i < VPL; ++i) unsafeAtomicAdd(p + i, x[i]);
 }
 
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+// two fp32 -> one word of two 16-bit values (round to nearest even); dt: 1 bf16, 2 IEEE half
+__device__ __forceinline__ uint32_t pack_pair(int dt, float lo, float hi) {
+    const f32x2_t v = {lo, hi};
+    if (dt == 2) {
+        const f16x2_t h = __builtin_convertvector(v, f16x2_t);
+        return *reinterpret_cast<const uint32_t *>(&h);
+    }
+    const bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
+    return *reinterpret_cast<const uint32_t *>(&b);
+}
+
+// Hand-over of a finished row to the update (the fused part of the flush, Sec. 3.6: a vertex graduates the
+// moment its count reaches zero).  When a group that this wave alone owns takes its destination's count to
+// zero, the finished sum is in the wave's registers: it leaves as the update's own left operand --
+// normalised and rounded to the 16-bit compute type exactly as the update would have done -- in the first
+// half of the accumulator row, instead of as fp32 sums that the update reads back, scales and rounds.  The
+// ready-list entry of such a vertex carries kHandedOver.  `row` is the start of the accumulator row, `x` the
+// group's sum of this lane's elements lane * VPL ..; the row so far is added unless the group is the
+// destination's first.  (Every lane's old values are in registers before any lane stores: the stores
+// depend on the loads of the same instruction.)
+constexpr int32_t kHandedOver = static_cast<int32_t>(0x80000000u);
+template <int VPL>
+__device__ __forceinline__ void row_hand_over(float *row, int lane, const float (&x)[VPL], bool first, float scale,
+                                              int dt) {
+    static_assert(VPL % 2 == 0, "pairs of elements");
+    float t[VPL];
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) t[i] = x[i];
+    if (!first) {
+#pragma unroll
+        for (int q = 0; q < VPL / 2; ++q) {
+            const f32x2_t v = __builtin_nontemporal_load(reinterpret_cast<f32x2_t *>(row + lane * VPL + 2 * q));
+            t[2 * q] += v[0];
+            t[2 * q + 1] += v[1];
+        }
+    }
+    uint32_t *o = reinterpret_cast<uint32_t *>(row) + lane * (VPL / 2);
+#pragma unroll
+    for (int q = 0; q < VPL / 2; ++q) o[q] = pack_pair(dt, t[2 * q] * scale, t[2 * q + 1] * scale);
+}
+
 // Second half of a tile's pending-count update: `old` is what the lane's read
 // (or atomic) returned.  The sole writer stores the new count here.
 __device__ __forceinline__ void finish_pending(bool closes, bool shared, int32_t old, int32_t c, int32_t dst,
-                                               const GroupedArgs &a, int32_t *stage, int &staged, int lane) {
+                                               bool handed, const GroupedArgs &a, int32_t *stage, int &staged,
+                                               int lane) {
     bool is_ready = false;
     if (closes) {
         is_ready = old == c;
         if (!shared) a.pending[dst] = old - c;
     }
-    stage_ready(is_ready, dst, stage, staged, a.ready, a.counters, lane);
+    // a handed-over row was written because the count read ahead equalled c: the same value as `old`
+    stage_ready(is_ready, handed ? dst | kHandedOver : dst, stage, staged, a.ready, a.counters, lane);
 }
 
-template <typename T, int VPL, int MODEL>
+template <typename T, int VPL, int MODEL, bool FUSE>
 // The kernel is latency-bound on the row gathers.  Instantiations whose eight
 // rows in flight take at most 16 registers are held to all 8 waves of a SIMD
 // (scalar registers beyond that budget spill to lanes, nothing to memory), the
@@ -505,6 +549,17 @@ void k_aggregate_grouped(GroupedArgs a) {
     int32_t ticket = 0;   // lane 0: counter value drawn for the wave's next run
     if (a.dynamic && t >= 0 && lane == 0) ticket = atomicAdd(&a.counters[CTR_NEXT_RUN], 1);
     int32_t s = 0, g0 = 0, prev_word = -1, gd = 0;
+    // FUSE: count and in-degree of the destination of every group that ends in the tile, read a tile ahead
+    int32_t pend_pre = 0, deg_pre = 1;
+    auto read_ahead = [&](bool ends, int32_t gdw, int32_t &pend, int32_t &deg) {
+        if constexpr (FUSE) {
+            if (ends) {
+                const int32_t v = gdw & 0x7fffffff & ~a.multi_bit;
+                pend = a.pending[v];
+                deg = a.indeg[v];
+            }
+        }
+    };
     if (t >= 0) {
         const int64_t e0 = static_cast<int64_t>(t) * kTileEdges;
         const int64_t left = a.n_edges - e0;
@@ -515,9 +570,11 @@ void k_aggregate_grouped(GroupedArgs a) {
         const bool is_end = lane < cnt && s < 0;
         const uint64_t below = __ballot(is_end) & ((1ull << lane) - 1ull);
         if (is_end || lane == cnt - 1) gd = a.grp_dst[g0 + __popcll(below)];
+        read_ahead(is_end, gd, pend_pre, deg_pre);
     }
     // pending-count update of the tile before, not yet consumed
-    bool pd_closes = false, pd_shared = false;
+    bool pd_closes = false, pd_shared = false, pd_handed = false;
+    int n_handed = 0;   // wave-uniform
     int32_t pd_old = 0, pd_c = 0, pd_dst = 0;
 
     while (t >= 0) {
@@ -540,6 +597,7 @@ void k_aggregate_grouped(GroupedArgs a) {
             if (a.dynamic && t_n >= 0 && lane == 0) ticket = atomicAdd(&a.counters[CTR_NEXT_RUN], 1);
         }
         int32_t s_n = 0, g0_n = 0, prev_word_n = -1, gd_n = 0;
+        int32_t pend_n = 0, deg_n = 1;
         int cnt_n = 0;
         if (t_n >= 0) {
             const int64_t e0n = static_cast<int64_t>(t_n) * kTileEdges;
@@ -575,6 +633,19 @@ void k_aggregate_grouped(GroupedArgs a) {
         }
         const uint64_t firstmask = __ballot(first_touch);
         const uint64_t multimask = __ballot(multi);
+        // FUSE: groups that lie wholly inside the tile are this wave's alone (sums, count); one of them that takes
+        // its destination's count to zero hands the finished row over instead of adding it
+        const int prev_end0 = below ? 63 - __clzll(static_cast<long long>(below)) : -1;
+        bool hands = false;
+        float hscale = 1.f;
+        if constexpr (FUSE) {
+            const bool owned = is_end && !(below == 0 && cut0) && !multi;
+            hands = owned && pend_pre == lane - prev_end0;
+            const float fd = static_cast<float>(deg_pre > 0 ? deg_pre : 1);
+            hscale = a.handover_norm == 0 ? 1.0f / fd : 1.0f / sqrtf(fd);
+        }
+        const uint64_t handmask = FUSE ? __ballot(hands) : 0ull;
+        if constexpr (FUSE) n_handed += __popcll(handmask);
         // accumulator row of the destination: the vertex id, or its slot in a bounded store
         int32_t rowv = dstv;
         if (MODEL != 2 && a.slot_of && closes) rowv = a.slot_of[dstv];
@@ -608,8 +679,9 @@ void k_aggregate_grouped(GroupedArgs a) {
                     const bool is_end_n = lane < cnt_n && s_n < 0;
                     const uint64_t below_n = __ballot(is_end_n) & ((1ull << lane) - 1ull);
                     if (is_end_n || lane == cnt_n - 1) gd_n = a.grp_dst[g0_n + __popcll(below_n)];
+                    read_ahead(is_end_n, gd_n, pend_n, deg_n);
                 }
-                finish_pending(pd_closes, pd_shared, pd_old, pd_c, pd_dst, a, stage, staged, lane);
+                finish_pending(pd_closes, pd_shared, pd_old, pd_c, pd_dst, pd_handed, a, stage, staged, lane);
                 pd_closes = false;
             }
             float r[U][VPL];
@@ -655,6 +727,11 @@ void k_aggregate_grouped(GroupedArgs a) {
                                     a.gat.m_cur[vh] = mn;
                                 }
                             }
+                        } else if (FUSE && ((handmask >> j) & 1ull)) {
+                            if constexpr (FUSE)
+                                row_hand_over<VPL>(dst - lane * VPL, lane, sum, ((firstmask >> j) & 1ull) != 0,
+                                                   __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(hscale), j)),
+                                                   a.handover_dt);
                         } else if (cut || ((multimask >> j) & 1ull)) {
                             row_add_shared<VPL>(dst, sum);
                         } else if ((firstmask >> j) & 1ull) {
@@ -685,8 +762,9 @@ void k_aggregate_grouped(GroupedArgs a) {
                 const bool is_end_n = lane < cnt_n && s_n < 0;
                 const uint64_t below_n = __ballot(is_end_n) & ((1ull << lane) - 1ull);
                 if (is_end_n || lane == cnt_n - 1) gd_n = a.grp_dst[g0_n + __popcll(below_n)];
+                read_ahead(is_end_n, gd_n, pend_n, deg_n);
             }
-            finish_pending(pd_closes, pd_shared, pd_old, pd_c, pd_dst, a, stage, staged, lane);
+            finish_pending(pd_closes, pd_shared, pd_old, pd_c, pd_dst, pd_handed, a, stage, staged, lane);
         }
 
         // pending count: minus the number of this tile's messages to the group.
@@ -696,8 +774,9 @@ void k_aggregate_grouped(GroupedArgs a) {
         // used (and the plain write made) while the next tile gathers.
         pd_closes = closes;
         pd_dst = dstv;
+        pd_handed = hands;
         if (closes) {
-            const int prev_end = below ? 63 - __clzll(static_cast<long long>(below)) : -1;
+            const int prev_end = prev_end0;
             pd_c = lane - prev_end;
             pd_shared = (below == 0 && cut0) || !is_end || multi;
             if (pd_shared) pd_old = atomicSub(&a.pending[dstv], pd_c);
@@ -706,9 +785,12 @@ void k_aggregate_grouped(GroupedArgs a) {
 
         rn = rn_n; t = t_n; t_end = t_end_n; run_start = run_start_n;
         s = s_n; g0 = g0_n; prev_word = prev_word_n; gd = gd_n;
+        pend_pre = pend_n; deg_pre = deg_n;
     }
-    finish_pending(pd_closes, pd_shared, pd_old, pd_c, pd_dst, a, stage, staged, lane);
+    finish_pending(pd_closes, pd_shared, pd_old, pd_c, pd_dst, pd_handed, a, stage, staged, lane);
     drain_ready(stage, staged, a.ready, a.counters, lane);
+    if (FUSE && lane == 0 && n_handed > 0)
+        atomicAdd(&a.counters64[CTR64_HANDED], static_cast<unsigned long long>(n_handed));
 }
 
 // GAT, first sweep of a planned chunk: one lane per edge of a 64-edge tile of
@@ -898,15 +980,27 @@ hipError_t launch_grouped_vpl(const GroupedArgs &a_in, int grid, uint32_t *run_t
         a.run_base = *run_tickets;
         *run_tickets += static_cast<uint32_t>(a.nruns);
     }
+    if constexpr (MODEL != 2 && sizeof(T) == 2) {
+        // finished rows are handed over in the 16-bit compute type: rows of 128 elements (the width whose flush
+        // kernel knows the hand-over), accumulators addressed by vertex id
+        // ... and only in launches whose groups are short on average: a group must lie inside a 64-edge tile to
+        // be handed over, and the hand-over's read-ahead (count and degree of every group end) costs a launch of
+        // long groups (the first chunk of a degree-ordered stream: 58 edges per group, nothing completes) more
+        // than it saves.
+        if (a.handover && !a.slot_of && a.d == 2 * kWave && a.n_groups > 0 && a.n_edges / a.n_groups < 32) {
+            hipLaunchKernelGGL((k_aggregate_grouped<T, 2, MODEL, true>), dim3(grid), dim3(kBlock), 0, s, a);
+            return hipGetLastError();
+        }
+    }
     switch (a.d / kWave) {
-        case 1: hipLaunchKernelGGL((k_aggregate_grouped<T, 1, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
-        case 2: hipLaunchKernelGGL((k_aggregate_grouped<T, 2, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
-        case 3: hipLaunchKernelGGL((k_aggregate_grouped<T, 3, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
-        case 4: hipLaunchKernelGGL((k_aggregate_grouped<T, 4, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
-        case 5: hipLaunchKernelGGL((k_aggregate_grouped<T, 5, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
-        case 6: hipLaunchKernelGGL((k_aggregate_grouped<T, 6, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
-        case 7: hipLaunchKernelGGL((k_aggregate_grouped<T, 7, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
-        case 8: hipLaunchKernelGGL((k_aggregate_grouped<T, 8, MODEL>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 1: hipLaunchKernelGGL((k_aggregate_grouped<T, 1, MODEL, false>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 2: hipLaunchKernelGGL((k_aggregate_grouped<T, 2, MODEL, false>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 3: hipLaunchKernelGGL((k_aggregate_grouped<T, 3, MODEL, false>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 4: hipLaunchKernelGGL((k_aggregate_grouped<T, 4, MODEL, false>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 5: hipLaunchKernelGGL((k_aggregate_grouped<T, 5, MODEL, false>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 6: hipLaunchKernelGGL((k_aggregate_grouped<T, 6, MODEL, false>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 7: hipLaunchKernelGGL((k_aggregate_grouped<T, 7, MODEL, false>), dim3(grid), dim3(kBlock), 0, s, a); break;
+        case 8: hipLaunchKernelGGL((k_aggregate_grouped<T, 8, MODEL, false>), dim3(grid), dim3(kBlock), 0, s, a); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

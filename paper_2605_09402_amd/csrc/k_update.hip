@@ -647,12 +647,19 @@ __device__ __forceinline__ int32_t quad_bcast(int32_t v, int i) {
 // of that row is masked off for the load, which costs no wait, while a dummy
 // load of a cached row still took its 512 bytes of the CU's load path (half
 // of all vertices at scale 26: 11.2 -> 10.6 ms per layer).
-template <int CT, int OWN>
+// A vertex whose row was handed over by the aggregation (bit 31 of its ready-list entry, `handv` != 0 in the
+// lane that holds the row's id) has the finished operand -- normalised, rounded to the compute type -- in the
+// first half of its accumulator row.  The load stays one unconditional 16-byte load per lane; only its
+// address differs: lanes 2k and 2k + 1 of the half-wave both read bytes 16 k .. 16 k + 15 of the row (eight
+// 16-bit values, four for each of them), so such a row costs 256 bytes of traffic instead of 512, and
+// pipe_store_rows picks the lane's half.  Straight-line code: this kernel is bound by instruction issue.
+template <int CT, int OWN, bool HAND>
 __device__ __forceinline__ void pipe_issue_rows(const UpdateArgs &a, int32_t idv, int32_t degv, int32_t slotv,
-                                                int lane, RowRegs<CT> &r) {
+                                                int32_t handv, int lane, RowRegs<CT> &r) {
     const int d = a.d_in;
     const int c4 = (lane & 31) * 4;
     const int col = c4 < d ? c4 : 0;
+    const int col_handed = ((lane & 31) >> 1) * 4;   // in floats: byte 16 * (l / 2) of the row
 #pragma unroll
     for (int i = 0; i < kPipeIters; ++i) {
         const int32_t id = quad_bcast(idv, i);
@@ -660,7 +667,9 @@ __device__ __forceinline__ void pipe_issue_rows(const UpdateArgs &a, int32_t idv
         const int32_t row = id >= 0 ? id : 0;
         const int32_t arow = a.slot_of ? quad_bcast(slotv, i) : row;
         r.acc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (dg > 0) r.acc[i] = *reinterpret_cast<const float4 *>(a.acc + static_cast<int64_t>(arow) * d + col);
+        int acol = col;
+        if constexpr (HAND) acol = quad_bcast(handv, i) != 0 ? col_handed : col;
+        if (dg > 0) r.acc[i] = *reinterpret_cast<const float4 *>(a.acc + static_cast<int64_t>(arow) * d + acol);
         if constexpr (OWN != 0) {
             const int64_t o = static_cast<int64_t>(row) * d + col;
             if constexpr (CT) r.own[i] = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(a.self_rows) + o);
@@ -672,9 +681,9 @@ __device__ __forceinline__ void pipe_issue_rows(const UpdateArgs &a, int32_t idv
 // Normalise and convert the rows loaded by pipe_issue_rows and store them into
 // the A tile.  Rows past the end of the ready list are stored as they came:
 // a row of A only feeds the same row of the product, which is never written.
-template <int CT, int OWN>
+template <int CT, int OWN, bool HAND>
 __device__ __forceinline__ void pipe_store_rows(const UpdateArgs &a, typename Elem<CT>::type *A, int stride,
-                                                int w, int lane, const RowRegs<CT> &r, int32_t degv) {
+                                                int w, int lane, const RowRegs<CT> &r, int32_t degv, int32_t handv) {
     const int d = a.d_in;
     const int c4 = (lane & 31) * 4;
     const float fd = static_cast<float>(degv > 0 ? degv : 1);
@@ -702,7 +711,16 @@ __device__ __forceinline__ void pipe_store_rows(const UpdateArgs &a, typename El
         }
         const bool keep = OWN == 2 || has_agg;
         if constexpr (CT) {
-            const uint32_t lo = pack2<CT>(v.x, v.y), hi = pack2<CT>(v.z, v.w);
+            uint32_t lo = pack2<CT>(v.x, v.y), hi = pack2<CT>(v.z, v.w);
+            if constexpr (HAND) {
+                // handed over: the 16 bytes loaded are the operand's values of this lane and its neighbour
+                const bool handed = quad_bcast(handv, i) != 0;
+                const bool odd = (lane & 1) != 0;
+                const uint32_t hlo = __float_as_uint(odd ? r.acc[i].z : r.acc[i].x);
+                const uint32_t hhi = __float_as_uint(odd ? r.acc[i].w : r.acc[i].y);
+                lo = handed ? hlo : lo;
+                hi = handed ? hhi : hi;
+            }
             *reinterpret_cast<uint2 *>(row) = make_uint2(keep ? lo : 0u, keep ? hi : 0u);
             // bf16 own rows go to LDS as they were loaded; the aggregate is rounded once
             if constexpr (OWN == 1) *reinterpret_cast<uint2 *>(row - d) = r.own[i];
@@ -769,7 +787,7 @@ __device__ __forceinline__ void contract_block(const typename Elem<CT>::type *ar
     }
 }
 
-template <int CT, int PPW, int OWN>
+template <int CT, int PPW, int OWN, bool HAND>
 __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
     using elem_t = typename Elem<CT>::type;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -800,6 +818,7 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
         for (size_t i = threadIdx.x; i < vecs; i += kPipeBlock) dst[i] = src[i];
     }
 
+    // ready-list entries: vertex id, bit 31 set when the aggregation handed the finished row over; -1: no row
     auto load_ids = [&](int tile) -> int32_t {
         int32_t id = -1;
         if (tile < ntiles) {
@@ -808,6 +827,8 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
         }
         return id;
     };
+    auto handed_of = [](int32_t raw) -> int32_t { return HAND && raw != -1 && raw < 0 ? 1 : 0; };
+    auto vertex_of = [](int32_t raw) -> int32_t { return HAND ? (raw == -1 ? -1 : raw & 0x7fffffff) : raw; };
     auto load_deg = [&](int32_t id) -> int32_t { return (a.indeg && id >= 0) ? a.indeg[id] : 1; };
     // bounded store: the slot that holds the vertex's accumulator row (-1 for vertices without in-edges,
     // whose row is never fetched)
@@ -841,29 +862,33 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
     // runs the contraction of the stored tile.
     int tile = blockIdx.x;
     const int G = gridDim.x;
-    int32_t id0 = load_ids(tile), id1 = load_ids(tile + G), id_a = load_ids(tile + 2 * G);
-    int32_t id_b = load_ids(tile + 3 * G);
+    int32_t raw0 = load_ids(tile), raw1 = load_ids(tile + G), raw_a = load_ids(tile + 2 * G);
+    int32_t id_b = load_ids(tile + 3 * G);   // still raw: cleaned when it moves up
+    int32_t id0 = vertex_of(raw0), id1 = vertex_of(raw1), id_a = vertex_of(raw_a);
+    int32_t hand0 = handed_of(raw0), hand1 = handed_of(raw1), hand_a = handed_of(raw_a);
     int32_t deg0 = load_deg(id0), deg1 = load_deg(id1), deg_a = load_deg(id_a);
     int32_t slot_a = load_slot(id_a);
     RowRegs<CT> r0, r1;
-    pipe_issue_rows<CT, OWN>(a, id0, deg0, load_slot(id0), lane, r0);
+    pipe_issue_rows<CT, OWN, HAND>(a, id0, deg0, load_slot(id0), hand0, lane, r0);
     __builtin_amdgcn_sched_barrier(0);   // keep the two sets' loads in this order, as in the loop
-    pipe_issue_rows<CT, OWN>(a, id1, deg1, load_slot(id1), lane, r1);
+    pipe_issue_rows<CT, OWN, HAND>(a, id1, deg1, load_slot(id1), hand1, lane, r1);
 
-    auto step = [&](RowRegs<CT> &regs, int32_t &idv, int32_t &degv, int buf) {
+    auto step = [&](RowRegs<CT> &regs, int32_t &idv, int32_t &degv, int32_t &handv, int buf) {
         elem_t *A = A0 + buf * a_elems;
         int32_t *tids = ids + buf * kTileRows;
-        pipe_store_rows<CT, OWN>(a, A, stride, w, lane, regs, degv);
+        pipe_store_rows<CT, OWN, HAND>(a, A, stride, w, lane, regs, degv, handv);
         if ((lane & 31) < 4) tids[w * kPipeRows + my_row] = idv;
         __syncthreads();
         idv = id_a;
         degv = deg_a;
+        handv = hand_a;
         const int32_t slotv = slot_a;
-        id_a = id_b;
+        id_a = vertex_of(id_b);
+        hand_a = handed_of(id_b);
         deg_a = load_deg(id_a);
         slot_a = load_slot(id_a);
         id_b = load_ids(tile + 4 * G);
-        pipe_issue_rows<CT, OWN>(a, idv, degv, slotv, lane, regs);
+        pipe_issue_rows<CT, OWN, HAND>(a, idv, degv, slotv, handv, lane, regs);
 
         f32x16_t c[PPW];
 #pragma unroll
@@ -896,9 +921,9 @@ __global__ __launch_bounds__(kPipeBlock) void k_update_pipelined(UpdateArgs a) {
     // between them the compiler has to assume that a round may start right
     // after the first step's loads were issued, and then waits for them all.
     for (; tile < ntiles; tile += G) {
-        step(r0, id0, deg0, 0);
+        step(r0, id0, deg0, hand0, 0);
         tile += G;
-        step(r1, id1, deg1, 1);
+        step(r1, id1, deg1, hand1, 1);
     }
 }
 
@@ -910,24 +935,31 @@ size_t pipelined_lds_bytes(int K, int d_out, bool bf16c) {
            2 * static_cast<size_t>(kTileRows) * (K + lds_pad(bf16c)) * es;
 }
 
-template <int CT, int PPW, int OWN>
+template <int CT, int PPW, int OWN, bool HAND>
 hipError_t launch_pipelined_t(const UpdateArgs &a, int grid, hipStream_t s) {
     const size_t lds = pipelined_lds_bytes(a.K, a.d_out, CT);
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_update_pipelined<CT, PPW, OWN>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_update_pipelined<CT, PPW, OWN, HAND>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL((k_update_pipelined<CT, PPW, OWN>), dim3(grid), dim3(kPipeBlock), lds, s, a);
+    hipLaunchKernelGGL((k_update_pipelined<CT, PPW, OWN, HAND>), dim3(grid), dim3(kPipeBlock), lds, s, a);
     return hipGetLastError();
 }
 
 template <int CT, int OWN>
 hipError_t launch_pipelined_o(const UpdateArgs &a, int grid, hipStream_t s) {
     const int NB = (a.d_out + 31) / 32;
-    return 2 * NB <= 8 ? launch_pipelined_t<CT, 1, OWN>(a, grid, s) : launch_pipelined_t<CT, 2, OWN>(a, grid, s);
+    if constexpr (CT != 0 && OWN != 2) {
+        // the ready list may hold rows handed over by the aggregation (bit 31 of the entry)
+        if (a.handed_rows)
+            return 2 * NB <= 8 ? launch_pipelined_t<CT, 1, OWN, true>(a, grid, s)
+                               : launch_pipelined_t<CT, 2, OWN, true>(a, grid, s);
+    }
+    return 2 * NB <= 8 ? launch_pipelined_t<CT, 1, OWN, false>(a, grid, s)
+                       : launch_pipelined_t<CT, 2, OWN, false>(a, grid, s);
 }
 
 // own row: concatenated (SAGE), added (GIN) or unused
@@ -1083,6 +1115,13 @@ hipError_t launch_pack_weights(const void *W, int w_dt, int K, int d_out, int co
         hipLaunchKernelGGL(k_pack_weights<0>, dim3(blocks), dim3(kBlock), 0, s, W, w_dt, K, d_out,
                            static_cast<float *>(packed));
     return hipGetLastError();
+}
+
+// Whether launch_update runs the pipelined kernel for a flush of this shape (the kernel that knows rows handed
+// over by the aggregation).
+bool update_takes_handed_rows(int model, int d_in, int K, int d_out, int compute_dt) {
+    return compute_dt != 0 && (model == 0 || model == 1) && d_in == 128 &&
+           pipelined_lds_bytes(K, d_out, true) <= 160 * 1024;
 }
 
 hipError_t launch_update(const UpdateArgs &a, hipStream_t s) {

@@ -133,7 +133,7 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
             planned_only: bool = False, hot_slots: int = 0, evict_policy: int = 0,
             transform_first: bool = False, plan_block: Optional[tuple] = None,
             device_later: bool = False, tiles_per_run: int = 0, piece_tiles: int = 0,
-            csr_stream: bool = False) -> GpuRun:
+            csr_stream: bool = False, no_handover: bool = False) -> GpuRun:
     """Drive all layers through the C ABI.  With pinned_host the graph and the
     layer-0 features stay in pinned host memory and are staged by the library.
     planned_only sets ATLAS_FLAG_PLANNED_ONLY (no zero fill of the accumulators;
@@ -141,7 +141,8 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
     device_later (with pinned_host): layers after the first are given the previous
     layer's output where it lies in device memory instead of a pinned host copy.
     tiles_per_run / piece_tiles: the launch-shape fields of atlas_dims_t (0: the library's choice).
-    csr_stream: ATLAS_FLAG_CSR_STREAM, long chunks without a planned chunk are not regrouped on the fly."""
+    csr_stream: ATLAS_FLAG_CSR_STREAM, long chunks without a planned chunk are not regrouped on the fly.
+    no_handover: ATLAS_FLAG_NO_HANDOVER, finished rows take the fp32 round trip to the update."""
     dev = torch.device("cuda:0")
     n, e = case.n, case.e
     run = GpuRun(extra_roundings=1 if transform_first else 0)
@@ -190,7 +191,8 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
                                (atlas.FLAG_EMB_RESIDENT if emb_resident else 0) |
                                (atlas.FLAG_PLANNED_ONLY if planned_only else 0) |
                                (atlas.FLAG_TRANSFORM_FIRST if transform_first else 0) |
-                               (atlas.FLAG_CSR_STREAM if csr_stream else 0),
+                               (atlas.FLAG_CSR_STREAM if csr_stream else 0) |
+                               (atlas.FLAG_NO_HANDOVER if no_handover else 0),
                                tiles_per_run=tiles_per_run, piece_tiles=piece_tiles)
         weights = atlas.make_weights(W, b, sdt, a_s, a_d)
         h = atlas.atlas_layer_init(graph, dims, weights, stream)

@@ -414,3 +414,46 @@ def test_long_chunks_without_a_plan_are_regrouped(oracle, H, model, store):
     run = H.run_gpu(case, csr_stream=True)
     H.check_outputs(oracle, case, run)
     assert all(st["chunks_regrouped"] == 0 and st["chunks_csr_stream"] == 2 for st in run.stats)
+
+
+@pytest.mark.parametrize("store", [torch.bfloat16, torch.float16], ids=["bf16", "f16"])
+@pytest.mark.parametrize("model", ["sage", "gcn"])
+@pytest.mark.parametrize("planned_only", [False, True])
+def test_finished_rows_handed_to_the_update(oracle, H, model, store, planned_only):
+    """The fused part of the flush: a vertex completed by an edge message inside a group that one
+    wavefront sums alone leaves the aggregation as the update's 16-bit operand.  Outputs must be
+    bit-identical with the hand-over switched off wherever the sums themselves are reproducible (a
+    vertex of in-degree <= 8 has at most two pieces per chunk, and a + b = b + a; heavier vertices are
+    added to with atomics in an order that varies from run to run), match the oracle, and the number of rows handed
+    over must be positive and at most the number of vertices an edge message completes (from the
+    oracle's in-neighbour lists).  Degree-ordered R-MAT scale 13, chunks of 1,000 sources (late
+    chunks complete many low-degree vertices), with and without the zero-fill-free layer start
+    (first-touch groups), also through pinned host memory in pieces and a regrouped chunk."""
+    g = gen.rmat_graph(SEED + 73, 13, 16, self_loops=(model == "gcn"))
+    off, col = gen.build_csr(g)
+    new_of_old, _ = oracle.reorder_indegree_desc(oracle.in_degree(g.n, col.numpy()))
+    g = g.with_relabel(torch.from_numpy(new_of_old.astype(np.int64)))
+    case = H.make_case(model, g, SEED + 73, [128, 128, 64], 1000, store=store)
+    run = H.run_gpu(case, snapshots=True, plan=True, planned_only=planned_only)
+    ref = H.run_gpu(case, plan=True, planned_only=planned_only, no_handover=True)
+    H.check_integers(oracle, case, run, layer=0)
+    H.check_integers(oracle, case, run, layer=1)
+    print("handed over", model, store, H.check_outputs(oracle, case, run), [st["rows_handed_over"] for st in run.stats])
+    il = oracle.InLists.from_csr(case.off.numpy(), case.col.numpy())
+    indeg = np.diff(il.in_off)
+    light = torch.from_numpy(indeg <= 8).to(run.outputs[0].device)
+
+    def same(got, want):
+        assert torch.equal(got[0][light], want[0][light]), "outputs differ with the hand-over switched off"
+        for a, b in zip(got, want):
+            assert torch.allclose(a.float(), b.float(), rtol=2.0 ** -6, atol=1e-3)
+    same(run.outputs, ref.outputs)
+    last_src = np.where(indeg > 0, il.in_src[np.maximum(il.in_off[1:] - 1, 0)], -1)
+    own = np.arange(case.n)
+    by_edge = (indeg > 0) & ((last_src // case.chunk >= own // case.chunk) if model == "sage" else True)
+    for st, st_ref in zip(run.stats, ref.stats):
+        assert 0 < st["rows_handed_over"] <= int(by_edge.sum()), (st["rows_handed_over"], int(by_edge.sum()))
+        assert st_ref["rows_handed_over"] == 0
+    run = H.run_gpu(case, plan=True, planned_only=planned_only, pinned_host=True, device_later=True, piece_tiles=3)
+    same(run.outputs, ref.outputs)
+    assert all(st["rows_handed_over"] > 0 for st in run.stats)
