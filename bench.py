@@ -405,7 +405,9 @@ def main() -> int:
     K = 2 * wl.dims[0] if wl.model == "sage" else wl.dims[0]
     upd_flops = 2.0 * n * K * wl.dims[1]      # SAGE / GCN: the flush GEMM; GAT: the per-chunk transform (in ms_self)
     upd_s = ps["ms_update"] / 1e3
-    upd_bytes = n_with_in * 4 * d + n * ((s_in * d if wl.model in ("sage", "gin") else 0) + s_in * wl.dims[1])
+    handed = main_res["last_stats"]["rows_handed_over"]   # their operand is read in the storage type, not as fp32 sums
+    upd_bytes = ((n_with_in - handed) * 4 * d + handed * s_in * d +
+                 n * ((s_in * d if wl.model in ("sage", "gin") else 0) + s_in * wl.dims[1]))
     mfma_peak = 2.5e15 if sdt in (atlas.DTYPE_BF16, atlas.DTYPE_F16) else 157.3e12
     # the contraction's ceiling at this shape: the MFMA peak, or its flops in the time its bytes need at the HBM peak
     upd_ceiling = min(mfma_peak, upd_flops / (upd_bytes / 8e12))
