@@ -418,3 +418,43 @@ def test_in_degree_from_the_plan(oracle, H, atlas, plan_block):
         assert ei.value.status == atlas.E_STATE
     finally:
         atlas.atlas_plan_destroy(hp)
+
+
+def test_measurement_probes(atlas):
+    """The benchmark's bare-kernel probes do what they say: the copy copies, the 2:1 stream
+    combines its two inputs, the gather runs over ragged id lists without touching anything but
+    its sink, and the dense-row contraction equals rows x W (fp64 matmul of the stored 16-bit
+    values, library routine) to the 16-bit output's rounding, for the K-sliced kernel (more than
+    128 columns), the generic one, a ragged row count and both 16-bit types."""
+    dev = torch.device("cuda:0")
+    a = torch.randint(-2 ** 31, 2 ** 31 - 1, (1 << 20,), dtype=torch.int32, device=dev)
+    b = torch.randint(-2 ** 31, 2 ** 31 - 1, (1 << 20,), dtype=torch.int32, device=dev)
+    out = torch.zeros_like(a)
+    atlas.atlas_probe_copy(out, a, a.numel() * 4)
+    torch.cuda.synchronize()
+    assert torch.equal(out, a)
+    atlas.atlas_probe_mix21(out, a, b, a.numel() * 4)
+    torch.cuda.synchronize()
+    assert torch.equal(out, a ^ b)
+    with pytest.raises(atlas.AtlasError):
+        atlas.atlas_probe_copy(out, a, 24)          # not a multiple of 16
+    table = torch.randint(0, 255, (4096, 256), dtype=torch.uint8, device=dev)
+    sink = torch.zeros(atlas.atlas_probe_gather_sink_bytes() // 4, dtype=torch.int32, device=dev)
+    for n_ids in (1, 63, 64, 65, 100_003):
+        ids = torch.randint(0, 4096, (n_ids,), dtype=torch.int32, device=dev)
+        before = table.clone()
+        atlas.atlas_probe_row_gather(table, 4096, ids, n_ids, sink)
+        torch.cuda.synchronize()
+        assert torch.equal(table, before)
+    for dt, tdt in ((atlas.DTYPE_BF16, torch.bfloat16), (atlas.DTYPE_F16, torch.float16)):
+        for n_rows, K, d_out in ((1000, 1024, 256), (515, 256, 128), (129, 512, 192)):
+            rows = (torch.rand((n_rows, K), device=dev) - 0.5).to(tdt)
+            W = (torch.rand((K, d_out), device=dev) - 0.5).to(tdt)
+            got = torch.full((n_rows, d_out), float("nan"), dtype=tdt, device=dev)
+            atlas.atlas_probe_dense_rows(dt, rows, n_rows, K, d_out, W, got, 2)
+            ref = rows.double().cpu().numpy() @ W.double().cpu().numpy()
+            err = np.abs(got.double().cpu().numpy() - ref).max() / np.abs(ref).max()
+            assert err <= (2.0 ** -8 if tdt == torch.bfloat16 else 2.0 ** -11), (tdt, n_rows, K, d_out, err)
+    with pytest.raises(atlas.AtlasError) as ei:
+        atlas.atlas_probe_dense_rows(atlas.DTYPE_F32, rows, n_rows, K, d_out, W, got, 1)
+    assert ei.value.status == atlas.E_BAD_DIMS
