@@ -63,9 +63,14 @@ def _draw_sgc(rng, oracle, H, idx, store):
     return case, opts, {"run": int(rng.choice([0, 2, 5, 8])), "piece": 0}
 
 
-def _draw(rng, oracle, H, idx):
+def _draw(rng, oracle, H, idx, handed=False):
+    """handed: only the combinations in which the flush may leave finished rows to the update as its 16-bit
+    operand (SAGE or GCN, 16-bit storage, 128 input features, a plan), drawn with the same other options."""
     model = ["sage", "gcn", "gin", "gat", "sgc"][int(rng.integers(5))]
     store = [torch.float32, torch.bfloat16, torch.float16][int(rng.integers(3))]
+    if handed:
+        model = ["sage", "gcn"][int(rng.integers(2))]
+        store = [torch.bfloat16, torch.float16][int(rng.integers(2))]
     if model == "gat":
         return _draw_gat(rng, oracle, H, idx)
     if model == "sgc":
@@ -81,7 +86,7 @@ def _draw(rng, oracle, H, idx):
         off, col = gen.build_csr(g)
         new_of_old, _ = oracle.reorder_indegree_desc(oracle.in_degree(g.n, col.numpy()))
         g = g.with_relabel(torch.from_numpy(new_of_old.astype(np.int64)))
-    d_in = int(rng.choice([64, 128, 192, 256]))
+    d_in = 128 if handed else int(rng.choice([64, 128, 192, 256]))
     if model == "sage" and store == torch.float32:
         d_in = min(d_in, 256)
     dims = [d_in, int(rng.choice([64, 128])), int(rng.choice([16, 48, 64]))]
@@ -90,6 +95,8 @@ def _draw(rng, oracle, H, idx):
     plan_kind = int(rng.integers(3))          # 0 none, 1 plain, 2 source-blocked
     pinned = bool(rng.random() < 0.4)
     tf = bool(rng.random() < 0.25)
+    if handed:
+        plan_kind, tf = max(1, plan_kind), False
     if model == "gin" and store == torch.float16:
         tf = True                             # half-precision GIN runs transform-first only
     if tf:
@@ -119,14 +126,18 @@ def _draw(rng, oracle, H, idx):
             opts["flush_every"] = 1       # the replay flushes after every chunk; later flushes hold rows longer
         except ValueError:
             pass
+    if handed and rng.random() < 0.25:
+        opts["no_handover"] = True
+    if not plan_kind and rng.random() < 0.3:
+        opts["csr_stream"] = True
     return case, opts, knobs
 
 
-@pytest.mark.parametrize("idx", range(48))
+@pytest.mark.parametrize("idx", range(64))
 def test_random_configuration(oracle, H, idx):
     import paper_2605_09402_amd as atlas
     rng = np.random.default_rng(SEED + 1000 + idx)
-    case, opts, knobs = _draw(rng, oracle, H, idx)
+    case, opts, knobs = _draw(rng, oracle, H, idx, handed=idx >= 48)
     print("config %d: %s %s n=%d e=%d dims=%s chunk=%d %s %s" % (idx, case.model, case.store, case.n, case.e, case.dims,
                                                                 case.chunk, opts, knobs), flush=True)
     run = H.run_gpu(case, tiles_per_run=knobs["run"], piece_tiles=knobs["piece"], **opts)
