@@ -83,6 +83,13 @@ def main() -> int:
                          "half-precision MFMA in the update)")
     ap.add_argument("--transform-first", action="store_true",
                     help="apply W to each chunk before it is pushed (d_out-wide messages and accumulators)")
+    ap.add_argument("--dense-max-gb", type=float, default=-1.0,
+                    help="plan with a dense part for the first chunk: byte limit of its cells in GB (0: none; "
+                         "default: 32 for config5, none for the other workloads)")
+    ap.add_argument("--dense-cells-per-edge", type=int, default=0,
+                    help="dense part: most cells a block may spend per edge it holds (0: the library's default)")
+    ap.add_argument("--no-dense", action="store_true",
+                    help="push the plan's dense part as the planned chunk it also is (ATLAS_FLAG_NO_DENSE)")
     ap.add_argument("--no-handover", action="store_true",
                     help="switch the fused part of the flush off: every finished row takes the fp32 round trip")
     ap.add_argument("--no-narrow-first", action="store_true",
@@ -193,7 +200,14 @@ def main() -> int:
             args.plan_hot_min = 32 * max(1, chunk >> args.plan_block_log2)
         if args.plan_block_log2 > 0 and chunk <= (1 << args.plan_block_log2):
             args.plan_block_log2 = 0   # a chunk of one block: nothing to reorder
-        if args.plan_block_log2 > 0:
+        if args.dense_max_gb < 0:
+            args.dense_max_gb = 32.0 if args.workload == "config5" and args.hot_slots_frac <= 0 else 0.0
+        if args.dense_max_gb > 0:
+            plan, prep["plan"] = timed_ms(lambda: atlas.atlas_plan_create_dense(
+                pg, chunk, (1 << args.plan_block_log2) if args.plan_block_log2 > 0 else 0,
+                args.plan_hot_min if args.plan_block_log2 > 0 else 0, int(args.dense_max_gb * 1e9),
+                args.dense_cells_per_edge))
+        elif args.plan_block_log2 > 0:
             plan, prep["plan"] = timed_ms(
                 lambda: atlas.atlas_plan_create_blocked(pg, chunk, 1 << args.plan_block_log2, args.plan_hot_min))
         else:
@@ -201,6 +215,10 @@ def main() -> int:
         plan_info = atlas.atlas_plan_info(plan)
         log("plan built in %.1f ms: %d groups, %.2f GB" % (prep["plan"], plan_info["num_groups"],
                                                             plan_info["bytes_device"] / 1e9))
+        if plan_info["dense_edges"]:
+            log("dense part of chunk 0: %.1f M edges (%.1f%% of all) in %.2f G cells, %d destinations x up to %d sources"
+                % (plan_info["dense_edges"] / 1e6, 100.0 * plan_info["dense_edges"] / max(e, 1),
+                   plan_info["dense_cells"] / 1e9, plan_info["dense_rows"], plan_info["dense_max_sources"]))
         # the ordered graph's in-degrees are the plan's group sizes
         _, prep["in_degree"] = timed_ms(lambda: atlas.atlas_plan_in_degree(plan, indeg))
     else:
@@ -240,7 +258,8 @@ def main() -> int:
                                flags=(atlas.FLAG_TIMING if timing else 0) | atlas.FLAG_EMB_RESIDENT |
                                (atlas.FLAG_PLANNED_ONLY if planned else 0) |
                                (atlas.FLAG_TRANSFORM_FIRST if tf else 0) |
-                               (atlas.FLAG_NO_HANDOVER if args.no_handover else 0),
+                               (atlas.FLAG_NO_HANDOVER if args.no_handover else 0) |
+                               (atlas.FLAG_NO_DENSE if args.no_dense else 0),
                                hot_slots=hot_slots, evict_policy=1 if args.evict_policy == "max" else 0)
         W, b = params[li]
         h = atlas.atlas_layer_init(graph, dims, atlas.make_weights(W, b, sdt, attn[li][0], attn[li][1]), stream)
@@ -285,7 +304,7 @@ def main() -> int:
         for _ in range(args.warmup):
             run_layer(graph, planned, 0, x0, True)
         torch.cuda.synchronize()
-        acc = {"ms_aggregate": 0.0, "ms_update": 0.0, "ms_self": 0.0, "ms_init": 0.0, "ms_copy": 0.0}
+        acc = {"ms_aggregate": 0.0, "ms_dense": 0.0, "ms_update": 0.0, "ms_self": 0.0, "ms_init": 0.0, "ms_copy": 0.0}
         step_ms = []   # atlas_layer_finish waits for the layer, so each step ends synchronised
         t0 = time.perf_counter()
         st = None
@@ -319,8 +338,8 @@ def main() -> int:
     if do_device:
         dev_res = time_layers(graph_dev, plan is not None, wl.X)
         ps = dev_res["per_step"]
-        log("HBM-resident layer: %.2f ms/step; aggregate %.2f, update %.2f, self %.2f, init %.2f ms per step"
-            % (dev_res["ms_per_step"], ps["ms_aggregate"], ps["ms_update"], ps["ms_self"], ps["ms_init"]))
+        log("HBM-resident layer: %.2f ms/step; aggregate %.2f, dense part %.2f, update %.2f, self %.2f, init %.2f ms per step"
+            % (dev_res["ms_per_step"], ps["ms_aggregate"], ps["ms_dense"], ps["ms_update"], ps["ms_self"], ps["ms_init"]))
         if args.sync_chunks:
             log("last layer, ms per chunk (kernels, no overlap): " + " ".join("%.1f" % v for v in chunk_wall_ms[-nchunks:]))
         if dev_res["e2e_ms"] is not None:
@@ -365,7 +384,14 @@ def main() -> int:
         # accumulator row -- written only by a destination's first group, read and written by every later one;
         # per 64-edge tile its first-group index.
         G, G1 = plan_info["num_groups"], plan_info["num_first_groups"]
-        algo_bytes_layer = e * (4 + d * s_in) + G * (4 + 8) + (2 * G - G1) * 4 * d + ((e + 63) // 64) * 4
+        e_list = e
+        if main_res["last_stats"]["edges_contracted"]:
+            # the dense part went through the contraction (timed apart, see `dense_part`): its edges and groups are
+            # not the edge-list kernel's, and its destinations' first touch is the contraction's
+            e_list = e - plan_info["dense_edges"]
+            G -= plan_info["dense_groups"]
+            G1 = max(0, G1 - plan_info["dense_groups"])
+        algo_bytes_layer = e_list * (4 + d * s_in) + G * (4 + 8) + (2 * G - G1) * 4 * d + ((e_list + 63) // 64) * 4
         algo_note = ("edge word + source row per edge; destination word, pending RMW and fp32 row "
                      "(store for a first group, read + write otherwise) per group; tile index per 64 edges")
     else:
@@ -398,8 +424,22 @@ def main() -> int:
         "traffic_over_compulsory": None if traffic is None else round(traffic * nchunks / compulsory_bytes, 2),
         "streaming_model_effective_GBps": round(streaming_bytes / agg_s_per_layer / 1e9, 1),
         "launches": launches, "avg_launch_ms": round(ps["ms_aggregate"] / nchunks, 4),
-        "edges_per_s_in_kernel": round(e / agg_s_per_layer, 1),
+        "edges_per_s_in_kernel": round((e_list if plan_info is not None else e) / agg_s_per_layer, 1),
     }
+    dense_part = None
+    if plan_info is not None and plan_info["dense_edges"]:
+        ms_d = ps["ms_dense"]
+        contracted = bool(main_res["last_stats"]["edges_contracted"])
+        dense_part = {"edges": plan_info["dense_edges"], "share_of_edges": round(plan_info["dense_edges"] / max(e, 1), 4),
+                      "cells": plan_info["dense_cells"], "destinations": plan_info["dense_rows"],
+                      "max_sources": plan_info["dense_max_sources"], "contracted": contracted,
+                      "ms_per_layer": round(ms_d, 3),
+                      "edges_per_s": round(plan_info["dense_edges"] / max(ms_d, 1e-9) * 1e3, 1)}
+        if contracted:
+            fl = 2.0 * plan_info["dense_cells"] * d
+            dense_part.update({"kernel": "k_dense_contract", "tflops": round(fl / (ms_d / 1e3) / 1e12, 1),
+                               "frac_of_mfma_peak": round(fl / (ms_d / 1e3) / 2.5e15, 4),
+                               "cells_GBps": round(plan_info["dense_cells"] / (ms_d / 1e3) / 1e9, 1)})
     if roofline["frac"] > 1.0:
         log("note: the kernel's algorithmic bytes per second exceed the HBM peak (rows served from cache)")
     K = 2 * wl.dims[0] if wl.model == "sage" else wl.dims[0]
@@ -601,8 +641,10 @@ def main() -> int:
         "hot_store": None if not hot_slots else {
             "slots": hot_slots, "policy": args.evict_policy + "-pending", "evictions_per_layer": st["hot_evictions"],
             "reloads_per_layer": st["hot_reloads"], "peak_slots": st["hot_peak_slots"]},
-        "layer_ms": {"aggregate": round(ps["ms_aggregate"], 3), "update": round(ps["ms_update"], 3),
-                     "self": round(ps["ms_self"], 3), "init": round(ps["ms_init"], 3)},
+        "layer_ms": {"aggregate": round(ps["ms_aggregate"], 3), "dense_part": round(ps["ms_dense"], 3),
+                     "update": round(ps["ms_update"], 3), "self": round(ps["ms_self"], 3), "init": round(ps["ms_init"], 3)},
+        # the first chunk's dense corner, pushed as a contraction on the matrix cores (atlas_plan_create_dense)
+        "dense_part": dense_part,
         # the fused part of the flush: rows that went from the aggregation to the update as its 16-bit operand
         "fused_flush": {"rows_handed_over_per_layer": st["rows_handed_over"],
                         "share_of_vertices": round(st["rows_handed_over"] / max(n, 1), 4)},

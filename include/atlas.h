@@ -98,6 +98,8 @@ enum atlas_flags {
                                     plans lack the list of rows to clear).  With it, ATLAS_DBG_ACC rows of vertices
                                     that have received nothing yet are undefined. */
     ATLAS_FLAG_NO_HANDOVER = 32, /* switch the fused part of the flush off (see atlas_flush_ready); for comparisons */
+    ATLAS_FLAG_NO_DENSE = 64,    /* push the dense part of a plan (see atlas_plan_create_dense) as the planned
+                                    chunk it also is instead of a contraction; for comparisons */
     ATLAS_FLAG_CSR_STREAM = 16,  /* never regroup a chunk on the fly: a chunk without a planned chunk is pushed
                                     straight from the CSR with fp32 atomics, whatever its length (see
                                     atlas_broadcast_chunk) */
@@ -236,8 +238,13 @@ typedef struct {
                                    num_chunks                                               */
     float ms_regroup;           /* host time of that regrouping (it is synchronous), always
                                    measured                                                 */
+    float ms_dense;             /* ATLAS_FLAG_TIMING: time of the dense part of the plan's first
+                                   chunk, pushed either way (not part of ms_aggregate)      */
     int64_t rows_handed_over;   /* vertices whose finished row went from the aggregation to the
                                    update as the update's operand (see atlas_flush_ready)   */
+    int64_t edges_contracted;   /* edges of the plan's dense part that were pushed as a dense
+                                   contraction (see atlas_plan_create_dense); they are part
+                                   of edges_processed                                       */
 } atlas_layer_stats_t;
 
 /* Create the state of one layer (Sec. 3.4: pending-message tracker and
@@ -340,6 +347,31 @@ int atlas_plan_create(const atlas_graph_t *graph, int64_t chunk_sources, atlas_p
  * Not for GAT layers (E_BAD_DIMS at atlas_layer_init); N < 2^30 (E_OVERFLOW). */
 int atlas_plan_create_blocked(const atlas_graph_t *graph, int64_t chunk_sources, int64_t block_sources,
                               int64_t hot_min_edges, atlas_plan_t **out);
+/* atlas_plan_create_blocked with a dense part for the first chunk (DEVICE graphs; E_BAD_DIMS
+ * otherwise).  With ids in in-degree-descending order (Sec. 3.8) the hottest sources and the
+ * hottest destinations both lie at the front, and the first chunk's edges between them are so
+ * many that this corner of the adjacency matrix holds more than one edge per hundred cells.
+ * There a message costs more as a 256-byte row gather than its cell costs in a dense product.
+ * The plan therefore keeps the multiplicities of that corner as a staircase of byte matrices
+ * (256 destinations form a band; a band takes its first S_band sources, S_band non-increasing
+ * over the bands) and the layer adds  multiplicities x rows  to the accumulators of those
+ * destinations on the matrix cores before it pushes the chunk's other edges: multiplicities up
+ * to 255 are exact 16-bit floats, the products are exact, the sums are fp32 -- the edge stream's
+ * sums in another order.  Pending counts drop by each destination's number of dense messages in
+ * one step, vertices that complete are appended to the ready list as for any other message.
+ * The region is chosen from the chunk's edge counts over log-spaced (source rank, destination
+ * rank) blocks: a block belongs to it when it holds at least one edge per dense_cells_per_edge
+ * cells (0: the library's default, 64) and so do the blocks before it; the value is halved until
+ * the cells fit dense_max_bytes (0: no dense part, plain atlas_plan_create_blocked).  A cell that
+ * is full (255) leaves further copies of its edge to the chunk's edge list.  When no block is
+ * dense enough the plan is an ordinary one.
+ * The contraction serves layers that sum plain rows (SAGE_MEAN, GIN, SGC_HOP), 16-bit rows of
+ * width 64 or 128 (with ATLAS_FLAG_TRANSFORM_FIRST: the pushed products); every other layer, and
+ * ATLAS_FLAG_NO_DENSE, pushes the same edges as a planned chunk, which the plan keeps as well.
+ * Not for GAT layers or a bounded accumulator store (E_BAD_DIMS at atlas_layer_init). */
+int atlas_plan_create_dense(const atlas_graph_t *graph, int64_t chunk_sources, int64_t block_sources,
+                            int64_t hot_min_edges, int64_t dense_max_bytes, int64_t dense_cells_per_edge,
+                            atlas_plan_t **out);
 int atlas_plan_destroy(atlas_plan_t *plan);
 
 /* In-degree of every vertex (histogram of col_indices), int32[N] in DEVICE
@@ -407,6 +439,11 @@ int atlas_sample_in_edges(const atlas_graph_t *graph, const uint32_t *edge_key, 
 typedef struct {
     int64_t num_chunks, num_edges, num_groups, num_first_groups;
     int64_t bytes_device, bytes_pinned_host;
+    int64_t dense_edges;        /* edges the dense part of the first chunk holds (0: no dense part) */
+    int64_t dense_groups;       /* their destination groups (part of num_groups)                    */
+    int64_t dense_cells;        /* its cells = bytes                                                */
+    int64_t dense_rows;         /* destinations [0, dense_rows) have a band                         */
+    int64_t dense_max_sources;  /* sources the longest band takes                                   */
 } atlas_plan_info_t;
 int atlas_plan_info(const atlas_plan_t *plan, atlas_plan_info_t *info);
 

@@ -27,6 +27,7 @@ FLAG_PLANNED_ONLY = 4
 FLAG_TRANSFORM_FIRST = 8
 FLAG_CSR_STREAM = 16
 FLAG_NO_HANDOVER = 32
+FLAG_NO_DENSE = 64
 EVICT_MIN_PENDING, EVICT_MAX_PENDING = 0, 1
 DBG_INDEG, DBG_PENDING, DBG_READY, DBG_READY_COUNT, DBG_ACC = range(5)
 
@@ -34,7 +35,7 @@ EXPORTS = [
     "atlas_layer_init", "atlas_attention_prepass", "atlas_broadcast_chunk", "atlas_flush_ready",
     "atlas_layer_finish", "atlas_in_degree", "atlas_reorder_indegree_desc", "atlas_debug_copy",
     "atlas_release_cache", "atlas_strerror", "atlas_last_hip_error", "atlas_plan_create", "atlas_plan_destroy",
-    "atlas_reorder_score_desc", "atlas_sample_in_edges", "atlas_plan_create_blocked",
+    "atlas_reorder_score_desc", "atlas_sample_in_edges", "atlas_plan_create_blocked", "atlas_plan_create_dense",
     "atlas_reorder_indegree_desc_noalloc", "atlas_plan_info", "atlas_plan_in_degree", "atlas_probe_copy", "atlas_probe_row_gather",
     "atlas_probe_dense_rows", "atlas_probe_gather_sink_bytes", "atlas_probe_mix21",
 ]
@@ -70,13 +71,15 @@ class atlas_layer_stats_t(ctypes.Structure):
                 ("ms_init", ctypes.c_float), ("hot_evictions", ctypes.c_int64), ("hot_reloads", ctypes.c_int64),
                 ("hot_peak_slots", ctypes.c_int64), ("chunks_planned", ctypes.c_int64),
                 ("chunks_csr_stream", ctypes.c_int64), ("chunks_regrouped", ctypes.c_int64),
-                ("ms_regroup", ctypes.c_float), ("rows_handed_over", ctypes.c_int64)]
+                ("ms_regroup", ctypes.c_float), ("ms_dense", ctypes.c_float), ("rows_handed_over", ctypes.c_int64),
+                ("edges_contracted", ctypes.c_int64)]
 
 
 class atlas_plan_info_t(ctypes.Structure):
     _fields_ = [("num_chunks", ctypes.c_int64), ("num_edges", ctypes.c_int64), ("num_groups", ctypes.c_int64),
                 ("num_first_groups", ctypes.c_int64), ("bytes_device", ctypes.c_int64),
-                ("bytes_pinned_host", ctypes.c_int64)]
+                ("bytes_pinned_host", ctypes.c_int64), ("dense_edges", ctypes.c_int64), ("dense_groups", ctypes.c_int64), ("dense_cells", ctypes.c_int64),
+                ("dense_rows", ctypes.c_int64), ("dense_max_sources", ctypes.c_int64)]
 
 
 class AtlasError(RuntimeError):
@@ -118,6 +121,7 @@ def lib() -> ctypes.CDLL:
         L.atlas_release_cache.argtypes = []
         L.atlas_plan_create.argtypes = [ctypes.POINTER(atlas_graph_t), i64, ctypes.POINTER(vp)]
         L.atlas_plan_create_blocked.argtypes = [ctypes.POINTER(atlas_graph_t), i64, i64, i64, ctypes.POINTER(vp)]
+        L.atlas_plan_create_dense.argtypes = [ctypes.POINTER(atlas_graph_t), i64, i64, i64, i64, i64, ctypes.POINTER(vp)]
         L.atlas_plan_destroy.argtypes = [vp]
         L.atlas_plan_info.argtypes = [vp, ctypes.POINTER(atlas_plan_info_t)]
         L.atlas_plan_in_degree.argtypes = [vp, vp, vp]
@@ -226,6 +230,15 @@ def atlas_plan_create_blocked(graph: atlas_graph_t, chunk_sources: int, block_so
     h = ctypes.c_void_p()
     _check(lib().atlas_plan_create_blocked(ctypes.byref(graph), chunk_sources, block_sources, hot_min_edges,
                                            ctypes.byref(h)), "atlas_plan_create_blocked")
+    return h.value
+
+
+def atlas_plan_create_dense(graph: atlas_graph_t, chunk_sources: int, block_sources: int, hot_min_edges: int,
+                            dense_max_bytes: int, dense_cells_per_edge: int = 0) -> int:
+    h = ctypes.c_void_p()
+    _check(lib().atlas_plan_create_dense(ctypes.byref(graph), chunk_sources, block_sources, hot_min_edges,
+                                         dense_max_bytes, dense_cells_per_edge, ctypes.byref(h)),
+           "atlas_plan_create_dense")
     return h.value
 
 

@@ -97,6 +97,9 @@ hipError_t cold_buffer(size_t bytes, void **out) {
 
 // tiles per piece of a long pinned-host chunk unless dims.piece_tiles says otherwise: 2^21 tiles = 2^27 edges
 constexpr int64_t kDefaultPieceTiles = int64_t(1) << 21;
+// A block of the first chunk goes to the dense part when it holds at least one edge per this many cells: a
+// cell costs a byte of the contraction's stream, an edge a 256-byte row gather.
+constexpr int64_t kDefaultDenseCellsPerEdge = 64;
 
 // The chunk loader's copy stream is created once per process and shared by
 // all layers: HIP spreads streams over a few hardware queues, and a stream
@@ -129,6 +132,8 @@ struct atlas_plan {
     std::vector<PlanChunk> chunks;  // grp_dst / tile_grp: device, or pinned host when `host`
     size_t max_stage_bytes = 0;     // host plans: largest staging slot any chunk needs
     int64_t n_first = 0;            // destinations that receive a message from some chunk (first-touch groups)
+    DensePart dense;                // device plans made by atlas_plan_create_dense: the dense part of chunk 0
+                                    // (dense.n_items > 0), pushed before chunks[0], which holds the chunk's other edges
 };
 
 namespace {
@@ -152,6 +157,8 @@ struct atlas_layer {
     Buf indeg_own, pending, ready, counters, counters64, acc, self_rows, packed_w, bias, dev_off;
     Buf gat_el, gat_er, gat_mcur, gat_mnext, gat_l, gat_wa, gat_z;   // GAT state
     Buf gat_scores;                                                  // GAT, planned chunks: per-edge logits
+    Buf dense_rows;                                                  // chunk 0's rows repacked for the dense part
+    int64_t edges_contracted = 0;                                    // edges pushed as a dense contraction
     int64_t prepass_next = 0, num_prepass = 0;
     const int32_t *indeg = nullptr;
     const int64_t *off_dev = nullptr;  // device-visible row offsets
@@ -202,7 +209,7 @@ struct atlas_layer {
     Buf stage_col[kStageSlots], stage_emb[kStageSlots];
     std::vector<hipEvent_t> piece_ev[kStageSlots];   // a long chunk's edge words arrive in pieces: one event each
 
-    std::vector<TimedSpan> t_agg, t_self, t_upd, t_copy, t_init;
+    std::vector<TimedSpan> t_agg, t_self, t_upd, t_copy, t_init, t_dense;
     hipStream_t last_stream = nullptr;
 
     int32_t *ctr() { return static_cast<int32_t *>(counters.p); }
@@ -216,7 +223,7 @@ struct atlas_layer {
     void destroy() {
         for (Buf *b : {&indeg_scratch, &indeg_own, &pending, &ready, &counters, &counters64, &acc, &self_rows, &packed_w, &bias,
                        &dev_off, &gat_el, &gat_er,
-                       &gat_mcur, &gat_mnext, &gat_l, &gat_wa, &gat_z, &gat_scores, &hs_slot_of, &hs_owner, &hs_free,
+                       &gat_mcur, &gat_mnext, &gat_l, &gat_wa, &gat_z, &gat_scores, &dense_rows, &hs_slot_of, &hs_owner, &hs_free,
                        &hs_stamp, &hs_need, &hs_ctr, &hs_keys, &hs_keys_sorted, &hs_sort_temp, &tf_z, &tf_self, &unpacked,
                        &packed_w2})
             b->release();
@@ -228,7 +235,7 @@ struct atlas_layer {
             for (hipEvent_t e : v) (void)hipEventDestroy(e);
         for (Buf &b : stage_col) b.release();
         for (Buf &b : stage_emb) b.release();
-        for (auto *v : {&t_agg, &t_self, &t_upd, &t_copy, &t_init})
+        for (auto *v : {&t_agg, &t_self, &t_upd, &t_copy, &t_init, &t_dense})
             for (auto &sp : *v) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
         for (int i = 0; i < kStageSlots; ++i) {
             if (slot_loaded[i]) (void)hipEventDestroy(slot_loaded[i]);
@@ -326,6 +333,8 @@ int init_impl(atlas_layer *L, const atlas_weights_t *w, hipStream_t s) {
     HIP_TRY(L->ready.alloc(n1 * sizeof(int32_t)));
     // A bounded store needs the per-chunk destination lists of a plan; it implies the planned-only promise.
     L->bounded = d.hot_slots > 0 && d.hot_slots < n;
+    // a plan with a dense part serves sum-aggregating layers whose accumulators are addressed by vertex id
+    if (L->g.plan && L->g.plan->dense.n_items > 0 && (L->bounded || d.model == ATLAS_MODEL_GAT)) return ATLAS_E_BAD_DIMS;
     if (L->bounded) {
         const atlas_plan *pl = L->g.plan;
         if (!pl || pl->host != (L->g.residency == ATLAS_RESIDENT_PINNED_HOST) || pl->n != n || pl->e != L->e)
@@ -1001,6 +1010,36 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         if ((rc = end_span(L, L->t_self, s)) != ATLAS_OK) return rc;
     }
     if (L->bounded && (rc = make_room_for_chunk(L, pc, src_begin, src_end, s, a, ga)) != ATLAS_OK) return rc;
+    if (pc && !regrouped && src_begin == 0 && plan->dense.n_items > 0) {
+        if ((rc = start_span(L, L->t_dense, s)) != ATLAS_OK) return rc;
+        // the first chunk's dense part goes first: as a contraction on the matrix cores where the kernel
+        // serves the rows' width and type, else as the planned chunk the plan keeps of the same edges
+        const DensePart &dp = plan->dense;
+        if (!(d.flags & ATLAS_FLAG_NO_DENSE) && a.model == 0 && dense_contract_takes(a.d, a.in_dt)) {
+            const size_t need = dense_packed_rows_bytes(dp, a.d);
+            if (L->dense_rows.bytes < need) {
+                L->dense_rows.release();
+                HIP_TRY(L->dense_rows.alloc(need));
+            }
+            HIP_TRY(launch_dense_part(dp, a.emb, src_end - src_begin, a.d, a.in_dt, L->dense_rows.p, a.acc, L->n,
+                                      a.pending, a.ready, a.counters, a.counters64, s));
+            L->edges_contracted += dp.list.n_edges;
+        } else {
+            GroupedArgs gd = ga;
+            gd.src_sorted = plan->src_sorted + dp.list.edge_base;
+            gd.grp_dst = dp.list.grp_dst;
+            gd.tile_grp = dp.list.tile_grp;
+            gd.n_edges = dp.list.n_edges;
+            gd.n_groups = dp.list.n_groups;
+            gd.multi_bit = 0;
+            if (gd.n_edges > 0) HIP_TRY(plan_runs(gd));
+            if (L->planned_only)
+                HIP_TRY(launch_zero_rows(dp.list.zero_rows, dp.list.zero_span, dp.list.n_zero_rows, gd.acc, gd.slot_of,
+                                         gd.d, &gd, s));
+            HIP_TRY(launch_aggregate_grouped(gd, &L->run_tickets, s));
+        }
+        if ((rc = end_span(L, L->t_dense, s)) != ATLAS_OK) return rc;
+    }
     if ((rc = start_span(L, L->t_agg, s)) != ATLAS_OK) return rc;
     if (pc) {
         for (int p = 0; p < st.npieces; ++p) {
@@ -1153,7 +1192,9 @@ int atlas_layer_finish(atlas_layer_t *L, atlas_layer_stats_t *stats) {
             }
         }
         if (rc == ATLAS_OK) {
+            stats->edges_contracted = L->edges_contracted;
             stats->ms_aggregate = sum_spans(L->t_agg);
+            stats->ms_dense = sum_spans(L->t_dense);
             stats->ms_self = sum_spans(L->t_self);
             stats->ms_init = sum_spans(L->t_init);
             stats->ms_update = sum_spans(L->t_upd);
@@ -1175,8 +1216,17 @@ int atlas_plan_create(const atlas_graph_t *graph, int64_t chunk_sources, atlas_p
 
 int atlas_plan_create_blocked(const atlas_graph_t *graph, int64_t chunk_sources, int64_t block_sources,
                               int64_t hot_min_edges, atlas_plan_t **out) {
+    return atlas_plan_create_dense(graph, chunk_sources, block_sources, hot_min_edges, 0, 0, out);
+}
+
+int atlas_plan_create_dense(const atlas_graph_t *graph, int64_t chunk_sources, int64_t block_sources,
+                            int64_t hot_min_edges, int64_t dense_max_bytes, int64_t dense_cells_per_edge,
+                            atlas_plan_t **out) {
     if (!graph || !out) return ATLAS_E_NULL;
-    if (block_sources < 0 || hot_min_edges < 0) return ATLAS_E_BAD_DIMS;
+    if (block_sources < 0 || hot_min_edges < 0 || dense_max_bytes < 0 || dense_cells_per_edge < 0)
+        return ATLAS_E_BAD_DIMS;
+    if (dense_max_bytes > 0 && graph->residency != ATLAS_RESIDENT_DEVICE) return ATLAS_E_BAD_DIMS;
+    if (dense_max_bytes > 0 && dense_cells_per_edge == 0) dense_cells_per_edge = kDefaultDenseCellsPerEdge;
     // bit 30 of a stored destination id marks destinations with several groups per chunk
     if (block_sources > 0 && graph->num_vertices >= (int64_t(1) << 30)) return ATLAS_E_OVERFLOW;
     if (!graph->row_offsets || (graph->num_edges > 0 && !graph->col_indices)) return ATLAS_E_NULL;
@@ -1230,8 +1280,14 @@ int atlas_plan_create_blocked(const atlas_graph_t *graph, int64_t chunk_sources,
         const int64_t ne = eend - ebeg;
         PlanChunk pc;
         if (!P->host) {
-            e = build_plan_chunk(graph->row_offsets, graph->col_indices, P->n, b, en, ebeg, eend,
-                                 P->src_sorted + ebeg, seen, block_sources, hot_min_edges, true, work, &pc);
+            if (k == 0 && dense_max_bytes > 0)
+                e = build_first_chunk_with_dense_part(graph->row_offsets, graph->col_indices, P->n, b, en, ebeg, eend,
+                                                      P->src_sorted + ebeg, seen, block_sources, hot_min_edges, true,
+                                                      static_cast<size_t>(dense_max_bytes), dense_cells_per_edge, work,
+                                                      &pc, &P->dense);
+            else
+                e = build_plan_chunk(graph->row_offsets, graph->col_indices, P->n, b, en, ebeg, eend,
+                                     P->src_sorted + ebeg, seen, block_sources, hot_min_edges, true, work, &pc);
             if (e != hipSuccess) { rc = hip_fail(e, "build_plan_chunk"); break; }
         } else {
             // stage the chunk's CSR slice into HBM, regroup there, bring the result back
@@ -1313,6 +1369,7 @@ int atlas_plan_destroy(atlas_plan_t *P) {
     if (P->src_sorted) (void)(P->host ? hipHostFree(P->src_sorted) : hipFree(P->src_sorted));
     if (P->src_packed) (void)hipHostFree(P->src_packed);
     if (P->dev_off) (void)hipFree(P->dev_off);
+    P->dense.release();
     delete P;
     return ATLAS_OK;
 }
@@ -1330,6 +1387,19 @@ int atlas_plan_info(const atlas_plan_t *P, atlas_plan_info_t *info) {
         (P->host ? host : dev) += arrays;
         dev += static_cast<size_t>(c.n_zero_rows) * 12;
     }
+    if (P->dense.n_items > 0) {
+        const PlanChunk &c = P->dense.list;
+        info->num_groups += c.n_groups;
+        dev += static_cast<size_t>(c.n_groups) * 4 + static_cast<size_t>((c.n_edges + 63) / 64) * 4 +
+               static_cast<size_t>(c.n_zero_rows) * 12;
+        dev += P->dense.cell_bytes + static_cast<size_t>(P->dense.rows) * 4 + static_cast<size_t>(P->dense.n_bands) * 12 +
+               static_cast<size_t>(P->dense.n_items) * 12;
+        info->dense_edges = c.n_edges;
+        info->dense_groups = c.n_groups;
+        info->dense_cells = static_cast<int64_t>(P->dense.cell_bytes);
+        info->dense_rows = std::min(P->dense.rows, P->n);
+        info->dense_max_sources = static_cast<int64_t>(P->dense.max_ksteps) * 64;
+    }
     if (P->src_packed) host += P->packed_bytes;
     else (P->host ? host : dev) += static_cast<size_t>(P->e) * 4;
     if (P->dev_off) dev += (static_cast<size_t>(P->n) + 1) * sizeof(int64_t);
@@ -1345,6 +1415,8 @@ int atlas_plan_in_degree(const atlas_plan_t *P, int32_t *in_degree, void *hip_st
     HIP_TRY(launch_fill_zero(in_degree, static_cast<size_t>(P->n) * sizeof(int32_t), s));
     for (const PlanChunk &c : P->chunks)
         HIP_TRY(launch_plan_chunk_in_degree(c, P->src_sorted + c.edge_base, in_degree, s));
+    if (P->dense.n_items > 0)
+        HIP_TRY(launch_plan_chunk_in_degree(P->dense.list, P->src_sorted + P->dense.list.edge_base, in_degree, s));
     return ATLAS_OK;
 }
 

@@ -176,6 +176,7 @@ struct GrowBuf {
 };
 struct PlanWork {
     GrowBuf tmp_src, dst_sorted, heads, temp, bkey, bkey_sorted, bpos, bpos_sorted, gstart, src_new, rows, cnt;
+    GrowBuf part_flags, part_pos, part_dst, part_src;   // split of a first chunk into its dense part and the rest
     PlanWork() = default;
     PlanWork(const PlanWork &) = delete;
     PlanWork &operator=(const PlanWork &) = delete;
@@ -190,10 +191,71 @@ struct PlanWork {
 // src_sorted receives the chunk's
 // edge_end - edge_begin entries; grp_dst and tile_grp (and, with want_zero_rows, the list of rows a
 // planned-only layer clears) are allocated with hipMalloc.
+// With `pairs` the chunk's edges are not read from the CSR but given as (destination, source) arrays of
+// pairs->count entries in CSR order (a subset of the chunk's edges); pairs->src is overwritten.
+struct EdgePairs {
+    const uint32_t *dst;
+    int32_t *src;
+    int64_t count;
+};
 hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int64_t n, int64_t src_begin,
                             int64_t src_end, int64_t edge_begin, int64_t edge_end, int32_t *src_sorted,
                             uint8_t *seen, int64_t block_sources, int64_t hot_min_edges, bool want_zero_rows,
-                            PlanWork &w, PlanChunk *out);
+                            PlanWork &w, PlanChunk *out, const EdgePairs *pairs = nullptr);
+
+// Dense part of a plan's first chunk (k_dense.hip): the multiplicities of the edges between the chunk's
+// first sources and the first destinations as a staircase of byte matrices, one band per 256 destinations,
+// and the same edges as an ordinary planned chunk (`list`) for layers the contraction does not serve.
+constexpr int kDenseBuckets = 24;        // log-spaced rank buckets of the density histogram
+constexpr int kDenseItemKsteps = 128;    // most k-steps (of 64 sources) one workgroup contracts
+struct DensePart {
+    int64_t rows = 0;                 // destinations [0, rows), a multiple of 256 (may exceed N)
+    int32_t n_bands = 0;              // rows / 256
+    int32_t max_ksteps = 0;           // sources / 64 of the longest band (a multiple of 4)
+    int32_t *band_ksteps = nullptr;   // device [n_bands]
+    int64_t *band_off = nullptr;      // device [n_bands]: byte offset of the band's cells
+    uint8_t *cells = nullptr;         // device
+    size_t cell_bytes = 0;
+    int32_t *msgs = nullptr;          // device [rows]: messages of the dense part to each destination
+    int32_t *items = nullptr;         // device [n_items][3]: band, first k-step, k-steps of every work item
+    int64_t n_items = 0;
+    PlanChunk list;                   // the part's edges, grouped by destination
+    void release();
+};
+// Builds the first chunk of a plan in two parts.  max_bytes bounds the cells; cells_per_edge is the most
+// cells a (source bucket, destination bucket) block may spend per edge it holds.  When no block is that
+// dense the chunk is built as usual and dense->n_items stays 0.
+hipError_t build_first_chunk_with_dense_part(const int64_t *off_dev, const int32_t *col_dev, int64_t n,
+                                             int64_t src_begin, int64_t src_end, int64_t edge_begin,
+                                             int64_t edge_end, int32_t *src_sorted, uint8_t *seen,
+                                             int64_t block_sources, int64_t hot_min_edges, bool want_zero_rows,
+                                             size_t max_bytes, int64_t cells_per_edge, PlanWork &w, PlanChunk *rest,
+                                             DensePart *dense);
+hipError_t launch_dense_histogram(const int32_t *src_of_edge, const int32_t *col, int64_t ne, int64_t src_begin,
+                                  unsigned long long *hist, hipStream_t s);
+hipError_t launch_dense_divert(const int32_t *src_of_edge, const int32_t *col, int64_t ne, int64_t src_begin,
+                               const DensePart &p, uint8_t *flags, hipStream_t s);
+hipError_t launch_dense_split(const int32_t *src_of_edge, const int32_t *col, const uint8_t *flags,
+                              const uint32_t *flagged_before, int64_t ne, int64_t n_rest, uint32_t *dst_out,
+                              int32_t *src_out, hipStream_t s);
+struct DenseArgs {
+    const uint8_t *cells;
+    const int64_t *band_off;
+    const int32_t *items;
+    const void *xt;
+    float *acc;
+    int64_t n;
+};
+// Whether the contraction serves rows of this width and storage type (otherwise the layer pushes `list`).
+bool dense_contract_takes(int d, int in_dt);
+// Bytes of the repacked chunk rows the contraction reads (`xt` below).
+size_t dense_packed_rows_bytes(const DensePart &p, int d);
+// acc[v] = sum of the dense part's messages to v for v < rows (the rows are overwritten: the part is pushed
+// before anything else of the layer), pending counts lowered, completed vertices appended to the ready list.
+// emb: the chunk's rows (chunk_rows of them, 16-bit, d wide).
+hipError_t launch_dense_part(const DensePart &p, const void *emb, int64_t chunk_rows, int d, int in_dt, void *xt,
+                             float *acc, int64_t n, int32_t *pending, int32_t *ready, int32_t *counters,
+                             unsigned long long *counters64, hipStream_t s);
 
 // indeg[v] += messages the chunk sends to v, for every destination of a planned chunk whose arrays are in
 // device memory (src_sorted: the chunk's slice).  indeg must have been zeroed before the first chunk.

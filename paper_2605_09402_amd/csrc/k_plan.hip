@@ -27,7 +27,9 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstring>
+#include <vector>
 
 #include <rocprim/device/device_radix_sort.hpp>
 #include <rocprim/device/device_scan.hpp>
@@ -161,7 +163,7 @@ struct MaxOp {
 
 PlanWork::~PlanWork() {
     for (GrowBuf *b : {&tmp_src, &dst_sorted, &heads, &temp, &bkey, &bkey_sorted, &bpos, &bpos_sorted, &gstart, &src_new,
-                       &rows, &cnt})
+                       &rows, &cnt, &part_flags, &part_pos, &part_dst, &part_src})
         b->release();
 }
 
@@ -182,10 +184,10 @@ void GrowBuf::release() {
 hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int64_t n, int64_t src_begin,
                             int64_t src_end, int64_t edge_begin, int64_t edge_end, int32_t *src_sorted,
                             uint8_t *seen, int64_t block_sources, int64_t hot_min_edges, bool want_zero_rows,
-                            PlanWork &w, PlanChunk *out) {
+                            PlanWork &w, PlanChunk *out, const EdgePairs *pairs) {
     *out = PlanChunk{};
     out->edge_base = edge_begin;
-    out->n_edges = edge_end - edge_begin;
+    out->n_edges = pairs ? pairs->count : edge_end - edge_begin;
     const int64_t ne = out->n_edges;
     if (ne <= 0) return hipSuccess;
     if (ne >= (int64_t(1) << 32)) return hipErrorInvalidValue;
@@ -198,17 +200,18 @@ hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int6
     size_t temp_bsort = 0;
     int bkey_bits = 1;
     size_t temp_sort = 0, temp_scan_max = 0, temp_scan_sum = 0, temp_bytes = 0;
-    const uint32_t *keys_in = reinterpret_cast<const uint32_t *>(col_dev + edge_begin);
+    const uint32_t *keys_in = pairs ? pairs->dst : reinterpret_cast<const uint32_t *>(col_dev + edge_begin);
     uint32_t last = 0;
     int end_bit = 1;
     while (end_bit < 32 && (int64_t(1) << end_bit) < n) ++end_bit;
     const size_t count = static_cast<size_t>(ne);
 
     // work arrays: kept from chunk to chunk, grown when a chunk is larger than any before it
-    if ((err = w.tmp_src.need(count * 4)) != hipSuccess) return err;
+    if (!pairs && (err = w.tmp_src.need(count * 4)) != hipSuccess) return err;
     if ((err = w.dst_sorted.need(count * 4)) != hipSuccess) return err;
     if ((err = w.heads.need(count * 4)) != hipSuccess) return err;
-    int32_t *tmp_src = static_cast<int32_t *>(w.tmp_src.p);   // source per edge (CSR order); reused for the group prefix sum
+    // source per edge (CSR order); reused for the group prefix sum
+    int32_t *tmp_src = pairs ? pairs->src : static_cast<int32_t *>(w.tmp_src.p);
     uint32_t *dst_sorted = static_cast<uint32_t *>(w.dst_sorted.p);
     uint32_t *heads = static_cast<uint32_t *>(w.heads.p);
     uint32_t *bkey = nullptr, *bkey_sorted = nullptr, *bpos = nullptr, *bpos_sorted = nullptr, *gstart = nullptr;
@@ -242,11 +245,13 @@ hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int6
     void *temp = w.temp.p;
 
     // 1. source of every edge
-    if ((err = hipMemsetAsync(tmp_src, 0, count * 4, nullptr)) != hipSuccess) goto done;
-    hipLaunchKernelGGL(k_mark_row_starts, dim3(blocks_for(src_end - src_begin)), dim3(kBlock), 0, nullptr, off_dev,
-                       src_begin, src_end, edge_begin, tmp_src);
-    if ((err = hipGetLastError()) != hipSuccess) goto done;
-    if ((err = rocprim::inclusive_scan(temp, temp_scan_max, tmp_src, tmp_src, count, MaxOp(), nullptr)) != hipSuccess) goto done;
+    if (!pairs) {
+        if ((err = hipMemsetAsync(tmp_src, 0, count * 4, nullptr)) != hipSuccess) goto done;
+        hipLaunchKernelGGL(k_mark_row_starts, dim3(blocks_for(src_end - src_begin)), dim3(kBlock), 0, nullptr, off_dev,
+                           src_begin, src_end, edge_begin, tmp_src);
+        if ((err = hipGetLastError()) != hipSuccess) goto done;
+        if ((err = rocprim::inclusive_scan(temp, temp_scan_max, tmp_src, tmp_src, count, MaxOp(), nullptr)) != hipSuccess) goto done;
+    }
     // 2. stable sort by destination
     if ((err = rocprim::radix_sort_pairs(temp, temp_sort, keys_in, dst_sorted, tmp_src, src_sorted, count, 0, end_bit,
                                          nullptr)) != hipSuccess) goto done;
@@ -329,6 +334,171 @@ done:
         out->zero_rows = nullptr;
         out->zero_span = nullptr;
     }
+    return err;
+}
+
+void DensePart::release() {
+    for (void *q : {static_cast<void *>(band_ksteps), static_cast<void *>(band_off), static_cast<void *>(cells),
+                    static_cast<void *>(msgs), static_cast<void *>(items), static_cast<void *>(list.grp_dst),
+                    static_cast<void *>(list.tile_grp), static_cast<void *>(list.zero_rows),
+                    static_cast<void *>(list.zero_span)})
+        if (q) (void)hipFree(q);
+    *this = DensePart{};
+}
+
+namespace {
+// The staircase: per destination bucket, how many sources (in k-steps of 64, a multiple of 4) its bands
+// take.  A (source bucket, destination bucket) block belongs to the region when it spends at most
+// cells_per_edge cells per edge it holds and so do all blocks before it in its row and column of buckets,
+// which keeps the extents non-increasing from one destination bucket to the next.
+int64_t bucket_begin(int k) { return k == 0 ? 0 : int64_t(1) << (7 + k); }
+int64_t bucket_end(int k) { return int64_t(1) << (8 + k); }
+void choose_staircase(const unsigned long long *hist, int64_t n, int64_t chunk_sources, int64_t cells_per_edge,
+                      int32_t (&ksteps)[kDenseBuckets]) {
+    const int64_t src_cap = (chunk_sources + 255) / 256 * 256;
+    int prev = kDenseBuckets;   // source buckets the previous destination bucket took
+    for (int j = 0; j < kDenseBuckets; ++j) {
+        ksteps[j] = 0;
+        if (bucket_begin(j) >= n) { prev = 0; continue; }
+        const double dsts = static_cast<double>(std::min(bucket_end(j), n) - bucket_begin(j));
+        int take = 0;
+        while (take < prev && bucket_begin(take) < chunk_sources) {
+            const double srcs = static_cast<double>(std::min(bucket_end(take), chunk_sources) - bucket_begin(take));
+            const double edges = static_cast<double>(hist[take * kDenseBuckets + j]);
+            if (edges * static_cast<double>(cells_per_edge) < srcs * dsts) break;
+            ++take;
+        }
+        prev = take;
+        if (take > 0) ksteps[j] = static_cast<int32_t>(std::min(bucket_end(take - 1), src_cap) / 64);
+    }
+}
+}  // namespace
+
+hipError_t build_first_chunk_with_dense_part(const int64_t *off_dev, const int32_t *col_dev, int64_t n,
+                                             int64_t src_begin, int64_t src_end, int64_t edge_begin,
+                                             int64_t edge_end, int32_t *src_sorted, uint8_t *seen,
+                                             int64_t block_sources, int64_t hot_min_edges, bool want_zero_rows,
+                                             size_t max_bytes, int64_t cells_per_edge, PlanWork &w, PlanChunk *rest,
+                                             DensePart *dense) {
+    *dense = DensePart{};
+    const int64_t ne = edge_end - edge_begin;
+    auto plain = [&]() {
+        return build_plan_chunk(off_dev, col_dev, n, src_begin, src_end, edge_begin, edge_end, src_sorted, seen,
+                                block_sources, hot_min_edges, want_zero_rows, w, rest);
+    };
+    if (ne <= 0 || ne >= (int64_t(1) << 32) || n >= (int64_t(1) << 30) || cells_per_edge <= 0) return plain();
+    const size_t count = static_cast<size_t>(ne);
+    const int32_t *col = col_dev + edge_begin;
+    hipError_t err = hipSuccess;
+    unsigned long long *hist_dev = nullptr;
+    unsigned long long hist[kDenseBuckets * kDenseBuckets];
+    int32_t ksteps[kDenseBuckets];
+    std::vector<int32_t> band_ksteps, items;
+    std::vector<int64_t> band_off;
+    size_t total = 0, temp_max = 0, temp_sum = 0;
+    uint32_t flagged_last = 0;
+    uint8_t flag_last = 0;
+    int64_t n_dense = 0, n_rest = 0;
+    EdgePairs pr{};
+
+    // source of every edge, as in build_plan_chunk
+    if ((err = w.tmp_src.need(count * 4)) != hipSuccess) return err;
+    int32_t *src_of_edge = static_cast<int32_t *>(w.tmp_src.p);
+    if ((err = rocprim::inclusive_scan(nullptr, temp_max, src_of_edge, src_of_edge, count, MaxOp(), nullptr)) != hipSuccess) return err;
+    if ((err = w.part_flags.need(count)) != hipSuccess) return err;
+    if ((err = w.part_pos.need(count * 4)) != hipSuccess) return err;
+    uint8_t *flags = static_cast<uint8_t *>(w.part_flags.p);
+    uint32_t *pos = static_cast<uint32_t *>(w.part_pos.p);
+    if ((err = rocprim::exclusive_scan(nullptr, temp_sum, flags, pos, uint32_t(0), count, rocprim::plus<uint32_t>(),
+                                       nullptr)) != hipSuccess) return err;
+    if ((err = w.temp.need(std::max<size_t>(std::max(temp_max, temp_sum), 16))) != hipSuccess) return err;
+    if ((err = hipMemsetAsync(src_of_edge, 0, count * 4, nullptr)) != hipSuccess) return err;
+    hipLaunchKernelGGL(k_mark_row_starts, dim3(blocks_for(src_end - src_begin)), dim3(kBlock), 0, nullptr, off_dev,
+                       src_begin, src_end, edge_begin, src_of_edge);
+    if ((err = hipGetLastError()) != hipSuccess) return err;
+    if ((err = rocprim::inclusive_scan(w.temp.p, temp_max, src_of_edge, src_of_edge, count, MaxOp(), nullptr)) != hipSuccess) return err;
+
+    // where the chunk is dense
+    if ((err = hipMalloc(&hist_dev, sizeof(hist))) != hipSuccess) return err;
+    err = launch_dense_histogram(src_of_edge, col, ne, src_begin, hist_dev, nullptr);
+    if (err == hipSuccess) err = hipMemcpy(hist, hist_dev, sizeof(hist), hipMemcpyDeviceToHost);
+    (void)hipFree(hist_dev);
+    if (err != hipSuccess) return err;
+    for (int64_t cpe = cells_per_edge; cpe > 0; cpe /= 2) {
+        choose_staircase(hist, n, src_end - src_begin, cpe, ksteps);
+        band_ksteps.clear();
+        band_off.clear();
+        total = 0;
+        for (int j = 0; j < kDenseBuckets && ksteps[j] > 0; ++j) {
+            const int64_t end = std::min(bucket_end(j), (n + 255) / 256 * 256);
+            for (int64_t r = bucket_begin(j); r < end; r += 256) {
+                band_ksteps.push_back(ksteps[j]);
+                band_off.push_back(static_cast<int64_t>(total));
+                total += static_cast<size_t>(ksteps[j]) * 16384;
+            }
+        }
+        if (total <= max_bytes) break;
+        band_ksteps.clear();
+    }
+    if (band_ksteps.empty()) return plain();
+
+    dense->n_bands = static_cast<int32_t>(band_ksteps.size());
+    dense->rows = static_cast<int64_t>(dense->n_bands) * 256;
+    dense->max_ksteps = band_ksteps[0];
+    dense->cell_bytes = total;
+    // work items in (source slice, band) order: the workgroups in flight at one time then read the same slice of
+    // the repacked rows, which stays in the L2 caches, while each streams its own cells
+    for (int32_t k = 0; k < dense->max_ksteps; k += kDenseItemKsteps)
+        for (int32_t b = 0; b < dense->n_bands && band_ksteps[b] > k; ++b) {
+            items.push_back(b);
+            items.push_back(k);
+            items.push_back(std::min<int32_t>(kDenseItemKsteps, band_ksteps[b] - k));
+        }
+    dense->n_items = static_cast<int64_t>(items.size() / 3);
+    if ((err = hipMalloc(&dense->band_ksteps, band_ksteps.size() * 4)) != hipSuccess) goto fail;
+    if ((err = hipMalloc(&dense->band_off, band_off.size() * 8)) != hipSuccess) goto fail;
+    if ((err = hipMalloc(&dense->items, items.size() * 4)) != hipSuccess) goto fail;
+    if ((err = hipMalloc(&dense->msgs, static_cast<size_t>(dense->rows) * 4)) != hipSuccess) goto fail;
+    if ((err = hipMalloc(&dense->cells, total)) != hipSuccess) goto fail;
+    if ((err = hipMemcpy(dense->band_ksteps, band_ksteps.data(), band_ksteps.size() * 4, hipMemcpyHostToDevice)) != hipSuccess) goto fail;
+    if ((err = hipMemcpy(dense->band_off, band_off.data(), band_off.size() * 8, hipMemcpyHostToDevice)) != hipSuccess) goto fail;
+    if ((err = hipMemcpy(dense->items, items.data(), items.size() * 4, hipMemcpyHostToDevice)) != hipSuccess) goto fail;
+    if ((err = hipMemsetAsync(dense->cells, 0, total, nullptr)) != hipSuccess) goto fail;
+    if ((err = hipMemsetAsync(dense->msgs, 0, static_cast<size_t>(dense->rows) * 4, nullptr)) != hipSuccess) goto fail;
+
+    // the edges the cells take over, and the two halves of the chunk in CSR order
+    if ((err = launch_dense_divert(src_of_edge, col, ne, src_begin, *dense, flags, nullptr)) != hipSuccess) goto fail;
+    if ((err = rocprim::exclusive_scan(w.temp.p, temp_sum, flags, pos, uint32_t(0), count, rocprim::plus<uint32_t>(),
+                                       nullptr)) != hipSuccess) goto fail;
+    if ((err = hipMemcpy(&flagged_last, pos + (count - 1), 4, hipMemcpyDeviceToHost)) != hipSuccess) goto fail;
+    if ((err = hipMemcpy(&flag_last, flags + (count - 1), 1, hipMemcpyDeviceToHost)) != hipSuccess) goto fail;
+    n_dense = static_cast<int64_t>(flagged_last) + (flag_last ? 1 : 0);
+    n_rest = ne - n_dense;
+    if (n_dense == 0) {
+        dense->release();
+        return plain();
+    }
+    if ((err = w.part_dst.need(count * 4)) != hipSuccess) goto fail;
+    if ((err = w.part_src.need(count * 4)) != hipSuccess) goto fail;
+    if ((err = launch_dense_split(src_of_edge, col, flags, pos, ne, n_rest, static_cast<uint32_t *>(w.part_dst.p),
+                                  static_cast<int32_t *>(w.part_src.p), nullptr)) != hipSuccess) goto fail;
+    // the dense part is pushed first: its groups are the first touch of their destinations
+    pr.dst = static_cast<const uint32_t *>(w.part_dst.p) + n_rest;
+    pr.src = static_cast<int32_t *>(w.part_src.p) + n_rest;
+    pr.count = n_dense;
+    if ((err = build_plan_chunk(off_dev, col_dev, n, src_begin, src_end, edge_begin + n_rest, edge_end,
+                                src_sorted + n_rest, seen, 0, 0, want_zero_rows, w, &dense->list, &pr)) != hipSuccess) goto fail;
+    if ((err = launch_plan_chunk_in_degree(dense->list, src_sorted + n_rest, dense->msgs, nullptr)) != hipSuccess) goto fail;
+    pr.dst = static_cast<const uint32_t *>(w.part_dst.p);
+    pr.src = static_cast<int32_t *>(w.part_src.p);
+    pr.count = n_rest;
+    if ((err = build_plan_chunk(off_dev, col_dev, n, src_begin, src_end, edge_begin, edge_begin + n_rest, src_sorted,
+                                seen, block_sources, hot_min_edges, want_zero_rows, w, rest, &pr)) != hipSuccess) goto fail;
+    if ((err = hipStreamSynchronize(nullptr)) != hipSuccess) goto fail;
+    return hipSuccess;
+fail:
+    (void)hipStreamSynchronize(nullptr);
+    dense->release();
     return err;
 }
 

@@ -121,6 +121,7 @@ class GpuRun:
     ready_per_flush: List[List[np.ndarray]] = field(default_factory=list)       # [layer][flush], incl. flush 0 at init
     indeg: Optional[np.ndarray] = None
     extra_roundings: int = 0    # transform-first layers push products rounded to the storage type
+    plan_info: Optional[dict] = None
 
 
 def _dt(store: torch.dtype) -> int:
@@ -133,7 +134,8 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
             planned_only: bool = False, hot_slots: int = 0, evict_policy: int = 0,
             transform_first: bool = False, plan_block: Optional[tuple] = None,
             device_later: bool = False, tiles_per_run: int = 0, piece_tiles: int = 0,
-            csr_stream: bool = False, no_handover: bool = False) -> GpuRun:
+            csr_stream: bool = False, no_handover: bool = False, plan_dense: Optional[tuple] = None,
+            no_dense: bool = False) -> GpuRun:
     """Drive all layers through the C ABI.  With pinned_host the graph and the
     layer-0 features stay in pinned host memory and are staged by the library.
     planned_only sets ATLAS_FLAG_PLANNED_ONLY (no zero fill of the accumulators;
@@ -142,7 +144,10 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
     layer's output where it lies in device memory instead of a pinned host copy.
     tiles_per_run / piece_tiles: the launch-shape fields of atlas_dims_t (0: the library's choice).
     csr_stream: ATLAS_FLAG_CSR_STREAM, long chunks without a planned chunk are not regrouped on the fly.
-    no_handover: ATLAS_FLAG_NO_HANDOVER, finished rows take the fp32 round trip to the update."""
+    no_handover: ATLAS_FLAG_NO_HANDOVER, finished rows take the fp32 round trip to the update.
+    plan_dense = (max_bytes, cells_per_edge): atlas_plan_create_dense, the first chunk's dense corner as byte
+    matrices; no_dense: ATLAS_FLAG_NO_DENSE, that part is pushed as the planned chunk it also is.
+    run.plan_info holds atlas_plan_info of the plan."""
     dev = torch.device("cuda:0")
     n, e = case.n, case.e
     run = GpuRun(extra_roundings=1 if transform_first else 0)
@@ -162,11 +167,15 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
     plan_h = None
     if plan:
         pg = atlas.make_graph(n, e, off_t, col_t, None, res)
-        if plan_block:   # (block_sources, hot_min_edges): source-blocked order for the heavy destinations
+        if plan_dense:
+            pb = plan_block or (0, 0)
+            plan_h = atlas.atlas_plan_create_dense(pg, plan_chunk or case.chunk, pb[0], pb[1], plan_dense[0], plan_dense[1])
+        elif plan_block:   # (block_sources, hot_min_edges): source-blocked order for the heavy destinations
             plan_h = atlas.atlas_plan_create_blocked(pg, plan_chunk or case.chunk, plan_block[0], plan_block[1])
         else:
             plan_h = atlas.atlas_plan_create(pg, plan_chunk or case.chunk)
     graph = atlas.make_graph(n, e, off_t, col_t, indeg_t, res, plan_h)
+    run.plan_info = atlas.atlas_plan_info(plan_h) if plan_h else None
     nl = len(case.layers) if max_layers is None else max_layers
     cur_dev = case.X.to(dev)
     cur_host = case.X.pin_memory() if pinned_host else None
@@ -192,7 +201,8 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
                                (atlas.FLAG_PLANNED_ONLY if planned_only else 0) |
                                (atlas.FLAG_TRANSFORM_FIRST if transform_first else 0) |
                                (atlas.FLAG_CSR_STREAM if csr_stream else 0) |
-                               (atlas.FLAG_NO_HANDOVER if no_handover else 0),
+                               (atlas.FLAG_NO_HANDOVER if no_handover else 0) |
+                               (atlas.FLAG_NO_DENSE if no_dense else 0),
                                tiles_per_run=tiles_per_run, piece_tiles=piece_tiles)
         weights = atlas.make_weights(W, b, sdt, a_s, a_d)
         h = atlas.atlas_layer_init(graph, dims, weights, stream)

@@ -457,3 +457,95 @@ def test_finished_rows_handed_to_the_update(oracle, H, model, store, planned_onl
     run = H.run_gpu(case, plan=True, planned_only=planned_only, pinned_host=True, device_later=True, piece_tiles=3)
     same(run.outputs, ref.outputs)
     assert all(st["rows_handed_over"] > 0 for st in run.stats)
+
+
+def _degree_ordered_rmat(oracle, seed, scale, edge_factor, self_loops=False, extra=None):
+    """R-MAT in in-degree-descending ids; extra = (src, dst, copies): that many more copies of one edge
+    (ids of the final order), appended as a batch of their own."""
+    g = gen.rmat_graph(seed, scale, edge_factor, self_loops=self_loops)
+    off, col = gen.build_csr(g)
+    new_of_old, _ = oracle.reorder_indegree_desc(oracle.in_degree(g.n, col.numpy()))
+    g = g.with_relabel(torch.from_numpy(new_of_old.astype(np.int64)))
+    if extra is None:
+        return g
+    s, d, copies = extra
+
+    def raw(k, base=g):
+        if k < base.num_batches:
+            return base.batch(k)
+        return (torch.full((copies,), s, dtype=torch.int64), torch.full((copies,), d, dtype=torch.int64))
+    return gen.EdgeSource(g.n, g.num_batches + 1, raw)
+
+
+@pytest.mark.parametrize("store", [torch.bfloat16, torch.float16], ids=["bf16", "f16"])
+@pytest.mark.parametrize("model", ["sage", "gin", "gcn"])
+@pytest.mark.parametrize("planned_only", [False, True])
+def test_dense_part_of_the_first_chunk(oracle, H, model, store, planned_only):
+    """atlas_plan_create_dense: the first chunk's edges between its first sources and the first destinations
+    are kept as byte matrices and pushed as a contraction on the matrix cores (16-bit plain row sums of width
+    128 and 64: SAGE and bf16 GIN here), or as the planned chunk the plan keeps of the same edges (GCN, whose
+    messages are scaled per source; half-precision GIN, which runs transform-first and pushes fp32; and
+    ATLAS_FLAG_NO_DENSE).  Integers and outputs must match the oracle either way, the two ways must agree,
+    and the stats must say which way the edges went.  Degree-ordered R-MAT scale 12, edge factor 32, chunks
+    of 1,000 sources (not a multiple of the 256-source unit), a region of up to one edge per 512 cells; one
+    edge is repeated 300 times, more than a cell can count."""
+    g = _degree_ordered_rmat(oracle, SEED + 81, 12, 32, self_loops=(model == "gcn"), extra=(3, 5, 300))
+    # (GIN does not normalise: on this graph's hubs its second layer leaves half's range, so half GIN has one layer)
+    tf = model == "gin" and store == torch.float16
+    case = H.make_case(model, g, SEED + 81, [128, 64] if tf else [128, 64, 64], 1000, store=store,
+                       eps=0.5 if model == "gin" else 0.0)
+    opts = dict(plan=True, planned_only=planned_only, transform_first=tf, plan_dense=(1 << 30, 512))
+    run = H.run_gpu(case, snapshots=True, **opts)
+    info = run.plan_info
+    print("dense part", model, store, info, H.check_outputs(oracle, case, run), [st["edges_contracted"] for st in run.stats])
+    assert info["dense_edges"] > 1000 and info["dense_cells"] >= 256 * 256 and info["dense_rows"] >= 256
+    H.check_integers(oracle, case, run, layer=0)
+    if not tf:
+        H.check_integers(oracle, case, run, layer=1)
+    contracts = model in ("sage", "gin") and not tf
+    for st in run.stats:
+        assert st["edges_processed"] == case.e and st["vertices_flushed"] == case.n
+        assert st["edges_contracted"] == (info["dense_edges"] if contracts else 0)
+    ref = H.run_gpu(case, no_dense=True, **opts)
+    H.check_outputs(oracle, case, ref)
+    assert all(st["edges_contracted"] == 0 and st["edges_processed"] == case.e for st in ref.stats)
+    for a, b in zip(run.outputs, ref.outputs):
+        assert torch.allclose(a.float(), b.float(), rtol=2.0 ** -6, atol=1e-3)
+
+
+def test_dense_part_choice_and_limits(oracle, H):
+    """Where no block of the first chunk is dense enough the plan is an ordinary one (uniform random graph,
+    default density); a byte limit below the smallest region leaves no dense part; GAT layers and a bounded
+    store refuse a plan with a dense part; a pinned-host graph refuses the call; a region that covers every
+    edge of the chunk leaves an empty rest of the chunk."""
+    import paper_2605_09402_amd as atlas
+    gu = gen.uniform_graph(SEED + 82, 3000, 40000)
+    case = H.make_case("sage", gu, SEED + 82, [128, 64], 1500, store=torch.bfloat16)
+    run = H.run_gpu(case, plan=True, plan_dense=(1 << 30, 0))
+    assert run.plan_info["dense_edges"] == 0 and all(st["edges_contracted"] == 0 for st in run.stats)
+    H.check_outputs(oracle, case, run)
+    g = _degree_ordered_rmat(oracle, SEED + 83, 11, 32)
+    case = H.make_case("sage", g, SEED + 83, [128, 64], 1024, store=torch.bfloat16)
+    run = H.run_gpu(case, plan=True, plan_dense=(1000, 512))       # fewer bytes than one band of four k-steps
+    assert run.plan_info["dense_edges"] == 0
+    H.check_outputs(oracle, case, run)
+    # every block counts as dense: the region is the whole chunk x all destinations, the rest of the chunk is empty
+    run = H.run_gpu(case, snapshots=True, plan=True, planned_only=True, plan_dense=(1 << 30, 1 << 40))
+    first_chunk_edges = int(case.off[1024])
+    src = np.repeat(np.arange(1024), np.diff(case.off.numpy()[:1025]))
+    _, mult = np.unique(src * case.n + case.col.numpy()[:first_chunk_edges], return_counts=True)
+    assert int(np.minimum(mult, 255).sum()) == first_chunk_edges     # no pair of this graph outgrows a cell
+    assert run.plan_info["dense_edges"] == first_chunk_edges and run.plan_info["dense_rows"] == case.n
+    H.check_integers(oracle, case, run, layer=0)
+    H.check_outputs(oracle, case, run)
+    assert run.stats[0]["edges_contracted"] == first_chunk_edges
+    with pytest.raises(atlas.AtlasError) as ei:
+        H.run_gpu(H.make_case("gat", g, SEED + 83, [64, 64], 1024, store=torch.float32, heads=2, act="elu"),
+                  plan=True, plan_dense=(1 << 30, 512))
+    assert ei.value.status == atlas.E_BAD_DIMS
+    with pytest.raises(atlas.AtlasError) as ei:
+        H.run_gpu(case, plan=True, plan_dense=(1 << 30, 512), hot_slots=case.n // 2)
+    assert ei.value.status == atlas.E_BAD_DIMS
+    with pytest.raises(atlas.AtlasError) as ei:
+        H.run_gpu(case, plan=True, plan_dense=(1 << 30, 512), pinned_host=True)
+    assert ei.value.status == atlas.E_BAD_DIMS

@@ -1,6 +1,6 @@
 """Seeded random combinations of graph shape, layer type, storage type, chunk
 size and the library's options (plan kind, residency, zero-fill-free start,
-flush cadence, run length, piece size, transform-first, bounded store), each
+flush cadence, run length, piece size, transform-first, bounded store, dense part of the first chunk), each
 checked against the oracle: outputs to the storage type's tolerance and the
 layer counters exactly.  The single-option cases live in the other files; this
 one looks for interactions."""
@@ -130,6 +130,12 @@ def _draw(rng, oracle, H, idx, handed=False):
         opts["no_handover"] = True
     if not plan_kind and rng.random() < 0.3:
         opts["csr_stream"] = True
+    if plan_kind and not pinned and "hot_slots" not in opts and rng.random() < 0.4:
+        # the first chunk's dense corner as byte matrices (contracted on the matrix cores where the layer's rows
+        # allow it, pushed as a planned chunk otherwise), at three densities
+        opts["plan_dense"] = (1 << 30, int(rng.choice([64, 512, 1 << 20])))
+        if rng.random() < 0.25:
+            opts["no_dense"] = True
     return case, opts, knobs
 
 
