@@ -371,14 +371,16 @@ class WorkloadRun:
     ready: List[np.ndarray] = field(default_factory=list)       # per layer: the whole ready list, completion order
     tails: List[np.ndarray] = field(default_factory=list)       # per layer: ready-list length at every flush
     pending_final_any: List[bool] = field(default_factory=list)
+    plan_info: Optional[dict] = None                            # plans with a dense part: atlas_plan_info
 
 
 def run_workload(wl, *, plan: bool = True, emb_resident: bool = False, planned_only: bool = False, plan_block=None,
                  pinned: bool = False, n_layers: Optional[int] = None, sample: Optional[Sample] = None,
-                 indeg: Optional[torch.Tensor] = None) -> WorkloadRun:
+                 indeg: Optional[torch.Tensor] = None, plan_dense: Optional[tuple] = None) -> WorkloadRun:
     """All (or the first n_layers) layers of a workload through the C ABI, flush after every chunk,
     each layer reading the previous layer's output where it lies in device memory.  plan_block =
-    (block_sources, hot_min_edges) builds the source-blocked plan.  pinned: the CSR and the
+    (block_sources, hot_min_edges) builds the source-blocked plan; plan_dense = (max_bytes, cells_per_edge) the
+    plan with a dense part for the first chunk (run.plan_info tells what it holds).  pinned: the CSR and the
     first layer's features are handed over in pinned host memory and streamed by the library.
     With a sample, layer 1 also records the pending counts of the sampled vertices after every chunk."""
     dev = wl.off.device
@@ -396,7 +398,12 @@ def run_workload(wl, *, plan: bool = True, emb_resident: bool = False, planned_o
     else:
         off_t, col_t, x0, res = wl.off, wl.col, wl.X, atlas.RESIDENT_DEVICE
     plan_h = None
-    if plan and plan_block:
+    if plan and plan_dense:
+        pb = plan_block or (0, 0)
+        plan_h = atlas.atlas_plan_create_dense(atlas.make_graph(n, e, off_t, col_t, None, res), wl.chunk, pb[0], pb[1],
+                                               plan_dense[0], plan_dense[1])
+        run.plan_info = atlas.atlas_plan_info(plan_h)
+    elif plan and plan_block:
         plan_h = atlas.atlas_plan_create_blocked(atlas.make_graph(n, e, off_t, col_t, None, res), wl.chunk, *plan_block)
     elif plan:
         plan_h = atlas.atlas_plan_create(atlas.make_graph(n, e, off_t, col_t, None, res), wl.chunk)

@@ -31,7 +31,7 @@ def H():
     return harness
 
 
-def _go(oracle, H, wl, plan=True, n_random=1 << 14, sample=None, indeg=None, **kw):
+def _go(oracle, H, wl, plan=True, n_random=1 << 14, sample=None, indeg=None, contracted=None, **kw):
     if sample is None:
         if indeg is None:
             indeg = torch.empty(wl.n, dtype=torch.int32, device=wl.off.device)
@@ -39,6 +39,11 @@ def _go(oracle, H, wl, plan=True, n_random=1 << 14, sample=None, indeg=None, **k
         sample = H.draw_sample(wl, indeg, n_random=n_random)
     run = H.run_workload(wl, plan=plan, sample=sample, indeg=indeg, **kw)
     assert len(run.outs) == len(wl.layers)
+    if contracted is not None:   # a plan with a dense part: it exists, and its edges went the expected way
+        assert run.plan_info["dense_edges"] > 0 and run.plan_info["dense_cells"] >= 64 * run.plan_info["dense_rows"]
+        for st in run.stats:
+            assert st["edges_contracted"] == (run.plan_info["dense_edges"] if contracted else 0)
+        print("dense part:", run.plan_info, flush=True)
     H.check_layer_counters(wl, run, planned=plan)
     H.check_sampled_integers(oracle, wl, run, sample)
     errs = H.check_sampled_layers(oracle, wl, run, sample)
@@ -65,7 +70,11 @@ def test_config2_gcn_scale20(oracle, H, order):
 def test_config3_sage_scale22_bf16(oracle, H):
     wl = workloads.config3("cuda:0")
     assert wl.n == 1 << 22 and wl.e == 25 * (1 << 22) and wl.chunk == 1 << 18 and wl.dims == [256, 256, 256, 128]
-    _go(oracle, H, wl)
+    s = _go(oracle, H, wl)
+    # the same with a dense part in the plan: the ids are not degree-ordered, so the region is whatever the
+    # first chunk happens to hold at one edge per 4,096 cells; rows of 256 features are wider than the
+    # contraction takes, so the part is pushed as the planned chunk it also is
+    _go(oracle, H, wl, sample=s, planned_only=True, plan_dense=(8 << 30, 4096), contracted=False)
 
 
 def test_config4_gat_scale22(oracle, H):
@@ -78,7 +87,8 @@ def test_config5_sage_scale26_bf16(oracle, H):
     """The benchmark's workload, three layers, in both executions the benchmark times.
     Device-resident: resident embeddings, every chunk planned (no zero fill at the layer
     start), source-blocked plan with 2 MiB of source rows per block and 32 messages per block
-    as the threshold for a blocked destination.  As the configuration states it: CSR and
+    as the threshold for a blocked destination, the first chunk's dense corner (up to 32 GB of
+    cells at the library's default density) contracted on the matrix cores in all three layers.  As the configuration states it: CSR and
     features in pinned host memory, plan in pinned host memory, chunks streamed on the copy
     stream (the first one in pieces), later layers fed from device memory.  The oracle computes
     2^18 random destinations and the 1,024 of highest in-degree, about 1.2e8 in-edges, for each
@@ -87,5 +97,5 @@ def test_config5_sage_scale26_bf16(oracle, H):
     assert wl.n == 1 << 26 and wl.e == 1 << 31 and wl.chunk == 1 << 22 and wl.dims == [128, 128, 128, 64]
     block = (2 << 20) // (wl.dims[0] * 2)
     s = _go(oracle, H, wl, emb_resident=True, n_random=1 << 18, planned_only=True,
-            plan_block=(block, 32 * (wl.chunk // block)))
+            plan_block=(block, 32 * (wl.chunk // block)), plan_dense=(32 * 10 ** 9, 0), contracted=True)
     _go(oracle, H, wl, sample=s, emb_resident=True, planned_only=True, pinned=True)
