@@ -304,7 +304,7 @@ def main() -> int:
         for _ in range(args.warmup):
             run_layer(graph, planned, 0, x0, True)
         torch.cuda.synchronize()
-        acc = {"ms_aggregate": 0.0, "ms_dense": 0.0, "ms_update": 0.0, "ms_self": 0.0, "ms_init": 0.0, "ms_copy": 0.0}
+        acc = {"ms_aggregate": 0.0, "ms_dense": 0.0, "ms_contract": 0.0, "ms_update": 0.0, "ms_self": 0.0, "ms_init": 0.0, "ms_copy": 0.0}
         step_ms = []   # atlas_layer_finish waits for the layer, so each step ends synchronised
         t0 = time.perf_counter()
         st = None
@@ -436,10 +436,14 @@ def main() -> int:
                       "ms_per_layer": round(ms_d, 3),
                       "edges_per_s": round(plan_info["dense_edges"] / max(ms_d, 1e-9) * 1e3, 1)}
         if contracted:
+            # the contraction kernel alone (ms_per_layer also clears the rows, repacks the chunk's rows and
+            # lowers the pending counts): flops of the dense product over the region's cells
             fl = 2.0 * plan_info["dense_cells"] * d
-            dense_part.update({"kernel": "k_dense_contract", "tflops": round(fl / (ms_d / 1e3) / 1e12, 1),
-                               "frac_of_mfma_peak": round(fl / (ms_d / 1e3) / 2.5e15, 4),
-                               "cells_GBps": round(plan_info["dense_cells"] / (ms_d / 1e3) / 1e9, 1)})
+            ms_c = ps["ms_contract"]
+            dense_part.update({"kernel": "k_dense_contract", "kernel_ms": round(ms_c, 3),
+                               "tflops": round(fl / (ms_c / 1e3) / 1e12, 1),
+                               "frac_of_mfma_peak": round(fl / (ms_c / 1e3) / 2.5e15, 4),
+                               "cell_stream_GBps": round(plan_info["dense_cells"] / 2 / (ms_c / 1e3) / 1e9, 1)})
     if roofline["frac"] > 1.0:
         log("note: the kernel's algorithmic bytes per second exceed the HBM peak (rows served from cache)")
     K = 2 * wl.dims[0] if wl.model == "sage" else wl.dims[0]
@@ -491,6 +495,15 @@ def main() -> int:
         del ids, ca
         mf = {}
         if sdt != atlas.DTYPE_F32:
+            # nothing but bf16 32x32x16 matrix instructions on register operands, 2 and 4 wavefronts per SIMD
+            for wps in (2, 4):
+                it_n = 1 << 15
+                fl = atlas.atlas_probe_mfma(wps, 1 << 10, sink)
+                t_ms = ev_ms(lambda: atlas.atlas_probe_mfma(wps, it_n, sink), 1)
+                fl = atlas.atlas_probe_mfma(wps, it_n, sink)
+                torch.cuda.synchronize()
+                mf["bare_issue_%d_waves_per_simd" % wps] = {
+                    "tflops": round(fl / (t_ms / 1e3) / 1e12, 1), "frac_of_mfma_peak": round(fl / (t_ms / 1e3) / mfma_peak, 4)}
             # the contraction on a block of rows small enough to stay in the memory-side cache, many passes:
             # the flush's shape (K = 2 d_in -> d_out) and the wide first-layer transform (K = 1024 -> 256)
             for label, rows_n, kk, dd in (("flush_shape", 1 << 16, K, wl.dims[1]), ("wide_transform", 1 << 15, 1024, 256)):

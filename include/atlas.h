@@ -245,6 +245,9 @@ typedef struct {
     int64_t edges_contracted;   /* edges of the plan's dense part that were pushed as a dense
                                    contraction (see atlas_plan_create_dense); they are part
                                    of edges_processed                                       */
+    float ms_contract;          /* ATLAS_FLAG_TIMING: the contraction kernel alone (part of
+                                   ms_dense, which also clears the rows, repacks the chunk
+                                   and lowers the pending counts)                           */
 } atlas_layer_stats_t;
 
 /* Create the state of one layer (Sec. 3.4: pending-message tracker and
@@ -352,18 +355,18 @@ int atlas_plan_create_blocked(const atlas_graph_t *graph, int64_t chunk_sources,
  * hottest destinations both lie at the front, and the first chunk's edges between them are so
  * many that this corner of the adjacency matrix holds more than one edge per hundred cells.
  * There a message costs more as a 256-byte row gather than its cell costs in a dense product.
- * The plan therefore keeps the multiplicities of that corner as a staircase of byte matrices
+ * The plan therefore keeps the multiplicities of that corner as a staircase of matrices of 4-bit counts
  * (256 destinations form a band; a band takes its first S_band sources, S_band non-increasing
  * over the bands) and the layer adds  multiplicities x rows  to the accumulators of those
  * destinations on the matrix cores before it pushes the chunk's other edges: multiplicities up
- * to 255 are exact 16-bit floats, the products are exact, the sums are fp32 -- the edge stream's
+ * to 15 are exact 16-bit floats, the products are exact, the sums are fp32 -- the edge stream's
  * sums in another order.  Pending counts drop by each destination's number of dense messages in
  * one step, vertices that complete are appended to the ready list as for any other message.
  * The region is chosen from the chunk's edge counts over log-spaced (source rank, destination
  * rank) blocks: a block belongs to it when it holds at least one edge per dense_cells_per_edge
- * cells (0: the library's default, 64) and so do the blocks before it; the value is halved until
+ * cells (0: the library's default, 96) and so do the blocks before it; the value is halved until
  * the cells fit dense_max_bytes (0: no dense part, plain atlas_plan_create_blocked).  A cell that
- * is full (255) leaves further copies of its edge to the chunk's edge list.  When no block is
+ * is full (15) leaves further copies of its edge to the chunk's edge list.  When no block is
  * dense enough the plan is an ordinary one.
  * The contraction serves layers that sum plain rows (SAGE_MEAN, GIN, SGC_HOP), 16-bit rows of
  * width 64 or 128 (with ATLAS_FLAG_TRANSFORM_FIRST: the pushed products); every other layer, and
@@ -441,7 +444,7 @@ typedef struct {
     int64_t bytes_device, bytes_pinned_host;
     int64_t dense_edges;        /* edges the dense part of the first chunk holds (0: no dense part) */
     int64_t dense_groups;       /* their destination groups (part of num_groups)                    */
-    int64_t dense_cells;        /* its cells = bytes                                                */
+    int64_t dense_cells;        /* its cells (half a byte each)                                     */
     int64_t dense_rows;         /* destinations [0, dense_rows) have a band                         */
     int64_t dense_max_sources;  /* sources the longest band takes                                   */
 } atlas_plan_info_t;
@@ -464,7 +467,13 @@ int atlas_plan_info(const atlas_plan_t *plan, atlas_plan_info_t *info);
  *                            (16-bit types; K a multiple of 64 up to 1024, d_out a multiple of 32 up
  *                            to 256), `repeat` passes over the same rows, so that a row block that
  *                            fits the caches shows the contraction's rate without the HBM cap.
+ *   atlas_probe_mfma:        nothing but bf16 32x32x16 matrix instructions on register operands:
+ *                            waves_per_simd (1..8) wavefronts on every SIMD, each `iters` (up to 2^24)
+ *                            rounds of four independent products; *flops (host) receives the
+ *                            launch's flop count.  What the matrix pipeline delivers when nothing is
+ *                            loaded, converted or synchronised.  sink: as for atlas_probe_row_gather.
  * Errors: E_NULL, E_BAD_DIMS, E_RANGE, E_HIP, E_NOMEM. */
+int atlas_probe_mfma(int32_t waves_per_simd, int32_t iters, void *sink, double *flops, void *hip_stream);
 int atlas_probe_copy(void *dst, const void *src, int64_t bytes, void *hip_stream);
 int atlas_probe_mix21(void *dst, const void *a, const void *b, int64_t bytes, void *hip_stream);
 int64_t atlas_probe_gather_sink_bytes(void);

@@ -37,7 +37,7 @@ EXPORTS = [
     "atlas_release_cache", "atlas_strerror", "atlas_last_hip_error", "atlas_plan_create", "atlas_plan_destroy",
     "atlas_reorder_score_desc", "atlas_sample_in_edges", "atlas_plan_create_blocked", "atlas_plan_create_dense",
     "atlas_reorder_indegree_desc_noalloc", "atlas_plan_info", "atlas_plan_in_degree", "atlas_probe_copy", "atlas_probe_row_gather",
-    "atlas_probe_dense_rows", "atlas_probe_gather_sink_bytes", "atlas_probe_mix21",
+    "atlas_probe_dense_rows", "atlas_probe_gather_sink_bytes", "atlas_probe_mix21", "atlas_probe_mfma",
 ]
 
 
@@ -72,7 +72,7 @@ class atlas_layer_stats_t(ctypes.Structure):
                 ("hot_peak_slots", ctypes.c_int64), ("chunks_planned", ctypes.c_int64),
                 ("chunks_csr_stream", ctypes.c_int64), ("chunks_regrouped", ctypes.c_int64),
                 ("ms_regroup", ctypes.c_float), ("ms_dense", ctypes.c_float), ("rows_handed_over", ctypes.c_int64),
-                ("edges_contracted", ctypes.c_int64)]
+                ("edges_contracted", ctypes.c_int64), ("ms_contract", ctypes.c_float)]
 
 
 class atlas_plan_info_t(ctypes.Structure):
@@ -127,6 +127,7 @@ def lib() -> ctypes.CDLL:
         L.atlas_plan_in_degree.argtypes = [vp, vp, vp]
         L.atlas_probe_copy.argtypes = [vp, vp, i64, vp]
         L.atlas_probe_mix21.argtypes = [vp, vp, vp, i64, vp]
+        L.atlas_probe_mfma.argtypes = [i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.atlas_probe_gather_sink_bytes.argtypes = []
         L.atlas_probe_row_gather.argtypes = [vp, i64, vp, i64, vp, vp]
         L.atlas_probe_dense_rows.argtypes = [i32, vp, i64, i32, i32, vp, vp, i32, vp]
@@ -254,6 +255,13 @@ def atlas_plan_in_degree(plan: int, in_degree, stream=None) -> None:
 
 def atlas_probe_copy(dst, src, nbytes: int, stream=None) -> None:
     _check(lib().atlas_probe_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "atlas_probe_copy")
+
+
+def atlas_probe_mfma(waves_per_simd: int, iters: int, sink, stream=None) -> float:
+    """Enqueues the bare matrix-instruction loop; returns the launch's flop count."""
+    fl = ctypes.c_double()
+    _check(lib().atlas_probe_mfma(waves_per_simd, iters, _ptr(sink), ctypes.byref(fl), _stream(stream)), "atlas_probe_mfma")
+    return fl.value
 
 
 def atlas_probe_mix21(dst, a, b, nbytes: int, stream=None) -> None:

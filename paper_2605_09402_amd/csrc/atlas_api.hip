@@ -99,7 +99,7 @@ hipError_t cold_buffer(size_t bytes, void **out) {
 constexpr int64_t kDefaultPieceTiles = int64_t(1) << 21;
 // A block of the first chunk goes to the dense part when it holds at least one edge per this many cells: a
 // cell costs a byte of the contraction's stream, an edge a 256-byte row gather.
-constexpr int64_t kDefaultDenseCellsPerEdge = 64;
+constexpr int64_t kDefaultDenseCellsPerEdge = 96;
 
 // The chunk loader's copy stream is created once per process and shared by
 // all layers: HIP spreads streams over a few hardware queues, and a stream
@@ -209,7 +209,7 @@ struct atlas_layer {
     Buf stage_col[kStageSlots], stage_emb[kStageSlots];
     std::vector<hipEvent_t> piece_ev[kStageSlots];   // a long chunk's edge words arrive in pieces: one event each
 
-    std::vector<TimedSpan> t_agg, t_self, t_upd, t_copy, t_init, t_dense;
+    std::vector<TimedSpan> t_agg, t_self, t_upd, t_copy, t_init, t_dense, t_contract;
     hipStream_t last_stream = nullptr;
 
     int32_t *ctr() { return static_cast<int32_t *>(counters.p); }
@@ -235,7 +235,7 @@ struct atlas_layer {
             for (hipEvent_t e : v) (void)hipEventDestroy(e);
         for (Buf &b : stage_col) b.release();
         for (Buf &b : stage_emb) b.release();
-        for (auto *v : {&t_agg, &t_self, &t_upd, &t_copy, &t_init, &t_dense})
+        for (auto *v : {&t_agg, &t_self, &t_upd, &t_copy, &t_init, &t_dense, &t_contract})
             for (auto &sp : *v) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
         for (int i = 0; i < kStageSlots; ++i) {
             if (slot_loaded[i]) (void)hipEventDestroy(slot_loaded[i]);
@@ -1021,8 +1021,11 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
                 L->dense_rows.release();
                 HIP_TRY(L->dense_rows.alloc(need));
             }
-            HIP_TRY(launch_dense_part(dp, a.emb, src_end - src_begin, a.d, a.in_dt, L->dense_rows.p, a.acc, L->n,
-                                      a.pending, a.ready, a.counters, a.counters64, s));
+            HIP_TRY(launch_dense_prepare(dp, a.emb, src_end - src_begin, a.d, a.in_dt, L->dense_rows.p, a.acc, L->n, s));
+            if ((rc = start_span(L, L->t_contract, s)) != ATLAS_OK) return rc;
+            HIP_TRY(launch_dense_contract(dp, a.d, a.in_dt, L->dense_rows.p, a.acc, L->n, s));
+            if ((rc = end_span(L, L->t_contract, s)) != ATLAS_OK) return rc;
+            HIP_TRY(launch_dense_pending(dp, L->n, a.pending, a.ready, a.counters, a.counters64, s));
             L->edges_contracted += dp.list.n_edges;
         } else {
             GroupedArgs gd = ga;
@@ -1195,6 +1198,7 @@ int atlas_layer_finish(atlas_layer_t *L, atlas_layer_stats_t *stats) {
             stats->edges_contracted = L->edges_contracted;
             stats->ms_aggregate = sum_spans(L->t_agg);
             stats->ms_dense = sum_spans(L->t_dense);
+            stats->ms_contract = sum_spans(L->t_contract);
             stats->ms_self = sum_spans(L->t_self);
             stats->ms_init = sum_spans(L->t_init);
             stats->ms_update = sum_spans(L->t_upd);
@@ -1396,7 +1400,7 @@ int atlas_plan_info(const atlas_plan_t *P, atlas_plan_info_t *info) {
                static_cast<size_t>(P->dense.n_items) * 12;
         info->dense_edges = c.n_edges;
         info->dense_groups = c.n_groups;
-        info->dense_cells = static_cast<int64_t>(P->dense.cell_bytes);
+        info->dense_cells = static_cast<int64_t>(P->dense.cell_bytes) * 2;   // half a byte each
         info->dense_rows = std::min(P->dense.rows, P->n);
         info->dense_max_sources = static_cast<int64_t>(P->dense.max_ksteps) * 64;
     }
@@ -1431,6 +1435,13 @@ int atlas_probe_mix21(void *dst, const void *a, const void *b, int64_t bytes, vo
     if (!dst || !a || !b) return ATLAS_E_NULL;
     if (bytes < 0 || bytes % 16 != 0) return ATLAS_E_RANGE;
     HIP_TRY(probe_mix21(dst, a, b, static_cast<size_t>(bytes), static_cast<hipStream_t>(hip_stream)));
+    return ATLAS_OK;
+}
+
+int atlas_probe_mfma(int32_t waves_per_simd, int32_t iters, void *sink, double *flops, void *hip_stream) {
+    if (!sink || !flops) return ATLAS_E_NULL;
+    if (waves_per_simd < 1 || waves_per_simd > 8 || iters < 1 || iters > (1 << 24)) return ATLAS_E_RANGE;
+    HIP_TRY(probe_mfma(waves_per_simd, iters, sink, flops, static_cast<hipStream_t>(hip_stream)));
     return ATLAS_OK;
 }
 

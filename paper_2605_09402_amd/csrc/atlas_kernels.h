@@ -204,20 +204,23 @@ hipError_t build_plan_chunk(const int64_t *off_dev, const int32_t *col_dev, int6
                             PlanWork &w, PlanChunk *out, const EdgePairs *pairs = nullptr);
 
 // Dense part of a plan's first chunk (k_dense.hip): the multiplicities of the edges between the chunk's
-// first sources and the first destinations as a staircase of byte matrices, one band per 256 destinations,
+// first sources and the first destinations as a staircase of matrices of 4-bit counts, one band per 256 destinations,
 // and the same edges as an ordinary planned chunk (`list`) for layers the contraction does not serve.
 constexpr int kDenseBuckets = 24;        // log-spaced rank buckets of the density histogram
-constexpr int kDenseItemKsteps = 128;    // most k-steps (of 64 sources) one workgroup contracts
+constexpr int kDenseKstepBytes = 8192;   // cells of one band and k-step: 256 destinations x 64 sources x 4 bits
+constexpr int kDenseKstepUnit = 12;      // a band's k-steps (of 64 sources) are a multiple of this
+constexpr int kDenseItemKsteps = 192;    // most k-steps one workgroup contracts (a multiple of the unit, below 2^16)
 struct DensePart {
     int64_t rows = 0;                 // destinations [0, rows), a multiple of 256 (may exceed N)
     int32_t n_bands = 0;              // rows / 256
-    int32_t max_ksteps = 0;           // sources / 64 of the longest band (a multiple of 4)
+    int32_t max_ksteps = 0;           // sources / 64 of the longest band (a multiple of kDenseKstepUnit)
     int32_t *band_ksteps = nullptr;   // device [n_bands]
     int64_t *band_off = nullptr;      // device [n_bands]: byte offset of the band's cells
     uint8_t *cells = nullptr;         // device
     size_t cell_bytes = 0;
     int32_t *msgs = nullptr;          // device [rows]: messages of the dense part to each destination
-    int32_t *items = nullptr;         // device [n_items][3]: band, first k-step, k-steps of every work item
+    int32_t *items = nullptr;         // device [n_items][3]: band, first k-step, k-steps (| 1 << 16: the band's
+                                      // only item) of every work item
     int64_t n_items = 0;
     PlanChunk list;                   // the part's edges, grouped by destination
     void release();
@@ -250,12 +253,17 @@ struct DenseArgs {
 bool dense_contract_takes(int d, int in_dt);
 // Bytes of the repacked chunk rows the contraction reads (`xt` below).
 size_t dense_packed_rows_bytes(const DensePart &p, int d);
-// acc[v] = sum of the dense part's messages to v for v < rows (the rows are overwritten: the part is pushed
-// before anything else of the layer), pending counts lowered, completed vertices appended to the ready list.
-// emb: the chunk's rows (chunk_rows of them, 16-bit, d wide).
-hipError_t launch_dense_part(const DensePart &p, const void *emb, int64_t chunk_rows, int d, int in_dt, void *xt,
-                             float *acc, int64_t n, int32_t *pending, int32_t *ready, int32_t *counters,
-                             unsigned long long *counters64, hipStream_t s);
+// The dense part in three launches (the part is pushed before anything else of the layer):
+//   prepare:  accumulator rows [0, rows) cleared, the chunk's rows (emb: chunk_rows of them, 16-bit, d wide)
+//             repacked into xt;
+//   contract: acc[v] += sum of the dense part's messages to v;
+//   pending:  pending counts lowered, completed vertices appended to the ready list, edges counted.
+hipError_t launch_dense_prepare(const DensePart &p, const void *emb, int64_t chunk_rows, int d, int in_dt, void *xt,
+                                float *acc, int64_t n, hipStream_t s);
+hipError_t launch_dense_contract(const DensePart &p, int d, int in_dt, const void *xt, float *acc, int64_t n,
+                                 hipStream_t s);
+hipError_t launch_dense_pending(const DensePart &p, int64_t n, int32_t *pending, int32_t *ready, int32_t *counters,
+                                unsigned long long *counters64, hipStream_t s);
 
 // indeg[v] += messages the chunk sends to v, for every destination of a planned chunk whose arrays are in
 // device memory (src_sorted: the chunk's slice).  indeg must have been zeroed before the first chunk.
@@ -385,6 +393,7 @@ hipError_t launch_advance_head(int32_t *counters, hipStream_t s);
 hipError_t probe_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
 hipError_t probe_mix21(void *dst, const void *a, const void *b, size_t bytes, hipStream_t s);
 size_t probe_gather_sink_bytes();
+hipError_t probe_mfma(int waves_per_simd, int iters, void *sink, double *flops, hipStream_t s);
 hipError_t probe_row_gather(const void *table, const int32_t *ids, int64_t n_ids, void *sink, hipStream_t s);
 
 // Degree ordering.

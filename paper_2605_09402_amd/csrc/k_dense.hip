@@ -5,20 +5,22 @@
 // that the corresponding corner of the adjacency matrix is denser than one
 // edge per hundred cells.  There the per-edge row gather (a 256-byte random
 // read per edge) costs more than multiplying the corner as a dense matrix:
-// the plan keeps the corner's multiplicities as bytes (`cells`), and the layer
-// adds  cells x X[sources]  to the accumulator rows on the matrix cores
-// (multiplicities up to 255 are exact 16-bit floats, products are exact, sums
+// the plan keeps the corner's multiplicities as 4-bit counts (`cells`), and the
+// layer adds  cells x X[sources]  to the accumulator rows on the matrix cores
+// (multiplicities up to 15 are exact 16-bit floats, products are exact, sums
 // are fp32: the same sums as the edge stream in another order).  The region is
 // a staircase: 256 destinations form a band, and each band has its own number
-// of sources.
+// of sources.  Half a byte per cell because the contraction is bound by the
+// stream of cells out of HBM, not by the matrix pipeline; the few pairs that
+// occur more than 15 times leave the surplus in the chunk's edge list.
 //
 // Cell layout.  A band's cells are stored in the order the kernel's wavefronts
 // consume them, so that every load is a contiguous kilobyte: per k-step of 64
-// sources 16 KB = [wave 0..3][row block 0..1][k pair 0..1][lane 0..63][16 bytes];
-// lane l of wave w holds destination row 64 w + 32 rb + (l & 31) of the band, and
-// its 16 bytes are the multiplicities of sources 32 p + 16 h + 8 (l >> 5) + j for
-// h = 0, 1 and j = 0..7 (bytes 8 h + j): the two 8-element operands of the lane
-// for the matrix instruction's k-steps 2 p and 2 p + 1.
+// sources 8 KB = [wave 0..3][row block 0..1][lane 0..63][16 bytes]; lane l of
+// wave w holds destination row 64 w + 32 rb + (l & 31) of the band, and dword u
+// of its 16 bytes holds the multiplicities of sources 16 u + 8 (l >> 5) + j,
+// j = 0..7: j < 4 in the low half of byte j, j >= 4 in the high half of byte
+// j - 4 -- the lane's 8-element operand for the matrix instruction's k-step u.
 #include "atlas_kernels.h"
 
 namespace atlas {
@@ -51,17 +53,19 @@ __global__ __launch_bounds__(kBlock) void k_dense_histogram(const int32_t *src_o
         if (h[i]) atomicAdd(&hist[i], static_cast<unsigned long long>(h[i]));
 }
 
-__device__ __forceinline__ int64_t cell_offset(const int64_t *band_off, uint32_t d, uint32_t s) {
+// byte offset of the cell of (destination d, source s) and, in *high, which half of the byte it is
+__device__ __forceinline__ int64_t cell_offset(const int64_t *band_off, uint32_t d, uint32_t s, uint32_t *high) {
     const uint32_t r = d & 255u, k = s & 63u;
     const uint32_t w = r >> 6, rb = (r >> 5) & 1u, row = r & 31u;
-    const uint32_t u = k >> 4, p = u >> 1, kg = (k >> 3) & 1u, j = k & 7u;
+    const uint32_t u = k >> 4, kg = (k >> 3) & 1u, j = k & 7u;
     const uint32_t lane = kg * 32u + row;
-    return band_off[d >> 8] + static_cast<int64_t>(s >> 6) * 16384 + (((w * 2u + rb) * 2u + p) * 64u + lane) * 16u +
-           (u & 1u) * 8u + j;
+    *high = j >> 2;
+    return band_off[d >> 8] + static_cast<int64_t>(s >> 6) * kDenseKstepBytes + ((w * 2u + rb) * 64u + lane) * 16u +
+           u * 4u + (j & 3u);
 }
 
 // Every edge of the chunk that falls into the region raises its cell by one
-// and is flagged; a cell that is full (255) leaves the edge to the edge list.
+// and is flagged; a cell that is full (15) leaves the edge to the edge list.
 __global__ __launch_bounds__(kBlock) void k_dense_divert(const int32_t *src_of_edge, const int32_t *col, int64_t ne,
                                                           int64_t src_begin, int64_t rows, const int32_t *band_ksteps,
                                                           const int64_t *band_off, uint8_t *cells, uint8_t *flags) {
@@ -71,11 +75,12 @@ __global__ __launch_bounds__(kBlock) void k_dense_divert(const int32_t *src_of_e
         const uint32_t d = static_cast<uint32_t>(col[i]);
         bool taken = false;
         if (static_cast<int64_t>(d) < rows && s < static_cast<uint32_t>(band_ksteps[d >> 8]) * 64u) {
-            const int64_t off = cell_offset(band_off, d, s);
+            uint32_t high = 0;
+            const int64_t off = cell_offset(band_off, d, s, &high);
             unsigned int *word = reinterpret_cast<unsigned int *>(cells) + (off >> 2);
-            const unsigned int sh = static_cast<unsigned int>(off & 3) * 8u;
+            const unsigned int sh = static_cast<unsigned int>(off & 3) * 8u + high * 4u;
             unsigned int old = __atomic_load_n(word, __ATOMIC_RELAXED);
-            while (((old >> sh) & 0xffu) != 0xffu) {
+            while (((old >> sh) & 0xfu) != 0xfu) {
                 const unsigned int seen = atomicCAS(word, old, old + (1u << sh));
                 if (seen == old) {
                     taken = true;
@@ -165,13 +170,19 @@ __device__ __forceinline__ typename Operand<CT>::type bytes_to_operand(uint32_t 
     return __builtin_bit_cast(typename Operand<CT>::type, q);
 }
 
+// eight 4-bit multiplicities: elements 0..3 in the low halves of the dword's bytes, 4..7 in the high halves
+template <int CT>
+__device__ __forceinline__ typename Operand<CT>::type nibbles_to_operand(uint32_t q) {
+    return bytes_to_operand<CT>(q & 0x0f0f0f0fu, (q >> 4) & 0x0f0f0f0fu);
+}
+
 template <int CT>
 __device__ __forceinline__ f32x16_t mfma(typename Operand<CT>::type a, typename Operand<CT>::type b, f32x16_t c) {
     if constexpr (CT == 1) return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
     else return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
 }
 
-struct CellRegs { uint4 q[2][2]; };   // [row block][k pair]
+struct CellRegs { uint4 q[2]; };   // [row block]: dword u = the lane's eight cells of the matrix instruction's k-step u
 
 // acc[band rows][N] += cells[band rows][sources of the item] x X[sources][N].
 // One workgroup (4 waves) per work item = 256 destinations x up to kDenseItemKsteps
@@ -179,8 +190,10 @@ struct CellRegs { uint4 q[2][2]; };   // [row block][k pair]
 // and all N features (NB blocks of 32).  The multiplicities go from HBM
 // straight into the registers of the lane that needs them (see the layout
 // above), two k-steps ahead; the rows' tile (N x 64, 16-bit) is shared by the
-// four waves through a double-buffered LDS tile, its loads two k-steps ahead too.  Partial
-// sums of a band's items meet in the accumulator through fp32 atomics: with the
+// four waves through a double-buffered LDS tile, its loads two k-steps ahead too.  A band
+// that is one item stores its sums (the 64-byte atomic requests of the epilogue are what the chip
+// retires slowest: some 20 G a second); partial sums of a longer band's items meet in the
+// accumulator through fp32 atomics: with the
 // cells as the FIRST operand a lane holds 16 destinations of ONE feature, so
 // the 32 lanes of a half-wave add to 128 consecutive bytes of one row.
 template <int CT, int NB>
@@ -192,16 +205,21 @@ __global__ __launch_bounds__(kBlock, 2) void k_dense_contract(DenseArgs a) {
     __shared__ __align__(16) unsigned char tile[2][kTileBytes];
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
-    const int32_t band = a.items[blockIdx.x * 3], ks0 = a.items[blockIdx.x * 3 + 1], nks = a.items[blockIdx.x * 3 + 2];
-    const unsigned char *cells = a.cells + a.band_off[band] + static_cast<int64_t>(ks0) * 16384 + (w * 4 * 64 + lane) * 16;
+    const int32_t band = a.items[blockIdx.x * 3], ks0 = a.items[blockIdx.x * 3 + 1];
+    const int32_t nks = a.items[blockIdx.x * 3 + 2] & 0xffff;
+    const bool sole = (a.items[blockIdx.x * 3 + 2] >> 16) != 0;   // the band's only item: its rows are this workgroup's alone
+    const unsigned char *cells = a.cells + a.band_off[band] + static_cast<int64_t>(ks0) * kDenseKstepBytes + (w * 2 * 64 + lane) * 16;
     const unsigned char *xt = static_cast<const unsigned char *>(a.xt) + static_cast<int64_t>(ks0) * kTileBytes + threadIdx.x * 16;
 
     auto load_cells = [&](int s, CellRegs &r) __attribute__((always_inline)) {
-        const unsigned char *p = cells + static_cast<int64_t>(s) * 16384;
+        const unsigned char *p = cells + static_cast<int64_t>(s) * kDenseKstepBytes;
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-            for (int pp = 0; pp < 2; ++pp) r.q[rb][pp] = *reinterpret_cast<const uint4 *>(p + (rb * 2 + pp) * 1024);
+        for (int rb = 0; rb < 2; ++rb) {
+            // read once: a streaming load, so that the cells do not push the shared row tiles out of the caches
+            typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+            const u4 v = __builtin_nontemporal_load(reinterpret_cast<const u4 *>(p + rb * 1024));
+            r.q[rb] = make_uint4(v.x, v.y, v.z, v.w);
+        }
     };
     // The tile registers are plain variables handled by macros: as arrays or structs passed to helper
     // closures they were kept in scratch memory across the loop's back edge.
@@ -252,28 +270,28 @@ __global__ __launch_bounds__(kBlock, 2) void k_dense_contract(DenseArgs a) {
     __syncthreads();
     // one step: HELD carries the tile of step S + 1 (stored to LDS at the end), FRESH receives that of S + 2
     // (loads past the item's end repeat its last k-step: in bounds, unused)
-#define ATLAS_DENSE_STEP(S, HELD, FRESH)                                                              \
+#define ATLAS_DENSE_STEP(S, HELD, FRESH, MC, MF)                                                      \
     {                                                                                                 \
         ATLAS_TILE_LOAD((S) + 2 < nks ? (S) + 2 : nks - 1, FRESH)                                     \
         __builtin_amdgcn_sched_barrier(0);                                                            \
-        load_cells((S) + 2 < nks ? (S) + 2 : nks - 1, m2);                                            \
+        load_cells((S) + 2 < nks ? (S) + 2 : nks - 1, MF);                                            \
         __builtin_amdgcn_sched_barrier(0);                                                            \
         const unsigned char *t = tile[(S) & 1] + roff_row;                                            \
-        op_t xb[NB], xn[NB];                                                                          \
+        op_t xb[NB], xn[NB], ma[2], mn[2];                                                            \
         _Pragma("unroll") for (int nb = 0; nb < NB; ++nb)                                             \
             xb[nb] = *reinterpret_cast<const op_t *>(t + nb * 4096 + ((roff_half ^ roff_swz) * 16));  \
+        _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                              \
+            ma[rb] = nibbles_to_operand<CT>(MC.q[rb].x);                                              \
         _Pragma("unroll") for (int u = 0; u < 4; ++u) {                                               \
-            /* the row operands of the next k-step of the matrix instruction are read from LDS */     \
-            /* before this one's products are issued */                                               \
+            /* operands of the matrix instruction's next k-step: rows from LDS, cells converted */    \
             if (u < 3) {                                                                              \
                 _Pragma("unroll") for (int nb = 0; nb < NB; ++nb)                                     \
                     xn[nb] = *reinterpret_cast<const op_t *>(                                         \
                         t + nb * 4096 + (((2 * (u + 1) + roff_half) ^ roff_swz) * 16));               \
-            }                                                                                         \
-            op_t ma[2];                                                                               \
-            _Pragma("unroll") for (int rb = 0; rb < 2; ++rb) {                                        \
-                const uint4 q = m0.q[rb][u >> 1];                                                     \
-                ma[rb] = (u & 1) ? bytes_to_operand<CT>(q.z, q.w) : bytes_to_operand<CT>(q.x, q.y);   \
+                _Pragma("unroll") for (int rb = 0; rb < 2; ++rb) {                                    \
+                    const uint4 q = MC.q[rb];                                                         \
+                    mn[rb] = nibbles_to_operand<CT>(u == 0 ? q.y : u == 1 ? q.z : q.w);               \
+                }                                                                                     \
             }                                                                                         \
             _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) {                                       \
                 _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                      \
@@ -281,17 +299,35 @@ __global__ __launch_bounds__(kBlock, 2) void k_dense_contract(DenseArgs a) {
             }                                                                                         \
             if (u < 3) {                                                                              \
                 _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) xb[nb] = xn[nb];                    \
+                ma[0] = mn[0];                                                                        \
+                ma[1] = mn[1];                                                                        \
             }                                                                                         \
         }                                                                                             \
+        /* issue order within the step: after the first operands, every product is followed by */     \
+        /* some of the next operands' conversion instructions and every second one by a read */      \
+        /* of a row operand, so that the matrix pipeline works while the vector ALU converts */       \
+        __builtin_amdgcn_sched_group_barrier(0x100, NB, 0);                                           \
+        __builtin_amdgcn_sched_group_barrier(0x002, 30, 0);                                           \
+        _Pragma("unroll") for (int g = 0; g < 3 * 2 * NB; ++g) {                                      \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                        \
+            __builtin_amdgcn_sched_group_barrier(0x002, (30 + 2 * NB - 1) / (2 * NB), 0);             \
+            if ((g & 1) == 0) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                      \
+        }                                                                                             \
+        __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB, 0);                                       \
         __builtin_amdgcn_sched_barrier(0);                                                            \
         if ((S) + 1 < nks) ATLAS_TILE_STORE(((S) + 1) & 1, HELD)                                      \
         __syncthreads();                                                                              \
-        m0 = m1;                                                                                      \
-        m1 = m2;                                                                                      \
     }
-    for (int s = 0; s < nks; s += 2) {   // an item has a multiple of four k-steps
-        ATLAS_DENSE_STEP(s, ta, tb)
-        ATLAS_DENSE_STEP(s + 1, tb, ta)
+    // Six steps per round: the two tile register sets and the three cell register sets return to their roles
+    // without a single register copy -- a copy of a set whose loads are still in flight would wait for them
+    // and expose the whole memory latency in every step.  An item has a multiple of twelve k-steps.
+    for (int s = 0; s < nks; s += 6) {
+        ATLAS_DENSE_STEP(s, ta, tb, m0, m2)
+        ATLAS_DENSE_STEP(s + 1, tb, ta, m1, m0)
+        ATLAS_DENSE_STEP(s + 2, ta, tb, m2, m1)
+        ATLAS_DENSE_STEP(s + 3, tb, ta, m0, m2)
+        ATLAS_DENSE_STEP(s + 4, ta, tb, m1, m0)
+        ATLAS_DENSE_STEP(s + 5, tb, ta, m2, m1)
     }
 #undef ATLAS_DENSE_STEP
 #undef ATLAS_TILE_LOAD
@@ -306,8 +342,13 @@ __global__ __launch_bounds__(kBlock, 2) void k_dense_contract(DenseArgs a) {
             const int64_t row = row0 + rb * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
             if (row < a.n) {
                 float *o = a.acc + row * N + (lane & 31);
+                if (sole) {
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) unsafeAtomicAdd(o + nb * 32, c[rb][nb][i]);
+                    for (int nb = 0; nb < NB; ++nb) o[nb * 32] = c[rb][nb][i];
+                } else {
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) unsafeAtomicAdd(o + nb * 32, c[rb][nb][i]);
+                }
             }
         }
 }
@@ -379,9 +420,8 @@ size_t dense_packed_rows_bytes(const DensePart &p, int d) {
     return static_cast<size_t>(p.max_ksteps) * static_cast<size_t>(d) * 128;
 }
 
-hipError_t launch_dense_part(const DensePart &p, const void *emb, int64_t chunk_rows, int d, int in_dt, void *xt,
-                             float *acc, int64_t n, int32_t *pending, int32_t *ready, int32_t *counters,
-                             unsigned long long *counters64, hipStream_t s) {
+hipError_t launch_dense_prepare(const DensePart &p, const void *emb, int64_t chunk_rows, int d, int in_dt, void *xt,
+                                float *acc, int64_t n, hipStream_t s) {
     if (!dense_contract_takes(d, in_dt) || p.n_items <= 0) return hipErrorInvalidValue;
     const int64_t rows = p.rows < n ? p.rows : n;
     hipError_t err = launch_fill_zero(acc, static_cast<size_t>(rows) * d * sizeof(float), s);
@@ -392,7 +432,12 @@ hipError_t launch_dense_part(const DensePart &p, const void *emb, int64_t chunk_
                                      static_cast<int64_t>(p.max_ksteps), static_cast<uint16_t *>(xt));
     else hipLaunchKernelGGL((k_dense_pack_rows<64>), dim3(pg), dim3(kBlock), 0, s, x, chunk_rows,
                             static_cast<int64_t>(p.max_ksteps), static_cast<uint16_t *>(xt));
-    if ((err = hipGetLastError()) != hipSuccess) return err;
+    return hipGetLastError();
+}
+
+hipError_t launch_dense_contract(const DensePart &p, int d, int in_dt, const void *xt, float *acc, int64_t n,
+                                 hipStream_t s) {
+    if (!dense_contract_takes(d, in_dt) || p.n_items <= 0) return hipErrorInvalidValue;
     DenseArgs a{};
     a.cells = p.cells;
     a.band_off = p.band_off;
@@ -408,7 +453,13 @@ hipError_t launch_dense_part(const DensePart &p, const void *emb, int64_t chunk_
         if (in_dt == 1) hipLaunchKernelGGL((k_dense_contract<1, 2>), g, b, 0, s, a);
         else hipLaunchKernelGGL((k_dense_contract<2, 2>), g, b, 0, s, a);
     }
-    if ((err = hipGetLastError()) != hipSuccess) return err;
+    return hipGetLastError();
+}
+
+hipError_t launch_dense_pending(const DensePart &p, int64_t n, int32_t *pending, int32_t *ready, int32_t *counters,
+                                unsigned long long *counters64, hipStream_t s) {
+    const int64_t rows = p.rows < n ? p.rows : n;
+    if (rows <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_dense_pending, dim3(static_cast<unsigned>((rows + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
                        p.msgs, rows, p.list.n_edges, pending, ready, counters, counters64);
     return hipGetLastError();

@@ -347,7 +347,7 @@ void DensePart::release() {
 }
 
 namespace {
-// The staircase: per destination bucket, how many sources (in k-steps of 64, a multiple of 4) its bands
+// The staircase: per destination bucket, how many sources (in k-steps of 64) its bands
 // take.  A (source bucket, destination bucket) block belongs to the region when it spends at most
 // cells_per_edge cells per edge it holds and so do all blocks before it in its row and column of buckets,
 // which keeps the extents non-increasing from one destination bucket to the next.
@@ -369,7 +369,11 @@ void choose_staircase(const unsigned long long *hist, int64_t n, int64_t chunk_s
             ++take;
         }
         prev = take;
-        if (take > 0) ksteps[j] = static_cast<int32_t>(std::min(bucket_end(take - 1), src_cap) / 64);
+        // (a multiple of kDenseKstepUnit k-steps: the contraction's loop is unrolled that far; sources past the
+        // chunk's end are zero rows to it)
+        if (take > 0)
+            ksteps[j] = static_cast<int32_t>((std::min(bucket_end(take - 1), src_cap) / 64 + kDenseKstepUnit - 1) /
+                                             kDenseKstepUnit * kDenseKstepUnit);
     }
 }
 }  // namespace
@@ -434,7 +438,7 @@ hipError_t build_first_chunk_with_dense_part(const int64_t *off_dev, const int32
             for (int64_t r = bucket_begin(j); r < end; r += 256) {
                 band_ksteps.push_back(ksteps[j]);
                 band_off.push_back(static_cast<int64_t>(total));
-                total += static_cast<size_t>(ksteps[j]) * 16384;
+                total += static_cast<size_t>(ksteps[j]) * kDenseKstepBytes;
             }
         }
         if (total <= max_bytes) break;
@@ -452,7 +456,9 @@ hipError_t build_first_chunk_with_dense_part(const int64_t *off_dev, const int32
         for (int32_t b = 0; b < dense->n_bands && band_ksteps[b] > k; ++b) {
             items.push_back(b);
             items.push_back(k);
-            items.push_back(std::min<int32_t>(kDenseItemKsteps, band_ksteps[b] - k));
+            // bits 16..: the band's only item (its sums are stored, not added)
+            items.push_back(std::min<int32_t>(kDenseItemKsteps, band_ksteps[b] - k) |
+                            (band_ksteps[b] <= kDenseItemKsteps ? 1 << 16 : 0));
         }
     dense->n_items = static_cast<int64_t>(items.size() / 3);
     if ((err = hipMalloc(&dense->band_ksteps, band_ksteps.size() * 4)) != hipSuccess) goto fail;

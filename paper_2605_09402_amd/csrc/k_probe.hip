@@ -65,6 +65,34 @@ __global__ __launch_bounds__(kBlock) void k_probe_row_gather(const uint32_t *__r
     sink[wave * kWave + lane] = fold;
 }
 
+// Nothing but matrix instructions: every wave keeps `ACCS` independent 32x32 accumulators and issues
+// bf16 32x32x16 products on them from registers, `iters` rounds; what the matrix pipeline delivers when
+// nothing has to be loaded, converted or synchronised.
+typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float probe_f32x16 __attribute__((ext_vector_type(16)));
+template <int ACCS>
+__global__ __launch_bounds__(kBlock) void k_probe_mfma(int iters, float *__restrict__ sink) {
+    const int lane = threadIdx.x & (kWave - 1);
+    uint4 qa = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);   // ones
+    uint4 qb = make_uint4(lane & 1 ? 0x3f800000u : 0u, 0u, 0u, 0u);
+    const probe_bf16x8 a = __builtin_bit_cast(probe_bf16x8, qa), b = __builtin_bit_cast(probe_bf16x8, qb);
+    probe_f32x16 c[ACCS];
+#pragma unroll
+    for (int k = 0; k < ACCS; ++k)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) c[k][i] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int k = 0; k < ACCS; ++k) c[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c[k], 0, 0, 0);
+    }
+    float fold = 0.f;
+#pragma unroll
+    for (int k = 0; k < ACCS; ++k)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) fold += c[k][i];
+    sink[static_cast<size_t>(blockIdx.x) * kBlock + threadIdx.x] = fold;
+}
+
 int cu_count() {
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess)
@@ -87,6 +115,16 @@ hipError_t probe_mix21(void *dst, const void *a, const void *b, size_t bytes, hi
     if (vecs == 0) return hipSuccess;
     hipLaunchKernelGGL(k_probe_mix21, dim3(cu_count() * 16), dim3(kBlock), 0, s, static_cast<const uint4 *>(a),
                        static_cast<const uint4 *>(b), static_cast<uint4 *>(dst), vecs);
+    return hipGetLastError();
+}
+
+hipError_t probe_mfma(int waves_per_simd, int iters, void *sink, double *flops, hipStream_t s) {
+    // sink: at least probe_gather_sink_bytes() bytes (8 workgroups of 256 threads per CU)
+    if (waves_per_simd < 1 || waves_per_simd > 8 || iters < 1) return hipErrorInvalidValue;
+    const int blocks = cu_count() * waves_per_simd;   // a workgroup of 4 waves puts one wave on every SIMD of its CU
+    constexpr int kAccs = 4;
+    *flops = static_cast<double>(blocks) * (kBlock / kWave) * static_cast<double>(iters) * kAccs * 2.0 * 32 * 32 * 16;
+    hipLaunchKernelGGL((k_probe_mfma<kAccs>), dim3(blocks), dim3(kBlock), 0, s, iters, static_cast<float *>(sink));
     return hipGetLastError();
 }
 

@@ -145,8 +145,8 @@ def run_gpu(case: Case, *, snapshots: bool = False, pinned_host: bool = False, f
     tiles_per_run / piece_tiles: the launch-shape fields of atlas_dims_t (0: the library's choice).
     csr_stream: ATLAS_FLAG_CSR_STREAM, long chunks without a planned chunk are not regrouped on the fly.
     no_handover: ATLAS_FLAG_NO_HANDOVER, finished rows take the fp32 round trip to the update.
-    plan_dense = (max_bytes, cells_per_edge): atlas_plan_create_dense, the first chunk's dense corner as byte
-    matrices; no_dense: ATLAS_FLAG_NO_DENSE, that part is pushed as the planned chunk it also is.
+    plan_dense = (max_bytes, cells_per_edge): atlas_plan_create_dense, the first chunk's dense corner as matrices
+    of 4-bit counts; no_dense: ATLAS_FLAG_NO_DENSE, that part is pushed as the planned chunk it also is.
     run.plan_info holds atlas_plan_info of the plan."""
     dev = torch.device("cuda:0")
     n, e = case.n, case.e

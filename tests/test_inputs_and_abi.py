@@ -129,4 +129,4 @@ def test_library_exports_every_declared_symbol():
     assert b"ascending" in lib.atlas_strerror(atlas.E_ORDER)
     # struct sizes the binding assumes (LP64)
     assert ctypes.sizeof(atlas.atlas_graph_t) == 56 and ctypes.sizeof(atlas.atlas_weights_t) == 40
-    assert ctypes.sizeof(atlas.atlas_dims_t) == 72 and ctypes.sizeof(atlas.atlas_layer_stats_t) == 152
+    assert ctypes.sizeof(atlas.atlas_dims_t) == 72 and ctypes.sizeof(atlas.atlas_layer_stats_t) == 160
