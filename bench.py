@@ -50,7 +50,7 @@ def cpu_model() -> str:
 def kernel_source_hash() -> str:
     """Identifies the kernels the committed HBM counter summary was taken with."""
     h = hashlib.sha256()
-    for name in ("k_aggregate.hip", "k_update.hip"):
+    for name in ("k_aggregate.hip", "k_update.hip", "k_dense.hip"):
         with open(os.path.join(ROOT, "paper_2605_09402_amd", "csrc", name), "rb") as f:
             h.update(f.read())
     return h.hexdigest()[:16]
@@ -179,8 +179,12 @@ def main() -> int:
         wl = workloads.config3(dev, scale=args.scale or 22, chunk=ck)
     else:
         wl = workloads.config4(dev, scale=args.scale or 22, chunk=ck)
+    # the run the committed counter summary was taken with: the default workload with the default plan and flags
     is_headline = (args.workload == "config5" and args.scale == 26 and args.edge_factor == 32 and ck is None
-                   and args.layer_type == "sage" and args.store == "bf16")
+                   and args.layer_type == "sage" and args.store == "bf16" and args.dense_max_gb < 0
+                   and args.dense_cells_per_edge == 0 and not args.no_dense and not args.no_handover
+                   and not args.no_plan and args.plan_block_log2 < 0 and args.hot_slots_frac <= 0
+                   and not args.transform_first)
     torch.cuda.synchronize()
     n, e, chunk = wl.n, wl.e, wl.chunk
     log("generated %s: N=%d E=%d chunk=%d in %.1f s" % (wl.name, n, e, chunk, time.time() - t0))
