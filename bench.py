@@ -532,7 +532,9 @@ def main() -> int:
             "gather_GBps": round(n_ids * 256 / (gather_ms / 1e3) / 1e9, 1),
             "gather": "2^27 random 256-byte rows of a 1 GiB table, one wave per row, 8 rows in flight per wave",
             "mfma": mf,
-            "aggregate_frac_of_measured_gather": round(e * (4 + d * s_in) / agg_s_per_layer / 1e9 /
+            # (the edges the edge-list kernel pushes: without those of a contracted dense part)
+            "aggregate_frac_of_measured_gather": round((e_list if plan_info is not None else e) * (4 + d * s_in) /
+                                                       agg_s_per_layer / 1e9 /
                                                        (n_ids * 256 / (gather_ms / 1e3) / 1e9), 4),
         }
         log("measured peaks: copy %.0f GB/s, row gather %.0f GB/s, MFMA %s" %
