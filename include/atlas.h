@@ -350,8 +350,7 @@ int atlas_plan_create(const atlas_graph_t *graph, int64_t chunk_sources, atlas_p
  * Not for GAT layers (E_BAD_DIMS at atlas_layer_init); N < 2^30 (E_OVERFLOW). */
 int atlas_plan_create_blocked(const atlas_graph_t *graph, int64_t chunk_sources, int64_t block_sources,
                               int64_t hot_min_edges, atlas_plan_t **out);
-/* atlas_plan_create_blocked with a dense part for the first chunk (DEVICE graphs; E_BAD_DIMS
- * otherwise).  With ids in in-degree-descending order (Sec. 3.8) the hottest sources and the
+/* atlas_plan_create_blocked with a dense part for the first chunk.  With ids in in-degree-descending order (Sec. 3.8) the hottest sources and the
  * hottest destinations both lie at the front, and the first chunk's edges between them are so
  * many that this corner of the adjacency matrix holds more than one edge per hundred cells.
  * There a message costs more as a 256-byte row gather than its cell costs in a dense product.
@@ -371,7 +370,11 @@ int atlas_plan_create_blocked(const atlas_graph_t *graph, int64_t chunk_sources,
  * The contraction serves layers that sum plain rows (SAGE_MEAN, GIN, SGC_HOP), 16-bit rows of
  * width 64 or 128 (with ATLAS_FLAG_TRANSFORM_FIRST: the pushed products); every other layer, and
  * ATLAS_FLAG_NO_DENSE, pushes the same edges as a planned chunk, which the plan keeps as well.
- * Not for GAT layers or a bounded accumulator store (E_BAD_DIMS at atlas_layer_init). */
+ * Not for GAT layers or a bounded accumulator store (E_BAD_DIMS at atlas_layer_init).
+ * The dense part always lives in device memory, also in the plan of a PINNED_HOST graph: it is
+ * then the part of the topology that does not cross the host link in every layer (the cells are
+ * half a byte each, and the part's edges as a planned chunk 4 bytes each, where a streamed edge
+ * costs 3 bytes per layer). */
 int atlas_plan_create_dense(const atlas_graph_t *graph, int64_t chunk_sources, int64_t block_sources,
                             int64_t hot_min_edges, int64_t dense_max_bytes, int64_t dense_cells_per_edge,
                             atlas_plan_t **out);

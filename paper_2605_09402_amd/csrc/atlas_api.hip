@@ -1029,7 +1029,7 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
             L->edges_contracted += dp.list.n_edges;
         } else {
             GroupedArgs gd = ga;
-            gd.src_sorted = plan->src_sorted + dp.list.edge_base;
+            gd.src_sorted = dp.list_src ? dp.list_src : plan->src_sorted + dp.list.edge_base;
             gd.grp_dst = dp.list.grp_dst;
             gd.tile_grp = dp.list.tile_grp;
             gd.n_edges = dp.list.n_edges;
@@ -1229,7 +1229,6 @@ int atlas_plan_create_dense(const atlas_graph_t *graph, int64_t chunk_sources, i
     if (!graph || !out) return ATLAS_E_NULL;
     if (block_sources < 0 || hot_min_edges < 0 || dense_max_bytes < 0 || dense_cells_per_edge < 0)
         return ATLAS_E_BAD_DIMS;
-    if (dense_max_bytes > 0 && graph->residency != ATLAS_RESIDENT_DEVICE) return ATLAS_E_BAD_DIMS;
     if (dense_max_bytes > 0 && dense_cells_per_edge == 0) dense_cells_per_edge = kDefaultDenseCellsPerEdge;
     // bit 30 of a stored destination id marks destinations with several groups per chunk
     if (block_sources > 0 && graph->num_vertices >= (int64_t(1) << 30)) return ATLAS_E_OVERFLOW;
@@ -1305,23 +1304,37 @@ int atlas_plan_create_dense(const atlas_graph_t *graph, int64_t chunk_sources, i
                 e = hipMemcpy(off_tmp, graph->row_offsets + b, (nsrc + 1) * sizeof(int64_t), hipMemcpyHostToDevice);
                 if (e == hipSuccess && ne > 0)
                     e = hipMemcpy(col_tmp, graph->col_indices + ebeg, static_cast<size_t>(ne) * 4, hipMemcpyHostToDevice);
-                if (e == hipSuccess)
+                if (e == hipSuccess && k == 0 && dense_max_bytes > 0) {
+                    // The dense part stays in HBM (cells, and its edges as a planned chunk): it is the part of the
+                    // topology that never crosses the host link again; the chunk's other edges go to host memory.
+                    e = build_first_chunk_with_dense_part(off_tmp - b, col_tmp - ebeg, P->n, b, en, ebeg, eend, src_tmp, seen,
+                                                          block_sources, hot_min_edges, true,
+                                                          static_cast<size_t>(dense_max_bytes), dense_cells_per_edge, work,
+                                                          &pc, &P->dense);
+                    if (e == hipSuccess && P->dense.n_items > 0) {
+                        const size_t lb = static_cast<size_t>(P->dense.list.n_edges) * 4;
+                        if ((e = hipMalloc(reinterpret_cast<void **>(&P->dense.list_src), lb)) == hipSuccess)
+                            e = hipMemcpy(P->dense.list_src, src_tmp + pc.n_edges, lb, hipMemcpyDeviceToDevice);
+                    }
+                } else if (e == hipSuccess) {
                     e = build_plan_chunk(off_tmp - b, col_tmp - ebeg, P->n, b, en, ebeg, eend, src_tmp, seen, block_sources,
                                          hot_min_edges, true, work, &pc);
-                if (e == hipSuccess && ne > 0 && packed) {
+                }
+                const int64_t pe = pc.n_edges;   // the chunk's edges that go to host memory
+                if (e == hipSuccess && pe > 0 && packed) {
                     // the CSR slice is no longer needed: its buffer takes the packed words
-                    const size_t pb = packed24_bytes(ne);
+                    const size_t pb = packed24_bytes(pe);
                     pc.packed_off = static_cast<int64_t>(packed_off);
                     if (packed_off + pb > P->packed_bytes) e = hipErrorInvalidValue;
-                    if (e == hipSuccess) e = launch_pack24(src_tmp, ne, b, col_tmp, nullptr);
+                    if (e == hipSuccess) e = launch_pack24(src_tmp, pe, b, col_tmp, nullptr);
                     if (e == hipSuccess) e = hipMemcpy(P->src_packed + packed_off, col_tmp, pb, hipMemcpyDeviceToHost);
                     packed_off += round_up(pb, 256);
-                } else if (e == hipSuccess && ne > 0) {
-                    e = hipMemcpy(P->src_sorted + ebeg, src_tmp, static_cast<size_t>(ne) * 4, hipMemcpyDeviceToHost);
+                } else if (e == hipSuccess && pe > 0) {
+                    e = hipMemcpy(P->src_sorted + ebeg, src_tmp, static_cast<size_t>(pe) * 4, hipMemcpyDeviceToHost);
                 }
-                if (e == hipSuccess && ne > 0) {
+                if (e == hipSuccess && pe > 0) {
                     int32_t *g_h = nullptr, *t_h = nullptr;
-                    const size_t gb = static_cast<size_t>(pc.n_groups) * 4, tb = static_cast<size_t>((ne + 63) / 64) * 4;
+                    const size_t gb = static_cast<size_t>(pc.n_groups) * 4, tb = static_cast<size_t>((pe + 63) / 64) * 4;
                     if ((e = hipHostMalloc(reinterpret_cast<void **>(&g_h), gb, hipHostMallocDefault)) == hipSuccess &&
                         (e = hipHostMalloc(reinterpret_cast<void **>(&t_h), tb, hipHostMallocDefault)) == hipSuccess &&
                         (e = hipMemcpy(g_h, pc.grp_dst, gb, hipMemcpyDeviceToHost)) == hipSuccess)
@@ -1397,7 +1410,7 @@ int atlas_plan_info(const atlas_plan_t *P, atlas_plan_info_t *info) {
         dev += static_cast<size_t>(c.n_groups) * 4 + static_cast<size_t>((c.n_edges + 63) / 64) * 4 +
                static_cast<size_t>(c.n_zero_rows) * 12;
         dev += P->dense.cell_bytes + static_cast<size_t>(P->dense.rows) * 4 + static_cast<size_t>(P->dense.n_bands) * 12 +
-               static_cast<size_t>(P->dense.n_items) * 12;
+               static_cast<size_t>(P->dense.n_items) * 12 + (P->dense.list_src ? static_cast<size_t>(c.n_edges) * 4 : 0);
         info->dense_edges = c.n_edges;
         info->dense_groups = c.n_groups;
         info->dense_cells = static_cast<int64_t>(P->dense.cell_bytes) * 2;   // half a byte each
@@ -1420,7 +1433,9 @@ int atlas_plan_in_degree(const atlas_plan_t *P, int32_t *in_degree, void *hip_st
     for (const PlanChunk &c : P->chunks)
         HIP_TRY(launch_plan_chunk_in_degree(c, P->src_sorted + c.edge_base, in_degree, s));
     if (P->dense.n_items > 0)
-        HIP_TRY(launch_plan_chunk_in_degree(P->dense.list, P->src_sorted + P->dense.list.edge_base, in_degree, s));
+        HIP_TRY(launch_plan_chunk_in_degree(P->dense.list, P->dense.list_src ? P->dense.list_src
+                                                                            : P->src_sorted + P->dense.list.edge_base,
+                                            in_degree, s));
     return ATLAS_OK;
 }
 

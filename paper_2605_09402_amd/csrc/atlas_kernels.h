@@ -223,6 +223,8 @@ struct DensePart {
                                       // only item) of every work item
     int64_t n_items = 0;
     PlanChunk list;                   // the part's edges, grouped by destination
+    int32_t *list_src = nullptr;      // plans of pinned-host graphs: the list's edge words (device memory, as all of
+                                      // the dense part); device plans keep them in the plan's array at list.edge_base
     void release();
 };
 // Builds the first chunk of a plan in two parts.  max_bytes bounds the cells; cells_per_edge is the most

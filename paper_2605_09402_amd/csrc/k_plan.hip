@@ -339,7 +339,8 @@ done:
 
 void DensePart::release() {
     for (void *q : {static_cast<void *>(band_ksteps), static_cast<void *>(band_off), static_cast<void *>(cells),
-                    static_cast<void *>(msgs), static_cast<void *>(items), static_cast<void *>(list.grp_dst),
+                    static_cast<void *>(msgs), static_cast<void *>(items), static_cast<void *>(list_src),
+                    static_cast<void *>(list.grp_dst),
                     static_cast<void *>(list.tile_grp), static_cast<void *>(list.zero_rows),
                     static_cast<void *>(list.zero_span)})
         if (q) (void)hipFree(q);

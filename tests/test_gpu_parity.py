@@ -511,13 +511,23 @@ def test_dense_part_of_the_first_chunk(oracle, H, model, store, planned_only):
     assert all(st["edges_contracted"] == 0 and st["edges_processed"] == case.e for st in ref.stats)
     for a, b in zip(run.outputs, ref.outputs):
         assert torch.allclose(a.float(), b.float(), rtol=2.0 ** -6, atol=1e-3)
+    # graph, features and the rest of the plan in pinned host memory, the dense part in device memory: the
+    # first chunk's other edges are streamed (in pieces of 3 tiles), its dense edges never cross the link
+    pin = H.run_gpu(case, snapshots=True, pinned_host=True, device_later=not planned_only, piece_tiles=3, **opts)
+    assert pin.plan_info["dense_edges"] == info["dense_edges"] and pin.plan_info["bytes_pinned_host"] > 0
+    H.check_integers(oracle, case, pin, layer=0)
+    H.check_outputs(oracle, case, pin)
+    for st, st_dev in zip(pin.stats, run.stats):
+        assert st["edges_processed"] == case.e and st["edges_contracted"] == st_dev["edges_contracted"]
+    for a, b in zip(pin.outputs, ref.outputs):
+        assert torch.allclose(a.float(), b.float(), rtol=2.0 ** -6, atol=1e-3)
 
 
 def test_dense_part_choice_and_limits(oracle, H):
     """Where no block of the first chunk is dense enough the plan is an ordinary one (uniform random graph,
     default density); a byte limit below the smallest region leaves no dense part; GAT layers and a bounded
-    store refuse a plan with a dense part; a pinned-host graph refuses the call; a region that covers the whole
-    chunk takes every edge but the copies of a pair beyond the fifteenth."""
+    store refuse a plan with a dense part; a region that covers the whole chunk takes every edge but the copies of
+    a pair beyond the fifteenth."""
     import paper_2605_09402_amd as atlas
     gu = gen.uniform_graph(SEED + 82, 3000, 40000)
     case = H.make_case("sage", gu, SEED + 82, [128, 64], 1500, store=torch.bfloat16)
@@ -546,7 +556,4 @@ def test_dense_part_choice_and_limits(oracle, H):
     assert ei.value.status == atlas.E_BAD_DIMS
     with pytest.raises(atlas.AtlasError) as ei:
         H.run_gpu(case, plan=True, plan_dense=(1 << 30, 512), hot_slots=case.n // 2)
-    assert ei.value.status == atlas.E_BAD_DIMS
-    with pytest.raises(atlas.AtlasError) as ei:
-        H.run_gpu(case, plan=True, plan_dense=(1 << 30, 512), pinned_host=True)
     assert ei.value.status == atlas.E_BAD_DIMS

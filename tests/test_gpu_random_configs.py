@@ -130,7 +130,7 @@ def _draw(rng, oracle, H, idx, handed=False):
         opts["no_handover"] = True
     if not plan_kind and rng.random() < 0.3:
         opts["csr_stream"] = True
-    if plan_kind and not pinned and "hot_slots" not in opts and rng.random() < 0.4:
+    if plan_kind and "hot_slots" not in opts and rng.random() < 0.4:
         # the first chunk's dense corner as matrices of 4-bit counts (contracted on the matrix cores where the layer's rows
         # allow it, pushed as a planned chunk otherwise), at three densities
         opts["plan_dense"] = (1 << 30, int(rng.choice([64, 512, 1 << 20])))
