@@ -521,6 +521,12 @@ def test_dense_part_of_the_first_chunk(oracle, H, model, store, planned_only):
         assert st["edges_processed"] == case.e and st["edges_contracted"] == st_dev["edges_contracted"]
     for a, b in zip(pin.outputs, ref.outputs):
         assert torch.allclose(a.float(), b.float(), rtol=2.0 ** -6, atol=1e-3)
+    if model == "sage":
+        # transform-first: the contraction pushes the chunk's products (64 wide in both layers) instead of its rows
+        tfr = H.run_gpu(case, snapshots=True, **dict(opts, transform_first=True))
+        H.check_integers(oracle, case, tfr, layer=0)
+        print("  transform-first", H.check_outputs(oracle, case, tfr))
+        assert all(st["edges_contracted"] == info["dense_edges"] for st in tfr.stats)
 
 
 def test_dense_part_choice_and_limits(oracle, H):
