@@ -684,6 +684,9 @@ def main() -> int:
         "end_to_end_layer_ms": [round(v, 2) for v in main_res["layer_ms"]],
         "prep_ms": prep_out,
         "end_to_end_with_prep_ms": None if main_res["e2e_ms"] is None else r1(main_res["e2e_ms"] + prep_total),
+        # the same layer in the execution the workload's configuration states (host-link inclusive), at top level too
+        "value_as_stated": None if stated is None else stated["gteps"],
+        "ms_per_step_as_stated": None if stated is None else stated["ms_per_step"],
         "config5_as_stated": stated,
         "roofline": roofline, "update": update, "measured_peak": measured, "cpu_baseline": cpu,
     }
