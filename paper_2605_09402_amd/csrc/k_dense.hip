@@ -185,17 +185,18 @@ __device__ __forceinline__ f32x16_t mfma(typename Operand<CT>::type a, typename 
 struct CellRegs { uint4 q[2]; };   // [row block]: dword u = the lane's eight cells of the matrix instruction's k-step u
 
 // acc[band rows][N] += cells[band rows][sources of the item] x X[sources][N].
-// One workgroup (4 waves) per work item = 256 destinations x up to kDenseItemKsteps
-// k-steps of 64 sources; wave w owns rows 64 w .. 64 w + 63 (two 32-row blocks)
-// and all N features (NB blocks of 32).  The multiplicities go from HBM
-// straight into the registers of the lane that needs them (see the layout
-// above), two k-steps ahead; the rows' tile (N x 64, 16-bit) is shared by the
-// four waves through a double-buffered LDS tile, its loads two k-steps ahead too.  A band
-// that is one item stores its sums (the 64-byte atomic requests of the epilogue are what the chip
-// retires slowest: some 20 G a second); partial sums of a longer band's items meet in the
-// accumulator through fp32 atomics: with the
-// cells as the FIRST operand a lane holds 16 destinations of ONE feature, so
-// the 32 lanes of a half-wave add to 128 consecutive bytes of one row.
+// One workgroup (4 waves) per work item = 256 destinations x up to
+// kDenseItemKsteps k-steps of 64 sources; wave w owns rows 64 w .. 64 w + 63
+// (two 32-row blocks) and all N features (NB blocks of 32).  The
+// multiplicities go from HBM straight into the registers of the lane that
+// needs them (see the layout above), two k-steps ahead; the rows' tile
+// (N x 64, 16-bit) is shared by the four waves through a double-buffered LDS
+// tile, its loads two k-steps ahead too.  With the cells as the FIRST operand
+// a lane holds 16 destinations of ONE feature, so the 32 lanes of a half-wave
+// write 128 consecutive bytes of one row.  A band that is one item stores its
+// sums; the partial sums of a longer band's items meet in the accumulator
+// through fp32 atomics (64-byte atomic requests are what the chip retires
+// slowest, some 20 G a second, so items are long and short bands avoid them).
 template <int CT, int NB>
 __global__ __launch_bounds__(kBlock, 2) void k_dense_contract(DenseArgs a) {
     constexpr int N = NB * 32;
