@@ -185,6 +185,8 @@ def main() -> int:
                    and args.dense_cells_per_edge == 0 and not args.no_dense and not args.no_handover
                    and not args.no_plan and args.plan_block_log2 < 0 and args.hot_slots_frac <= 0
                    and not args.transform_first)
+    if args.dense_max_gb < 0:   # default: a dense part for the large workload's first chunk, up to 32 GB of cells
+        args.dense_max_gb = 32.0 if args.workload == "config5" and args.hot_slots_frac <= 0 else 0.0
     torch.cuda.synchronize()
     n, e, chunk = wl.n, wl.e, wl.chunk
     log("generated %s: N=%d E=%d chunk=%d in %.1f s" % (wl.name, n, e, chunk, time.time() - t0))
@@ -197,15 +199,17 @@ def main() -> int:
     plan_info = None
     if not args.no_plan and do_device:
         pg = atlas.make_graph(n, e, wl.off, wl.col)
-        if args.plan_block_log2 < 0:   # default: 2 MiB of source rows per block on the large workload
+        if args.plan_block_log2 < 0:
+            # default: plain destination order.  (Source blocks of 2 MiB of rows for the heavy destinations gained
+            # 4 ms on the large workload before the plan had a dense part; with it they gain nothing and cost 58 ms
+            # of plan construction.  The large workload without a dense part still gets them.)
             row_bytes = wl.dims[0] * (2 if wl.store != torch.float32 else 4)
-            args.plan_block_log2 = max(6, ((2 << 20) // row_bytes).bit_length() - 1) if args.workload == "config5" else 0
+            args.plan_block_log2 = (max(6, ((2 << 20) // row_bytes).bit_length() - 1)
+                                    if args.workload == "config5" and args.dense_max_gb <= 0 else 0)
         if args.plan_block_log2 > 0 and args.plan_hot_min <= 0:
             args.plan_hot_min = 32 * max(1, chunk >> args.plan_block_log2)
         if args.plan_block_log2 > 0 and chunk <= (1 << args.plan_block_log2):
             args.plan_block_log2 = 0   # a chunk of one block: nothing to reorder
-        if args.dense_max_gb < 0:
-            args.dense_max_gb = 32.0 if args.workload == "config5" and args.hot_slots_frac <= 0 else 0.0
         if args.dense_max_gb > 0:
             plan, prep["plan"] = timed_ms(lambda: atlas.atlas_plan_create_dense(
                 pg, chunk, (1 << args.plan_block_log2) if args.plan_block_log2 > 0 else 0,

@@ -86,8 +86,7 @@ def test_config4_gat_scale22(oracle, H):
 def test_config5_sage_scale26_bf16(oracle, H):
     """The benchmark's workload, three layers, in both executions the benchmark times.
     Device-resident: resident embeddings, every chunk planned (no zero fill at the layer
-    start), source-blocked plan with 2 MiB of source rows per block and 32 messages per block
-    as the threshold for a blocked destination, the first chunk's dense corner (up to 32 GB of
+    start), plan in plain destination order with the first chunk's dense corner (up to 32 GB of
     cells at the library's default density) contracted on the matrix cores in all three layers.  As the configuration states it: CSR and
     features in pinned host memory, plan in pinned host memory except the first chunk's dense
     corner (device memory), chunks streamed on the copy stream (the first one in pieces), later
@@ -96,8 +95,7 @@ def test_config5_sage_scale26_bf16(oracle, H):
     of the three layers of both runs."""
     wl = workloads.config5("cuda:0", reorder=H.gpu_reorder)
     assert wl.n == 1 << 26 and wl.e == 1 << 31 and wl.chunk == 1 << 22 and wl.dims == [128, 128, 128, 64]
-    block = (2 << 20) // (wl.dims[0] * 2)
-    s = _go(oracle, H, wl, emb_resident=True, n_random=1 << 18, planned_only=True,
-            plan_block=(block, 32 * (wl.chunk // block)), plan_dense=(32 * 10 ** 9, 0), contracted=True)
+    s = _go(oracle, H, wl, emb_resident=True, n_random=1 << 18, planned_only=True, plan_dense=(32 * 10 ** 9, 0),
+            contracted=True)
     _go(oracle, H, wl, sample=s, emb_resident=True, planned_only=True, pinned=True, plan_dense=(32 * 10 ** 9, 0),
         contracted=True)
