@@ -301,9 +301,11 @@ int atlas_broadcast_chunk(atlas_layer_t *layer, int64_t src_begin, int64_t src_e
  * not NULL the call waits for the stream and stores the number of rows written;
  * with NULL it only enqueues.  Errors: E_NULL, E_STATE, E_HIP.
  * Fused part (Sec. 3.6 hands a vertex to the transform the moment its count reaches zero): in
- * SAGE_MEAN / GCN_SYM layers with 16-bit embeddings of width 128, a vertex that is completed by
- * an edge message of a planned or regrouped chunk -- by a group of messages that one wavefront
- * sums alone -- does not go through an fp32 accumulator round trip: the aggregation writes the
+ * SAGE_MEAN / GCN_SYM layers with 16-bit embeddings of width 128, a vertex whose last edge
+ * message belongs to a group of a planned or regrouped chunk that one wavefront sums alone --
+ * the group completes the vertex, or (SAGE_MEAN) leaves only the vertex's own message
+ * outstanding, which carries no data for the sum -- does not go through an fp32 accumulator
+ * round trip: the aggregation writes the
  * finished row as this call's own left operand (normalised, rounded to the compute type exactly
  * as this call would have) and marks the vertex's ready-list entry; this call reads half the
  * bytes for it and skips the normalisation.  Results are bit-identical with and without it

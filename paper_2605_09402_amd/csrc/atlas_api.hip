@@ -990,6 +990,8 @@ int atlas_broadcast_chunk(atlas_layer_t *L, int64_t src_begin, int64_t src_end, 
         ga.handover = L->handover ? 1 : 0;
         ga.handover_dt = d.in_dtype;
         ga.handover_norm = d.model == ATLAS_MODEL_GCN_SYM ? 1 : 0;
+        ga.handover_self = L->handover && L->selfmsg ? 1 : 0;
+        ga.self_from = src_end;
     }
     if (d.model == ATLAS_MODEL_GAT) {
         if (pc) {
@@ -1597,6 +1599,10 @@ int atlas_debug_copy(atlas_layer_t *L, int what, void *host_dst, int64_t bytes) 
     if (what == ATLAS_DBG_READY) {   // bit 31 of an entry says how the row reaches the update, not which vertex
         int32_t *ids = static_cast<int32_t *>(host_dst);
         for (int64_t i = 0; i < bytes / 4; ++i) ids[i] &= 0x7fffffff;
+    }
+    if (what == ATLAS_DBG_PENDING) {   // likewise bit 30 of a count (see kPendingHanded)
+        int32_t *cnt = static_cast<int32_t *>(host_dst);
+        for (int64_t i = 0; i < bytes / 4; ++i) cnt[i] &= ~kPendingHanded;
     }
     return ATLAS_OK;
 }

@@ -16,6 +16,10 @@ enum Counter {
 };
 
 // 64-bit counters (separate block): edges pushed so far.
+// Bit of a pending count: the vertex's finished row already lies in its accumulator row as the update's
+// 16-bit operand; only its own message is outstanding (see GroupedArgs::handover_self).
+constexpr int32_t kPendingHanded = 0x40000000;
+
 enum Counter64 { CTR64_EDGES = 0, CTR64_HANDED = 1 /* rows handed over to the update */, CTR64_COUNT = 8 };
 
 // Bounded accumulator store (paper Sec. 3.5): a fixed number of slots in HBM,
@@ -141,6 +145,10 @@ struct GroupedArgs {
     int handover_dt = 1;        // row as the update's 16-bit operand (type handover_dt: 1 bf16, 2 IEEE half; normalised
     int handover_norm = 0;      // by 1/deg (0) or deg^-1/2 (1)) into the first half of the accumulator row, and the
                                 // vertex's ready-list entry carries bit 31
+    int handover_self = 0;      // 1 (layers whose vertices receive their own embedding as a message, with their own
+    int64_t self_from = 0;      // chunk): a group that leaves only that message outstanding (destination >= self_from,
+                                // the first source after this chunk) hands the row over as well and marks the
+                                // vertex's pending count with kPendingHanded for k_self_message
     int forced_run = 0;         // the layer's run length (1..kMaxTilesPerRun), 0: chosen per launch
     int tiles_per_run = 1;      // consecutive 64-edge tiles one wave takes at a time (set by the launcher)
     int64_t tile_begin = 0;     // the launch covers tiles [tile_begin, tile_end) of the chunk (tile_end < 0: all).

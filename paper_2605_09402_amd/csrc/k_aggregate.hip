@@ -265,18 +265,21 @@ __global__ __launch_bounds__(kBlock) void k_self_message(int64_t b, int64_t e, i
     int32_t *stage = stage_all + (threadIdx.x >> 6) * (kSelfFlush + kWave);
     int staged = 0;
     for (int64_t i0 = wave * (kWave * kPer); i0 < span; i0 += nwaves * (kWave * kPer)) {
-        int32_t left[kPer];
+        int32_t left[kPer], mark[kPer];
 #pragma unroll
         for (int k = 0; k < kPer; ++k) {
             const int64_t i = i0 + k * kWave + lane;
-            left[k] = i < span ? pending[b + i] - 1 : -1;
+            const int32_t p = i < span ? pending[b + i] : 0;
+            // bit 30: the aggregation has already left the vertex's finished row as the update's 16-bit operand
+            mark[k] = p & kPendingHanded;
+            left[k] = i < span ? (p & ~kPendingHanded) - 1 : -1;
         }
 #pragma unroll
         for (int k = 0; k < kPer; ++k) {
             const int64_t i = i0 + k * kWave + lane;
             if (i < span) pending[b + i] = left[k];
-            stage_ready<kSelfFlush>(i < span && left[k] == 0, static_cast<int32_t>(b + i), stage, staged, ready,
-                                    counters, lane);
+            const int32_t entry = static_cast<int32_t>(b + i) | (mark[k] ? static_cast<int32_t>(0x80000000u) : 0);
+            stage_ready<kSelfFlush>(i < span && left[k] == 0, entry, stage, staged, ready, counters, lane);
         }
     }
     drain_ready(stage, staged, ready, counters, lane);
@@ -465,12 +468,14 @@ __device__ __forceinline__ void row_hand_over(float *row, int lane, const float 
 // Second half of a tile's pending-count update: `old` is what the lane's read
 // (or atomic) returned.  The sole writer stores the new count here.
 __device__ __forceinline__ void finish_pending(bool closes, bool shared, int32_t old, int32_t c, int32_t dst,
-                                               bool handed, const GroupedArgs &a, int32_t *stage, int &staged,
-                                               int lane) {
+                                               bool handed, bool handed_early, const GroupedArgs &a, int32_t *stage,
+                                               int &staged, int lane) {
     bool is_ready = false;
     if (closes) {
         is_ready = old == c;
-        if (!shared) a.pending[dst] = old - c;
+        // handed_early: only the vertex's own message is outstanding and the row is already the update's operand;
+        // the count carries the mark to k_self_message, which completes the vertex
+        if (!shared) a.pending[dst] = (old - c) | (handed_early ? kPendingHanded : 0);
     }
     // a handed-over row was written because the count read ahead equalled c: the same value as `old`
     stage_ready(is_ready, handed ? dst | kHandedOver : dst, stage, staged, a.ready, a.counters, lane);
@@ -573,7 +578,7 @@ void k_aggregate_grouped(GroupedArgs a) {
         read_ahead(is_end, gd, pend_pre, deg_pre);
     }
     // pending-count update of the tile before, not yet consumed
-    bool pd_closes = false, pd_shared = false, pd_handed = false;
+    bool pd_closes = false, pd_shared = false, pd_handed = false, pd_early = false;
     int n_handed = 0;   // wave-uniform
     int32_t pd_old = 0, pd_c = 0, pd_dst = 0;
 
@@ -636,11 +641,15 @@ void k_aggregate_grouped(GroupedArgs a) {
         // FUSE: groups that lie wholly inside the tile are this wave's alone (sums, count); one of them that takes
         // its destination's count to zero hands the finished row over instead of adding it
         const int prev_end0 = below ? 63 - __clzll(static_cast<long long>(below)) : -1;
-        bool hands = false;
+        bool hands = false, hands_early = false;
         float hscale = 1.f;
         if constexpr (FUSE) {
             const bool owned = is_end && !(below == 0 && cut0) && !multi;
             hands = owned && pend_pre == lane - prev_end0;
+            // the same when the one message still outstanding is the vertex's own, which comes with its own
+            // (later) chunk and carries no data for the sum: the row is final now
+            hands_early = owned && a.handover_self && dstv >= a.self_from && pend_pre == lane - prev_end0 + 1;
+            hands = hands || hands_early;
             const float fd = static_cast<float>(deg_pre > 0 ? deg_pre : 1);
             hscale = a.handover_norm == 0 ? 1.0f / fd : 1.0f / sqrtf(fd);
         }
@@ -681,7 +690,7 @@ void k_aggregate_grouped(GroupedArgs a) {
                     if (is_end_n || lane == cnt_n - 1) gd_n = a.grp_dst[g0_n + __popcll(below_n)];
                     read_ahead(is_end_n, gd_n, pend_n, deg_n);
                 }
-                finish_pending(pd_closes, pd_shared, pd_old, pd_c, pd_dst, pd_handed, a, stage, staged, lane);
+                finish_pending(pd_closes, pd_shared, pd_old, pd_c, pd_dst, pd_handed, pd_early, a, stage, staged, lane);
                 pd_closes = false;
             }
             float r[U][VPL];
@@ -764,7 +773,7 @@ void k_aggregate_grouped(GroupedArgs a) {
                 if (is_end_n || lane == cnt_n - 1) gd_n = a.grp_dst[g0_n + __popcll(below_n)];
                 read_ahead(is_end_n, gd_n, pend_n, deg_n);
             }
-            finish_pending(pd_closes, pd_shared, pd_old, pd_c, pd_dst, pd_handed, a, stage, staged, lane);
+            finish_pending(pd_closes, pd_shared, pd_old, pd_c, pd_dst, pd_handed, pd_early, a, stage, staged, lane);
         }
 
         // pending count: minus the number of this tile's messages to the group.
@@ -774,7 +783,8 @@ void k_aggregate_grouped(GroupedArgs a) {
         // used (and the plain write made) while the next tile gathers.
         pd_closes = closes;
         pd_dst = dstv;
-        pd_handed = hands;
+        pd_handed = hands && !hands_early;
+        pd_early = hands_early;
         if (closes) {
             const int prev_end = prev_end0;
             pd_c = lane - prev_end;
@@ -787,7 +797,7 @@ void k_aggregate_grouped(GroupedArgs a) {
         s = s_n; g0 = g0_n; prev_word = prev_word_n; gd = gd_n;
         pend_pre = pend_n; deg_pre = deg_n;
     }
-    finish_pending(pd_closes, pd_shared, pd_old, pd_c, pd_dst, pd_handed, a, stage, staged, lane);
+    finish_pending(pd_closes, pd_shared, pd_old, pd_c, pd_dst, pd_handed, pd_early, a, stage, staged, lane);
     drain_ready(stage, staged, a.ready, a.counters, lane);
     if (FUSE && lane == 0 && n_handed > 0)
         atomicAdd(&a.counters64[CTR64_HANDED], static_cast<unsigned long long>(n_handed));
@@ -987,7 +997,11 @@ hipError_t launch_grouped_vpl(const GroupedArgs &a_in, int grid, uint32_t *run_t
         // be handed over, and the hand-over's read-ahead (count and degree of every group end) costs a launch of
         // long groups (the first chunk of a degree-ordered stream: 58 edges per group, nothing completes) more
         // than it saves.
-        if (a.handover && !a.slot_of && a.d == 2 * kWave && a.n_groups > 0 && a.n_edges / a.n_groups < 32) {
+        // Where vertices also receive their own embedding as a message (handover_self), most low-degree vertices
+        // have all their edge messages in by the first chunk and wait for that message only: there the hand-over
+        // pays in every launch.
+        if (a.handover && !a.slot_of && a.d == 2 * kWave && a.n_groups > 0 &&
+            (a.handover_self || a.n_edges / a.n_groups < 32)) {
             hipLaunchKernelGGL((k_aggregate_grouped<T, 2, MODEL, true>), dim3(grid), dim3(kBlock), 0, s, a);
             return hipGetLastError();
         }

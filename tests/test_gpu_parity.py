@@ -451,8 +451,13 @@ def test_finished_rows_handed_to_the_update(oracle, H, model, store, planned_onl
     last_src = np.where(indeg > 0, il.in_src[np.maximum(il.in_off[1:] - 1, 0)], -1)
     own = np.arange(case.n)
     by_edge = (indeg > 0) & ((last_src // case.chunk >= own // case.chunk) if model == "sage" else True)
+    # SAGE: a vertex whose own message (which comes with its own chunk and carries no data for the sum) is the only
+    # one outstanding after a group is handed over as well, so every vertex with an in-edge may be
+    bound = int((indeg > 0).sum()) if model == "sage" else int(by_edge.sum())
     for st, st_ref in zip(run.stats, ref.stats):
-        assert 0 < st["rows_handed_over"] <= int(by_edge.sum()), (st["rows_handed_over"], int(by_edge.sum()))
+        assert 0 < st["rows_handed_over"] <= bound, (st["rows_handed_over"], bound)
+        if model == "sage":
+            assert st["rows_handed_over"] > int(by_edge.sum()) // 2
         assert st_ref["rows_handed_over"] == 0
     run = H.run_gpu(case, plan=True, planned_only=planned_only, pinned_host=True, device_later=True, piece_tiles=3)
     same(run.outputs, ref.outputs)
