@@ -407,8 +407,11 @@ def main() -> int:
             G -= plan_info["dense_groups"]
             G1 = max(0, G1 - plan_info["dense_groups"])
         algo_bytes_layer = e_list * (4 + d * s_in) + G * (4 + 8) + (2 * G - G1) * 4 * d + ((e_list + 63) // 64) * 4
+        # a row handed over to the update leaves the kernel in the storage type, not as an fp32 row
+        algo_bytes_layer -= main_res["last_stats"]["rows_handed_over"] * (4 - s_in) * d
         algo_note = ("edge word + source row per edge; destination word, pending RMW and fp32 row "
-                     "(store for a first group, read + write otherwise) per group; tile index per 64 edges")
+                     "(store for a first group, read + write otherwise; a row handed over to the update is written in "
+                     "the storage type) per group; tile index per 64 edges")
     else:
         # CSR stream with atomics: destination id, fp32 row read-modify-write and pending RMW per edge
         algo_bytes_layer = e * (4 + 2 * 4 * d + 8) + n * (d * s_in + 8)
