@@ -498,8 +498,8 @@ enum atlas_debug_what {
 int atlas_debug_copy(atlas_layer_t *layer, int what, void *host_dst, int64_t bytes);
 
 /* Free what the library keeps for reuse between layers: its cache of device buffers, the
- * bounded store's pinned cold tier, and the chunk loader's copy stream (created again when
- * next needed).  Call it when no layer is alive, e.g. before the process ends: the HIP
+ * work arrays of the on-the-fly regrouping (see atlas_broadcast_chunk), the bounded store's
+ * pinned cold tier, and the chunk loader's copy stream (created again when next needed).  Call it when no layer is alive, e.g. before the process ends: the HIP
  * runtime may already be shutting down when static destructors run, so the library frees
  * nothing by itself at exit. */
 int atlas_release_cache(void);

@@ -79,6 +79,28 @@ size_t dtype_size(int dt) { return dt == ATLAS_DTYPE_F32 ? 4 : 2; }
 // process, grown on demand and kept until atlas_release_cache (pinning tens of
 // gigabytes takes seconds; layers with a bounded store run one after another
 // and reuse it).
+// Work arrays of the on-the-fly regrouping (tens of gigabytes for a long chunk), parked between layers so that
+// a run without a plan does not allocate and free them per layer; one set: a second layer that regroups at the
+// same time gets its own.  Freed by atlas_release_cache.
+PlanWork *g_regroup_work = nullptr;
+PlanWork *take_regroup_work() {
+    std::lock_guard<std::mutex> lk(g_cache_mu);
+    PlanWork *w = g_regroup_work;
+    g_regroup_work = nullptr;
+    return w;
+}
+void park_regroup_work(PlanWork *w) {
+    if (!w) return;
+    {
+        std::lock_guard<std::mutex> lk(g_cache_mu);
+        if (!g_regroup_work) {
+            g_regroup_work = w;
+            return;
+        }
+    }
+    delete w;
+}
+
 void *g_cold = nullptr;
 size_t g_cold_bytes = 0;
 hipError_t cold_buffer(size_t bytes, void **out) {
@@ -228,7 +250,7 @@ struct atlas_layer {
                        &packed_w2})
             b->release();
         free_regrouped();
-        delete regroup_work;
+        park_regroup_work(regroup_work);
         regroup_work = nullptr;
         regroup_src.release();
         for (auto &v : piece_ev)
@@ -721,7 +743,8 @@ int regroup_chunk(atlas_layer *L, int64_t src_begin, int64_t src_end, int64_t e0
     if (L->copy_stream) HIP_TRY(hipStreamSynchronize(L->copy_stream));
     L->free_regrouped();
     if (!L->regroup_work) {
-        L->regroup_work = new (std::nothrow) PlanWork();
+        L->regroup_work = take_regroup_work();
+        if (!L->regroup_work) L->regroup_work = new (std::nothrow) PlanWork();
         if (!L->regroup_work) return ATLAS_E_NOMEM;
     }
     const size_t words = static_cast<size_t>(e1 - e0) * sizeof(int32_t);
@@ -1615,6 +1638,8 @@ int atlas_release_cache(void) {
         if (e != hipSuccess && first == hipSuccess) first = e;
     }
     g_cache.clear();
+    delete g_regroup_work;
+    g_regroup_work = nullptr;
     if (g_cold) {
         hipError_t e = hipHostFree(g_cold);
         if (e != hipSuccess && first == hipSuccess) first = e;
