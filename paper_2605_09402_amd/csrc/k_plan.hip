@@ -452,8 +452,10 @@ hipError_t build_first_chunk_with_dense_part(const int64_t *off_dev, const int32
     dense->max_ksteps = band_ksteps[0];
     dense->cell_bytes = total;
     // work items in (source slice, band) order: the workgroups in flight at one time then read the same slice of
-    // the repacked rows, which stays in the L2 caches, while each streams its own cells
-    for (int32_t k = 0; k < dense->max_ksteps; k += kDenseItemKsteps)
+    // the repacked rows, which stays in the L2 caches, while each streams its own cells.  Last slice first: only
+    // the longest bands reach it and all its items are full length; the first slice, with the thousands of short
+    // bands of the staircase's lower steps, then fills the end of the launch evenly.
+    for (int32_t k = (dense->max_ksteps - 1) / kDenseItemKsteps * kDenseItemKsteps; k >= 0; k -= kDenseItemKsteps)
         for (int32_t b = 0; b < dense->n_bands && band_ksteps[b] > k; ++b) {
             items.push_back(b);
             items.push_back(k);
