@@ -425,7 +425,8 @@ def test_measurement_probes(atlas):
     combines its two inputs, the gather runs over ragged id lists without touching anything but
     its sink, and the dense-row contraction equals rows x W (fp64 matmul of the stored 16-bit
     values, library routine) to the 16-bit output's rounding, for the K-sliced kernel (more than
-    128 columns), the generic one, a ragged row count and both 16-bit types."""
+    128 columns), the generic one, a ragged row count and both 16-bit types; the bare loop of matrix
+    instructions leaves the sums its operands imply."""
     dev = torch.device("cuda:0")
     a = torch.randint(-2 ** 31, 2 ** 31 - 1, (1 << 20,), dtype=torch.int32, device=dev)
     b = torch.randint(-2 ** 31, 2 ** 31 - 1, (1 << 20,), dtype=torch.int32, device=dev)
@@ -458,3 +459,16 @@ def test_measurement_probes(atlas):
     with pytest.raises(atlas.AtlasError) as ei:
         atlas.atlas_probe_dense_rows(atlas.DTYPE_F32, rows, n_rows, K, d_out, W, got, 1)
     assert ei.value.status == atlas.E_BAD_DIMS
+    # the bare matrix-instruction loop: ones times a matrix with two ones in every odd column, four accumulators
+    # of 16 values per lane, `iters` rounds: every lane of an odd column folds 4 x 16 x 2 x iters, the others 0
+    sink.zero_()
+    for wps, iters in ((1, 10), (4, 3)):
+        flops = atlas.atlas_probe_mfma(wps, iters, sink)
+        torch.cuda.synchronize()
+        threads = int(flops / (iters * 4 * 2 * 32 * 32 * 16)) * 64
+        assert threads > 0 and threads % 256 == 0 and threads * 4 <= atlas.atlas_probe_gather_sink_bytes()
+        got = sink.view(torch.float32)[:threads].cpu().numpy()
+        want = np.where(np.arange(threads) % 2 == 1, 128.0 * iters, 0.0)
+        assert np.array_equal(got, want)
+    with pytest.raises(atlas.AtlasError):
+        atlas.atlas_probe_mfma(9, 1, sink)
